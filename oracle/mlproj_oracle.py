@@ -1,0 +1,225 @@
+"""CPU oracle for the bi-level / tri-level l1,q projections (Perez & Barlaud,
+"Multi-level projection with exponential parallel speedup", arXiv 2405.02086).
+
+THIS IS TEST INFRASTRUCTURE.  It is slow, plain and written to be checked
+against the paper by eye.  Only tests, the smoke check and the benchmark's
+CPU-baseline leg may import it; the GPU library never does, and this file
+imports nothing from the GPU package.
+
+Conventions
+-----------
+* A matrix Y has shape (n, m); column j (Y[:, j]) is group j (Sec. 2, Eq. 1-2).
+* Storage is fp32.  Every sum, the l1-ball threshold and every division are
+  taken in fp64.  max / min / abs / copysign are exact in fp32 and done there.
+* Where fp64 meets fp32 (the radii u_j that bound fp32 data) the radius is
+  rounded to fp32 first, then compared -- the same decision rule the fp32
+  storage format forces on any implementation.
+* A group is kept iff v_j > tau (strict); v_j == tau gives u_j = 0.
+
+Every function is pinned by tests/test_oracle_pins.py against optimality
+certificates of the Euclidean projection (Eq. 4), brute force, closed forms and
+hand-worked examples; nothing here is "parity unpinned".
+"""
+import numpy as np
+
+__all__ = [
+    "column_norms", "norm_l1q", "project_l1_ball_nonneg", "project_l1_ball",
+    "project_linf_ball", "project_l2_ball", "bilevel_l1inf", "bilevel_l11",
+    "bilevel_l12", "trilevel_l1infinf", "bilevel",
+]
+
+
+# --------------------------------------------------------------------------
+# Sec. 2, Eq. 1-2: column norms and the l_{1,q} matrix norm
+# --------------------------------------------------------------------------
+def column_norms(Y, q):
+    """v_q = (||y_1||_q, ..., ||y_m||_q), the aggregate vector of Sec. 3.
+
+    q = "inf": exact fp32 maxima (returned as float32).
+    q = 1, 2 : fp64 accumulation (returned as float64).
+    """
+    Y = np.asarray(Y)
+    assert Y.ndim == 2 and Y.dtype == np.float32
+    n, m = Y.shape
+    if q == "inf":
+        v = np.zeros(m, dtype=np.float32)
+        for i in range(n):                       # plain loop over rows
+            v = np.maximum(v, np.abs(Y[i, :]))
+        return v
+    if q == 1:
+        v = np.zeros(m, dtype=np.float64)
+        for i in range(n):
+            v += np.abs(Y[i, :].astype(np.float64))
+        return v
+    if q == 2:
+        s = np.zeros(m, dtype=np.float64)
+        for i in range(n):
+            r = Y[i, :].astype(np.float64)
+            s += r * r
+        return np.sqrt(s)
+    raise ValueError("q must be 'inf', 1 or 2")
+
+
+def norm_l1q(Y, q):
+    """||Y||_{1,q} = sum_j ||y_j||_q  (Eq. 1 with p = 1; Eq. 10 for q = inf)."""
+    return float(np.sum(column_norms(Y, q).astype(np.float64)))
+
+
+# --------------------------------------------------------------------------
+# Eq. 4 with p = 1: Euclidean projection onto the l1 ball (sort-based)
+# --------------------------------------------------------------------------
+def project_l1_ball_nonneg(v, eta):
+    """P^1_eta(v) for v >= 0, in fp64.  Returns (u, tau).
+
+    The minimiser of ||u - v||_2 over {u : ||u||_1 <= eta} is
+    u_j = max(v_j - tau, 0) with tau = 0 if sum(v) <= eta, and otherwise the
+    unique tau > 0 with sum_j max(v_j - tau, 0) = eta.  tau is found from the
+    values sorted in decreasing order mu_1 >= ... >= mu_m and their prefix sums
+    c_k: K = max{k : mu_k > (c_k - eta)/k}, tau = (c_K - eta)/K.
+    """
+    v = np.asarray(v, dtype=np.float64)
+    assert v.ndim == 1 and np.all(v >= 0.0)
+    eta = float(eta)
+    assert eta >= 0.0
+    if v.size == 0:
+        return v.copy(), 0.0
+    if eta == 0.0:
+        return np.zeros_like(v), float(np.max(v))
+    if float(np.sum(v)) <= eta:
+        return v.copy(), 0.0
+    mu = np.sort(v)[::-1]
+    c = np.cumsum(mu)
+    k = np.arange(1, v.size + 1, dtype=np.float64)
+    cand = (c - eta) / k
+    K = int(np.nonzero(mu > cand)[0][-1]) + 1     # largest k with mu_k > cand_k
+    tau = float(cand[K - 1])
+    u = np.maximum(v - tau, 0.0)
+    return u, tau
+
+
+def project_l1_ball(y, r):
+    """P^1_r(y) for a signed vector: sign(y) * P^1_r(|y|).  Returns (x, tau)."""
+    y = np.asarray(y, dtype=np.float64)
+    a, tau = project_l1_ball_nonneg(np.abs(y), r)
+    return np.copysign(a, y), tau
+
+
+# --------------------------------------------------------------------------
+# Per-group maps of Eq. 9: projections onto the l_inf and l2 balls
+# --------------------------------------------------------------------------
+def project_linf_ball(y, r):
+    """P^inf_r(y) = sign(y) * min(|y|, r), elementwise; r broadcasts.
+
+    Sec. 4.1 prints this map without the sign; the Euclidean projection onto
+    {x : max|x_i| <= r} is the symmetric clip written here.
+    fp32 in, fp32 out, exact.
+    """
+    y = np.asarray(y, dtype=np.float32)
+    r = np.asarray(r, dtype=np.float32)
+    return np.copysign(np.minimum(np.abs(y), r), y).astype(np.float32)
+
+
+def project_l2_ball(y, r, norm=None):
+    """P^2_r(y) = y * min(1, r / ||y||_2) in fp64 (0 if y = 0)."""
+    y = np.asarray(y, dtype=np.float64)
+    nrm = float(np.sqrt(np.sum(y * y))) if norm is None else float(norm)
+    if nrm <= r:
+        return y.copy()
+    return y * r / nrm
+
+
+# --------------------------------------------------------------------------
+# Alg. 2 / 3 / 4: bi-level projections BP^{1,q}_eta
+# --------------------------------------------------------------------------
+def _out_and_columns(Y, columns):
+    """Output buffer and the list of columns step 3 visits.  With `columns`
+    given (a sample of a huge input) the unvisited columns stay NaN."""
+    if columns is None:
+        return np.empty_like(Y), range(Y.shape[1])
+    return np.full_like(Y, np.nan), list(columns)
+
+
+def bilevel_l1inf(Y, eta, columns=None):
+    """BP^{1,inf}_eta(Y), Eq. 13 / Alg. 2.  Returns dict(X, v, u, tau)."""
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32 and Y.ndim == 2
+    v = column_norms(Y, "inf")                         # step 1
+    u64, tau = project_l1_ball_nonneg(v, eta)          # step 2
+    u = u64.astype(np.float32)
+    X, cols = _out_and_columns(Y, columns)
+    for j in cols:                                     # step 3, column by column
+        X[:, j] = project_linf_ball(Y[:, j], u[j])
+    return {"X": X, "v": v, "u": u, "tau": tau}
+
+
+def bilevel_l12(Y, eta, columns=None):
+    """BP^{1,2}_eta(Y), Eq. 15 / Alg. 4.  Returns dict(X, v, u, tau) (v, u fp64)."""
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32 and Y.ndim == 2
+    v = column_norms(Y, 2)
+    u, tau = project_l1_ball_nonneg(v, eta)
+    X, cols = _out_and_columns(Y, columns)
+    for j in cols:
+        X[:, j] = project_l2_ball(Y[:, j], u[j], norm=v[j]).astype(np.float32)
+    return {"X": X, "v": v, "u": u, "tau": tau}
+
+
+def bilevel_l11(Y, eta, columns=None):
+    """BP^{1,1}_eta(Y), Eq. 14 / Alg. 3.
+
+    Returns dict(X, v, u, tau, tau_col); tau_col[j] is the inner threshold of
+    column j.  `columns` (optional index list) restricts step 3 to those
+    columns; the others are left as NaN in X (used to sample huge inputs).
+    """
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32 and Y.ndim == 2
+    v = column_norms(Y, 1)
+    u, tau = project_l1_ball_nonneg(v, eta)
+    X, cols = _out_and_columns(Y, columns)
+    tau_col = np.full(Y.shape[1], np.nan)
+    for j in cols:
+        x, tj = project_l1_ball(Y[:, j], u[j])
+        X[:, j] = x.astype(np.float32)
+        tau_col[j] = tj
+    return {"X": X, "v": v, "u": u, "tau": tau, "tau_col": tau_col}
+
+
+def bilevel(Y, eta, q, columns=None):
+    return {"inf": bilevel_l1inf, 1: bilevel_l11, 2: bilevel_l12}[q](Y, eta, columns)
+
+
+# --------------------------------------------------------------------------
+# Def. 5.1, Alg. 5 and its iterative form (appendix Alg. 7): tri-level
+# --------------------------------------------------------------------------
+def trilevel_l1infinf(Y, eta):
+    """TP^{1,inf,inf}_eta of a C-order tensor Y[a, b, c].
+
+    Axis convention: groups live on axis 0; the innermost aggregate runs over
+    axis 2, the second over axis 1.  This is the paper's R^{c,n,m} tensor with
+    the axis names reversed (the paper aggregates its first axis, then its
+    second, and keeps groups on its last).
+
+    Follows the iterative form step by step and keeps the intermediate radius
+    matrix U2, so that "the element clip only needs u_a" is something tests
+    can check rather than something assumed here.
+    Returns dict(X, V, w, u, U2, tau).
+    """
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32 and Y.ndim == 3
+    d0, d1, d2 = Y.shape
+    V = np.zeros((d0, d1), dtype=np.float32)           # V_inf: fibre maxima
+    for c in range(d2):
+        V = np.maximum(V, np.abs(Y[:, :, c]))
+    w = np.zeros(d0, dtype=np.float32)                 # v_{inf,inf}
+    for b in range(d1):
+        w = np.maximum(w, V[:, b])
+    u64, tau = project_l1_ball_nonneg(w, eta)          # u^3
+    u = u64.astype(np.float32)
+    U2 = np.empty_like(V)
+    for a in range(d0):                                # first loop: U^2_t
+        U2[a, :] = project_linf_ball(V[a, :], u[a])
+    X = np.empty_like(Y)
+    for a in range(d0):                                # second loop: U^1_t
+        for b in range(d1):
+            X[a, b, :] = project_linf_ball(Y[a, b, :], U2[a, b])
+    return {"X": X, "V": V, "w": w, "u": u, "U2": U2, "tau": tau}
