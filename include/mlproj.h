@@ -1,0 +1,141 @@
+/*
+ * mlproj -- bi-level and tri-level projection onto the l_{1,q} ball on one AMD
+ * MI355X (gfx950), after Perez & Barlaud, "Multi-level projection with
+ * exponential parallel speedup" (arXiv 2405.02086).
+ *
+ * For a matrix Y in R^{n x m} whose columns y_j are the groups, the bi-level
+ * projection BP^{1,q}_eta (Sec. 3, Eq. 5-9, Alg. 1) is three steps:
+ *   1. v_j = ||y_j||_q                       (column aggregate, Sec. 3)
+ *   2. u   = P^1_eta(v)                      (Euclidean projection of v onto the
+ *                                             l1 ball of radius eta, Eq. 6-7)
+ *   3. x_j = P^q_{u_j}(y_j) for every j      (per-column projection, Eq. 8-9)
+ *
+ * GENERAL CONVENTIONS (all entry points)
+ *  - Pure C ABI.  Every pointer named "device" is GPU global memory of the
+ *    current HIP device; `stream` is a hipStream_t passed as void* (NULL = the
+ *    default stream).  Calls only enqueue work on `stream` and return; they never
+ *    synchronise, never copy to the host and never allocate or free memory.
+ *  - Matrices are dense row-major fp32: element (i, j) of an n x m matrix is
+ *    Y[i*m + j].  Tensors are dense C-order fp32.
+ *  - The caller owns every buffer.  X may alias Y exactly (in-place); any other
+ *    overlap between buffers is undefined.  Y must hold finite values.
+ *  - `workspace`: device scratch of at least mlproj_workspace_bytes(...) bytes,
+ *    256-byte aligned, prepared ONCE after allocation by mlproj_workspace_init()
+ *    (it clears the inter-workgroup tickets).  Every call leaves the workspace
+ *    ready for the next one.  One workspace serves one call at a time: two calls
+ *    that may overlap on the GPU (different streams) need two workspaces.
+ *    A workspace sized for one shape serves any call whose own requirement is
+ *    not larger.
+ *  - After a call has completed on the stream, the first bytes of the workspace
+ *    hold a mlproj_result record (threshold tau, norm, active count, ...).
+ *  - v_out / u_out: optional device arrays (NULL to skip) that receive the
+ *    aggregate v and the radii u, rounded to fp32.
+ *  - Return value: MLPROJ_OK or a negative mlproj_status.  All argument checks
+ *    run on the host before anything is enqueued; on error nothing was enqueued.
+ *  - eta >= 0 (Sec. 4.1).  eta = 0 gives X = 0.  ||Y||_{1,q} <= eta gives X = Y
+ *    bit for bit.  A group is kept iff v_j > tau.
+ */
+#ifndef MLPROJ_H
+#define MLPROJ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mlproj_status {
+  MLPROJ_OK = 0,
+  MLPROJ_ERR_NULL_POINTER = -1,   /* a required pointer is NULL                       */
+  MLPROJ_ERR_BAD_DIMENSION = -2,  /* a dimension is <= 0                              */
+  MLPROJ_ERR_TOO_LARGE = -3,      /* element count or a dimension exceeds the limits  */
+  MLPROJ_ERR_BAD_RADIUS = -4,     /* eta is negative, NaN or infinite                 */
+  MLPROJ_ERR_WORKSPACE = -5,      /* workspace too small or misaligned                */
+  MLPROJ_ERR_BAD_VARIANT = -6,    /* unknown variant / norm selector                  */
+  MLPROJ_ERR_ALIGNMENT = -7,      /* Y or X not 4-byte aligned                        */
+  MLPROJ_ERR_LAUNCH = -8          /* the HIP runtime refused a launch (see hipGetLastError) */
+} mlproj_status;
+
+/* Which projection a workspace is sized for. */
+typedef enum mlproj_variant {
+  MLPROJ_L1INF = 0,     /* bilevel_proj_l1inf,      dims (n, m, 1)     */
+  MLPROJ_L11 = 1,       /* bilevel_proj_l11,        dims (n, m, 1)     */
+  MLPROJ_L12 = 2,       /* bilevel_proj_l12,        dims (n, m, 1)     */
+  MLPROJ_L1INFINF = 3   /* trilevel_proj_l1infinf,  dims (d0, d1, d2)  */
+} mlproj_variant;
+
+/* Record left at offset 0 of the workspace by every projection / norm call. */
+typedef struct mlproj_result {
+  double tau;            /* threshold of step 2: u_j = max(v_j - tau, 0); 0 when Y is inside the ball */
+  double norm;           /* ||Y||_{1,q} = sum_j v_j (fp64)                                            */
+  double vmax;           /* max_j v_j                                                                 */
+  uint32_t n_active;     /* number of groups with u_j > 0                                             */
+  uint32_t inside_ball;  /* 1 when ||Y||_{1,q} <= eta (X = Y)                                         */
+  uint32_t search_iters; /* fixed-point iterations the threshold search of step 2 took                */
+  uint32_t inner_sweeps; /* l1,1 only: passes over Y the per-column threshold searches took           */
+  uint32_t inner_pending;/* l1,1 only: columns whose inner search had not converged (0 = exact)       */
+  uint32_t reserved[7];
+} mlproj_result;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int mlproj_version(void);
+
+/* Static, human-readable text for a status code. */
+const char* mlproj_status_string(int status);
+
+/* Bytes of workspace a call of `variant` on dims (d0, d1, d2) needs; bi-level
+ * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.            */
+int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2,
+                           size_t* bytes_out /* host */);
+
+/* Prepare a freshly allocated workspace (clears it with a fill kernel on `stream`).
+ * Needed once per allocation, not per call.                                      */
+int mlproj_workspace_init(void* workspace /* device */, size_t workspace_bytes, void* stream);
+
+/* ||Y||_{1,q} = sum_j ||y_j||_q (Sec. 2, Eq. 1-2 with p = 1; Eq. 10 for q = inf).
+ * q_variant is MLPROJ_L1INF, MLPROJ_L11 or MLPROJ_L12.  The fp64 norm is written to
+ * norm_out[0] (device) and to the workspace record; v_out optionally gets v.      */
+int mlproj_norm_l1q(const float* Y /* device, n*m */, long long n, long long m, int q_variant,
+                    void* workspace /* device */, size_t workspace_bytes,
+                    double* norm_out /* device, 1; may be NULL */,
+                    float* v_out /* device, m; may be NULL */, void* stream);
+
+/* BP^{1,inf}_eta (Sec. 4.1, Eq. 13, Alg. 2): v_j = max_i |Y_ij| (exact), u = P^1_eta(v),
+ * X_ij = sign(Y_ij) * min(|Y_ij|, u_j).                                                */
+int bilevel_proj_l1inf(const float* Y /* device, n*m */, float* X /* device, n*m */,
+                       long long n, long long m, float eta,
+                       void* workspace /* device */, size_t workspace_bytes,
+                       float* v_out /* device, m; may be NULL */,
+                       float* u_out /* device, m; may be NULL */, void* stream);
+
+/* BP^{1,1}_eta (Sec. 4.3.1, Eq. 14, Alg. 3): v_j = sum_i |Y_ij|, u = P^1_eta(v),
+ * x_j = P^1_{u_j}(y_j), i.e. X_ij = sign(Y_ij) * max(|Y_ij| - tau_j, 0) with the
+ * per-column threshold tau_j that makes ||x_j||_1 = u_j.                          */
+int bilevel_proj_l11(const float* Y, float* X, long long n, long long m, float eta,
+                     void* workspace, size_t workspace_bytes,
+                     float* v_out, float* u_out, void* stream);
+
+/* BP^{1,2}_eta (Sec. 4.3.2, Eq. 15, Alg. 4): v_j = ||y_j||_2, u = P^1_eta(v),
+ * x_j = y_j * u_j / v_j (x_j = 0 when v_j = 0).                                   */
+int bilevel_proj_l12(const float* Y, float* X, long long n, long long m, float eta,
+                     void* workspace, size_t workspace_bytes,
+                     float* v_out, float* u_out, void* stream);
+
+/* TP^{1,inf,inf}_eta (Sec. 5.1, Def. 5.1, Alg. 5; iterative form in the appendix) on a
+ * C-order tensor Y[a][b][c] of shape (d0, d1, d2).  Groups live on axis 0: the inner
+ * aggregate is V_ab = max_c |Y_abc|, the outer one w_a = max_b V_ab, u = P^1_eta(w), and
+ * each fibre Y_ab. is clipped to min(V_ab, u_a) -- which equals clipping it to u_a.
+ * (The paper indexes its tensor (c, n, m) and keeps groups on the last axis; that is this
+ * function applied to the transposed tensor, or bilevel_proj_l1inf on the (c*n) x m
+ * reshape.)  v_out / u_out have d0 entries (w and u).                               */
+int trilevel_proj_l1infinf(const float* Y /* device, d0*d1*d2 */, float* X /* device, same */,
+                           long long d0, long long d1, long long d2, float eta,
+                           void* workspace, size_t workspace_bytes,
+                           float* v_out /* device, d0; may be NULL */,
+                           float* u_out /* device, d0; may be NULL */, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLPROJ_H */

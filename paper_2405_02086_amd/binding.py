@@ -1,0 +1,193 @@
+"""ctypes binding for libmlproj.so (declared in include/mlproj.h).
+
+Argument marshalling only: every step of the projection runs in the HIP kernels.
+PyTorch is used for device memory and streams.  There is no CPU fallback: if the
+shared library has not been built, every entry point raises.
+"""
+import ctypes
+import os
+import struct
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmlproj.so")
+SRC_PATH = os.path.join(_HERE, "csrc", "mlproj.hip")
+
+L1INF, L11, L12, L1INFINF = 0, 1, 2, 3
+_VARIANTS = {"l1inf": L1INF, "l11": L11, "l12": L12, "tri": L1INFINF}
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    # keep the compiler from forming packed-fp32 VALU ops
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+]
+
+
+class MlprojError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().mlproj_status_string(status).decode() if _lib is not None else "?"
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def build(verbose=False):
+    """Compile csrc/mlproj.hip for gfx950 into libmlproj.so next to this file."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH, SRC_PATH]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or proc.returncode != 0:
+        print(" ".join(cmd))
+        print(proc.stdout + proc.stderr)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed building libmlproj.so")
+    global _lib
+    _lib = None
+    return LIB_PATH
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+            "There is no CPU fallback.")
+    L = ctypes.CDLL(LIB_PATH)
+    c_ll, c_sz, c_vp, c_f, c_i = ctypes.c_longlong, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_float, ctypes.c_int
+    L.mlproj_version.restype = c_i
+    L.mlproj_version.argtypes = []
+    L.mlproj_status_string.restype = ctypes.c_char_p
+    L.mlproj_status_string.argtypes = [c_i]
+    L.mlproj_workspace_bytes.restype = c_i
+    L.mlproj_workspace_bytes.argtypes = [c_i, c_ll, c_ll, c_ll, ctypes.POINTER(c_sz)]
+    L.mlproj_workspace_init.restype = c_i
+    L.mlproj_workspace_init.argtypes = [c_vp, c_sz, c_vp]
+    L.mlproj_norm_l1q.restype = c_i
+    L.mlproj_norm_l1q.argtypes = [c_vp, c_ll, c_ll, c_i, c_vp, c_sz, c_vp, c_vp, c_vp]
+    for name in ("bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12"):
+        fn = getattr(L, name)
+        fn.restype = c_i
+        fn.argtypes = [c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
+    L.trilevel_proj_l1infinf.restype = c_i
+    L.trilevel_proj_l1infinf.argtypes = [c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
+    _lib = L
+    return L
+
+
+EXPORTS = (
+    "mlproj_version", "mlproj_status_string", "mlproj_workspace_bytes", "mlproj_workspace_init",
+    "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
+    "trilevel_proj_l1infinf",
+)
+
+
+def _check(status, where):
+    if status != 0:
+        raise MlprojError(status, where)
+
+
+def workspace_bytes(variant, d0, d1, d2=1):
+    out = ctypes.c_size_t(0)
+    v = _VARIANTS.get(variant, variant)
+    _check(lib().mlproj_workspace_bytes(v, d0, d1, d2, ctypes.byref(out)), "mlproj_workspace_bytes")
+    return out.value
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class Workspace:
+    """Device scratch for one call at a time, prepared once with mlproj_workspace_init."""
+
+    def __init__(self, nbytes, device="cuda", stream=None):
+        import torch
+        nbytes = (int(nbytes) + 255) // 256 * 256
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        assert self.buf.data_ptr() % 256 == 0
+        self.nbytes = nbytes
+        _check(lib().mlproj_workspace_init(_ptr(self.buf), nbytes, _stream(stream)), "mlproj_workspace_init")
+
+    @classmethod
+    def for_call(cls, variant, d0, d1, d2=1, **kw):
+        return cls(workspace_bytes(variant, d0, d1, d2), **kw)
+
+    def result(self):
+        """Synchronise and decode the mlproj_result record at the head of the workspace."""
+        raw = bytes(self.buf[:64].cpu().numpy().tobytes())
+        tau, norm, vmax, n_active, inside, iters, sweeps, pending = struct.unpack_from("<dddIIIII", raw)
+        return {"tau": tau, "norm": norm, "vmax": vmax, "n_active": n_active,
+                "inside_ball": bool(inside), "search_iters": iters,
+                "inner_sweeps": sweeps, "inner_pending": pending}
+
+
+def _prep(Y, X):
+    import torch
+    assert Y.is_cuda and Y.dtype == torch.float32 and Y.is_contiguous(), "Y: contiguous fp32 device tensor"
+    if X is None:
+        X = torch.empty_like(Y)
+    assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and X.shape == Y.shape
+    return X
+
+
+def _bilevel(name, variant, Y, eta, X, workspace, v_out, u_out, stream):
+    assert Y.dim() == 2
+    n, m = Y.shape
+    X = _prep(Y, X)
+    if workspace is None:
+        workspace = Workspace.for_call(variant, n, m, device=Y.device, stream=stream)
+    st = getattr(lib(), name)(_ptr(Y), _ptr(X), n, m, ctypes.c_float(eta), _ptr(workspace.buf),
+                              workspace.nbytes, _ptr(v_out), _ptr(u_out), _stream(stream))
+    _check(st, name)
+    return X
+
+
+def bilevel_proj_l1inf(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
+    return _bilevel("bilevel_proj_l1inf", L1INF, Y, eta, X, workspace, v_out, u_out, stream)
+
+
+def bilevel_proj_l11(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
+    return _bilevel("bilevel_proj_l11", L11, Y, eta, X, workspace, v_out, u_out, stream)
+
+
+def bilevel_proj_l12(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
+    return _bilevel("bilevel_proj_l12", L12, Y, eta, X, workspace, v_out, u_out, stream)
+
+
+def trilevel_proj_l1infinf(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
+    assert Y.dim() == 3
+    d0, d1, d2 = Y.shape
+    X = _prep(Y, X)
+    if workspace is None:
+        workspace = Workspace.for_call(L1INFINF, d0, d1, d2, device=Y.device, stream=stream)
+    st = lib().trilevel_proj_l1infinf(_ptr(Y), _ptr(X), d0, d1, d2, ctypes.c_float(eta),
+                                      _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out),
+                                      _stream(stream))
+    _check(st, "trilevel_proj_l1infinf")
+    return X
+
+
+def norm_l1q(Y, variant, workspace=None, v_out=None, stream=None):
+    """||Y||_{1,q} computed on the device; returns a python float (synchronises)."""
+    import torch
+    assert Y.dim() == 2 and Y.is_cuda and Y.dtype == torch.float32 and Y.is_contiguous()
+    n, m = Y.shape
+    v = _VARIANTS.get(variant, variant)
+    if workspace is None:
+        workspace = Workspace.for_call(v, n, m, device=Y.device, stream=stream)
+    out = torch.empty(1, dtype=torch.float64, device=Y.device)
+    st = lib().mlproj_norm_l1q(_ptr(Y), n, m, v, _ptr(workspace.buf), workspace.nbytes, _ptr(out),
+                               _ptr(v_out), _stream(stream))
+    _check(st, "mlproj_norm_l1q")
+    return float(out.item())

@@ -1,0 +1,98 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every function the
+header declares, sizes workspaces sanely, and rejects bad arguments before enqueuing."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2405_02086_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(1 << 20)       # non-null, 256-aligned; never dereferenced on these paths
+F = ctypes.c_float
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        binding.build()
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mlproj.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", text, flags=re.M)))
+
+
+def test_every_declared_function_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert lib.mlproj_version() >= 100
+    seen = {lib.mlproj_status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and b"unknown status" not in seen
+    assert lib.mlproj_status_string(-99) == b"unknown status"
+
+
+def test_workspace_sizes(lib):
+    small = binding.workspace_bytes("l1inf", 1, 1)
+    assert 0 < small <= 1 << 16
+    for variant, dims in [("l1inf", (4096, 4096, 1)), ("l1inf", (262144, 256, 1)), ("l1inf", (256, 262144, 1)),
+                          ("l11", (16384, 16384, 1)), ("l12", (16384, 16384, 1)), ("tri", (256, 256, 256))]:
+        b = binding.workspace_bytes(variant, *dims)
+        assert b % 256 == 0 and small <= b < 64 << 20, (variant, dims, b)
+    out = ctypes.c_size_t(0)
+    assert lib.mlproj_workspace_bytes(0, 0, 4, 1, ctypes.byref(out)) == -2
+    assert lib.mlproj_workspace_bytes(0, 4, -1, 1, ctypes.byref(out)) == -2
+    assert lib.mlproj_workspace_bytes(0, 4, 4, 2, ctypes.byref(out)) == -2     # bi-level takes d2 = 1
+    assert lib.mlproj_workspace_bytes(9, 4, 4, 1, ctypes.byref(out)) == -6
+    assert lib.mlproj_workspace_bytes(0, 1 << 30, 1 << 30, 1, ctypes.byref(out)) == -3
+    assert lib.mlproj_workspace_bytes(0, 4, 1 << 32, 1, ctypes.byref(out)) == -3
+    assert lib.mlproj_workspace_bytes(0, 4, 4, 1, None) == -1
+
+
+@pytest.mark.parametrize("name", ["bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12"])
+def test_bilevel_argument_checks_happen_before_any_launch(lib, name):
+    fn = getattr(lib, name)
+    big = 1 << 30
+    assert fn(None, FAKE, 4, 4, F(1), FAKE, big, None, None, None) == -1
+    assert fn(FAKE, None, 4, 4, F(1), FAKE, big, None, None, None) == -1
+    assert fn(FAKE, FAKE, 4, 4, F(1), None, big, None, None, None) == -1
+    assert fn(FAKE, FAKE, 0, 4, F(1), FAKE, big, None, None, None) == -2
+    assert fn(FAKE, FAKE, 4, -3, F(1), FAKE, big, None, None, None) == -2
+    assert fn(FAKE, FAKE, 1 << 21, 1 << 21, F(1), FAKE, big, None, None, None) == -3
+    assert fn(FAKE, FAKE, 4, 4, F(-1e-9), FAKE, big, None, None, None) == -4
+    assert fn(FAKE, FAKE, 4, 4, F(float("nan")), FAKE, big, None, None, None) == -4
+    assert fn(FAKE, FAKE, 4, 4, F(float("inf")), FAKE, big, None, None, None) == -4
+    assert fn(FAKE, FAKE, 4, 4, F(1), FAKE, 512, None, None, None) == -5            # too small
+    assert fn(FAKE, FAKE, 4, 4, F(1), ctypes.c_void_p((1 << 20) + 64), big, None, None, None) == -5
+    assert fn(ctypes.c_void_p((1 << 20) + 2), FAKE, 4, 4, F(1), FAKE, big, None, None, None) == -7
+
+
+def test_trilevel_and_norm_argument_checks(lib):
+    big = 1 << 30
+    tri = lib.trilevel_proj_l1infinf
+    assert tri(None, FAKE, 2, 2, 2, F(1), FAKE, big, None, None, None) == -1
+    assert tri(FAKE, FAKE, 2, 0, 2, F(1), FAKE, big, None, None, None) == -2
+    assert tri(FAKE, FAKE, 2, 2, 2, F(-1), FAKE, big, None, None, None) == -4
+    assert tri(FAKE, FAKE, 2, 2, 2, F(1), FAKE, 16, None, None, None) == -5
+    assert tri(FAKE, FAKE, 1 << 14, 1 << 14, 1 << 14, F(1), FAKE, big, None, None, None) == -3
+    nrm = lib.mlproj_norm_l1q
+    assert nrm(None, 4, 4, 0, FAKE, big, None, None, None) == -1
+    assert nrm(FAKE, 4, 4, 7, FAKE, big, None, None, None) == -6
+    assert nrm(FAKE, 4, 0, 0, FAKE, big, None, None, None) == -2
+    assert lib.mlproj_workspace_init(None, 4096, None) == -1
+    assert lib.mlproj_workspace_init(FAKE, 10, None) == -5
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.lib()
