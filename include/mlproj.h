@@ -20,12 +20,10 @@
  *  - The caller owns every buffer.  X may alias Y exactly (in-place); any other
  *    overlap between buffers is undefined.  Y must hold finite values.
  *  - `workspace`: device scratch of at least mlproj_workspace_bytes(...) bytes,
- *    256-byte aligned, prepared ONCE after allocation by mlproj_workspace_init()
- *    (it clears the inter-workgroup tickets).  Every call leaves the workspace
- *    ready for the next one.  One workspace serves one call at a time: two calls
- *    that may overlap on the GPU (different streams) need two workspaces.
- *    A workspace sized for one shape serves any call whose own requirement is
- *    not larger.
+ *    256-byte aligned.  Its contents on entry do not matter (no clearing is
+ *    needed, ever).  One workspace serves one call at a time: two calls that may
+ *    overlap on the GPU (different streams) need two workspaces.  A workspace
+ *    sized for one shape serves any call whose own requirement is not larger.
  *  - After a call has completed on the stream, the first bytes of the workspace
  *    hold a mlproj_result record (threshold tau, norm, active count, ...).
  *  - v_out / u_out: optional device arrays (NULL to skip) that receive the
@@ -67,12 +65,12 @@ typedef enum mlproj_variant {
 
 /* Record left at offset 0 of the workspace by every projection / norm call. */
 typedef struct mlproj_result {
-  double tau;            /* threshold of step 2: u_j = max(v_j - tau, 0); 0 when Y is inside the ball */
+  double tau;            /* threshold of u = P^1_eta(v): u_j = max(v_j - tau, 0); 0 inside the ball  */
   double norm;           /* ||Y||_{1,q} = sum_j v_j (fp64)                                            */
   double vmax;           /* max_j v_j                                                                 */
   uint32_t n_active;     /* number of groups with u_j > 0                                             */
   uint32_t inside_ball;  /* 1 when ||Y||_{1,q} <= eta (X = Y)                                         */
-  uint32_t search_iters; /* fixed-point iterations the threshold search of step 2 took                */
+  uint32_t search_iters; /* fixed-point iterations the search for tau took                            */
   uint32_t inner_sweeps; /* l1,1 only: passes over Y the per-column threshold searches took           */
   uint32_t inner_pending;/* l1,1 only: columns whose inner search had not converged (0 = exact)       */
   uint32_t reserved[7];
@@ -88,10 +86,6 @@ const char* mlproj_status_string(int status);
  * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.            */
 int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2,
                            size_t* bytes_out /* host */);
-
-/* Prepare a freshly allocated workspace (clears it with a fill kernel on `stream`).
- * Needed once per allocation, not per call.                                      */
-int mlproj_workspace_init(void* workspace /* device */, size_t workspace_bytes, void* stream);
 
 /* ||Y||_{1,q} = sum_j ||y_j||_q (Sec. 2, Eq. 1-2 with p = 1; Eq. 10 for q = inf).
  * q_variant is MLPROJ_L1INF, MLPROJ_L11 or MLPROJ_L12.  The fp64 norm is written to
@@ -121,6 +115,18 @@ int bilevel_proj_l11(const float* Y, float* X, long long n, long long m, float e
 int bilevel_proj_l12(const float* Y, float* X, long long n, long long m, float eta,
                      void* workspace, size_t workspace_bytes,
                      float* v_out, float* u_out, void* stream);
+
+/* The two halves of a bi-level call, for callers that want the radii before (or without)
+ * writing X.  bilevel_radii computes the aggregate v and u = P^1_eta(v) of Alg. 1 (for
+ * MLPROJ_L11 also the per-column thresholds Alg. 3 needs) and leaves the outcome in the
+ * workspace; bilevel_apply then maps the columns, x_j = P^q_{u_j}(y_j), from that workspace,
+ * on the same Y, n, m and variant.  bilevel_proj_* is exactly bilevel_radii then bilevel_apply. */
+int bilevel_radii(int variant, const float* Y /* device, n*m */, long long n, long long m, float eta,
+                  void* workspace /* device */, size_t workspace_bytes,
+                  float* v_out /* device, m; may be NULL */, void* stream);
+int bilevel_apply(int variant, const float* Y /* device, n*m */, float* X /* device, n*m */,
+                  long long n, long long m, void* workspace /* device */, size_t workspace_bytes,
+                  float* u_out /* device, m; may be NULL */, void* stream);
 
 /* TP^{1,inf,inf}_eta (Sec. 5.1, Def. 5.1, Alg. 5; iterative form in the appendix) on a
  * C-order tensor Y[a][b][c] of shape (d0, d1, d2).  Groups live on axis 0: the inner

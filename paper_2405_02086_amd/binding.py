@@ -65,14 +65,16 @@ def lib():
     L.mlproj_status_string.argtypes = [c_i]
     L.mlproj_workspace_bytes.restype = c_i
     L.mlproj_workspace_bytes.argtypes = [c_i, c_ll, c_ll, c_ll, ctypes.POINTER(c_sz)]
-    L.mlproj_workspace_init.restype = c_i
-    L.mlproj_workspace_init.argtypes = [c_vp, c_sz, c_vp]
     L.mlproj_norm_l1q.restype = c_i
     L.mlproj_norm_l1q.argtypes = [c_vp, c_ll, c_ll, c_i, c_vp, c_sz, c_vp, c_vp, c_vp]
     for name in ("bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12"):
         fn = getattr(L, name)
         fn.restype = c_i
         fn.argtypes = [c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
+    L.bilevel_radii.restype = c_i
+    L.bilevel_radii.argtypes = [c_i, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp]
+    L.bilevel_apply.restype = c_i
+    L.bilevel_apply.argtypes = [c_i, c_vp, c_vp, c_ll, c_ll, c_vp, c_sz, c_vp, c_vp]
     L.trilevel_proj_l1infinf.restype = c_i
     L.trilevel_proj_l1infinf.argtypes = [c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     _lib = L
@@ -80,9 +82,9 @@ def lib():
 
 
 EXPORTS = (
-    "mlproj_version", "mlproj_status_string", "mlproj_workspace_bytes", "mlproj_workspace_init",
+    "mlproj_version", "mlproj_status_string", "mlproj_workspace_bytes",
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
-    "trilevel_proj_l1infinf",
+    "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
 )
 
 
@@ -109,7 +111,7 @@ def _stream(stream):
 
 
 class Workspace:
-    """Device scratch for one call at a time, prepared once with mlproj_workspace_init."""
+    """Device scratch for one call at a time; needs no initialisation."""
 
     def __init__(self, nbytes, device="cuda", stream=None):
         import torch
@@ -117,7 +119,6 @@ class Workspace:
         self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
         assert self.buf.data_ptr() % 256 == 0
         self.nbytes = nbytes
-        _check(lib().mlproj_workspace_init(_ptr(self.buf), nbytes, _stream(stream)), "mlproj_workspace_init")
 
     @classmethod
     def for_call(cls, variant, d0, d1, d2=1, **kw):
@@ -163,6 +164,21 @@ def bilevel_proj_l11(Y, eta, X=None, workspace=None, v_out=None, u_out=None, str
 
 def bilevel_proj_l12(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
     return _bilevel("bilevel_proj_l12", L12, Y, eta, X, workspace, v_out, u_out, stream)
+
+
+def bilevel_radii(variant, Y, eta, workspace, v_out=None, stream=None):
+    n, m = Y.shape
+    v = _VARIANTS.get(variant, variant)
+    _check(lib().bilevel_radii(v, _ptr(Y), n, m, ctypes.c_float(eta), _ptr(workspace.buf), workspace.nbytes,
+                               _ptr(v_out), _stream(stream)), "bilevel_radii")
+
+
+def bilevel_apply(variant, Y, X, workspace, u_out=None, stream=None):
+    n, m = Y.shape
+    v = _VARIANTS.get(variant, variant)
+    _check(lib().bilevel_apply(v, _ptr(Y), _ptr(X), n, m, _ptr(workspace.buf), workspace.nbytes,
+                               _ptr(u_out), _stream(stream)), "bilevel_apply")
+    return X
 
 
 def trilevel_proj_l1infinf(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):

@@ -34,7 +34,7 @@ def test_every_declared_function_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert lib.mlproj_version() >= 100
+    assert lib.mlproj_version() >= 200
     seen = {lib.mlproj_status_string(s) for s in range(0, -9, -1)}
     assert len(seen) == 9 and b"unknown status" not in seen
     assert lib.mlproj_status_string(-99) == b"unknown status"
@@ -87,8 +87,11 @@ def test_trilevel_and_norm_argument_checks(lib):
     assert nrm(None, 4, 4, 0, FAKE, big, None, None, None) == -1
     assert nrm(FAKE, 4, 4, 7, FAKE, big, None, None, None) == -6
     assert nrm(FAKE, 4, 0, 0, FAKE, big, None, None, None) == -2
-    assert lib.mlproj_workspace_init(None, 4096, None) == -1
-    assert lib.mlproj_workspace_init(FAKE, 10, None) == -5
+    assert lib.bilevel_radii(0, None, 4, 4, F(1), FAKE, big, None, None) == -1
+    assert lib.bilevel_radii(5, FAKE, 4, 4, F(1), FAKE, big, None, None) == -6
+    assert lib.bilevel_radii(1, FAKE, 4, 4, F(-2), FAKE, big, None, None) == -4
+    assert lib.bilevel_apply(0, FAKE, None, 4, 4, FAKE, big, None, None) == -1
+    assert lib.bilevel_apply(2, FAKE, FAKE, 4, 4, FAKE, 64, None, None) == -5
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
