@@ -56,22 +56,32 @@ def time_calls(torch, fn, pairs, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def time_stages(torch, stages, pairs, steps, warmup):
-    """Average duration (ms) of each stage, from HIP events recorded on the launch stream
-    around every stage call inside the same rotating loop."""
+KERNEL_LABELS = {
+    4: ["colagg", "reduce", "colmap+search"],
+    5: ["colagg", "reduce", "search", "colmap"],
+    6: ["colagg", "reduce", "search", "l11_sweeps", "colmap"],
+}
+
+
+def time_kernels(torch, mp, fn, pairs, steps, warmup):
+    """Average duration (ms) of every kernel of a call, from HIP events the library records on
+    the launch stream before each kernel and after the last one (mlproj_trace_*), inside the
+    same rotating loop the wall-clock figure uses."""
     for i in range(warmup):
-        for st in stages:
-            st(*pairs[i % len(pairs)])
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in stages]
-          for _ in range(steps)]
+        fn(*pairs[i % len(pairs)])
     torch.cuda.synchronize()
-    for i in range(steps):
-        for k, st in enumerate(stages):
-            ev[i][k][0].record()
-            st(*pairs[i % len(pairs)])
-            ev[i][k][1].record()
-    torch.cuda.synchronize()
-    return [statistics.mean(e[k][0].elapsed_time(e[k][1]) for e in ev) for k in range(len(stages))]
+    tr = mp.KernelTrace(steps * 8)
+    with tr:
+        for i in range(steps):
+            fn(*pairs[i % len(pairs)])
+    d = tr.durations_ms()
+    per_call = tr.count // steps
+    tr.close()
+    labels = KERNEL_LABELS[per_call]
+    out = {}
+    for k, name in enumerate(labels):
+        out[name] = statistics.mean(d[i * per_call + k] for i in range(steps))
+    return out
 
 
 def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True):
@@ -89,10 +99,7 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True):
     fn = getattr(mp, "bilevel_proj_" + variant)
     ms = time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, steps, warmup)
     res = ws.result()
-    st_ms = time_stages(
-        torch,
-        [lambda Y, X: mp.bilevel_radii(variant, Y, eta, ws), lambda Y, X: mp.bilevel_apply(variant, Y, X, ws)],
-        pairs, min(steps, 100), min(warmup, 10))
+    k_ms = time_kernels(torch, mp, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, min(steps, 100), min(warmup, 10))
     warm_ms = time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs[:1], steps, warmup) if npairs > 1 else ms
     elems = n * m
     out = {
@@ -101,7 +108,7 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True):
         "eff_GBps_8B": 8.0 * elems / ms / 1e6,
         "frac_of_peak_8B": 8.0 * elems / ms / 1e6 / HBM_PEAK_GBS,
         "eff_GBps_12B": 12.0 * elems / ms / 1e6,
-        "stage_ms": {"radii": st_ms[0], "apply": st_ms[1]},
+        "kernel_ms": k_ms,
         "tau": res["tau"], "n_active": res["n_active"], "search_iters": res["search_iters"],
         "inner_sweeps": res["inner_sweeps"], "inner_pending": res["inner_pending"],
     }
@@ -142,16 +149,17 @@ def main():
     head = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, args.steps, args.warmup)
     n, m = Y.shape
     elems = n * m
-    # the dominant kernel is the apply pass: it reads Y once and writes X once
-    apply_ms = head["stage_ms"]["apply"]
+    # the dominant kernel is the map pass: it reads Y once and writes X once (8 B/element)
+    kms = head["kernel_ms"]
+    map_name = [k for k in kms if k.startswith("colmap")][0]
+    map_ms = kms[map_name]
     roofline = {
-        "bound": "hbm", "kernel": "colmap_kernel<l1inf> (clip pass: 8 B/element)",
-        "achieved": 8.0 * elems / apply_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": 8.0 * elems / apply_ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
-        "kernel_ms": apply_ms,
-        "other_kernels": {"colagg_kernel<l1inf> (aggregate + search: 4 B/element)": {
-            "kernel_ms": head["stage_ms"]["radii"],
-            "achieved": 4.0 * elems / head["stage_ms"]["radii"] / 1e6}},
+        "bound": "hbm", "kernel": "colmap_kernel<l1inf> (%s; reads Y, writes X: 8 B/element)" % map_name,
+        "achieved": 8.0 * elems / map_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": 8.0 * elems / map_ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
+        "kernel_ms": map_ms,
+        "other_kernels": {"colagg_kernel<l1inf> (reads Y: 4 B/element)": {
+            "kernel_ms": kms["colagg"], "achieved": 4.0 * elems / kms["colagg"] / 1e6}},
     }
     line = {
         "metric": "effective HBM GB/s of one bi-level l1,inf projection (8 B/element: read Y, write X), cold caches",

@@ -82,6 +82,15 @@ int mlproj_version(void);
 /* Static, human-readable text for a status code. */
 const char* mlproj_status_string(int status);
 
+/* Per-kernel timing aid.  Between mlproj_trace_begin and mlproj_trace_end, every projection
+ * or norm call made by the calling thread records one of the caller's HIP events
+ * (events[0], events[1], ... each a hipEvent_t created by the caller) on its stream before
+ * each kernel it launches and one after the last kernel; recording stops silently when
+ * `capacity` events are used.  mlproj_trace_end closes the trace and returns how many events
+ * were recorded.  Off by default; adds nothing to calls made outside a trace.              */
+int mlproj_trace_begin(void** events /* host array of hipEvent_t */, int capacity);
+int mlproj_trace_end(void);
+
 /* Bytes of workspace a call of `variant` on dims (d0, d1, d2) needs; bi-level
  * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.            */
 int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2,

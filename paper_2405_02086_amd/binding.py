@@ -65,6 +65,10 @@ def lib():
     L.mlproj_status_string.argtypes = [c_i]
     L.mlproj_workspace_bytes.restype = c_i
     L.mlproj_workspace_bytes.argtypes = [c_i, c_ll, c_ll, c_ll, ctypes.POINTER(c_sz)]
+    L.mlproj_trace_begin.restype = c_i
+    L.mlproj_trace_begin.argtypes = [ctypes.POINTER(c_vp), c_i]
+    L.mlproj_trace_end.restype = c_i
+    L.mlproj_trace_end.argtypes = []
     L.mlproj_norm_l1q.restype = c_i
     L.mlproj_norm_l1q.argtypes = [c_vp, c_ll, c_ll, c_i, c_vp, c_sz, c_vp, c_vp, c_vp]
     for name in ("bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12"):
@@ -82,7 +86,7 @@ def lib():
 
 
 EXPORTS = (
-    "mlproj_version", "mlproj_status_string", "mlproj_workspace_bytes",
+    "mlproj_version", "mlproj_status_string", "mlproj_workspace_bytes", "mlproj_trace_begin", "mlproj_trace_end",
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
 )
@@ -207,3 +211,44 @@ def norm_l1q(Y, variant, workspace=None, v_out=None, stream=None):
                                _ptr(v_out), _stream(stream))
     _check(st, "mlproj_norm_l1q")
     return float(out.item())
+
+
+class KernelTrace:
+    """Times the kernels inside library calls with HIP events (mlproj_trace_begin / _end).
+
+    with KernelTrace(capacity) as tr: ...calls...; tr.durations_ms() then gives the time
+    between consecutive events, i.e. one entry per kernel launched, in launch order.
+    """
+
+    def __init__(self, capacity):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.capacity = capacity
+        self.events = (ctypes.c_void_p * capacity)()
+        for i in range(capacity):
+            ev = ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(ev)) == 0
+            self.events[i] = ev
+        self.count = 0
+
+    def __enter__(self):
+        _check(lib().mlproj_trace_begin(self.events, self.capacity), "mlproj_trace_begin")
+        return self
+
+    def __exit__(self, *exc):
+        self.count = lib().mlproj_trace_end()
+        return False
+
+    def durations_ms(self):
+        import torch
+        torch.cuda.synchronize()
+        out = []
+        for i in range(self.count - 1):
+            ms = ctypes.c_float()
+            assert self.hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(self.events[i]),
+                                                ctypes.c_void_p(self.events[i + 1])) == 0
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for i in range(self.capacity):
+            self.hip.hipEventDestroy(ctypes.c_void_p(self.events[i]))

@@ -34,6 +34,7 @@ constexpr int MAX_INNER_SWEEPS = 32;     // l1,1: passes over Y allowed to the i
 constexpr int QINF = MLPROJ_L1INF, Q1 = MLPROJ_L11, Q2 = MLPROJ_L12;
 constexpr int MODE_PROJECT = 0, MODE_NORM = 1;
 constexpr long long TARGET_WGS = 512;    // streaming workgroups per launch (2 per CU)
+constexpr long long FUSED_SEARCH_MAX = (long long)WG * SEARCH_CACHE;  // groups a map workgroup can search in registers
 
 // ------------------------------------------------------------------ host-side geometry
 // A matrix is cut into column tiles of 64*vec columns; each tile is shared by `groups` row
@@ -146,20 +147,59 @@ __device__ __forceinline__ void store_row_nt(float* p, const float (&x)[VEC]) {
   }
 }
 
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-  for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_down(x, o, WAVE);
-  return x;
+// Wavefront reductions on the DPP crossbar (no LDS round trips).  Each step adds the value of
+// another lane: swap within pairs, swap pairs within quads, shift the 16-lane row by 4 and by
+// 8, then carry row totals across the four rows; lanes with no source lane add 0, which is
+// neutral for sums and for maxima of non-negative values.  Lane 63 ends with the total and is
+// broadcast.  The order of operations is fixed, so results repeat bit for bit.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_u32(unsigned x) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
 }
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+  const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+  const unsigned lo = dpp_u32<CTRL>((unsigned)b), hi = dpp_u32<CTRL>((unsigned)(b >> 32));
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+constexpr int DPP_SWAP1 = 0xb1, DPP_SWAP2 = 0x4e, DPP_SHR4 = 0x114, DPP_SHR8 = 0x118,
+              DPP_BCAST15 = 0x142, DPP_BCAST31 = 0x143;
+
+__device__ __forceinline__ unsigned bcast63_u32(unsigned x) {
+  return (unsigned)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ double bcast63_f64(double x) {
+  const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+  const unsigned lo = bcast63_u32((unsigned)b), hi = bcast63_u32((unsigned)(b >> 32));
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ double wave_sum(double x) {
+  x += dpp_f64<DPP_SWAP1>(x);
+  x += dpp_f64<DPP_SWAP2>(x);
+  x += dpp_f64<DPP_SHR4>(x);
+  x += dpp_f64<DPP_SHR8>(x);
+  x += dpp_f64<DPP_BCAST15>(x);
+  x += dpp_f64<DPP_BCAST31>(x);
+  return bcast63_f64(x);
+}
+// maximum of non-negative values
 __device__ __forceinline__ double wave_max(double x) {
-#pragma unroll
-  for (int o = WAVE / 2; o > 0; o >>= 1) x = fmax(x, __shfl_down(x, o, WAVE));
-  return x;
+  x = fmax(x, dpp_f64<DPP_SWAP1>(x));
+  x = fmax(x, dpp_f64<DPP_SWAP2>(x));
+  x = fmax(x, dpp_f64<DPP_SHR4>(x));
+  x = fmax(x, dpp_f64<DPP_SHR8>(x));
+  x = fmax(x, dpp_f64<DPP_BCAST15>(x));
+  x = fmax(x, dpp_f64<DPP_BCAST31>(x));
+  return bcast63_f64(x);
 }
 __device__ __forceinline__ unsigned wave_sum_u(unsigned x) {
-#pragma unroll
-  for (int o = WAVE / 2; o > 0; o >>= 1) x += __shfl_down(x, o, WAVE);
-  return x;
+  x += dpp_u32<DPP_SWAP1>(x);
+  x += dpp_u32<DPP_SWAP2>(x);
+  x += dpp_u32<DPP_SHR4>(x);
+  x += dpp_u32<DPP_SHR8>(x);
+  x += dpp_u32<DPP_BCAST15>(x);
+  x += dpp_u32<DPP_BCAST31>(x);
+  return bcast63_u32(x);
 }
 
 // Workgroup-wide reductions for NW wavefronts; every thread gets the result.  The order of
@@ -306,46 +346,57 @@ __global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ pa
 // sum(v) <= eta, otherwise the root of sum_j max(v_j - tau, 0) = eta.  The root is reached
 // by the fixed point tau <- (sum_{v_j > tau} v_j - eta) / #{v_j > tau}, started from a lower
 // bound; tau rises monotonically, the active set only shrinks, and when it stops shrinking
-// tau is exactly (sum over the final active set - eta) / K, in fp64.  One workgroup.
-__global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
-                                                     int mode, double* __restrict__ norm_out) {
-  __shared__ BlockScratch<SWAVES> s;
+// tau is exactly (sum over the final active set - eta) / K, in fp64.
+// Run by one whole workgroup of NT threads; every thread returns the same record.  Because
+// the arithmetic and its order are fixed, any number of workgroups that run it on the same v
+// get the same bits, which lets the map kernels run it redundantly instead of waiting for a
+// separate one-workgroup kernel.
+struct SearchOut {
+  double tau, total, vmax;
+  unsigned active, iters, inside;
+};
+
+template <int NT>
+__device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, long long ngroups,
+                                                  double eta, int mode,
+                                                  BlockScratch<NT / WAVE>& s) {
   const int tid = threadIdx.x;
   double vr[SEARCH_CACHE];
   double a = 0.0, mx = 0.0;
 #pragma unroll
   for (int k = 0; k < SEARCH_CACHE; ++k) {
-    const long long i = tid + (long long)k * SWG;
-    vr[k] = i < ngroups ? ws.v[i] : 0.0;  // 0 is never active: tau >= 0 and the test is strict
+    const long long i = tid + (long long)k * NT;
+    vr[k] = i < ngroups ? v[i] : 0.0;  // 0 is never active: tau >= 0 and the test is strict
     a += vr[k];
     mx = fmax(mx, vr[k]);
   }
-  for (long long i = tid + (long long)SEARCH_CACHE * SWG; i < ngroups; i += SWG) {
-    const double x = ws.v[i];
+  for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT) {
+    const double x = v[i];
     a += x;
     mx = fmax(mx, x);
   }
-  const double total = block_sum(a, s);
-  const double vmax = block_max(mx, s);
-  if (tid <= MAX_INNER_SWEEPS) ws.pending[tid] = 0u;
-
-  double tau = 0.0;
-  unsigned active = 0, iters = 0, inside = 0;
+  SearchOut o;
+  o.total = block_sum(a, s);
+  o.vmax = block_max(mx, s);
+  o.tau = 0.0;
+  o.active = 0;
+  o.iters = 0;
+  o.inside = 0;
   if (mode == MODE_NORM) {
     // norm only: nothing to search
   } else if (eta == 0.0) {
-    tau = vmax;  // nothing exceeds vmax: every u_j is 0
-  } else if (total <= eta) {
-    inside = 1;  // already in the ball: tau = 0, u = v
+    o.tau = o.vmax;  // nothing exceeds vmax: every u_j is 0
+  } else if (o.total <= eta) {
+    o.inside = 1;  // already in the ball: tau = 0, u = v
     unsigned c = 0;
 #pragma unroll
     for (int k = 0; k < SEARCH_CACHE; ++k) c += vr[k] > 0.0 ? 1u : 0u;
-    for (long long i = tid + (long long)SEARCH_CACHE * SWG; i < ngroups; i += SWG)
-      c += ws.v[i] > 0.0 ? 1u : 0u;
-    active = block_sum_u(c, s);
+    for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT)
+      c += v[i] > 0.0 ? 1u : 0u;
+    o.active = block_sum_u(c, s);
   } else {
     // two lower bounds on the root: all groups active, and only the largest active
-    tau = fmax((total - eta) / (double)ngroups, vmax - eta);
+    double tau = fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
     unsigned kprev = 0xffffffffu;
     for (;;) {
       double sum = 0.0;
@@ -354,32 +405,44 @@ __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, d
       for (int k = 0; k < SEARCH_CACHE; ++k) {
         if (vr[k] > tau) { sum += vr[k]; ++cnt; }
       }
-      for (long long i = tid + (long long)SEARCH_CACHE * SWG; i < ngroups; i += SWG) {
-        const double x = ws.v[i];
+      for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT) {
+        const double x = v[i];
         if (x > tau) { sum += x; ++cnt; }
       }
       const double S = block_sum(sum, s);
       const unsigned K = block_sum_u(cnt, s);
-      active = K;
+      o.active = K;
       if (K == 0u || K == kprev) break;  // K == 0: eta below the resolution of vmax
       kprev = K;
       const double t = (S - eta) / (double)K;
       if (t > tau) tau = t;
-      ++iters;
+      ++o.iters;
     }
+    o.tau = tau;
   }
-  if (tid == 0) {
-    mlproj_result* r = ws.res;
-    r->tau = tau;
-    r->norm = total;
-    r->vmax = vmax;
-    r->n_active = active;
-    r->inside_ball = inside;
-    r->search_iters = iters;
-    r->inner_sweeps = 0;
-    r->inner_pending = 0;
-    if (norm_out) *norm_out = total;
-  }
+  return o;
+}
+
+__device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
+                                             double* __restrict__ norm_out) {
+  mlproj_result* r = ws.res;
+  r->tau = o.tau;
+  r->norm = o.total;
+  r->vmax = o.vmax;
+  r->n_active = o.active;
+  r->inside_ball = o.inside;
+  r->search_iters = o.iters;
+  r->inner_sweeps = 0;
+  r->inner_pending = 0;
+  if (norm_out) *norm_out = o.total;
+}
+
+__global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
+                                                     int mode, double* __restrict__ norm_out) {
+  __shared__ BlockScratch<SWAVES> s;
+  const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, s);
+  if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
+  if (threadIdx.x == 0) write_result(ws, o, norm_out);
 }
 
 // ------------------------------------------------------------------ per-column map
@@ -389,20 +452,32 @@ __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, d
 //   q = 1   : X = sign(Y) max(|Y| - tau_j, 0)    with tau_j from the inner searches
 // Row blocks are visited from the bottom up, the reverse of the aggregate pass, so the rows
 // read last there (the ones most likely still cached) are read first here.
+// With fused_eta >= 0 every workgroup first runs the threshold search itself (see
+// search_block) and workgroup 0 files the result record; otherwise tau is read from it.
 template <int Q, int VEC, bool XVEC>
 __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, long long n,
                                                     long long m, Geometry g, Ws ws,
-                                                    float* __restrict__ u_out) {
+                                                    float* __restrict__ u_out, double fused_eta) {
   constexpr int TILE_W = WAVE * VEC;
+  __shared__ BlockScratch<WAVES> bs;
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
   const long long grp = blockIdx.x / g.tiles;
   const long long col0 = t * TILE_W + (long long)lane * VEC;
-  if (col0 >= m) return;
 
-  const double tau = ws.res->tau;
-  const bool inside = ws.res->inside_ball != 0u;
+  double tau;
+  bool inside;
+  if (fused_eta >= 0.0) {
+    const SearchOut o = search_block<WG>(ws.v, m, fused_eta, MODE_PROJECT, bs);
+    tau = o.tau;
+    inside = o.inside != 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) write_result(ws, o, nullptr);
+  } else {
+    tau = ws.res->tau;
+    inside = ws.res->inside_ball != 0u;
+  }
+  if (col0 >= m) return;
   float uf[VEC];
   double par[VEC];  // q = 2: scale u_j / v_j;  q = 1: inner threshold tau_j
 #pragma unroll
@@ -632,12 +707,21 @@ __global__ __launch_bounds__(WG) void slabagg_kernel(const float* __restrict__ Y
 template <int VEC, bool XVEC>
 __global__ __launch_bounds__(WG) void slabmap_kernel(const float* Y, float* X, long long d0,
                                                      long long len, Geometry g, Ws ws,
-                                                     float* __restrict__ u_out) {
+                                                     float* __restrict__ u_out, double fused_eta) {
+  __shared__ BlockScratch<WAVES> bs;
   const long long a = d0 - 1 - blockIdx.x / g.groups;
   const long long c = blockIdx.x % g.groups;
   const long long lo = c * g.span;
   const long long hi = (lo + g.span < len) ? lo + g.span : len;
-  const float u = (float)fmax(ws.v[a] - ws.res->tau, 0.0);
+  double tau;
+  if (fused_eta >= 0.0) {
+    const SearchOut o = search_block<WG>(ws.v, d0, fused_eta, MODE_PROJECT, bs);
+    tau = o.tau;
+    if (blockIdx.x == 0 && threadIdx.x == 0) write_result(ws, o, nullptr);
+  } else {
+    tau = ws.res->tau;
+  }
+  const float u = (float)fmax(ws.v[a] - tau, 0.0);
   if (u_out && c == 0 && threadIdx.x == 0) u_out[a] = u;
   const float* p = Y + a * len;
   float* q = X + a * len;
@@ -717,6 +801,20 @@ static int check_radius(float eta) {
 
 static int launch_status() { return hipGetLastError() == hipSuccess ? MLPROJ_OK : MLPROJ_ERR_LAUNCH; }
 
+// Optional per-kernel timing: while a trace is open on the calling thread, an event is
+// recorded on the stream before every kernel of a call and after its last one.
+struct Trace {
+  hipEvent_t* events = nullptr;
+  int capacity = 0;
+  int count = 0;
+};
+static thread_local Trace g_trace;
+
+static inline void mark(hipStream_t stream) {
+  if (g_trace.events && g_trace.count < g_trace.capacity)
+    (void)hipEventRecord(g_trace.events[g_trace.count++], stream);
+}
+
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
 // STAGE_APPLY = the per-column map.
 template <int Q>
@@ -744,16 +842,26 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
   const dim3 rgrid((unsigned)cdiv(m, WAVE)), rblock(SWG);
+  // A whole call on few enough groups lets every map workgroup find tau by itself, which
+  // takes the one-workgroup search kernel off the critical path.
+  const bool fuse = mode == MODE_PROJECT && stages == STAGE_ALL && Q != Q1 && m <= FUSED_SEARCH_MAX;
+  const double fused_eta = fuse ? (double)eta : -1.0;
 
   if (stages & STAGE_AGGREGATE) {
+    mark(stream);
     if (vec == 4)
       hipLaunchKernelGGL((colagg_kernel<Q, 4>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     else
       hipLaunchKernelGGL((colagg_kernel<Q, 1>), grid, block, 0, stream, Y, n, m, g, ws.partial);
+    mark(stream);
     hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, ws.v, v_out);
-    hipLaunchKernelGGL(search_kernel, dim3(1), rblock, 0, stream, ws, m, (double)eta, mode, norm_out);
-    if (mode == MODE_NORM) return launch_status();
+    if (!fuse) {
+      mark(stream);
+      hipLaunchKernelGGL(search_kernel, dim3(1), rblock, 0, stream, ws, m, (double)eta, mode, norm_out);
+    }
+    if (mode == MODE_NORM) { mark(stream); return launch_status(); }
     if constexpr (Q == Q1) {
+      mark(stream);
       for (int s = 0; s < MAX_INNER_SWEEPS; ++s) {
         if (s == 0) {
           if (vec == 4) hipLaunchKernelGGL((l11_sweep_kernel<4, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
@@ -769,13 +877,15 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
     }
   }
   if (stages & STAGE_APPLY) {
+    mark(stream);
     if (vec == 4 && x_vec)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, true>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out);
+      hipLaunchKernelGGL((colmap_kernel<Q, 4, true>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
     else if (vec == 4)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, false>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out);
+      hipLaunchKernelGGL((colmap_kernel<Q, 4, false>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
     else
-      hipLaunchKernelGGL((colmap_kernel<Q, 1, false>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out);
+      hipLaunchKernelGGL((colmap_kernel<Q, 1, false>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
   }
+  mark(stream);
   return launch_status();
 }
 
@@ -811,6 +921,21 @@ const char* mlproj_status_string(int status) {
     case MLPROJ_ERR_LAUNCH: return "HIP refused a kernel launch";
     default: return "unknown status";
   }
+}
+
+int mlproj_trace_begin(void** events, int capacity) {
+  if (!events) return MLPROJ_ERR_NULL_POINTER;
+  if (capacity <= 0) return MLPROJ_ERR_BAD_DIMENSION;
+  g_trace.events = reinterpret_cast<hipEvent_t*>(events);
+  g_trace.capacity = capacity;
+  g_trace.count = 0;
+  return MLPROJ_OK;
+}
+
+int mlproj_trace_end(void) {
+  const int n = g_trace.count;
+  g_trace = Trace{};
+  return n;
 }
 
 int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2, size_t* bytes_out) {
@@ -878,16 +1003,25 @@ int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1,
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
   const dim3 rgrid((unsigned)cdiv(d0, WAVE)), rblock(SWG);
   float* partial = static_cast<float*>(ws.partial);
+  mark(stream);
   if (vec == 4) hipLaunchKernelGGL((slabagg_kernel<4>), grid, block, 0, stream, Y, len, g, partial);
   else hipLaunchKernelGGL((slabagg_kernel<1>), grid, block, 0, stream, Y, len, g, partial);
+  mark(stream);
   hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, ws.v, v_out);
-  hipLaunchKernelGGL(search_kernel, dim3(1), rblock, 0, stream, ws, d0, (double)eta, MODE_PROJECT, (double*)nullptr);
+  const bool fuse = d0 <= FUSED_SEARCH_MAX;
+  const double fused_eta = fuse ? (double)eta : -1.0;
+  if (!fuse) {
+    mark(stream);
+    hipLaunchKernelGGL(search_kernel, dim3(1), rblock, 0, stream, ws, d0, (double)eta, MODE_PROJECT, (double*)nullptr);
+  }
+  mark(stream);
   if (vec == 4 && x_vec)
-    hipLaunchKernelGGL((slabmap_kernel<4, true>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out);
+    hipLaunchKernelGGL((slabmap_kernel<4, true>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, fused_eta);
   else if (vec == 4)
-    hipLaunchKernelGGL((slabmap_kernel<4, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out);
+    hipLaunchKernelGGL((slabmap_kernel<4, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, fused_eta);
   else
-    hipLaunchKernelGGL((slabmap_kernel<1, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out);
+    hipLaunchKernelGGL((slabmap_kernel<1, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, fused_eta);
+  mark(stream);
   return launch_status();
 }
 

@@ -87,6 +87,8 @@ def test_trilevel_and_norm_argument_checks(lib):
     assert nrm(None, 4, 4, 0, FAKE, big, None, None, None) == -1
     assert nrm(FAKE, 4, 4, 7, FAKE, big, None, None, None) == -6
     assert nrm(FAKE, 4, 0, 0, FAKE, big, None, None, None) == -2
+    assert lib.mlproj_trace_begin(None, 4) == -1
+    assert lib.mlproj_trace_end() == 0
     assert lib.bilevel_radii(0, None, 4, 4, F(1), FAKE, big, None, None) == -1
     assert lib.bilevel_radii(5, FAKE, 4, 4, F(1), FAKE, big, None, None) == -6
     assert lib.bilevel_radii(1, FAKE, 4, 4, F(-2), FAKE, big, None, None) == -4
