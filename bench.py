@@ -24,6 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
+# profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for this library version only.
+TRAFFIC_VERSION = 201
+TRAFFIC_KIB = {"square_4096": 32957.2 * 2.0 + 65625.7, "square_16384": 524388.6 * 2.0 + 1048795.0}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 
@@ -55,6 +59,9 @@ def time_calls(torch, fn, pairs, steps, warmup):
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
 
+
+DIST_TEXT = {"normal": "i.i.d. N(0,1)", "normal_colscale": "N(0,1) x per-column scale log-uniform in [0.01,1]",
+             "laplace": "i.i.d. Laplace(0,1)", "uniform": "i.i.d. U(0,1)"}
 
 KERNEL_LABELS = {
     4: ["colagg", "reduce", "colmap+search"],
@@ -156,7 +163,10 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "colmap_kernel<l1inf> (%s; reads Y, writes X: 8 B/element)" % map_name,
         "achieved": 8.0 * elems / map_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": 8.0 * elems / map_ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
+        "frac": 8.0 * elems / map_ms / 1e6 / HBM_PEAK_GBS,
+        "traffic": (TRAFFIC_KIB[args.workload] * 1024.0
+                    if args.workload in TRAFFIC_KIB and mp.lib().mlproj_version() == TRAFFIC_VERSION else None),
+        "algorithmic_bytes": 8.0 * elems,
         "kernel_ms": map_ms,
         "other_kernels": {"colagg_kernel<l1inf> (reads Y: 4 B/element)": {
             "kernel_ms": kms["colagg"], "achieved": 4.0 * elems / kms["colagg"] / 1e6}},
@@ -166,8 +176,8 @@ def main():
         "value": head["eff_GBps_8B"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %dx%d fp32 row-major, N(0,1) x log-uniform column scales, eta=%.2f*||Y||_1,inf"
-                               % (args.workload, n, m, w.eta_frac),
+        "config": {"workload": "%s: %dx%d fp32 row-major, entries %s, eta=%.2f*||Y||_1,inf"
+                               % (args.workload, n, m, DIST_TEXT[w.dist], w.eta_frac),
                    "buffer_pairs": head["buffer_pairs"], "timing": "cold (rotating buffers > Infinity Cache)"},
         "frac_of_hbm_peak": head["frac_of_peak_8B"], "ms_per_step_warm": head["ms_warm"],
         "detail": head, "roofline": roofline,

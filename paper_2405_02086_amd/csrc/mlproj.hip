@@ -906,7 +906,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 200; }
+int mlproj_version(void) { return 201; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
