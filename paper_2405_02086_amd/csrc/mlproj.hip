@@ -14,6 +14,7 @@
 // costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only.
 // The tri-level form uses the same chain with groups that are contiguous slabs.
 #include <hip/hip_runtime.h>
+#include <hip/hip_cooperative_groups.h>
 
 #include <cmath>
 #include <cstdint>
@@ -33,7 +34,12 @@ constexpr int SEARCH_CACHE = 16;         // values of v per search thread kept i
 constexpr int MAX_INNER_SWEEPS = 32;     // l1,1: passes over Y allowed to the inner searches
 constexpr int QINF = MLPROJ_L1INF, Q1 = MLPROJ_L11, Q2 = MLPROJ_L12;
 constexpr int MODE_PROJECT = 0, MODE_NORM = 1;
-constexpr long long TARGET_WGS = 512;    // streaming workgroups per launch (2 per CU)
+constexpr int MAP_UNROLL = 4;            // rows in flight per wavefront in the map pass (x2: pipelined)
+constexpr int MAP_RBLK = WAVES * MAP_UNROLL;
+constexpr long long TARGET_WGS = 512;    // workgroups of a read-only pass on 256 CUs (2 per CU)
+constexpr long long TARGET_WGS_MAP = 256;  // workgroups of the read+write pass (1 per CU)
+constexpr int COOP_MAX_WGS = 256;        // workgroups of the grid-wide search (one per CU at most)
+constexpr int COOP_VALUES = 8;           // values of v per thread there
 constexpr long long FUSED_SEARCH_MAX = (long long)WG * SEARCH_CACHE;  // groups a map workgroup can search in registers
 
 // ------------------------------------------------------------------ host-side geometry
@@ -44,6 +50,7 @@ constexpr long long FUSED_SEARCH_MAX = (long long)WG * SEARCH_CACHE;  // groups 
 struct Geometry {
   long long tiles;
   long long groups;
+  long long map_groups;  // columns only: row groups of the map pass (its own workgroup count)
   long long span;   // slabs only: elements per chunk
   int vec;          // floats per lane per access: 4 or 1
   int tile_w;       // partial results per (tile, group): 64*vec for columns, 1 for slabs
@@ -52,6 +59,9 @@ struct Geometry {
 struct Ws {
   mlproj_result* res;
   unsigned* pending;       // [MAX_INNER_SWEEPS + 1] l1,1: columns still searching before sweep s
+  double* coop_d;          // [2][COOP_MAX_WGS] grid-wide search: per-workgroup sums, by parity
+  double* coop_m;          // [COOP_MAX_WGS]    per-workgroup maxima
+  unsigned* coop_u;        // [2][COOP_MAX_WGS] per-workgroup counts, by parity
   double* v;               // [groups] aggregate, fp64 (exact for q = inf)
   double* tauj;            // [m] l1,1 inner thresholds
   unsigned* kprev;         // [m] l1,1 previous active counts
@@ -60,13 +70,16 @@ struct Ws {
 };
 
 struct Layout {
-  size_t off_pending, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, bytes;
+  size_t off_pending, off_coop_d, off_coop_m, off_coop_u, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, bytes;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
 
-static Geometry plan_columns(long long n, long long m, int vec) {
+// Both passes were tuned on an MI355X: a read-only pass is fastest with about two workgroups
+// per CU, the read+write pass with one per CU and fewer rows in flight (a narrower band of
+// DRAM pages open at a time); counts that are not multiples of the CU count lose 10-25 %.
+static Geometry plan_columns(long long n, long long m, int vec, int variant) {
   Geometry g;
   g.vec = vec;
   g.tile_w = WAVE * vec;
@@ -76,6 +89,12 @@ static Geometry plan_columns(long long n, long long m, int vec) {
   if (grp > max_grp) grp = max_grp;
   if (grp < 1) grp = 1;
   g.groups = grp;
+  // the l1,1 map does fp64 arithmetic per element and wants the second workgroup per CU
+  long long mg = cdiv(variant == Q1 ? TARGET_WGS : TARGET_WGS_MAP, g.tiles);
+  const long long max_mg = cdiv(n, MAP_RBLK);
+  if (mg > max_mg) mg = max_mg;
+  if (mg < 1) mg = 1;
+  g.map_groups = mg;
   g.span = 0;
   return g;
 }
@@ -85,6 +104,7 @@ static Geometry plan_slabs(long long d0, long long len, int vec) {
   g.vec = vec;
   g.tile_w = 1;
   g.tiles = d0;
+  g.map_groups = 0;
   long long chunks = cdiv(TARGET_WGS, d0);
   const long long quantum = (long long)WG * vec * 4;  // one unrolled trip of the workgroup
   long long span = cdiv(cdiv(len, chunks), quantum) * quantum;
@@ -97,6 +117,9 @@ static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   Layout L{};
   size_t o = align_up(sizeof(mlproj_result), 256);
   L.off_pending = o;       o = align_up(o + (MAX_INNER_SWEEPS + 1) * 4, 256);
+  L.off_coop_d = o;        o = align_up(o + 2 * COOP_MAX_WGS * 8, 256);
+  L.off_coop_m = o;        o = align_up(o + COOP_MAX_WGS * 8, 256);
+  L.off_coop_u = o;        o = align_up(o + 2 * COOP_MAX_WGS * 4, 256);
   L.off_v = o;             o = align_up(o + (size_t)ngroups * 8, 256);
   L.off_tauj = o;          o = align_up(o + (variant == Q1 ? (size_t)ngroups * 8 : 0), 256);
   L.off_kprev = o;         o = align_up(o + (variant == Q1 ? (size_t)ngroups * 4 : 0), 256);
@@ -112,6 +135,9 @@ static Ws bind(void* workspace, const Layout& L) {
   Ws w;
   w.res = reinterpret_cast<mlproj_result*>(b);
   w.pending = reinterpret_cast<unsigned*>(b + L.off_pending);
+  w.coop_d = reinterpret_cast<double*>(b + L.off_coop_d);
+  w.coop_m = reinterpret_cast<double*>(b + L.off_coop_m);
+  w.coop_u = reinterpret_cast<unsigned*>(b + L.off_coop_u);
   w.v = reinterpret_cast<double*>(b + L.off_v);
   w.tauj = reinterpret_cast<double*>(b + L.off_tauj);
   w.kprev = reinterpret_cast<unsigned*>(b + L.off_kprev);
@@ -312,29 +338,46 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const float* __restrict__ Y,
   }
 }
 
-// v_j from the partials of its tile, folded in a fixed order.  64 groups per workgroup, 16
-// threads per group.  Serves columns (tile_w = 64*vec) and slabs (tile_w = 1) alike.
+// v_j from the partials of its tile, folded in a fixed order.  A workgroup of 1024 threads
+// covers 1024/parts groups with `parts` threads each (parts = 1..16, a power of two chosen on
+// the host from the number of partials per group); every thread keeps 8 loads in flight.
+// Serves columns (tile_w = 64*vec) and slabs (tile_w = 1) alike.
+static int reduce_parts(long long partials_per_group) {
+  int parts = 1;
+  while (parts < SWAVES && parts < partials_per_group) parts *= 2;
+  return parts;
+}
+
 template <int Q>
 __global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ partial_,
-                                                     long long ngroups, Geometry g,
+                                                     long long ngroups, Geometry g, int parts,
                                                      double* __restrict__ v,
                                                      float* __restrict__ v_out) {
   using Acc = typename AccOf<Q>::type;
-  __shared__ Acc sm[SWAVES][WAVE];
-  const int lane = threadIdx.x & (WAVE - 1);
-  const int part = threadIdx.x / WAVE;
-  const long long j = (long long)blockIdx.x * WAVE + lane;
+  __shared__ Acc sm[SWG];
+  const int cols = SWG / parts;
+  const int c_local = threadIdx.x % cols;
+  const int part = threadIdx.x / cols;
+  const long long j = (long long)blockIdx.x * cols + c_local;
   Acc a = (Acc)0;
   if (j < ngroups) {
     const long long t = j / g.tile_w, c = j % g.tile_w;
     const Acc* q = static_cast<const Acc*>(partial_) + (size_t)t * g.groups * g.tile_w + c;
-    for (long long b = part; b < g.groups; b += SWAVES) a = combine<Q>(a, q[(size_t)b * g.tile_w]);
+    const size_t stride = (size_t)g.tile_w;
+    long long b0 = part;
+    for (; b0 + 7LL * parts < g.groups; b0 += 8LL * parts) {
+      Acc x[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) x[r] = q[(size_t)(b0 + (long long)r * parts) * stride];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) a = combine<Q>(a, x[r]);
+    }
+    for (; b0 < g.groups; b0 += parts) a = combine<Q>(a, q[(size_t)b0 * stride]);
   }
-  sm[part][lane] = a;
+  sm[threadIdx.x] = a;
   __syncthreads();
   if (part == 0 && j < ngroups) {
-#pragma unroll
-    for (int w = 1; w < SWAVES; ++w) a = combine<Q>(a, sm[w][lane]);
+    for (int w = 1; w < parts; ++w) a = combine<Q>(a, sm[w * cols + c_local]);
     const double vj = (Q == Q2) ? sqrt((double)a) : (double)a;
     v[j] = vj;
     if (v_out) v_out[j] = (float)vj;
@@ -445,6 +488,91 @@ __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, d
   if (threadIdx.x == 0) write_result(ws, o, norm_out);
 }
 
+// The same search for very long v (more groups than one workgroup holds in registers): a
+// cooperative launch of up to one workgroup per CU, each keeping its slice of v in registers.
+// Every round each workgroup files the sum and count of its slice above tau, the grid
+// synchronises, and every workgroup adds up all slices in the same fixed order, so all of
+// them step tau identically and leave the loop together.  Slots alternate by round parity so
+// that a fast workgroup never overwrites what a slow one is still reading.
+__global__ __launch_bounds__(SWG) void search_coop_kernel(Ws ws, long long ngroups, double eta,
+                                                          int mode, double* __restrict__ norm_out) {
+  namespace cg = cooperative_groups;
+  cg::grid_group grid = cg::this_grid();
+  __shared__ BlockScratch<SWAVES> s;
+  const int tid = threadIdx.x;
+  const int nwg = (int)gridDim.x, wg = (int)blockIdx.x;
+  const long long chunk = (ngroups + nwg - 1) / nwg;
+  const long long lo = (long long)wg * chunk;
+  const long long hi = (lo + chunk < ngroups) ? lo + chunk : ngroups;
+
+  double vr[COOP_VALUES];
+  double a = 0.0, mx = 0.0;
+#pragma unroll
+  for (int k = 0; k < COOP_VALUES; ++k) {
+    const long long i = lo + tid + (long long)k * SWG;
+    vr[k] = i < hi ? ws.v[i] : 0.0;
+    a += vr[k];
+    mx = fmax(mx, vr[k]);
+  }
+  for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
+    const double x = ws.v[i];
+    a += x;
+    mx = fmax(mx, x);
+  }
+  a = block_sum(a, s);
+  mx = block_max(mx, s);
+  if (tid == 0) { ws.coop_d[wg] = a; ws.coop_m[wg] = mx; }
+  grid.sync();
+  SearchOut o;
+  o.total = block_sum(tid < nwg ? ws.coop_d[tid] : 0.0, s);
+  o.vmax = block_max(tid < nwg ? ws.coop_m[tid] : 0.0, s);
+  o.tau = 0.0;
+  o.active = 0;
+  o.iters = 0;
+  o.inside = 0;
+  unsigned round = 1;  // parity 0 was used by the totals above
+  if (mode == MODE_NORM) {
+  } else if (eta == 0.0) {
+    o.tau = o.vmax;
+  } else {
+    const bool inside = o.total <= eta;
+    double tau = inside ? 0.0 : fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
+    unsigned kprev = 0xffffffffu;
+    for (;;) {
+      double sum = 0.0;
+      unsigned cnt = 0;
+#pragma unroll
+      for (int k = 0; k < COOP_VALUES; ++k) {
+        if (vr[k] > tau) { sum += vr[k]; ++cnt; }
+      }
+      for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
+        const double x = ws.v[i];
+        if (x > tau) { sum += x; ++cnt; }
+      }
+      sum = block_sum(sum, s);
+      cnt = block_sum_u(cnt, s);
+      const unsigned par = round & 1u;
+      if (tid == 0) { ws.coop_d[par * COOP_MAX_WGS + wg] = sum; ws.coop_u[par * COOP_MAX_WGS + wg] = cnt; }
+      grid.sync();
+      const double S = block_sum(tid < nwg ? ws.coop_d[par * COOP_MAX_WGS + tid] : 0.0, s);
+      const unsigned K = block_sum_u(tid < nwg ? ws.coop_u[par * COOP_MAX_WGS + tid] : 0u, s);
+      ++round;
+      o.active = K;
+      if (inside || K == 0u || K == kprev) break;  // inside: one round, just to count
+      kprev = K;
+      const double t = (S - eta) / (double)K;
+      if (t > tau) tau = t;
+      ++o.iters;
+    }
+    o.tau = tau;
+    o.inside = inside ? 1u : 0u;
+  }
+  if (wg == 0) {
+    if (tid <= MAX_INNER_SWEEPS) ws.pending[tid] = 0u;
+    if (tid == 0) write_result(ws, o, norm_out);
+  }
+}
+
 // ------------------------------------------------------------------ per-column map
 // x_j = P^q_{u_j}(y_j) (Eq. 8-9) with u_j = max(v_j - tau, 0):
 //   q = inf : X = sign(Y) min(|Y|, u_j)          (the symmetric clip; Sec. 4.1)
@@ -459,12 +587,30 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
                                                     long long m, Geometry g, Ws ws,
                                                     float* __restrict__ u_out, double fused_eta) {
   constexpr int TILE_W = WAVE * VEC;
+  constexpr int U = MAP_UNROLL;
   __shared__ BlockScratch<WAVES> bs;
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
   const long long grp = blockIdx.x / g.tiles;
   const long long col0 = t * TILE_W + (long long)lane * VEC;
+  const bool col_ok = col0 < m;
+  const float* p = Y + col0;
+  float* q = X + col0;
+
+  // Row blocks of MAP_RBLK rows, bottom block first; the last block may be ragged.
+  const long long nblk = (n + MAP_RBLK - 1) / MAP_RBLK;
+  long long b = nblk - 1 - grp;
+  float x[U][VEC], y[U][VEC];
+  auto load_block = [&](long long blk, float (&dst)[U][VEC]) {
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      const long long row = blk * MAP_RBLK + wave + (long long)r * WAVES;
+      if (row < n) load_row<VEC>(p + row * m, dst[r]);
+    }
+  };
+  // The first block is requested before tau is known, so its latency hides the search.
+  if (col_ok && b >= 0) load_block(b, x);
 
   double tau;
   bool inside;
@@ -477,7 +623,8 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
     tau = ws.res->tau;
     inside = ws.res->inside_ball != 0u;
   }
-  if (col0 >= m) return;
+  if (!col_ok) return;
+
   float uf[VEC];
   double par[VEC];  // q = 2: scale u_j / v_j;  q = 1: inner threshold tau_j
 #pragma unroll
@@ -494,36 +641,30 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
     for (int k = 0; k < VEC; ++k) u_out[col0 + k] = uf[k];
   }
 
-  auto apply = [&](float y, int k) -> float {
-    if constexpr (Q == QINF) return copysignf(fminf(fabsf(y), uf[k]), y);
-    else if constexpr (Q == Q2) return (float)((double)y * par[k]);
-    else return copysignf((float)fmax((double)fabsf(y) - par[k], 0.0), y);
+  auto apply = [&](float yv, int k) -> float {
+    if constexpr (Q == QINF) return copysignf(fminf(fabsf(yv), uf[k]), yv);
+    else if constexpr (Q == Q2) return (float)((double)yv * par[k]);
+    else return copysignf((float)fmax((double)fabsf(yv) - par[k], 0.0), yv);
   };
 
-  const float* p = Y + col0;
-  float* q = X + col0;
-  const long long nblk = (n + RBLK - 1) / RBLK;  // row blocks, the last one maybe ragged
-  for (long long b = nblk - 1 - grp; b >= 0; b -= g.groups) {
-    const long long r0 = b * RBLK;
-    if (r0 + RBLK <= n) {
-      float x[UNROLL][VEC];
+  // Software pipeline: the next block's loads are in flight while this block is mapped and
+  // stored.  A thread reads and writes the same elements only, so X may alias Y.
+  for (; b >= 0; b -= g.map_groups) {
+    const long long nb = b - g.map_groups;
+    if (nb >= 0) load_block(nb, y);
 #pragma unroll
-      for (int r = 0; r < UNROLL; ++r) load_row<VEC>(p + (r0 + wave + (long long)r * WAVES) * m, x[r]);
-#pragma unroll
-      for (int r = 0; r < UNROLL; ++r) {
+    for (int r = 0; r < U; ++r) {
+      const long long row = b * MAP_RBLK + wave + (long long)r * WAVES;
+      if (row < n) {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) x[r][k] = apply(x[r][k], k);
-        store_row_nt<VEC, XVEC>(q + (r0 + wave + (long long)r * WAVES) * m, x[r]);
-      }
-    } else {
-      for (long long i = r0 + wave; i < n; i += WAVES) {
-        float x[VEC];
-        load_row<VEC>(p + i * m, x);
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) x[k] = apply(x[k], k);
-        store_row_nt<VEC, XVEC>(q + i * m, x);
+        store_row_nt<VEC, XVEC>(q + row * m, x[r]);
       }
     }
+#pragma unroll
+    for (int r = 0; r < U; ++r)
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) x[r][k] = y[r][k];
   }
 }
 
@@ -609,35 +750,35 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
 
 template <bool FIRST>
 __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long m, Geometry g,
-                                                         Ws ws, int sweep) {
-  __shared__ double sm_sum[SWAVES][WAVE];
-  __shared__ unsigned sm_cnt[SWAVES][WAVE];
+                                                         int parts, Ws ws, int sweep) {
+  __shared__ double sm_sum[SWG];
+  __shared__ unsigned sm_cnt[SWG];
   __shared__ BlockScratch<SWAVES> bs;
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
   if (!FIRST && ws.pending[sweep] == 0u) return;
 
-  const int lane = threadIdx.x & (WAVE - 1);
-  const int part = threadIdx.x / WAVE;
-  const long long j = (long long)blockIdx.x * WAVE + lane;
+  const int cols = SWG / parts;
+  const int c_local = threadIdx.x % cols;
+  const int part = threadIdx.x / cols;
+  const long long j = (long long)blockIdx.x * cols + c_local;
   double S = 0.0;
   unsigned K = 0u;
   if (j < m) {
     const long long t = j / g.tile_w, c = j % g.tile_w;
     const size_t base = (size_t)t * g.groups * g.tile_w + c;
     const double* ps = static_cast<const double*>(ws.partial);
-    for (long long b = part; b < g.groups; b += SWAVES) {
+    for (long long b = part; b < g.groups; b += parts) {
       S += ps[base + (size_t)b * g.tile_w];
       K += ws.partial_cnt[base + (size_t)b * g.tile_w];
     }
   }
-  sm_sum[part][lane] = S;
-  sm_cnt[part][lane] = K;
+  sm_sum[threadIdx.x] = S;
+  sm_cnt[threadIdx.x] = K;
   __syncthreads();
   unsigned open = 0u;
   if (part == 0 && j < m) {
-#pragma unroll
-    for (int w = 1; w < SWAVES; ++w) { S += sm_sum[w][lane]; K += sm_cnt[w][lane]; }
+    for (int w = 1; w < parts; ++w) { S += sm_sum[w * cols + c_local]; K += sm_cnt[w * cols + c_local]; }
     const double tau = res->tau;
     const double vj = ws.v[j];
     const double uj = fmax(vj - tau, 0.0);
@@ -783,7 +924,7 @@ static int workspace_bytes_impl(int variant, long long d0, long long d1, long lo
       ngroups = d0;
     } else {
       if (d1 > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
-      g = plan_columns(d0, d1, vec);
+      g = plan_columns(d0, d1, vec, variant);
       ngroups = d1;
     }
     if (g.tiles * g.groups > MAX_GRID) return MLPROJ_ERR_TOO_LARGE;
@@ -815,6 +956,23 @@ static inline void mark(hipStream_t stream) {
     (void)hipEventRecord(g_trace.events[g_trace.count++], stream);
 }
 
+// The stand-alone search: one workgroup when v fits its registers, the cooperative grid-wide
+// form beyond that (falling back to the one-workgroup kernel if the runtime refuses it).
+static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, double* norm_out,
+                          hipStream_t stream) {
+  if (ngroups > (long long)SWG * SEARCH_CACHE) {
+    long long nwg = cdiv(ngroups, (long long)SWG * COOP_VALUES);
+    if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
+    Ws w = ws;
+    void* args[] = {&w, &ngroups, &eta, &mode, &norm_out};
+    const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(search_coop_kernel),
+                                                    dim3((unsigned)nwg), dim3(SWG), args, 0, stream);
+    if (e == hipSuccess) return;
+    (void)hipGetLastError();
+  }
+  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
+}
+
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
 // STAGE_APPLY = the per-column map.
 template <int Q>
@@ -834,14 +992,16 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
   // call agree on the geometry whatever X is; a misaligned X takes the scalar store path.
   const int vec = pick_vec(Y, m);
   const bool x_vec = !X || aligned(X, 16);
-  const Geometry g = plan_columns(n, m, vec);
+  const Geometry g = plan_columns(n, m, vec, Q);
   if (g.tiles * g.groups > MAX_GRID) return MLPROJ_ERR_TOO_LARGE;
   const Layout L = layout_for(g, m, Q);
   if (workspace_bytes < L.bytes) return MLPROJ_ERR_WORKSPACE;
   const Ws ws = bind(workspace, L);
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
-  const dim3 rgrid((unsigned)cdiv(m, WAVE)), rblock(SWG);
+  const dim3 mgrid((unsigned)(g.tiles * g.map_groups));
+  const int parts = reduce_parts(g.groups);
+  const dim3 rgrid((unsigned)cdiv(m, SWG / parts)), rblock(SWG);
   // A whole call on few enough groups lets every map workgroup find tau by itself, which
   // takes the one-workgroup search kernel off the critical path.
   const bool fuse = mode == MODE_PROJECT && stages == STAGE_ALL && Q != Q1 && m <= FUSED_SEARCH_MAX;
@@ -854,10 +1014,10 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
     else
       hipLaunchKernelGGL((colagg_kernel<Q, 1>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     mark(stream);
-    hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, ws.v, v_out);
+    hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out);
     if (!fuse) {
       mark(stream);
-      hipLaunchKernelGGL(search_kernel, dim3(1), rblock, 0, stream, ws, m, (double)eta, mode, norm_out);
+      launch_search(ws, m, (double)eta, mode, norm_out, stream);
     }
     if (mode == MODE_NORM) { mark(stream); return launch_status(); }
     if constexpr (Q == Q1) {
@@ -866,11 +1026,11 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
         if (s == 0) {
           if (vec == 4) hipLaunchKernelGGL((l11_sweep_kernel<4, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
           else hipLaunchKernelGGL((l11_sweep_kernel<1, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          hipLaunchKernelGGL((l11_update_kernel<true>), rgrid, rblock, 0, stream, n, m, g, ws, s);
+          hipLaunchKernelGGL((l11_update_kernel<true>), rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
         } else {
           if (vec == 4) hipLaunchKernelGGL((l11_sweep_kernel<4, false>), grid, block, 0, stream, Y, n, m, g, ws, s);
           else hipLaunchKernelGGL((l11_sweep_kernel<1, false>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          hipLaunchKernelGGL((l11_update_kernel<false>), rgrid, rblock, 0, stream, n, m, g, ws, s);
+          hipLaunchKernelGGL((l11_update_kernel<false>), rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
         }
       }
       hipLaunchKernelGGL(l11_close_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
@@ -879,11 +1039,11 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
   if (stages & STAGE_APPLY) {
     mark(stream);
     if (vec == 4 && x_vec)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, true>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
+      hipLaunchKernelGGL((colmap_kernel<Q, 4, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
     else if (vec == 4)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, false>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
+      hipLaunchKernelGGL((colmap_kernel<Q, 4, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
     else
-      hipLaunchKernelGGL((colmap_kernel<Q, 1, false>), grid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
+      hipLaunchKernelGGL((colmap_kernel<Q, 1, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
   }
   mark(stream);
   return launch_status();
@@ -906,7 +1066,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 201; }
+int mlproj_version(void) { return 202; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -1001,18 +1161,19 @@ int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1,
   const Ws ws = bind(workspace, L);
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
-  const dim3 rgrid((unsigned)cdiv(d0, WAVE)), rblock(SWG);
+  const int parts = reduce_parts(g.groups);
+  const dim3 rgrid((unsigned)cdiv(d0, SWG / parts)), rblock(SWG);
   float* partial = static_cast<float*>(ws.partial);
   mark(stream);
   if (vec == 4) hipLaunchKernelGGL((slabagg_kernel<4>), grid, block, 0, stream, Y, len, g, partial);
   else hipLaunchKernelGGL((slabagg_kernel<1>), grid, block, 0, stream, Y, len, g, partial);
   mark(stream);
-  hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, ws.v, v_out);
+  hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, parts, ws.v, v_out);
   const bool fuse = d0 <= FUSED_SEARCH_MAX;
   const double fused_eta = fuse ? (double)eta : -1.0;
   if (!fuse) {
     mark(stream);
-    hipLaunchKernelGGL(search_kernel, dim3(1), rblock, 0, stream, ws, d0, (double)eta, MODE_PROJECT, (double*)nullptr);
+    launch_search(ws, d0, (double)eta, MODE_PROJECT, nullptr, stream);
   }
   mark(stream);
   if (vec == 4 && x_vec)

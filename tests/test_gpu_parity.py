@@ -76,6 +76,17 @@ def test_bilevel_matches_oracle_on_ragged_shapes(mp, q, shape):
 
 
 @pytest.mark.parametrize("q", ["inf", 1, 2])
+@pytest.mark.parametrize("shape", [(3, 40001), (8, 70000), (2, 16388), (40, 300000)])
+def test_many_columns_use_the_grid_wide_search(mp, q, shape):
+    """More columns than one workgroup can search from registers (m > 16384)."""
+    rng = np.random.default_rng([shape[0], shape[1], 99])
+    Y = rng.laplace(size=shape).astype(np.float32)
+    nrm = orc.norm_l1q(Y, q)
+    for eta in (eta_for(Y, q, 0.01), eta_for(Y, q, 0.6), float(np.float32(1.01 * nrm)), 0.0):
+        check_against_oracle(run_gpu(mp, Y, eta, q), orc.bilevel(Y, eta, q), q)
+
+
+@pytest.mark.parametrize("q", ["inf", 1, 2])
 def test_degenerate_radii_and_inputs(mp, q):
     rng = np.random.default_rng(7)
     Y = rng.standard_normal((65, 70)).astype(np.float32)
