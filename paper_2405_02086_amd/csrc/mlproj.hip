@@ -14,7 +14,6 @@
 // costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only.
 // The tri-level form uses the same chain with groups that are contiguous slabs.
 #include <hip/hip_runtime.h>
-#include <hip/hip_cooperative_groups.h>
 
 #include <cmath>
 #include <cstdint>
@@ -38,8 +37,9 @@ constexpr int MAP_UNROLL = 4;            // rows in flight per wavefront in the 
 constexpr int MAP_RBLK = WAVES * MAP_UNROLL;
 constexpr long long TARGET_WGS = 512;    // workgroups of a read-only pass on 256 CUs (2 per CU)
 constexpr long long TARGET_WGS_MAP = 256;  // workgroups of the read+write pass (1 per CU)
-constexpr int COOP_MAX_WGS = 256;        // workgroups of the grid-wide search (one per CU at most)
+constexpr int COOP_MAX_WGS = 64;         // workgroups of the grid-wide search (far fewer than CUs)
 constexpr int COOP_VALUES = 8;           // values of v per thread there
+constexpr unsigned SPIN_LIMIT = 1u << 22; // polls before a waiting workgroup gives up (~0.1 s)
 constexpr long long FUSED_SEARCH_MAX = (long long)WG * SEARCH_CACHE;  // groups a map workgroup can search in registers
 
 // ------------------------------------------------------------------ host-side geometry
@@ -62,6 +62,7 @@ struct Ws {
   double* coop_d;          // [2][COOP_MAX_WGS] grid-wide search: per-workgroup sums, by parity
   double* coop_m;          // [COOP_MAX_WGS]    per-workgroup maxima
   unsigned* coop_u;        // [2][COOP_MAX_WGS] per-workgroup counts, by parity
+  unsigned* flags;         // [0] arrivals at the grid-wide search's barrier, [1] that search gave up
   double* v;               // [groups] aggregate, fp64 (exact for q = inf)
   double* tauj;            // [m] l1,1 inner thresholds
   unsigned* kprev;         // [m] l1,1 previous active counts
@@ -70,7 +71,7 @@ struct Ws {
 };
 
 struct Layout {
-  size_t off_pending, off_coop_d, off_coop_m, off_coop_u, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, bytes;
+  size_t off_pending, off_coop_d, off_coop_m, off_coop_u, off_flags, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, bytes;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -120,6 +121,7 @@ static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   L.off_coop_d = o;        o = align_up(o + 2 * COOP_MAX_WGS * 8, 256);
   L.off_coop_m = o;        o = align_up(o + COOP_MAX_WGS * 8, 256);
   L.off_coop_u = o;        o = align_up(o + 2 * COOP_MAX_WGS * 4, 256);
+  L.off_flags = o;         o += 256;
   L.off_v = o;             o = align_up(o + (size_t)ngroups * 8, 256);
   L.off_tauj = o;          o = align_up(o + (variant == Q1 ? (size_t)ngroups * 8 : 0), 256);
   L.off_kprev = o;         o = align_up(o + (variant == Q1 ? (size_t)ngroups * 4 : 0), 256);
@@ -138,6 +140,7 @@ static Ws bind(void* workspace, const Layout& L) {
   w.coop_d = reinterpret_cast<double*>(b + L.off_coop_d);
   w.coop_m = reinterpret_cast<double*>(b + L.off_coop_m);
   w.coop_u = reinterpret_cast<unsigned*>(b + L.off_coop_u);
+  w.flags = reinterpret_cast<unsigned*>(b + L.off_flags);
   w.v = reinterpret_cast<double*>(b + L.off_v);
   w.tauj = reinterpret_cast<double*>(b + L.off_tauj);
   w.kprev = reinterpret_cast<unsigned*>(b + L.off_kprev);
@@ -352,9 +355,11 @@ template <int Q>
 __global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ partial_,
                                                      long long ngroups, Geometry g, int parts,
                                                      double* __restrict__ v,
-                                                     float* __restrict__ v_out) {
+                                                     float* __restrict__ v_out,
+                                                     unsigned* __restrict__ flags) {
   using Acc = typename AccOf<Q>::type;
   __shared__ Acc sm[SWG];
+  if (blockIdx.x == 0 && threadIdx.x < 2) flags[threadIdx.x] = 0u;  // for the grid-wide search
   const int cols = SWG / parts;
   const int c_local = threadIdx.x % cols;
   const int part = threadIdx.x / cols;
@@ -481,24 +486,65 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
 }
 
 __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
-                                                     int mode, double* __restrict__ norm_out) {
+                                                     int mode, double* __restrict__ norm_out,
+                                                     int only_as_fallback) {
   __shared__ BlockScratch<SWAVES> s;
+  if (only_as_fallback && ws.flags[1] == 0u) return;
   const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, s);
   if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
   if (threadIdx.x == 0) write_result(ws, o, norm_out);
 }
 
-// The same search for very long v (more groups than one workgroup holds in registers): a
-// cooperative launch of up to one workgroup per CU, each keeping its slice of v in registers.
-// Every round each workgroup files the sum and count of its slice above tau, the grid
-// synchronises, and every workgroup adds up all slices in the same fixed order, so all of
-// them step tau identically and leave the loop together.  Slots alternate by round parity so
-// that a fast workgroup never overwrites what a slow one is still reading.
-__global__ __launch_bounds__(SWG) void search_coop_kernel(Ws ws, long long ngroups, double eta,
+// The same search for very long v (more groups than one workgroup holds in registers): up to
+// 64 workgroups, each keeping its slice of v in registers.  Every round each workgroup files
+// the sum and count of its slice above tau, all wait at a barrier, and every workgroup adds up
+// all slices in the same fixed order, so all of them step tau identically and leave the loop
+// together.  Slots alternate by round parity so that a fast workgroup never overwrites what a
+// slow one is still reading.
+//
+// The barrier is built for this GPU, where a device-scope fence means an L2 write-back
+// (microseconds, and it serialises): everything the workgroups exchange -- the slots and the
+// arrival counter -- is written with device-scope atomic read-modify-writes, which are
+// performed at the memory side, and read with device-scope atomic loads, which bypass the
+// per-XCD L2; "s_waitcnt vmcnt(0)" makes a wavefront's slot writes complete before its
+// arrival is counted.  No ordinary load or store takes part, so no cache has to be flushed.
+// The grid is far smaller than the chip, so all workgroups become resident; a workgroup that
+// nevertheless waits SPIN_LIMIT polls raises flags[1] and everybody leaves: the kernel always
+// ends, and the one-workgroup search_kernel queued behind it then does the work instead.
+__device__ __forceinline__ bool wide_barrier(unsigned* flags, unsigned target, unsigned* lds_ok) {
+  if (threadIdx.x == 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __hip_atomic_fetch_add(&flags[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0, ok = 1;
+    while (__hip_atomic_load(&flags[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (__hip_atomic_load(&flags[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u || ++spins > SPIN_LIMIT) {
+        ok = 0;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok) __hip_atomic_exchange(&flags[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *lds_ok = ok;
+  }
+  __syncthreads();
+  const bool ok = *lds_ok != 0u;
+  __syncthreads();
+  return ok;
+}
+__device__ __forceinline__ void put_f64(double* p, double x) {
+  __hip_atomic_exchange(reinterpret_cast<unsigned long long*>(p),
+                        (unsigned long long)__double_as_longlong(x), __ATOMIC_RELAXED,
+                        __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double get_f64(const double* p) {
+  return __longlong_as_double((long long)__hip_atomic_load(
+      reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+__global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngroups, double eta,
                                                           int mode, double* __restrict__ norm_out) {
-  namespace cg = cooperative_groups;
-  cg::grid_group grid = cg::this_grid();
   __shared__ BlockScratch<SWAVES> s;
+  __shared__ unsigned lds_ok;
   const int tid = threadIdx.x;
   const int nwg = (int)gridDim.x, wg = (int)blockIdx.x;
   const long long chunk = (ngroups + nwg - 1) / nwg;
@@ -521,16 +567,16 @@ __global__ __launch_bounds__(SWG) void search_coop_kernel(Ws ws, long long ngrou
   }
   a = block_sum(a, s);
   mx = block_max(mx, s);
-  if (tid == 0) { ws.coop_d[wg] = a; ws.coop_m[wg] = mx; }
-  grid.sync();
+  if (tid == 0) { put_f64(&ws.coop_d[wg], a); put_f64(&ws.coop_m[wg], mx); }
+  unsigned round = 1;  // barrier rounds so far; parity 0 carries the totals
+  if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
   SearchOut o;
-  o.total = block_sum(tid < nwg ? ws.coop_d[tid] : 0.0, s);
-  o.vmax = block_max(tid < nwg ? ws.coop_m[tid] : 0.0, s);
+  o.total = block_sum(tid < nwg ? get_f64(&ws.coop_d[tid]) : 0.0, s);
+  o.vmax = block_max(tid < nwg ? get_f64(&ws.coop_m[tid]) : 0.0, s);
   o.tau = 0.0;
   o.active = 0;
   o.iters = 0;
   o.inside = 0;
-  unsigned round = 1;  // parity 0 was used by the totals above
   if (mode == MODE_NORM) {
   } else if (eta == 0.0) {
     o.tau = o.vmax;
@@ -552,11 +598,15 @@ __global__ __launch_bounds__(SWG) void search_coop_kernel(Ws ws, long long ngrou
       sum = block_sum(sum, s);
       cnt = block_sum_u(cnt, s);
       const unsigned par = round & 1u;
-      if (tid == 0) { ws.coop_d[par * COOP_MAX_WGS + wg] = sum; ws.coop_u[par * COOP_MAX_WGS + wg] = cnt; }
-      grid.sync();
-      const double S = block_sum(tid < nwg ? ws.coop_d[par * COOP_MAX_WGS + tid] : 0.0, s);
-      const unsigned K = block_sum_u(tid < nwg ? ws.coop_u[par * COOP_MAX_WGS + tid] : 0u, s);
+      if (tid == 0) {
+        put_f64(&ws.coop_d[par * COOP_MAX_WGS + wg], sum);
+        __hip_atomic_exchange(&ws.coop_u[par * COOP_MAX_WGS + wg], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
       ++round;
+      if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
+      const double S = block_sum(tid < nwg ? get_f64(&ws.coop_d[par * COOP_MAX_WGS + tid]) : 0.0, s);
+      const unsigned K = block_sum_u(
+          tid < nwg ? __hip_atomic_load(&ws.coop_u[par * COOP_MAX_WGS + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u, s);
       o.active = K;
       if (inside || K == 0u || K == kprev) break;  // inside: one round, just to count
       kprev = K;
@@ -670,12 +720,17 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
 
 // ------------------------------------------------------------------ l1,1: inner searches
 // Alg. 3 needs, for every kept column, the threshold tau_j with
-// sum_i max(|Y_ij| - tau_j, 0) = u_j.  All columns run the same monotone fixed point as the
-// outer search, in lock step: one sweep = one pass over Y that gives every column the sum
-// and count of its entries above the current tau_j, then a small update kernel moves every
-// tau_j.  A column is finished when its count repeats.  pending[s] is the number of columns
-// still open before sweep s; both kernels of a sweep return at once when it is zero.
-template <int VEC, bool FIRST>
+// f_j(tau_j) = sum_i max(|Y_ij| - tau_j, 0) = u_j.  f_j is convex, decreasing and piecewise
+// linear, and one sweep over Y gives every column the sum S and count K of its entries above
+// its current point t, i.e. f_j(t) and its slope -K; the Newton step t' = (S - u_j)/K then
+// lands at or left of the root from ANY t (the tangent of a convex function lies below it),
+// and from the left the steps rise monotonically.  When two consecutive points see the same
+// count there is no entry between them, f_j is linear there and t' is the exact root, in
+// fp64.  All columns step in lock step: sweep kernel, then a small update kernel.
+// The first point is a guess (l11_init_kernel), so typically three sweeps suffice.
+// pending[s] is the number of columns still open before sweep s; both kernels of a sweep
+// return at once when it is zero.
+template <int VEC>
 __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__ Y, long long n,
                                                        long long m, Geometry g, Ws ws,
                                                        int sweep) {
@@ -685,14 +740,13 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
 
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
-  if (!FIRST && ws.pending[sweep] == 0u) return;
+  if (sweep > 0 && ws.pending[sweep] == 0u) return;
 
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
   const long long grp = blockIdx.x / g.tiles;
   const long long col0 = t * TILE_W + (long long)lane * VEC;
-  const double tau = res->tau;
 
   double sum[VEC];
   unsigned cnt[VEC];
@@ -702,11 +756,7 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
   if (col0 < m) {
     double tj[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-      // first sweep: all n entries active gives the lower bound (v_j - u_j)/n = tau/n
-      if constexpr (FIRST) tj[k] = (ws.v[col0 + k] > tau) ? tau / (double)n : HUGE_VAL;
-      else tj[k] = ws.tauj[col0 + k];
-    }
+    for (int k = 0; k < VEC; ++k) tj[k] = ws.tauj[col0 + k];
     const float* p = Y + col0;
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
@@ -748,7 +798,36 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
   }
 }
 
-template <bool FIRST>
+// Starting points of the inner searches.  Dropped columns get +inf (every entry maps to 0).
+// For a kept column the guess assumes its entries are Gaussian with the scale its l1 norm
+// implies: E|y| = sigma*sqrt(2/pi) = v_j/n and E max(|y| - t, 0) = sigma*h(t/sigma) with
+// h(z) = 2*phi(z) - z*erfc(z/sqrt 2), so z solves h(z) = (u_j/v_j)*sqrt(2/pi) (a few Newton
+// steps on the convex h) and the guess is sigma*z.  Only the speed depends on the guess.
+__global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, Ws ws) {
+  const mlproj_result* res = ws.res;
+  if (res->inside_ball != 0u || res->n_active == 0u) return;
+  const long long j = (long long)blockIdx.x * WG + threadIdx.x;
+  if (j >= m) return;
+  const double tau = res->tau;
+  const double vj = ws.v[j];
+  const double uj = fmax(vj - tau, 0.0);
+  double tj = HUGE_VAL;
+  if (uj > 0.0) {
+    const double c = (uj / vj) * 0.7978845608028654;  // sqrt(2/pi)
+    double z = 0.0;
+    for (int it = 0; it < 8; ++it) {
+      const double tail = erfc(z * 0.7071067811865476);            // 2*(1 - Phi(z))
+      const double h = 0.7978845608028654 * exp(-0.5 * z * z) - z * tail;
+      if (!(tail > 1e-300)) break;
+      z += (h - c) / tail;
+    }
+    const double sigma = (vj / (double)n) * 1.2533141373155001;   // sqrt(pi/2)
+    tj = fmax(sigma * z, tau / (double)n);  // never below the all-active bound (v_j - u_j)/n
+  }
+  ws.tauj[j] = tj;
+  ws.kprev[j] = 0xffffffffu;
+}
+
 __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long m, Geometry g,
                                                          int parts, Ws ws, int sweep) {
   __shared__ double sm_sum[SWG];
@@ -756,7 +835,7 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
   __shared__ BlockScratch<SWAVES> bs;
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
-  if (!FIRST && ws.pending[sweep] == 0u) return;
+  if (sweep > 0 && ws.pending[sweep] == 0u) return;
 
   const int cols = SWG / parts;
   const int c_local = threadIdx.x % cols;
@@ -780,19 +859,24 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
   if (part == 0 && j < m) {
     for (int w = 1; w < parts; ++w) { S += sm_sum[w * cols + c_local]; K += sm_cnt[w * cols + c_local]; }
     const double tau = res->tau;
-    const double vj = ws.v[j];
-    const double uj = fmax(vj - tau, 0.0);
-    double tj;
-    if constexpr (FIRST) tj = (vj > tau) ? tau / (double)n : HUGE_VAL;
-    else tj = ws.tauj[j];
-    const unsigned kp = FIRST ? 0xffffffffu : ws.kprev[j];
-    if (uj > 0.0 && K > 0u) {
-      const double tn = (S - uj) / (double)K;
-      if (tn > tj) tj = tn;
-      open = (K != kp) ? 1u : 0u;
+    const double uj = fmax(ws.v[j] - tau, 0.0);
+    if (uj > 0.0) {
+      double tj = ws.tauj[j];
+      const unsigned kp = ws.kprev[j];
+      if (K == 0u) {
+        // the guess overshot every entry: restart from the all-active lower bound
+        tj = tau / (double)n;
+        K = 0xffffffffu;
+        open = 1u;
+      } else {
+        const double tn = (S - uj) / (double)K;
+        // from the guess any move is allowed; afterwards the points only rise
+        tj = (sweep == 0 || kp == 0xffffffffu) ? tn : fmax(tj, tn);
+        open = (K != kp) ? 1u : 0u;
+      }
+      ws.tauj[j] = tj;
+      ws.kprev[j] = K;
     }
-    ws.tauj[j] = tj;
-    ws.kprev[j] = K;
   }
   const unsigned wg_open = block_sum_u(open, bs);
   if (threadIdx.x == 0) {
@@ -956,21 +1040,19 @@ static inline void mark(hipStream_t stream) {
     (void)hipEventRecord(g_trace.events[g_trace.count++], stream);
 }
 
-// The stand-alone search: one workgroup when v fits its registers, the cooperative grid-wide
-// form beyond that (falling back to the one-workgroup kernel if the runtime refuses it).
+// The stand-alone search: one workgroup when v fits its registers, the grid-wide form beyond
+// that, followed by the one-workgroup kernel as a fallback that returns at once unless the
+// grid-wide one gave up.
 static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, double* norm_out,
                           hipStream_t stream) {
+  int only_as_fallback = 0;
   if (ngroups > (long long)SWG * SEARCH_CACHE) {
     long long nwg = cdiv(ngroups, (long long)SWG * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-    Ws w = ws;
-    void* args[] = {&w, &ngroups, &eta, &mode, &norm_out};
-    const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<const void*>(search_coop_kernel),
-                                                    dim3((unsigned)nwg), dim3(SWG), args, 0, stream);
-    if (e == hipSuccess) return;
-    (void)hipGetLastError();
+    hipLaunchKernelGGL(search_wide_kernel, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
+    only_as_fallback = 1;
   }
-  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
+  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out, only_as_fallback);
 }
 
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
@@ -1014,7 +1096,7 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
     else
       hipLaunchKernelGGL((colagg_kernel<Q, 1>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     mark(stream);
-    hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out);
+    hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
     if (!fuse) {
       mark(stream);
       launch_search(ws, m, (double)eta, mode, norm_out, stream);
@@ -1022,16 +1104,11 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
     if (mode == MODE_NORM) { mark(stream); return launch_status(); }
     if constexpr (Q == Q1) {
       mark(stream);
+      hipLaunchKernelGGL(l11_init_kernel, dim3((unsigned)cdiv(m, WG)), block, 0, stream, n, m, ws);
       for (int s = 0; s < MAX_INNER_SWEEPS; ++s) {
-        if (s == 0) {
-          if (vec == 4) hipLaunchKernelGGL((l11_sweep_kernel<4, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          else hipLaunchKernelGGL((l11_sweep_kernel<1, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          hipLaunchKernelGGL((l11_update_kernel<true>), rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
-        } else {
-          if (vec == 4) hipLaunchKernelGGL((l11_sweep_kernel<4, false>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          else hipLaunchKernelGGL((l11_sweep_kernel<1, false>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          hipLaunchKernelGGL((l11_update_kernel<false>), rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
-        }
+        if (vec == 4) hipLaunchKernelGGL((l11_sweep_kernel<4>), grid, block, 0, stream, Y, n, m, g, ws, s);
+        else hipLaunchKernelGGL((l11_sweep_kernel<1>), grid, block, 0, stream, Y, n, m, g, ws, s);
+        hipLaunchKernelGGL(l11_update_kernel, rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
       }
       hipLaunchKernelGGL(l11_close_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
     }
@@ -1168,7 +1245,7 @@ int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1,
   if (vec == 4) hipLaunchKernelGGL((slabagg_kernel<4>), grid, block, 0, stream, Y, len, g, partial);
   else hipLaunchKernelGGL((slabagg_kernel<1>), grid, block, 0, stream, Y, len, g, partial);
   mark(stream);
-  hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, parts, ws.v, v_out);
+  hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, parts, ws.v, v_out, ws.flags);
   const bool fuse = d0 <= FUSED_SEARCH_MAX;
   const double fused_eta = fuse ? (double)eta : -1.0;
   if (!fuse) {
