@@ -273,6 +273,41 @@ __device__ __forceinline__ unsigned block_sum_u(unsigned x, BlockScratch<NW>& s)
   return r;
 }
 
+// Two reductions for the price of one barrier pair: (sum, max) and (sum, count).
+template <int NW>
+struct PairScratch {
+  double a[NW];
+  double b[NW];
+  unsigned u[NW];
+};
+template <int NW>
+__device__ __forceinline__ void block_sum_max(double& sum, double& mx, PairScratch<NW>& s) {
+  sum = wave_sum(sum);
+  mx = wave_max(mx);
+  if ((threadIdx.x & (WAVE - 1)) == 0) { s.a[threadIdx.x / WAVE] = sum; s.b[threadIdx.x / WAVE] = mx; }
+  __syncthreads();
+  double r = 0.0, q = 0.0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { r += s.a[w]; q = fmax(q, s.b[w]); }
+  __syncthreads();
+  sum = r;
+  mx = q;
+}
+template <int NW>
+__device__ __forceinline__ void block_sum_count(double& sum, unsigned& cnt, PairScratch<NW>& s) {
+  sum = wave_sum(sum);
+  cnt = wave_sum_u(cnt);
+  if ((threadIdx.x & (WAVE - 1)) == 0) { s.a[threadIdx.x / WAVE] = sum; s.u[threadIdx.x / WAVE] = cnt; }
+  __syncthreads();
+  double r = 0.0;
+  unsigned c = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { r += s.a[w]; c += s.u[w]; }
+  __syncthreads();
+  sum = r;
+  cnt = c;
+}
+
 template <int Q> struct AccOf { using type = double; };
 template <> struct AccOf<QINF> { using type = float; };
 
@@ -407,7 +442,7 @@ struct SearchOut {
 template <int NT>
 __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, long long ngroups,
                                                   double eta, int mode,
-                                                  BlockScratch<NT / WAVE>& s) {
+                                                  PairScratch<NT / WAVE>& s) {
   const int tid = threadIdx.x;
   double vr[SEARCH_CACHE];
   double a = 0.0, mx = 0.0;
@@ -424,8 +459,9 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
     mx = fmax(mx, x);
   }
   SearchOut o;
-  o.total = block_sum(a, s);
-  o.vmax = block_max(mx, s);
+  block_sum_max(a, mx, s);
+  o.total = a;
+  o.vmax = mx;
   o.tau = 0.0;
   o.active = 0;
   o.iters = 0;
@@ -441,7 +477,9 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
     for (int k = 0; k < SEARCH_CACHE; ++k) c += vr[k] > 0.0 ? 1u : 0u;
     for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT)
       c += v[i] > 0.0 ? 1u : 0u;
-    o.active = block_sum_u(c, s);
+    double zero = 0.0;
+    block_sum_count(zero, c, s);
+    o.active = c;
   } else {
     // two lower bounds on the root: all groups active, and only the largest active
     double tau = fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
@@ -457,8 +495,9 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
         const double x = v[i];
         if (x > tau) { sum += x; ++cnt; }
       }
-      const double S = block_sum(sum, s);
-      const unsigned K = block_sum_u(cnt, s);
+      block_sum_count(sum, cnt, s);
+      const double S = sum;
+      const unsigned K = cnt;
       o.active = K;
       if (K == 0u || K == kprev) break;  // K == 0: eta below the resolution of vmax
       kprev = K;
@@ -488,7 +527,7 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
 __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
                                                      int mode, double* __restrict__ norm_out,
                                                      int only_as_fallback) {
-  __shared__ BlockScratch<SWAVES> s;
+  __shared__ PairScratch<SWAVES> s;
   if (only_as_fallback && ws.flags[1] == 0u) return;
   const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, s);
   if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
@@ -543,7 +582,7 @@ __device__ __forceinline__ double get_f64(const double* p) {
 
 __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngroups, double eta,
                                                           int mode, double* __restrict__ norm_out) {
-  __shared__ BlockScratch<SWAVES> s;
+  __shared__ PairScratch<SWAVES> s;
   __shared__ unsigned lds_ok;
   const int tid = threadIdx.x;
   const int nwg = (int)gridDim.x, wg = (int)blockIdx.x;
@@ -565,14 +604,14 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
     a += x;
     mx = fmax(mx, x);
   }
-  a = block_sum(a, s);
-  mx = block_max(mx, s);
+  block_sum_max(a, mx, s);
   if (tid == 0) { put_f64(&ws.coop_d[wg], a); put_f64(&ws.coop_m[wg], mx); }
   unsigned round = 1;  // barrier rounds so far; parity 0 carries the totals
   if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
   SearchOut o;
-  o.total = block_sum(tid < nwg ? get_f64(&ws.coop_d[tid]) : 0.0, s);
-  o.vmax = block_max(tid < nwg ? get_f64(&ws.coop_m[tid]) : 0.0, s);
+  o.total = tid < nwg ? get_f64(&ws.coop_d[tid]) : 0.0;
+  o.vmax = tid < nwg ? get_f64(&ws.coop_m[tid]) : 0.0;
+  block_sum_max(o.total, o.vmax, s);
   o.tau = 0.0;
   o.active = 0;
   o.iters = 0;
@@ -595,8 +634,7 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
         const double x = ws.v[i];
         if (x > tau) { sum += x; ++cnt; }
       }
-      sum = block_sum(sum, s);
-      cnt = block_sum_u(cnt, s);
+      block_sum_count(sum, cnt, s);
       const unsigned par = round & 1u;
       if (tid == 0) {
         put_f64(&ws.coop_d[par * COOP_MAX_WGS + wg], sum);
@@ -604,9 +642,9 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
       }
       ++round;
       if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
-      const double S = block_sum(tid < nwg ? get_f64(&ws.coop_d[par * COOP_MAX_WGS + tid]) : 0.0, s);
-      const unsigned K = block_sum_u(
-          tid < nwg ? __hip_atomic_load(&ws.coop_u[par * COOP_MAX_WGS + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u, s);
+      double S = tid < nwg ? get_f64(&ws.coop_d[par * COOP_MAX_WGS + tid]) : 0.0;
+      unsigned K = tid < nwg ? __hip_atomic_load(&ws.coop_u[par * COOP_MAX_WGS + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      block_sum_count(S, K, s);
       o.active = K;
       if (inside || K == 0u || K == kprev) break;  // inside: one round, just to count
       kprev = K;
@@ -638,7 +676,7 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
                                                     float* __restrict__ u_out, double fused_eta) {
   constexpr int TILE_W = WAVE * VEC;
   constexpr int U = MAP_UNROLL;
-  __shared__ BlockScratch<WAVES> bs;
+  __shared__ PairScratch<WAVES> bs;
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
@@ -697,8 +735,11 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
     else return copysignf((float)fmax((double)fabsf(yv) - par[k], 0.0), yv);
   };
 
-  // Software pipeline: the next block's loads are in flight while this block is mapped and
-  // stored.  A thread reads and writes the same elements only, so X may alias Y.
+  // Software pipeline: the next block's loads are issued first, then this block is mapped
+  // and stored, and only then does the wavefront wait.  On gfx9 loads and stores share one
+  // counter, so any wait for a load also waits for every store issued before it: the wait
+  // must come after both have been issued, or the two never overlap.
+  // A thread reads and writes the same elements only, so X may alias Y.
   for (; b >= 0; b -= g.map_groups) {
     const long long nb = b - g.map_groups;
     if (nb >= 0) load_block(nb, y);
@@ -933,7 +974,7 @@ template <int VEC, bool XVEC>
 __global__ __launch_bounds__(WG) void slabmap_kernel(const float* Y, float* X, long long d0,
                                                      long long len, Geometry g, Ws ws,
                                                      float* __restrict__ u_out, double fused_eta) {
-  __shared__ BlockScratch<WAVES> bs;
+  __shared__ PairScratch<WAVES> bs;
   const long long a = d0 - 1 - blockIdx.x / g.groups;
   const long long c = blockIdx.x % g.groups;
   const long long lo = c * g.span;
