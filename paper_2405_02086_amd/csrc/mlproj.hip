@@ -30,7 +30,8 @@ constexpr int RBLK = WAVES * UNROLL;     // rows one workgroup consumes per trip
 constexpr int SWG = 1024;                // threads of the search / reduce workgroups
 constexpr int SWAVES = SWG / WAVE;
 constexpr int SEARCH_CACHE = 16;         // values of v per search thread kept in registers
-constexpr int MAX_INNER_SWEEPS = 32;     // l1,1: passes over Y allowed to the inner searches
+constexpr int MAX_INNER_SWEEPS = 24;     // l1,1: passes over Y allowed to the inner searches
+constexpr double L11_WINDOW = 1.0 / 16;  // l1,1: relative width of the window that samples the density
 constexpr int QINF = MLPROJ_L1INF, Q1 = MLPROJ_L11, Q2 = MLPROJ_L12;
 constexpr int MODE_PROJECT = 0, MODE_NORM = 1;
 constexpr int MAP_UNROLL = 4;            // rows in flight per wavefront in the map pass (x2: pipelined)
@@ -67,11 +68,12 @@ struct Ws {
   double* tauj;            // [m] l1,1 inner thresholds
   unsigned* kprev;         // [m] l1,1 previous active counts
   void* partial;           // [tiles][groups][tile_w] float (q = inf) or double
-  unsigned* partial_cnt;   // [tiles][groups][tile_w] l1,1
+  unsigned* partial_cnt;   // [tiles][groups][tile_w] l1,1: entries above t
+  unsigned* partial_cnt2;  // [tiles][groups][tile_w] l1,1: entries above t*(1 + L11_WINDOW)
 };
 
 struct Layout {
-  size_t off_pending, off_coop_d, off_coop_m, off_coop_u, off_flags, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, bytes;
+  size_t off_pending, off_coop_d, off_coop_m, off_coop_u, off_flags, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, off_partial_cnt2, bytes;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -128,6 +130,7 @@ static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   const size_t cells = (size_t)g.tiles * (size_t)g.groups * (size_t)g.tile_w;
   L.off_partial = o;       o = align_up(o + cells * 8, 256);
   L.off_partial_cnt = o;   o = align_up(o + (variant == Q1 ? cells * 4 : 0), 256);
+  L.off_partial_cnt2 = o;  o = align_up(o + (variant == Q1 ? cells * 4 : 0), 256);
   L.bytes = o;
   return L;
 }
@@ -146,6 +149,7 @@ static Ws bind(void* workspace, const Layout& L) {
   w.kprev = reinterpret_cast<unsigned*>(b + L.off_kprev);
   w.partial = b + L.off_partial;
   w.partial_cnt = reinterpret_cast<unsigned*>(b + L.off_partial_cnt);
+  w.partial_cnt2 = reinterpret_cast<unsigned*>(b + L.off_partial_cnt2);
   return w;
 }
 
@@ -768,7 +772,11 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
 // and from the left the steps rise monotonically.  When two consecutive points see the same
 // count there is no entry between them, f_j is linear there and t' is the exact root, in
 // fp64.  All columns step in lock step: sweep kernel, then a small update kernel.
-// The first point is a guess (l11_init_kernel), so typically three sweeps suffice.
+// The first point is a guess (l11_init_kernel).  The sweep also counts the entries above
+// t*(1 + L11_WINDOW); at the guess that gives the local density of entries, i.e. the
+// curvature of f_j, and the first move solves the quadratic model instead of the tangent.
+// That move carries no guarantee, so the count is forgotten after it and the Newton steps
+// that follow restore the invariants.  Typically three or four sweeps suffice.
 // pending[s] is the number of columns still open before sweep s; both kernels of a sweep
 // return at once when it is zero.
 template <int VEC>
@@ -778,6 +786,7 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
   constexpr int TILE_W = WAVE * VEC;
   __shared__ double sm_sum[WAVES][TILE_W];
   __shared__ unsigned sm_cnt[WAVES][TILE_W];
+  __shared__ unsigned sm_cnt2[WAVES][TILE_W];
 
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
@@ -790,14 +799,17 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
   const long long col0 = t * TILE_W + (long long)lane * VEC;
 
   double sum[VEC];
-  unsigned cnt[VEC];
+  unsigned cnt[VEC], cnt2[VEC];
 #pragma unroll
-  for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; }
+  for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; cnt2[k] = 0u; }
 
   if (col0 < m) {
-    double tj[VEC];
+    double tj[VEC], tw[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) tj[k] = ws.tauj[col0 + k];
+    for (int k = 0; k < VEC; ++k) {
+      tj[k] = ws.tauj[col0 + k];
+      tw[k] = tj[k] * (1.0 + L11_WINDOW);
+    }
     const float* p = Y + col0;
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
@@ -810,6 +822,7 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
         for (int k = 0; k < VEC; ++k) {
           const double a = (double)fabsf(x[r][k]);
           if (a > tj[k]) { sum[k] += a; ++cnt[k]; }
+          cnt2[k] += a > tw[k] ? 1u : 0u;
         }
     }
     for (long long i = r0 + wave; i < n; i += WAVES) {
@@ -819,6 +832,7 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
       for (int k = 0; k < VEC; ++k) {
         const double a = (double)fabsf(x[k]);
         if (a > tj[k]) { sum[k] += a; ++cnt[k]; }
+        cnt2[k] += a > tw[k] ? 1u : 0u;
       }
     }
   }
@@ -826,16 +840,22 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
   for (int k = 0; k < VEC; ++k) {
     sm_sum[wave][lane * VEC + k] = sum[k];
     sm_cnt[wave][lane * VEC + k] = cnt[k];
+    sm_cnt2[wave][lane * VEC + k] = cnt2[k];
   }
   __syncthreads();
   if (threadIdx.x < TILE_W) {
     double a = sm_sum[0][threadIdx.x];
-    unsigned c = sm_cnt[0][threadIdx.x];
+    unsigned c = sm_cnt[0][threadIdx.x], c2 = sm_cnt2[0][threadIdx.x];
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) { a += sm_sum[w][threadIdx.x]; c += sm_cnt[w][threadIdx.x]; }
+    for (int w = 1; w < WAVES; ++w) {
+      a += sm_sum[w][threadIdx.x];
+      c += sm_cnt[w][threadIdx.x];
+      c2 += sm_cnt2[w][threadIdx.x];
+    }
     const size_t cell = ((size_t)t * g.groups + grp) * TILE_W + threadIdx.x;
     static_cast<double*>(ws.partial)[cell] = a;
     ws.partial_cnt[cell] = c;
+    ws.partial_cnt2[cell] = c2;
   }
 }
 
@@ -873,6 +893,7 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
                                                          int parts, Ws ws, int sweep) {
   __shared__ double sm_sum[SWG];
   __shared__ unsigned sm_cnt[SWG];
+  __shared__ unsigned sm_cnt2[SWG];
   __shared__ BlockScratch<SWAVES> bs;
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
@@ -883,7 +904,7 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
   const int part = threadIdx.x / cols;
   const long long j = (long long)blockIdx.x * cols + c_local;
   double S = 0.0;
-  unsigned K = 0u;
+  unsigned K = 0u, K2 = 0u;
   if (j < m) {
     const long long t = j / g.tile_w, c = j % g.tile_w;
     const size_t base = (size_t)t * g.groups * g.tile_w + c;
@@ -891,14 +912,20 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
     for (long long b = part; b < g.groups; b += parts) {
       S += ps[base + (size_t)b * g.tile_w];
       K += ws.partial_cnt[base + (size_t)b * g.tile_w];
+      K2 += ws.partial_cnt2[base + (size_t)b * g.tile_w];
     }
   }
   sm_sum[threadIdx.x] = S;
   sm_cnt[threadIdx.x] = K;
+  sm_cnt2[threadIdx.x] = K2;
   __syncthreads();
   unsigned open = 0u;
   if (part == 0 && j < m) {
-    for (int w = 1; w < parts; ++w) { S += sm_sum[w * cols + c_local]; K += sm_cnt[w * cols + c_local]; }
+    for (int w = 1; w < parts; ++w) {
+      S += sm_sum[w * cols + c_local];
+      K += sm_cnt[w * cols + c_local];
+      K2 += sm_cnt2[w * cols + c_local];
+    }
     const double tau = res->tau;
     const double uj = fmax(ws.v[j] - tau, 0.0);
     if (uj > 0.0) {
@@ -909,10 +936,20 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
         tj = tau / (double)n;
         K = 0xffffffffu;
         open = 1u;
+      } else if (sweep == 0) {
+        // at the guess g: residual r = f(g) - u, slope -K, curvature rho (entries per unit
+        // just above g); solve r - K d + rho d^2 / 2 = 0 for the move d, in the stable form
+        const double r = (S - (double)K * tj) - uj;
+        const double rho = (double)(K - K2) / (tj * L11_WINDOW);
+        const double disc = (double)K * (double)K - 2.0 * rho * r;
+        const double d = (rho > 0.0 && disc > 0.0) ? 2.0 * r / ((double)K + sqrt(disc)) : r / (double)K;
+        tj = fmax(tj + d, tau / (double)n);
+        K = 0xffffffffu;  // not a Newton point: the next count comparison must not conclude
+        open = 1u;
       } else {
         const double tn = (S - uj) / (double)K;
-        // from the guess any move is allowed; afterwards the points only rise
-        tj = (sweep == 0 || kp == 0xffffffffu) ? tn : fmax(tj, tn);
+        // after a free move any Newton point is taken; afterwards the points only rise
+        tj = (kp == 0xffffffffu) ? tn : fmax(tj, tn);
         open = (K != kp) ? 1u : 0u;
       }
       ws.tauj[j] = tj;
