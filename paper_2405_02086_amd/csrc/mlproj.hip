@@ -1221,7 +1221,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 202; }
+int mlproj_version(void) { return 203; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -236,3 +236,95 @@ def test_workload_square_16384(mp, big_square, q):
     dev = torch.device("cuda:0")
     Xd = torch.from_numpy(X).to(dev)
     assert mp.norm_l1q(Xd, QNAME[q]) == pytest.approx(eta, rel=1e-5)
+
+
+# ------------------------------------------------------------------ API corners
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+def test_unaligned_pointers_take_the_narrow_paths(mp, q):
+    """Y or X starting 4 bytes into an allocation cannot use 16-byte accesses."""
+    rng = np.random.default_rng(21)
+    dev = torch.device("cuda:0")
+    n, m = 130, 264
+    Y = rng.standard_normal((n, m)).astype(np.float32)
+    eta = eta_for(Y, q, 0.3)
+    ref = orc.bilevel(Y, eta, q)
+    fn = getattr(mp, "bilevel_proj_" + QNAME[q])
+    ws = mp.Workspace.for_call(QNAME[q], n, m, device=dev)
+    for y_off, x_off in ((1, 0), (0, 1), (1, 1), (0, 0)):
+        ybuf = torch.zeros(n * m + 4, dtype=torch.float32, device=dev)
+        xbuf = torch.full((n * m + 4,), 7.0, dtype=torch.float32, device=dev)
+        Yd = ybuf[y_off:y_off + n * m].view(n, m)
+        Xd = xbuf[x_off:x_off + n * m].view(n, m)
+        Yd.copy_(torch.from_numpy(Y))
+        assert (Yd.data_ptr() % 16 != 0) == bool(y_off) and (Xd.data_ptr() % 16 != 0) == bool(x_off)
+        fn(Yd, eta, X=Xd, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(Xd.cpu().numpy(), ref["X"], rtol=RTOL, atol=ATOL)
+        rest = torch.cat([xbuf[:x_off], xbuf[x_off + n * m:]]).cpu().numpy()
+        assert np.all(rest == 7.0), "wrote outside X"
+
+
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+def test_split_call_equals_whole_call_and_other_stream(mp, q):
+    rng = np.random.default_rng(22)
+    dev = torch.device("cuda:0")
+    Y = rng.standard_normal((700, 520)).astype(np.float32)
+    eta = eta_for(Y, q, 0.25)
+    Yd = torch.from_numpy(Y).to(dev)
+    ws = mp.Workspace.for_call(QNAME[q], *Y.shape, device=dev)
+    whole = getattr(mp, "bilevel_proj_" + QNAME[q])(Yd, eta, workspace=ws)      # no v_out / u_out
+    torch.cuda.synchronize()
+    tau_whole = ws.result()["tau"]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        v = torch.empty(Y.shape[1], dtype=torch.float32, device=dev)
+        u = torch.empty(Y.shape[1], dtype=torch.float32, device=dev)
+        mp.bilevel_radii(QNAME[q], Yd, eta, ws, v_out=v, stream=stream)
+        X2 = torch.empty_like(Yd)
+        mp.bilevel_apply(QNAME[q], Yd, X2, ws, u_out=u, stream=stream)
+    stream.synchronize()
+    assert ws.result()["tau"] == tau_whole
+    assert torch.equal(whole, X2)
+    ref = orc.bilevel(Y, eta, q)
+    np.testing.assert_allclose(u.cpu().numpy(), np.asarray(ref["u"], dtype=np.float32), rtol=RTOL, atol=ATOL)
+
+
+def test_kernel_trace_records_one_event_per_kernel(mp):
+    dev = torch.device("cuda:0")
+    Yd = torch.randn(512, 512, device=dev)
+    ws = mp.Workspace.for_call("l1inf", 512, 512, device=dev)
+    tr = mp.KernelTrace(16)
+    with tr:
+        mp.bilevel_proj_l1inf(Yd, 10.0, workspace=ws)
+    d = tr.durations_ms()
+    tr.close()
+    assert tr.count == 4 and len(d) == 3 and all(x > 0 for x in d)     # aggregate, reduce, map(+search)
+    mp.bilevel_proj_l1inf(Yd, 10.0, workspace=ws)                          # tracing is off again
+    assert mp.lib().mlproj_trace_end() == 0
+
+
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+def test_extreme_magnitudes_and_radii(mp, q):
+    rng = np.random.default_rng(23)
+    base = rng.standard_normal((96, 80)).astype(np.float32)
+    for scale in (np.float32(1e-18), np.float32(1e15)):
+        Y = base * scale
+        eta = eta_for(Y, q, 0.2)
+        got, ref = run_gpu(mp, Y, eta, q), orc.bilevel(Y, eta, q)
+        np.testing.assert_allclose(got["X"], ref["X"], rtol=RTOL, atol=ATOL * float(scale))
+        assert np.array_equal(got["u"] == 0, np.asarray(ref["u"]) == 0)
+    # a radius far below the resolution of the norms: everything (or all but one column) goes
+    got = run_gpu(mp, base, 1e-30, q)
+    assert np.abs(got["X"]).sum() <= 1e-6
+    # a radius that keeps exactly one column for q = inf
+    Y = base.copy()
+    Y[:, 5] *= 50
+    eta = 0.5 * float(np.abs(Y[:, 5]).max())
+    check_against_oracle(run_gpu(mp, Y, eta, "inf"), orc.bilevel_l1inf(Y, eta), "inf")
+
+
+def test_paper_timing_shape_uniform_entries(mp):
+    """The shape and distribution of the paper's own timing runs (Sec. 6.1): 1000 x 10000, U(0,1), eta = 1."""
+    w, Y = workloads.make("paper_1000x10000")
+    for eta in (0.25, 1.0, 4.0):
+        check_against_oracle(run_gpu(mp, Y, eta, "inf"), orc.bilevel_l1inf(Y, eta), "inf")
