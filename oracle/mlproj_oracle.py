@@ -25,7 +25,7 @@ import numpy as np
 __all__ = [
     "column_norms", "norm_l1q", "project_l1_ball_nonneg", "project_l1_ball",
     "project_linf_ball", "project_l2_ball", "bilevel_l1inf", "bilevel_l11",
-    "bilevel_l12", "trilevel_l1infinf", "bilevel",
+    "bilevel_l12", "trilevel_l1infinf", "bilevel", "multilevel",
 ]
 
 
@@ -223,3 +223,62 @@ def trilevel_l1infinf(Y, eta):
         for b in range(d1):
             X[a, b, :] = project_linf_ball(Y[a, b, :], U2[a, b])
     return {"X": X, "V": V, "w": w, "u": u, "U2": U2, "tau": tau}
+
+
+# --------------------------------------------------------------------------
+# Def. 5.2, Alg. 6 and its iterative form (appendix Alg. 8): multi-level
+# --------------------------------------------------------------------------
+def _fibre_norms(A, q):
+    """q-norm of every last-axis fibre of A, in fp64 (the aggregation V_nu of Sec. 5.2)."""
+    A = np.asarray(A, dtype=np.float64)
+    if q == "inf":
+        return np.max(np.abs(A), axis=-1)
+    if q == 1:
+        return np.sum(np.abs(A), axis=-1)
+    if q == 2:
+        return np.sqrt(np.sum(A * A, axis=-1))
+    raise ValueError("norm must be 'inf', 1 or 2")
+
+
+def _project_fibre(y, r, q):
+    """P^q_r of one fibre (fp64), by the single-vector projections defined above."""
+    y = np.asarray(y, dtype=np.float64)
+    if q == "inf":
+        return np.copysign(np.minimum(np.abs(y), r), y)
+    if q == 2:
+        return project_l2_ball(y, r)
+    return project_l1_ball(y, r)[0]
+
+
+def multilevel(Y, norms, eta):
+    """MP^nu_eta of a C-order tensor with single-axis norms, outermost norm l1.
+
+    `norms` lists the inner norms innermost first: norms[0] aggregates the LAST axis, norms[1]
+    the one before, ... down to axis 1; axis 0 carries the groups whose aggregate vector is
+    projected onto the l1 ball of radius eta.  In the paper's notation (which keeps the groups
+    on the last axis and aggregates the first axes first) this is nu = ((norms[0]), ...,
+    (norms[-1]), (1)) on the tensor with its axes reversed.
+
+    Follows the iterative form: aggregate level by level up to the vector, project it, then
+    for each level going back down project every fibre of that level's aggregate onto the
+    ball whose radius is the corresponding entry of the level above.
+    All intermediate levels in fp64; the result is rounded to fp32 once.
+    Returns dict(X, w, u, tau, V (list of aggregates), U (list of projected aggregates)).
+    """
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32 and Y.ndim >= 2 and len(norms) == Y.ndim - 1
+    V = [Y.astype(np.float64)]
+    for q in norms:                                   # aggregation, innermost axis first
+        V.append(_fibre_norms(V[-1], q))
+    w = V[-1]
+    u, tau = project_l1_ball_nonneg(w, eta)
+    U = [None] * len(V)
+    U[-1] = u
+    for k in range(len(norms), 0, -1):                # back down: level k radii -> level k-1
+        q = norms[k - 1]
+        src, rad = V[k - 1], U[k]
+        out = np.empty_like(src)
+        for idx in np.ndindex(rad.shape):
+            out[idx] = _project_fibre(src[idx], rad[idx], q)
+        U[k - 1] = out
+    return {"X": U[0].astype(np.float32), "w": w, "u": u, "tau": tau, "V": V, "U": U}

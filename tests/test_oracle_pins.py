@@ -319,3 +319,64 @@ def test_small_workload_through_the_oracle():
     assert orc.norm_l1q(out["X"], "inf") == pytest.approx(eta, rel=1e-5)
     zeroed = int((out["u"] == 0).sum())
     assert 0 < zeroed < 128
+
+
+# ---------------------------------------------------------------- multi-level
+def test_golden_multilevel_l111_worked(golden):
+    g = golden("multilevel_worked_2x2x2.txt")
+    out = orc.multilevel(np.array(g["Y"], dtype=np.float32), g["norms"], g["eta"])
+    np.testing.assert_allclose(out["w"], g["w"], rtol=1e-15)
+    assert out["tau"] == pytest.approx(g["tau"], rel=1e-15)
+    np.testing.assert_allclose(out["u"], g["u"], rtol=1e-15)
+    np.testing.assert_allclose(out["U"][1], np.array(g["U1"]), rtol=1e-15, atol=1e-15)
+    np.testing.assert_allclose(out["X"], np.array(g["X"]), rtol=1e-7, atol=0)
+
+
+@pytest.mark.parametrize("q", QS)
+def test_multilevel_with_one_inner_norm_is_the_bilevel_projection(q):
+    """nu = ((q),(1)) is the bi-level l1,q projection (Sec. 5.2); with groups on axis 0 the
+    matrix is the transpose of the column-group layout."""
+    Y = rand_matrix(13, 21)                      # 21 column groups
+    eta = 0.3 * orc.norm_l1q(Y, q)
+    bi = orc.bilevel(Y, eta, q)
+    ml = orc.multilevel(np.ascontiguousarray(Y.T), [q], eta)
+    np.testing.assert_allclose(ml["X"].T, bi["X"], rtol=1e-6, atol=1e-7)
+    assert ml["tau"] == pytest.approx(bi["tau"], rel=1e-12)
+
+
+def test_multilevel_inf_inf_is_the_trilevel_projection():
+    Y = RNG.standard_normal((5, 4, 7)).astype(np.float32)
+    eta = 0.4 * float(np.abs(Y).reshape(5, -1).max(axis=1).astype(np.float64).sum())
+    tri = orc.trilevel_l1infinf(Y, eta)
+    ml = orc.multilevel(Y, ["inf", "inf"], eta)
+    assert np.array_equal(ml["X"], tri["X"])
+    assert np.array_equal(ml["U"][1].astype(np.float32), tri["U2"])
+
+
+@pytest.mark.parametrize("norms", [[1, 1], [2, 2], ["inf", 1], [1, "inf"], [2, "inf"], [1, 2], ["inf", 2, 1], [1, 1, 1]])
+@pytest.mark.parametrize("frac", [0.05, 0.6, 1.5])
+def test_multilevel_every_level_is_a_projection(norms, frac):
+    """Def. 5.2: the top vector is projected onto the l1 ball, and at every level each fibre
+    of that level's aggregate is the projection onto the ball of the radius from above."""
+    shape = (4, 3, 5) if len(norms) == 2 else (3, 2, 3, 4)
+    Y = RNG.standard_normal(shape).astype(np.float32)
+    nrm = Y.astype(np.float64)
+    for q in norms:
+        nrm = lq(nrm, q, axis=-1)
+    eta = frac * float(nrm.sum())
+    out = orc.multilevel(Y, norms, eta)
+    np.testing.assert_allclose(out["w"], nrm, rtol=1e-13)
+    assert_is_projection(out["w"], out["u"], eta, 1)
+    for k in range(len(norms), 0, -1):
+        q = norms[k - 1]
+        for idx in np.ndindex(out["U"][k].shape):
+            assert_is_projection(out["V"][k - 1][idx], out["U"][k - 1][idx], float(out["U"][k][idx]), q)
+    # the result is feasible for the nested norm, and on the boundary when Y was outside
+    got = out["X"].astype(np.float64)
+    for q in norms:
+        got = lq(got, q, axis=-1)
+    assert got.sum() <= eta * (1 + 1e-5)
+    if frac < 1:
+        assert got.sum() == pytest.approx(eta, rel=1e-5)
+    else:
+        assert np.array_equal(out["X"], Y)
