@@ -63,6 +63,13 @@ typedef enum mlproj_variant {
   MLPROJ_L1INFINF = 3   /* trilevel_proj_l1infinf,  dims (d0, d1, d2)  */
 } mlproj_variant;
 
+/* Inner norms of the multi-level projection. */
+typedef enum mlproj_norm {
+  MLPROJ_NORM_INF = 0,
+  MLPROJ_NORM_L1 = 1,
+  MLPROJ_NORM_L2 = 2
+} mlproj_norm;
+
 /* Record left at offset 0 of the workspace by every projection / norm call. */
 typedef struct mlproj_result {
   double tau;            /* threshold of u = P^1_eta(v): u_j = max(v_j - tau, 0); 0 inside the ball  */
@@ -149,6 +156,26 @@ int trilevel_proj_l1infinf(const float* Y /* device, d0*d1*d2 */, float* X /* de
                            void* workspace, size_t workspace_bytes,
                            float* v_out /* device, d0; may be NULL */,
                            float* u_out /* device, d0; may be NULL */, void* stream);
+
+/* MP^nu_eta (Sec. 5.2, Def. 5.2, Alg. 6; iterative form in the appendix) on a C-order tensor of
+ * shape dims[0..ndim-1] (2 <= ndim <= 8) with single-axis inner norms and the l1 norm outside.
+ * Groups live on axis 0.  norms[0] aggregates the last axis, norms[1] the one before, ... ,
+ * norms[ndim-2] aggregates axis 1 (each MLPROJ_NORM_INF, _L1 or _L2); the resulting length-dims[0]
+ * vector is projected onto the l1 ball of radius eta, and on the way back every fibre of every
+ * level is projected onto the ball (of that level's norm) whose radius is the matching entry of
+ * the level above.  In the paper's notation, which keeps the groups on the last axis and
+ * aggregates the first axes first, this is nu = ((norms[0]), ..., (norms[ndim-2]), (1)) on the
+ * tensor with its axes reversed: ndim = 3 with two MLPROJ_NORM_INF is the tri-level
+ * l1,inf,inf, three MLPROJ_NORM_L1 levels give the l1,1,1 of Sec. 6.1, ndim = 2 is the bi-level
+ * projection of the transposed matrix.  dims and norms are host arrays; v_out / u_out have
+ * dims[0] entries.  The workspace comes from mlproj_multilevel_workspace_bytes.            */
+int mlproj_multilevel_workspace_bytes(int ndim, const long long* dims /* host */,
+                                      size_t* bytes_out /* host */);
+int multilevel_proj(const float* Y /* device */, float* X /* device, same size */, int ndim,
+                    const long long* dims /* host, ndim */, const int* norms /* host, ndim-1 */,
+                    float eta, void* workspace /* device */, size_t workspace_bytes,
+                    float* v_out /* device, dims[0]; may be NULL */,
+                    float* u_out /* device, dims[0]; may be NULL */, void* stream);
 
 #ifdef __cplusplus
 }

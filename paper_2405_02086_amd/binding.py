@@ -79,6 +79,11 @@ def lib():
     L.bilevel_radii.argtypes = [c_i, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp]
     L.bilevel_apply.restype = c_i
     L.bilevel_apply.argtypes = [c_i, c_vp, c_vp, c_ll, c_ll, c_vp, c_sz, c_vp, c_vp]
+    L.mlproj_multilevel_workspace_bytes.restype = c_i
+    L.mlproj_multilevel_workspace_bytes.argtypes = [c_i, ctypes.POINTER(c_ll), ctypes.POINTER(c_sz)]
+    L.multilevel_proj.restype = c_i
+    L.multilevel_proj.argtypes = [c_vp, c_vp, c_i, ctypes.POINTER(c_ll), ctypes.POINTER(c_i), c_f, c_vp, c_sz,
+                                  c_vp, c_vp, c_vp]
     L.trilevel_proj_l1infinf.restype = c_i
     L.trilevel_proj_l1infinf.argtypes = [c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     _lib = L
@@ -89,6 +94,7 @@ EXPORTS = (
     "mlproj_version", "mlproj_status_string", "mlproj_workspace_bytes", "mlproj_trace_begin", "mlproj_trace_end",
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
+    "mlproj_multilevel_workspace_bytes", "multilevel_proj",
 )
 
 
@@ -195,6 +201,33 @@ def trilevel_proj_l1infinf(Y, eta, X=None, workspace=None, v_out=None, u_out=Non
                                       _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out),
                                       _stream(stream))
     _check(st, "trilevel_proj_l1infinf")
+    return X
+
+
+NORM_INF, NORM_L1, NORM_L2 = 0, 1, 2
+_NORMS = {"inf": NORM_INF, 1: NORM_L1, 2: NORM_L2}
+
+
+def multilevel_workspace_bytes(shape):
+    dims = (ctypes.c_longlong * len(shape))(*shape)
+    out = ctypes.c_size_t(0)
+    _check(lib().mlproj_multilevel_workspace_bytes(len(shape), dims, ctypes.byref(out)),
+           "mlproj_multilevel_workspace_bytes")
+    return out.value
+
+
+def multilevel_proj(Y, norms, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
+    """norms: inner norms, innermost (last axis) first, each "inf", 1 or 2; groups on axis 0."""
+    X = _prep(Y, X)
+    shape = tuple(Y.shape)
+    assert len(norms) == len(shape) - 1
+    if workspace is None:
+        workspace = Workspace(multilevel_workspace_bytes(shape), device=Y.device)
+    dims = (ctypes.c_longlong * len(shape))(*shape)
+    nrm = (ctypes.c_int * len(norms))(*[_NORMS[q] for q in norms])
+    st = lib().multilevel_proj(_ptr(Y), _ptr(X), len(shape), dims, nrm, ctypes.c_float(eta),
+                               _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out), _stream(stream))
+    _check(st, "multilevel_proj")
     return X
 
 

@@ -17,6 +17,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <type_traits>
 
 #include "../../include/mlproj.h"
 
@@ -1050,6 +1051,230 @@ __global__ __launch_bounds__(WG) void slabmap_kernel(const float* Y, float* X, l
   }
 }
 
+// ------------------------------------------------------------------ multi-level: fibre kernels
+// The generic multi-level projection MP^nu (Sec. 5.2, Def. 5.2, Alg. 6 and its iterative form
+// in the appendix) on a C-order tensor with the groups on axis 0: every level aggregates the
+// contiguous last-axis fibres of the level below (fibre_agg), the top vector is projected
+// onto the l1 ball (the search above), and on the way back every fibre is projected onto the
+// ball whose radius is the matching entry of the level above (fibre_map).
+// SEG lanes (4, 16 or 64) cooperate on one fibre, so a wavefront holds 64/SEG fibres; segment
+// reductions run on the DPP crossbar with rotations, which leave the result in every lane.
+constexpr int DPP_ROR4 = 0x124, DPP_ROR8 = 0x128;
+
+template <int SEG>
+__device__ __forceinline__ double seg_sum(double x) {
+  x += dpp_f64<DPP_SWAP1>(x);
+  x += dpp_f64<DPP_SWAP2>(x);
+  if constexpr (SEG >= 16) {
+    x += dpp_f64<DPP_ROR4>(x);
+    x += dpp_f64<DPP_ROR8>(x);
+  }
+  if constexpr (SEG == 64) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    double r = 0.0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+      const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, row * 16);
+      const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), row * 16);
+      r += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+    }
+    x = r;
+  }
+  return x;
+}
+template <int SEG>
+__device__ __forceinline__ double seg_max(double x) {  // non-negative values
+  x = fmax(x, dpp_f64<DPP_SWAP1>(x));
+  x = fmax(x, dpp_f64<DPP_SWAP2>(x));
+  if constexpr (SEG >= 16) {
+    x = fmax(x, dpp_f64<DPP_ROR4>(x));
+    x = fmax(x, dpp_f64<DPP_ROR8>(x));
+  }
+  if constexpr (SEG == 64) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    double r = 0.0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+      const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, row * 16);
+      const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), row * 16);
+      r = fmax(r, __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo)));
+    }
+    x = r;
+  }
+  return x;
+}
+template <int SEG>
+__device__ __forceinline__ unsigned seg_sum_u(unsigned x) {
+  x += dpp_u32<DPP_SWAP1>(x);
+  x += dpp_u32<DPP_SWAP2>(x);
+  if constexpr (SEG >= 16) {
+    x += dpp_u32<DPP_ROR4>(x);
+    x += dpp_u32<DPP_ROR8>(x);
+  }
+  if constexpr (SEG == 64) {
+    unsigned r = 0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) r += (unsigned)__builtin_amdgcn_readlane((int)x, row * 16);
+    x = r;
+  }
+  return x;
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_elems(const T* p, double (&x)[VEC]) {
+  if constexpr (VEC == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+  } else {
+    x[0] = (double)*p;
+  }
+}
+
+template <int Q>
+__device__ __forceinline__ void accumulate_d(double& a, double y) {
+  if constexpr (Q == QINF) a = fmax(a, fabs(y));
+  else if constexpr (Q == Q1) a += fabs(y);
+  else a = fma(y, y, a);
+}
+
+constexpr int FIB_UNROLL = 4;  // fibres a segment works on at once (loads in flight)
+
+// V[f] = || fibre f ||_q for nf contiguous fibres of len elements (len = nvec * VEC).
+template <int Q, typename TIN, int SEG, int VEC>
+__global__ __launch_bounds__(WG) void fibre_agg_kernel(const TIN* __restrict__ A, long long nf,
+                                                       long long len, double* __restrict__ V,
+                                                       float* __restrict__ v_out) {
+  constexpr int PER_WAVE = WAVE / SEG;
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int sl = lane % SEG;
+  const long long nvec = len / VEC;
+  const long long wave_id = (long long)blockIdx.x * WAVES + threadIdx.x / WAVE;
+  const long long nwaves = (long long)gridDim.x * WAVES;
+  const long long step = nwaves * PER_WAVE;
+  for (long long f0 = wave_id * PER_WAVE + lane / SEG; f0 - lane / SEG < nf; f0 += step * FIB_UNROLL) {
+    double acc[FIB_UNROLL];
+#pragma unroll
+    for (int u = 0; u < FIB_UNROLL; ++u) acc[u] = 0.0;
+    for (long long i = sl; i < nvec; i += SEG) {
+      double x[FIB_UNROLL][VEC];
+#pragma unroll
+      for (int u = 0; u < FIB_UNROLL; ++u) {
+        const long long f = f0 + (long long)u * step;
+        if (f < nf) load_elems<TIN, VEC>(A + f * len + i * VEC, x[u]);
+        else {
+#pragma unroll
+          for (int k = 0; k < VEC; ++k) x[u][k] = 0.0;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < FIB_UNROLL; ++u)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) accumulate_d<Q>(acc[u], x[u][k]);
+    }
+#pragma unroll
+    for (int u = 0; u < FIB_UNROLL; ++u) {
+      const double tot = (Q == QINF) ? seg_max<SEG>(acc[u]) : seg_sum<SEG>(acc[u]);
+      const long long f = f0 + (long long)u * step;
+      if (sl == 0 && f < nf) {
+        const double vf = (Q == Q2) ? sqrt(tot) : tot;
+        V[f] = vf;
+        if (v_out) v_out[f] = (float)vf;
+      }
+    }
+  }
+}
+
+__global__ void clear_flags_kernel(Ws ws) {
+  if (threadIdx.x < 2) ws.flags[threadIdx.x] = 0u;
+}
+
+// Radii of the top level from the threshold: R[a] = max(w[a] - tau, 0).
+__global__ __launch_bounds__(WG) void top_radii_kernel(Ws ws, long long d0, double* __restrict__ R,
+                                                       float* __restrict__ u_out) {
+  const long long a = (long long)blockIdx.x * WG + threadIdx.x;
+  if (a >= d0) return;
+  const double u = fmax(ws.v[a] - ws.res->tau, 0.0);
+  R[a] = u;
+  if (u_out) u_out[a] = (float)u;
+}
+
+// out fibre f = P^q_{R[f]}(fibre f of A), where Vn[f] is that fibre's own q-norm (known from
+// the aggregation): clip (q = inf), rescale by R/Vn (q = 2), or shrink by the fibre's own
+// threshold (q = 1), which the segment finds with the same Newton iteration as everywhere
+// else, re-reading its fibre from cache on every step.
+template <int Q, typename TIN, typename TOUT, int SEG, int VEC>
+__global__ __launch_bounds__(WG) void fibre_map_kernel(const TIN* A, long long nf, long long len,
+                                                       const double* __restrict__ R,
+                                                       const double* __restrict__ Vn, TOUT* out) {
+  constexpr int PER_WAVE = WAVE / SEG;
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int sl = lane % SEG;
+  const long long nvec = len / VEC;
+  const long long wave_id = (long long)blockIdx.x * WAVES + threadIdx.x / WAVE;
+  const long long nwaves = (long long)gridDim.x * WAVES;
+  const long long step = nwaves * PER_WAVE;
+  for (long long f0 = wave_id * PER_WAVE + lane / SEG; f0 - lane / SEG < nf; f0 += step) {
+    const bool live = f0 < nf;
+    const long long f = live ? f0 : nf - 1;  // idle segments shadow the last fibre, stores off
+    const double r = R[f];
+    const double nv = Vn[f];
+    const TIN* p = A + f * len;
+    TOUT* q = out + f * len;
+    double par = 0.0;  // q = 2: scale; q = 1: threshold
+    if constexpr (Q == Q2) par = nv > r ? r / nv : 1.0;
+    if constexpr (Q == Q1) {
+      // all lanes of the wavefront stay in the loop until every segment is done
+      bool open = nv > r;
+      double t = open ? (nv - r) / (double)len : 0.0;  // every entry active: a lower bound
+      unsigned kprev = 0xffffffffu;
+      while (__any(open)) {
+        double s = 0.0;
+        unsigned c = 0;
+        for (long long i = sl; i < nvec; i += SEG) {
+          double x[VEC];
+          load_elems<TIN, VEC>(p + i * VEC, x);
+#pragma unroll
+          for (int k = 0; k < VEC; ++k) {
+            const double a = fabs(x[k]);
+            if (a > t) { s += a; ++c; }
+          }
+        }
+        s = seg_sum<SEG>(s);
+        c = seg_sum_u<SEG>(c);
+        if (open) {
+          if (c == 0u || c == kprev) open = false;
+          else {
+            kprev = c;
+            const double tn = (s - r) / (double)c;
+            if (tn > t) t = tn;
+          }
+        }
+      }
+      par = t;
+    }
+    for (long long i = sl; i < nvec; i += SEG) {
+      double x[VEC];
+      load_elems<TIN, VEC>(p + i * VEC, x);
+      TOUT y[VEC];
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        double z;
+        if constexpr (Q == QINF) z = copysign(fmin(fabs(x[k]), r), x[k]);
+        else if constexpr (Q == Q2) z = x[k] * par;
+        else z = copysign(fmax(fabs(x[k]) - par, 0.0), x[k]);
+        y[k] = (TOUT)z;
+      }
+      if (live) {
+        if constexpr (VEC == 4) {
+          *reinterpret_cast<float4*>(q + i * VEC) = make_float4(y[0], y[1], y[2], y[3]);
+        } else {
+          q[i] = y[0];
+        }
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ host: checks + launches
 constexpr long long MAX_ELEMS = 1LL << 40;       // 4 TiB of fp32: far beyond one GPU
 constexpr long long MAX_GROUPS = (1LL << 31) - 1;
@@ -1214,6 +1439,145 @@ static int dispatch_q(int variant, A... a) {
   }
 }
 
+// ------------------------------------------------------------------ host: multi-level driver
+constexpr int ML_MAX_DIMS = 8;
+constexpr long long ML_TARGET_WGS = 1024;
+
+struct MlPlan {
+  int ndim;
+  long long size[ML_MAX_DIMS];   // size[k] = elements of level k = prod dims[0 .. ndim-1-k]
+  long long len[ML_MAX_DIMS];    // len[k]  = fibre length aggregated to make level k (k >= 1)
+  size_t off_V[ML_MAX_DIMS], off_R[ML_MAX_DIMS];  // fp64 arrays of level k (k = 1 .. ndim-1)
+  Layout base;
+  size_t bytes;
+};
+
+static int ml_plan(int ndim, const long long* dims, const int* norms, MlPlan* P) {
+  if (!dims || !norms) return MLPROJ_ERR_NULL_POINTER;
+  if (ndim < 2 || ndim > ML_MAX_DIMS) return MLPROJ_ERR_BAD_DIMENSION;
+  long long total = 1;
+  for (int i = 0; i < ndim; ++i) {
+    if (dims[i] <= 0) return MLPROJ_ERR_BAD_DIMENSION;
+    if (dims[i] > MAX_ELEMS || total > MAX_ELEMS / dims[i]) return MLPROJ_ERR_TOO_LARGE;
+    total *= dims[i];
+  }
+  if (dims[0] > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
+  for (int k = 0; k < ndim - 1; ++k)
+    if (norms[k] != MLPROJ_NORM_INF && norms[k] != MLPROJ_NORM_L1 && norms[k] != MLPROJ_NORM_L2)
+      return MLPROJ_ERR_BAD_VARIANT;
+  P->ndim = ndim;
+  long long sz = total;
+  for (int k = 0; k < ndim; ++k) {
+    P->size[k] = sz;
+    P->len[k] = k == 0 ? 0 : dims[ndim - k];
+    if (k + 1 < ndim) sz /= dims[ndim - 1 - k];
+  }
+  Geometry g{};  // no column partials: only the record, the search scratch and v[d0] are used
+  g.tiles = 1; g.groups = 1; g.tile_w = 1; g.vec = 1;
+  P->base = layout_for(g, dims[0], MLPROJ_L1INF);
+  size_t o = P->base.bytes;
+  for (int k = 1; k < ndim; ++k) {
+    P->off_V[k] = o; o = align_up(o + (size_t)P->size[k] * 8, 256);
+    P->off_R[k] = o; o = align_up(o + (size_t)P->size[k] * 8, 256);
+  }
+  P->bytes = o;
+  return MLPROJ_OK;
+}
+
+static int seg_for(long long nvec) { return nvec <= 4 ? 4 : (nvec <= 16 ? 16 : 64); }
+
+static unsigned fibre_grid(long long nf, int seg, int unroll) {
+  const long long per_wg = (long long)WAVES * (WAVE / seg) * unroll;
+  long long wgs = cdiv(nf, per_wg);
+  if (wgs > ML_TARGET_WGS) wgs = ML_TARGET_WGS;
+  return (unsigned)(wgs < 1 ? 1 : wgs);
+}
+
+template <int Q, typename TIN, int VEC>
+static void launch_fibre_agg(const TIN* A, long long nf, long long len, double* V, float* v_out,
+                             hipStream_t stream) {
+  const int seg = seg_for(len / VEC);
+  const dim3 grid(fibre_grid(nf, seg, FIB_UNROLL)), block(WG);
+  if (seg == 4) hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 4, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+  else if (seg == 16) hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 16, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+  else hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 64, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+}
+
+template <int Q, typename TIN, typename TOUT, int VEC>
+static void launch_fibre_map(const TIN* A, long long nf, long long len, const double* R,
+                             const double* Vn, TOUT* out, hipStream_t stream) {
+  const int seg = seg_for(len / VEC);
+  const dim3 grid(fibre_grid(nf, seg, 1)), block(WG);
+  if (seg == 4) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 4, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
+  else if (seg == 16) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 16, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
+  else hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 64, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
+}
+
+template <typename F>
+static void by_norm(int norm, F&& f) {
+  if (norm == MLPROJ_NORM_INF) f(std::integral_constant<int, QINF>{});
+  else if (norm == MLPROJ_NORM_L1) f(std::integral_constant<int, Q1>{});
+  else f(std::integral_constant<int, Q2>{});
+}
+
+static int run_multilevel(const float* Y, float* X, int ndim, const long long* dims,
+                          const int* norms, float eta, void* workspace, size_t workspace_bytes,
+                          float* v_out, float* u_out, void* stream_) {
+  if (!Y || !X || !workspace) return MLPROJ_ERR_NULL_POINTER;
+  MlPlan P;
+  int st = ml_plan(ndim, dims, norms, &P);
+  if (st != MLPROJ_OK) return st;
+  if ((st = check_radius(eta)) != MLPROJ_OK) return st;
+  if (!aligned(Y, 4) || !aligned(X, 4)) return MLPROJ_ERR_ALIGNMENT;
+  if (!aligned(workspace, 256) || workspace_bytes < P.bytes) return MLPROJ_ERR_WORKSPACE;
+  const Ws ws = bind(workspace, P.base);
+  char* base = static_cast<char*>(workspace);
+  double* V[ML_MAX_DIMS];
+  double* R[ML_MAX_DIMS];
+  for (int k = 1; k < ndim; ++k) {
+    V[k] = reinterpret_cast<double*>(base + P.off_V[k]);
+    R[k] = reinterpret_cast<double*>(base + P.off_R[k]);
+  }
+  V[ndim - 1] = ws.v;  // the top aggregate is the vector the search reads
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const long long len1 = P.len[1];
+  const bool vec4 = len1 % 4 == 0 && aligned(Y, 16) && aligned(X, 16);
+
+  // up: aggregate level by level
+  mark(stream);
+  by_norm(norms[0], [&](auto q) {
+    float* vo = ndim == 2 ? v_out : nullptr;
+    if (vec4) launch_fibre_agg<decltype(q)::value, float, 4>(Y, P.size[1], len1, V[1], vo, stream);
+    else launch_fibre_agg<decltype(q)::value, float, 1>(Y, P.size[1], len1, V[1], vo, stream);
+  });
+  for (int k = 2; k < ndim; ++k) {
+    by_norm(norms[k - 1], [&](auto q) {
+      launch_fibre_agg<decltype(q)::value, double, 1>(V[k - 1], P.size[k], P.len[k], V[k],
+                                                      k == ndim - 1 ? v_out : nullptr, stream);
+    });
+  }
+  // top: threshold of the l1-ball projection of the length-d0 vector, then its radii
+  mark(stream);
+  hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
+  launch_search(ws, dims[0], (double)eta, MODE_PROJECT, nullptr, stream);
+  hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
+                     dims[0], R[ndim - 1], u_out);
+  // down: project the fibres of every level onto the balls of the level above
+  mark(stream);
+  for (int k = ndim - 1; k >= 2; --k) {
+    by_norm(norms[k - 1], [&](auto q) {
+      launch_fibre_map<decltype(q)::value, double, double, 1>(V[k - 1], P.size[k], P.len[k], R[k], V[k],
+                                                              R[k - 1], stream);
+    });
+  }
+  by_norm(norms[0], [&](auto q) {
+    if (vec4) launch_fibre_map<decltype(q)::value, float, float, 4>(Y, P.size[1], len1, R[1], V[1], X, stream);
+    else launch_fibre_map<decltype(q)::value, float, float, 1>(Y, P.size[1], len1, R[1], V[1], X, stream);
+  });
+  mark(stream);
+  return launch_status();
+}
+
 }  // namespace mlproj
 
 // ------------------------------------------------------------------ C ABI
@@ -1294,6 +1658,22 @@ int bilevel_apply(int variant, const float* Y, float* X, long long n, long long 
                   void* workspace, size_t workspace_bytes, float* u_out, void* stream) {
   return dispatch_q(variant, Y, X, n, m, 0.f, workspace, workspace_bytes, (float*)nullptr, u_out,
                     stream, MODE_PROJECT, (double*)nullptr, STAGE_APPLY);
+}
+
+int mlproj_multilevel_workspace_bytes(int ndim, const long long* dims, size_t* bytes_out) {
+  if (!bytes_out) return MLPROJ_ERR_NULL_POINTER;
+  int norms[ML_MAX_DIMS] = {0};
+  MlPlan P;
+  const int st = ml_plan(ndim, dims, norms, &P);
+  if (st != MLPROJ_OK) return st;
+  *bytes_out = P.bytes;
+  return MLPROJ_OK;
+}
+
+int multilevel_proj(const float* Y, float* X, int ndim, const long long* dims, const int* norms,
+                    float eta, void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
+                    void* stream) {
+  return run_multilevel(Y, X, ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream);
 }
 
 int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1, long long d2,

@@ -328,3 +328,67 @@ def test_paper_timing_shape_uniform_entries(mp):
     w, Y = workloads.make("paper_1000x10000")
     for eta in (0.25, 1.0, 4.0):
         check_against_oracle(run_gpu(mp, Y, eta, "inf"), orc.bilevel_l1inf(Y, eta), "inf")
+
+
+# ------------------------------------------------------------------ multi-level (generic)
+def run_multi(mp, Y, norms, eta):
+    dev = torch.device("cuda:0")
+    Yd = torch.from_numpy(Y).to(dev)
+    d0 = Y.shape[0]
+    ws = mp.Workspace(mp.multilevel_workspace_bytes(Y.shape), device=dev)
+    v = torch.full((d0,), -1.0, dtype=torch.float32, device=dev)
+    u = torch.full((d0,), -1.0, dtype=torch.float32, device=dev)
+    X = mp.multilevel_proj(Yd, norms, eta, workspace=ws, v_out=v, u_out=u)
+    torch.cuda.synchronize()
+    return {"X": X.cpu().numpy(), "v": v.cpu().numpy(), "u": u.cpu().numpy(), "res": ws.result()}
+
+
+def nested_norm(Y, norms):
+    a = Y.astype(np.float64)
+    for q in norms:
+        a = {"inf": lambda z: np.abs(z).max(axis=-1), 1: lambda z: np.abs(z).sum(axis=-1),
+             2: lambda z: np.sqrt((z * z).sum(axis=-1))}[q](a)
+    return float(a.sum())
+
+
+def check_multi(got, ref):
+    np.testing.assert_allclose(got["v"], ref["w"].astype(np.float32), rtol=2e-7)
+    np.testing.assert_allclose(got["u"], ref["u"].astype(np.float32), rtol=RTOL, atol=ATOL)
+    assert np.array_equal(got["u"] == 0, ref["u"] == 0)
+    assert got["res"]["tau"] == pytest.approx(ref["tau"], rel=1e-9, abs=1e-300)
+    np.testing.assert_allclose(got["X"], ref["X"], rtol=RTOL, atol=ATOL)
+
+
+ML_CASES = [
+    ((5, 7), [1]), ((5, 7), ["inf"]), ((300, 33), [2]), ((6, 1030), [1]),
+    ((4, 3, 5), [1, 1]), ((4, 3, 5), ["inf", "inf"]), ((4, 3, 5), [2, 2]), ((9, 16, 3), ["inf", 1]),
+    ((9, 16, 3), [1, 2]), ((7, 5, 64), [1, "inf"]), ((3, 40, 260), [1, 1]), ((3, 40, 260), [2, 1]),
+    ((5, 4, 3, 6), [1, 1, 1]), ((5, 4, 3, 6), ["inf", 2, 1]), ((2, 3, 2, 2, 8), [1, "inf", 2, 1]),
+    ((20000, 2, 4), [1, 1]), ((1, 1, 1), [1, 1]), ((3, 1, 2000), [1, 1]),
+]
+
+
+@pytest.mark.parametrize("shape,norms", ML_CASES)
+def test_multilevel_matches_oracle(mp, shape, norms):
+    rng = np.random.default_rng(list(shape) + [len(norms)])
+    Y = rng.standard_normal(shape).astype(np.float32)
+    nrm = nested_norm(Y, norms)
+    for frac in (0.05, 0.5, 1.5, 0.0):
+        eta = float(np.float32(frac * nrm))
+        check_multi(run_multi(mp, Y, norms, eta), orc.multilevel(Y, norms, eta))
+
+
+def test_multilevel_inf_inf_equals_the_trilevel_entry_point(mp):
+    rng = np.random.default_rng(31)
+    Y = rng.standard_normal((40, 24, 36)).astype(np.float32)
+    eta = float(np.float32(0.3 * nested_norm(Y, ["inf", "inf"])))
+    a = run_multi(mp, Y, ["inf", "inf"], eta)
+    b = run_tri(mp, Y, eta)
+    assert np.array_equal(a["X"], b["X"]) and np.array_equal(a["u"], b["u"])
+
+
+@pytest.mark.parametrize("norms", [[1, 1], ["inf", "inf"], [2, 1]])
+def test_workload_tensor_256_multilevel(mp, norms):
+    w, Y = workloads.make("tensor_256x256x256")
+    eta = float(np.float32(w.eta_frac * nested_norm(Y, norms)))
+    check_multi(run_multi(mp, Y, norms, eta), orc.multilevel(Y, norms, eta))
