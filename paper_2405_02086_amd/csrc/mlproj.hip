@@ -529,14 +529,24 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
   if (norm_out) *norm_out = o.total;
 }
 
+// radii / u_out (optional): also write u_j = max(v_j - tau, 0) for every group.
 __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
                                                      int mode, double* __restrict__ norm_out,
-                                                     int only_as_fallback) {
+                                                     int only_as_fallback,
+                                                     double* __restrict__ radii,
+                                                     float* __restrict__ u_out) {
   __shared__ PairScratch<SWAVES> s;
   if (only_as_fallback && ws.flags[1] == 0u) return;
   const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, s);
   if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
   if (threadIdx.x == 0) write_result(ws, o, norm_out);
+  if (radii) {
+    for (long long i = threadIdx.x; i < ngroups; i += SWG) {
+      const double u = fmax(ws.v[i] - o.tau, 0.0);
+      radii[i] = u;
+      if (u_out) u_out[i] = (float)u;
+    }
+  }
 }
 
 // The same search for very long v (more groups than one workgroup holds in registers): up to
@@ -1275,6 +1285,111 @@ __global__ __launch_bounds__(WG) void fibre_map_kernel(const TIN* A, long long n
   }
 }
 
+// The same map for fibres short enough to sit in registers (at most KREG chunks of VEC elements
+// per lane): each segment loads FIB_MAP_UNROLL fibres once, searches in registers, and stores.
+constexpr int FIB_MAP_UNROLL = 2;
+
+template <int Q, typename TIN, typename TOUT, int SEG, int VEC, int KREG>
+__global__ __launch_bounds__(WG) void fibre_map_cached_kernel(const TIN* A, long long nf,
+                                                              long long len,
+                                                              const double* __restrict__ R,
+                                                              const double* __restrict__ Vn,
+                                                              TOUT* out) {
+  constexpr int PER_WAVE = WAVE / SEG;
+  constexpr int UF = FIB_MAP_UNROLL;
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int sl = lane % SEG;
+  const long long nvec = len / VEC;
+  const long long wave_id = (long long)blockIdx.x * WAVES + threadIdx.x / WAVE;
+  const long long nwaves = (long long)gridDim.x * WAVES;
+  const long long step = nwaves * PER_WAVE;
+  for (long long f0 = wave_id * PER_WAVE + lane / SEG; f0 - lane / SEG < nf; f0 += step * UF) {
+    double x[UF][KREG][VEC];
+    double r[UF], nv[UF];
+    bool live[UF];
+    long long f[UF];
+#pragma unroll
+    for (int u = 0; u < UF; ++u) {
+      const long long fu = f0 + (long long)u * step;
+      live[u] = fu < nf;
+      f[u] = live[u] ? fu : nf - 1;  // idle segments shadow the last fibre, stores off
+#pragma unroll
+      for (int k = 0; k < KREG; ++k) {
+        const long long i = sl + (long long)k * SEG;
+        if (i < nvec) load_elems<TIN, VEC>(A + f[u] * len + i * VEC, x[u][k]);
+        else {
+#pragma unroll
+          for (int c = 0; c < VEC; ++c) x[u][k][c] = 0.0;  // 0 never counts: thresholds are > 0
+        }
+      }
+      r[u] = R[f[u]];
+      nv[u] = Vn[f[u]];
+    }
+    double par[UF];
+#pragma unroll
+    for (int u = 0; u < UF; ++u) par[u] = (Q == Q2) ? (nv[u] > r[u] ? r[u] / nv[u] : 1.0) : 0.0;
+    if constexpr (Q == Q1) {
+      bool open[UF];
+      unsigned kprev[UF];
+      bool any_open = false;
+#pragma unroll
+      for (int u = 0; u < UF; ++u) {
+        open[u] = nv[u] > r[u];
+        par[u] = open[u] ? (nv[u] - r[u]) / (double)len : 0.0;
+        kprev[u] = 0xffffffffu;
+        any_open = any_open || open[u];
+      }
+      while (__any(any_open)) {
+        any_open = false;
+#pragma unroll
+        for (int u = 0; u < UF; ++u) {
+          double s = 0.0;
+          unsigned c = 0;
+#pragma unroll
+          for (int k = 0; k < KREG; ++k)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+              const double a = fabs(x[u][k][e]);
+              if (a > par[u]) { s += a; ++c; }
+            }
+          s = seg_sum<SEG>(s);
+          c = seg_sum_u<SEG>(c);
+          if (open[u]) {
+            if (c == 0u || c == kprev[u]) open[u] = false;
+            else {
+              kprev[u] = c;
+              const double tn = (s - r[u]) / (double)c;
+              if (tn > par[u]) par[u] = tn;
+            }
+          }
+          any_open = any_open || open[u];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UF; ++u) {
+#pragma unroll
+      for (int k = 0; k < KREG; ++k) {
+        const long long i = sl + (long long)k * SEG;
+        TOUT y[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          double z;
+          if constexpr (Q == QINF) z = copysign(fmin(fabs(x[u][k][e]), r[u]), x[u][k][e]);
+          else if constexpr (Q == Q2) z = x[u][k][e] * par[u];
+          else z = copysign(fmax(fabs(x[u][k][e]) - par[u], 0.0), x[u][k][e]);
+          y[e] = (TOUT)z;
+        }
+        if (live[u] && i < nvec) {
+          TOUT* q = out + f[u] * len + i * VEC;
+          if constexpr (VEC == 4) *reinterpret_cast<float4*>(q) = make_float4(y[0], y[1], y[2], y[3]);
+          else q[0] = y[0];
+        }
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ host: checks + launches
 constexpr long long MAX_ELEMS = 1LL << 40;       // 4 TiB of fp32: far beyond one GPU
 constexpr long long MAX_GROUPS = (1LL << 31) - 1;
@@ -1355,7 +1470,8 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
     hipLaunchKernelGGL(search_wide_kernel, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
     only_as_fallback = 1;
   }
-  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out, only_as_fallback);
+  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out, only_as_fallback,
+                     (double*)nullptr, (float*)nullptr);
 }
 
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
@@ -1484,7 +1600,8 @@ static int ml_plan(int ndim, const long long* dims, const int* norms, MlPlan* P)
   return MLPROJ_OK;
 }
 
-static int seg_for(long long nvec) { return nvec <= 4 ? 4 : (nvec <= 16 ? 16 : 64); }
+// lanes per fibre: few enough that every lane has up to four chunks to itself
+static int seg_for(long long nvec) { return nvec <= 16 ? 4 : (nvec <= 64 ? 16 : 64); }
 
 static unsigned fibre_grid(long long nf, int seg, int unroll) {
   const long long per_wg = (long long)WAVES * (WAVE / seg) * unroll;
@@ -1506,7 +1623,21 @@ static void launch_fibre_agg(const TIN* A, long long nf, long long len, double* 
 template <int Q, typename TIN, typename TOUT, int VEC>
 static void launch_fibre_map(const TIN* A, long long nf, long long len, const double* R,
                              const double* Vn, TOUT* out, hipStream_t stream) {
-  const int seg = seg_for(len / VEC);
+  const long long nvec = len / VEC;
+  const int seg = seg_for(nvec);
+  if (nvec <= (long long)seg * 4) {
+    // the fibre fits the registers of its segment
+    const dim3 cgrid(fibre_grid(nf, seg, FIB_MAP_UNROLL)), cblock(WG);
+    const int kreg = nvec <= seg ? 1 : (nvec <= 2LL * seg ? 2 : 4);
+#define MLPROJ_LAUNCH_CACHED(SEG_, K_)                                                              \
+  hipLaunchKernelGGL((fibre_map_cached_kernel<Q, TIN, TOUT, SEG_, VEC, K_>), cgrid, cblock, 0, stream, \
+                     A, nf, len, R, Vn, out)
+    if (seg == 4) { if (kreg == 1) MLPROJ_LAUNCH_CACHED(4, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(4, 2); else MLPROJ_LAUNCH_CACHED(4, 4); }
+    else if (seg == 16) { if (kreg == 1) MLPROJ_LAUNCH_CACHED(16, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(16, 2); else MLPROJ_LAUNCH_CACHED(16, 4); }
+    else { if (kreg == 1) MLPROJ_LAUNCH_CACHED(64, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(64, 2); else MLPROJ_LAUNCH_CACHED(64, 4); }
+#undef MLPROJ_LAUNCH_CACHED
+    return;
+  }
   const dim3 grid(fibre_grid(nf, seg, 1)), block(WG);
   if (seg == 4) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 4, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
   else if (seg == 16) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 16, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
@@ -1558,10 +1689,15 @@ static int run_multilevel(const float* Y, float* X, int ndim, const long long* d
   }
   // top: threshold of the l1-ball projection of the length-d0 vector, then its radii
   mark(stream);
-  hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
-  launch_search(ws, dims[0], (double)eta, MODE_PROJECT, nullptr, stream);
-  hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
-                     dims[0], R[ndim - 1], u_out);
+  if (dims[0] <= (long long)SWG * SEARCH_CACHE) {
+    hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
+                       (double*)nullptr, 0, R[ndim - 1], u_out);
+  } else {
+    hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
+    launch_search(ws, dims[0], (double)eta, MODE_PROJECT, nullptr, stream);
+    hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
+                       dims[0], R[ndim - 1], u_out);
+  }
   // down: project the fibres of every level onto the balls of the level above
   mark(stream);
   for (int k = ndim - 1; k >= 2; --k) {
