@@ -124,6 +124,40 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True):
     return out
 
 
+def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
+    """Tri-level l1,inf,inf (its own entry point) and the generic multi-level engine on a 3-D tensor."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    d0 = Y_host.shape[0]
+    npairs = max(2, -(-3 * INFINITY_CACHE_BYTES // (2 * Y_host.nbytes)))
+    Y0 = torch.from_numpy(Y_host).to(dev)
+    pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
+    elems = Y_host.size
+    out = {}
+
+    def record(name, fn, ws, eta):
+        ms = time_calls(torch, fn, pairs, steps, warmup)
+        res = ws.result()
+        out[name] = {"shape": list(Y_host.shape), "eta": eta, "ms": ms, "eff_GBps_8B": 8.0 * elems / ms / 1e6,
+                     "frac_of_peak_8B": 8.0 * elems / ms / 1e6 / HBM_PEAK_GBS, "tau": res["tau"],
+                     "n_active": res["n_active"]}
+
+    # eta from the library itself: the nested norm is the sum of the aggregate vector
+    for name, norms in (("l1infinf", ["inf", "inf"]), ("l111", [1, 1]), ("l122", [2, 2])):
+        ws = mp.Workspace(mp.multilevel_workspace_bytes(Y_host.shape), device=dev)
+        v = torch.empty(d0, dtype=torch.float32, device=dev)
+        mp.multilevel_proj(pairs[0][0], norms, 3.0e38, X=pairs[0][1], workspace=ws, v_out=v)
+        torch.cuda.synchronize()
+        eta = float(np.float32(frac * ws.result()["norm"]))
+        if name == "l1infinf":
+            ws3 = mp.Workspace.for_call("tri", *Y_host.shape, device=dev)
+            record("trilevel_proj_l1infinf", lambda Y, X: mp.trilevel_proj_l1infinf(Y, eta, X=X, workspace=ws3), ws3, eta)
+        record("multilevel_proj/" + name, lambda Y, X: mp.multilevel_proj(Y, norms, eta, X=X, workspace=ws), ws, eta)
+    del pairs
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(Y_host, frac, budget_s=20.0):
     """The oracle as it stands, single numpy thread, on the headline workload."""
     import numpy as np
@@ -188,6 +222,9 @@ def main():
         for variant, steps in (("l1inf", 20), ("l12", 20), ("l11", 5)):
             also["square_16384/" + variant] = bench_bilevel(torch, mp, Yb, variant, wb.eta_frac, steps, 3)
         del Yb
+        wt, Yt = workloads.make("tensor_256x256x256")
+        for k, v in bench_tensor(torch, mp, Yt, wt.eta_frac, 100, 10).items():
+            also["tensor_256x256x256/" + k] = v
         line["also"] = also
     if not (args.quick or args.no_cpu):
         line["cpu_baseline"] = cpu_baseline(Y, w.eta_frac)

@@ -101,3 +101,24 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.lib()
+
+
+def test_multilevel_argument_checks(lib):
+    big = 1 << 30
+    LL, I = ctypes.c_longlong, ctypes.c_int
+    dims = (LL * 3)(4, 5, 6)
+    norms = (I * 2)(0, 1)
+    out = ctypes.c_size_t(0)
+    assert lib.mlproj_multilevel_workspace_bytes(3, dims, ctypes.byref(out)) == 0 and out.value % 256 == 0
+    assert lib.mlproj_multilevel_workspace_bytes(1, dims, ctypes.byref(out)) == -2
+    assert lib.mlproj_multilevel_workspace_bytes(9, dims, ctypes.byref(out)) == -2
+    assert lib.mlproj_multilevel_workspace_bytes(3, None, ctypes.byref(out)) == -1
+    assert lib.mlproj_multilevel_workspace_bytes(3, dims, None) == -1
+    assert lib.mlproj_multilevel_workspace_bytes(3, (LL * 3)(4, 0, 6), ctypes.byref(out)) == -2
+    assert lib.mlproj_multilevel_workspace_bytes(3, (LL * 3)(1 << 20, 1 << 20, 1 << 20), ctypes.byref(out)) == -3
+    ml = lib.multilevel_proj
+    assert ml(None, FAKE, 3, dims, norms, F(1), FAKE, big, None, None, None) == -1
+    assert ml(FAKE, FAKE, 3, dims, None, F(1), FAKE, big, None, None, None) == -1
+    assert ml(FAKE, FAKE, 3, dims, (I * 2)(0, 7), F(1), FAKE, big, None, None, None) == -6
+    assert ml(FAKE, FAKE, 3, dims, norms, F(-1), FAKE, big, None, None, None) == -4
+    assert ml(FAKE, FAKE, 3, dims, norms, F(1), FAKE, 64, None, None, None) == -5
