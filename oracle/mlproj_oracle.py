@@ -132,7 +132,7 @@ def project_l2_ball(y, r, norm=None):
 # Alg. 2 / 3 / 4: bi-level projections BP^{1,q}_eta
 # --------------------------------------------------------------------------
 def _out_and_columns(Y, columns):
-    """Output buffer and the list of columns step 3 visits.  With `columns`
+    """Output buffer and the list of columns the per-column map visits.  With `columns`
     given (a sample of a huge input) the unvisited columns stay NaN."""
     if columns is None:
         return np.empty_like(Y), range(Y.shape[1])
@@ -143,11 +143,11 @@ def bilevel_l1inf(Y, eta, columns=None):
     """BP^{1,inf}_eta(Y), Eq. 13 / Alg. 2.  Returns dict(X, v, u, tau)."""
     Y = np.asarray(Y)
     assert Y.dtype == np.float32 and Y.ndim == 2
-    v = column_norms(Y, "inf")                         # step 1
-    u64, tau = project_l1_ball_nonneg(v, eta)          # step 2
+    v = column_norms(Y, "inf")                         # aggregate
+    u64, tau = project_l1_ball_nonneg(v, eta)          # u = P^1_eta(v)
     u = u64.astype(np.float32)
     X, cols = _out_and_columns(Y, columns)
-    for j in cols:                                     # step 3, column by column
+    for j in cols:                                     # x_j = P^inf_{u_j}(y_j), column by column
         X[:, j] = project_linf_ball(Y[:, j], u[j])
     return {"X": X, "v": v, "u": u, "tau": tau}
 
@@ -168,7 +168,7 @@ def bilevel_l11(Y, eta, columns=None):
     """BP^{1,1}_eta(Y), Eq. 14 / Alg. 3.
 
     Returns dict(X, v, u, tau, tau_col); tau_col[j] is the inner threshold of
-    column j.  `columns` (optional index list) restricts step 3 to those
+    column j.  `columns` (optional index list) restricts the per-column map to those
     columns; the others are left as NaN in X (used to sample huge inputs).
     """
     Y = np.asarray(Y)

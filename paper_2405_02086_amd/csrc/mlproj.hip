@@ -1,18 +1,21 @@
-// mlproj: bi-level / tri-level projection onto the l_{1,q} ball for gfx950 (MI355X).
+// mlproj: bi-level / tri-level / multi-level projection onto the l_{1,q} ball for gfx950 (MI355X).
 // Method: Perez & Barlaud, "Multi-level projection with exponential parallel speedup",
-// arXiv 2405.02086 -- Sec. 3 (Eq. 5-9, Alg. 1), Sec. 4 (Alg. 2-4), Sec. 5.1 (Alg. 5) and the
+// arXiv 2405.02086 -- Sec. 3 (Eq. 5-9, Alg. 1), Sec. 4 (Alg. 2-4), Sec. 5 (Alg. 5-6) and the
 // iterative forms in the appendix.  The paper describes CPU code only; the kernels below are
 // an independent design for a 256-CU, 64-lane-wavefront, HBM-bound machine.
 //
 // One bi-level call is a chain of kernels on the caller's stream; nothing returns to the host:
 //   colagg    Y -> per-(column tile, row group) partial aggregates        (reads Y once)
-//   colreduce partials -> v_j = ||y_j||_q                                  (tiny)
-//   search    v -> tau, the l1-ball threshold (one workgroup)              (tiny)
+//   reduce    partials -> v_j = ||y_j||_q                                  (tiny)
+//   search    v -> tau, the l1-ball threshold; run redundantly at the head of colmap when
+//             there are at most 4096 groups, a kernel of its own otherwise      (tiny)
 //   [sweep/update]  l1,1 only: per-column inner thresholds, one read of Y per iteration
 //   colmap    Y, v, tau -> X                                  (reads Y again, writes X once)
 // Workgroups never wait for one another inside a kernel: on this GPU a device-scope fence
-// costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only.
-// The tri-level form uses the same chain with groups that are contiguous slabs.
+// costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only
+// (the one exception, the search over more than 16384 groups, meets at a barrier made of
+// device-scope atomics alone).  The tri-level form uses the same chain with groups that are
+// contiguous slabs; the generic multi-level form works on contiguous fibres, level by level.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
