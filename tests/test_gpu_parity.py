@@ -392,3 +392,47 @@ def test_workload_tensor_256_multilevel(mp, norms):
     w, Y = workloads.make("tensor_256x256x256")
     eta = float(np.float32(w.eta_frac * nested_norm(Y, norms)))
     check_multi(run_multi(mp, Y, norms, eta), orc.multilevel(Y, norms, eta))
+
+
+# ------------------------------------------------------------------ repeatability, concurrency
+def test_results_repeat_bit_for_bit(mp):
+    """Fixed reduction orders everywhere: every repetition gives the same bits, including the
+    grid-wide search (m > 16384) whose workgroups meet at a barrier."""
+    rng = np.random.default_rng(41)
+    dev = torch.device("cuda:0")
+    for q, shape in (("inf", (64, 50000)), (1, (512, 1536)), (2, (1500, 700)), ("inf", (1500, 700))):
+        Y = rng.standard_normal(shape).astype(np.float32)
+        eta = eta_for(Y, q, 0.15)
+        Yd = torch.from_numpy(Y).to(dev)
+        ws = mp.Workspace.for_call(QNAME[q], *shape, device=dev)
+        fn = getattr(mp, "bilevel_proj_" + QNAME[q])
+        first, tau0 = None, None
+        for rep in range(40):
+            X = fn(Yd, eta, workspace=ws)
+            torch.cuda.synchronize()
+            tau = ws.result()["tau"]
+            if first is None:
+                first, tau0 = X.clone(), tau
+            else:
+                assert tau == tau0 and torch.equal(X, first), (q, shape, rep)
+
+
+def test_two_streams_two_workspaces(mp):
+    rng = np.random.default_rng(42)
+    dev = torch.device("cuda:0")
+    jobs = []
+    for q, shape in (("inf", (2048, 1024)), (2, (1024, 2048)), (1, (600, 900)), ("inf", (16, 30000))):
+        Y = rng.standard_normal(shape).astype(np.float32)
+        eta = eta_for(Y, q, 0.3)
+        jobs.append((q, Y, eta, torch.from_numpy(Y).to(dev), mp.Workspace.for_call(QNAME[q], *shape, device=dev),
+                     torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(5):
+        outs = []
+        for q, Y, eta, Yd, ws, st in jobs:
+            with torch.cuda.stream(st):
+                outs.append(getattr(mp, "bilevel_proj_" + QNAME[q])(Yd, eta, workspace=ws, stream=st))
+    torch.cuda.synchronize()
+    for (q, Y, eta, Yd, ws, st), X in zip(jobs, outs):
+        np.testing.assert_allclose(X.cpu().numpy(), orc.bilevel(Y, eta, q)["X"], rtol=RTOL, atol=ATOL)
