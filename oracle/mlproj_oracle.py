@@ -25,7 +25,7 @@ import numpy as np
 __all__ = [
     "column_norms", "norm_l1q", "project_l1_ball_nonneg", "project_l1_ball",
     "project_linf_ball", "project_l2_ball", "bilevel_l1inf", "bilevel_l11",
-    "bilevel_l12", "trilevel_l1infinf", "bilevel", "multilevel",
+    "bilevel_l12", "trilevel_l1infinf", "bilevel", "multilevel", "project_outer",
 ]
 
 
@@ -128,8 +128,22 @@ def project_l2_ball(y, r, norm=None):
     return y * r / nrm
 
 
+def project_outer(v, eta, p=1):
+    """u = P^p_eta(v) for the non-negative aggregate vector v (Eq. 6-7), p in {1, 2, "inf"}:
+    the l1-ball projection above, the rescale onto the l2 ball, or the clip to [0, eta].
+    Returns (u, tau); tau is the l1 threshold and 0 for the other two norms."""
+    v = np.asarray(v, dtype=np.float64)
+    if p == 1:
+        return project_l1_ball_nonneg(v, eta)
+    if p == 2:
+        return project_l2_ball(v, eta), 0.0
+    if p == "inf":
+        return np.minimum(v, eta), 0.0
+    raise ValueError("outer norm must be 1, 2 or 'inf'")
+
+
 # --------------------------------------------------------------------------
-# Alg. 2 / 3 / 4: bi-level projections BP^{1,q}_eta
+# Alg. 1 with p in {1, 2, inf}; Alg. 2 / 3 / 4: bi-level projections BP^{p,q}_eta
 # --------------------------------------------------------------------------
 def _out_and_columns(Y, columns):
     """Output buffer and the list of columns the per-column map visits.  With `columns`
@@ -139,12 +153,12 @@ def _out_and_columns(Y, columns):
     return np.full_like(Y, np.nan), list(columns)
 
 
-def bilevel_l1inf(Y, eta, columns=None):
-    """BP^{1,inf}_eta(Y), Eq. 13 / Alg. 2.  Returns dict(X, v, u, tau)."""
+def bilevel_l1inf(Y, eta, columns=None, p=1):
+    """BP^{p,inf}_eta(Y); p = 1 is Eq. 13 / Alg. 2.  Returns dict(X, v, u, tau)."""
     Y = np.asarray(Y)
     assert Y.dtype == np.float32 and Y.ndim == 2
     v = column_norms(Y, "inf")                         # aggregate
-    u64, tau = project_l1_ball_nonneg(v, eta)          # u = P^1_eta(v)
+    u64, tau = project_outer(v, eta, p)                # u = P^p_eta(v)
     u = u64.astype(np.float32)
     X, cols = _out_and_columns(Y, columns)
     for j in cols:                                     # x_j = P^inf_{u_j}(y_j), column by column
@@ -152,20 +166,20 @@ def bilevel_l1inf(Y, eta, columns=None):
     return {"X": X, "v": v, "u": u, "tau": tau}
 
 
-def bilevel_l12(Y, eta, columns=None):
-    """BP^{1,2}_eta(Y), Eq. 15 / Alg. 4.  Returns dict(X, v, u, tau) (v, u fp64)."""
+def bilevel_l12(Y, eta, columns=None, p=1):
+    """BP^{p,2}_eta(Y); p = 1 is Eq. 15 / Alg. 4.  Returns dict(X, v, u, tau) (v, u fp64)."""
     Y = np.asarray(Y)
     assert Y.dtype == np.float32 and Y.ndim == 2
     v = column_norms(Y, 2)
-    u, tau = project_l1_ball_nonneg(v, eta)
+    u, tau = project_outer(v, eta, p)
     X, cols = _out_and_columns(Y, columns)
     for j in cols:
         X[:, j] = project_l2_ball(Y[:, j], u[j], norm=v[j]).astype(np.float32)
     return {"X": X, "v": v, "u": u, "tau": tau}
 
 
-def bilevel_l11(Y, eta, columns=None):
-    """BP^{1,1}_eta(Y), Eq. 14 / Alg. 3.
+def bilevel_l11(Y, eta, columns=None, p=1):
+    """BP^{p,1}_eta(Y); p = 1 is Eq. 14 / Alg. 3.
 
     Returns dict(X, v, u, tau, tau_col); tau_col[j] is the inner threshold of
     column j.  `columns` (optional index list) restricts the per-column map to those
@@ -174,7 +188,7 @@ def bilevel_l11(Y, eta, columns=None):
     Y = np.asarray(Y)
     assert Y.dtype == np.float32 and Y.ndim == 2
     v = column_norms(Y, 1)
-    u, tau = project_l1_ball_nonneg(v, eta)
+    u, tau = project_outer(v, eta, p)
     X, cols = _out_and_columns(Y, columns)
     tau_col = np.full(Y.shape[1], np.nan)
     for j in cols:
@@ -184,8 +198,9 @@ def bilevel_l11(Y, eta, columns=None):
     return {"X": X, "v": v, "u": u, "tau": tau, "tau_col": tau_col}
 
 
-def bilevel(Y, eta, q, columns=None):
-    return {"inf": bilevel_l1inf, 1: bilevel_l11, 2: bilevel_l12}[q](Y, eta, columns)
+def bilevel(Y, eta, q, columns=None, p=1):
+    """BP^{p,q}_eta(Y), Alg. 1, for p, q in {1, 2, "inf"}."""
+    return {"inf": bilevel_l1inf, 1: bilevel_l11, 2: bilevel_l12}[q](Y, eta, columns, p)
 
 
 # --------------------------------------------------------------------------
@@ -250,8 +265,8 @@ def _project_fibre(y, r, q):
     return project_l1_ball(y, r)[0]
 
 
-def multilevel(Y, norms, eta):
-    """MP^nu_eta of a C-order tensor with single-axis norms, outermost norm l1.
+def multilevel(Y, norms, eta, p=1):
+    """MP^nu_eta of a C-order tensor with single-axis norms, outermost norm p (l1 by default).
 
     `norms` lists the inner norms innermost first: norms[0] aggregates the LAST axis, norms[1]
     the one before, ... down to axis 1; axis 0 carries the groups whose aggregate vector is
@@ -271,7 +286,7 @@ def multilevel(Y, norms, eta):
     for q in norms:                                   # aggregation, innermost axis first
         V.append(_fibre_norms(V[-1], q))
     w = V[-1]
-    u, tau = project_l1_ball_nonneg(w, eta)
+    u, tau = project_outer(w, eta, p)
     U = [None] * len(V)
     U[-1] = u
     for k in range(len(norms), 0, -1):                # back down: level k radii -> level k-1

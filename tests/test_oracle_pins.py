@@ -380,3 +380,45 @@ def test_multilevel_every_level_is_a_projection(norms, frac):
         assert got.sum() == pytest.approx(eta, rel=1e-5)
     else:
         assert np.array_equal(out["X"], Y)
+
+
+# ---------------------------------------------------------------- other outer norms (Alg. 1, general p)
+@pytest.mark.parametrize("p", [2, "inf"])
+@pytest.mark.parametrize("q", QS)
+@pytest.mark.parametrize("frac", [0.05, 0.5, 1.2])
+def test_bilevel_pq_is_the_composition_of_two_projections(p, q, frac):
+    """Alg. 1 for a general outer norm: u = P^p_eta(v_q), then x_j = P^q_{u_j}(y_j)."""
+    Y = rand_matrix(23, 14)
+    v = lq(Y, q, axis=0)
+    eta = frac * float(lq(v, p))
+    out = orc.bilevel(Y, eta, q, p=p)
+    assert_is_projection(v, out["u"], eta, p, tol=3e-7 if q == "inf" else 1e-9)
+    for j in range(Y.shape[1]):
+        assert_is_projection(Y[:, j], out["X"][:, j], float(out["u"][j]), q, tol=3e-7)
+    got = lq(lq(out["X"], q, axis=0), p)
+    if frac < 1:
+        assert got == pytest.approx(eta, rel=1e-5)
+    else:
+        assert np.array_equal(out["X"], Y)
+
+
+def test_outer_projection_closed_forms():
+    v = np.array([3.0, 4.0, 0.0])
+    u, tau = orc.project_outer(v, 2.5, 2)
+    np.testing.assert_allclose(u, [1.5, 2.0, 0.0], rtol=1e-15)        # ||v||_2 = 5 -> scale 1/2
+    u, tau = orc.project_outer(v, 3.5, "inf")
+    assert u.tolist() == [3.0, 3.5, 0.0] and tau == 0.0
+    u, _ = orc.project_outer(v, 6.0, 2)
+    assert np.array_equal(u, v)
+
+
+@pytest.mark.parametrize("p", [2, "inf"])
+def test_multilevel_outer_norm(p):
+    Y = RNG.standard_normal((6, 3, 5)).astype(np.float32)
+    norms = [1, "inf"]
+    w = lq(lq(Y, 1, axis=-1), "inf", axis=-1)
+    eta = 0.4 * float(lq(w, p))
+    out = orc.multilevel(Y, norms, eta, p=p)
+    assert_is_projection(w, out["u"], eta, p)
+    got = lq(lq(lq(out["X"], 1, axis=-1), "inf", axis=-1), p)
+    assert got == pytest.approx(eta, rel=1e-5)
