@@ -70,17 +70,27 @@ typedef enum mlproj_norm {
   MLPROJ_NORM_L2 = 2
 } mlproj_norm;
 
-/* Record left at offset 0 of the workspace by every projection / norm call. */
+/* Outer norm p of the generic BP^{p,q} / MP^nu entry points. */
+typedef enum mlproj_outer {
+  MLPROJ_OUTER_L1 = 0,
+  MLPROJ_OUTER_L2 = 1,
+  MLPROJ_OUTER_LINF = 2
+} mlproj_outer;
+
+/* Record left at offset 0 of the workspace by every projection / norm call.
+ * The outer projection acts on every aggregate as u_j = min(cap, scale * max(v_j - tau, 0)). */
 typedef struct mlproj_result {
-  double tau;            /* threshold of u = P^1_eta(v): u_j = max(v_j - tau, 0); 0 inside the ball  */
-  double norm;           /* ||Y||_{1,q} = sum_j v_j (fp64)                                            */
+  double tau;            /* p = 1: threshold of u = P^1_eta(v); 0 inside the ball and for p = 2, inf */
+  double norm;           /* ||Y||_{p,q} of the input (fp64); mlproj_norm_l1q: sum_j v_j              */
   double vmax;           /* max_j v_j                                                                 */
+  double scale;          /* p = 2: eta / ||v||_2 when outside the ball; 1 otherwise                   */
+  double cap;            /* p = inf: eta when outside the ball; +inf otherwise                        */
   uint32_t n_active;     /* number of groups with u_j > 0                                             */
   uint32_t inside_ball;  /* 1 when ||Y||_{1,q} <= eta (X = Y)                                         */
   uint32_t search_iters; /* fixed-point iterations the search for tau took                            */
   uint32_t inner_sweeps; /* l1,1 only: passes over Y the per-column threshold searches took           */
   uint32_t inner_pending;/* l1,1 only: columns whose inner search had not converged (0 = exact)       */
-  uint32_t reserved[7];
+  uint32_t reserved[3];
 } mlproj_result;
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -132,6 +142,17 @@ int bilevel_proj_l12(const float* Y, float* X, long long n, long long m, float e
                      void* workspace, size_t workspace_bytes,
                      float* v_out, float* u_out, void* stream);
 
+/* BP^{p,q}_eta for a general outer norm (Alg. 1; Sec. 3 names the l1, l2 and l_inf balls as
+ * outer projections with known linear-time algorithms): v_j = ||y_j||_q with q given by
+ * `variant` (MLPROJ_L1INF, MLPROJ_L11, MLPROJ_L12), u = P^p_eta(v) with p = outer_norm
+ * (a mlproj_outer: soft threshold, rescale by eta/||v||_2, or cap at eta), x_j = P^q_{u_j}(y_j).
+ * outer_norm = MLPROJ_OUTER_L1 is exactly bilevel_proj_l1inf / _l11 / _l12.                   */
+int bilevel_proj_pq(int outer_norm, int variant, const float* Y /* device, n*m */,
+                    float* X /* device, n*m */, long long n, long long m, float eta,
+                    void* workspace /* device */, size_t workspace_bytes,
+                    float* v_out /* device, m; may be NULL */,
+                    float* u_out /* device, m; may be NULL */, void* stream);
+
 /* The two halves of a bi-level call, for callers that want the radii before (or without)
  * writing X.  bilevel_radii computes the aggregate v and u = P^1_eta(v) of Alg. 1 (for
  * MLPROJ_L11 also the per-column thresholds Alg. 3 needs) and leaves the outcome in the
@@ -176,6 +197,11 @@ int multilevel_proj(const float* Y /* device */, float* X /* device, same size *
                     float eta, void* workspace /* device */, size_t workspace_bytes,
                     float* v_out /* device, dims[0]; may be NULL */,
                     float* u_out /* device, dims[0]; may be NULL */, void* stream);
+
+/* multilevel_proj with the outermost norm p = outer_norm (a mlproj_outer) instead of l1. */
+int multilevel_proj_p(int outer_norm, const float* Y, float* X, int ndim, const long long* dims,
+                      const int* norms, float eta, void* workspace, size_t workspace_bytes,
+                      float* v_out, float* u_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -84,6 +84,11 @@ def lib():
     L.multilevel_proj.restype = c_i
     L.multilevel_proj.argtypes = [c_vp, c_vp, c_i, ctypes.POINTER(c_ll), ctypes.POINTER(c_i), c_f, c_vp, c_sz,
                                   c_vp, c_vp, c_vp]
+    L.multilevel_proj_p.restype = c_i
+    L.multilevel_proj_p.argtypes = [c_i, c_vp, c_vp, c_i, ctypes.POINTER(c_ll), ctypes.POINTER(c_i), c_f, c_vp,
+                                    c_sz, c_vp, c_vp, c_vp]
+    L.bilevel_proj_pq.restype = c_i
+    L.bilevel_proj_pq.argtypes = [c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     L.trilevel_proj_l1infinf.restype = c_i
     L.trilevel_proj_l1infinf.argtypes = [c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     _lib = L
@@ -94,7 +99,7 @@ EXPORTS = (
     "mlproj_version", "mlproj_status_string", "mlproj_workspace_bytes", "mlproj_trace_begin", "mlproj_trace_end",
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
-    "mlproj_multilevel_workspace_bytes", "multilevel_proj",
+    "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
 )
 
 
@@ -137,8 +142,8 @@ class Workspace:
     def result(self):
         """Synchronise and decode the mlproj_result record at the head of the workspace."""
         raw = bytes(self.buf[:64].cpu().numpy().tobytes())
-        tau, norm, vmax, n_active, inside, iters, sweeps, pending = struct.unpack_from("<dddIIIII", raw)
-        return {"tau": tau, "norm": norm, "vmax": vmax, "n_active": n_active,
+        tau, norm, vmax, scale, cap, n_active, inside, iters, sweeps, pending = struct.unpack_from("<dddddIIIII", raw)
+        return {"tau": tau, "norm": norm, "vmax": vmax, "scale": scale, "cap": cap, "n_active": n_active,
                 "inside_ball": bool(inside), "search_iters": iters,
                 "inner_sweeps": sweeps, "inner_pending": pending}
 
@@ -204,6 +209,24 @@ def trilevel_proj_l1infinf(Y, eta, X=None, workspace=None, v_out=None, u_out=Non
     return X
 
 
+OUTER_L1, OUTER_L2, OUTER_LINF = 0, 1, 2
+_OUTERS = {1: OUTER_L1, 2: OUTER_L2, "inf": OUTER_LINF}
+
+
+def bilevel_proj_pq(p, q, Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
+    """BP^{p,q}: p in {1, 2, "inf"} (outer), q in {"inf", 1, 2} (per column)."""
+    assert Y.dim() == 2
+    n, m = Y.shape
+    X = _prep(Y, X)
+    variant = {"inf": L1INF, 1: L11, 2: L12}[q]
+    if workspace is None:
+        workspace = Workspace.for_call(variant, n, m, device=Y.device, stream=stream)
+    st = lib().bilevel_proj_pq(_OUTERS[p], variant, _ptr(Y), _ptr(X), n, m, ctypes.c_float(eta),
+                               _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out), _stream(stream))
+    _check(st, "bilevel_proj_pq")
+    return X
+
+
 NORM_INF, NORM_L1, NORM_L2 = 0, 1, 2
 _NORMS = {"inf": NORM_INF, 1: NORM_L1, 2: NORM_L2}
 
@@ -216,8 +239,9 @@ def multilevel_workspace_bytes(shape):
     return out.value
 
 
-def multilevel_proj(Y, norms, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
-    """norms: inner norms, innermost (last axis) first, each "inf", 1 or 2; groups on axis 0."""
+def multilevel_proj(Y, norms, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None, p=1):
+    """norms: inner norms, innermost (last axis) first, each "inf", 1 or 2; groups on axis 0;
+    p: outermost norm (1, 2 or "inf")."""
     X = _prep(Y, X)
     shape = tuple(Y.shape)
     assert len(norms) == len(shape) - 1
@@ -225,8 +249,12 @@ def multilevel_proj(Y, norms, eta, X=None, workspace=None, v_out=None, u_out=Non
         workspace = Workspace(multilevel_workspace_bytes(shape), device=Y.device)
     dims = (ctypes.c_longlong * len(shape))(*shape)
     nrm = (ctypes.c_int * len(norms))(*[_NORMS[q] for q in norms])
-    st = lib().multilevel_proj(_ptr(Y), _ptr(X), len(shape), dims, nrm, ctypes.c_float(eta),
-                               _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out), _stream(stream))
+    if p == 1:
+        st = lib().multilevel_proj(_ptr(Y), _ptr(X), len(shape), dims, nrm, ctypes.c_float(eta),
+                                   _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out), _stream(stream))
+    else:
+        st = lib().multilevel_proj_p(_OUTERS[p], _ptr(Y), _ptr(X), len(shape), dims, nrm, ctypes.c_float(eta),
+                                     _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out), _stream(stream))
     _check(st, "multilevel_proj")
     return X
 

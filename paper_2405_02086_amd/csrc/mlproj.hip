@@ -443,13 +443,27 @@ __global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ pa
 // get the same bits, which lets the map kernels run it redundantly instead of waiting for a
 // separate one-workgroup kernel.
 struct SearchOut {
-  double tau, total, vmax;
+  double tau, scale, cap;   // u_j = min(cap, scale * max(v_j - tau, 0))
+  double total, vmax, norm; // sum v, max v, ||v||_p
   unsigned active, iters, inside;
 };
 
+// How the outer projection u = P^p_eta(v) acts on one aggregate (Eq. 6-7; Sec. 3 names the
+// l1, l2 and l_inf balls as available outer projections): shrink by tau (p = 1), rescale
+// (p = 2) or cap at eta (p = inf).  For p = 1 scale is 1 and cap is +inf, which leaves
+// max(v - tau, 0) bit for bit.
+struct Top {
+  double tau, scale, cap;
+};
+__device__ __forceinline__ double radius(double v, const Top& t) {
+  return fmin(t.cap, t.scale * fmax(v - t.tau, 0.0));
+}
+__device__ __forceinline__ Top top_of(const SearchOut& o) { return Top{o.tau, o.scale, o.cap}; }
+__device__ __forceinline__ Top top_of(const mlproj_result* r) { return Top{r->tau, r->scale, r->cap}; }
+
 template <int NT>
 __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, long long ngroups,
-                                                  double eta, int mode,
+                                                  double eta, int mode, int outer,
                                                   PairScratch<NT / WAVE>& s) {
   const int tid = threadIdx.x;
   double vr[SEARCH_CACHE];
@@ -470,12 +484,38 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
   block_sum_max(a, mx, s);
   o.total = a;
   o.vmax = mx;
+  o.norm = a;
   o.tau = 0.0;
+  o.scale = 1.0;
+  o.cap = HUGE_VAL;
   o.active = 0;
   o.iters = 0;
   o.inside = 0;
   if (mode == MODE_NORM) {
     // norm only: nothing to search
+  } else if (outer != MLPROJ_OUTER_L1) {
+    // l2 ball: rescale by eta / ||v||_2; l_inf ball: cap at eta.  No iteration.
+    double sq = 0.0, dummy = 0.0;
+    unsigned c = 0;
+#pragma unroll
+    for (int k = 0; k < SEARCH_CACHE; ++k) { sq = fma(vr[k], vr[k], sq); c += vr[k] > 0.0 ? 1u : 0u; }
+    for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT) {
+      const double x = v[i];
+      sq = fma(x, x, sq);
+      c += x > 0.0 ? 1u : 0u;
+    }
+    block_sum_count(sq, c, s);
+    (void)dummy;
+    if (outer == MLPROJ_OUTER_L2) {
+      o.norm = sqrt(sq);
+      o.inside = o.norm <= eta ? 1u : 0u;
+      if (!o.inside) o.scale = eta / o.norm;
+    } else {
+      o.norm = o.vmax;
+      o.inside = o.vmax <= eta ? 1u : 0u;
+      if (!o.inside) o.cap = eta;
+    }
+    o.active = eta == 0.0 ? 0u : c;
   } else if (eta == 0.0) {
     o.tau = o.vmax;  // nothing exceeds vmax: every u_j is 0
   } else if (o.total <= eta) {
@@ -522,7 +562,9 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
                                              double* __restrict__ norm_out) {
   mlproj_result* r = ws.res;
   r->tau = o.tau;
-  r->norm = o.total;
+  r->scale = o.scale;
+  r->cap = o.cap;
+  r->norm = o.norm;
   r->vmax = o.vmax;
   r->n_active = o.active;
   r->inside_ball = o.inside;
@@ -534,18 +576,20 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
 
 // radii / u_out (optional): also write u_j = max(v_j - tau, 0) for every group.
 __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
-                                                     int mode, double* __restrict__ norm_out,
+                                                     int mode, int outer,
+                                                     double* __restrict__ norm_out,
                                                      int only_as_fallback,
                                                      double* __restrict__ radii,
                                                      float* __restrict__ u_out) {
   __shared__ PairScratch<SWAVES> s;
   if (only_as_fallback && ws.flags[1] == 0u) return;
-  const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, s);
+  const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, outer, s);
   if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
   if (threadIdx.x == 0) write_result(ws, o, norm_out);
   if (radii) {
+    const Top top = top_of(o);
     for (long long i = threadIdx.x; i < ngroups; i += SWG) {
-      const double u = fmax(ws.v[i] - o.tau, 0.0);
+      const double u = radius(ws.v[i], top);
       radii[i] = u;
       if (u_out) u_out[i] = (float)u;
     }
@@ -630,7 +674,10 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
   o.total = tid < nwg ? get_f64(&ws.coop_d[tid]) : 0.0;
   o.vmax = tid < nwg ? get_f64(&ws.coop_m[tid]) : 0.0;
   block_sum_max(o.total, o.vmax, s);
+  o.norm = o.total;
   o.tau = 0.0;
+  o.scale = 1.0;
+  o.cap = HUGE_VAL;
   o.active = 0;
   o.iters = 0;
   o.inside = 0;
@@ -691,7 +738,8 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
 template <int Q, int VEC, bool XVEC>
 __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, long long n,
                                                     long long m, Geometry g, Ws ws,
-                                                    float* __restrict__ u_out, double fused_eta) {
+                                                    float* __restrict__ u_out, double fused_eta,
+                                                    int outer) {
   constexpr int TILE_W = WAVE * VEC;
   constexpr int U = MAP_UNROLL;
   __shared__ PairScratch<WAVES> bs;
@@ -718,15 +766,15 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
   // The first block is requested before tau is known, so its latency hides the search.
   if (col_ok && b >= 0) load_block(b, x);
 
-  double tau;
+  Top top;
   bool inside;
   if (fused_eta >= 0.0) {
-    const SearchOut o = search_block<WG>(ws.v, m, fused_eta, MODE_PROJECT, bs);
-    tau = o.tau;
+    const SearchOut o = search_block<WG>(ws.v, m, fused_eta, MODE_PROJECT, outer, bs);
+    top = top_of(o);
     inside = o.inside != 0u;
     if (blockIdx.x == 0 && threadIdx.x == 0) write_result(ws, o, nullptr);
   } else {
-    tau = ws.res->tau;
+    top = top_of(ws.res);
     inside = ws.res->inside_ball != 0u;
   }
   if (!col_ok) return;
@@ -736,7 +784,7 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
 #pragma unroll
   for (int k = 0; k < VEC; ++k) {
     const double vj = ws.v[col0 + k];
-    const double uj = fmax(vj - tau, 0.0);
+    const double uj = radius(vj, top);
     uf[k] = (float)uj;
     if constexpr (Q == Q2) par[k] = vj > 0.0 ? uj / vj : 0.0;
     else if constexpr (Q == Q1) par[k] = inside ? 0.0 : (uj > 0.0 ? ws.tauj[col0 + k] : HUGE_VAL);
@@ -883,9 +931,8 @@ __global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, 
   if (res->inside_ball != 0u || res->n_active == 0u) return;
   const long long j = (long long)blockIdx.x * WG + threadIdx.x;
   if (j >= m) return;
-  const double tau = res->tau;
   const double vj = ws.v[j];
-  const double uj = fmax(vj - tau, 0.0);
+  const double uj = radius(vj, top_of(res));
   double tj = HUGE_VAL;
   if (uj > 0.0) {
     const double c = (uj / vj) * 0.7978845608028654;  // sqrt(2/pi)
@@ -897,7 +944,7 @@ __global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, 
       z += (h - c) / tail;
     }
     const double sigma = (vj / (double)n) * 1.2533141373155001;   // sqrt(pi/2)
-    tj = fmax(sigma * z, tau / (double)n);  // never below the all-active bound (v_j - u_j)/n
+    tj = fmax(sigma * z, (vj - uj) / (double)n);  // never below the all-active bound
   }
   ws.tauj[j] = tj;
   ws.kprev[j] = 0xffffffffu;
@@ -940,14 +987,15 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
       K += sm_cnt[w * cols + c_local];
       K2 += sm_cnt2[w * cols + c_local];
     }
-    const double tau = res->tau;
-    const double uj = fmax(ws.v[j] - tau, 0.0);
+    const double vj = ws.v[j];
+    const double uj = radius(vj, top_of(res));
+    const double floor_t = (vj - uj) / (double)n;  // every entry active: a lower bound on the root
     if (uj > 0.0) {
       double tj = ws.tauj[j];
       const unsigned kp = ws.kprev[j];
       if (K == 0u) {
         // the guess overshot every entry: restart from the all-active lower bound
-        tj = tau / (double)n;
+        tj = floor_t;
         K = 0xffffffffu;
         open = 1u;
       } else if (sweep == 0) {
@@ -957,7 +1005,7 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
         const double rho = (double)(K - K2) / (tj * L11_WINDOW);
         const double disc = (double)K * (double)K - 2.0 * rho * r;
         const double d = (rho > 0.0 && disc > 0.0) ? 2.0 * r / ((double)K + sqrt(disc)) : r / (double)K;
-        tj = fmax(tj + d, tau / (double)n);
+        tj = fmax(tj + d, floor_t);
         K = 0xffffffffu;  // not a Newton point: the next count comparison must not conclude
         open = 1u;
       } else {
@@ -1030,15 +1078,15 @@ __global__ __launch_bounds__(WG) void slabmap_kernel(const float* Y, float* X, l
   const long long c = blockIdx.x % g.groups;
   const long long lo = c * g.span;
   const long long hi = (lo + g.span < len) ? lo + g.span : len;
-  double tau;
+  Top top;
   if (fused_eta >= 0.0) {
-    const SearchOut o = search_block<WG>(ws.v, d0, fused_eta, MODE_PROJECT, bs);
-    tau = o.tau;
+    const SearchOut o = search_block<WG>(ws.v, d0, fused_eta, MODE_PROJECT, MLPROJ_OUTER_L1, bs);
+    top = top_of(o);
     if (blockIdx.x == 0 && threadIdx.x == 0) write_result(ws, o, nullptr);
   } else {
-    tau = ws.res->tau;
+    top = top_of(ws.res);
   }
-  const float u = (float)fmax(ws.v[a] - tau, 0.0);
+  const float u = (float)radius(ws.v[a], top);
   if (u_out && c == 0 && threadIdx.x == 0) u_out[a] = u;
   const float* p = Y + a * len;
   float* q = X + a * len;
@@ -1206,7 +1254,7 @@ __global__ __launch_bounds__(WG) void top_radii_kernel(Ws ws, long long d0, doub
                                                        float* __restrict__ u_out) {
   const long long a = (long long)blockIdx.x * WG + threadIdx.x;
   if (a >= d0) return;
-  const double u = fmax(ws.v[a] - ws.res->tau, 0.0);
+  const double u = radius(ws.v[a], top_of(ws.res));
   R[a] = u;
   if (u_out) u_out[a] = (float)u;
 }
@@ -1464,17 +1512,18 @@ static inline void mark(hipStream_t stream) {
 // The stand-alone search: one workgroup when v fits its registers, the grid-wide form beyond
 // that, followed by the one-workgroup kernel as a fallback that returns at once unless the
 // grid-wide one gave up.
-static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, double* norm_out,
-                          hipStream_t stream) {
+static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, int outer,
+                          double* norm_out, hipStream_t stream) {
   int only_as_fallback = 0;
-  if (ngroups > (long long)SWG * SEARCH_CACHE) {
+  // (the l2 and l_inf outer projections need no iteration: one workgroup reads v once)
+  if (ngroups > (long long)SWG * SEARCH_CACHE && (outer == MLPROJ_OUTER_L1 || mode == MODE_NORM)) {
     long long nwg = cdiv(ngroups, (long long)SWG * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
     hipLaunchKernelGGL(search_wide_kernel, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
     only_as_fallback = 1;
   }
-  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out, only_as_fallback,
-                     (double*)nullptr, (float*)nullptr);
+  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
+                     only_as_fallback, (double*)nullptr, (float*)nullptr);
 }
 
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
@@ -1482,7 +1531,8 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
 template <int Q>
 static int run_bilevel(const float* Y, float* X, long long n, long long m, float eta,
                        void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
-                       void* stream_, int mode, double* norm_out, int stages) {
+                       void* stream_, int mode, double* norm_out, int stages, int outer) {
+  if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
   const bool need_x = mode == MODE_PROJECT && (stages & STAGE_APPLY);
   if (!Y || !workspace || (need_x && !X)) return MLPROJ_ERR_NULL_POINTER;
   int st = check_dims(n, m, 1);
@@ -1521,7 +1571,7 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
     hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
     if (!fuse) {
       mark(stream);
-      launch_search(ws, m, (double)eta, mode, norm_out, stream);
+      launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
     }
     if (mode == MODE_NORM) { mark(stream); return launch_status(); }
     if constexpr (Q == Q1) {
@@ -1538,11 +1588,11 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
   if (stages & STAGE_APPLY) {
     mark(stream);
     if (vec == 4 && x_vec)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
+      hipLaunchKernelGGL((colmap_kernel<Q, 4, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta, outer);
     else if (vec == 4)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
+      hipLaunchKernelGGL((colmap_kernel<Q, 4, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta, outer);
     else
-      hipLaunchKernelGGL((colmap_kernel<Q, 1, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta);
+      hipLaunchKernelGGL((colmap_kernel<Q, 1, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta, outer);
   }
   mark(stream);
   return launch_status();
@@ -1654,10 +1704,11 @@ static void by_norm(int norm, F&& f) {
   else f(std::integral_constant<int, Q2>{});
 }
 
-static int run_multilevel(const float* Y, float* X, int ndim, const long long* dims,
+static int run_multilevel(int outer, const float* Y, float* X, int ndim, const long long* dims,
                           const int* norms, float eta, void* workspace, size_t workspace_bytes,
                           float* v_out, float* u_out, void* stream_) {
   if (!Y || !X || !workspace) return MLPROJ_ERR_NULL_POINTER;
+  if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
   MlPlan P;
   int st = ml_plan(ndim, dims, norms, &P);
   if (st != MLPROJ_OK) return st;
@@ -1692,12 +1743,12 @@ static int run_multilevel(const float* Y, float* X, int ndim, const long long* d
   }
   // top: threshold of the l1-ball projection of the length-d0 vector, then its radii
   mark(stream);
-  if (dims[0] <= (long long)SWG * SEARCH_CACHE) {
+  if (dims[0] <= (long long)SWG * SEARCH_CACHE || outer != MLPROJ_OUTER_L1) {
     hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
-                       (double*)nullptr, 0, R[ndim - 1], u_out);
+                       outer, (double*)nullptr, 0, R[ndim - 1], u_out);
   } else {
     hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
-    launch_search(ws, dims[0], (double)eta, MODE_PROJECT, nullptr, stream);
+    launch_search(ws, dims[0], (double)eta, MODE_PROJECT, outer, nullptr, stream);
     hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
                        dims[0], R[ndim - 1], u_out);
   }
@@ -1724,7 +1775,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 203; }
+int mlproj_version(void) { return 300; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -1763,40 +1814,40 @@ int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2
 int mlproj_norm_l1q(const float* Y, long long n, long long m, int q_variant, void* workspace,
                     size_t workspace_bytes, double* norm_out, float* v_out, void* stream) {
   return dispatch_q(q_variant, Y, (float*)nullptr, n, m, 0.f, workspace, workspace_bytes, v_out,
-                    (float*)nullptr, stream, MODE_NORM, norm_out, STAGE_AGGREGATE);
+                    (float*)nullptr, stream, MODE_NORM, norm_out, STAGE_AGGREGATE, (int)MLPROJ_OUTER_L1);
 }
 
 int bilevel_proj_l1inf(const float* Y, float* X, long long n, long long m, float eta,
                        void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
                        void* stream) {
   return run_bilevel<QINF>(Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, stream,
-                           MODE_PROJECT, nullptr, STAGE_ALL);
+                           MODE_PROJECT, nullptr, STAGE_ALL, (int)MLPROJ_OUTER_L1);
 }
 
 int bilevel_proj_l11(const float* Y, float* X, long long n, long long m, float eta,
                      void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
                      void* stream) {
   return run_bilevel<Q1>(Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, stream,
-                         MODE_PROJECT, nullptr, STAGE_ALL);
+                         MODE_PROJECT, nullptr, STAGE_ALL, (int)MLPROJ_OUTER_L1);
 }
 
 int bilevel_proj_l12(const float* Y, float* X, long long n, long long m, float eta,
                      void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
                      void* stream) {
   return run_bilevel<Q2>(Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, stream,
-                         MODE_PROJECT, nullptr, STAGE_ALL);
+                         MODE_PROJECT, nullptr, STAGE_ALL, (int)MLPROJ_OUTER_L1);
 }
 
 int bilevel_radii(int variant, const float* Y, long long n, long long m, float eta,
                   void* workspace, size_t workspace_bytes, float* v_out, void* stream) {
   return dispatch_q(variant, Y, (float*)nullptr, n, m, eta, workspace, workspace_bytes, v_out,
-                    (float*)nullptr, stream, MODE_PROJECT, (double*)nullptr, STAGE_AGGREGATE);
+                    (float*)nullptr, stream, MODE_PROJECT, (double*)nullptr, STAGE_AGGREGATE, (int)MLPROJ_OUTER_L1);
 }
 
 int bilevel_apply(int variant, const float* Y, float* X, long long n, long long m,
                   void* workspace, size_t workspace_bytes, float* u_out, void* stream) {
   return dispatch_q(variant, Y, X, n, m, 0.f, workspace, workspace_bytes, (float*)nullptr, u_out,
-                    stream, MODE_PROJECT, (double*)nullptr, STAGE_APPLY);
+                    stream, MODE_PROJECT, (double*)nullptr, STAGE_APPLY, (int)MLPROJ_OUTER_L1);
 }
 
 int mlproj_multilevel_workspace_bytes(int ndim, const long long* dims, size_t* bytes_out) {
@@ -1812,7 +1863,20 @@ int mlproj_multilevel_workspace_bytes(int ndim, const long long* dims, size_t* b
 int multilevel_proj(const float* Y, float* X, int ndim, const long long* dims, const int* norms,
                     float eta, void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
                     void* stream) {
-  return run_multilevel(Y, X, ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream);
+  return run_multilevel(MLPROJ_OUTER_L1, Y, X, ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream);
+}
+
+int multilevel_proj_p(int outer_norm, const float* Y, float* X, int ndim, const long long* dims,
+                      const int* norms, float eta, void* workspace, size_t workspace_bytes,
+                      float* v_out, float* u_out, void* stream) {
+  return run_multilevel(outer_norm, Y, X, ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream);
+}
+
+int bilevel_proj_pq(int outer_norm, int variant, const float* Y, float* X, long long n, long long m,
+                    float eta, void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
+                    void* stream) {
+  return dispatch_q(variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, stream,
+                    MODE_PROJECT, (double*)nullptr, STAGE_ALL, outer_norm);
 }
 
 int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1, long long d2,
@@ -1847,7 +1911,7 @@ int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1,
   const double fused_eta = fuse ? (double)eta : -1.0;
   if (!fuse) {
     mark(stream);
-    launch_search(ws, d0, (double)eta, MODE_PROJECT, nullptr, stream);
+    launch_search(ws, d0, (double)eta, MODE_PROJECT, MLPROJ_OUTER_L1, nullptr, stream);
   }
   mark(stream);
   if (vec == 4 && x_vec)

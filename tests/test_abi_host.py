@@ -122,3 +122,17 @@ def test_multilevel_argument_checks(lib):
     assert ml(FAKE, FAKE, 3, dims, (I * 2)(0, 7), F(1), FAKE, big, None, None, None) == -6
     assert ml(FAKE, FAKE, 3, dims, norms, F(-1), FAKE, big, None, None, None) == -4
     assert ml(FAKE, FAKE, 3, dims, norms, F(1), FAKE, 64, None, None, None) == -5
+
+
+def test_general_outer_norm_argument_checks(lib):
+    big = 1 << 30
+    pq = lib.bilevel_proj_pq
+    assert pq(0, 0, None, FAKE, 4, 4, F(1), FAKE, big, None, None, None) == -1
+    assert pq(3, 0, FAKE, FAKE, 4, 4, F(1), FAKE, big, None, None, None) == -6      # unknown outer norm
+    assert pq(-1, 0, FAKE, FAKE, 4, 4, F(1), FAKE, big, None, None, None) == -6
+    assert pq(1, 9, FAKE, FAKE, 4, 4, F(1), FAKE, big, None, None, None) == -6      # unknown q
+    assert pq(2, 1, FAKE, FAKE, 4, 4, F(-1), FAKE, big, None, None, None) == -4
+    LL, I = ctypes.c_longlong, ctypes.c_int
+    dims, norms = (LL * 3)(4, 5, 6), (I * 2)(0, 1)
+    assert lib.multilevel_proj_p(5, FAKE, FAKE, 3, dims, norms, F(1), FAKE, big, None, None, None) == -6
+    assert lib.multilevel_proj_p(1, FAKE, FAKE, 3, dims, norms, F(1), FAKE, 64, None, None, None) == -5

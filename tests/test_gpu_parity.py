@@ -436,3 +436,55 @@ def test_two_streams_two_workspaces(mp):
     torch.cuda.synchronize()
     for (q, Y, eta, Yd, ws, st), X in zip(jobs, outs):
         np.testing.assert_allclose(X.cpu().numpy(), orc.bilevel(Y, eta, q)["X"], rtol=RTOL, atol=ATOL)
+
+
+# ------------------------------------------------------------------ other outer norms (BP^{p,q}, general p)
+def lp(x, p):
+    x = np.asarray(x, dtype=np.float64)
+    return float({1: np.abs(x).sum(), 2: np.sqrt((x * x).sum()), "inf": np.abs(x).max()}[p])
+
+
+@pytest.mark.parametrize("p", [2, "inf"])
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+@pytest.mark.parametrize("shape", [(1, 1), (9, 7), (300, 257), (2065, 260), (40, 5000), (8, 40000)])
+def test_bilevel_pq_matches_oracle(mp, p, q, shape):
+    rng = np.random.default_rng([shape[0], shape[1], 7])
+    dev = torch.device("cuda:0")
+    Y = rng.standard_normal(shape).astype(np.float32)
+    Y *= np.power(10.0, rng.uniform(-1.0, 0.0, shape[1])).astype(np.float32)[None, :]
+    vnorm = lp(orc.column_norms(Y, q), p)
+    Yd = torch.from_numpy(Y).to(dev)
+    n, m = shape
+    for frac in (0.05, 0.5, 1.3, 0.0):
+        eta = float(np.float32(frac * vnorm))
+        ref = orc.bilevel(Y, eta, q, p=p)
+        ws = mp.Workspace.for_call(QNAME[q], n, m, device=dev)
+        u = torch.empty(m, dtype=torch.float32, device=dev)
+        X = mp.bilevel_proj_pq(p, q, Yd, eta, workspace=ws, u_out=u)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(u.cpu().numpy(), np.asarray(ref["u"], dtype=np.float32), rtol=RTOL, atol=ATOL)
+        np.testing.assert_allclose(X.cpu().numpy(), ref["X"], rtol=RTOL, atol=ATOL)
+        res = ws.result()
+        assert res["norm"] == pytest.approx(vnorm, rel=1e-12)
+        assert res["inside_ball"] == (vnorm <= eta)
+        if q == 1:
+            assert res["inner_pending"] == 0
+        if frac > 1:
+            assert np.array_equal(X.cpu().numpy(), Y)
+
+
+@pytest.mark.parametrize("p", [2, "inf"])
+def test_multilevel_outer_norm_matches_oracle(mp, p):
+    rng = np.random.default_rng(77)
+    dev = torch.device("cuda:0")
+    for shape, norms in (((30, 12, 20), [1, "inf"]), ((300, 40), [2]), ((6, 5, 4, 8), ["inf", 1, 2])):
+        Y = rng.standard_normal(shape).astype(np.float32)
+        a = Y.astype(np.float64)
+        for qq in norms:
+            a = {"inf": lambda z: np.abs(z).max(axis=-1), 1: lambda z: np.abs(z).sum(axis=-1),
+                 2: lambda z: np.sqrt((z * z).sum(axis=-1))}[qq](a)
+        eta = float(np.float32(0.4 * lp(a, p)))
+        ref = orc.multilevel(Y, norms, eta, p=p)
+        X = mp.multilevel_proj(torch.from_numpy(Y).to(dev), norms, eta, p=p)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(X.cpu().numpy(), ref["X"], rtol=RTOL, atol=ATOL)
