@@ -488,3 +488,31 @@ def test_multilevel_outer_norm_matches_oracle(mp, p):
         X = mp.multilevel_proj(torch.from_numpy(Y).to(dev), norms, eta, p=p)
         torch.cuda.synchronize()
         np.testing.assert_allclose(X.cpu().numpy(), ref["X"], rtol=RTOL, atol=ATOL)
+
+
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(mp):
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a
+    call can be recorded once and replayed; every replay must equal the eager result."""
+    rng = np.random.default_rng(51)
+    dev = torch.device("cuda:0")
+    for q, shape in (("inf", (1024, 768)), (2, (640, 512)), (1, (300, 260))):
+        Y = rng.standard_normal(shape).astype(np.float32)
+        eta = eta_for(Y, q, 0.25)
+        fn = getattr(mp, "bilevel_proj_" + QNAME[q])
+        Yd = torch.from_numpy(Y).to(dev)
+        Xg = torch.zeros_like(Yd)
+        ws = mp.Workspace.for_call(QNAME[q], *shape, device=dev)
+        eager = fn(Yd, eta, workspace=ws).clone()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn(Yd, eta, X=Xg, workspace=ws)
+        for rep in range(4):
+            Xg.zero_()
+            if rep == 2:                       # new data in the same buffers
+                Yd.mul_(0.5)
+                eager = fn(Yd, eta, workspace=ws).clone()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Xg, eager), (q, rep)
