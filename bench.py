@@ -91,7 +91,7 @@ def time_kernels(torch, mp, fn, pairs, steps, warmup):
     return out
 
 
-def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True):
+def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, eta_abs=None):
     import numpy as np
     dev = torch.device("cuda:0")
     n, m = Y_host.shape
@@ -102,10 +102,15 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True):
     Y0 = torch.from_numpy(Y_host).to(dev)
     pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
     ws = mp.Workspace.for_call(variant, n, m, device=dev)
-    eta = device_eta(mp, Y0, variant, frac, ws)
+    eta = device_eta(mp, Y0, variant, frac, ws) if eta_abs is None else float(eta_abs)
     fn = getattr(mp, "bilevel_proj_" + variant)
     ms = time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, steps, warmup)
     res = ws.result()
+    # how far the nearest aggregate is from the threshold, relative: the support is safe
+    # against fp64 summation-order differences as long as this is far above 1e-13
+    vbuf = torch.empty(m, dtype=torch.float32, device=dev)
+    fn(pairs[0][0], eta, X=pairs[0][1], workspace=ws, v_out=vbuf)
+    margin = float(((vbuf.double() - res["tau"]).abs().min() / res["tau"]).item()) if res["tau"] > 0 else None
     k_raw = time_kernels(torch, mp, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, min(steps, 100), min(warmup, 10))
     # Bracketing every kernel with events drains the queue around it, which adds the same
     # dispatch-from-idle latency to every interval; the untraced loop above has none of it.
@@ -121,7 +126,8 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True):
         "frac_of_peak_8B": 8.0 * elems / ms / 1e6 / HBM_PEAK_GBS,
         "eff_GBps_12B": 12.0 * elems / ms / 1e6,
         "kernel_ms": k_ms, "kernel_ms_event_intervals": k_raw,
-        "tau": res["tau"], "n_active": res["n_active"], "search_iters": res["search_iters"],
+        "tau": res["tau"], "n_active": res["n_active"], "support_margin": margin,
+        "search_iters": res["search_iters"],
         "inner_sweeps": res["inner_sweeps"], "inner_pending": res["inner_pending"],
     }
     del pairs
@@ -227,6 +233,12 @@ def main():
         for variant, steps in (("l1inf", 20), ("l12", 20), ("l11", 5)):
             also["square_16384/" + variant] = bench_bilevel(torch, mp, Yb, variant, wb.eta_frac, steps, 3)
         del Yb
+        # the shape and distribution of the paper's own timing runs (Sec. 6.1): time against the radius
+        wp, Yp = workloads.make("paper_1000x10000")
+        for eta_abs in (0.25, 1.0, 4.0):
+            also["paper_1000x10000/l1inf/eta=%g" % eta_abs] = bench_bilevel(torch, mp, Yp, "l1inf", None, 100, 10,
+                                                                         eta_abs=eta_abs)
+        del Yp
         wt, Yt = workloads.make("tensor_256x256x256")
         for k, v in bench_tensor(torch, mp, Yt, wt.eta_frac, 100, 10).items():
             also["tensor_256x256x256/" + k] = v
