@@ -87,6 +87,18 @@ def test_many_columns_use_the_grid_wide_search(mp, q, shape):
 
 
 @pytest.mark.parametrize("q", ["inf", 1, 2])
+@pytest.mark.parametrize("shape", [(50000, 3), (100000, 1), (1, 100000), (2, 20000), (70001, 65)])
+def test_very_tall_and_single_row_shapes(mp, q, shape):
+    """A handful of columns under many row groups (one tile, every workgroup on it), and the
+    one-row matrix, where the aggregate is |Y| itself and the projection is the plain l1 one."""
+    rng = np.random.default_rng([shape[0], shape[1], 5])
+    Y = rng.standard_normal(shape).astype(np.float32)
+    for frac in (0.02, 0.7):
+        eta = eta_for(Y, q, frac)
+        check_against_oracle(run_gpu(mp, Y, eta, q), orc.bilevel(Y, eta, q), q)
+
+
+@pytest.mark.parametrize("q", ["inf", 1, 2])
 def test_degenerate_radii_and_inputs(mp, q):
     rng = np.random.default_rng(7)
     Y = rng.standard_normal((65, 70)).astype(np.float32)
