@@ -26,6 +26,7 @@ __all__ = [
     "column_norms", "norm_l1q", "project_l1_ball_nonneg", "project_l1_ball",
     "project_linf_ball", "project_l2_ball", "bilevel_l1inf", "bilevel_l11",
     "bilevel_l12", "trilevel_l1infinf", "bilevel", "multilevel", "project_outer",
+    "round_to_storage", "bilevel_stored",
 ]
 
 
@@ -201,6 +202,48 @@ def bilevel_l11(Y, eta, columns=None, p=1):
 def bilevel(Y, eta, q, columns=None, p=1):
     """BP^{p,q}_eta(Y), Alg. 1, for p, q in {1, 2, "inf"}."""
     return {"inf": bilevel_l1inf, 1: bilevel_l11, 2: bilevel_l12}[q](Y, eta, columns, p)
+
+
+# --------------------------------------------------------------------------
+# 16-bit storage (an extension for training loops; the paper fixes no storage format)
+# --------------------------------------------------------------------------
+def round_to_storage(x, storage):
+    """Round fp32 values to the storage format, to nearest with ties to even, and return them
+    as fp32 again.  storage: "f32" (identity), "f16" (IEEE binary16: 10 fraction bits,
+    subnormals, overflow to infinity) or "bf16" (the upper 16 bits of binary32: 7 fraction bits).
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if storage == "f32":
+        return x.copy()
+    if storage == "f16":
+        with np.errstate(over="ignore"):              # beyond 65504 the format has only infinity
+            return x.astype(np.float16).astype(np.float32)
+    if storage == "bf16":
+        b = x.view(np.uint32).astype(np.uint64)
+        kept_lsb = (b >> 16) & 1                      # ties go to the even 16-bit pattern
+        r = ((b + 0x7FFF + kept_lsb) >> 16) << 16
+        out = (r & 0xFFFFFFFF).astype(np.uint32).view(np.float32).reshape(x.shape)
+        return np.where(np.isnan(x), x, out)
+    raise ValueError("storage must be 'f32', 'f16' or 'bf16'")
+
+
+def bilevel_stored(Y, eta, q, storage, columns=None, p=1):
+    """BP^{p,q}_eta (Alg. 1) on a matrix kept in a 16-bit format.
+
+    Y is an fp32 array whose values are all representable in `storage` (the caller's 16-bit
+    data widened exactly).  The projection is the fp32-storage one, unchanged; only its
+    result X is rounded to the storage format (returned widened to fp32).  The aggregate v,
+    the radii u and tau are not rounded.  Also returns mask (u_j > 0: the kept columns) and
+    X32, the result before rounding.
+    """
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32
+    assert np.array_equal(round_to_storage(Y, storage), Y), "Y must be representable in the storage format"
+    out = dict(bilevel(Y, eta, q, columns, p))
+    out["X32"] = out["X"]
+    out["X"] = round_to_storage(out["X32"], storage)
+    out["mask"] = np.asarray(out["u"], dtype=np.float64) > 0
+    return out
 
 
 # --------------------------------------------------------------------------

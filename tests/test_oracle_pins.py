@@ -422,3 +422,66 @@ def test_multilevel_outer_norm(p):
     assert_is_projection(w, out["u"], eta, p)
     got = lq(lq(lq(out["X"], 1, axis=-1), "inf", axis=-1), p)
     assert got == pytest.approx(eta, rel=1e-5)
+
+
+# ------------------------------------------------------------------ 16-bit storage
+def test_storage_rounding_hand_cases():
+    """Ties go to the even pattern; values written as exact binary fractions."""
+    bf = lambda x: float(orc.round_to_storage(np.float32([x]), "bf16")[0])
+    assert bf(1.0 + 2.0 ** -8) == 1.0                        # halfway between 1 and 1+2^-7: even is 1
+    assert bf(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6        # halfway between 1+2^-7 and 1+2^-6: even is up
+    assert bf(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7
+    assert bf(-(1.0 + 2.0 ** -8 - 2.0 ** -20)) == -1.0
+    assert bf(3.3895313892515355e38) == 3.3895313892515355e38          # the largest finite bf16 value
+    assert bf(0.0) == 0.0 and np.signbit(orc.round_to_storage(np.float32([-0.0]), "bf16")[0])
+    h = lambda x: float(orc.round_to_storage(np.float32([x]), "f16")[0])
+    assert h(1.0 + 2.0 ** -11) == 1.0 and h(1.0 + 3 * 2.0 ** -11) == 1.0 + 2.0 ** -9
+    assert h(65504.0) == 65504.0 and h(65519.0) == 65504.0 and np.isinf(h(65520.0))
+    assert h(2.0 ** -24) == 2.0 ** -24 and h(2.0 ** -25) == 0.0 and h(1.5 * 2.0 ** -24) == 2.0 ** -23
+    x = np.float32([0.1, -2.5, 7.0])
+    assert np.array_equal(orc.round_to_storage(x, "f32"), x)
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16"])
+def test_storage_rounding_matches_a_library_conversion_and_is_monotone(storage):
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(200000) * 10.0 ** rng.uniform(-6, 4, 200000),
+                        np.float32([0.0, -0.0, 1e-40, -1e-40, 6.0e-8, 65504.0])]).astype(np.float32)
+    ties = (np.arange(1 << 16, dtype=np.uint32) << 16 | 0x8000).view(np.float32)   # every bf16 midpoint
+    ties = ties[np.isfinite(ties)]
+    x = np.concatenate([x, ties])
+    if storage == "f16":
+        x = x[np.abs(x) < 65000]
+    want = torch.from_numpy(x).to({"bf16": torch.bfloat16, "f16": torch.float16}[storage]).float().numpy()
+    got = orc.round_to_storage(x, storage)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert np.array_equal(orc.round_to_storage(got, storage), got)        # idempotent
+    xs = np.sort(x)
+    assert np.all(np.diff(orc.round_to_storage(xs, storage)) >= 0)        # monotone
+    rel = np.abs(got.astype(np.float64) - x) / np.maximum(np.abs(x), 1e-30)
+    normal = (np.abs(x) > (1e-37 if storage == "bf16" else 6.2e-5)) & np.isfinite(got)
+    assert rel[normal].max() <= 2.0 ** (-8 if storage == "bf16" else -11)   # half a unit in the last place
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16"])
+@pytest.mark.parametrize("q", QS)
+def test_bilevel_stored_is_the_fp32_result_rounded(storage, q):
+    Y = orc.round_to_storage(rand_matrix(40, 30), storage)
+    eta = 0.3 * orc.norm_l1q(Y, q)
+    out = orc.bilevel_stored(Y, eta, q, storage)
+    ref = orc.bilevel(Y, eta, q)
+    assert np.array_equal(out["X32"], ref["X"]) and out["tau"] == ref["tau"]
+    assert np.array_equal(out["X"], orc.round_to_storage(ref["X"], storage))
+    assert np.array_equal(out["mask"], np.abs(ref["X"]).max(axis=0) > 0)
+    # rounding moves every entry by at most half a unit in the last place of the format
+    half_ulp = 2.0 ** (-8 if storage == "bf16" else -11)
+    assert np.all(np.abs(out["X"].astype(np.float64) - ref["X"]) <= half_ulp * np.abs(ref["X"]) + 1e-7)
+    assert lq(lq(out["X"], q, axis=0), 1) <= eta * (1 + 2 * half_ulp)
+    if q == "inf":   # entries under the radius are untouched, the others sit on the rounded radius
+        ur = orc.round_to_storage(np.asarray(ref["u"], dtype=np.float32), storage)
+        inside = np.abs(Y) <= np.asarray(ref["u"], dtype=np.float32)[None, :]
+        assert np.array_equal(out["X"][inside], Y[inside])
+        assert np.array_equal(np.abs(out["X"])[~inside], np.broadcast_to(ur, Y.shape)[~inside])
+    with pytest.raises(AssertionError):
+        orc.bilevel_stored(Y + np.float32(1e-3), eta, q, storage)
