@@ -91,19 +91,28 @@ def time_kernels(torch, mp, fn, pairs, steps, warmup):
     return out
 
 
-def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, eta_abs=None):
+def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, eta_abs=None, storage="f32"):
+    """storage "bf16" / "f16": the same matrix rounded to 16 bits, through bilevel_proj_stored
+    (half the bytes: 4 per element instead of 8 in the effective figures)."""
     import numpy as np
     dev = torch.device("cuda:0")
     n, m = Y_host.shape
-    nbytes = Y_host.nbytes
+    elem = 4 if storage == "f32" else 2
+    nbytes = n * m * elem
     npairs = 1
     if cold and 2 * nbytes < 2 * INFINITY_CACHE_BYTES:
         npairs = max(2, -(-3 * INFINITY_CACHE_BYTES // (2 * nbytes)))   # > 3 caches of working set
     Y0 = torch.from_numpy(Y_host).to(dev)
-    pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
     ws = mp.Workspace.for_call(variant, n, m, device=dev)
-    eta = device_eta(mp, Y0, variant, frac, ws) if eta_abs is None else float(eta_abs)
-    fn = getattr(mp, "bilevel_proj_" + variant)
+    if storage != "f32":
+        Y0 = Y0.to({"bf16": torch.bfloat16, "f16": torch.float16}[storage])
+        eta = device_eta(mp, Y0.float(), variant, frac, ws) if eta_abs is None else float(eta_abs)
+        q = {"l1inf": "inf", "l11": 1, "l12": 2}[variant]
+        fn = lambda Y, eta, X, workspace, v_out=None: mp.bilevel_proj_stored(Y, eta, q, X=X, workspace=workspace, v_out=v_out)
+    else:
+        eta = device_eta(mp, Y0, variant, frac, ws) if eta_abs is None else float(eta_abs)
+        fn = getattr(mp, "bilevel_proj_" + variant)
+    pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
     ms = time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, steps, warmup)
     res = ws.result()
     # how far the nearest aggregate is from the threshold, relative: the support is safe
@@ -119,12 +128,14 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
     k_ms = {k: max(v - excess, 0.0) for k, v in k_raw.items()}
     warm_ms = time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs[:1], steps, warmup) if npairs > 1 else ms
     elems = n * m
+    b = 2.0 * elem   # read Y once, write X once
     out = {
-        "shape": [n, m], "variant": variant, "eta": eta, "buffer_pairs": npairs,
+        "shape": [n, m], "variant": variant, "storage": storage, "eta": eta, "buffer_pairs": npairs,
         "ms": ms, "ms_warm": warm_ms,
-        "eff_GBps_8B": 8.0 * elems / ms / 1e6,
-        "frac_of_peak_8B": 8.0 * elems / ms / 1e6 / HBM_PEAK_GBS,
-        "eff_GBps_12B": 12.0 * elems / ms / 1e6,
+        "bytes_per_element_rw": b,   # "rw": read Y once + write X once; "rrw": two reads + one write
+        "eff_GBps_rw": b * elems / ms / 1e6,
+        "frac_of_peak_rw": b * elems / ms / 1e6 / HBM_PEAK_GBS,
+        "eff_GBps_rrw": 1.5 * b * elems / ms / 1e6,
         "kernel_ms": k_ms, "kernel_ms_event_intervals": k_raw,
         "tau": res["tau"], "n_active": res["n_active"], "support_margin": margin,
         "search_iters": res["search_iters"],
@@ -149,8 +160,8 @@ def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
     def record(name, fn, ws, eta):
         ms = time_calls(torch, fn, pairs, steps, warmup)
         res = ws.result()
-        out[name] = {"shape": list(Y_host.shape), "eta": eta, "ms": ms, "eff_GBps_8B": 8.0 * elems / ms / 1e6,
-                     "frac_of_peak_8B": 8.0 * elems / ms / 1e6 / HBM_PEAK_GBS, "tau": res["tau"],
+        out[name] = {"shape": list(Y_host.shape), "eta": eta, "ms": ms, "eff_GBps_rw": 8.0 * elems / ms / 1e6,
+                     "frac_of_peak_rw": 8.0 * elems / ms / 1e6 / HBM_PEAK_GBS, "tau": res["tau"],
                      "n_active": res["n_active"]}
 
     # eta from the library itself: the nested norm is the sum of the aggregate vector
@@ -218,13 +229,13 @@ def main():
     }
     line = {
         "metric": "effective HBM GB/s of one bi-level l1,inf projection (8 B/element: read Y, write X), cold caches",
-        "value": head["eff_GBps_8B"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": head["eff_GBps_rw"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %dx%d fp32 row-major, entries %s, eta=%.2f*||Y||_1,inf"
                                % (args.workload, n, m, DIST_TEXT[w.dist], w.eta_frac),
                    "buffer_pairs": head["buffer_pairs"], "timing": "cold (rotating buffers > Infinity Cache)"},
-        "frac_of_hbm_peak": head["frac_of_peak_8B"], "ms_per_step_warm": head["ms_warm"],
+        "frac_of_hbm_peak": head["frac_of_peak_rw"], "ms_per_step_warm": head["ms_warm"],
         "detail": head, "roofline": roofline,
     }
     if not args.quick:
@@ -232,6 +243,10 @@ def main():
         wb, Yb = workloads.make("square_16384")
         for variant, steps in (("l1inf", 20), ("l12", 20), ("l11", 5)):
             also["square_16384/" + variant] = bench_bilevel(torch, mp, Yb, variant, wb.eta_frac, steps, 3)
+        # the same matrix kept in 16 bits (4 bytes per element in the effective figures, not 8)
+        also["square_16384/l1inf/bf16"] = bench_bilevel(torch, mp, Yb, "l1inf", wb.eta_frac, 20, 3, storage="bf16")
+        also["square_16384/l11/bf16"] = bench_bilevel(torch, mp, Yb, "l11", wb.eta_frac, 5, 3, storage="bf16")
+        also["square_4096/l1inf/bf16"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, storage="bf16")
         del Yb
         # the shape and distribution of the paper's own timing runs (Sec. 6.1): time against the radius
         wp, Yp = workloads.make("paper_1000x10000")

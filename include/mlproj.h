@@ -51,7 +51,7 @@ typedef enum mlproj_status {
   MLPROJ_ERR_BAD_RADIUS = -4,     /* eta is negative, NaN or infinite                 */
   MLPROJ_ERR_WORKSPACE = -5,      /* workspace too small or misaligned                */
   MLPROJ_ERR_BAD_VARIANT = -6,    /* unknown variant / norm selector                  */
-  MLPROJ_ERR_ALIGNMENT = -7,      /* Y or X not 4-byte aligned                        */
+  MLPROJ_ERR_ALIGNMENT = -7,      /* Y or X not aligned to the element size            */
   MLPROJ_ERR_LAUNCH = -8          /* the HIP runtime refused a launch (see hipGetLastError) */
 } mlproj_status;
 
@@ -76,6 +76,15 @@ typedef enum mlproj_outer {
   MLPROJ_OUTER_L2 = 1,
   MLPROJ_OUTER_LINF = 2
 } mlproj_outer;
+
+/* Element type of Y and X in bilevel_proj_stored.  The 16-bit formats are storage only: each
+ * element is widened exactly to fp32 on load, all arithmetic is the fp32 / fp64 of the fp32
+ * entry points, and X is rounded to nearest (ties to even) on store.                       */
+typedef enum mlproj_storage {
+  MLPROJ_STORE_F32 = 0,
+  MLPROJ_STORE_BF16 = 1,  /* upper half of IEEE binary32: 8 exponent, 7 fraction bits */
+  MLPROJ_STORE_F16 = 2    /* IEEE binary16 */
+} mlproj_storage;
 
 /* Record left at offset 0 of the workspace by every projection / norm call.
  * The outer projection acts on every aggregate as u_j = min(cap, scale * max(v_j - tau, 0)). */
@@ -152,6 +161,22 @@ int bilevel_proj_pq(int outer_norm, int variant, const float* Y /* device, n*m *
                     void* workspace /* device */, size_t workspace_bytes,
                     float* v_out /* device, m; may be NULL */,
                     float* u_out /* device, m; may be NULL */, void* stream);
+
+/* bilevel_proj_pq on a matrix stored in fp32, bf16 or fp16 (a mlproj_storage), for training
+ * loops that keep weights in 16 bits and prune by column (the use Sec. 6.3 makes of the
+ * projection): Alg. 1 unchanged, computed on the widened values; only X is rounded to the
+ * storage format.  v_out and u_out stay fp32.  mask_out[j] = 1 when column j is kept
+ * (u_j > 0, decided in fp64) and 0 when the projection zeroes it.  Y and X must be aligned to
+ * the element size; the 16-byte accesses need 16-byte aligned pointers and m a multiple of
+ * 16 / element size, other inputs take an element-wise path.  X may alias Y.  The workspace
+ * size is mlproj_workspace_bytes(variant, n, m, 1) for every storage type.                  */
+int bilevel_proj_stored(int storage, int outer_norm, int variant,
+                        const void* Y /* device, n*m elements */, void* X /* device, n*m elements */,
+                        long long n, long long m, float eta,
+                        void* workspace /* device */, size_t workspace_bytes,
+                        float* v_out /* device, m; may be NULL */,
+                        float* u_out /* device, m; may be NULL */,
+                        unsigned char* mask_out /* device, m; may be NULL */, void* stream);
 
 /* The two halves of a bi-level call, for callers that want the radii before (or without)
  * writing X.  bilevel_radii computes the aggregate v and u = P^1_eta(v) of Alg. 1 (for

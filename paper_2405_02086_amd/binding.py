@@ -89,6 +89,8 @@ def lib():
                                     c_sz, c_vp, c_vp, c_vp]
     L.bilevel_proj_pq.restype = c_i
     L.bilevel_proj_pq.argtypes = [c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
+    L.bilevel_proj_stored.restype = c_i
+    L.bilevel_proj_stored.argtypes = [c_i, c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.trilevel_proj_l1infinf.restype = c_i
     L.trilevel_proj_l1infinf.argtypes = [c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     _lib = L
@@ -100,6 +102,7 @@ EXPORTS = (
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
+    "bilevel_proj_stored",
 )
 
 
@@ -224,6 +227,31 @@ def bilevel_proj_pq(p, q, Y, eta, X=None, workspace=None, v_out=None, u_out=None
     st = lib().bilevel_proj_pq(_OUTERS[p], variant, _ptr(Y), _ptr(X), n, m, ctypes.c_float(eta),
                                _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out), _stream(stream))
     _check(st, "bilevel_proj_pq")
+    return X
+
+
+STORE_F32, STORE_BF16, STORE_F16 = 0, 1, 2
+
+
+def bilevel_proj_stored(Y, eta, q, p=1, X=None, workspace=None, v_out=None, u_out=None, mask_out=None,
+                        stream=None):
+    """BP^{p,q} on a contiguous fp32, bf16 or fp16 device matrix (X has Y's dtype); mask_out is an
+    optional uint8 tensor of m entries that receives 1 for every kept column."""
+    import torch
+    storages = {torch.float32: STORE_F32, torch.bfloat16: STORE_BF16, torch.float16: STORE_F16}
+    assert Y.is_cuda and Y.dim() == 2 and Y.is_contiguous() and Y.dtype in storages
+    n, m = Y.shape
+    if X is None:
+        X = torch.empty_like(Y)
+    assert X.is_cuda and X.dtype == Y.dtype and X.is_contiguous() and X.shape == Y.shape
+    assert mask_out is None or (mask_out.dtype == torch.uint8 and mask_out.numel() >= m)
+    variant = {"inf": L1INF, 1: L11, 2: L12}[q]
+    if workspace is None:
+        workspace = Workspace.for_call(variant, n, m, device=Y.device, stream=stream)
+    st = lib().bilevel_proj_stored(storages[Y.dtype], _OUTERS[p], variant, _ptr(Y), _ptr(X), n, m,
+                                   ctypes.c_float(eta), _ptr(workspace.buf), workspace.nbytes, _ptr(v_out),
+                                   _ptr(u_out), _ptr(mask_out), _stream(stream))
+    _check(st, "bilevel_proj_stored")
     return X
 
 

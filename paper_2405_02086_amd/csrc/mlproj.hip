@@ -158,29 +158,53 @@ static Ws bind(void* workspace, const Layout& L) {
 }
 
 // ------------------------------------------------------------------ device helpers
-template <int VEC>
-__device__ __forceinline__ void load_row(const float* p, float (&x)[VEC]) {
-  if constexpr (VEC == 4) {
-    const float4 t = *reinterpret_cast<const float4*>(p);
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+// Storage types of Y and X: fp32, or a 16-bit format widened to fp32 on load and rounded to
+// nearest-even on store (the arithmetic is the same fp32 / fp64 in every case).
+using bf16_t = __bf16;
+using f16_t = _Float16;
+
+// One lane's share of a row: VEC consecutive elements, 16 bytes when VEC > 1.
+template <typename T, int VEC>
+struct alignas(sizeof(T) * VEC) Pack {
+  static_assert(VEC == 1 || sizeof(T) * VEC == 16, "a vector access is 16 bytes");
+  T e[VEC];
+};
+
+template <int VEC, typename T>
+__device__ __forceinline__ void load_row(const T* p, float (&x)[VEC]) {
+  const Pack<T, VEC> t = *reinterpret_cast<const Pack<T, VEC>*>(p);
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) x[k] = (float)t.e[k];
+}
+
+template <typename T>
+__device__ __forceinline__ void store_one_nt(T* p, float x) {
+  if constexpr (sizeof(T) == 4) {
+    __builtin_nontemporal_store(x, p);
   } else {
-    x[0] = *p;
+    const T t = (T)x;
+    unsigned short bits;
+    __builtin_memcpy(&bits, &t, 2);
+    __builtin_nontemporal_store(bits, reinterpret_cast<unsigned short*>(p));
   }
 }
 
 // X is written once and never read again by this call: a non-temporal store keeps it from
-// displacing Y in the caches between the two passes over Y.
-template <int VEC, bool WIDE = (VEC == 4)>
-__device__ __forceinline__ void store_row_nt(float* p, const float (&x)[VEC]) {
-  if constexpr (VEC == 4 && !WIDE) {
+// displacing Y in the caches between the two passes over Y.  WIDE = one 16-byte store
+// (X 16-byte aligned), otherwise element by element.
+template <int VEC, bool WIDE = (VEC > 1), typename T>
+__device__ __forceinline__ void store_row_nt(T* p, const float (&x)[VEC]) {
+  if constexpr (VEC > 1 && WIDE) {
+    typedef unsigned vu4 __attribute__((ext_vector_type(4)));
+    Pack<T, VEC> t;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) __builtin_nontemporal_store(x[k], p + k);
-  } else if constexpr (VEC == 4) {
-    typedef float vf4 __attribute__((ext_vector_type(4)));
-    vf4 t = {x[0], x[1], x[2], x[3]};
-    __builtin_nontemporal_store(t, reinterpret_cast<vf4*>(p));
+    for (int k = 0; k < VEC; ++k) t.e[k] = (T)x[k];
+    vu4 w;
+    __builtin_memcpy(&w, &t, 16);
+    __builtin_nontemporal_store(w, reinterpret_cast<vu4*>(p));
   } else {
-    __builtin_nontemporal_store(x[0], p);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) store_one_nt(p + k, x[k]);
   }
 }
 
@@ -336,8 +360,8 @@ __device__ __forceinline__ typename AccOf<Q>::type combine(typename AccOf<Q>::ty
 // Partial column aggregates of v_j = ||y_j||_q (Sec. 3): max |.| (exact), sum |.| or sum of
 // squares (both in fp64).  Lane l of every wavefront owns VEC consecutive columns; the four
 // wavefronts of a workgroup take rows r, r+1, r+2, r+3 (mod 4) of each row block.
-template <int Q, int VEC>
-__global__ __launch_bounds__(WG) void colagg_kernel(const float* __restrict__ Y, long long n,
+template <int Q, typename T, int VEC>
+__global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, long long n,
                                                     long long m, Geometry g,
                                                     void* __restrict__ partial_) {
   using Acc = typename AccOf<Q>::type;
@@ -355,7 +379,7 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const float* __restrict__ Y,
   for (int k = 0; k < VEC; ++k) acc[k] = (Acc)0;
 
   if (col0 < m) {
-    const float* p = Y + col0;
+    const T* p = Y + col0;
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
       float x[UNROLL][VEC];
@@ -376,11 +400,11 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const float* __restrict__ Y,
 #pragma unroll
   for (int k = 0; k < VEC; ++k) sm[wave][lane * VEC + k] = acc[k];
   __syncthreads();
-  if (threadIdx.x < TILE_W) {
-    Acc a = sm[0][threadIdx.x];
+  for (int c = threadIdx.x; c < TILE_W; c += WG) {
+    Acc a = sm[0][c];
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) a = combine<Q>(a, sm[w][threadIdx.x]);
-    static_cast<Acc*>(partial_)[((size_t)t * g.groups + grp) * TILE_W + threadIdx.x] = a;
+    for (int w = 1; w < WAVES; ++w) a = combine<Q>(a, sm[w][c]);
+    static_cast<Acc*>(partial_)[((size_t)t * g.groups + grp) * TILE_W + c] = a;
   }
 }
 
@@ -735,11 +759,12 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
 // read last there (the ones most likely still cached) are read first here.
 // With fused_eta >= 0 every workgroup first runs the threshold search itself (see
 // search_block) and workgroup 0 files the result record; otherwise tau is read from it.
-template <int Q, int VEC, bool XVEC>
-__global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, long long n,
+template <int Q, typename T, int VEC, bool XVEC>
+__global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long n,
                                                     long long m, Geometry g, Ws ws,
-                                                    float* __restrict__ u_out, double fused_eta,
-                                                    int outer) {
+                                                    float* __restrict__ u_out,
+                                                    unsigned char* __restrict__ mask_out,
+                                                    double fused_eta, int outer) {
   constexpr int TILE_W = WAVE * VEC;
   constexpr int U = MAP_UNROLL;
   __shared__ PairScratch<WAVES> bs;
@@ -749,18 +774,20 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
   const long long grp = blockIdx.x / g.tiles;
   const long long col0 = t * TILE_W + (long long)lane * VEC;
   const bool col_ok = col0 < m;
-  const float* p = Y + col0;
-  float* q = X + col0;
+  const T* p = Y + col0;
+  T* q = X + col0;
 
   // Row blocks of MAP_RBLK rows, bottom block first; the last block may be ragged.
   const long long nblk = (n + MAP_RBLK - 1) / MAP_RBLK;
   long long b = nblk - 1 - grp;
-  float x[U][VEC], y[U][VEC];
-  auto load_block = [&](long long blk, float (&dst)[U][VEC]) {
+  // The two buffers hold the elements as stored: widening them here would put a use of the
+  // loaded values, and with it the wait for them, ahead of the stores of the current block.
+  Pack<T, VEC> x[U], y[U];
+  auto load_block = [&](long long blk, Pack<T, VEC> (&dst)[U]) {
 #pragma unroll
     for (int r = 0; r < U; ++r) {
       const long long row = blk * MAP_RBLK + wave + (long long)r * WAVES;
-      if (row < n) load_row<VEC>(p + row * m, dst[r]);
+      if (row < n) dst[r] = *reinterpret_cast<const Pack<T, VEC>*>(p + row * m);
     }
   };
   // The first block is requested before tau is known, so its latency hides the search.
@@ -790,9 +817,15 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
     else if constexpr (Q == Q1) par[k] = inside ? 0.0 : (uj > 0.0 ? ws.tauj[col0 + k] : HUGE_VAL);
     else par[k] = 0.0;
   }
-  if (u_out && grp == 0 && wave == 0) {
+  if (grp == 0 && wave == 0) {
+    if (u_out) {
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) u_out[col0 + k] = uf[k];
+      for (int k = 0; k < VEC; ++k) u_out[col0 + k] = uf[k];
+    }
+    if (mask_out) {  // the kept columns, decided where the radius is: in fp64
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) mask_out[col0 + k] = radius(ws.v[col0 + k], top) > 0.0 ? 1 : 0;
+    }
   }
 
   auto apply = [&](float yv, int k) -> float {
@@ -813,15 +846,14 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
     for (int r = 0; r < U; ++r) {
       const long long row = b * MAP_RBLK + wave + (long long)r * WAVES;
       if (row < n) {
+        float f[VEC];
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) x[r][k] = apply(x[r][k], k);
-        store_row_nt<VEC, XVEC>(q + row * m, x[r]);
+        for (int k = 0; k < VEC; ++k) f[k] = apply((float)x[r].e[k], k);
+        store_row_nt<VEC, XVEC>(q + row * m, f);
       }
     }
 #pragma unroll
-    for (int r = 0; r < U; ++r)
-#pragma unroll
-      for (int k = 0; k < VEC; ++k) x[r][k] = y[r][k];
+    for (int r = 0; r < U; ++r) x[r] = y[r];
   }
 }
 
@@ -841,8 +873,8 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const float* Y, float* X, lo
 // that follow restore the invariants.  Typically three or four sweeps suffice.
 // pending[s] is the number of columns still open before sweep s; both kernels of a sweep
 // return at once when it is zero.
-template <int VEC>
-__global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__ Y, long long n,
+template <typename T, int VEC>
+__global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, long long n,
                                                        long long m, Geometry g, Ws ws,
                                                        int sweep) {
   constexpr int TILE_W = WAVE * VEC;
@@ -872,7 +904,7 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
       tj[k] = ws.tauj[col0 + k];
       tw[k] = tj[k] * (1.0 + L11_WINDOW);
     }
-    const float* p = Y + col0;
+    const T* p = Y + col0;
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
       float x[UNROLL][VEC];
@@ -905,16 +937,16 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const float* __restrict__
     sm_cnt2[wave][lane * VEC + k] = cnt2[k];
   }
   __syncthreads();
-  if (threadIdx.x < TILE_W) {
-    double a = sm_sum[0][threadIdx.x];
-    unsigned c = sm_cnt[0][threadIdx.x], c2 = sm_cnt2[0][threadIdx.x];
+  for (int col = threadIdx.x; col < TILE_W; col += WG) {
+    double a = sm_sum[0][col];
+    unsigned c = sm_cnt[0][col], c2 = sm_cnt2[0][col];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) {
-      a += sm_sum[w][threadIdx.x];
-      c += sm_cnt[w][threadIdx.x];
-      c2 += sm_cnt2[w][threadIdx.x];
+      a += sm_sum[w][col];
+      c += sm_cnt[w][col];
+      c2 += sm_cnt2[w][col];
     }
-    const size_t cell = ((size_t)t * g.groups + grp) * TILE_W + threadIdx.x;
+    const size_t cell = ((size_t)t * g.groups + grp) * TILE_W + col;
     static_cast<double*>(ws.partial)[cell] = a;
     ws.partial_cnt[cell] = c;
     ws.partial_cnt2[cell] = c2;
@@ -1456,8 +1488,10 @@ static int check_dims(long long a, long long b, long long c) {
 
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-static int pick_vec(const void* Y, long long row_len) {
-  return (row_len % 4 == 0 && aligned(Y, 16)) ? 4 : 1;
+// Elements per lane and access: 16 bytes when the rows allow it, one element otherwise.
+static int pick_vec(const void* Y, long long row_len, int elem_bytes = 4) {
+  const int wide = 16 / elem_bytes;
+  return (row_len % wide == 0 && aligned(Y, 16)) ? wide : 1;
 }
 
 static int workspace_bytes_impl(int variant, long long d0, long long d1, long long d2,
@@ -1468,10 +1502,11 @@ static int workspace_bytes_impl(int variant, long long d0, long long d1, long lo
   const int st = check_dims(d0, d1, d2);
   if (st != MLPROJ_OK) return st;
   size_t best = 0;
-  for (int vec : {4, 1}) {
+  for (int vec : {8, 4, 1}) {   // 8: the 16-bit storage formats of the bi-level entry points
     Geometry g;
     long long ngroups;
     if (variant == MLPROJ_L1INFINF) {
+      if (vec == 8) continue;
       if (d0 > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
       g = plan_slabs(d0, d1 * d2, vec);
       ngroups = d0;
@@ -1528,10 +1563,12 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
 
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
 // STAGE_APPLY = the per-column map.
-template <int Q>
-static int run_bilevel(const float* Y, float* X, long long n, long long m, float eta,
+template <int Q, typename T = float>
+static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
                        void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
-                       void* stream_, int mode, double* norm_out, int stages, int outer) {
+                       void* stream_, int mode, double* norm_out, int stages, int outer,
+                       unsigned char* mask_out = nullptr) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
   if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
   const bool need_x = mode == MODE_PROJECT && (stages & STAGE_APPLY);
   if (!Y || !workspace || (need_x && !X)) return MLPROJ_ERR_NULL_POINTER;
@@ -1540,11 +1577,11 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
   if (m > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
   if (mode == MODE_PROJECT && (stages & STAGE_AGGREGATE) && (st = check_radius(eta)) != MLPROJ_OK)
     return st;
-  if (!aligned(Y, 4) || (X && !aligned(X, 4))) return MLPROJ_ERR_ALIGNMENT;
+  if (!aligned(Y, sizeof(T)) || (X && !aligned(X, sizeof(T)))) return MLPROJ_ERR_ALIGNMENT;
   if (!aligned(workspace, 256)) return MLPROJ_ERR_WORKSPACE;
   // The access width is a function of m and of Y alone, so that the two stages of a split
   // call agree on the geometry whatever X is; a misaligned X takes the scalar store path.
-  const int vec = pick_vec(Y, m);
+  const int vec = pick_vec(Y, m, (int)sizeof(T));
   const bool x_vec = !X || aligned(X, 16);
   const Geometry g = plan_columns(n, m, vec, Q);
   if (g.tiles * g.groups > MAX_GRID) return MLPROJ_ERR_TOO_LARGE;
@@ -1563,10 +1600,10 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
 
   if (stages & STAGE_AGGREGATE) {
     mark(stream);
-    if (vec == 4)
-      hipLaunchKernelGGL((colagg_kernel<Q, 4>), grid, block, 0, stream, Y, n, m, g, ws.partial);
+    if (vec == WIDE)
+      hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     else
-      hipLaunchKernelGGL((colagg_kernel<Q, 1>), grid, block, 0, stream, Y, n, m, g, ws.partial);
+      hipLaunchKernelGGL((colagg_kernel<Q, T, 1>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     mark(stream);
     hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
     if (!fuse) {
@@ -1578,8 +1615,8 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
       mark(stream);
       hipLaunchKernelGGL(l11_init_kernel, dim3((unsigned)cdiv(m, WG)), block, 0, stream, n, m, ws);
       for (int s = 0; s < MAX_INNER_SWEEPS; ++s) {
-        if (vec == 4) hipLaunchKernelGGL((l11_sweep_kernel<4>), grid, block, 0, stream, Y, n, m, g, ws, s);
-        else hipLaunchKernelGGL((l11_sweep_kernel<1>), grid, block, 0, stream, Y, n, m, g, ws, s);
+        if (vec == WIDE) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws, s);
+        else hipLaunchKernelGGL((l11_sweep_kernel<T, 1>), grid, block, 0, stream, Y, n, m, g, ws, s);
         hipLaunchKernelGGL(l11_update_kernel, rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
       }
       hipLaunchKernelGGL(l11_close_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
@@ -1587,12 +1624,12 @@ static int run_bilevel(const float* Y, float* X, long long n, long long m, float
   }
   if (stages & STAGE_APPLY) {
     mark(stream);
-    if (vec == 4 && x_vec)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta, outer);
-    else if (vec == 4)
-      hipLaunchKernelGGL((colmap_kernel<Q, 4, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta, outer);
+    if (vec == WIDE && x_vec)
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+    else if (vec == WIDE)
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else
-      hipLaunchKernelGGL((colmap_kernel<Q, 1, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, fused_eta, outer);
+      hipLaunchKernelGGL((colmap_kernel<Q, T, 1, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
   }
   mark(stream);
   return launch_status();
@@ -1606,6 +1643,15 @@ static int dispatch_q(int variant, A... a) {
     case MLPROJ_L12: return run_bilevel<Q2>(a...);
     default: return MLPROJ_ERR_BAD_VARIANT;
   }
+}
+
+template <typename T>
+static int dispatch_stored(int outer, int variant, const void* Y, void* X, long long n, long long m,
+                           float eta, void* workspace, size_t workspace_bytes, float* v_out,
+                           float* u_out, unsigned char* mask_out, void* stream) {
+  return dispatch_q(variant, static_cast<const T*>(Y), static_cast<T*>(X), n, m, eta, workspace,
+                    workspace_bytes, v_out, u_out, stream, MODE_PROJECT, (double*)nullptr, STAGE_ALL,
+                    outer, mask_out);
 }
 
 // ------------------------------------------------------------------ host: multi-level driver
@@ -1775,7 +1821,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 300; }
+int mlproj_version(void) { return 310; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -1786,7 +1832,7 @@ const char* mlproj_status_string(int status) {
     case MLPROJ_ERR_BAD_RADIUS: return "eta must be finite and >= 0";
     case MLPROJ_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
     case MLPROJ_ERR_BAD_VARIANT: return "unknown variant";
-    case MLPROJ_ERR_ALIGNMENT: return "Y and X must be 4-byte aligned";
+    case MLPROJ_ERR_ALIGNMENT: return "Y and X must be aligned to their element size";
     case MLPROJ_ERR_LAUNCH: return "HIP refused a kernel launch";
     default: return "unknown status";
   }
@@ -1877,6 +1923,21 @@ int bilevel_proj_pq(int outer_norm, int variant, const float* Y, float* X, long 
                     void* stream) {
   return dispatch_q(variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, stream,
                     MODE_PROJECT, (double*)nullptr, STAGE_ALL, outer_norm);
+}
+
+int bilevel_proj_stored(int storage, int outer_norm, int variant, const void* Y, void* X,
+                        long long n, long long m, float eta, void* workspace,
+                        size_t workspace_bytes, float* v_out, float* u_out,
+                        unsigned char* mask_out, void* stream) {
+  switch (storage) {
+    case MLPROJ_STORE_F32:
+      return dispatch_stored<float>(outer_norm, variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    case MLPROJ_STORE_BF16:
+      return dispatch_stored<bf16_t>(outer_norm, variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    case MLPROJ_STORE_F16:
+      return dispatch_stored<f16_t>(outer_norm, variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    default: return MLPROJ_ERR_BAD_VARIANT;
+  }
 }
 
 int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1, long long d2,

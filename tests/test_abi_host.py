@@ -136,3 +136,22 @@ def test_general_outer_norm_argument_checks(lib):
     dims, norms = (LL * 3)(4, 5, 6), (I * 2)(0, 1)
     assert lib.multilevel_proj_p(5, FAKE, FAKE, 3, dims, norms, F(1), FAKE, big, None, None, None) == -6
     assert lib.multilevel_proj_p(1, FAKE, FAKE, 3, dims, norms, F(1), FAKE, 64, None, None, None) == -5
+
+
+def test_stored_entry_point_argument_checks(lib):
+    big = 1 << 30
+    st = lib.bilevel_proj_stored
+    odd2 = ctypes.c_void_p((1 << 20) + 2)      # 2-byte aligned only
+    odd1 = ctypes.c_void_p((1 << 20) + 1)
+    assert st(3, 0, 0, FAKE, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -6     # unknown storage
+    assert st(-1, 0, 0, FAKE, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -6
+    for storage in (0, 1, 2):
+        assert st(storage, 0, 0, None, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -1
+        assert st(storage, 0, 0, FAKE, None, 4, 4, F(1), FAKE, big, None, None, None, None) == -1
+        assert st(storage, 4, 0, FAKE, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -6
+        assert st(storage, 0, 3, FAKE, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -6
+        assert st(storage, 0, 0, FAKE, FAKE, 4, 0, F(1), FAKE, big, None, None, None, None) == -2
+        assert st(storage, 0, 0, FAKE, FAKE, 4, 4, F(-1), FAKE, big, None, None, None, None) == -4
+        assert st(storage, 0, 0, FAKE, FAKE, 4, 4, F(1), FAKE, 64, None, None, None, None) == -5
+        assert st(storage, 0, 0, odd1, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -7
+    assert st(0, 0, 0, odd2, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -7      # fp32 wants 4 bytes

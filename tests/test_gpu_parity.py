@@ -528,3 +528,117 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(mp):
             graph.replay()
             torch.cuda.synchronize()
             assert torch.equal(Xg, eager), (q, rep)
+
+
+# ------------------------------------------------------------------ 16-bit storage
+STORE_DTYPES = {"bf16": "bfloat16", "f16": "float16", "f32": "float32"}
+
+
+def stored_input(shape, storage, seed, scale=1.0):
+    rng = np.random.default_rng([shape[0], shape[1], seed])
+    Y = (rng.standard_normal(shape) * scale).astype(np.float32)
+    Y *= np.power(10.0, rng.uniform(-1.0, 0.0, shape[1])).astype(np.float32)[None, :]
+    return orc.round_to_storage(Y, storage)
+
+
+def run_stored(mp, Y, eta, q, storage, p=1, inplace=False, offset=0, x_offset=0):
+    """Y: fp32 array of storage-representable values; offset / x_offset shift the device
+    pointers by that many elements to reach the element-wise paths."""
+    dev = torch.device("cuda:0")
+    dt = getattr(torch, STORE_DTYPES[storage])
+    n, m = Y.shape
+    ybuf = torch.zeros(n * m + 16, dtype=dt, device=dev)
+    Yd = ybuf[offset:offset + n * m].view(n, m)
+    Yd.copy_(torch.from_numpy(Y).to(dev))
+    assert np.array_equal(Yd.float().cpu().numpy(), Y)
+    xbuf = torch.zeros(n * m + 16, dtype=dt, device=dev)
+    Xd = Yd if inplace else xbuf[x_offset:x_offset + n * m].view(n, m)
+    v = torch.full((m,), -1.0, dtype=torch.float32, device=dev)
+    u = torch.full((m,), -1.0, dtype=torch.float32, device=dev)
+    mask = torch.full((m,), 7, dtype=torch.uint8, device=dev)
+    ws = mp.Workspace.for_call(QNAME[q], n, m, device=dev)
+    X = mp.bilevel_proj_stored(Yd, eta, q, p=p, X=Xd, workspace=ws, v_out=v, u_out=u, mask_out=mask)
+    torch.cuda.synchronize()
+    if not inplace:   # nothing outside X's n*m elements was written
+        assert not xbuf[:x_offset].any() and not xbuf[x_offset + n * m:].any()
+    return {"X": X.float().cpu().numpy(), "v": v.cpu().numpy(), "u": u.cpu().numpy(),
+            "mask": mask.cpu().numpy(), "res": ws.result()}
+
+
+def check_stored(got, ref, q, storage):
+    """The fp32 bar (rtol 1e-5, atol 1e-6) applies before rounding; rounding is monotone, so the
+    stored value must lie between the roundings of the two ends of that interval."""
+    check_against_oracle({**got, "X": ref["X32"]}, {**ref, "X": ref["X32"]}, q)      # v, u, tau, support
+    assert np.array_equal(got["mask"], ref["mask"].astype(np.uint8))
+    x = ref["X32"].astype(np.float64)
+    tol = RTOL * np.abs(x) + ATOL
+    lo = orc.round_to_storage((x - tol).astype(np.float32), storage)
+    hi = orc.round_to_storage((x + tol).astype(np.float32), storage)
+    assert np.all((got["X"] >= lo) & (got["X"] <= hi))
+    assert np.mean(got["X"] != ref["X"]) < 0.02, "more than a few entries sit on a rounding boundary"
+    assert not got["X"][:, ~ref["mask"]].any()
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+@pytest.mark.parametrize("shape", [(1, 1), (9, 7), (300, 257), (2065, 264), (131, 1032), (40, 5000),
+                                   (8, 40000), (1000, 1024), (70, 4104)])
+def test_stored_matches_oracle(mp, storage, q, shape):
+    Y = stored_input(shape, storage, 31)
+    for frac in (0.05, 0.6):
+        eta = eta_for(Y, q, frac)
+        check_stored(run_stored(mp, Y, eta, q, storage), orc.bilevel_stored(Y, eta, q, storage), q, storage)
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16"])
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+def test_stored_inplace_unaligned_outer_norms_and_degenerate(mp, storage, q):
+    Y = stored_input((333, 520), storage, 32)
+    eta = eta_for(Y, q, 0.3)
+    ref = orc.bilevel_stored(Y, eta, q, storage)
+    check_stored(run_stored(mp, Y, eta, q, storage, inplace=True), ref, q, storage)
+    check_stored(run_stored(mp, Y, eta, q, storage, offset=1), ref, q, storage)        # Y 2-byte aligned
+    check_stored(run_stored(mp, Y, eta, q, storage, x_offset=3), ref, q, storage)      # only X misaligned
+    for p in (2, "inf"):
+        v = orc.column_norms(Y, q).astype(np.float64)
+        r = float(np.float32(0.4 * (np.sqrt((v * v).sum()) if p == 2 else v.max())))
+        check_stored(run_stored(mp, Y, r, q, storage, p=p), orc.bilevel_stored(Y, r, q, storage, p=p), q, storage)
+    big = float(np.float32(2 * orc.norm_l1q(Y, q)))                                       # inside the ball
+    got = run_stored(mp, Y, big, q, storage)
+    assert np.array_equal(got["X"], Y) and got["mask"].all() and got["res"]["inside_ball"]
+    got = run_stored(mp, Y, 0.0, q, storage)
+    assert not got["X"].any() and not got["mask"].any()
+
+
+def test_stored_f32_is_the_fp32_entry_point_bit_for_bit(mp):
+    dev = torch.device("cuda:0")
+    for q in ("inf", 1, 2):
+        Y = stored_input((700, 1028), "f32", 33)
+        eta = eta_for(Y, q, 0.2)
+        Yd = torch.from_numpy(Y).to(dev)
+        a = mp.bilevel_proj_pq(1, q, Yd, eta)
+        b = mp.bilevel_proj_stored(Yd, eta, q)
+        assert torch.equal(a, b)
+
+
+def test_stored_extreme_values(mp):
+    """fp16 at the ends of its range (largest finite, subnormals); bf16 across fp32's exponents."""
+    rng = np.random.default_rng(34)
+    Yh = rng.standard_normal((64, 96)).astype(np.float32)
+    Yh[:, :32] *= 2.0 ** -20            # subnormal fp16 territory after rounding
+    Yh[:, 32:64] *= 9000.0
+    Yh = np.clip(Yh, -65504.0, 65504.0)
+    Yh[0, 40] = 65504.0
+    Yh = orc.round_to_storage(Yh, "f16")
+    Yb = orc.round_to_storage((rng.standard_normal((64, 96)) * 10.0 ** rng.uniform(-12, 12, 96)).astype(np.float32), "bf16")
+    for Y, storage in ((Yh, "f16"), (Yb, "bf16")):
+        for q in ("inf", 1, 2):
+            eta = eta_for(Y, q, 0.5)
+            ref = orc.bilevel_stored(Y, eta, q, storage)
+            got = run_stored(mp, Y, eta, q, storage)
+            assert np.array_equal(got["mask"], ref["mask"].astype(np.uint8))
+            x = ref["X32"].astype(np.float64)
+            tol = RTOL * np.abs(x) + 1e-30
+            lo = orc.round_to_storage((x - tol).astype(np.float32), storage)
+            hi = orc.round_to_storage((x + tol).astype(np.float32), storage)
+            assert np.all((got["X"] >= lo) & (got["X"] <= hi))
