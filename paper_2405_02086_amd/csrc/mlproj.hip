@@ -36,6 +36,9 @@ constexpr int SWAVES = SWG / WAVE;
 constexpr int SEARCH_CACHE = 16;         // values of v per search thread kept in registers
 constexpr int MAX_INNER_SWEEPS = 24;     // l1,1: passes over Y allowed to the inner searches
 constexpr double L11_WINDOW = 1.0 / 16;  // l1,1: relative width of the window that samples the density
+constexpr int FILTER_LDS_SLOTS = 8192;   // l1,1: entries a workgroup can stage for its tile (32 KiB of LDS)
+constexpr int FILTER_MAX_LIST = 256;     // l1,1: entries kept per column
+constexpr unsigned NO_COUNT = 0xffffffffu;
 constexpr int QINF = MLPROJ_L1INF, Q1 = MLPROJ_L11, Q2 = MLPROJ_L12;
 constexpr int MODE_PROJECT = 0, MODE_NORM = 1;
 constexpr int MAP_UNROLL = 4;            // rows in flight per wavefront in the map pass (x2: pipelined)
@@ -69,8 +72,16 @@ struct Ws {
   unsigned* coop_u;        // [2][COOP_MAX_WGS] per-workgroup counts, by parity
   unsigned* flags;         // [0] arrivals at the grid-wide search's barrier, [1] that search gave up
   double* v;               // [groups] aggregate, fp64 (exact for q = inf)
-  double* tauj;            // [m] l1,1 inner thresholds
-  unsigned* kprev;         // [m] l1,1 previous active counts
+  double* tauj;            // [m] l1,1 inner thresholds: the point the next sweep evaluates, then the result
+  double* tlo;             // [m] l1,1: lower end of the window whose entries the next sweep lists
+  double* lb;              // [m] l1,1: certified lower bound on the threshold
+  double* ub;              // [m] l1,1: certified upper bound
+  unsigned* kprev;         // [m] l1,1: active count at the point whose Newton step is tlo, or NO_COUNT
+  unsigned* done;          // [m] l1,1: 1 once tauj is final
+  unsigned* gcnt;          // [m] l1,1: entries in the window, all workgroups
+  unsigned* gflag;         // [m] l1,1: some workgroup could not stage all of its window entries
+  float* cand;             // [list_cap][m] l1,1: the window entries, slot-major
+  int list_cap;            // slots per column in cand
   void* partial;           // [tiles][groups][tile_w] float (q = inf) or double
   unsigned* partial_cnt;   // [tiles][groups][tile_w] l1,1: entries above t
   unsigned* partial_cnt2;  // [tiles][groups][tile_w] l1,1: entries above t*(1 + L11_WINDOW)
@@ -78,6 +89,8 @@ struct Ws {
 
 struct Layout {
   size_t off_pending, off_coop_d, off_coop_m, off_coop_u, off_flags, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, off_partial_cnt2, bytes;
+  size_t off_tlo, off_lb, off_ub, off_done, off_gcnt, off_gflag, off_cand;
+  int list_cap;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -120,6 +133,16 @@ static Geometry plan_slabs(long long d0, long long len, int vec) {
   return g;
 }
 
+// Threads per group in the kernels that fold per-(tile, row group) partials: a power of two,
+// at most 16, chosen from the number of partials per group.
+static int reduce_parts(long long partials_per_group) {
+  int parts = 1;
+  while (parts < SWAVES && parts < partials_per_group) parts *= 2;
+  return parts;
+}
+
+constexpr int LIST_PER_THREAD = 32;      // l1,1: listed entries one update thread holds in registers
+
 static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   Layout L{};
   size_t o = align_up(sizeof(mlproj_result), 256);
@@ -135,6 +158,20 @@ static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   L.off_partial = o;       o = align_up(o + cells * 8, 256);
   L.off_partial_cnt = o;   o = align_up(o + (variant == Q1 ? cells * 4 : 0), 256);
   L.off_partial_cnt2 = o;  o = align_up(o + (variant == Q1 ? cells * 4 : 0), 256);
+  // l1,1: a column's list takes what its row groups can stage together, up to FILTER_MAX_LIST
+  // and what the update kernel's threads of that column can hold in registers
+  long long staged = g.groups * (FILTER_LDS_SLOTS / (g.tile_w > 0 ? g.tile_w : 1));
+  if (staged > FILTER_MAX_LIST) staged = FILTER_MAX_LIST;
+  if (staged > (long long)LIST_PER_THREAD * reduce_parts(g.groups)) staged = (long long)LIST_PER_THREAD * reduce_parts(g.groups);
+  L.list_cap = (int)staged;
+  const size_t per_col8 = variant == Q1 ? (size_t)ngroups * 8 : 0, per_col4 = variant == Q1 ? (size_t)ngroups * 4 : 0;
+  L.off_tlo = o;           o = align_up(o + per_col8, 256);
+  L.off_lb = o;            o = align_up(o + per_col8, 256);
+  L.off_ub = o;            o = align_up(o + per_col8, 256);
+  L.off_done = o;          o = align_up(o + per_col4, 256);
+  L.off_gcnt = o;          o = align_up(o + per_col4, 256);
+  L.off_gflag = o;         o = align_up(o + per_col4, 256);
+  L.off_cand = o;          o = align_up(o + per_col4 * (size_t)L.list_cap, 256);
   L.bytes = o;
   return L;
 }
@@ -154,6 +191,14 @@ static Ws bind(void* workspace, const Layout& L) {
   w.partial = b + L.off_partial;
   w.partial_cnt = reinterpret_cast<unsigned*>(b + L.off_partial_cnt);
   w.partial_cnt2 = reinterpret_cast<unsigned*>(b + L.off_partial_cnt2);
+  w.tlo = reinterpret_cast<double*>(b + L.off_tlo);
+  w.lb = reinterpret_cast<double*>(b + L.off_lb);
+  w.ub = reinterpret_cast<double*>(b + L.off_ub);
+  w.done = reinterpret_cast<unsigned*>(b + L.off_done);
+  w.gcnt = reinterpret_cast<unsigned*>(b + L.off_gcnt);
+  w.gflag = reinterpret_cast<unsigned*>(b + L.off_gflag);
+  w.cand = reinterpret_cast<float*>(b + L.off_cand);
+  w.list_cap = L.list_cap;
   return w;
 }
 
@@ -412,12 +457,6 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, lon
 // covers 1024/parts groups with `parts` threads each (parts = 1..16, a power of two chosen on
 // the host from the number of partials per group); every thread keeps 8 loads in flight.
 // Serves columns (tile_w = 64*vec) and slabs (tile_w = 1) alike.
-static int reduce_parts(long long partials_per_group) {
-  int parts = 1;
-  while (parts < SWAVES && parts < partials_per_group) parts *= 2;
-  return parts;
-}
-
 template <int Q>
 __global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ partial_,
                                                      long long ngroups, Geometry g, int parts,
@@ -860,23 +899,40 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
 // ------------------------------------------------------------------ l1,1: inner searches
 // Alg. 3 needs, for every kept column, the threshold tau_j with
 // f_j(tau_j) = sum_i max(|Y_ij| - tau_j, 0) = u_j.  f_j is convex, decreasing and piecewise
-// linear, and one sweep over Y gives every column the sum S and count K of its entries above
-// its current point t, i.e. f_j(t) and its slope -K; the Newton step t' = (S - u_j)/K then
-// lands at or left of the root from ANY t (the tangent of a convex function lies below it),
-// and from the left the steps rise monotonically.  When two consecutive points see the same
-// count there is no entry between them, f_j is linear there and t' is the exact root, in
-// fp64.  All columns step in lock step: sweep kernel, then a small update kernel.
-// The first point is a guess (l11_init_kernel).  The sweep also counts the entries above
-// t*(1 + L11_WINDOW); at the guess that gives the local density of entries, i.e. the
-// curvature of f_j, and the first move solves the quadratic model instead of the tangent.
-// That move carries no guarantee, so the count is forgotten after it and the Newton steps
-// that follow restore the invariants.  Typically three or four sweeps suffice.
-// pending[s] is the number of columns still open before sweep s; both kernels of a sweep
+// linear.  One pass over Y gives every column the sum S and count K of its entries above a
+// point t, i.e. f_j(t) = S - K t and its slope -K; the Newton step N(t) = (S - u_j)/K lands at
+// or left of the root from ANY t (the tangent of a convex function lies below it).
+// All columns step in lock step, a pass over Y and then a small update kernel per sweep:
+//   sweep 0  evaluates a guess g (l11_init_kernel) and counts the entries in (g, g(1+1/16)]:
+//            value, slope and density give a quadratic model of f_j, whose root t is the
+//            estimate, with an error bar delta from the size of the move and the density;
+//   sweep s  evaluates hi = t + delta and LISTS the entries in the window (lo, hi],
+//            lo = t - delta (l11_filter_kernel).  With the few listed entries f_j is known on
+//            the whole window: if f_j(lo) >= u_j >= f_j(hi) the root is found among them
+//            exactly, in fp64, as in the outer search.  Otherwise the evaluated points tighten
+//            the certified bounds lb <= tau_j <= ub (Newton steps from below, points with
+//            f_j <= u_j from above) and the model gives the next window.
+// A column is also closed when the count at a Newton point N(p) equals the count at p (no
+// entry between them: f_j is linear there and N(p) is the root), or when the bounds meet.
+// On Gaussian data two sweeps close every column; heavy tails take a few more.
+// pending[s] is the number of columns still open before sweep s; the kernels of a sweep
 // return at once when it is zero.
+//
+// A window is kept within a factor 2 (hi <= 2 lo), so its entries differ by at most one
+// binary exponent and any fp64 sum of them is exact: the order in which workgroups append
+// to a column's list does not reach the result, which stays bit-reproducible.
+
+// The smallest float strictly above t: a float a satisfies a > t exactly when a >= above(t).
+__device__ __forceinline__ float above(double t) {
+  float f = (float)t;
+  if ((double)f <= t) f = nextafterf(f, INFINITY);
+  return f;
+}
+
+// Sweep 0: sum and count of the entries above t = tauj, count above t*(1 + L11_WINDOW).
 template <typename T, int VEC>
 __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, long long n,
-                                                       long long m, Geometry g, Ws ws,
-                                                       int sweep) {
+                                                       long long m, Geometry g, Ws ws) {
   constexpr int TILE_W = WAVE * VEC;
   __shared__ double sm_sum[WAVES][TILE_W];
   __shared__ unsigned sm_cnt[WAVES][TILE_W];
@@ -884,7 +940,6 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
 
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
-  if (sweep > 0 && ws.pending[sweep] == 0u) return;
 
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
@@ -898,36 +953,39 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
   for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; cnt2[k] = 0u; }
 
   if (col0 < m) {
-    double tj[VEC], tw[VEC];
+    // The entries are fp32 (or narrower), so "a > t" with t in fp64 is "a >= above(t)" in fp32.
+    float cj[VEC], cw[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-      tj[k] = ws.tauj[col0 + k];
-      tw[k] = tj[k] * (1.0 + L11_WINDOW);
+      const double tj = ws.tauj[col0 + k];
+      cj[k] = above(tj);
+      cw[k] = above(tj * (1.0 + L11_WINDOW));
     }
+    auto visit = [&](float y, int k) {
+      const float a = fabsf(y);
+      const bool in = a >= cj[k];
+      sum[k] += (double)(in ? a : 0.0f);
+      cnt[k] += in ? 1u : 0u;
+      cnt2[k] += a >= cw[k] ? 1u : 0u;
+    };
     const T* p = Y + col0;
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
-      float x[UNROLL][VEC];
+      Pack<T, VEC> x[UNROLL];
 #pragma unroll
-      for (int r = 0; r < UNROLL; ++r) load_row<VEC>(p + (r0 + wave + (long long)r * WAVES) * m, x[r]);
+      for (int r = 0; r < UNROLL; ++r)
+        x[r] = *reinterpret_cast<const Pack<T, VEC>*>(p + (r0 + wave + (long long)r * WAVES) * m);
+      __builtin_amdgcn_sched_barrier(0);  // every load of the block is in flight before the first use
 #pragma unroll
       for (int r = 0; r < UNROLL; ++r)
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-          const double a = (double)fabsf(x[r][k]);
-          if (a > tj[k]) { sum[k] += a; ++cnt[k]; }
-          cnt2[k] += a > tw[k] ? 1u : 0u;
-        }
+        for (int k = 0; k < VEC; ++k) visit((float)x[r].e[k], k);
     }
     for (long long i = r0 + wave; i < n; i += WAVES) {
       float x[VEC];
       load_row<VEC>(p + i * m, x);
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) {
-        const double a = (double)fabsf(x[k]);
-        if (a > tj[k]) { sum[k] += a; ++cnt[k]; }
-        cnt2[k] += a > tw[k] ? 1u : 0u;
-      }
+      for (int k = 0; k < VEC; ++k) visit(x[k], k);
     }
   }
 #pragma unroll
@@ -953,11 +1011,132 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
   }
 }
 
+// Sweeps 1, 2, ...: sum and count of the entries above hi = tauj, and the entries in
+// (tlo, hi] themselves.  A workgroup stages the window entries of its tile's columns in LDS
+// (FILTER_LDS_SLOTS / TILE_W slots per column), then reserves room in each column's list with
+// one atomic add per column and copies them out.  gcnt ends as the true number of window
+// entries of the column whether or not they all fitted; gflag marks a column some workgroup
+// could not stage completely.
+template <typename T, int VEC>
+__global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y, long long n,
+                                                        long long m, Geometry g, Ws ws,
+                                                        int sweep) {
+  constexpr int TILE_W = WAVE * VEC;
+  constexpr int CAPW = FILTER_LDS_SLOTS / TILE_W;
+  __shared__ double sm_sum[WAVES][TILE_W];
+  __shared__ unsigned sm_cnt[WAVES][TILE_W];
+  __shared__ float staged[CAPW][TILE_W];   // slot-major: the lanes of a wavefront hit different banks
+  __shared__ unsigned staged_cnt[TILE_W];
+
+  const mlproj_result* res = ws.res;
+  if (res->inside_ball != 0u || res->n_active == 0u) return;
+  if (ws.pending[sweep] == 0u) return;
+
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave = threadIdx.x / WAVE;
+  const long long t = blockIdx.x % g.tiles;
+  const long long grp = blockIdx.x / g.tiles;
+  const long long col0 = t * TILE_W + (long long)lane * VEC;
+
+  for (int c = threadIdx.x; c < TILE_W; c += WG) staged_cnt[c] = 0u;
+  __syncthreads();
+
+  double sum[VEC];
+  unsigned cnt[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; }
+
+  if (col0 < m) {
+    float chi[VEC], clo[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      chi[k] = above(ws.tauj[col0 + k]);
+      clo[k] = above(ws.tlo[col0 + k]);
+    }
+    // One row of the lane's columns.  Window entries are rare, so the row is tested as a
+    // whole and the staging code runs only for rows that have one.
+    auto visit_row = [&](const float (&y)[VEC]) {
+      bool any = false;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        const float a = fabsf(y[k]);
+        const bool in = a >= chi[k];
+        sum[k] += (double)(in ? a : 0.0f);
+        cnt[k] += in ? 1u : 0u;
+        any |= (a >= clo[k]) != in;   // clo <= chi: "above lo but not above hi"
+      }
+      if (any) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          const float a = fabsf(y[k]);
+          if (a >= clo[k] && !(a >= chi[k])) {
+            const int c = lane * VEC + k;
+            const unsigned slot = atomicAdd(&staged_cnt[c], 1u);
+            if (slot < (unsigned)CAPW) staged[slot][c] = a;
+          }
+        }
+      }
+    };
+    const T* p = Y + col0;
+    long long r0 = grp * RBLK;
+    for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
+      Pack<T, VEC> x[UNROLL];
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r)
+        x[r] = *reinterpret_cast<const Pack<T, VEC>*>(p + (r0 + wave + (long long)r * WAVES) * m);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r) {
+        float y[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) y[k] = (float)x[r].e[k];
+        visit_row(y);
+      }
+    }
+    for (long long i = r0 + wave; i < n; i += WAVES) {
+      float y[VEC];
+      load_row<VEC>(p + i * m, y);
+      visit_row(y);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) {
+    sm_sum[wave][lane * VEC + k] = sum[k];
+    sm_cnt[wave][lane * VEC + k] = cnt[k];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < TILE_W; c += WG) {
+    double a = sm_sum[0][c];
+    unsigned k = sm_cnt[0][c];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) {
+      a += sm_sum[w][c];
+      k += sm_cnt[w][c];
+    }
+    const size_t cell = ((size_t)t * g.groups + grp) * TILE_W + c;
+    static_cast<double*>(ws.partial)[cell] = a;
+    ws.partial_cnt[cell] = k;
+    const long long col = t * TILE_W + c;
+    const unsigned r = staged_cnt[c];
+    if (col < m && r > 0u) {
+      if (r > (unsigned)CAPW) {
+        ws.gflag[col] = 1u;
+        atomicAdd(&ws.gcnt[col], r);
+      } else {
+        const unsigned off = atomicAdd(&ws.gcnt[col], r);
+        for (unsigned s = 0; s < r && off + s < (unsigned)ws.list_cap; ++s)
+          ws.cand[(size_t)(off + s) * (size_t)m + (size_t)col] = staged[s][c];
+      }
+    }
+  }
+}
+
 // Starting points of the inner searches.  Dropped columns get +inf (every entry maps to 0).
 // For a kept column the guess assumes its entries are Gaussian with the scale its l1 norm
 // implies: E|y| = sigma*sqrt(2/pi) = v_j/n and E max(|y| - t, 0) = sigma*h(t/sigma) with
 // h(z) = 2*phi(z) - z*erfc(z/sqrt 2), so z solves h(z) = (u_j/v_j)*sqrt(2/pi) (a few Newton
 // steps on the convex h) and the guess is sigma*z.  Only the speed depends on the guess.
+// The first certified bounds: every entry active gives the lower bound (v_j - u_j)/n.
 __global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, Ws ws) {
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
@@ -965,21 +1144,75 @@ __global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, 
   if (j >= m) return;
   const double vj = ws.v[j];
   const double uj = radius(vj, top_of(res));
-  double tj = HUGE_VAL;
+  double tj = HUGE_VAL, floor_t = HUGE_VAL;
   if (uj > 0.0) {
-    const double c = (uj / vj) * 0.7978845608028654;  // sqrt(2/pi)
-    double z = 0.0;
+    // (fp32 is plenty here: the guess is a statistical estimate, off by percents)
+    const float c = (float)(uj / vj) * 0.79788456f;  // sqrt(2/pi)
+    float z = 0.0f;
     for (int it = 0; it < 8; ++it) {
-      const double tail = erfc(z * 0.7071067811865476);            // 2*(1 - Phi(z))
-      const double h = 0.7978845608028654 * exp(-0.5 * z * z) - z * tail;
-      if (!(tail > 1e-300)) break;
+      const float tail = erfcf(z * 0.70710678f);                  // 2*(1 - Phi(z))
+      const float h = 0.79788456f * expf(-0.5f * z * z) - z * tail;
+      if (!(tail > 1e-30f)) break;
       z += (h - c) / tail;
     }
     const double sigma = (vj / (double)n) * 1.2533141373155001;   // sqrt(pi/2)
-    tj = fmax(sigma * z, (vj - uj) / (double)n);  // never below the all-active bound
+    floor_t = fmax((vj - uj) / (double)n, 0.0);
+    tj = fmax(sigma * (double)z, floor_t);  // never below the all-active bound
   }
   ws.tauj[j] = tj;
-  ws.kprev[j] = 0xffffffffu;
+  ws.tlo[j] = tj;
+  ws.lb[j] = floor_t;
+  ws.ub[j] = HUGE_VAL;
+  ws.kprev[j] = NO_COUNT;
+  ws.done[j] = uj > 0.0 ? 0u : 1u;
+  ws.gcnt[j] = 0u;
+  ws.gflag[j] = 0u;
+}
+
+// Root of the local model of f_j - u_j: value fb, slope -kb, entry density rho at the base
+// point, fb - kb d + rho d^2 / 2 = 0 for the move d (the root next to the base point, in the
+// form that does not cancel); the tangent alone when no density is known.
+__device__ __forceinline__ double model_step(double fb, double kb, double rho) {
+  const double disc = kb * kb - 2.0 * rho * fb;
+  if (rho > 0.0 && disc > 0.0) {
+    const double den = kb + sqrt(disc);
+    if (den > 0.0) return 2.0 * fb / den;
+  }
+  return kb > 0.0 ? fb / kb : 0.0;
+}
+
+struct Window {
+  double lo, hi;
+  unsigned kp;  // count at the point whose Newton step is lo, or NO_COUNT
+};
+
+// The next window: the model's root +- an error bar (a quarter of the move plus six entries'
+// worth of spacing, at most an eighth of the list's capacity), cut to the certified bounds
+// [lb, ub] and to a factor 2.  `stuck`: nothing was seen at or below the point: step from lb.
+__device__ __forceinline__ Window next_window(double base, double fb, double kb, double rho,
+                                              double lb, unsigned k_lb, double ub, bool stuck,
+                                              int list_cap) {
+  Window w;
+  w.kp = NO_COUNT;
+  if (stuck) {
+    w.lo = w.hi = lb;
+    return w;
+  }
+  const double d = model_step(fb, kb, rho);
+  const double t = base + d;
+  double delta = 0.25 * fabs(d);
+  if (rho > 0.0) delta = fmin(delta + 6.0 / rho, 0.125 * (double)list_cap / rho);
+  double lo = t - delta, hi = t + delta;
+  if (!(lo > lb)) {
+    lo = lb;
+    w.kp = k_lb;
+  }
+  hi = fmax(hi, lo);
+  hi = fmin(hi, fmax(ub, lo));
+  hi = fmin(hi, 2.0 * lo);
+  w.lo = lo;
+  w.hi = hi;
+  return w;
 }
 
 __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long m, Geometry g,
@@ -987,6 +1220,8 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
   __shared__ double sm_sum[SWG];
   __shared__ unsigned sm_cnt[SWG];
   __shared__ unsigned sm_cnt2[SWG];
+  __shared__ double col_t[SWG];       // per column of this workgroup: the point of the current round
+  __shared__ unsigned col_live[SWG];  // ... and whether its window is still being solved
   __shared__ BlockScratch<SWAVES> bs;
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
@@ -996,8 +1231,18 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
   const int c_local = threadIdx.x % cols;
   const int part = threadIdx.x / cols;
   const long long j = (long long)blockIdx.x * cols + c_local;
+  const bool mine = j < m && ws.done[j] == 0u;
+
+  // Fold the partial sums and counts of the sweep; the `parts` threads of a column also split
+  // the column's listed window entries between them, in registers.
   double S = 0.0;
   unsigned K = 0u, K2 = 0u;
+  unsigned r = 0u;
+  bool complete = false;
+  float mylist[LIST_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < LIST_PER_THREAD; ++i) mylist[i] = 0.0f;
+  double my_sum = 0.0;
   if (j < m) {
     const long long t = j / g.tile_w, c = j % g.tile_w;
     const size_t base = (size_t)t * g.groups * g.tile_w + c;
@@ -1005,50 +1250,145 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
     for (long long b = part; b < g.groups; b += parts) {
       S += ps[base + (size_t)b * g.tile_w];
       K += ws.partial_cnt[base + (size_t)b * g.tile_w];
-      K2 += ws.partial_cnt2[base + (size_t)b * g.tile_w];
+      if (sweep == 0) K2 += ws.partial_cnt2[base + (size_t)b * g.tile_w];
+    }
+    if (sweep > 0 && mine) {
+      r = ws.gcnt[j];
+      complete = ws.gflag[j] == 0u && r <= (unsigned)ws.list_cap;
+      if (complete) {
+#pragma unroll
+        for (int i = 0; i < LIST_PER_THREAD; ++i) {
+          const unsigned s = (unsigned)part + (unsigned)i * (unsigned)parts;
+          if (s < r) mylist[i] = ws.cand[(size_t)s * (size_t)m + (size_t)j];
+          my_sum += (double)mylist[i];
+        }
+      }
     }
   }
   sm_sum[threadIdx.x] = S;
   sm_cnt[threadIdx.x] = K;
   sm_cnt2[threadIdx.x] = K2;
+  col_t[threadIdx.x] = my_sum;   // (borrowed for the fold of the listed entries' sums)
   __syncthreads();
+
+  bool closed = false, decided = false, solving = false;
+  double tau = 0.0, uj = 0.0, lo = 0.0, lb = 0.0, ub = 0.0;
+  Window w{0.0, 0.0, NO_COUNT};
+  unsigned kp = NO_COUNT;
+  if (part == 0 && mine) {
+    double sc = my_sum;
+    for (int p = 1; p < parts; ++p) {
+      S += sm_sum[p * cols + c_local];
+      K += sm_cnt[p * cols + c_local];
+      K2 += sm_cnt2[p * cols + c_local];
+      sc += col_t[p * cols + c_local];
+    }
+    decided = true;
+    uj = radius(ws.v[j], top_of(res));
+    const double hi = ws.tauj[j];
+    lo = ws.tlo[j];
+    lb = ws.lb[j];
+    ub = ws.ub[j];
+    unsigned k_lb = NO_COUNT;  // count at the point whose Newton step is lb, when lb moved now
+    tau = hi;
+    w = Window{hi, hi, NO_COUNT};
+    const double f_hi = (S - (double)K * hi) - uj;
+    const double n_hi = K > 0u ? (S - uj) / (double)K : -HUGE_VAL;
+    if (sweep == 0) {
+      // evaluated at the guess hi = lo, density from the entries in (hi, hi(1 + 1/16)]
+      if (n_hi > lb) { lb = n_hi; k_lb = K; }
+      if (f_hi <= 0.0) ub = fmin(ub, hi);
+      const double rho = (double)(K - K2) / (hi * L11_WINDOW);
+      if (ub <= lb * (1.0 + 1e-12)) { closed = true; tau = lb; }
+      else w = next_window(hi, f_hi, (double)K, rho, lb, k_lb, ub, K == 0u, ws.list_cap);
+    } else {
+      const unsigned k_lo = K + r;  // entries above lo
+      double f_lo = 0.0, n_lo = -HUGE_VAL;
+      if (complete) {
+        const double s_lo = S + sc;
+        f_lo = (s_lo - (double)k_lo * lo) - uj;
+        if (k_lo > 0u) n_lo = (s_lo - uj) / (double)k_lo;
+      }
+      if (ws.kprev[j] != NO_COUNT && k_lo == ws.kprev[j]) {
+        closed = true;  // lo is the Newton step of a point with the same active set
+        tau = lo;
+      } else if (K > 0u && fabs(f_hi) <= 1e-13 * (S + uj)) {
+        closed = true;  // the Newton step from hi does not move: hi is the root, to rounding
+        tau = n_hi;
+      } else if (complete && f_lo >= 0.0 && f_hi <= 0.0) {
+        closed = true;  // the root is inside the window and every entry of the window is known
+        solving = true;
+      } else {
+        if (n_hi > lb) { lb = n_hi; k_lb = K; }
+        if (complete && n_lo > lb) { lb = n_lo; k_lb = k_lo; }
+        if (f_hi <= 0.0) ub = fmin(ub, hi);
+        if (complete && f_lo <= 0.0) ub = fmin(ub, lo);
+        if (ub <= lb * (1.0 + 1e-12)) { closed = true; tau = lb; }
+        else {
+          const double rho = (hi > lo && r > 0u) ? (double)r / (hi - lo) : 0.0;
+          const bool from_lo = complete && fabs(f_lo) < fabs(f_hi);
+          w = next_window(from_lo ? lo : hi, from_lo ? f_lo : f_hi, (double)(from_lo ? k_lo : K),
+                          rho, lb, k_lb, ub, K == 0u && r == 0u, ws.list_cap);
+        }
+      }
+    }
+  }
+
+  // The root inside a window whose entries are all listed: the fixed point of the outer
+  // search on "entries above hi" (S, K) plus the listed ones, started at lo where f_j >= u_j;
+  // every column of the workgroup that needs it runs its rounds together.
+  __syncthreads();
+  if (part == 0) {
+    col_t[c_local] = lo;
+    col_live[c_local] = solving ? 1u : 0u;
+    tau = solving ? lo : tau;
+  }
+  int any = __syncthreads_or(solving ? 1 : 0);
+  for (unsigned round = 0; any && round < (unsigned)FILTER_MAX_LIST + 2u; ++round) {
+    const double t = col_t[c_local];
+    double sa = 0.0;
+    unsigned ka = 0u;
+    if (col_live[c_local] != 0u) {
+#pragma unroll
+      for (int i = 0; i < LIST_PER_THREAD; ++i)
+        if ((double)mylist[i] > t) { sa += (double)mylist[i]; ++ka; }
+    }
+    sm_sum[threadIdx.x] = sa;
+    sm_cnt[threadIdx.x] = ka;
+    __syncthreads();
+    if (solving) {
+      for (int p = 1; p < parts; ++p) {
+        sa += sm_sum[p * cols + c_local];
+        ka += sm_cnt[p * cols + c_local];
+      }
+      ka += K;
+      const double tn = ka > 0u ? ((S + sa) - uj) / (double)ka : tau;
+      if (ka == kp || ka == 0u) {
+        tau = tn;
+        solving = false;
+        col_live[c_local] = 0u;
+      } else {
+        kp = ka;
+        tau = fmax(tau, tn);
+        col_t[c_local] = tau;
+      }
+    }
+    any = __syncthreads_or(solving ? 1 : 0);
+  }
+
   unsigned open = 0u;
   if (part == 0 && j < m) {
-    for (int w = 1; w < parts; ++w) {
-      S += sm_sum[w * cols + c_local];
-      K += sm_cnt[w * cols + c_local];
-      K2 += sm_cnt2[w * cols + c_local];
+    if (decided) {
+      ws.tauj[j] = closed ? tau : w.hi;
+      ws.tlo[j] = closed ? tau : w.lo;
+      ws.kprev[j] = w.kp;
+      ws.lb[j] = lb;
+      ws.ub[j] = ub;
+      ws.done[j] = closed ? 1u : 0u;
+      open = closed ? 0u : 1u;
     }
-    const double vj = ws.v[j];
-    const double uj = radius(vj, top_of(res));
-    const double floor_t = (vj - uj) / (double)n;  // every entry active: a lower bound on the root
-    if (uj > 0.0) {
-      double tj = ws.tauj[j];
-      const unsigned kp = ws.kprev[j];
-      if (K == 0u) {
-        // the guess overshot every entry: restart from the all-active lower bound
-        tj = floor_t;
-        K = 0xffffffffu;
-        open = 1u;
-      } else if (sweep == 0) {
-        // at the guess g: residual r = f(g) - u, slope -K, curvature rho (entries per unit
-        // just above g); solve r - K d + rho d^2 / 2 = 0 for the move d, in the stable form
-        const double r = (S - (double)K * tj) - uj;
-        const double rho = (double)(K - K2) / (tj * L11_WINDOW);
-        const double disc = (double)K * (double)K - 2.0 * rho * r;
-        const double d = (rho > 0.0 && disc > 0.0) ? 2.0 * r / ((double)K + sqrt(disc)) : r / (double)K;
-        tj = fmax(tj + d, floor_t);
-        K = 0xffffffffu;  // not a Newton point: the next count comparison must not conclude
-        open = 1u;
-      } else {
-        const double tn = (S - uj) / (double)K;
-        // after a free move any Newton point is taken; afterwards the points only rise
-        tj = (kp == 0xffffffffu) ? tn : fmax(tj, tn);
-        open = (K != kp) ? 1u : 0u;
-      }
-      ws.tauj[j] = tj;
-      ws.kprev[j] = K;
-    }
+    ws.gcnt[j] = 0u;
+    ws.gflag[j] = 0u;
   }
   const unsigned wg_open = block_sum_u(open, bs);
   if (threadIdx.x == 0) {
@@ -1615,8 +1955,13 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       mark(stream);
       hipLaunchKernelGGL(l11_init_kernel, dim3((unsigned)cdiv(m, WG)), block, 0, stream, n, m, ws);
       for (int s = 0; s < MAX_INNER_SWEEPS; ++s) {
-        if (vec == WIDE) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws, s);
-        else hipLaunchKernelGGL((l11_sweep_kernel<T, 1>), grid, block, 0, stream, Y, n, m, g, ws, s);
+        if (s == 0) {
+          if (vec == WIDE) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws);
+          else hipLaunchKernelGGL((l11_sweep_kernel<T, 1>), grid, block, 0, stream, Y, n, m, g, ws);
+        } else {
+          if (vec == WIDE) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws, s);
+          else hipLaunchKernelGGL((l11_filter_kernel<T, 1>), grid, block, 0, stream, Y, n, m, g, ws, s);
+        }
         hipLaunchKernelGGL(l11_update_kernel, rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
       }
       hipLaunchKernelGGL(l11_close_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
