@@ -642,3 +642,41 @@ def test_stored_extreme_values(mp):
             lo = orc.round_to_storage((x - tol).astype(np.float32), storage)
             hi = orc.round_to_storage((x + tol).astype(np.float32), storage)
             assert np.all((got["X"] >= lo) & (got["X"] <= hi))
+
+
+# ------------------------------------------------------------------ l1,1 inner searches on hard inputs
+def _hard_family(name, rng, n, m):
+    if name == "cauchy":
+        return rng.standard_cauchy((n, m))
+    if name == "lognormal3":
+        return rng.lognormal(0.0, 3.0, (n, m)) * rng.choice([-1.0, 1.0], (n, m))
+    if name == "sparse":
+        return rng.standard_normal((n, m)) * (rng.uniform(size=(n, m)) < 0.01)
+    if name == "clusters":
+        return np.where(rng.uniform(size=(n, m)) < 0.5, 1 + 0.01 * rng.standard_normal((n, m)),
+                        10 + 0.1 * rng.standard_normal((n, m)))
+    if name == "constant":
+        return np.full((n, m), -2.5)
+    if name == "integers":
+        return rng.integers(-7, 8, (n, m)).astype(np.float64)
+    if name == "geometric":
+        return np.tile((0.999 ** np.arange(n))[:, None], (1, m))
+    if name == "uniform":
+        return rng.uniform(size=(n, m))
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("family", ["cauchy", "lognormal3", "sparse", "clusters", "constant", "integers",
+                                    "geometric", "uniform"])
+def test_l11_inner_searches_converge_on_hard_distributions(mp, family):
+    """Heavy tails, clusters, ties and constant columns: the windowed lock-step search must
+    close every column (inner_pending == 0, checked by check_against_oracle) well inside its
+    sweep limit, and match the oracle's sort-based thresholds."""
+    rng = np.random.default_rng([len(family), 77])
+    n, m = 4099, 300
+    Y = _hard_family(family, rng, n, m).astype(np.float32)
+    for frac in (0.001, 0.1, 0.5, 0.95):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert got["res"]["inner_sweeps"] <= 12, (family, frac, got["res"]["inner_sweeps"])
