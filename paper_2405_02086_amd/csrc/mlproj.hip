@@ -109,8 +109,8 @@ static Geometry plan_columns(long long n, long long m, int vec, int variant) {
   if (grp > max_grp) grp = max_grp;
   if (grp < 1) grp = 1;
   g.groups = grp;
-  // the l1,1 map does fp64 arithmetic per element and wants the second workgroup per CU
-  long long mg = cdiv(variant == Q1 ? TARGET_WGS : TARGET_WGS_MAP, g.tiles);
+  (void)variant;
+  long long mg = cdiv(TARGET_WGS_MAP, g.tiles);
   const long long max_mg = cdiv(n, MAP_RBLK);
   if (mg > max_mg) mg = max_mg;
   if (mg < 1) mg = 1;
@@ -856,6 +856,15 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
     else if constexpr (Q == Q1) par[k] = inside ? 0.0 : (uj > 0.0 ? ws.tauj[col0 + k] : HUGE_VAL);
     else par[k] = 0.0;
   }
+  // q = 1: tau_j as an unevaluated fp32 pair, tau_j = th + tl to 2^-48 relative.  |y| - th is
+  // exact while |y| <= 2 th (the only place cancellation can occur) and carries one fp32
+  // rounding beyond that, so (|y| - th) - tl stays within two fp32 units of the fp64 result.
+  float th[VEC], tl[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) {
+    th[k] = (float)par[k];
+    tl[k] = (Q == Q1 && par[k] < HUGE_VAL) ? (float)(par[k] - (double)th[k]) : 0.0f;
+  }
   if (grp == 0 && wave == 0) {
     if (u_out) {
 #pragma unroll
@@ -870,7 +879,7 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
   auto apply = [&](float yv, int k) -> float {
     if constexpr (Q == QINF) return copysignf(fminf(fabsf(yv), uf[k]), yv);
     else if constexpr (Q == Q2) return (float)((double)yv * par[k]);
-    else return copysignf((float)fmax((double)fabsf(yv) - par[k], 0.0), yv);
+    else return copysignf(fmaxf((fabsf(yv) - th[k]) - tl[k], 0.0f), yv);
   };
 
   // Software pipeline: the next block's loads are issued first, then this block is mapped

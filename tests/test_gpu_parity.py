@@ -575,7 +575,8 @@ def check_stored(got, ref, q, storage):
     lo = orc.round_to_storage((x - tol).astype(np.float32), storage)
     hi = orc.round_to_storage((x + tol).astype(np.float32), storage)
     assert np.all((got["X"] >= lo) & (got["X"] <= hi))
-    assert np.mean(got["X"] != ref["X"]) < 0.02, "more than a few entries sit on a rounding boundary"
+    if storage != "f32":   # 16-bit units are 2^8 .. 2^16 coarser than the fp32 differences
+        assert np.mean(got["X"] != ref["X"]) < 0.02, "more than a few entries sit on a rounding boundary"
     assert not got["X"][:, ~ref["mask"]].any()
 
 
