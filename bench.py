@@ -91,7 +91,8 @@ def time_kernels(torch, mp, fn, pairs, steps, warmup):
     return out
 
 
-def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, eta_abs=None, storage="f32"):
+def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, eta_abs=None, storage="f32",
+                  keep_output=False):
     """storage "bf16" / "f16": the same matrix rounded to 16 bits, through bilevel_proj_stored
     (half the bytes: 4 per element instead of 8 in the effective figures)."""
     import numpy as np
@@ -115,6 +116,7 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
     pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
     ms = time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, steps, warmup)
     res = ws.result()
+    x_timed = pairs[(steps - 1) % npairs][1].cpu().numpy() if keep_output else None   # X of the last timed step
     # how far the nearest aggregate is from the threshold, relative: the support is safe
     # against fp64 summation-order differences as long as this is far above 1e-13
     vbuf = torch.empty(m, dtype=torch.float32, device=dev)
@@ -141,6 +143,8 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
         "search_iters": res["search_iters"],
         "inner_sweeps": res["inner_sweeps"], "inner_pending": res["inner_pending"],
     }
+    if keep_output:
+        out["_x_timed"] = x_timed
     del pairs
     torch.cuda.empty_cache()
     return out
@@ -180,22 +184,28 @@ def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
     return out
 
 
-def cpu_baseline(Y_host, frac, budget_s=20.0):
-    """The oracle as it stands, single numpy thread, on the headline workload."""
+def cpu_baseline(Y_host, eta, x_timed, tau_gpu, budget_s=20.0):
+    """The oracle as it stands, single numpy thread, on the headline workload with the radius
+    the GPU runs used; its result also checks the X the last timed GPU step produced."""
     import numpy as np
     from oracle import mlproj_oracle as orc
-    eta = float(np.float32(frac * orc.norm_l1q(Y_host, "inf")))
     times = []
     t_all = time.perf_counter()
     while len(times) < 5 and (time.perf_counter() - t_all) < budget_s:
         t0 = time.perf_counter()
-        orc.bilevel_l1inf(Y_host, eta)
+        ref = orc.bilevel_l1inf(Y_host, eta)
         times.append(time.perf_counter() - t0)
     t = statistics.median(times)
     n, m = Y_host.shape
+    err = np.abs(x_timed.astype(np.float64) - ref["X"])
+    bar = 1e-5 * np.abs(ref["X"]) + 1e-6
+    parity = {"checked": "X of the last timed step against the oracle, element by element",
+              "max_abs_err": float(err.max()), "within_rtol1e-5_atol1e-6": bool((err <= bar).all()),
+              "support_identical": bool(np.array_equal(np.abs(x_timed).max(axis=0) > 0, np.asarray(ref["u"]) > 0)),
+              "tau_rel_err": abs(tau_gpu - ref["tau"]) / ref["tau"] if ref["tau"] > 0 else 0.0}
     return {"value": 8.0 * n * m / t / 1e9, "unit": "GB/s", "ms": t * 1e3, "cores": 1, "kind": "oracle",
             "sample": "full %dx%d workload, median of %d runs of oracle.bilevel_l1inf (numpy, one thread)"
-                      % (n, m, len(times))}
+                      % (n, m, len(times)), "parity_of_timed_output": parity}
 
 
 def main():
@@ -209,7 +219,9 @@ def main():
     mp.lib()   # fail loudly if the HIP library is missing
 
     w, Y = workloads.make(args.workload)
-    head = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, args.steps, args.warmup)
+    want_cpu = not (args.quick or args.no_cpu)
+    head = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
+    x_timed = head.pop("_x_timed", None)
     n, m = Y.shape
     elems = n * m
     # the dominant kernel is the map pass: it reads Y once and writes X once (8 B/element)
@@ -258,8 +270,8 @@ def main():
         for k, v in bench_tensor(torch, mp, Yt, wt.eta_frac, 100, 10).items():
             also["tensor_256x256x256/" + k] = v
         line["also"] = also
-    if not (args.quick or args.no_cpu):
-        line["cpu_baseline"] = cpu_baseline(Y, w.eta_frac)
+    if want_cpu:
+        line["cpu_baseline"] = cpu_baseline(Y, head["eta"], x_timed, head["tau"])
     print(json.dumps(line))
 
 

@@ -15,8 +15,9 @@
  *    current HIP device; `stream` is a hipStream_t passed as void* (NULL = the
  *    default stream).  Calls only enqueue work on `stream` and return; they never
  *    synchronise, never copy to the host and never allocate or free memory.
- *  - Matrices are dense row-major fp32: element (i, j) of an n x m matrix is
- *    Y[i*m + j].  Tensors are dense C-order fp32.
+ *  - Matrices are dense row-major fp32 (bilevel_proj_stored also takes bf16 and
+ *    fp16): element (i, j) of an n x m matrix is Y[i*m + j].  Tensors are dense
+ *    C-order fp32.
  *  - The caller owns every buffer.  X may alias Y exactly (in-place); any other
  *    overlap between buffers is undefined.  Y must hold finite values.
  *  - `workspace`: device scratch of at least mlproj_workspace_bytes(...) bytes,
@@ -118,7 +119,9 @@ int mlproj_trace_begin(void** events /* host array of hipEvent_t */, int capacit
 int mlproj_trace_end(void);
 
 /* Bytes of workspace a call of `variant` on dims (d0, d1, d2) needs; bi-level
- * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.            */
+ * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.  The size is a few
+ * MiB plus 8-16 bytes per column; MLPROJ_L11 adds up to about 1 KiB per column for the
+ * lists of its per-column threshold searches.                                   */
 int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2,
                            size_t* bytes_out /* host */);
 
