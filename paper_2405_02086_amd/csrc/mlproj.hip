@@ -98,19 +98,22 @@ static inline long long cdiv(long long a, long long b) { return (a + b - 1) / b;
 
 // Both passes were tuned on an MI355X: a read-only pass is fastest with about two workgroups
 // per CU, the read+write pass with one per CU and fewer rows in flight (a narrower band of
-// DRAM pages open at a time); counts that are not multiples of the CU count lose 10-25 %.
+// DRAM pages open at a time).
 static Geometry plan_columns(long long n, long long m, int vec, int variant) {
   Geometry g;
   g.vec = vec;
   g.tile_w = WAVE * vec;
   g.tiles = cdiv(m, g.tile_w);
-  long long grp = cdiv(TARGET_WGS, g.tiles);
+  // Row groups per tile: as many as keep the whole grid within the target, so that every
+  // workgroup is resident at once.  One workgroup too many runs alone after all the others
+  // and a pass takes twice as long (what an odd number of tiles used to cost).
+  long long grp = TARGET_WGS / g.tiles;
   const long long max_grp = cdiv(n, RBLK);
   if (grp > max_grp) grp = max_grp;
   if (grp < 1) grp = 1;
   g.groups = grp;
   (void)variant;
-  long long mg = cdiv(TARGET_WGS_MAP, g.tiles);
+  long long mg = TARGET_WGS_MAP / g.tiles;
   const long long max_mg = cdiv(n, MAP_RBLK);
   if (mg > max_mg) mg = max_mg;
   if (mg < 1) mg = 1;
@@ -252,6 +255,58 @@ __device__ __forceinline__ void store_row_nt(T* p, const float (&x)[VEC]) {
     for (int k = 0; k < VEC; ++k) store_one_nt(p + k, x[k]);
   }
 }
+
+// The columns of a tile that one lane owns, and how it reaches them in a row.
+//   wide    : VEC consecutive columns, one 16-byte access per row; needs 16-byte aligned
+//             rows (base aligned, row length a multiple of VEC);
+//   strided : columns lane, lane + 64, lane + 128, ... of the tile, one element per access,
+//             for any alignment and row length.  A wavefront's access is still one coalesced
+//             run of 64 elements and a lane has the same bytes in flight as in the wide form.
+template <typename T, int VEC, bool STRIDED>
+struct LaneCols {
+  long long first;      // the first owned column
+  bool ok[VEC];         // which owned columns exist (column < m)
+  long long from[VEC];  // strided: the column to read for slot k (an existing one, see load)
+  __device__ __forceinline__ LaneCols(long long tile0, int lane, long long m) {
+    first = STRIDED ? tile0 + lane : tile0 + (long long)lane * VEC;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      ok[k] = col(k) < m;
+      from[k] = ok[k] ? col(k) : first;
+    }
+  }
+  __device__ __forceinline__ long long col(int k) const {
+    return STRIDED ? first + (long long)k * WAVE : first + k;
+  }
+  // position of owned column k inside the tile
+  static __device__ __forceinline__ int slot(int lane, int k) {
+    return STRIDED ? lane + k * WAVE : lane * VEC + k;
+  }
+  __device__ __forceinline__ bool any() const { return ok[0]; }  // owned columns ascend with k
+  // The lane's elements of the row that starts at `row`, as stored.  Call only when any().
+  // Strided: a slot whose column does not exist reads the lane's first column instead, so
+  // that no load is conditional (a conditional load brings its wait with it); what such a slot
+  // computes is never stored or read.
+  __device__ __forceinline__ void load(const T* row, Pack<T, VEC>& dst) const {
+    if constexpr (STRIDED) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) dst.e[k] = row[from[k]];
+    } else {
+      dst = *reinterpret_cast<const Pack<T, VEC>*>(row + first);
+    }
+  }
+  // XWIDE: one 16-byte store (wide form and X 16-byte aligned), else element by element
+  template <bool XWIDE>
+  __device__ __forceinline__ void store_nt(T* row, const float (&x)[VEC]) const {
+    if constexpr (STRIDED) {
+#pragma unroll
+      for (int k = 0; k < VEC; ++k)
+        if (ok[k]) store_one_nt(row + col(k), x[k]);
+    } else {
+      store_row_nt<VEC, XWIDE>(row + first, x);
+    }
+  }
+};
 
 // Wavefront reductions on the DPP crossbar (no LDS round trips).  Each step adds the value of
 // another lane: swap within pairs, swap pairs within quads, shift the 16-lane row by 4 and by
@@ -403,9 +458,9 @@ __device__ __forceinline__ typename AccOf<Q>::type combine(typename AccOf<Q>::ty
 
 // ------------------------------------------------------------------ column aggregate
 // Partial column aggregates of v_j = ||y_j||_q (Sec. 3): max |.| (exact), sum |.| or sum of
-// squares (both in fp64).  Lane l of every wavefront owns VEC consecutive columns; the four
+// squares (both in fp64).  Every lane owns VEC columns of the tile (see LaneCols); the four
 // wavefronts of a workgroup take rows r, r+1, r+2, r+3 (mod 4) of each row block.
-template <int Q, typename T, int VEC>
+template <int Q, typename T, int VEC, bool STRIDED>
 __global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, long long n,
                                                     long long m, Geometry g,
                                                     void* __restrict__ partial_) {
@@ -417,33 +472,32 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, lon
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
   const long long grp = blockIdx.x / g.tiles;
-  const long long col0 = t * TILE_W + (long long)lane * VEC;
+  const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
 
   Acc acc[VEC];
 #pragma unroll
   for (int k = 0; k < VEC; ++k) acc[k] = (Acc)0;
 
-  if (col0 < m) {
-    const T* p = Y + col0;
+  if (lc.any()) {
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
-      float x[UNROLL][VEC];
+      Pack<T, VEC> x[UNROLL];
 #pragma unroll
-      for (int r = 0; r < UNROLL; ++r) load_row<VEC>(p + (r0 + wave + (long long)r * WAVES) * m, x[r]);
+      for (int r = 0; r < UNROLL; ++r) lc.load(Y + (r0 + wave + (long long)r * WAVES) * m, x[r]);
 #pragma unroll
       for (int r = 0; r < UNROLL; ++r)
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) accumulate<Q>(acc[k], x[r][k]);
+        for (int k = 0; k < VEC; ++k) accumulate<Q>(acc[k], (float)x[r].e[k]);
     }
     for (long long i = r0 + wave; i < n; i += WAVES) {  // the one ragged block at the bottom
-      float x[VEC];
-      load_row<VEC>(p + i * m, x);
+      Pack<T, VEC> x;
+      lc.load(Y + i * m, x);
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) accumulate<Q>(acc[k], x[k]);
+      for (int k = 0; k < VEC; ++k) accumulate<Q>(acc[k], (float)x.e[k]);
     }
   }
 #pragma unroll
-  for (int k = 0; k < VEC; ++k) sm[wave][lane * VEC + k] = acc[k];
+  for (int k = 0; k < VEC; ++k) sm[wave][lc.slot(lane, k)] = acc[k];
   __syncthreads();
   for (int c = threadIdx.x; c < TILE_W; c += WG) {
     Acc a = sm[0][c];
@@ -798,7 +852,7 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
 // read last there (the ones most likely still cached) are read first here.
 // With fused_eta >= 0 every workgroup first runs the threshold search itself (see
 // search_block) and workgroup 0 files the result record; otherwise tau is read from it.
-template <int Q, typename T, int VEC, bool XVEC>
+template <int Q, typename T, int VEC, bool STRIDED, bool XVEC>
 __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long n,
                                                     long long m, Geometry g, Ws ws,
                                                     float* __restrict__ u_out,
@@ -811,10 +865,8 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
   const long long grp = blockIdx.x / g.tiles;
-  const long long col0 = t * TILE_W + (long long)lane * VEC;
-  const bool col_ok = col0 < m;
-  const T* p = Y + col0;
-  T* q = X + col0;
+  const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
+  const bool col_ok = lc.any();
 
   // Row blocks of MAP_RBLK rows, bottom block first; the last block may be ragged.
   const long long nblk = (n + MAP_RBLK - 1) / MAP_RBLK;
@@ -826,7 +878,7 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
 #pragma unroll
     for (int r = 0; r < U; ++r) {
       const long long row = blk * MAP_RBLK + wave + (long long)r * WAVES;
-      if (row < n) dst[r] = *reinterpret_cast<const Pack<T, VEC>*>(p + row * m);
+      if (row < n) lc.load(Y + row * m, dst[r]);
     }
   };
   // The first block is requested before tau is known, so its latency hides the search.
@@ -849,11 +901,11 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
   double par[VEC];  // q = 2: scale u_j / v_j;  q = 1: inner threshold tau_j
 #pragma unroll
   for (int k = 0; k < VEC; ++k) {
-    const double vj = ws.v[col0 + k];
+    const double vj = lc.ok[k] ? ws.v[lc.col(k)] : 0.0;
     const double uj = radius(vj, top);
     uf[k] = (float)uj;
     if constexpr (Q == Q2) par[k] = vj > 0.0 ? uj / vj : 0.0;
-    else if constexpr (Q == Q1) par[k] = inside ? 0.0 : (uj > 0.0 ? ws.tauj[col0 + k] : HUGE_VAL);
+    else if constexpr (Q == Q1) par[k] = inside ? 0.0 : ((uj > 0.0 && lc.ok[k]) ? ws.tauj[lc.col(k)] : HUGE_VAL);
     else par[k] = 0.0;
   }
   // q = 1: tau_j as an unevaluated fp32 pair, tau_j = th + tl to 2^-48 relative.  |y| - th is
@@ -868,11 +920,13 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
   if (grp == 0 && wave == 0) {
     if (u_out) {
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) u_out[col0 + k] = uf[k];
+      for (int k = 0; k < VEC; ++k)
+        if (lc.ok[k]) u_out[lc.col(k)] = uf[k];
     }
     if (mask_out) {  // the kept columns, decided where the radius is: in fp64
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) mask_out[col0 + k] = radius(ws.v[col0 + k], top) > 0.0 ? 1 : 0;
+      for (int k = 0; k < VEC; ++k)
+        if (lc.ok[k]) mask_out[lc.col(k)] = radius(ws.v[lc.col(k)], top) > 0.0 ? 1 : 0;
     }
   }
 
@@ -897,7 +951,7 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
         float f[VEC];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) f[k] = apply((float)x[r].e[k], k);
-        store_row_nt<VEC, XVEC>(q + row * m, f);
+        lc.template store_nt<XVEC>(X + row * m, f);
       }
     }
 #pragma unroll
@@ -939,7 +993,7 @@ __device__ __forceinline__ float above(double t) {
 }
 
 // Sweep 0: sum and count of the entries above t = tauj, count above t*(1 + L11_WINDOW).
-template <typename T, int VEC>
+template <typename T, int VEC, bool STRIDED>
 __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, long long n,
                                                        long long m, Geometry g, Ws ws) {
   constexpr int TILE_W = WAVE * VEC;
@@ -954,19 +1008,19 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
   const long long grp = blockIdx.x / g.tiles;
-  const long long col0 = t * TILE_W + (long long)lane * VEC;
+  const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
 
   double sum[VEC];
   unsigned cnt[VEC], cnt2[VEC];
 #pragma unroll
   for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; cnt2[k] = 0u; }
 
-  if (col0 < m) {
+  if (lc.any()) {
     // The entries are fp32 (or narrower), so "a > t" with t in fp64 is "a >= above(t)" in fp32.
     float cj[VEC], cw[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-      const double tj = ws.tauj[col0 + k];
+      const double tj = lc.ok[k] ? ws.tauj[lc.col(k)] : HUGE_VAL;
       cj[k] = above(tj);
       cw[k] = above(tj * (1.0 + L11_WINDOW));
     }
@@ -977,13 +1031,11 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
       cnt[k] += in ? 1u : 0u;
       cnt2[k] += a >= cw[k] ? 1u : 0u;
     };
-    const T* p = Y + col0;
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
       Pack<T, VEC> x[UNROLL];
 #pragma unroll
-      for (int r = 0; r < UNROLL; ++r)
-        x[r] = *reinterpret_cast<const Pack<T, VEC>*>(p + (r0 + wave + (long long)r * WAVES) * m);
+      for (int r = 0; r < UNROLL; ++r) lc.load(Y + (r0 + wave + (long long)r * WAVES) * m, x[r]);
       __builtin_amdgcn_sched_barrier(0);  // every load of the block is in flight before the first use
 #pragma unroll
       for (int r = 0; r < UNROLL; ++r)
@@ -991,17 +1043,17 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
         for (int k = 0; k < VEC; ++k) visit((float)x[r].e[k], k);
     }
     for (long long i = r0 + wave; i < n; i += WAVES) {
-      float x[VEC];
-      load_row<VEC>(p + i * m, x);
+      Pack<T, VEC> x;
+      lc.load(Y + i * m, x);
 #pragma unroll
-      for (int k = 0; k < VEC; ++k) visit(x[k], k);
+      for (int k = 0; k < VEC; ++k) visit((float)x.e[k], k);
     }
   }
 #pragma unroll
   for (int k = 0; k < VEC; ++k) {
-    sm_sum[wave][lane * VEC + k] = sum[k];
-    sm_cnt[wave][lane * VEC + k] = cnt[k];
-    sm_cnt2[wave][lane * VEC + k] = cnt2[k];
+    sm_sum[wave][lc.slot(lane, k)] = sum[k];
+    sm_cnt[wave][lc.slot(lane, k)] = cnt[k];
+    sm_cnt2[wave][lc.slot(lane, k)] = cnt2[k];
   }
   __syncthreads();
   for (int col = threadIdx.x; col < TILE_W; col += WG) {
@@ -1026,7 +1078,7 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
 // one atomic add per column and copies them out.  gcnt ends as the true number of window
 // entries of the column whether or not they all fitted; gflag marks a column some workgroup
 // could not stage completely.
-template <typename T, int VEC>
+template <typename T, int VEC, bool STRIDED>
 __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y, long long n,
                                                         long long m, Geometry g, Ws ws,
                                                         int sweep) {
@@ -1045,7 +1097,7 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
   const int wave = threadIdx.x / WAVE;
   const long long t = blockIdx.x % g.tiles;
   const long long grp = blockIdx.x / g.tiles;
-  const long long col0 = t * TILE_W + (long long)lane * VEC;
+  const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
 
   for (int c = threadIdx.x; c < TILE_W; c += WG) staged_cnt[c] = 0u;
   __syncthreads();
@@ -1055,12 +1107,12 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
 #pragma unroll
   for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; }
 
-  if (col0 < m) {
+  if (lc.any()) {
     float chi[VEC], clo[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-      chi[k] = above(ws.tauj[col0 + k]);
-      clo[k] = above(ws.tlo[col0 + k]);
+      chi[k] = lc.ok[k] ? above(ws.tauj[lc.col(k)]) : INFINITY;
+      clo[k] = lc.ok[k] ? above(ws.tlo[lc.col(k)]) : INFINITY;
     }
     // One row of the lane's columns.  Window entries are rare, so the row is tested as a
     // whole and the staging code runs only for rows that have one.
@@ -1079,20 +1131,18 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
         for (int k = 0; k < VEC; ++k) {
           const float a = fabsf(y[k]);
           if (a >= clo[k] && !(a >= chi[k])) {
-            const int c = lane * VEC + k;
+            const int c = lc.slot(lane, k);
             const unsigned slot = atomicAdd(&staged_cnt[c], 1u);
             if (slot < (unsigned)CAPW) staged[slot][c] = a;
           }
         }
       }
     };
-    const T* p = Y + col0;
     long long r0 = grp * RBLK;
     for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
       Pack<T, VEC> x[UNROLL];
 #pragma unroll
-      for (int r = 0; r < UNROLL; ++r)
-        x[r] = *reinterpret_cast<const Pack<T, VEC>*>(p + (r0 + wave + (long long)r * WAVES) * m);
+      for (int r = 0; r < UNROLL; ++r) lc.load(Y + (r0 + wave + (long long)r * WAVES) * m, x[r]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < UNROLL; ++r) {
@@ -1103,15 +1153,18 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
       }
     }
     for (long long i = r0 + wave; i < n; i += WAVES) {
+      Pack<T, VEC> x;
+      lc.load(Y + i * m, x);
       float y[VEC];
-      load_row<VEC>(p + i * m, y);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) y[k] = (float)x.e[k];
       visit_row(y);
     }
   }
 #pragma unroll
   for (int k = 0; k < VEC; ++k) {
-    sm_sum[wave][lane * VEC + k] = sum[k];
-    sm_cnt[wave][lane * VEC + k] = cnt[k];
+    sm_sum[wave][lc.slot(lane, k)] = sum[k];
+    sm_cnt[wave][lc.slot(lane, k)] = cnt[k];
   }
   __syncthreads();
   for (int c = threadIdx.x; c < TILE_W; c += WG) {
@@ -1851,9 +1904,10 @@ static int workspace_bytes_impl(int variant, long long d0, long long d1, long lo
   const int st = check_dims(d0, d1, d2);
   if (st != MLPROJ_OK) return st;
   size_t best = 0;
-  for (int vec : {8, 4, 1}) {   // 8: the 16-bit storage formats of the bi-level entry points
+  for (int vec : {8, 4, 1}) {   // bi-level: 4 (fp32) or 8 (16-bit storage) columns per lane
     Geometry g;
     long long ngroups;
+    if (variant != MLPROJ_L1INFINF && vec == 1) continue;
     if (variant == MLPROJ_L1INFINF) {
       if (vec == 8) continue;
       if (d0 > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
@@ -1928,11 +1982,12 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     return st;
   if (!aligned(Y, sizeof(T)) || (X && !aligned(X, sizeof(T)))) return MLPROJ_ERR_ALIGNMENT;
   if (!aligned(workspace, 256)) return MLPROJ_ERR_WORKSPACE;
-  // The access width is a function of m and of Y alone, so that the two stages of a split
-  // call agree on the geometry whatever X is; a misaligned X takes the scalar store path.
-  const int vec = pick_vec(Y, m, (int)sizeof(T));
+  // Every lane owns WIDE columns; rows that are not 16-byte aligned are read element-wise
+  // (the strided form of LaneCols), and a misaligned X alone only narrows the stores.  The
+  // geometry depends on n and m only, so the two stages of a split call agree on it.
+  const bool wide = pick_vec(Y, m, (int)sizeof(T)) == WIDE;
   const bool x_vec = !X || aligned(X, 16);
-  const Geometry g = plan_columns(n, m, vec, Q);
+  const Geometry g = plan_columns(n, m, WIDE, Q);
   if (g.tiles * g.groups > MAX_GRID) return MLPROJ_ERR_TOO_LARGE;
   const Layout L = layout_for(g, m, Q);
   if (workspace_bytes < L.bytes) return MLPROJ_ERR_WORKSPACE;
@@ -1949,10 +2004,10 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
 
   if (stages & STAGE_AGGREGATE) {
     mark(stream);
-    if (vec == WIDE)
-      hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws.partial);
+    if (wide)
+      hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     else
-      hipLaunchKernelGGL((colagg_kernel<Q, T, 1>), grid, block, 0, stream, Y, n, m, g, ws.partial);
+      hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     mark(stream);
     hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
     if (!fuse) {
@@ -1965,11 +2020,11 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       hipLaunchKernelGGL(l11_init_kernel, dim3((unsigned)cdiv(m, WG)), block, 0, stream, n, m, ws);
       for (int s = 0; s < MAX_INNER_SWEEPS; ++s) {
         if (s == 0) {
-          if (vec == WIDE) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws);
-          else hipLaunchKernelGGL((l11_sweep_kernel<T, 1>), grid, block, 0, stream, Y, n, m, g, ws);
+          if (wide) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws);
+          else hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws);
         } else {
-          if (vec == WIDE) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          else hipLaunchKernelGGL((l11_filter_kernel<T, 1>), grid, block, 0, stream, Y, n, m, g, ws, s);
+          if (wide) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws, s);
+          else hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
         }
         hipLaunchKernelGGL(l11_update_kernel, rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
       }
@@ -1978,12 +2033,12 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   }
   if (stages & STAGE_APPLY) {
     mark(stream);
-    if (vec == WIDE && x_vec)
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
-    else if (vec == WIDE)
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+    if (wide && x_vec)
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+    else if (wide)
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else
-      hipLaunchKernelGGL((colmap_kernel<Q, T, 1, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, true, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
   }
   mark(stream);
   return launch_status();
@@ -2175,7 +2230,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 310; }
+int mlproj_version(void) { return 320; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
