@@ -49,6 +49,8 @@ constexpr int COOP_MAX_WGS = 64;         // workgroups of the grid-wide search (
 constexpr int COOP_VALUES = 8;           // values of v per thread there
 constexpr unsigned SPIN_LIMIT = 1u << 22; // polls before a waiting workgroup gives up (~0.1 s)
 constexpr long long FUSED_SEARCH_MAX = (long long)WG * SEARCH_CACHE;  // groups a map workgroup can search in registers
+constexpr int SEARCH_CACHE_BIG = 64;     // ... the same with four times the registers, for up to 16384 groups
+constexpr long long FUSED_SEARCH_MAX_BIG = (long long)WG * SEARCH_CACHE_BIG;
 
 // ------------------------------------------------------------------ host-side geometry
 // A matrix is cut into column tiles of 64*vec columns; each tile is shared by `groups` row
@@ -578,21 +580,21 @@ __device__ __forceinline__ double radius(double v, const Top& t) {
 __device__ __forceinline__ Top top_of(const SearchOut& o) { return Top{o.tau, o.scale, o.cap}; }
 __device__ __forceinline__ Top top_of(const mlproj_result* r) { return Top{r->tau, r->scale, r->cap}; }
 
-template <int NT>
+template <int NT, int CACHE = SEARCH_CACHE>
 __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, long long ngroups,
                                                   double eta, int mode, int outer,
                                                   PairScratch<NT / WAVE>& s) {
   const int tid = threadIdx.x;
-  double vr[SEARCH_CACHE];
+  double vr[CACHE];
   double a = 0.0, mx = 0.0;
 #pragma unroll
-  for (int k = 0; k < SEARCH_CACHE; ++k) {
+  for (int k = 0; k < CACHE; ++k) {
     const long long i = tid + (long long)k * NT;
     vr[k] = i < ngroups ? v[i] : 0.0;  // 0 is never active: tau >= 0 and the test is strict
     a += vr[k];
     mx = fmax(mx, vr[k]);
   }
-  for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT) {
+  for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
     const double x = v[i];
     a += x;
     mx = fmax(mx, x);
@@ -615,8 +617,8 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
     double sq = 0.0, dummy = 0.0;
     unsigned c = 0;
 #pragma unroll
-    for (int k = 0; k < SEARCH_CACHE; ++k) { sq = fma(vr[k], vr[k], sq); c += vr[k] > 0.0 ? 1u : 0u; }
-    for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT) {
+    for (int k = 0; k < CACHE; ++k) { sq = fma(vr[k], vr[k], sq); c += vr[k] > 0.0 ? 1u : 0u; }
+    for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
       const double x = v[i];
       sq = fma(x, x, sq);
       c += x > 0.0 ? 1u : 0u;
@@ -639,8 +641,8 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
     o.inside = 1;  // already in the ball: tau = 0, u = v
     unsigned c = 0;
 #pragma unroll
-    for (int k = 0; k < SEARCH_CACHE; ++k) c += vr[k] > 0.0 ? 1u : 0u;
-    for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT)
+    for (int k = 0; k < CACHE; ++k) c += vr[k] > 0.0 ? 1u : 0u;
+    for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT)
       c += v[i] > 0.0 ? 1u : 0u;
     double zero = 0.0;
     block_sum_count(zero, c, s);
@@ -653,10 +655,10 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
       double sum = 0.0;
       unsigned cnt = 0;
 #pragma unroll
-      for (int k = 0; k < SEARCH_CACHE; ++k) {
+      for (int k = 0; k < CACHE; ++k) {
         if (vr[k] > tau) { sum += vr[k]; ++cnt; }
       }
-      for (long long i = tid + (long long)SEARCH_CACHE * NT; i < ngroups; i += NT) {
+      for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
         const double x = v[i];
         if (x > tau) { sum += x; ++cnt; }
       }
@@ -852,7 +854,7 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
 // read last there (the ones most likely still cached) are read first here.
 // With fused_eta >= 0 every workgroup first runs the threshold search itself (see
 // search_block) and workgroup 0 files the result record; otherwise tau is read from it.
-template <int Q, typename T, int VEC, bool STRIDED, bool XVEC>
+template <int Q, typename T, int VEC, bool STRIDED, bool XVEC, int SC = SEARCH_CACHE>
 __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long n,
                                                     long long m, Geometry g, Ws ws,
                                                     float* __restrict__ u_out,
@@ -887,7 +889,7 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
   Top top;
   bool inside;
   if (fused_eta >= 0.0) {
-    const SearchOut o = search_block<WG>(ws.v, m, fused_eta, MODE_PROJECT, outer, bs);
+    const SearchOut o = search_block<WG, SC>(ws.v, m, fused_eta, MODE_PROJECT, outer, bs);
     top = top_of(o);
     inside = o.inside != 0u;
     if (blockIdx.x == 0 && threadIdx.x == 0) write_result(ws, o, nullptr);
@@ -1998,8 +2000,10 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   const int parts = reduce_parts(g.groups);
   const dim3 rgrid((unsigned)cdiv(m, SWG / parts)), rblock(SWG);
   // A whole call on few enough groups lets every map workgroup find tau by itself, which
-  // takes the one-workgroup search kernel off the critical path.
-  const bool fuse = mode == MODE_PROJECT && stages == STAGE_ALL && Q != Q1 && m <= FUSED_SEARCH_MAX;
+  // takes the one-workgroup search kernel off the critical path (16 values of v per thread
+  // up to 4096 groups, 64 per thread up to 16384).
+  const bool fuse = mode == MODE_PROJECT && stages == STAGE_ALL && Q != Q1 && m <= FUSED_SEARCH_MAX_BIG;
+  const bool fuse_big = fuse && m > FUSED_SEARCH_MAX;
   const double fused_eta = fuse ? (double)eta : -1.0;
 
   if (stages & STAGE_AGGREGATE) {
@@ -2033,7 +2037,13 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   }
   if (stages & STAGE_APPLY) {
     mark(stream);
-    if (wide && x_vec)
+    if (fuse_big && wide && x_vec)
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, true, SEARCH_CACHE_BIG>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+    else if (fuse_big && wide)
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, false, SEARCH_CACHE_BIG>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+    else if (fuse_big)
+      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, true, false, SEARCH_CACHE_BIG>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+    else if (wide && x_vec)
       hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else if (wide)
       hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
