@@ -26,8 +26,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for this library version only.
-TRAFFIC_VERSION = 310
-TRAFFIC_KIB = {"square_4096": 32973.7 * 1.999 + 65556.5, "square_16384": 524404.7 * 1.999 + 1048614.8}
+TRAFFIC_VERSION = 330
+TRAFFIC_KIB = {"square_4096": 32974.4 * 1.999 + 65564.0, "square_16384": 524914.2 * 1.999 + 1048616.0}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 

@@ -2240,7 +2240,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 320; }
+int mlproj_version(void) { return 330; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
