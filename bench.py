@@ -259,6 +259,8 @@ def main():
         also["square_16384/l1inf/bf16"] = bench_bilevel(torch, mp, Yb, "l1inf", wb.eta_frac, 20, 3, storage="bf16")
         also["square_16384/l11/bf16"] = bench_bilevel(torch, mp, Yb, "l11", wb.eta_frac, 5, 3, storage="bf16")
         also["square_4096/l1inf/bf16"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, storage="bf16")
+        also["square_4096/l12"] = bench_bilevel(torch, mp, Y, "l12", w.eta_frac, 100, 10)
+        also["square_4096/l11"] = bench_bilevel(torch, mp, Y, "l11", w.eta_frac, 50, 5)
         del Yb
         # the shape and distribution of the paper's own timing runs (Sec. 6.1): time against the radius
         wp, Yp = workloads.make("paper_1000x10000")

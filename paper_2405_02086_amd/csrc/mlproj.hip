@@ -34,7 +34,7 @@ constexpr int RBLK = WAVES * UNROLL;     // rows one workgroup consumes per trip
 constexpr int SWG = 1024;                // threads of the search / reduce workgroups
 constexpr int SWAVES = SWG / WAVE;
 constexpr int SEARCH_CACHE = 16;         // values of v per search thread kept in registers
-constexpr int MAX_INNER_SWEEPS = 24;     // l1,1: passes over Y allowed to the inner searches
+constexpr int MAX_INNER_SWEEPS = 12;     // l1,1: passes over Y allowed to the inner searches
 constexpr double L11_WINDOW = 1.0 / 16;  // l1,1: relative width of the window that samples the density
 constexpr int FILTER_LDS_SLOTS = 8192;   // l1,1: entries a workgroup can stage for its tile (32 KiB of LDS)
 constexpr int FILTER_MAX_LIST = 256;     // l1,1: entries kept per column
@@ -146,7 +146,8 @@ static int reduce_parts(long long partials_per_group) {
   return parts;
 }
 
-constexpr int LIST_PER_THREAD = 32;      // l1,1: listed entries one update thread holds in registers
+constexpr int LIST_PER_THREAD = 16;      // l1,1: listed entries one lane of the update kernel holds in registers
+constexpr int LIST_LANES = 16;           // ... and the lanes that share a column there
 
 static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   Layout L{};
@@ -164,10 +165,10 @@ static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   L.off_partial_cnt = o;   o = align_up(o + (variant == Q1 ? cells * 4 : 0), 256);
   L.off_partial_cnt2 = o;  o = align_up(o + (variant == Q1 ? cells * 4 : 0), 256);
   // l1,1: a column's list takes what its row groups can stage together, up to FILTER_MAX_LIST
-  // and what the update kernel's threads of that column can hold in registers
+  // and what the update kernel's lanes of that column can hold in registers
   long long staged = g.groups * (FILTER_LDS_SLOTS / (g.tile_w > 0 ? g.tile_w : 1));
   if (staged > FILTER_MAX_LIST) staged = FILTER_MAX_LIST;
-  if (staged > (long long)LIST_PER_THREAD * reduce_parts(g.groups)) staged = (long long)LIST_PER_THREAD * reduce_parts(g.groups);
+  if (staged > (long long)LIST_PER_THREAD * LIST_LANES) staged = (long long)LIST_PER_THREAD * LIST_LANES;
   L.list_cap = (int)staged;
   const size_t per_col8 = variant == Q1 ? (size_t)ngroups * 8 : 0, per_col4 = variant == Q1 ? (size_t)ngroups * 4 : 0;
   L.off_tlo = o;           o = align_up(o + per_col8, 256);
@@ -440,6 +441,71 @@ __device__ __forceinline__ void block_sum_count(double& sum, unsigned& cnt, Pair
   __syncthreads();
   sum = r;
   cnt = c;
+}
+
+// Segment reductions: SEG lanes (4, 16 or 64) of a wavefront that cooperate on one item
+// (a fibre of a tensor, a column's partials) reduce on the DPP crossbar with rotations, which
+// leave a result in every lane of the segment (for floating-point sums the lanes may differ
+// in the last bit: take one lane's value where that matters).
+constexpr int DPP_ROR4 = 0x124, DPP_ROR8 = 0x128;
+
+template <int SEG>
+__device__ __forceinline__ double seg_sum(double x) {
+  x += dpp_f64<DPP_SWAP1>(x);
+  x += dpp_f64<DPP_SWAP2>(x);
+  if constexpr (SEG >= 16) {
+    x += dpp_f64<DPP_ROR4>(x);
+    x += dpp_f64<DPP_ROR8>(x);
+  }
+  if constexpr (SEG == 64) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    double r = 0.0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+      const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, row * 16);
+      const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), row * 16);
+      r += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+    }
+    x = r;
+  }
+  return x;
+}
+template <int SEG>
+__device__ __forceinline__ double seg_max(double x) {  // non-negative values
+  x = fmax(x, dpp_f64<DPP_SWAP1>(x));
+  x = fmax(x, dpp_f64<DPP_SWAP2>(x));
+  if constexpr (SEG >= 16) {
+    x = fmax(x, dpp_f64<DPP_ROR4>(x));
+    x = fmax(x, dpp_f64<DPP_ROR8>(x));
+  }
+  if constexpr (SEG == 64) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    double r = 0.0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+      const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, row * 16);
+      const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), row * 16);
+      r = fmax(r, __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo)));
+    }
+    x = r;
+  }
+  return x;
+}
+template <int SEG>
+__device__ __forceinline__ unsigned seg_sum_u(unsigned x) {
+  x += dpp_u32<DPP_SWAP1>(x);
+  x += dpp_u32<DPP_SWAP2>(x);
+  if constexpr (SEG >= 16) {
+    x += dpp_u32<DPP_ROR4>(x);
+    x += dpp_u32<DPP_ROR8>(x);
+  }
+  if constexpr (SEG == 64) {
+    unsigned r = 0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) r += (unsigned)__builtin_amdgcn_readlane((int)x, row * 16);
+    x = r;
+  }
+  return x;
 }
 
 template <int Q> struct AccOf { using type = double; };
@@ -896,6 +962,13 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
   } else {
     top = top_of(ws.res);
     inside = ws.res->inside_ball != 0u;
+    if constexpr (Q == Q1) {
+      // how many columns the inner searches left open (0 = every threshold is exact)
+      if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const unsigned s = ws.res->inner_sweeps;
+        ws.res->inner_pending = (s >= (unsigned)MAX_INNER_SWEEPS) ? ws.pending[MAX_INNER_SWEEPS] : 0u;
+      }
+    }
   }
   if (!col_ok) return;
 
@@ -1279,75 +1352,74 @@ __device__ __forceinline__ Window next_window(double base, double fb, double kb,
   return w;
 }
 
-__global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long m, Geometry g,
-                                                         int parts, Ws ws, int sweep) {
-  __shared__ double sm_sum[SWG];
-  __shared__ unsigned sm_cnt[SWG];
-  __shared__ unsigned sm_cnt2[SWG];
-  __shared__ double col_t[SWG];       // per column of this workgroup: the point of the current round
-  __shared__ unsigned col_live[SWG];  // ... and whether its window is still being solved
-  __shared__ BlockScratch<SWAVES> bs;
+// One segment of UPD_SEG = 16 lanes per column: the lanes split the column's partials and its
+// listed window entries (in registers), reduce on the DPP crossbar, and every lane takes the
+// same decisions from the same numbers, so the kernel needs no LDS and no barrier.
+constexpr int UPD_SEG = 16;
+constexpr int UPD_COLS = WG / UPD_SEG;   // columns per workgroup
+static_assert(UPD_SEG == LIST_LANES, "the list capacity is planned for this many lanes per column");
+
+__global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m, Geometry g,
+                                                        Ws ws, int sweep) {
+  __shared__ BlockScratch<WAVES> bs;
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
   if (sweep > 0 && ws.pending[sweep] == 0u) return;
 
-  const int cols = SWG / parts;
-  const int c_local = threadIdx.x % cols;
-  const int part = threadIdx.x / cols;
-  const long long j = (long long)blockIdx.x * cols + c_local;
+  const int part = threadIdx.x % UPD_SEG;
+  const int seg_base = (threadIdx.x & (WAVE - 1)) & ~(UPD_SEG - 1);   // first lane of the segment
+  const long long j = (long long)blockIdx.x * UPD_COLS + threadIdx.x / UPD_SEG;
   const bool mine = j < m && ws.done[j] == 0u;
 
-  // Fold the partial sums and counts of the sweep; the `parts` threads of a column also split
-  // the column's listed window entries between them, in registers.
+  // fold the partial sums and counts of the sweep
   double S = 0.0;
   unsigned K = 0u, K2 = 0u;
+  if (mine) {
+    const long long t = j / g.tile_w, c = j % g.tile_w;
+    const size_t base = (size_t)t * g.groups * g.tile_w + c;
+    const double* ps = static_cast<const double*>(ws.partial);
+    for (long long b = part; b < g.groups; b += UPD_SEG) {
+      S += ps[base + (size_t)b * g.tile_w];
+      K += ws.partial_cnt[base + (size_t)b * g.tile_w];
+      if (sweep == 0) K2 += ws.partial_cnt2[base + (size_t)b * g.tile_w];
+    }
+  }
+  S = __shfl(seg_sum<UPD_SEG>(S), seg_base);   // one lane's sum for all: the lanes must agree
+  K = seg_sum_u<UPD_SEG>(K);
+  K2 = seg_sum_u<UPD_SEG>(K2);
+
+  // the listed window entries, split over the lanes
   unsigned r = 0u;
   bool complete = false;
   float mylist[LIST_PER_THREAD];
 #pragma unroll
   for (int i = 0; i < LIST_PER_THREAD; ++i) mylist[i] = 0.0f;
-  double my_sum = 0.0;
-  if (j < m) {
-    const long long t = j / g.tile_w, c = j % g.tile_w;
-    const size_t base = (size_t)t * g.groups * g.tile_w + c;
-    const double* ps = static_cast<const double*>(ws.partial);
-    for (long long b = part; b < g.groups; b += parts) {
-      S += ps[base + (size_t)b * g.tile_w];
-      K += ws.partial_cnt[base + (size_t)b * g.tile_w];
-      if (sweep == 0) K2 += ws.partial_cnt2[base + (size_t)b * g.tile_w];
-    }
-    if (sweep > 0 && mine) {
-      r = ws.gcnt[j];
-      complete = ws.gflag[j] == 0u && r <= (unsigned)ws.list_cap;
-      if (complete) {
+  double sc = 0.0;
+  if (sweep > 0 && mine) {
+    r = ws.gcnt[j];
+    complete = ws.gflag[j] == 0u && r <= (unsigned)ws.list_cap;
+    if (complete && r > 0u) {
+      // every load is unconditional (a slot past the end re-reads the last entry and is then
+      // blanked), so they are all in flight together
 #pragma unroll
-        for (int i = 0; i < LIST_PER_THREAD; ++i) {
-          const unsigned s = (unsigned)part + (unsigned)i * (unsigned)parts;
-          if (s < r) mylist[i] = ws.cand[(size_t)s * (size_t)m + (size_t)j];
-          my_sum += (double)mylist[i];
-        }
+      for (int i = 0; i < LIST_PER_THREAD; ++i) {
+        const unsigned s = (unsigned)part + (unsigned)i * (unsigned)UPD_SEG;
+        mylist[i] = ws.cand[(size_t)(s < r ? s : r - 1u) * (size_t)m + (size_t)j];
+      }
+#pragma unroll
+      for (int i = 0; i < LIST_PER_THREAD; ++i) {
+        const unsigned s = (unsigned)part + (unsigned)i * (unsigned)UPD_SEG;
+        if (s >= r) mylist[i] = 0.0f;
+        sc += (double)mylist[i];
       }
     }
   }
-  sm_sum[threadIdx.x] = S;
-  sm_cnt[threadIdx.x] = K;
-  sm_cnt2[threadIdx.x] = K2;
-  col_t[threadIdx.x] = my_sum;   // (borrowed for the fold of the listed entries' sums)
-  __syncthreads();
+  sc = seg_sum<UPD_SEG>(sc);   // exact (see the note on windows above): the same in every lane
 
-  bool closed = false, decided = false, solving = false;
+  bool closed = false, solving = false;
   double tau = 0.0, uj = 0.0, lo = 0.0, lb = 0.0, ub = 0.0;
   Window w{0.0, 0.0, NO_COUNT};
-  unsigned kp = NO_COUNT;
-  if (part == 0 && mine) {
-    double sc = my_sum;
-    for (int p = 1; p < parts; ++p) {
-      S += sm_sum[p * cols + c_local];
-      K += sm_cnt[p * cols + c_local];
-      K2 += sm_cnt2[p * cols + c_local];
-      sc += col_t[p * cols + c_local];
-    }
-    decided = true;
+  if (mine) {
     uj = radius(ws.v[j], top_of(res));
     const double hi = ws.tauj[j];
     lo = ws.tlo[j];
@@ -1382,6 +1454,7 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
       } else if (complete && f_lo >= 0.0 && f_hi <= 0.0) {
         closed = true;  // the root is inside the window and every entry of the window is known
         solving = true;
+        tau = lo;
       } else {
         if (n_hi > lb) { lb = n_hi; k_lb = K; }
         if (complete && n_lo > lb) { lb = n_lo; k_lb = k_lo; }
@@ -1399,50 +1472,32 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
   }
 
   // The root inside a window whose entries are all listed: the fixed point of the outer
-  // search on "entries above hi" (S, K) plus the listed ones, started at lo where f_j >= u_j;
-  // every column of the workgroup that needs it runs its rounds together.
-  __syncthreads();
-  if (part == 0) {
-    col_t[c_local] = lo;
-    col_live[c_local] = solving ? 1u : 0u;
-    tau = solving ? lo : tau;
-  }
-  int any = __syncthreads_or(solving ? 1 : 0);
-  for (unsigned round = 0; any && round < (unsigned)FILTER_MAX_LIST + 2u; ++round) {
-    const double t = col_t[c_local];
+  // search on "entries above hi" (S, K) plus the listed ones, started at lo where f_j >= u_j.
+  // The lanes of a wavefront loop together until the last of its columns is done.
+  unsigned kp = NO_COUNT;
+  for (unsigned round = 0; __any(solving) && round < (unsigned)FILTER_MAX_LIST + 2u; ++round) {
     double sa = 0.0;
     unsigned ka = 0u;
-    if (col_live[c_local] != 0u) {
 #pragma unroll
-      for (int i = 0; i < LIST_PER_THREAD; ++i)
-        if ((double)mylist[i] > t) { sa += (double)mylist[i]; ++ka; }
-    }
-    sm_sum[threadIdx.x] = sa;
-    sm_cnt[threadIdx.x] = ka;
-    __syncthreads();
+    for (int i = 0; i < LIST_PER_THREAD; ++i)
+      if ((double)mylist[i] > tau) { sa += (double)mylist[i]; ++ka; }
+    sa = seg_sum<UPD_SEG>(sa);   // exact, the same in every lane
+    ka = seg_sum_u<UPD_SEG>(ka) + K;
     if (solving) {
-      for (int p = 1; p < parts; ++p) {
-        sa += sm_sum[p * cols + c_local];
-        ka += sm_cnt[p * cols + c_local];
-      }
-      ka += K;
       const double tn = ka > 0u ? ((S + sa) - uj) / (double)ka : tau;
       if (ka == kp || ka == 0u) {
         tau = tn;
         solving = false;
-        col_live[c_local] = 0u;
       } else {
         kp = ka;
         tau = fmax(tau, tn);
-        col_t[c_local] = tau;
       }
     }
-    any = __syncthreads_or(solving ? 1 : 0);
   }
 
   unsigned open = 0u;
   if (part == 0 && j < m) {
-    if (decided) {
+    if (mine) {
       ws.tauj[j] = closed ? tau : w.hi;
       ws.tlo[j] = closed ? tau : w.lo;
       ws.kprev[j] = w.kp;
@@ -1462,6 +1517,7 @@ __global__ __launch_bounds__(SWG) void l11_update_kernel(long long n, long long 
 }
 
 // After the last sweep: how many columns were still open (0 = every inner search is exact).
+// (Only for a call that stops before the map pass, which otherwise does this itself.)
 __global__ void l11_close_kernel(Ws ws) {
   if (threadIdx.x == 0) {
     const unsigned s = ws.res->inner_sweeps;
@@ -1554,69 +1610,8 @@ __global__ __launch_bounds__(WG) void slabmap_kernel(const float* Y, float* X, l
 // contiguous last-axis fibres of the level below (fibre_agg), the top vector is projected
 // onto the l1 ball (the search above), and on the way back every fibre is projected onto the
 // ball whose radius is the matching entry of the level above (fibre_map).
-// SEG lanes (4, 16 or 64) cooperate on one fibre, so a wavefront holds 64/SEG fibres; segment
-// reductions run on the DPP crossbar with rotations, which leave the result in every lane.
-constexpr int DPP_ROR4 = 0x124, DPP_ROR8 = 0x128;
-
-template <int SEG>
-__device__ __forceinline__ double seg_sum(double x) {
-  x += dpp_f64<DPP_SWAP1>(x);
-  x += dpp_f64<DPP_SWAP2>(x);
-  if constexpr (SEG >= 16) {
-    x += dpp_f64<DPP_ROR4>(x);
-    x += dpp_f64<DPP_ROR8>(x);
-  }
-  if constexpr (SEG == 64) {
-    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
-    double r = 0.0;
-#pragma unroll
-    for (int row = 0; row < 4; ++row) {
-      const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, row * 16);
-      const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), row * 16);
-      r += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-    }
-    x = r;
-  }
-  return x;
-}
-template <int SEG>
-__device__ __forceinline__ double seg_max(double x) {  // non-negative values
-  x = fmax(x, dpp_f64<DPP_SWAP1>(x));
-  x = fmax(x, dpp_f64<DPP_SWAP2>(x));
-  if constexpr (SEG >= 16) {
-    x = fmax(x, dpp_f64<DPP_ROR4>(x));
-    x = fmax(x, dpp_f64<DPP_ROR8>(x));
-  }
-  if constexpr (SEG == 64) {
-    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
-    double r = 0.0;
-#pragma unroll
-    for (int row = 0; row < 4; ++row) {
-      const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, row * 16);
-      const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), row * 16);
-      r = fmax(r, __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo)));
-    }
-    x = r;
-  }
-  return x;
-}
-template <int SEG>
-__device__ __forceinline__ unsigned seg_sum_u(unsigned x) {
-  x += dpp_u32<DPP_SWAP1>(x);
-  x += dpp_u32<DPP_SWAP2>(x);
-  if constexpr (SEG >= 16) {
-    x += dpp_u32<DPP_ROR4>(x);
-    x += dpp_u32<DPP_ROR8>(x);
-  }
-  if constexpr (SEG == 64) {
-    unsigned r = 0;
-#pragma unroll
-    for (int row = 0; row < 4; ++row) r += (unsigned)__builtin_amdgcn_readlane((int)x, row * 16);
-    x = r;
-  }
-  return x;
-}
-
+// SEG lanes (4, 16 or 64) cooperate on one fibre, so a wavefront holds 64/SEG fibres (see the
+// segment reductions above).
 template <typename T, int VEC>
 __device__ __forceinline__ void load_elems(const T* p, double (&x)[VEC]) {
   if constexpr (VEC == 4) {
@@ -2030,9 +2025,9 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
           if (wide) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws, s);
           else hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
         }
-        hipLaunchKernelGGL(l11_update_kernel, rgrid, rblock, 0, stream, n, m, g, parts, ws, s);
+        hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s);
       }
-      hipLaunchKernelGGL(l11_close_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
+      if (!(stages & STAGE_APPLY)) hipLaunchKernelGGL(l11_close_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
     }
   }
   if (stages & STAGE_APPLY) {

@@ -680,4 +680,4 @@ def test_l11_inner_searches_converge_on_hard_distributions(mp, family):
         eta = eta_for(Y, 1, frac)
         got = run_gpu(mp, Y, eta, 1)
         check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
-        assert got["res"]["inner_sweeps"] <= 12, (family, frac, got["res"]["inner_sweeps"])
+        assert got["res"]["inner_sweeps"] <= 10, (family, frac, got["res"]["inner_sweeps"])
