@@ -31,7 +31,8 @@ class MlprojError(RuntimeError):
 
 
 def build(verbose=False):
-    """Compile csrc/mlproj.hip for gfx950 into libmlproj.so next to this file."""
+    """Compile csrc/mlproj.hip (one translation unit that includes csrc/*.h) for gfx950 into
+    libmlproj.so next to this file."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH, SRC_PATH]
     proc = subprocess.run(cmd, capture_output=True, text=True)

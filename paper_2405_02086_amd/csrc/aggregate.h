@@ -1,0 +1,121 @@
+// mlproj: the aggregate pass over columns (v_j = ||y_j||_q, Sec. 3) and the fold of its partials.
+#ifndef MLPROJ_AGGREGATE_H
+#define MLPROJ_AGGREGATE_H
+
+#include "common.h"
+#include "reduce.h"
+
+namespace mlproj {
+
+template <int Q> struct AccOf { using type = double; };
+template <> struct AccOf<QINF> { using type = float; };
+
+template <int Q>
+__device__ __forceinline__ void accumulate(typename AccOf<Q>::type& a, float y) {
+  if constexpr (Q == QINF) a = fmaxf(a, fabsf(y));
+  else if constexpr (Q == Q1) a += (double)fabsf(y);
+  else a = fma((double)y, (double)y, a);
+}
+template <int Q>
+__device__ __forceinline__ typename AccOf<Q>::type combine(typename AccOf<Q>::type a,
+                                                           typename AccOf<Q>::type b) {
+  if constexpr (Q == QINF) return fmaxf(a, b);
+  else return a + b;
+}
+
+// ------------------------------------------------------------------ column aggregate
+// Partial column aggregates of v_j = ||y_j||_q (Sec. 3): max |.| (exact), sum |.| or sum of
+// squares (both in fp64).  Every lane owns VEC columns of the tile (see LaneCols); the four
+// wavefronts of a workgroup take rows r, r+1, r+2, r+3 (mod 4) of each row block.
+template <int Q, typename T, int VEC, bool STRIDED>
+__global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, long long n,
+                                                    long long m, Geometry g,
+                                                    void* __restrict__ partial_) {
+  using Acc = typename AccOf<Q>::type;
+  constexpr int TILE_W = WAVE * VEC;
+  __shared__ Acc sm[WAVES][TILE_W];
+
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave = threadIdx.x / WAVE;
+  const long long t = blockIdx.x % g.tiles;
+  const long long grp = blockIdx.x / g.tiles;
+  const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
+
+  Acc acc[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) acc[k] = (Acc)0;
+
+  if (lc.any()) {
+    long long r0 = grp * RBLK;
+    for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
+      Pack<T, VEC> x[UNROLL];
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r) lc.load(Y + (r0 + wave + (long long)r * WAVES) * m, x[r]);
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) accumulate<Q>(acc[k], (float)x[r].e[k]);
+    }
+    for (long long i = r0 + wave; i < n; i += WAVES) {  // the one ragged block at the bottom
+      Pack<T, VEC> x;
+      lc.load(Y + i * m, x);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) accumulate<Q>(acc[k], (float)x.e[k]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) sm[wave][lc.slot(lane, k)] = acc[k];
+  __syncthreads();
+  for (int c = threadIdx.x; c < TILE_W; c += WG) {
+    Acc a = sm[0][c];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) a = combine<Q>(a, sm[w][c]);
+    static_cast<Acc*>(partial_)[((size_t)t * g.groups + grp) * TILE_W + c] = a;
+  }
+}
+
+// v_j from the partials of its tile, folded in a fixed order.  A workgroup of 1024 threads
+// covers 1024/parts groups with `parts` threads each (parts = 1..16, a power of two chosen on
+// the host from the number of partials per group); every thread keeps 8 loads in flight.
+// Serves columns (tile_w = 64*vec) and slabs (tile_w = 1) alike.
+template <int Q>
+__global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ partial_,
+                                                     long long ngroups, Geometry g, int parts,
+                                                     double* __restrict__ v,
+                                                     float* __restrict__ v_out,
+                                                     unsigned* __restrict__ flags) {
+  using Acc = typename AccOf<Q>::type;
+  __shared__ Acc sm[SWG];
+  if (blockIdx.x == 0 && threadIdx.x < 2) flags[threadIdx.x] = 0u;  // for the grid-wide search
+  const int cols = SWG / parts;
+  const int c_local = threadIdx.x % cols;
+  const int part = threadIdx.x / cols;
+  const long long j = (long long)blockIdx.x * cols + c_local;
+  Acc a = (Acc)0;
+  if (j < ngroups) {
+    const long long t = j / g.tile_w, c = j % g.tile_w;
+    const Acc* q = static_cast<const Acc*>(partial_) + (size_t)t * g.groups * g.tile_w + c;
+    const size_t stride = (size_t)g.tile_w;
+    long long b0 = part;
+    for (; b0 + 7LL * parts < g.groups; b0 += 8LL * parts) {
+      Acc x[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) x[r] = q[(size_t)(b0 + (long long)r * parts) * stride];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) a = combine<Q>(a, x[r]);
+    }
+    for (; b0 < g.groups; b0 += parts) a = combine<Q>(a, q[(size_t)b0 * stride]);
+  }
+  sm[threadIdx.x] = a;
+  __syncthreads();
+  if (part == 0 && j < ngroups) {
+    for (int w = 1; w < parts; ++w) a = combine<Q>(a, sm[w * cols + c_local]);
+    const double vj = (Q == Q2) ? sqrt((double)a) : (double)a;
+    v[j] = vj;
+    if (v_out) v_out[j] = (float)vj;
+  }
+}
+
+}  // namespace mlproj
+
+#endif

@@ -1,0 +1,504 @@
+// mlproj: per-column threshold searches of the bi-level l1,1 projection (Alg. 3).
+#ifndef MLPROJ_L11_H
+#define MLPROJ_L11_H
+
+#include "common.h"
+#include "reduce.h"
+#include "search.h"
+
+namespace mlproj {
+
+// ------------------------------------------------------------------ l1,1: inner searches
+// Alg. 3 needs, for every kept column, the threshold tau_j with
+// f_j(tau_j) = sum_i max(|Y_ij| - tau_j, 0) = u_j.  f_j is convex, decreasing and piecewise
+// linear.  One pass over Y gives every column the sum S and count K of its entries above a
+// point t, i.e. f_j(t) = S - K t and its slope -K; the Newton step N(t) = (S - u_j)/K lands at
+// or left of the root from ANY t (the tangent of a convex function lies below it).
+// All columns step in lock step, a pass over Y and then a small update kernel per sweep:
+//   sweep 0  evaluates a guess g (l11_init_kernel) and counts the entries in (g, g(1+1/16)]:
+//            value, slope and density give a quadratic model of f_j, whose root t is the
+//            estimate, with an error bar delta from the size of the move and the density;
+//   sweep s  evaluates hi = t + delta and LISTS the entries in the window (lo, hi],
+//            lo = t - delta (l11_filter_kernel).  With the few listed entries f_j is known on
+//            the whole window: if f_j(lo) >= u_j >= f_j(hi) the root is found among them
+//            exactly, in fp64, as in the outer search.  Otherwise the evaluated points tighten
+//            the certified bounds lb <= tau_j <= ub (Newton steps from below, points with
+//            f_j <= u_j from above) and the model gives the next window.
+// A column is also closed when the count at a Newton point N(p) equals the count at p (no
+// entry between them: f_j is linear there and N(p) is the root), or when the bounds meet.
+// On Gaussian data two sweeps close every column; heavy tails take a few more.
+// pending[s] is the number of columns still open before sweep s; the kernels of a sweep
+// return at once when it is zero.
+//
+// A window is kept within a factor 2 (hi <= 2 lo), so its entries differ by at most one
+// binary exponent and any fp64 sum of them is exact: the order in which workgroups append
+// to a column's list does not reach the result, which stays bit-reproducible.
+
+// The smallest float strictly above t: a float a satisfies a > t exactly when a >= above(t).
+__device__ __forceinline__ float above(double t) {
+  float f = (float)t;
+  if ((double)f <= t) f = nextafterf(f, INFINITY);
+  return f;
+}
+
+// Sweep 0: sum and count of the entries above t = tauj, count above t*(1 + L11_WINDOW).
+template <typename T, int VEC, bool STRIDED>
+__global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, long long n,
+                                                       long long m, Geometry g, Ws ws) {
+  constexpr int TILE_W = WAVE * VEC;
+  __shared__ double sm_sum[WAVES][TILE_W];
+  __shared__ unsigned sm_cnt[WAVES][TILE_W];
+  __shared__ unsigned sm_cnt2[WAVES][TILE_W];
+
+  const mlproj_result* res = ws.res;
+  if (res->inside_ball != 0u || res->n_active == 0u) return;
+
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave = threadIdx.x / WAVE;
+  const long long t = blockIdx.x % g.tiles;
+  const long long grp = blockIdx.x / g.tiles;
+  const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
+
+  double sum[VEC];
+  unsigned cnt[VEC], cnt2[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; cnt2[k] = 0u; }
+
+  if (lc.any()) {
+    // The entries are fp32 (or narrower), so "a > t" with t in fp64 is "a >= above(t)" in fp32.
+    float cj[VEC], cw[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      const double tj = lc.ok[k] ? ws.tauj[lc.col(k)] : HUGE_VAL;
+      cj[k] = above(tj);
+      cw[k] = above(tj * (1.0 + L11_WINDOW));
+    }
+    auto visit = [&](float y, int k) {
+      const float a = fabsf(y);
+      const bool in = a >= cj[k];
+      sum[k] += (double)(in ? a : 0.0f);
+      cnt[k] += in ? 1u : 0u;
+      cnt2[k] += a >= cw[k] ? 1u : 0u;
+    };
+    long long r0 = grp * RBLK;
+    for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
+      Pack<T, VEC> x[UNROLL];
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r) lc.load(Y + (r0 + wave + (long long)r * WAVES) * m, x[r]);
+      __builtin_amdgcn_sched_barrier(0);  // every load of the block is in flight before the first use
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) visit((float)x[r].e[k], k);
+    }
+    for (long long i = r0 + wave; i < n; i += WAVES) {
+      Pack<T, VEC> x;
+      lc.load(Y + i * m, x);
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) visit((float)x.e[k], k);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) {
+    sm_sum[wave][lc.slot(lane, k)] = sum[k];
+    sm_cnt[wave][lc.slot(lane, k)] = cnt[k];
+    sm_cnt2[wave][lc.slot(lane, k)] = cnt2[k];
+  }
+  __syncthreads();
+  for (int col = threadIdx.x; col < TILE_W; col += WG) {
+    double a = sm_sum[0][col];
+    unsigned c = sm_cnt[0][col], c2 = sm_cnt2[0][col];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) {
+      a += sm_sum[w][col];
+      c += sm_cnt[w][col];
+      c2 += sm_cnt2[w][col];
+    }
+    const size_t cell = ((size_t)t * g.groups + grp) * TILE_W + col;
+    static_cast<double*>(ws.partial)[cell] = a;
+    ws.partial_cnt[cell] = c;
+    ws.partial_cnt2[cell] = c2;
+  }
+}
+
+// Sweeps 1, 2, ...: sum and count of the entries above hi = tauj, and the entries in
+// (tlo, hi] themselves.  A workgroup stages the window entries of its tile's columns in LDS
+// (FILTER_LDS_SLOTS / TILE_W slots per column), then reserves room in each column's list with
+// one atomic add per column and copies them out.  gcnt ends as the true number of window
+// entries of the column whether or not they all fitted; gflag marks a column some workgroup
+// could not stage completely.
+template <typename T, int VEC, bool STRIDED>
+__global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y, long long n,
+                                                        long long m, Geometry g, Ws ws,
+                                                        int sweep) {
+  constexpr int TILE_W = WAVE * VEC;
+  constexpr int CAPW = FILTER_LDS_SLOTS / TILE_W;
+  __shared__ double sm_sum[WAVES][TILE_W];
+  __shared__ unsigned sm_cnt[WAVES][TILE_W];
+  __shared__ float staged[CAPW][TILE_W];   // slot-major: the lanes of a wavefront hit different banks
+  __shared__ unsigned staged_cnt[TILE_W];
+
+  const mlproj_result* res = ws.res;
+  if (res->inside_ball != 0u || res->n_active == 0u) return;
+  if (ws.pending[sweep] == 0u) return;
+
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave = threadIdx.x / WAVE;
+  const long long t = blockIdx.x % g.tiles;
+  const long long grp = blockIdx.x / g.tiles;
+  const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
+
+  for (int c = threadIdx.x; c < TILE_W; c += WG) staged_cnt[c] = 0u;
+  __syncthreads();
+
+  double sum[VEC];
+  unsigned cnt[VEC];
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) { sum[k] = 0.0; cnt[k] = 0u; }
+
+  if (lc.any()) {
+    float chi[VEC], clo[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+      chi[k] = lc.ok[k] ? above(ws.tauj[lc.col(k)]) : INFINITY;
+      clo[k] = lc.ok[k] ? above(ws.tlo[lc.col(k)]) : INFINITY;
+    }
+    // One row of the lane's columns.  Window entries are rare, so the row is tested as a
+    // whole and the staging code runs only for rows that have one.
+    auto visit_row = [&](const float (&y)[VEC]) {
+      bool any = false;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) {
+        const float a = fabsf(y[k]);
+        const bool in = a >= chi[k];
+        sum[k] += (double)(in ? a : 0.0f);
+        cnt[k] += in ? 1u : 0u;
+        any |= (a >= clo[k]) != in;   // clo <= chi: "above lo but not above hi"
+      }
+      if (any) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+          const float a = fabsf(y[k]);
+          if (a >= clo[k] && !(a >= chi[k])) {
+            const int c = lc.slot(lane, k);
+            const unsigned slot = atomicAdd(&staged_cnt[c], 1u);
+            if (slot < (unsigned)CAPW) staged[slot][c] = a;
+          }
+        }
+      }
+    };
+    long long r0 = grp * RBLK;
+    for (; r0 + RBLK <= n; r0 += g.groups * RBLK) {
+      Pack<T, VEC> x[UNROLL];
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r) lc.load(Y + (r0 + wave + (long long)r * WAVES) * m, x[r]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r) {
+        float y[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) y[k] = (float)x[r].e[k];
+        visit_row(y);
+      }
+    }
+    for (long long i = r0 + wave; i < n; i += WAVES) {
+      Pack<T, VEC> x;
+      lc.load(Y + i * m, x);
+      float y[VEC];
+#pragma unroll
+      for (int k = 0; k < VEC; ++k) y[k] = (float)x.e[k];
+      visit_row(y);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < VEC; ++k) {
+    sm_sum[wave][lc.slot(lane, k)] = sum[k];
+    sm_cnt[wave][lc.slot(lane, k)] = cnt[k];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < TILE_W; c += WG) {
+    double a = sm_sum[0][c];
+    unsigned k = sm_cnt[0][c];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) {
+      a += sm_sum[w][c];
+      k += sm_cnt[w][c];
+    }
+    const size_t cell = ((size_t)t * g.groups + grp) * TILE_W + c;
+    static_cast<double*>(ws.partial)[cell] = a;
+    ws.partial_cnt[cell] = k;
+    const long long col = t * TILE_W + c;
+    const unsigned r = staged_cnt[c];
+    if (col < m && r > 0u) {
+      if (r > (unsigned)CAPW) {
+        ws.gflag[col] = 1u;
+        atomicAdd(&ws.gcnt[col], r);
+      } else {
+        const unsigned off = atomicAdd(&ws.gcnt[col], r);
+        for (unsigned s = 0; s < r && off + s < (unsigned)ws.list_cap; ++s)
+          ws.cand[(size_t)(off + s) * (size_t)m + (size_t)col] = staged[s][c];
+      }
+    }
+  }
+}
+
+// Starting points of the inner searches.  Dropped columns get +inf (every entry maps to 0).
+// For a kept column the guess assumes its entries are Gaussian with the scale its l1 norm
+// implies: E|y| = sigma*sqrt(2/pi) = v_j/n and E max(|y| - t, 0) = sigma*h(t/sigma) with
+// h(z) = 2*phi(z) - z*erfc(z/sqrt 2), so z solves h(z) = (u_j/v_j)*sqrt(2/pi) (a few Newton
+// steps on the convex h) and the guess is sigma*z.  Only the speed depends on the guess.
+// The first certified bounds: every entry active gives the lower bound (v_j - u_j)/n.
+__global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, Ws ws) {
+  const mlproj_result* res = ws.res;
+  if (res->inside_ball != 0u || res->n_active == 0u) return;
+  const long long j = (long long)blockIdx.x * WG + threadIdx.x;
+  if (j >= m) return;
+  const double vj = ws.v[j];
+  const double uj = radius(vj, top_of(res));
+  double tj = HUGE_VAL, floor_t = HUGE_VAL;
+  if (uj > 0.0) {
+    // (fp32 is plenty here: the guess is a statistical estimate, off by percents)
+    const float c = (float)(uj / vj) * 0.79788456f;  // sqrt(2/pi)
+    float z = 0.0f;
+    for (int it = 0; it < 8; ++it) {
+      const float tail = erfcf(z * 0.70710678f);                  // 2*(1 - Phi(z))
+      const float h = 0.79788456f * expf(-0.5f * z * z) - z * tail;
+      if (!(tail > 1e-30f)) break;
+      z += (h - c) / tail;
+    }
+    const double sigma = (vj / (double)n) * 1.2533141373155001;   // sqrt(pi/2)
+    floor_t = fmax((vj - uj) / (double)n, 0.0);
+    tj = fmax(sigma * (double)z, floor_t);  // never below the all-active bound
+  }
+  ws.tauj[j] = tj;
+  ws.tlo[j] = tj;
+  ws.lb[j] = floor_t;
+  ws.ub[j] = HUGE_VAL;
+  ws.kprev[j] = NO_COUNT;
+  ws.done[j] = uj > 0.0 ? 0u : 1u;
+  ws.gcnt[j] = 0u;
+  ws.gflag[j] = 0u;
+}
+
+// Root of the local model of f_j - u_j: value fb, slope -kb, entry density rho at the base
+// point, fb - kb d + rho d^2 / 2 = 0 for the move d (the root next to the base point, in the
+// form that does not cancel); the tangent alone when no density is known.
+__device__ __forceinline__ double model_step(double fb, double kb, double rho) {
+  const double disc = kb * kb - 2.0 * rho * fb;
+  if (rho > 0.0 && disc > 0.0) {
+    const double den = kb + sqrt(disc);
+    if (den > 0.0) return 2.0 * fb / den;
+  }
+  return kb > 0.0 ? fb / kb : 0.0;
+}
+
+struct Window {
+  double lo, hi;
+  unsigned kp;  // count at the point whose Newton step is lo, or NO_COUNT
+};
+
+// The next window: the model's root +- an error bar (a quarter of the move plus six entries'
+// worth of spacing, at most an eighth of the list's capacity), cut to the certified bounds
+// [lb, ub] and to a factor 2.  `stuck`: nothing was seen at or below the point: step from lb.
+__device__ __forceinline__ Window next_window(double base, double fb, double kb, double rho,
+                                              double lb, unsigned k_lb, double ub, bool stuck,
+                                              int list_cap) {
+  Window w;
+  w.kp = NO_COUNT;
+  if (stuck) {
+    w.lo = w.hi = lb;
+    return w;
+  }
+  const double d = model_step(fb, kb, rho);
+  const double t = base + d;
+  double delta = 0.25 * fabs(d);
+  if (rho > 0.0) delta = fmin(delta + 6.0 / rho, 0.125 * (double)list_cap / rho);
+  double lo = t - delta, hi = t + delta;
+  if (!(lo > lb)) {
+    lo = lb;
+    w.kp = k_lb;
+  }
+  hi = fmax(hi, lo);
+  hi = fmin(hi, fmax(ub, lo));
+  hi = fmin(hi, 2.0 * lo);
+  w.lo = lo;
+  w.hi = hi;
+  return w;
+}
+
+// One segment of UPD_SEG = 16 lanes per column: the lanes split the column's partials and its
+// listed window entries (in registers), reduce on the DPP crossbar, and every lane takes the
+// same decisions from the same numbers, so the kernel needs no LDS and no barrier.
+constexpr int UPD_SEG = 16;
+constexpr int UPD_COLS = WG / UPD_SEG;   // columns per workgroup
+static_assert(UPD_SEG == LIST_LANES, "the list capacity is planned for this many lanes per column");
+
+__global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m, Geometry g,
+                                                        Ws ws, int sweep) {
+  __shared__ BlockScratch<WAVES> bs;
+  const mlproj_result* res = ws.res;
+  if (res->inside_ball != 0u || res->n_active == 0u) return;
+  if (sweep > 0 && ws.pending[sweep] == 0u) return;
+
+  const int part = threadIdx.x % UPD_SEG;
+  const int seg_base = (threadIdx.x & (WAVE - 1)) & ~(UPD_SEG - 1);   // first lane of the segment
+  const long long j = (long long)blockIdx.x * UPD_COLS + threadIdx.x / UPD_SEG;
+  const bool mine = j < m && ws.done[j] == 0u;
+
+  // fold the partial sums and counts of the sweep
+  double S = 0.0;
+  unsigned K = 0u, K2 = 0u;
+  if (mine) {
+    const long long t = j / g.tile_w, c = j % g.tile_w;
+    const size_t base = (size_t)t * g.groups * g.tile_w + c;
+    const double* ps = static_cast<const double*>(ws.partial);
+    for (long long b = part; b < g.groups; b += UPD_SEG) {
+      S += ps[base + (size_t)b * g.tile_w];
+      K += ws.partial_cnt[base + (size_t)b * g.tile_w];
+      if (sweep == 0) K2 += ws.partial_cnt2[base + (size_t)b * g.tile_w];
+    }
+  }
+  S = __shfl(seg_sum<UPD_SEG>(S), seg_base);   // one lane's sum for all: the lanes must agree
+  K = seg_sum_u<UPD_SEG>(K);
+  K2 = seg_sum_u<UPD_SEG>(K2);
+
+  // the listed window entries, split over the lanes
+  unsigned r = 0u;
+  bool complete = false;
+  float mylist[LIST_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < LIST_PER_THREAD; ++i) mylist[i] = 0.0f;
+  double sc = 0.0;
+  if (sweep > 0 && mine) {
+    r = ws.gcnt[j];
+    complete = ws.gflag[j] == 0u && r <= (unsigned)ws.list_cap;
+    if (complete && r > 0u) {
+      // every load is unconditional (a slot past the end re-reads the last entry and is then
+      // blanked), so they are all in flight together
+#pragma unroll
+      for (int i = 0; i < LIST_PER_THREAD; ++i) {
+        const unsigned s = (unsigned)part + (unsigned)i * (unsigned)UPD_SEG;
+        mylist[i] = ws.cand[(size_t)(s < r ? s : r - 1u) * (size_t)m + (size_t)j];
+      }
+#pragma unroll
+      for (int i = 0; i < LIST_PER_THREAD; ++i) {
+        const unsigned s = (unsigned)part + (unsigned)i * (unsigned)UPD_SEG;
+        if (s >= r) mylist[i] = 0.0f;
+        sc += (double)mylist[i];
+      }
+    }
+  }
+  sc = seg_sum<UPD_SEG>(sc);   // exact (see the note on windows above): the same in every lane
+
+  bool closed = false, solving = false;
+  double tau = 0.0, uj = 0.0, lo = 0.0, lb = 0.0, ub = 0.0;
+  Window w{0.0, 0.0, NO_COUNT};
+  if (mine) {
+    uj = radius(ws.v[j], top_of(res));
+    const double hi = ws.tauj[j];
+    lo = ws.tlo[j];
+    lb = ws.lb[j];
+    ub = ws.ub[j];
+    unsigned k_lb = NO_COUNT;  // count at the point whose Newton step is lb, when lb moved now
+    tau = hi;
+    w = Window{hi, hi, NO_COUNT};
+    const double f_hi = (S - (double)K * hi) - uj;
+    const double n_hi = K > 0u ? (S - uj) / (double)K : -HUGE_VAL;
+    if (sweep == 0) {
+      // evaluated at the guess hi = lo, density from the entries in (hi, hi(1 + 1/16)]
+      if (n_hi > lb) { lb = n_hi; k_lb = K; }
+      if (f_hi <= 0.0) ub = fmin(ub, hi);
+      const double rho = (double)(K - K2) / (hi * L11_WINDOW);
+      if (ub <= lb * (1.0 + 1e-12)) { closed = true; tau = lb; }
+      else w = next_window(hi, f_hi, (double)K, rho, lb, k_lb, ub, K == 0u, ws.list_cap);
+    } else {
+      const unsigned k_lo = K + r;  // entries above lo
+      double f_lo = 0.0, n_lo = -HUGE_VAL;
+      if (complete) {
+        const double s_lo = S + sc;
+        f_lo = (s_lo - (double)k_lo * lo) - uj;
+        if (k_lo > 0u) n_lo = (s_lo - uj) / (double)k_lo;
+      }
+      if (ws.kprev[j] != NO_COUNT && k_lo == ws.kprev[j]) {
+        closed = true;  // lo is the Newton step of a point with the same active set
+        tau = lo;
+      } else if (K > 0u && fabs(f_hi) <= 1e-13 * (S + uj)) {
+        closed = true;  // the Newton step from hi does not move: hi is the root, to rounding
+        tau = n_hi;
+      } else if (complete && f_lo >= 0.0 && f_hi <= 0.0) {
+        closed = true;  // the root is inside the window and every entry of the window is known
+        solving = true;
+        tau = lo;
+      } else {
+        if (n_hi > lb) { lb = n_hi; k_lb = K; }
+        if (complete && n_lo > lb) { lb = n_lo; k_lb = k_lo; }
+        if (f_hi <= 0.0) ub = fmin(ub, hi);
+        if (complete && f_lo <= 0.0) ub = fmin(ub, lo);
+        if (ub <= lb * (1.0 + 1e-12)) { closed = true; tau = lb; }
+        else {
+          const double rho = (hi > lo && r > 0u) ? (double)r / (hi - lo) : 0.0;
+          const bool from_lo = complete && fabs(f_lo) < fabs(f_hi);
+          w = next_window(from_lo ? lo : hi, from_lo ? f_lo : f_hi, (double)(from_lo ? k_lo : K),
+                          rho, lb, k_lb, ub, K == 0u && r == 0u, ws.list_cap);
+        }
+      }
+    }
+  }
+
+  // The root inside a window whose entries are all listed: the fixed point of the outer
+  // search on "entries above hi" (S, K) plus the listed ones, started at lo where f_j >= u_j.
+  // The lanes of a wavefront loop together until the last of its columns is done.
+  unsigned kp = NO_COUNT;
+  for (unsigned round = 0; __any(solving) && round < (unsigned)FILTER_MAX_LIST + 2u; ++round) {
+    double sa = 0.0;
+    unsigned ka = 0u;
+#pragma unroll
+    for (int i = 0; i < LIST_PER_THREAD; ++i)
+      if ((double)mylist[i] > tau) { sa += (double)mylist[i]; ++ka; }
+    sa = seg_sum<UPD_SEG>(sa);   // exact, the same in every lane
+    ka = seg_sum_u<UPD_SEG>(ka) + K;
+    if (solving) {
+      const double tn = ka > 0u ? ((S + sa) - uj) / (double)ka : tau;
+      if (ka == kp || ka == 0u) {
+        tau = tn;
+        solving = false;
+      } else {
+        kp = ka;
+        tau = fmax(tau, tn);
+      }
+    }
+  }
+
+  unsigned open = 0u;
+  if (part == 0 && j < m) {
+    if (mine) {
+      ws.tauj[j] = closed ? tau : w.hi;
+      ws.tlo[j] = closed ? tau : w.lo;
+      ws.kprev[j] = w.kp;
+      ws.lb[j] = lb;
+      ws.ub[j] = ub;
+      ws.done[j] = closed ? 1u : 0u;
+      open = closed ? 0u : 1u;
+    }
+    ws.gcnt[j] = 0u;
+    ws.gflag[j] = 0u;
+  }
+  const unsigned wg_open = block_sum_u(open, bs);
+  if (threadIdx.x == 0) {
+    if (wg_open) atomicAdd(&ws.pending[sweep + 1], wg_open);
+    if (blockIdx.x == 0) ws.res->inner_sweeps = (unsigned)sweep + 1u;
+  }
+}
+
+// After the last sweep: how many columns were still open (0 = every inner search is exact).
+// (Only for a call that stops before the map pass, which otherwise does this itself.)
+__global__ void l11_close_kernel(Ws ws) {
+  if (threadIdx.x == 0) {
+    const unsigned s = ws.res->inner_sweeps;
+    ws.res->inner_pending = (s >= (unsigned)MAX_INNER_SWEEPS) ? ws.pending[MAX_INNER_SWEEPS] : 0u;
+  }
+}
+
+}  // namespace mlproj
+
+#endif

@@ -1,0 +1,306 @@
+// mlproj: the l1-ball threshold search (Eq. 6-7) and the other outer projections.
+#ifndef MLPROJ_SEARCH_H
+#define MLPROJ_SEARCH_H
+
+#include "common.h"
+#include "reduce.h"
+
+namespace mlproj {
+
+// ------------------------------------------------------------------ threshold search
+// Euclidean projection of v >= 0 onto the l1 ball of radius eta (Eq. 6-7): tau = 0 when
+// sum(v) <= eta, otherwise the root of sum_j max(v_j - tau, 0) = eta.  The root is reached
+// by the fixed point tau <- (sum_{v_j > tau} v_j - eta) / #{v_j > tau}, started from a lower
+// bound; tau rises monotonically, the active set only shrinks, and when it stops shrinking
+// tau is exactly (sum over the final active set - eta) / K, in fp64.
+// Run by one whole workgroup of NT threads; every thread returns the same record.  Because
+// the arithmetic and its order are fixed, any number of workgroups that run it on the same v
+// get the same bits, which lets the map kernels run it redundantly instead of waiting for a
+// separate one-workgroup kernel.
+struct SearchOut {
+  double tau, scale, cap;   // u_j = min(cap, scale * max(v_j - tau, 0))
+  double total, vmax, norm; // sum v, max v, ||v||_p
+  unsigned active, iters, inside;
+};
+
+// How the outer projection u = P^p_eta(v) acts on one aggregate (Eq. 6-7; Sec. 3 names the
+// l1, l2 and l_inf balls as available outer projections): shrink by tau (p = 1), rescale
+// (p = 2) or cap at eta (p = inf).  For p = 1 scale is 1 and cap is +inf, which leaves
+// max(v - tau, 0) bit for bit.
+struct Top {
+  double tau, scale, cap;
+};
+__device__ __forceinline__ double radius(double v, const Top& t) {
+  return fmin(t.cap, t.scale * fmax(v - t.tau, 0.0));
+}
+__device__ __forceinline__ Top top_of(const SearchOut& o) { return Top{o.tau, o.scale, o.cap}; }
+__device__ __forceinline__ Top top_of(const mlproj_result* r) { return Top{r->tau, r->scale, r->cap}; }
+
+template <int NT, int CACHE = SEARCH_CACHE>
+__device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, long long ngroups,
+                                                  double eta, int mode, int outer,
+                                                  PairScratch<NT / WAVE>& s) {
+  const int tid = threadIdx.x;
+  double vr[CACHE];
+  double a = 0.0, mx = 0.0;
+#pragma unroll
+  for (int k = 0; k < CACHE; ++k) {
+    const long long i = tid + (long long)k * NT;
+    vr[k] = i < ngroups ? v[i] : 0.0;  // 0 is never active: tau >= 0 and the test is strict
+    a += vr[k];
+    mx = fmax(mx, vr[k]);
+  }
+  for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
+    const double x = v[i];
+    a += x;
+    mx = fmax(mx, x);
+  }
+  SearchOut o;
+  block_sum_max(a, mx, s);
+  o.total = a;
+  o.vmax = mx;
+  o.norm = a;
+  o.tau = 0.0;
+  o.scale = 1.0;
+  o.cap = HUGE_VAL;
+  o.active = 0;
+  o.iters = 0;
+  o.inside = 0;
+  if (mode == MODE_NORM) {
+    // norm only: nothing to search
+  } else if (outer != MLPROJ_OUTER_L1) {
+    // l2 ball: rescale by eta / ||v||_2; l_inf ball: cap at eta.  No iteration.
+    double sq = 0.0, dummy = 0.0;
+    unsigned c = 0;
+#pragma unroll
+    for (int k = 0; k < CACHE; ++k) { sq = fma(vr[k], vr[k], sq); c += vr[k] > 0.0 ? 1u : 0u; }
+    for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
+      const double x = v[i];
+      sq = fma(x, x, sq);
+      c += x > 0.0 ? 1u : 0u;
+    }
+    block_sum_count(sq, c, s);
+    (void)dummy;
+    if (outer == MLPROJ_OUTER_L2) {
+      o.norm = sqrt(sq);
+      o.inside = o.norm <= eta ? 1u : 0u;
+      if (!o.inside) o.scale = eta / o.norm;
+    } else {
+      o.norm = o.vmax;
+      o.inside = o.vmax <= eta ? 1u : 0u;
+      if (!o.inside) o.cap = eta;
+    }
+    o.active = eta == 0.0 ? 0u : c;
+  } else if (eta == 0.0) {
+    o.tau = o.vmax;  // nothing exceeds vmax: every u_j is 0
+  } else if (o.total <= eta) {
+    o.inside = 1;  // already in the ball: tau = 0, u = v
+    unsigned c = 0;
+#pragma unroll
+    for (int k = 0; k < CACHE; ++k) c += vr[k] > 0.0 ? 1u : 0u;
+    for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT)
+      c += v[i] > 0.0 ? 1u : 0u;
+    double zero = 0.0;
+    block_sum_count(zero, c, s);
+    o.active = c;
+  } else {
+    // two lower bounds on the root: all groups active, and only the largest active
+    double tau = fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
+    unsigned kprev = 0xffffffffu;
+    for (;;) {
+      double sum = 0.0;
+      unsigned cnt = 0;
+#pragma unroll
+      for (int k = 0; k < CACHE; ++k) {
+        if (vr[k] > tau) { sum += vr[k]; ++cnt; }
+      }
+      for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
+        const double x = v[i];
+        if (x > tau) { sum += x; ++cnt; }
+      }
+      block_sum_count(sum, cnt, s);
+      const double S = sum;
+      const unsigned K = cnt;
+      o.active = K;
+      if (K == 0u || K == kprev) break;  // K == 0: eta below the resolution of vmax
+      kprev = K;
+      const double t = (S - eta) / (double)K;
+      if (t > tau) tau = t;
+      ++o.iters;
+    }
+    o.tau = tau;
+  }
+  return o;
+}
+
+__device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
+                                             double* __restrict__ norm_out) {
+  mlproj_result* r = ws.res;
+  r->tau = o.tau;
+  r->scale = o.scale;
+  r->cap = o.cap;
+  r->norm = o.norm;
+  r->vmax = o.vmax;
+  r->n_active = o.active;
+  r->inside_ball = o.inside;
+  r->search_iters = o.iters;
+  r->inner_sweeps = 0;
+  r->inner_pending = 0;
+  if (norm_out) *norm_out = o.total;
+}
+
+// radii / u_out (optional): also write u_j = max(v_j - tau, 0) for every group.
+__global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
+                                                     int mode, int outer,
+                                                     double* __restrict__ norm_out,
+                                                     int only_as_fallback,
+                                                     double* __restrict__ radii,
+                                                     float* __restrict__ u_out) {
+  __shared__ PairScratch<SWAVES> s;
+  if (only_as_fallback && ws.flags[1] == 0u) return;
+  const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, outer, s);
+  if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
+  if (threadIdx.x == 0) write_result(ws, o, norm_out);
+  if (radii) {
+    const Top top = top_of(o);
+    for (long long i = threadIdx.x; i < ngroups; i += SWG) {
+      const double u = radius(ws.v[i], top);
+      radii[i] = u;
+      if (u_out) u_out[i] = (float)u;
+    }
+  }
+}
+
+// The same search for very long v (more groups than one workgroup holds in registers): up to
+// 64 workgroups, each keeping its slice of v in registers.  Every round each workgroup files
+// the sum and count of its slice above tau, all wait at a barrier, and every workgroup adds up
+// all slices in the same fixed order, so all of them step tau identically and leave the loop
+// together.  Slots alternate by round parity so that a fast workgroup never overwrites what a
+// slow one is still reading.
+//
+// The barrier is built for this GPU, where a device-scope fence means an L2 write-back
+// (microseconds, and it serialises): everything the workgroups exchange -- the slots and the
+// arrival counter -- is written with device-scope atomic read-modify-writes, which are
+// performed at the memory side, and read with device-scope atomic loads, which bypass the
+// per-XCD L2; "s_waitcnt vmcnt(0)" makes a wavefront's slot writes complete before its
+// arrival is counted.  No ordinary load or store takes part, so no cache has to be flushed.
+// The grid is far smaller than the chip, so all workgroups become resident; a workgroup that
+// nevertheless waits SPIN_LIMIT polls raises flags[1] and everybody leaves: the kernel always
+// ends, and the one-workgroup search_kernel queued behind it then does the work instead.
+__device__ __forceinline__ bool wide_barrier(unsigned* flags, unsigned target, unsigned* lds_ok) {
+  if (threadIdx.x == 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __hip_atomic_fetch_add(&flags[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0, ok = 1;
+    while (__hip_atomic_load(&flags[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (__hip_atomic_load(&flags[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u || ++spins > SPIN_LIMIT) {
+        ok = 0;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok) __hip_atomic_exchange(&flags[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *lds_ok = ok;
+  }
+  __syncthreads();
+  const bool ok = *lds_ok != 0u;
+  __syncthreads();
+  return ok;
+}
+__device__ __forceinline__ void put_f64(double* p, double x) {
+  __hip_atomic_exchange(reinterpret_cast<unsigned long long*>(p),
+                        (unsigned long long)__double_as_longlong(x), __ATOMIC_RELAXED,
+                        __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double get_f64(const double* p) {
+  return __longlong_as_double((long long)__hip_atomic_load(
+      reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+__global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngroups, double eta,
+                                                          int mode, double* __restrict__ norm_out) {
+  __shared__ PairScratch<SWAVES> s;
+  __shared__ unsigned lds_ok;
+  const int tid = threadIdx.x;
+  const int nwg = (int)gridDim.x, wg = (int)blockIdx.x;
+  const long long chunk = (ngroups + nwg - 1) / nwg;
+  const long long lo = (long long)wg * chunk;
+  const long long hi = (lo + chunk < ngroups) ? lo + chunk : ngroups;
+
+  double vr[COOP_VALUES];
+  double a = 0.0, mx = 0.0;
+#pragma unroll
+  for (int k = 0; k < COOP_VALUES; ++k) {
+    const long long i = lo + tid + (long long)k * SWG;
+    vr[k] = i < hi ? ws.v[i] : 0.0;
+    a += vr[k];
+    mx = fmax(mx, vr[k]);
+  }
+  for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
+    const double x = ws.v[i];
+    a += x;
+    mx = fmax(mx, x);
+  }
+  block_sum_max(a, mx, s);
+  if (tid == 0) { put_f64(&ws.coop_d[wg], a); put_f64(&ws.coop_m[wg], mx); }
+  unsigned round = 1;  // barrier rounds so far; parity 0 carries the totals
+  if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
+  SearchOut o;
+  o.total = tid < nwg ? get_f64(&ws.coop_d[tid]) : 0.0;
+  o.vmax = tid < nwg ? get_f64(&ws.coop_m[tid]) : 0.0;
+  block_sum_max(o.total, o.vmax, s);
+  o.norm = o.total;
+  o.tau = 0.0;
+  o.scale = 1.0;
+  o.cap = HUGE_VAL;
+  o.active = 0;
+  o.iters = 0;
+  o.inside = 0;
+  if (mode == MODE_NORM) {
+  } else if (eta == 0.0) {
+    o.tau = o.vmax;
+  } else {
+    const bool inside = o.total <= eta;
+    double tau = inside ? 0.0 : fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
+    unsigned kprev = 0xffffffffu;
+    for (;;) {
+      double sum = 0.0;
+      unsigned cnt = 0;
+#pragma unroll
+      for (int k = 0; k < COOP_VALUES; ++k) {
+        if (vr[k] > tau) { sum += vr[k]; ++cnt; }
+      }
+      for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
+        const double x = ws.v[i];
+        if (x > tau) { sum += x; ++cnt; }
+      }
+      block_sum_count(sum, cnt, s);
+      const unsigned par = round & 1u;
+      if (tid == 0) {
+        put_f64(&ws.coop_d[par * COOP_MAX_WGS + wg], sum);
+        __hip_atomic_exchange(&ws.coop_u[par * COOP_MAX_WGS + wg], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      ++round;
+      if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
+      double S = tid < nwg ? get_f64(&ws.coop_d[par * COOP_MAX_WGS + tid]) : 0.0;
+      unsigned K = tid < nwg ? __hip_atomic_load(&ws.coop_u[par * COOP_MAX_WGS + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      block_sum_count(S, K, s);
+      o.active = K;
+      if (inside || K == 0u || K == kprev) break;  // inside: one round, just to count
+      kprev = K;
+      const double t = (S - eta) / (double)K;
+      if (t > tau) tau = t;
+      ++o.iters;
+    }
+    o.tau = tau;
+    o.inside = inside ? 1u : 0u;
+  }
+  if (wg == 0) {
+    if (tid <= MAX_INNER_SWEEPS) ws.pending[tid] = 0u;
+    if (tid == 0) write_result(ws, o, norm_out);
+  }
+}
+
+}  // namespace mlproj
+
+#endif
