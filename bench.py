@@ -184,6 +184,36 @@ def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
     return out
 
 
+def bench_batch(torch, mp, shape, count, frac, steps, warmup):
+    """`count` matrices of one shape: one bilevel_proj_batch call against a loop of single calls."""
+    import numpy as np
+    from paper_2405_02086_amd import workloads
+    dev = torch.device("cuda:0")
+    Ys = [torch.from_numpy(workloads.generate(shape, "normal", workloads.BASE_SEED + 100 + i)).to(dev) for i in range(count)]
+    Xs = [torch.empty_like(Y) for Y in Ys]
+    wss = [mp.Workspace.for_call("l1inf", shape[0], shape[1], device=dev) for _ in Ys]
+    etas = [device_eta(mp, Y, "l1inf", frac, ws) for Y, ws in zip(Ys, wss)]
+
+    def loop():
+        for Y, X, ws, eta in zip(Ys, Xs, wss, etas):
+            mp.bilevel_proj_l1inf(Y, eta, X=X, workspace=ws)
+
+    def batch():
+        mp.bilevel_proj_batch(Ys, etas, "inf", Xs=Xs, workspaces=wss)
+
+    out = {"shape": list(shape), "count": count}
+    for name, fn in (("ms_loop_of_single_calls", loop), ("ms_one_batch_call", batch)):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        out[name] = (time.perf_counter() - t0) * 1e3 / steps
+    return out
+
+
 def cpu_baseline(Y_host, eta, x_timed, tau_gpu, budget_s=20.0):
     """The oracle as it stands, single numpy thread, on the headline workload with the radius
     the GPU runs used; its result also checks the X the last timed GPU step produced."""
@@ -271,6 +301,8 @@ def main():
         wt, Yt = workloads.make("tensor_256x256x256")
         for k, v in bench_tensor(torch, mp, Yt, wt.eta_frac, 100, 10).items():
             also["tensor_256x256x256/" + k] = v
+        also["batch/16x(256x128)"] = bench_batch(torch, mp, (256, 128), 16, 0.1, 100, 10)
+        also["batch/16x(1024x1024)"] = bench_batch(torch, mp, (1024, 1024), 16, 0.1, 100, 10)
         line["also"] = also
     if want_cpu:
         line["cpu_baseline"] = cpu_baseline(Y, head["eta"], x_timed, head["tau"])

@@ -181,6 +181,30 @@ int bilevel_proj_stored(int storage, int outer_norm, int variant,
                         float* u_out /* device, m; may be NULL */,
                         unsigned char* mask_out /* device, m; may be NULL */, void* stream);
 
+/* One problem of a batch: the arguments of bilevel_proj_stored for one matrix. */
+typedef struct mlproj_problem {
+  const void* Y;              /* device, n*m elements                               */
+  void* X;                    /* device, n*m elements; may alias Y                  */
+  long long n, m;
+  float eta;
+  void* workspace;            /* device; its own for every problem of the batch     */
+  size_t workspace_bytes;     /* at least mlproj_workspace_bytes(variant, n, m, 1)  */
+  float* v_out;               /* device, m; may be NULL                             */
+  float* u_out;               /* device, m; may be NULL                             */
+  unsigned char* mask_out;    /* device, m; may be NULL                             */
+} mlproj_problem;
+
+/* `count` independent bi-level projections that share storage type, outer norm and variant
+ * (the weight matrices a training loop projects after a step, Sec. 6.3), with the results of
+ * `count` calls of bilevel_proj_stored, bit for bit.  Matrices of at most 16384 columns with
+ * variant MLPROJ_L1INF or MLPROJ_L12 share their kernel launches, 16 matrices at a time (three
+ * launches for all of them instead of three each, which is what small matrices cost); the
+ * others are enqueued one after another behind them.  `problems` is a host array, read before
+ * the call returns; all of it is checked before anything is enqueued.  Outputs of different
+ * problems must not overlap.                                                                 */
+int bilevel_proj_batch(int storage, int outer_norm, int variant, int count,
+                       const mlproj_problem* problems /* host */, void* stream);
+
 /* The two halves of a bi-level call, for callers that want the radii before (or without)
  * writing X.  bilevel_radii computes the aggregate v and u = P^1_eta(v) of Alg. 1 (for
  * MLPROJ_L11 also the per-column thresholds Alg. 3 needs) and leaves the outcome in the

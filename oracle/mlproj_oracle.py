@@ -26,7 +26,7 @@ __all__ = [
     "column_norms", "norm_l1q", "project_l1_ball_nonneg", "project_l1_ball",
     "project_linf_ball", "project_l2_ball", "bilevel_l1inf", "bilevel_l11",
     "bilevel_l12", "trilevel_l1infinf", "bilevel", "multilevel", "project_outer",
-    "round_to_storage", "bilevel_stored",
+    "round_to_storage", "bilevel_stored", "bilevel_batch",
 ]
 
 
@@ -244,6 +244,12 @@ def bilevel_stored(Y, eta, q, storage, columns=None, p=1):
     out["X"] = round_to_storage(out["X32"], storage)
     out["mask"] = np.asarray(out["u"], dtype=np.float64) > 0
     return out
+
+
+def bilevel_batch(Ys, etas, q, storage="f32", p=1):
+    """A batch is nothing but independent projections: one bilevel_stored per matrix."""
+    assert len(Ys) == len(etas)
+    return [bilevel_stored(Y, eta, q, storage, p=p) for Y, eta in zip(Ys, etas)]
 
 
 # --------------------------------------------------------------------------

@@ -92,10 +92,19 @@ def lib():
     L.bilevel_proj_pq.argtypes = [c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     L.bilevel_proj_stored.restype = c_i
     L.bilevel_proj_stored.argtypes = [c_i, c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
+    L.bilevel_proj_batch.restype = c_i
+    L.bilevel_proj_batch.argtypes = [c_i, c_i, c_i, c_i, ctypes.POINTER(Problem), c_vp]
     L.trilevel_proj_l1infinf.restype = c_i
     L.trilevel_proj_l1infinf.argtypes = [c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     _lib = L
     return L
+
+
+class Problem(ctypes.Structure):
+    """mlproj_problem of include/mlproj.h."""
+    _fields_ = [("Y", ctypes.c_void_p), ("X", ctypes.c_void_p), ("n", ctypes.c_longlong), ("m", ctypes.c_longlong),
+                ("eta", ctypes.c_float), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("v_out", ctypes.c_void_p), ("u_out", ctypes.c_void_p), ("mask_out", ctypes.c_void_p)]
 
 
 EXPORTS = (
@@ -103,7 +112,7 @@ EXPORTS = (
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
-    "bilevel_proj_stored",
+    "bilevel_proj_stored", "bilevel_proj_batch",
 )
 
 
@@ -254,6 +263,41 @@ def bilevel_proj_stored(Y, eta, q, p=1, X=None, workspace=None, v_out=None, u_ou
                                    _ptr(u_out), _ptr(mask_out), _stream(stream))
     _check(st, "bilevel_proj_stored")
     return X
+
+
+def bilevel_proj_batch(Ys, etas, q, p=1, Xs=None, workspaces=None, v_outs=None, u_outs=None, mask_outs=None,
+                       stream=None):
+    """Independent BP^{p,q} projections of the matrices in Ys (same dtype, any shapes) with radii
+    etas, through bilevel_proj_batch; returns the list of X tensors.  Optional lists give the
+    per-problem X, workspace, v_out, u_out and mask_out."""
+    import torch
+    storages = {torch.float32: STORE_F32, torch.bfloat16: STORE_BF16, torch.float16: STORE_F16}
+    count = len(Ys)
+    assert count > 0 and len(etas) == count
+    variant = {"inf": L1INF, 1: L11, 2: L12}[q]
+    pick = lambda lst, i: None if lst is None else lst[i]
+    problems = (Problem * count)()
+    out = []
+    alive = []   # every problem needs a workspace of its own until the batch has been enqueued
+    for i, Y in enumerate(Ys):
+        assert Y.is_cuda and Y.dim() == 2 and Y.is_contiguous() and Y.dtype == Ys[0].dtype and Y.dtype in storages
+        n, m = Y.shape
+        X = pick(Xs, i)
+        if X is None:
+            X = torch.empty_like(Y)
+        assert X.is_cuda and X.dtype == Y.dtype and X.is_contiguous() and X.shape == Y.shape
+        ws = pick(workspaces, i) or Workspace.for_call(variant, n, m, device=Y.device, stream=stream)
+        alive.append(ws)
+        out.append(X)
+        pr = problems[i]
+        pr.Y, pr.X, pr.n, pr.m, pr.eta = Y.data_ptr(), X.data_ptr(), n, m, float(etas[i])
+        pr.workspace, pr.workspace_bytes = ws.buf.data_ptr(), ws.nbytes
+        for field, lst in (("v_out", v_outs), ("u_out", u_outs), ("mask_out", mask_outs)):
+            t = pick(lst, i)
+            setattr(pr, field, None if t is None else t.data_ptr())
+    st = lib().bilevel_proj_batch(storages[Ys[0].dtype], _OUTERS[p], variant, count, problems, _stream(stream))
+    _check(st, "bilevel_proj_batch")
+    return out
 
 
 NORM_INF, NORM_L1, NORM_L2 = 0, 1, 2

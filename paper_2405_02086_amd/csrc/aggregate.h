@@ -27,18 +27,19 @@ __device__ __forceinline__ typename AccOf<Q>::type combine(typename AccOf<Q>::ty
 // Partial column aggregates of v_j = ||y_j||_q (Sec. 3): max |.| (exact), sum |.| or sum of
 // squares (both in fp64).  Every lane owns VEC columns of the tile (see LaneCols); the four
 // wavefronts of a workgroup take rows r, r+1, r+2, r+3 (mod 4) of each row block.
+// `bid` is the workgroup's number within its own problem (blockIdx.x for a single matrix).
 template <int Q, typename T, int VEC, bool STRIDED>
-__global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, long long n,
-                                                    long long m, Geometry g,
-                                                    void* __restrict__ partial_) {
+__device__ __forceinline__ void colagg_body(const T* __restrict__ Y, long long n, long long m,
+                                            const Geometry& g, void* __restrict__ partial_,
+                                            long long bid) {
   using Acc = typename AccOf<Q>::type;
   constexpr int TILE_W = WAVE * VEC;
   __shared__ Acc sm[WAVES][TILE_W];
 
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
-  const long long t = blockIdx.x % g.tiles;
-  const long long grp = blockIdx.x / g.tiles;
+  const long long t = bid % g.tiles;
+  const long long grp = bid / g.tiles;
   const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
 
   Acc acc[VEC];
@@ -74,23 +75,29 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, lon
   }
 }
 
+template <int Q, typename T, int VEC, bool STRIDED>
+__global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, long long n,
+                                                    long long m, Geometry g,
+                                                    void* __restrict__ partial_) {
+  colagg_body<Q, T, VEC, STRIDED>(Y, n, m, g, partial_, blockIdx.x);
+}
+
 // v_j from the partials of its tile, folded in a fixed order.  A workgroup of 1024 threads
 // covers 1024/parts groups with `parts` threads each (parts = 1..16, a power of two chosen on
 // the host from the number of partials per group); every thread keeps 8 loads in flight.
 // Serves columns (tile_w = 64*vec) and slabs (tile_w = 1) alike.
 template <int Q>
-__global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ partial_,
-                                                     long long ngroups, Geometry g, int parts,
-                                                     double* __restrict__ v,
-                                                     float* __restrict__ v_out,
-                                                     unsigned* __restrict__ flags) {
+__device__ __forceinline__ void reduce_body(const void* __restrict__ partial_, long long ngroups,
+                                            const Geometry& g, int parts, double* __restrict__ v,
+                                            float* __restrict__ v_out,
+                                            unsigned* __restrict__ flags, long long bid) {
   using Acc = typename AccOf<Q>::type;
   __shared__ Acc sm[SWG];
-  if (blockIdx.x == 0 && threadIdx.x < 2) flags[threadIdx.x] = 0u;  // for the grid-wide search
+  if (bid == 0 && threadIdx.x < 2) flags[threadIdx.x] = 0u;  // for the grid-wide search
   const int cols = SWG / parts;
   const int c_local = threadIdx.x % cols;
   const int part = threadIdx.x / cols;
-  const long long j = (long long)blockIdx.x * cols + c_local;
+  const long long j = bid * cols + c_local;
   Acc a = (Acc)0;
   if (j < ngroups) {
     const long long t = j / g.tile_w, c = j % g.tile_w;
@@ -114,6 +121,15 @@ __global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ pa
     v[j] = vj;
     if (v_out) v_out[j] = (float)vj;
   }
+}
+
+template <int Q>
+__global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ partial_,
+                                                     long long ngroups, Geometry g, int parts,
+                                                     double* __restrict__ v,
+                                                     float* __restrict__ v_out,
+                                                     unsigned* __restrict__ flags) {
+  reduce_body<Q>(partial_, ngroups, g, parts, v, v_out, flags, blockIdx.x);
 }
 
 }  // namespace mlproj

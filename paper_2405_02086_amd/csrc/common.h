@@ -81,13 +81,13 @@ struct Layout {
   int list_cap;
 };
 
-static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-static inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
+__host__ __device__ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+__host__ __device__ static inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
 
 // Both passes were tuned on an MI355X: a read-only pass is fastest with about two workgroups
 // per CU, the read+write pass with one per CU and fewer rows in flight (a narrower band of
 // DRAM pages open at a time).
-static Geometry plan_columns(long long n, long long m, int vec, int variant) {
+__host__ __device__ static inline Geometry plan_columns(long long n, long long m, int vec, int variant) {
   Geometry g;
   g.vec = vec;
   g.tile_w = WAVE * vec;
@@ -126,7 +126,7 @@ static Geometry plan_slabs(long long d0, long long len, int vec) {
 
 // Threads per group in the kernels that fold per-(tile, row group) partials: a power of two,
 // at most 16, chosen from the number of partials per group.
-static int reduce_parts(long long partials_per_group) {
+__host__ __device__ static inline int reduce_parts(long long partials_per_group) {
   int parts = 1;
   while (parts < SWAVES && parts < partials_per_group) parts *= 2;
   return parts;
@@ -135,7 +135,7 @@ static int reduce_parts(long long partials_per_group) {
 constexpr int LIST_PER_THREAD = 16;      // l1,1: listed entries one lane of the update kernel holds in registers
 constexpr int LIST_LANES = 16;           // ... and the lanes that share a column there
 
-static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
+__host__ __device__ static inline Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   Layout L{};
   size_t o = align_up(sizeof(mlproj_result), 256);
   L.off_pending = o;       o = align_up(o + (MAX_INNER_SWEEPS + 1) * 4, 256);
@@ -168,7 +168,7 @@ static Layout layout_for(const Geometry& g, long long ngroups, int variant) {
   return L;
 }
 
-static Ws bind(void* workspace, const Layout& L) {
+__host__ __device__ static inline Ws bind(void* workspace, const Layout& L) {
   char* b = static_cast<char*>(workspace);
   Ws w;
   w.res = reinterpret_cast<mlproj_result*>(b);

@@ -17,19 +17,20 @@ namespace mlproj {
 // read last there (the ones most likely still cached) are read first here.
 // With fused_eta >= 0 every workgroup first runs the threshold search itself (see
 // search_block) and workgroup 0 files the result record; otherwise tau is read from it.
-template <int Q, typename T, int VEC, bool STRIDED, bool XVEC, int SC = SEARCH_CACHE>
-__global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long n,
-                                                    long long m, Geometry g, Ws ws,
-                                                    float* __restrict__ u_out,
-                                                    unsigned char* __restrict__ mask_out,
-                                                    double fused_eta, int outer) {
+// `bid` is the workgroup's number within its own problem (blockIdx.x for a single matrix).
+template <int Q, typename T, int VEC, bool STRIDED, bool XVEC, int SC>
+__device__ __forceinline__ void colmap_body(const T* Y, T* X, long long n, long long m,
+                                            const Geometry& g, const Ws& ws,
+                                            float* __restrict__ u_out,
+                                            unsigned char* __restrict__ mask_out,
+                                            double fused_eta, int outer, long long bid) {
   constexpr int TILE_W = WAVE * VEC;
   constexpr int U = MAP_UNROLL;
   __shared__ PairScratch<WAVES> bs;
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
-  const long long t = blockIdx.x % g.tiles;
-  const long long grp = blockIdx.x / g.tiles;
+  const long long t = bid % g.tiles;
+  const long long grp = bid / g.tiles;
   const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
   const bool col_ok = lc.any();
 
@@ -55,13 +56,13 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
     const SearchOut o = search_block<WG, SC>(ws.v, m, fused_eta, MODE_PROJECT, outer, bs);
     top = top_of(o);
     inside = o.inside != 0u;
-    if (blockIdx.x == 0 && threadIdx.x == 0) write_result(ws, o, nullptr);
+    if (bid == 0 && threadIdx.x == 0) write_result(ws, o, nullptr);
   } else {
     top = top_of(ws.res);
     inside = ws.res->inside_ball != 0u;
     if constexpr (Q == Q1) {
       // how many columns the inner searches left open (0 = every threshold is exact)
-      if (blockIdx.x == 0 && threadIdx.x == 0) {
+      if (bid == 0 && threadIdx.x == 0) {
         const unsigned s = ws.res->inner_sweeps;
         ws.res->inner_pending = (s >= (unsigned)MAX_INNER_SWEEPS) ? ws.pending[MAX_INNER_SWEEPS] : 0u;
       }
@@ -129,6 +130,16 @@ __global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long 
 #pragma unroll
     for (int r = 0; r < U; ++r) x[r] = y[r];
   }
+}
+
+template <int Q, typename T, int VEC, bool STRIDED, bool XVEC, int SC = SEARCH_CACHE>
+__global__ __launch_bounds__(WG) void colmap_kernel(const T* Y, T* X, long long n,
+                                                    long long m, Geometry g, Ws ws,
+                                                    float* __restrict__ u_out,
+                                                    unsigned char* __restrict__ mask_out,
+                                                    double fused_eta, int outer) {
+  colmap_body<Q, T, VEC, STRIDED, XVEC, SC>(Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer,
+                                            blockIdx.x);
 }
 
 }  // namespace mlproj

@@ -24,6 +24,7 @@
 #include "l11.h"
 #include "slab.h"
 #include "fibre.h"
+#include "batch.h"
 
 namespace mlproj {
 
@@ -122,7 +123,7 @@ template <int Q, typename T = float>
 static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
                        void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
                        void* stream_, int mode, double* norm_out, int stages, int outer,
-                       unsigned char* mask_out = nullptr) {
+                       unsigned char* mask_out = nullptr, bool check_only = false) {
   constexpr int WIDE = 16 / (int)sizeof(T);
   if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
   const bool need_x = mode == MODE_PROJECT && (stages & STAGE_APPLY);
@@ -143,6 +144,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   if (g.tiles * g.groups > MAX_GRID) return MLPROJ_ERR_TOO_LARGE;
   const Layout L = layout_for(g, m, Q);
   if (workspace_bytes < L.bytes) return MLPROJ_ERR_WORKSPACE;
+  if (check_only) return MLPROJ_OK;
   const Ws ws = bind(workspace, L);
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
@@ -221,6 +223,76 @@ static int dispatch_stored(int outer, int variant, const void* Y, void* X, long 
   return dispatch_q(variant, static_cast<const T*>(Y), static_cast<T*>(X), n, m, eta, workspace,
                     workspace_bytes, v_out, u_out, stream, MODE_PROJECT, (double*)nullptr, STAGE_ALL,
                     outer, mask_out);
+}
+
+// ------------------------------------------------------------------ host: batches
+// Every problem is checked first (nothing is enqueued if one fails).  Problems whose map pass
+// can search tau itself (q = inf or 2, at most 16384 columns) go through the batch kernels,
+// BATCH_MAX at a time; the others (l1,1, more columns) are enqueued one by one behind them.
+template <int Q, typename T>
+static int run_batch(int outer, int count, const mlproj_problem* pr, void* stream_) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  for (int i = 0; i < count; ++i) {
+    const int st = run_bilevel<Q, T>(static_cast<const T*>(pr[i].Y), static_cast<T*>(pr[i].X), pr[i].n, pr[i].m,
+                                     pr[i].eta, pr[i].workspace, pr[i].workspace_bytes, pr[i].v_out,
+                                     pr[i].u_out, stream_, MODE_PROJECT, nullptr, STAGE_ALL, outer,
+                                     pr[i].mask_out, true);
+    if (st != MLPROJ_OK) return st;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  auto batchable = [&](int i) { return Q != Q1 && pr[i].m <= FUSED_SEARCH_MAX_BIG; };
+  int i = 0;
+  while (i < count) {
+    BatchItems it;
+    BatchGrid agg, red, map;
+    it.count = 0;
+    bool big = false;
+    unsigned a = 0, r = 0, mp = 0;
+    for (; i < count && it.count < BATCH_MAX; ++i) {
+      if (!batchable(i)) continue;
+      const mlproj_problem& p = pr[i];
+      BatchItem& b = it.item[it.count];
+      b.Y = p.Y; b.X = p.X; b.ws = p.workspace;
+      b.v_out = p.v_out; b.u_out = p.u_out; b.mask_out = p.mask_out;
+      b.n = p.n; b.m = p.m; b.eta = (double)p.eta;
+      b.wide = pick_vec(p.Y, p.m, (int)sizeof(T)) == WIDE ? 1 : 0;
+      b.x_vec = aligned(p.X, 16) ? 1 : 0;
+      const Geometry g = plan_columns(p.n, p.m, WIDE, Q);
+      agg.first[it.count] = a; a += (unsigned)(g.tiles * g.groups);
+      red.first[it.count] = r; r += (unsigned)cdiv(p.m, SWG / reduce_parts(g.groups));
+      map.first[it.count] = mp; mp += (unsigned)(g.tiles * g.map_groups);
+      big = big || p.m > FUSED_SEARCH_MAX;
+      ++it.count;
+    }
+    if (it.count == 0) break;
+    agg.first[it.count] = a; red.first[it.count] = r; map.first[it.count] = mp;
+    mark(stream);
+    hipLaunchKernelGGL((colagg_batch_kernel<Q, T>), dim3(a), dim3(WG), 0, stream, it, agg);
+    mark(stream);
+    hipLaunchKernelGGL((reduce_batch_kernel<Q, T>), dim3(r), dim3(SWG), 0, stream, it, red);
+    mark(stream);
+    if (big) hipLaunchKernelGGL((colmap_batch_kernel<Q, T, SEARCH_CACHE_BIG>), dim3(mp), dim3(WG), 0, stream, it, map, outer);
+    else hipLaunchKernelGGL((colmap_batch_kernel<Q, T, SEARCH_CACHE>), dim3(mp), dim3(WG), 0, stream, it, map, outer);
+    mark(stream);
+  }
+  int st = launch_status();
+  for (int k = 0; k < count && st == MLPROJ_OK; ++k) {
+    if (batchable(k)) continue;
+    st = run_bilevel<Q, T>(static_cast<const T*>(pr[k].Y), static_cast<T*>(pr[k].X), pr[k].n, pr[k].m, pr[k].eta,
+                           pr[k].workspace, pr[k].workspace_bytes, pr[k].v_out, pr[k].u_out, stream_,
+                           MODE_PROJECT, nullptr, STAGE_ALL, outer, pr[k].mask_out);
+  }
+  return st;
+}
+
+template <typename T>
+static int dispatch_batch(int outer, int variant, int count, const mlproj_problem* pr, void* stream) {
+  switch (variant) {
+    case MLPROJ_L1INF: return run_batch<QINF, T>(outer, count, pr, stream);
+    case MLPROJ_L11: return run_batch<Q1, T>(outer, count, pr, stream);
+    case MLPROJ_L12: return run_batch<Q2, T>(outer, count, pr, stream);
+    default: return MLPROJ_ERR_BAD_VARIANT;
+  }
 }
 
 // ------------------------------------------------------------------ host: multi-level driver
@@ -390,7 +462,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 330; }
+int mlproj_version(void) { return 340; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -505,6 +577,18 @@ int bilevel_proj_stored(int storage, int outer_norm, int variant, const void* Y,
       return dispatch_stored<bf16_t>(outer_norm, variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
     case MLPROJ_STORE_F16:
       return dispatch_stored<f16_t>(outer_norm, variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    default: return MLPROJ_ERR_BAD_VARIANT;
+  }
+}
+
+int bilevel_proj_batch(int storage, int outer_norm, int variant, int count,
+                       const mlproj_problem* problems, void* stream) {
+  if (!problems) return MLPROJ_ERR_NULL_POINTER;
+  if (count <= 0) return MLPROJ_ERR_BAD_DIMENSION;
+  switch (storage) {
+    case MLPROJ_STORE_F32: return dispatch_batch<float>(outer_norm, variant, count, problems, stream);
+    case MLPROJ_STORE_BF16: return dispatch_batch<bf16_t>(outer_norm, variant, count, problems, stream);
+    case MLPROJ_STORE_F16: return dispatch_batch<f16_t>(outer_norm, variant, count, problems, stream);
     default: return MLPROJ_ERR_BAD_VARIANT;
   }
 }

@@ -155,3 +155,29 @@ def test_stored_entry_point_argument_checks(lib):
         assert st(storage, 0, 0, FAKE, FAKE, 4, 4, F(1), FAKE, 64, None, None, None, None) == -5
         assert st(storage, 0, 0, odd1, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -7
     assert st(0, 0, 0, odd2, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -7      # fp32 wants 4 bytes
+
+
+def test_batch_argument_checks(lib):
+    big = 1 << 30
+    bt = lib.bilevel_proj_batch
+    P = binding.Problem
+
+    def problems(*specs):
+        arr = (P * len(specs))()
+        for pr, (Y, X, n, m, eta, ws, nbytes) in zip(arr, specs):
+            pr.Y, pr.X, pr.n, pr.m, pr.eta, pr.workspace, pr.workspace_bytes = Y, X, n, m, eta, ws, nbytes
+        return arr
+
+    good = (FAKE.value, FAKE.value, 4, 4, 1.0, FAKE.value, big)
+    assert bt(0, 0, 0, 1, None, None) == -1
+    assert bt(0, 0, 0, 0, problems(good), None) == -2
+    assert bt(7, 0, 0, 1, problems(good), None) == -6                       # unknown storage
+    assert bt(0, 0, 5, 1, problems(good), None) == -6                       # unknown variant
+    assert bt(0, 9, 0, 1, problems(good), None) == -6                       # unknown outer norm
+    # one bad problem anywhere rejects the whole batch before anything is enqueued
+    assert bt(0, 0, 0, 3, problems(good, (None, FAKE.value, 4, 4, 1.0, FAKE.value, big), good), None) == -1
+    assert bt(1, 0, 2, 2, problems(good, (FAKE.value, FAKE.value, 4, 0, 1.0, FAKE.value, big)), None) == -2
+    assert bt(0, 0, 0, 2, problems(good, (FAKE.value, FAKE.value, 4, 4, -1.0, FAKE.value, big)), None) == -4
+    assert bt(2, 0, 1, 2, problems(good, (FAKE.value, FAKE.value, 4, 4, 1.0, FAKE.value, 64)), None) == -5
+    assert bt(0, 0, 0, 2, problems(good, (FAKE.value + 2, FAKE.value, 4, 4, 1.0, FAKE.value, big)), None) == -7
+    assert ctypes.sizeof(P) == 80

@@ -681,3 +681,50 @@ def test_l11_inner_searches_converge_on_hard_distributions(mp, family):
         got = run_gpu(mp, Y, eta, 1)
         check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
         assert got["res"]["inner_sweeps"] <= 10, (family, frac, got["res"]["inner_sweeps"])
+
+
+# ------------------------------------------------------------------ batches
+BATCH_SHAPES = [(256, 128), (1, 1), (33, 20), (300, 257), (131, 1028), (64, 4100), (9, 5000), (512, 8192),
+                (7, 16388), (40, 17000), (256, 128), (100, 260), (2065, 264), (5, 3), (77, 1024), (16, 16),
+                (300, 300), (64, 64), (1000, 10)]      # 19 problems: two launches of the batch kernels
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+@pytest.mark.parametrize("q", ["inf", 2, 1])
+def test_batch_matches_oracle_and_single_calls(mp, q, storage):
+    dev = torch.device("cuda:0")
+    dt = getattr(torch, STORE_DTYPES[storage])
+    Ys = [stored_input(sh, storage, 40 + i) for i, sh in enumerate(BATCH_SHAPES)]
+    etas = [eta_for(Y, q, 0.05 + 0.9 * (i % 5) / 5) for i, Y in enumerate(Ys)]
+    etas[3] = float(np.float32(2 * orc.norm_l1q(Ys[3], q)))     # one problem inside its ball
+    etas[5] = 0.0                                               # one with radius zero
+    Yd = [torch.from_numpy(Y).to(dev).to(dt) for Y in Ys]
+    wss = [mp.Workspace.for_call(QNAME[q], *Y.shape, device=dev) for Y in Ys]
+    vs = [torch.full((Y.shape[1],), -1.0, device=dev) for Y in Ys]
+    us = [torch.full((Y.shape[1],), -1.0, device=dev) for Y in Ys]
+    masks = [torch.full((Y.shape[1],), 7, dtype=torch.uint8, device=dev) for Y in Ys]
+    Xs = mp.bilevel_proj_batch(Yd, etas, q, workspaces=wss, v_outs=vs, u_outs=us, mask_outs=masks)
+    torch.cuda.synchronize()
+    refs = orc.bilevel_batch(Ys, etas, q, storage)
+    for i, (Y, ref) in enumerate(zip(Ys, refs)):
+        got = {"X": Xs[i].float().cpu().numpy(), "v": vs[i].cpu().numpy(), "u": us[i].cpu().numpy(),
+               "mask": masks[i].cpu().numpy(), "res": wss[i].result()}
+        check_stored(got, ref, q, storage)
+        single = mp.bilevel_proj_stored(Yd[i], etas[i], q)
+        assert torch.equal(single, Xs[i]), "problem %d differs from its single call" % i
+
+
+def test_batch_in_place_and_kernel_count(mp):
+    """In place; and the three launches of a small batch, seen through the event trace."""
+    dev = torch.device("cuda:0")
+    Ys = [stored_input(sh, "f32", 60 + i) for i, sh in enumerate(BATCH_SHAPES[:8])]
+    etas = [eta_for(Y, "inf", 0.3) for Y in Ys]
+    Yd = [torch.from_numpy(Y).to(dev) for Y in Ys]
+    tr = mp.KernelTrace(16)
+    with tr:
+        mp.bilevel_proj_batch(Yd, etas, "inf", Xs=Yd)
+    tr.durations_ms()
+    tr.close()
+    assert tr.count == 4                                   # aggregate, fold, map and the closing event
+    for Y, eta, X in zip(Ys, etas, Yd):
+        np.testing.assert_allclose(X.cpu().numpy(), orc.bilevel(Y, eta, "inf")["X"], rtol=RTOL, atol=ATOL)

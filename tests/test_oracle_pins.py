@@ -485,3 +485,17 @@ def test_bilevel_stored_is_the_fp32_result_rounded(storage, q):
         assert np.array_equal(np.abs(out["X"])[~inside], np.broadcast_to(ur, Y.shape)[~inside])
     with pytest.raises(AssertionError):
         orc.bilevel_stored(Y + np.float32(1e-3), eta, q, storage)
+
+
+def test_batch_is_independent_projections():
+    """Each member of a batch satisfies the single-matrix certificates on its own."""
+    shapes = [(5, 7), (40, 3), (1, 9)]
+    Ys = [rand_matrix(*sh) for sh in shapes]
+    etas = [0.3 * orc.norm_l1q(Y, "inf") for Y in Ys]
+    outs = orc.bilevel_batch(Ys, etas, "inf")
+    assert len(outs) == 3
+    for Y, eta, out in zip(Ys, etas, outs):
+        v = lq(Y, "inf", axis=0)
+        assert_is_projection(v, out["u"], eta, 1, tol=3e-7)
+        for j in range(Y.shape[1]):
+            assert_is_projection(Y[:, j], out["X"][:, j], float(out["u"][j]), "inf", tol=3e-7)
