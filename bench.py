@@ -184,6 +184,34 @@ def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
     return out
 
 
+def bench_small(torch, mp, Y_host, frac, steps, warmup):
+    """The small workload is launch-bound: eager calls against replays of one call captured in a
+    HIP graph (what the three kernels cost once the host is out of the way)."""
+    dev = torch.device("cuda:0")
+    n, m = Y_host.shape
+    Y = torch.from_numpy(Y_host).to(dev)
+    X = torch.empty_like(Y)
+    ws = mp.Workspace.for_call("l1inf", n, m, device=dev)
+    eta = device_eta(mp, Y, "l1inf", frac, ws)
+    call = lambda: mp.bilevel_proj_l1inf(Y, eta, X=X, workspace=ws)
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    out = {"shape": [n, m]}
+    for name, fn in (("ms_eager", call), ("ms_graph_replay", graph.replay)):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        out[name] = (time.perf_counter() - t0) * 1e3 / steps
+    return out
+
+
 def bench_batch(torch, mp, shape, count, frac, steps, warmup):
     """`count` matrices of one shape: one bilevel_proj_batch call against a loop of single calls."""
     import numpy as np
@@ -301,6 +329,12 @@ def main():
         wt, Yt = workloads.make("tensor_256x256x256")
         for k, v in bench_tensor(torch, mp, Yt, wt.eta_frac, 100, 10).items():
             also["tensor_256x256x256/" + k] = v
+        for name in ("tall_262144x256", "wide_256x262144"):
+            wk, Yk = workloads.make(name)
+            also[name + "/l1inf"] = bench_bilevel(torch, mp, Yk, "l1inf", wk.eta_frac, 50, 5)
+            del Yk
+        ws_, Ys_ = workloads.make("small_256x128")
+        also["small_256x128/l1inf"] = bench_small(torch, mp, Ys_, ws_.eta_frac, 200, 20)
         also["batch/16x(256x128)"] = bench_batch(torch, mp, (256, 128), 16, 0.1, 100, 10)
         also["batch/16x(1024x1024)"] = bench_batch(torch, mp, (1024, 1024), 16, 0.1, 100, 10)
         line["also"] = also
