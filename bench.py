@@ -26,8 +26,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for this library version only.
-TRAFFIC_VERSION = 330
-TRAFFIC_KIB = {"square_4096": 32974.4 * 1.999 + 65564.0, "square_16384": 524914.2 * 1.999 + 1048616.0}
+TRAFFIC_VERSION = 340
+TRAFFIC_KIB = {"square_4096": 32975.2 * 1.999 + 65559.4, "square_16384": 524911.1 * 1.999 + 1048618.7}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 
