@@ -269,7 +269,7 @@ def cpu_baseline(Y_host, eta, x_timed, tau_gpu, budget_s=20.0):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
