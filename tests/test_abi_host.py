@@ -181,3 +181,29 @@ def test_batch_argument_checks(lib):
     assert bt(2, 0, 1, 2, problems(good, (FAKE.value, FAKE.value, 4, 4, 1.0, FAKE.value, 64)), None) == -5
     assert bt(0, 0, 0, 2, problems(good, (FAKE.value + 2, FAKE.value, 4, 4, 1.0, FAKE.value, big)), None) == -7
     assert ctypes.sizeof(P) == 80
+
+
+def _imports(path):
+    import ast
+    names = set()
+    for node in ast.walk(ast.parse(open(path).read())):
+        if isinstance(node, ast.Import):
+            names.update(a.name.split(".")[0] for a in node.names)
+        elif isinstance(node, ast.ImportFrom) and node.module:
+            names.add(node.module.split(".")[0])
+    return names
+
+
+def test_product_and_oracle_do_not_import_each_other():
+    """The package (binding, workloads) never touches the oracle, the oracle never touches the
+    binding, and no C++/HIP source mentions the oracle: parity claims rest on that."""
+    pkg = os.path.join(ROOT, "paper_2405_02086_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            assert "oracle" not in _imports(os.path.join(pkg, name)), name
+    for name in os.listdir(os.path.join(ROOT, "oracle")):
+        if name.endswith(".py"):
+            assert "paper_2405_02086_amd" not in _imports(os.path.join(ROOT, "oracle", name)), name
+    for name in os.listdir(os.path.join(pkg, "csrc")):
+        assert "oracle" not in open(os.path.join(pkg, "csrc", name)).read().lower(), name
+    assert "oracle" not in open(os.path.join(ROOT, "include", "mlproj.h")).read().lower()
