@@ -728,3 +728,27 @@ def test_batch_in_place_and_kernel_count(mp):
     assert tr.count == 4                                   # aggregate, fold, map and the closing event
     for Y, eta, X in zip(Ys, etas, Yd):
         np.testing.assert_allclose(X.cpu().numpy(), orc.bilevel(Y, eta, "inf")["X"], rtol=RTOL, atol=ATOL)
+
+
+# ------------------------------------------------------------------ seeded random cases
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes_and_options(mp, seed):
+    """Shape, storage type, inner and outer norm, radius and pointer offsets drawn from a seed."""
+    rng = np.random.default_rng([seed, 2405])
+    n = int(np.exp(rng.uniform(0, np.log(3000))))
+    m = int(np.exp(rng.uniform(0, np.log(6000))))
+    q = ["inf", 1, 2][rng.integers(3)]
+    p = [1, 1, 2, "inf"][rng.integers(4)]
+    storage = ["f32", "bf16", "f16"][rng.integers(3)]
+    dist = rng.integers(3)
+    Y = (rng.standard_normal((n, m)) if dist == 0 else rng.laplace(size=(n, m)) if dist == 1
+         else rng.uniform(-1, 1, (n, m))).astype(np.float32)
+    if rng.integers(2):
+        Y *= np.power(10.0, rng.uniform(-2, 0, m)).astype(np.float32)[None, :]
+    Y = orc.round_to_storage(Y, storage)
+    v = orc.column_norms(Y, q).astype(np.float64)
+    norm_p = v.sum() if p == 1 else (np.sqrt((v * v).sum()) if p == 2 else v.max())
+    eta = float(np.float32(rng.uniform(0.01, 1.1) * norm_p))
+    offset, x_offset = int(rng.integers(0, 4)), int(rng.integers(0, 4))
+    got = run_stored(mp, Y, eta, q, storage, p=p, offset=offset, x_offset=x_offset)
+    check_stored(got, orc.bilevel_stored(Y, eta, q, storage, p=p), q, storage)
