@@ -16,6 +16,7 @@ import argparse
 import json
 import os
 import statistics
+import zlib
 import sys
 import time
 
@@ -304,7 +305,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %dx%d fp32 row-major, entries %s, eta=%.2f*||Y||_1,inf"
                                % (args.workload, n, m, DIST_TEXT[w.dist], w.eta_frac),
-                   "buffer_pairs": head["buffer_pairs"], "timing": "cold (rotating buffers > Infinity Cache)"},
+                   "buffer_pairs": head["buffer_pairs"], "timing": "cold (rotating buffers > Infinity Cache)",
+                   "generator": "numpy Generator(PCG64(%d)), see paper_2405_02086_amd/workloads.py" % w.seed,
+                   "input_crc32": "%08x" % zlib.crc32(Y.tobytes())},
         "frac_of_hbm_peak": head["frac_of_peak_rw"], "ms_per_step_warm": head["ms_warm"],
         "detail": head, "roofline": roofline,
     }
