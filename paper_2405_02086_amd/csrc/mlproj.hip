@@ -8,14 +8,19 @@
 //   colagg    Y -> per-(column tile, row group) partial aggregates        (reads Y once)
 //   reduce    partials -> v_j = ||y_j||_q                                  (tiny)
 //   search    v -> tau, the l1-ball threshold; run redundantly at the head of colmap when
-//             there are at most 4096 groups, a kernel of its own otherwise      (tiny)
-//   [sweep/update]  l1,1 only: per-column inner thresholds, one read of Y per iteration
+//             there are at most 16384 groups, a kernel of its own otherwise     (tiny)
+//   [init, sweep, filter/update ...]  l1,1 only: per-column inner thresholds, one read of Y
+//             per sweep, typically two sweeps
 //   colmap    Y, v, tau -> X                                  (reads Y again, writes X once)
 // Workgroups never wait for one another inside a kernel: on this GPU a device-scope fence
 // costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only
 // (the one exception, the search over more than 16384 groups, meets at a barrier made of
 // device-scope atomics alone).  The tri-level form uses the same chain with groups that are
-// contiguous slabs; the generic multi-level form works on contiguous fibres, level by level.
+// contiguous slabs; the generic multi-level form works on contiguous fibres, level by level;
+// a batch of matrices shares the three launches of the chain.
+//
+// This file is the one translation unit: the kernels live in the headers it includes (one per
+// pass), the host code below checks arguments, plans the launch geometry and enqueues.
 #include "common.h"
 #include "reduce.h"
 #include "aggregate.h"
