@@ -752,3 +752,46 @@ def test_random_shapes_and_options(mp, seed):
     offset, x_offset = int(rng.integers(0, 4)), int(rng.integers(0, 4))
     got = run_stored(mp, Y, eta, q, storage, p=p, offset=offset, x_offset=x_offset)
     check_stored(got, orc.bilevel_stored(Y, eta, q, storage, p=p), q, storage)
+
+
+def _adversarial_l11_cases():
+    rng = np.random.default_rng(5)
+    n, m = 1037, 130
+    cases = {}
+    cases["binary"] = (rng.uniform(size=(n, m)) < 0.3).astype(np.float32)
+    c = np.full((n, m), 1e-30, np.float32)
+    c[rng.integers(0, n, m), np.arange(m)] = 1e30
+    cases["outlier"] = c
+    cases["pow2"] = np.tile((2.0 ** -(np.arange(n) % 40))[:, None], (1, m)).astype(np.float32)
+    t = np.ones((n, m), np.float32)
+    t[: n // 3] = 3.0
+    cases["two_levels"] = t
+    cases["two_rows"] = rng.standard_normal((2, 5000)).astype(np.float32)
+    cases["denormal"] = (rng.standard_normal((n, m)) * 1e-41).astype(np.float32)
+    cases["huge"] = (rng.standard_normal((n, m)) * 1e30).astype(np.float32)
+    cases["ramp"] = np.tile(np.arange(1, n + 1, dtype=np.float32)[:, None], (1, m))
+    cases["mixed_columns"] = np.concatenate([cases["binary"][:, :40], cases["pow2"][:, :40],
+                                             rng.standard_cauchy((n, 50)).astype(np.float32)], axis=1)
+    return cases
+
+
+@pytest.mark.parametrize("name", ["binary", "outlier", "pow2", "two_levels", "two_rows", "denormal", "huge", "ramp",
+                                  "mixed_columns"])
+def test_l11_inner_searches_on_adversarial_columns(mp, name):
+    """Ties everywhere, one giant entry, powers of two, subnormal and huge magnitudes, and
+    columns of different kinds side by side (lock step must serve the slowest)."""
+    Y = _adversarial_l11_cases()[name]
+    for frac in (1e-4, 0.01, 0.3, 0.9, 0.999):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert got["res"]["inner_sweeps"] <= 10
+
+
+def test_l11_root_exactly_on_repeated_entries(mp):
+    """Columns (3,3,3,1,1) with u_j = 6: the inner threshold is exactly 1, the value of two entries."""
+    Y = np.tile(np.float32([3, 3, 3, 1, 1])[:, None], (1, 64))
+    got = run_gpu(mp, Y, 384.0, 1)          # v_j = 11, tau = 5, u_j = 6
+    ref = orc.bilevel(Y, 384.0, 1)
+    assert np.allclose(ref["tau_col"], 1.0) and ref["tau"] == 5.0
+    check_against_oracle(got, ref, 1)
