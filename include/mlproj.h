@@ -230,6 +230,17 @@ int trilevel_proj_l1infinf(const float* Y /* device, d0*d1*d2 */, float* X /* de
                            float* v_out /* device, d0; may be NULL */,
                            float* u_out /* device, d0; may be NULL */, void* stream);
 
+/* trilevel_proj_l1infinf on a tensor stored in fp32, bf16 or fp16 (a mlproj_storage, as in
+ * bilevel_proj_stored: the 16-bit formats are storage only and X is rounded to nearest-even),
+ * with an optional mask of the kept slabs: mask_out[a] = 1 when u_a > 0.                      */
+int trilevel_proj_stored(int storage, const void* Y /* device, d0*d1*d2 elements */,
+                         void* X /* device, d0*d1*d2 elements */,
+                         long long d0, long long d1, long long d2, float eta,
+                         void* workspace /* device */, size_t workspace_bytes,
+                         float* v_out /* device, d0; may be NULL */,
+                         float* u_out /* device, d0; may be NULL */,
+                         unsigned char* mask_out /* device, d0; may be NULL */, void* stream);
+
 /* MP^nu_eta (Sec. 5.2, Def. 5.2, Alg. 6; iterative form in the appendix) on a C-order tensor of
  * shape dims[0..ndim-1] (2 <= ndim <= 8) with single-axis inner norms and the l1 norm outside.
  * Groups live on axis 0.  norms[0] aggregates the last axis, norms[1] the one before, ... ,

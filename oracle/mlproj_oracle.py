@@ -26,7 +26,7 @@ __all__ = [
     "column_norms", "norm_l1q", "project_l1_ball_nonneg", "project_l1_ball",
     "project_linf_ball", "project_l2_ball", "bilevel_l1inf", "bilevel_l11",
     "bilevel_l12", "trilevel_l1infinf", "bilevel", "multilevel", "project_outer",
-    "round_to_storage", "bilevel_stored", "bilevel_batch",
+    "round_to_storage", "bilevel_stored", "bilevel_batch", "trilevel_stored",
 ]
 
 
@@ -287,6 +287,19 @@ def trilevel_l1infinf(Y, eta):
         for b in range(d1):
             X[a, b, :] = project_linf_ball(Y[a, b, :], U2[a, b])
     return {"X": X, "V": V, "w": w, "u": u, "U2": U2, "tau": tau}
+
+
+def trilevel_stored(Y, eta, storage):
+    """TP^{1,inf,inf}_eta (Alg. 5) on a tensor kept in a 16-bit format: the fp32-storage result,
+    with X rounded to the storage format; mask = kept slabs (u_a > 0)."""
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32
+    assert np.array_equal(round_to_storage(Y, storage), Y), "Y must be representable in the storage format"
+    out = dict(trilevel_l1infinf(Y, eta))
+    out["X32"] = out["X"]
+    out["X"] = round_to_storage(out["X32"], storage)
+    out["mask"] = np.asarray(out["u"], dtype=np.float64) > 0
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -94,6 +94,8 @@ def lib():
     L.bilevel_proj_stored.argtypes = [c_i, c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.bilevel_proj_batch.restype = c_i
     L.bilevel_proj_batch.argtypes = [c_i, c_i, c_i, c_i, ctypes.POINTER(Problem), c_vp]
+    L.trilevel_proj_stored.restype = c_i
+    L.trilevel_proj_stored.argtypes = [c_i, c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.trilevel_proj_l1infinf.restype = c_i
     L.trilevel_proj_l1infinf.argtypes = [c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
     _lib = L
@@ -112,7 +114,7 @@ EXPORTS = (
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
-    "bilevel_proj_stored", "bilevel_proj_batch",
+    "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored",
 )
 
 
@@ -262,6 +264,24 @@ def bilevel_proj_stored(Y, eta, q, p=1, X=None, workspace=None, v_out=None, u_ou
                                    ctypes.c_float(eta), _ptr(workspace.buf), workspace.nbytes, _ptr(v_out),
                                    _ptr(u_out), _ptr(mask_out), _stream(stream))
     _check(st, "bilevel_proj_stored")
+    return X
+
+
+def trilevel_proj_stored(Y, eta, X=None, workspace=None, v_out=None, u_out=None, mask_out=None, stream=None):
+    """TP^{1,inf,inf} on a contiguous fp32, bf16 or fp16 device tensor of three axes."""
+    import torch
+    storages = {torch.float32: STORE_F32, torch.bfloat16: STORE_BF16, torch.float16: STORE_F16}
+    assert Y.is_cuda and Y.dim() == 3 and Y.is_contiguous() and Y.dtype in storages
+    d0, d1, d2 = Y.shape
+    if X is None:
+        X = torch.empty_like(Y)
+    assert X.is_cuda and X.dtype == Y.dtype and X.is_contiguous() and X.shape == Y.shape
+    if workspace is None:
+        workspace = Workspace.for_call("tri", d0, d1, d2, device=Y.device, stream=stream)
+    st = lib().trilevel_proj_stored(storages[Y.dtype], _ptr(Y), _ptr(X), d0, d1, d2, ctypes.c_float(eta),
+                                    _ptr(workspace.buf), workspace.nbytes, _ptr(v_out), _ptr(u_out),
+                                    _ptr(mask_out), _stream(stream))
+    _check(st, "trilevel_proj_stored")
     return X
 
 

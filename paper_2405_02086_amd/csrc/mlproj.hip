@@ -67,7 +67,6 @@ static int workspace_bytes_impl(int variant, long long d0, long long d1, long lo
     long long ngroups;
     if (variant != MLPROJ_L1INFINF && vec == 1) continue;
     if (variant == MLPROJ_L1INFINF) {
-      if (vec == 8) continue;
       if (d0 > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
       g = plan_slabs(d0, d1 * d2, vec);
       ngroups = d0;
@@ -229,6 +228,55 @@ static int dispatch_stored(int outer, int variant, const void* Y, void* X, long 
                     workspace_bytes, v_out, u_out, stream, MODE_PROJECT, (double*)nullptr, STAGE_ALL,
                     outer, mask_out);
 }
+
+// ------------------------------------------------------------------ host: tri-level
+template <typename T>
+static int run_trilevel(const T* Y, T* X, long long d0, long long d1, long long d2, float eta,
+                        void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
+                        unsigned char* mask_out, void* stream_) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  if (!Y || !X || !workspace) return MLPROJ_ERR_NULL_POINTER;
+  int st = check_dims(d0, d1, d2);
+  if (st != MLPROJ_OK) return st;
+  if (d0 > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
+  if ((st = check_radius(eta)) != MLPROJ_OK) return st;
+  if (!aligned(Y, sizeof(T)) || !aligned(X, sizeof(T))) return MLPROJ_ERR_ALIGNMENT;
+  if (!aligned(workspace, 256)) return MLPROJ_ERR_WORKSPACE;
+  const long long len = d1 * d2;
+  const int vec = pick_vec(Y, len, (int)sizeof(T));
+  const bool x_vec = aligned(X, 16);
+  const Geometry g = plan_slabs(d0, len, vec);
+  if (g.tiles * g.groups > MAX_GRID) return MLPROJ_ERR_TOO_LARGE;
+  const Layout L = layout_for(g, d0, MLPROJ_L1INFINF);
+  if (workspace_bytes < L.bytes) return MLPROJ_ERR_WORKSPACE;
+  const Ws ws = bind(workspace, L);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
+  const int parts = reduce_parts(g.groups);
+  const dim3 rgrid((unsigned)cdiv(d0, SWG / parts)), rblock(SWG);
+  float* partial = static_cast<float*>(ws.partial);
+  mark(stream);
+  if (vec == WIDE) hipLaunchKernelGGL((slabagg_kernel<T, WIDE>), grid, block, 0, stream, Y, len, g, partial);
+  else hipLaunchKernelGGL((slabagg_kernel<T, 1>), grid, block, 0, stream, Y, len, g, partial);
+  mark(stream);
+  hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, parts, ws.v, v_out, ws.flags);
+  const bool fuse = d0 <= FUSED_SEARCH_MAX;
+  const double fused_eta = fuse ? (double)eta : -1.0;
+  if (!fuse) {
+    mark(stream);
+    launch_search(ws, d0, (double)eta, MODE_PROJECT, MLPROJ_OUTER_L1, nullptr, stream);
+  }
+  mark(stream);
+  if (vec == WIDE && x_vec)
+    hipLaunchKernelGGL((slabmap_kernel<T, WIDE, true>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
+  else if (vec == WIDE)
+    hipLaunchKernelGGL((slabmap_kernel<T, WIDE, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
+  else
+    hipLaunchKernelGGL((slabmap_kernel<T, 1, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
+  mark(stream);
+  return launch_status();
+}
+
 
 // ------------------------------------------------------------------ host: batches
 // Every problem is checked first (nothing is enqueued if one fails).  Problems whose map pass
@@ -467,7 +515,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 340; }
+int mlproj_version(void) { return 341; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -600,47 +648,22 @@ int bilevel_proj_batch(int storage, int outer_norm, int variant, int count,
 
 int trilevel_proj_l1infinf(const float* Y, float* X, long long d0, long long d1, long long d2,
                            float eta, void* workspace, size_t workspace_bytes, float* v_out,
-                           float* u_out, void* stream_) {
-  if (!Y || !X || !workspace) return MLPROJ_ERR_NULL_POINTER;
-  int st = check_dims(d0, d1, d2);
-  if (st != MLPROJ_OK) return st;
-  if (d0 > MAX_GROUPS) return MLPROJ_ERR_TOO_LARGE;
-  if ((st = check_radius(eta)) != MLPROJ_OK) return st;
-  if (!aligned(Y, 4) || !aligned(X, 4)) return MLPROJ_ERR_ALIGNMENT;
-  if (!aligned(workspace, 256)) return MLPROJ_ERR_WORKSPACE;
-  const long long len = d1 * d2;
-  const int vec = pick_vec(Y, len);
-  const bool x_vec = aligned(X, 16);
-  const Geometry g = plan_slabs(d0, len, vec);
-  if (g.tiles * g.groups > MAX_GRID) return MLPROJ_ERR_TOO_LARGE;
-  const Layout L = layout_for(g, d0, MLPROJ_L1INFINF);
-  if (workspace_bytes < L.bytes) return MLPROJ_ERR_WORKSPACE;
-  const Ws ws = bind(workspace, L);
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
-  const int parts = reduce_parts(g.groups);
-  const dim3 rgrid((unsigned)cdiv(d0, SWG / parts)), rblock(SWG);
-  float* partial = static_cast<float*>(ws.partial);
-  mark(stream);
-  if (vec == 4) hipLaunchKernelGGL((slabagg_kernel<4>), grid, block, 0, stream, Y, len, g, partial);
-  else hipLaunchKernelGGL((slabagg_kernel<1>), grid, block, 0, stream, Y, len, g, partial);
-  mark(stream);
-  hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, parts, ws.v, v_out, ws.flags);
-  const bool fuse = d0 <= FUSED_SEARCH_MAX;
-  const double fused_eta = fuse ? (double)eta : -1.0;
-  if (!fuse) {
-    mark(stream);
-    launch_search(ws, d0, (double)eta, MODE_PROJECT, MLPROJ_OUTER_L1, nullptr, stream);
+                           float* u_out, void* stream) {
+  return run_trilevel<float>(Y, X, d0, d1, d2, eta, workspace, workspace_bytes, v_out, u_out, nullptr, stream);
+}
+
+int trilevel_proj_stored(int storage, const void* Y, void* X, long long d0, long long d1, long long d2,
+                         float eta, void* workspace, size_t workspace_bytes, float* v_out,
+                         float* u_out, unsigned char* mask_out, void* stream) {
+  switch (storage) {
+    case MLPROJ_STORE_F32:
+      return run_trilevel<float>(static_cast<const float*>(Y), static_cast<float*>(X), d0, d1, d2, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    case MLPROJ_STORE_BF16:
+      return run_trilevel<bf16_t>(static_cast<const bf16_t*>(Y), static_cast<bf16_t*>(X), d0, d1, d2, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    case MLPROJ_STORE_F16:
+      return run_trilevel<f16_t>(static_cast<const f16_t*>(Y), static_cast<f16_t*>(X), d0, d1, d2, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    default: return MLPROJ_ERR_BAD_VARIANT;
   }
-  mark(stream);
-  if (vec == 4 && x_vec)
-    hipLaunchKernelGGL((slabmap_kernel<4, true>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, fused_eta);
-  else if (vec == 4)
-    hipLaunchKernelGGL((slabmap_kernel<4, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, fused_eta);
-  else
-    hipLaunchKernelGGL((slabmap_kernel<1, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, fused_eta);
-  mark(stream);
-  return launch_status();
 }
 
 }  // extern "C"

@@ -11,15 +11,15 @@ namespace mlproj {
 // ------------------------------------------------------------------ tri-level: slab kernels
 // Groups are the d0 contiguous slabs of len = d1*d2 elements.  w_a = max over the slab equals
 // the two nested maxima of Alg. 5 (max over the fibre, then over the fibres of the slab).
-template <int VEC>
-__global__ __launch_bounds__(WG) void slabagg_kernel(const float* __restrict__ Y, long long len,
+template <typename T, int VEC>
+__global__ __launch_bounds__(WG) void slabagg_kernel(const T* __restrict__ Y, long long len,
                                                      Geometry g, float* __restrict__ partial) {
   __shared__ BlockScratch<WAVES> bs;
   const long long a = blockIdx.x / g.groups;
   const long long c = blockIdx.x % g.groups;
   const long long lo = c * g.span;
   const long long hi = (lo + g.span < len) ? lo + g.span : len;
-  const float* p = Y + a * len;
+  const T* p = Y + a * len;
   float mx = 0.0f;
   long long i = lo + (long long)threadIdx.x * VEC;
   constexpr long long STEP = (long long)WG * VEC;
@@ -44,10 +44,12 @@ __global__ __launch_bounds__(WG) void slabagg_kernel(const float* __restrict__ Y
 
 // X_abc = sign(Y_abc) min(|Y_abc|, u_a).  The appendix form clips each fibre to
 // U2_ab = min(V_ab, u_a); since |Y_abc| <= V_ab the two clips give the same value.
-template <int VEC, bool XVEC>
-__global__ __launch_bounds__(WG) void slabmap_kernel(const float* Y, float* X, long long d0,
+template <typename T, int VEC, bool XVEC>
+__global__ __launch_bounds__(WG) void slabmap_kernel(const T* Y, T* X, long long d0,
                                                      long long len, Geometry g, Ws ws,
-                                                     float* __restrict__ u_out, double fused_eta) {
+                                                     float* __restrict__ u_out,
+                                                     unsigned char* __restrict__ mask_out,
+                                                     double fused_eta) {
   __shared__ PairScratch<WAVES> bs;
   const long long a = d0 - 1 - blockIdx.x / g.groups;
   const long long c = blockIdx.x % g.groups;
@@ -61,10 +63,14 @@ __global__ __launch_bounds__(WG) void slabmap_kernel(const float* Y, float* X, l
   } else {
     top = top_of(ws.res);
   }
-  const float u = (float)radius(ws.v[a], top);
-  if (u_out && c == 0 && threadIdx.x == 0) u_out[a] = u;
-  const float* p = Y + a * len;
-  float* q = X + a * len;
+  const double ud = radius(ws.v[a], top);
+  const float u = (float)ud;
+  if (c == 0 && threadIdx.x == 0) {
+    if (u_out) u_out[a] = u;
+    if (mask_out) mask_out[a] = ud > 0.0 ? 1 : 0;
+  }
+  const T* p = Y + a * len;
+  T* q = X + a * len;
   long long i = lo + (long long)threadIdx.x * VEC;
   constexpr long long STEP = (long long)WG * VEC;
   for (; i + 3 * STEP < hi; i += 4 * STEP) {

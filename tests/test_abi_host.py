@@ -207,3 +207,15 @@ def test_product_and_oracle_do_not_import_each_other():
     for name in os.listdir(os.path.join(pkg, "csrc")):
         assert "oracle" not in open(os.path.join(pkg, "csrc", name)).read().lower(), name
     assert "oracle" not in open(os.path.join(ROOT, "include", "mlproj.h")).read().lower()
+
+
+def test_stored_trilevel_argument_checks(lib):
+    big = 1 << 30
+    tri = lib.trilevel_proj_stored
+    assert tri(5, FAKE, FAKE, 2, 2, 2, F(1), FAKE, big, None, None, None, None) == -6
+    for storage in (0, 1, 2):
+        assert tri(storage, None, FAKE, 2, 2, 2, F(1), FAKE, big, None, None, None, None) == -1
+        assert tri(storage, FAKE, FAKE, 2, 0, 2, F(1), FAKE, big, None, None, None, None) == -2
+        assert tri(storage, FAKE, FAKE, 2, 2, 2, F(-1), FAKE, big, None, None, None, None) == -4
+        assert tri(storage, FAKE, FAKE, 2, 2, 2, F(1), FAKE, 16, None, None, None, None) == -5
+        assert tri(storage, ctypes.c_void_p((1 << 20) + 1), FAKE, 2, 2, 2, F(1), FAKE, big, None, None, None, None) == -7

@@ -795,3 +795,35 @@ def test_l11_root_exactly_on_repeated_entries(mp):
     ref = orc.bilevel(Y, 384.0, 1)
     assert np.allclose(ref["tau_col"], 1.0) and ref["tau"] == 5.0
     check_against_oracle(got, ref, 1)
+
+
+# ------------------------------------------------------------------ tri-level on 16-bit storage
+@pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 4, 5), (17, 16, 16), (6, 50, 41), (300, 3, 2), (4, 64, 1024), (40, 33, 264)])
+def test_trilevel_stored_matches_oracle(mp, storage, shape):
+    dev = torch.device("cuda:0")
+    dt = getattr(torch, STORE_DTYPES[storage])
+    rng = np.random.default_rng(list(shape) + [9])
+    Y = orc.round_to_storage(rng.standard_normal(shape).astype(np.float32), storage)
+    w = np.abs(Y).reshape(shape[0], -1).max(axis=1).astype(np.float64)
+    Yd = torch.from_numpy(Y).to(dev).to(dt)
+    for frac in (0.1, 0.7, 1.5, 0.0):
+        eta = float(np.float32(frac * w.sum()))
+        ws = mp.Workspace.for_call("tri", *shape, device=dev)
+        v = torch.full((shape[0],), -1.0, device=dev)
+        u = torch.full((shape[0],), -1.0, device=dev)
+        mask = torch.full((shape[0],), 7, dtype=torch.uint8, device=dev)
+        X = mp.trilevel_proj_stored(Yd, eta, workspace=ws, v_out=v, u_out=u, mask_out=mask)
+        torch.cuda.synchronize()
+        ref = orc.trilevel_stored(Y, eta, storage)
+        assert np.array_equal(v.cpu().numpy(), ref["w"])
+        np.testing.assert_allclose(u.cpu().numpy(), np.asarray(ref["u"], dtype=np.float32), rtol=RTOL, atol=ATOL)
+        assert np.array_equal(mask.cpu().numpy(), ref["mask"].astype(np.uint8))
+        x = ref["X32"].astype(np.float64)
+        tol = RTOL * np.abs(x) + ATOL
+        lo = orc.round_to_storage((x - tol).astype(np.float32), storage)
+        hi = orc.round_to_storage((x + tol).astype(np.float32), storage)
+        got = X.float().cpu().numpy()
+        assert np.all((got >= lo) & (got <= hi))
+        if storage == "f32":
+            assert torch.equal(X, mp.trilevel_proj_l1infinf(Yd, eta))

@@ -499,3 +499,18 @@ def test_batch_is_independent_projections():
         assert_is_projection(v, out["u"], eta, 1, tol=3e-7)
         for j in range(Y.shape[1]):
             assert_is_projection(Y[:, j], out["X"][:, j], float(out["u"][j]), "inf", tol=3e-7)
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16"])
+def test_trilevel_stored_is_the_fp32_result_rounded(storage):
+    Y = orc.round_to_storage(RNG.standard_normal((6, 5, 9)).astype(np.float32), storage)
+    w = np.abs(Y).reshape(6, -1).max(axis=1)
+    eta = 0.4 * float(w.sum())
+    out = orc.trilevel_stored(Y, eta, storage)
+    ref = orc.trilevel_l1infinf(Y, eta)
+    assert np.array_equal(out["X32"], ref["X"]) and np.array_equal(out["X"], orc.round_to_storage(ref["X"], storage))
+    assert np.array_equal(out["mask"], np.abs(ref["X"]).reshape(6, -1).max(axis=1) > 0)
+    ur = orc.round_to_storage(np.asarray(ref["u"], dtype=np.float32), storage)
+    inside = np.abs(Y) <= np.asarray(ref["u"], dtype=np.float32)[:, None, None]
+    assert np.array_equal(out["X"][inside], Y[inside])
+    assert np.array_equal(np.abs(out["X"])[~inside], np.broadcast_to(ur[:, None, None], Y.shape)[~inside])
