@@ -26,8 +26,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
-# profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for this library version only.
-TRAFFIC_VERSION = 340
+# profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
+TRAFFIC_VERSIONS = (340, 341)   # (341 added entry points only: the column kernels are those of 340)
 TRAFFIC_KIB = {"square_4096": 32975.2 * 1.999 + 65559.4, "square_16384": 524911.1 * 1.999 + 1048618.7}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
@@ -292,7 +292,7 @@ def main():
         "achieved": 8.0 * elems / map_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": 8.0 * elems / map_ms / 1e6 / HBM_PEAK_GBS,
         "traffic": (TRAFFIC_KIB[args.workload] * 1024.0
-                    if args.workload in TRAFFIC_KIB and mp.lib().mlproj_version() == TRAFFIC_VERSION else None),
+                    if args.workload in TRAFFIC_KIB and mp.lib().mlproj_version() in TRAFFIC_VERSIONS else None),
         "algorithmic_bytes": 8.0 * elems,
         "kernel_ms": map_ms,
         "other_kernels": {"colagg_kernel<l1inf> (reads Y: 4 B/element)": {
