@@ -240,6 +240,13 @@ def bench_batch(torch, mp, shape, count, frac, steps, warmup):
             fn()
         torch.cuda.synchronize()
         out[name] = (time.perf_counter() - t0) * 1e3 / steps
+    # what the GPU spends on one batch call, from the library's own events (aggregate, fold, map)
+    tr = mp.KernelTrace(8)
+    with tr:
+        batch()
+    d = tr.durations_ms()
+    tr.close()
+    out["batch_kernel_ms_event_intervals"] = dict(zip(["colagg", "reduce", "colmap+search"], d))
     return out
 
 
