@@ -219,3 +219,18 @@ def test_stored_trilevel_argument_checks(lib):
         assert tri(storage, FAKE, FAKE, 2, 2, 2, F(-1), FAKE, big, None, None, None, None) == -4
         assert tri(storage, FAKE, FAKE, 2, 2, 2, F(1), FAKE, 16, None, None, None, None) == -5
         assert tri(storage, ctypes.c_void_p((1 << 20) + 1), FAKE, 2, 2, 2, F(1), FAKE, big, None, None, None, None) == -7
+
+
+def test_header_is_plain_c():
+    """include/mlproj.h stands on its own as C99 and as C++11 (no HIP or torch types in it)."""
+    import shutil
+    import subprocess
+    header = os.path.join(ROOT, "include", "mlproj.h")
+    for cc, flags in (("gcc", ["-std=c99", "-x", "c"]), ("g++", ["-std=c++11", "-x", "c++"])):
+        if shutil.which(cc) is None:
+            pytest.skip(cc + " not installed")
+        proc = subprocess.run([cc, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only"] + flags + [header],
+                              capture_output=True, text=True)
+        assert proc.returncode == 0, proc.stderr
+    text = open(header).read()
+    assert "hip" not in re.sub(r"/\*.*?\*/", "", text, flags=re.S).lower() and "torch" not in text.lower()
