@@ -444,17 +444,63 @@ static void by_norm(int norm, F&& f) {
   else f(std::integral_constant<int, Q2>{});
 }
 
-static int run_multilevel(int outer, const float* Y, float* X, int ndim, const long long* dims,
-                          const int* norms, float eta, void* workspace, size_t workspace_bytes,
+// The workspace of a multi-level call: what the level arrays of the unmerged plan need, and
+// what the slab kernels need when every inner norm is l_inf (see run_multilevel).
+static int ml_workspace_bytes(int ndim, const long long* dims, size_t* out) {
+  int norms[ML_MAX_DIMS] = {0};
+  MlPlan P;
+  int st = ml_plan(ndim, dims, norms, &P);
+  if (st != MLPROJ_OK) return st;
+  size_t tri = 0;
+  st = workspace_bytes_impl(MLPROJ_L1INFINF, dims[0], P.size[0] / dims[0], 1, &tri);
+  if (st != MLPROJ_OK) return st;
+  *out = P.bytes > tri ? P.bytes : tri;
+  return MLPROJ_OK;
+}
+
+static int run_multilevel(int outer, const float* Y, float* X, int ndim, const long long* dims_in,
+                          const int* norms_in, float eta, void* workspace, size_t workspace_bytes,
                           float* v_out, float* u_out, void* stream_) {
   if (!Y || !X || !workspace) return MLPROJ_ERR_NULL_POINTER;
   if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
   MlPlan P;
-  int st = ml_plan(ndim, dims, norms, &P);
+  int st = ml_plan(ndim, dims_in, norms_in, &P);   // checks the arguments as given
+  if (st != MLPROJ_OK) return st;
+  size_t need = 0;
+  if ((st = ml_workspace_bytes(ndim, dims_in, &need)) != MLPROJ_OK) return st;
+  if (!aligned(workspace, 256) || workspace_bytes < need) return MLPROJ_ERR_WORKSPACE;
+  // Two neighbouring l_inf levels are one: the max of maxima is the max over both axes, and
+  // clipping a fibre to min(its own max, the radius above) clips it to the radius above.  So
+  // neighbouring l_inf axes are merged (the tensor is C-order: they are contiguous), and a
+  // projection whose inner norms are all l_inf is the slab form of the tri-level projection.
+  long long dims[ML_MAX_DIMS];
+  int norms[ML_MAX_DIMS];
+  int nd = 1;
+  dims[0] = dims_in[0];
+  // level k = 1..ndim-1 aggregates axis ndim-k with norms_in[k-1]; walk the axes from the outside in
+  for (int axis = 1; axis < ndim; ++axis) {
+    const int nrm = norms_in[ndim - 1 - axis];
+    if (nd > 1 && nrm == MLPROJ_NORM_INF && norms[nd - 1] == MLPROJ_NORM_INF) {
+      dims[nd - 1] *= dims_in[axis];
+    } else {
+      dims[nd] = dims_in[axis];
+      norms[nd] = nrm;
+      ++nd;
+    }
+  }
+  // norms[] above is indexed by axis (1..nd-1); ml_plan wants it innermost first
+  int norms_inner_first[ML_MAX_DIMS];
+  for (int axis = 1; axis < nd; ++axis) norms_inner_first[nd - 1 - axis] = norms[axis];
+  if (nd == 2 && norms_inner_first[0] == MLPROJ_NORM_INF && outer == MLPROJ_OUTER_L1)
+    return run_trilevel<float>(Y, X, dims[0], dims[1], 1, eta, workspace, workspace_bytes, v_out, u_out,
+                               nullptr, stream_);
+  ndim = nd;
+  const int* norms_use = norms_inner_first;
+  st = ml_plan(ndim, dims, norms_use, &P);
   if (st != MLPROJ_OK) return st;
   if ((st = check_radius(eta)) != MLPROJ_OK) return st;
   if (!aligned(Y, 4) || !aligned(X, 4)) return MLPROJ_ERR_ALIGNMENT;
-  if (!aligned(workspace, 256) || workspace_bytes < P.bytes) return MLPROJ_ERR_WORKSPACE;
+  if (workspace_bytes < P.bytes) return MLPROJ_ERR_WORKSPACE;
   const Ws ws = bind(workspace, P.base);
   char* base = static_cast<char*>(workspace);
   double* V[ML_MAX_DIMS];
@@ -470,13 +516,13 @@ static int run_multilevel(int outer, const float* Y, float* X, int ndim, const l
 
   // up: aggregate level by level
   mark(stream);
-  by_norm(norms[0], [&](auto q) {
+  by_norm(norms_use[0], [&](auto q) {
     float* vo = ndim == 2 ? v_out : nullptr;
     if (vec4) launch_fibre_agg<decltype(q)::value, float, 4>(Y, P.size[1], len1, V[1], vo, stream);
     else launch_fibre_agg<decltype(q)::value, float, 1>(Y, P.size[1], len1, V[1], vo, stream);
   });
   for (int k = 2; k < ndim; ++k) {
-    by_norm(norms[k - 1], [&](auto q) {
+    by_norm(norms_use[k - 1], [&](auto q) {
       launch_fibre_agg<decltype(q)::value, double, 1>(V[k - 1], P.size[k], P.len[k], V[k],
                                                       k == ndim - 1 ? v_out : nullptr, stream);
     });
@@ -495,12 +541,12 @@ static int run_multilevel(int outer, const float* Y, float* X, int ndim, const l
   // down: project the fibres of every level onto the balls of the level above
   mark(stream);
   for (int k = ndim - 1; k >= 2; --k) {
-    by_norm(norms[k - 1], [&](auto q) {
+    by_norm(norms_use[k - 1], [&](auto q) {
       launch_fibre_map<decltype(q)::value, double, double, 1>(V[k - 1], P.size[k], P.len[k], R[k], V[k],
                                                               R[k - 1], stream);
     });
   }
-  by_norm(norms[0], [&](auto q) {
+  by_norm(norms_use[0], [&](auto q) {
     if (vec4) launch_fibre_map<decltype(q)::value, float, float, 4>(Y, P.size[1], len1, R[1], V[1], X, stream);
     else launch_fibre_map<decltype(q)::value, float, float, 1>(Y, P.size[1], len1, R[1], V[1], X, stream);
   });
@@ -592,12 +638,7 @@ int bilevel_apply(int variant, const float* Y, float* X, long long n, long long 
 
 int mlproj_multilevel_workspace_bytes(int ndim, const long long* dims, size_t* bytes_out) {
   if (!bytes_out) return MLPROJ_ERR_NULL_POINTER;
-  int norms[ML_MAX_DIMS] = {0};
-  MlPlan P;
-  const int st = ml_plan(ndim, dims, norms, &P);
-  if (st != MLPROJ_OK) return st;
-  *bytes_out = P.bytes;
-  return MLPROJ_OK;
+  return ml_workspace_bytes(ndim, dims, bytes_out);
 }
 
 int multilevel_proj(const float* Y, float* X, int ndim, const long long* dims, const int* norms,

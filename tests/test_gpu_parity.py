@@ -377,6 +377,9 @@ ML_CASES = [
     ((9, 16, 3), [1, 2]), ((7, 5, 64), [1, "inf"]), ((3, 40, 260), [1, 1]), ((3, 40, 260), [2, 1]),
     ((5, 4, 3, 6), [1, 1, 1]), ((5, 4, 3, 6), ["inf", 2, 1]), ((2, 3, 2, 2, 8), [1, "inf", 2, 1]),
     ((20000, 2, 4), [1, 1]), ((1, 1, 1), [1, 1]), ((3, 1, 2000), [1, 1]),
+    # neighbouring l_inf levels (merged into one by the driver)
+    ((5, 4, 3, 6), ["inf", "inf", 1]), ((5, 4, 3, 6), [1, "inf", "inf"]), ((4, 3, 5, 2), ["inf", "inf", 2]),
+    ((3, 4, 2, 5, 6), ["inf", "inf", "inf", "inf"]), ((6, 2, 3, 4, 5), ["inf", "inf", 1, "inf"]),
 ]
 
 
