@@ -130,11 +130,15 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
     excess = max(0.0, (sum(k_raw.values()) - ms) / len(k_raw))
     k_ms = {k: max(v - excess, 0.0) for k, v in k_raw.items()}
     warm_ms = time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs[:1], steps, warmup) if npairs > 1 else ms
+    # spread of the cold figure: ten more loops of steps/10 calls each
+    chunk = max(1, steps // 10)
+    chunks = [time_calls(torch, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, chunk, 0) for _ in range(10)]
     elems = n * m
     b = 2.0 * elem   # read Y once, write X once
     out = {
         "shape": [n, m], "variant": variant, "storage": storage, "eta": eta, "buffer_pairs": npairs,
         "ms": ms, "ms_warm": warm_ms,
+        "ms_median_of_10_chunks": statistics.median(chunks), "ms_min_of_10_chunks": min(chunks),
         "bytes_per_element_rw": b,   # "rw": read Y once + write X once; "rrw": two reads + one write
         "eff_GBps_rw": b * elems / ms / 1e6,
         "frac_of_peak_rw": b * elems / ms / 1e6 / HBM_PEAK_GBS,
