@@ -351,6 +351,7 @@ def main():
         also["small_256x128/l1inf"] = bench_small(torch, mp, Ys_, ws_.eta_frac, 200, 20)
         also["batch/16x(256x128)"] = bench_batch(torch, mp, (256, 128), 16, 0.1, 100, 10)
         also["batch/16x(1024x1024)"] = bench_batch(torch, mp, (1024, 1024), 16, 0.1, 100, 10)
+        also["batch/6x(4096x4096)"] = bench_batch(torch, mp, (4096, 4096), 6, 0.3, 30, 3)
         line["also"] = also
     if want_cpu:
         line["cpu_baseline"] = cpu_baseline(Y, head["eta"], x_timed, head["tau"])
