@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (340, 341)   # (341 added entry points only: the column kernels are those of 340)
+TRAFFIC_VERSIONS = (340, 341, 342)   # (341, 342: entry points and l1,1 kernels only; the column kernels are those of 340)
 TRAFFIC_KIB = {"square_4096": 32975.2 * 1.999 + 65559.4, "square_16384": 524911.1 * 1.999 + 1048618.7}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 

@@ -98,9 +98,11 @@ typedef struct mlproj_result {
   uint32_t n_active;     /* number of groups with u_j > 0                                             */
   uint32_t inside_ball;  /* 1 when ||Y||_{1,q} <= eta (X = Y)                                         */
   uint32_t search_iters; /* fixed-point iterations the search for tau took                            */
-  uint32_t inner_sweeps; /* l1,1 only: passes over Y the per-column threshold searches took           */
-  uint32_t inner_pending;/* l1,1 only: columns whose inner search had not converged (0 = exact)       */
-  uint32_t reserved[3];
+  uint32_t inner_sweeps; /* l1,1 only: lock-step passes over Y the per-column threshold searches took */
+  uint32_t inner_pending;/* l1,1 only: columns whose inner search had not converged; always 0, since  */
+                         /* the finishing pass closes every column exactly                           */
+  uint32_t inner_finished;/* l1,1 only: columns the lock-step passes left to the finishing pass       */
+  uint32_t reserved[2];
 } mlproj_result;
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -117,6 +119,15 @@ const char* mlproj_status_string(int status);
  * were recorded.  Off by default; adds nothing to calls made outside a trace.              */
 int mlproj_trace_begin(void** events /* host array of hipEvent_t */, int capacity);
 int mlproj_trace_end(void);
+
+/* Tuning knob for MLPROJ_L11 (Alg. 3): how many lock-step passes over Y a call enqueues for
+ * the per-column threshold searches before the column-wise finishing pass closes whatever is
+ * still open.  1..16, or 0 for the default, which grows with the number of rows (1 up to 512
+ * rows, 3 at 4096, 6 at 16384, 12 beyond 131072): the finishing pass costs more per column
+ * the taller the matrix.  The thresholds are exact for any value; only the time changes.
+ * Process-wide and read when a call is enqueued: set it while no other thread is calling.
+ * Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value outside 0..16.       */
+int mlproj_set_l11_sweeps(int sweeps);
 
 /* Bytes of workspace a call of `variant` on dims (d0, d1, d2) needs; bi-level
  * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.  The size is a few

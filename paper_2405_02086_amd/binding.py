@@ -70,6 +70,8 @@ def lib():
     L.mlproj_trace_begin.argtypes = [ctypes.POINTER(c_vp), c_i]
     L.mlproj_trace_end.restype = c_i
     L.mlproj_trace_end.argtypes = []
+    L.mlproj_set_l11_sweeps.restype = c_i
+    L.mlproj_set_l11_sweeps.argtypes = [c_i]
     L.mlproj_norm_l1q.restype = c_i
     L.mlproj_norm_l1q.argtypes = [c_vp, c_ll, c_ll, c_i, c_vp, c_sz, c_vp, c_vp, c_vp]
     for name in ("bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12"):
@@ -114,13 +116,21 @@ EXPORTS = (
     "mlproj_norm_l1q", "bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12",
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
-    "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored",
+    "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored", "mlproj_set_l11_sweeps",
 )
 
 
 def _check(status, where):
     if status != 0:
         raise MlprojError(status, where)
+
+
+def set_l11_sweeps(sweeps):
+    """Lock-step passes an l1,1 call enqueues before its finishing pass (0 = default); returns the old value."""
+    before = lib().mlproj_set_l11_sweeps(int(sweeps))
+    if before < 0:
+        raise MlprojError(before, "mlproj_set_l11_sweeps")
+    return before
 
 
 def workspace_bytes(variant, d0, d1, d2=1):
@@ -157,10 +167,10 @@ class Workspace:
     def result(self):
         """Synchronise and decode the mlproj_result record at the head of the workspace."""
         raw = bytes(self.buf[:64].cpu().numpy().tobytes())
-        tau, norm, vmax, scale, cap, n_active, inside, iters, sweeps, pending = struct.unpack_from("<dddddIIIII", raw)
+        tau, norm, vmax, scale, cap, n_active, inside, iters, sweeps, pending, finished = struct.unpack_from("<dddddIIIIII", raw)
         return {"tau": tau, "norm": norm, "vmax": vmax, "scale": scale, "cap": cap, "n_active": n_active,
                 "inside_ball": bool(inside), "search_iters": iters,
-                "inner_sweeps": sweeps, "inner_pending": pending}
+                "inner_sweeps": sweeps, "inner_pending": pending, "inner_finished": finished}
 
 
 def _prep(Y, X):

@@ -28,7 +28,10 @@ namespace mlproj {
 // entry between them: f_j is linear there and N(p) is the root), or when the bounds meet.
 // On Gaussian data two sweeps close every column; heavy tails take a few more.
 // pending[s] is the number of columns still open before sweep s; the kernels of a sweep
-// return at once when it is zero.
+// return at once when it is zero, or at most `handoff`: the host sets that to a few hundred
+// when a sweep costs more than finishing that many stragglers column by column.  Only a few
+// sweeps are enqueued (see plan_l11 on the host side); columns still open after them go to
+// the finishing pass (l11_finish_kernel).
 //
 // A window is kept within a factor 2 (hi <= 2 lo), so its entries differ by at most one
 // binary exponent and any fp64 sum of them is exact: the order in which workgroups append
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
 template <typename T, int VEC, bool STRIDED>
 __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y, long long n,
                                                         long long m, Geometry g, Ws ws,
-                                                        int sweep) {
+                                                        int sweep, unsigned handoff) {
   constexpr int TILE_W = WAVE * VEC;
   constexpr int CAPW = FILTER_LDS_SLOTS / TILE_W;
   __shared__ double sm_sum[WAVES][TILE_W];
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
 
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
-  if (ws.pending[sweep] == 0u) return;
+  if (ws.pending[sweep] <= handoff) return;
 
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
@@ -248,13 +251,33 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
 // h(z) = 2*phi(z) - z*erfc(z/sqrt 2), so z solves h(z) = (u_j/v_j)*sqrt(2/pi) (a few Newton
 // steps on the convex h) and the guess is sigma*z.  Only the speed depends on the guess.
 // The first certified bounds: every entry active gives the lower bound (v_j - u_j)/n.
-__global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, Ws ws) {
-  const mlproj_result* res = ws.res;
-  if (res->inside_ball != 0u || res->n_active == 0u) return;
+// With fused_eta >= 0 every workgroup first runs the outer threshold search itself (see
+// search_block) and workgroup 0 files the result record and clears the sweep counters, which
+// takes the one-workgroup search kernel off the critical path; otherwise the record is read.
+template <int SC>
+__global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, Ws ws,
+                                                      double fused_eta, int outer) {
+  __shared__ PairScratch<WAVES> bs;
+  Top top;
+  bool nothing_to_do;
+  if (fused_eta >= 0.0) {
+    const SearchOut o = search_block<WG, SC>(ws.v, m, fused_eta, MODE_PROJECT, outer, bs);
+    top = top_of(o);
+    nothing_to_do = o.inside != 0u || o.active == 0u;
+    if (blockIdx.x == 0) {
+      if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
+      if (threadIdx.x == 0) write_result(ws, o, nullptr);
+    }
+  } else {
+    const mlproj_result* res = ws.res;
+    top = top_of(res);
+    nothing_to_do = res->inside_ball != 0u || res->n_active == 0u;
+  }
+  if (nothing_to_do) return;
   const long long j = (long long)blockIdx.x * WG + threadIdx.x;
   if (j >= m) return;
   const double vj = ws.v[j];
-  const double uj = radius(vj, top_of(res));
+  const double uj = radius(vj, top);
   double tj = HUGE_VAL, floor_t = HUGE_VAL;
   if (uj > 0.0) {
     // (fp32 is plenty here: the guess is a statistical estimate, off by percents)
@@ -334,11 +357,11 @@ constexpr int UPD_COLS = WG / UPD_SEG;   // columns per workgroup
 static_assert(UPD_SEG == LIST_LANES, "the list capacity is planned for this many lanes per column");
 
 __global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m, Geometry g,
-                                                        Ws ws, int sweep) {
+                                                        Ws ws, int sweep, unsigned handoff) {
   __shared__ BlockScratch<WAVES> bs;
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
-  if (sweep > 0 && ws.pending[sweep] == 0u) return;
+  if (sweep > 0 && ws.pending[sweep] <= handoff) return;
 
   const int part = threadIdx.x % UPD_SEG;
   const int seg_base = (threadIdx.x & (WAVE - 1)) & ~(UPD_SEG - 1);   // first lane of the segment
@@ -490,12 +513,102 @@ __global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m
   }
 }
 
-// After the last sweep: how many columns were still open (0 = every inner search is exact).
-// (Only for a call that stops before the map pass, which otherwise does this itself.)
-__global__ void l11_close_kernel(Ws ws) {
-  if (threadIdx.x == 0) {
-    const unsigned s = ws.res->inner_sweeps;
-    ws.res->inner_pending = (s >= (unsigned)MAX_INNER_SWEEPS) ? ws.pending[MAX_INNER_SWEEPS] : 0u;
+// The finishing pass: whatever the lock-step sweeps left open is closed here, column by
+// column, with the plain fixed point of the outer search, tau <- (sum_{|y| > tau} |y| - u_j) /
+// #{|y| > tau}, started at the certified lower bound the sweeps reached.  From below the
+// iteration rises monotonically and the active count only shrinks, so it ends after at most n
+// steps (in practice a handful: the bound is already tight) at the exact root, in fp64.
+// A workgroup owns FIN_COLS = 16 neighbouring columns (one 64-byte run of every row) and
+// leaves at once when none of them is open; thread (r, c) reads rows r, r + 64, ... of column
+// c, the four lanes of a wavefront that share a column add up on the crossbar, the sixteen
+// wavefronts through LDS in a fixed order.  The columns are strided in memory, so this pass
+// moves 64 bytes for every 4 it needs from a lone open column: good for stragglers, and no
+// worse than a sweep when many neighbouring columns are open.  It replaces a long tail of
+// lock-step launches that found nothing to do.
+constexpr int FIN_COLS = 16;
+constexpr int FIN_ROWS = SWG / FIN_COLS;   // rows one trip of the workgroup covers
+constexpr int FIN_UNROLL = 8;              // loads in flight per thread
+
+template <typename T>
+__global__ __launch_bounds__(SWG) void l11_finish_kernel(const T* __restrict__ Y, long long n,
+                                                         long long m, Ws ws, int sweeps,
+                                                         unsigned handoff) {
+  __shared__ double sm_s[SWAVES][FIN_COLS];
+  __shared__ unsigned sm_k[SWAVES][FIN_COLS];
+  mlproj_result* res = ws.res;
+  if (res->inside_ball != 0u || res->n_active == 0u) return;
+  int stop = 1;   // the sweep at which the lock-step kernels stopped (see `handoff` there)
+  while (stop < sweeps && ws.pending[stop] > handoff) ++stop;
+  const unsigned left = ws.pending[stop];
+  if (blockIdx.x == 0 && threadIdx.x == 0) res->inner_finished = left;
+  if (left == 0u) return;
+
+  const int c = threadIdx.x % FIN_COLS;
+  const int r = threadIdx.x / FIN_COLS;
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave = threadIdx.x / WAVE;
+  const long long j = (long long)blockIdx.x * FIN_COLS + c;
+  const long long jj = j < m ? j : m - 1;   // a column past the end shadows the last one
+  const bool mine = j < m && ws.done[jj] == 0u;
+  bool open = mine;
+  if (!__syncthreads_or(open ? 1 : 0)) return;
+
+  const double uj = radius(ws.v[jj], top_of(res));
+  double t = ws.lb[jj];
+  unsigned kprev = NO_COUNT;
+  const T* col = Y + jj;
+  for (;;) {
+    const float ct = above(t);
+    double s = 0.0;
+    unsigned k = 0u;
+    auto visit = [&](T x) {
+      const float a = fabsf((float)x);
+      const bool in = a >= ct;
+      s += (double)(in ? a : 0.0f);
+      k += in ? 1u : 0u;
+    };
+    long long i = r;
+    for (; i + (long long)(FIN_UNROLL - 1) * FIN_ROWS < n; i += (long long)FIN_UNROLL * FIN_ROWS) {
+      T x[FIN_UNROLL];
+#pragma unroll
+      for (int u = 0; u < FIN_UNROLL; ++u) x[u] = col[(i + (long long)u * FIN_ROWS) * m];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < FIN_UNROLL; ++u) visit(x[u]);
+    }
+    for (; i < n; i += FIN_ROWS) visit(col[i * m]);
+    // lanes c, c + 16, c + 32, c + 48 of a wavefront share the column
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    k += __shfl_xor(k, 16);
+    k += __shfl_xor(k, 32);
+    if (lane < FIN_COLS) {
+      sm_s[wave][c] = s;
+      sm_k[wave][c] = k;
+    }
+    __syncthreads();
+    double S = sm_s[0][c];
+    unsigned K = sm_k[0][c];
+#pragma unroll
+    for (int w = 1; w < SWAVES; ++w) {
+      S += sm_s[w][c];
+      K += sm_k[w][c];
+    }
+    if (open) {
+      if (K == 0u || K == kprev) {
+        open = false;   // t came from this very active set: it is the root
+      } else {
+        kprev = K;
+        const double tn = (S - uj) / (double)K;
+        if (tn > t) t = tn;
+        else open = false;   // no move left: t is the root, to rounding
+      }
+    }
+    if (!__syncthreads_or(open ? 1 : 0)) break;   // (also keeps the LDS rows until all have read them)
+  }
+  if (r == 0 && mine) {
+    ws.tauj[j] = t;
+    ws.done[j] = 1u;
   }
 }
 

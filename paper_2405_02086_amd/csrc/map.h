@@ -60,13 +60,6 @@ __device__ __forceinline__ void colmap_body(const T* Y, T* X, long long n, long 
   } else {
     top = top_of(ws.res);
     inside = ws.res->inside_ball != 0u;
-    if constexpr (Q == Q1) {
-      // how many columns the inner searches left open (0 = every threshold is exact)
-      if (bid == 0 && threadIdx.x == 0) {
-        const unsigned s = ws.res->inner_sweeps;
-        ws.res->inner_pending = (s >= (unsigned)MAX_INNER_SWEEPS) ? ws.pending[MAX_INNER_SWEEPS] : 0u;
-      }
-    }
   }
   if (!col_ok) return;
 

@@ -7,10 +7,11 @@
 // One bi-level call is a chain of kernels on the caller's stream; nothing returns to the host:
 //   colagg    Y -> per-(column tile, row group) partial aggregates        (reads Y once)
 //   reduce    partials -> v_j = ||y_j||_q                                  (tiny)
-//   search    v -> tau, the l1-ball threshold; run redundantly at the head of colmap when
-//             there are at most 16384 groups, a kernel of its own otherwise     (tiny)
-//   [init, sweep, filter/update ...]  l1,1 only: per-column inner thresholds, one read of Y
-//             per sweep, typically two sweeps
+//   search    v -> tau, the l1-ball threshold; run redundantly at the head of colmap (of the
+//             seeding kernel for l1,1) when there are at most 16384 groups, a kernel of its
+//             own otherwise                                                     (tiny)
+//   [init, sweep, filter/update ..., finish]  l1,1 only: per-column inner thresholds, one
+//             read of Y per lock-step sweep (typically two), stragglers column by column
 //   colmap    Y, v, tau -> X                                  (reads Y again, writes X once)
 // Workgroups never wait for one another inside a kernel: on this GPU a device-scope fence
 // costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only
@@ -121,6 +122,24 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
                      only_as_fallback, (double*)nullptr, (float*)nullptr);
 }
 
+// l1,1: how many lock-step sweeps to enqueue before the finishing pass, and the number of
+// open columns at which the remaining sweeps hand over to it (see l11.h).  Measured on an
+// MI355X: a sweep that finds nothing to do costs two launches (3.6 us); one iteration of the
+// finishing pass costs about n/512 us for up to 512 groups of 16 columns, and it needs about
+// four from the bounds the sweeps leave; two sweeps close every column on Gaussian data,
+// heavy tails take up to ten.  So short matrices get few sweeps (finishing is cheap), tall
+// ones more, and where a sweep is dearer than finishing a few hundred stragglers the sweeps
+// stop as soon as no more than that are open.
+static int g_l11_sweeps = 0;  // 0 = automatic
+static void plan_l11(long long n, long long m, int elem_bytes, int* sweeps, unsigned* handoff) {
+  const double sweep_us = (double)n * (double)m * elem_bytes / 4e6 + 6.0;
+  const double finish_us = 4.0 * (double)n / 512.0;
+  *handoff = sweep_us > finish_us ? 512u : 0u;
+  if (g_l11_sweeps > 0) { *sweeps = g_l11_sweeps; return; }
+  *sweeps = n <= 512 ? 1 : n <= 2048 ? 2 : n <= 4096 ? 3 : n <= 8192 ? 4 : n <= 32768 ? 6
+          : n <= 131072 ? 8 : 12;
+}
+
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
 // STAGE_APPLY = the per-column map.
 template <int Q, typename T = float>
@@ -170,25 +189,37 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     mark(stream);
     hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
-    if (!fuse) {
+    // (l1,1: the kernel that seeds the inner searches runs the outer search the same way)
+    const bool fuse_l11 = Q == Q1 && mode == MODE_PROJECT && m <= FUSED_SEARCH_MAX_BIG;
+    if (!fuse && !fuse_l11) {
       mark(stream);
       launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
     }
     if (mode == MODE_NORM) { mark(stream); return launch_status(); }
     if constexpr (Q == Q1) {
       mark(stream);
-      hipLaunchKernelGGL(l11_init_kernel, dim3((unsigned)cdiv(m, WG)), block, 0, stream, n, m, ws);
-      for (int s = 0; s < MAX_INNER_SWEEPS; ++s) {
+      const dim3 igrid((unsigned)cdiv(m, WG));
+      if (!fuse_l11)
+        hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, -1.0, outer);
+      else if (m > FUSED_SEARCH_MAX)
+        hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE_BIG>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
+      else
+        hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
+      if (fuse_l11) mark(stream);   // (keeps one interval for search + seeding, one for the sweeps)
+      int sweeps;
+      unsigned handoff;
+      plan_l11(n, m, (int)sizeof(T), &sweeps, &handoff);
+      for (int s = 0; s < sweeps; ++s) {
         if (s == 0) {
           if (wide) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws);
           else hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws);
         } else {
-          if (wide) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws, s);
-          else hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws, s);
+          if (wide) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
+          else hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
         }
-        hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s);
+        hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s, handoff);
       }
-      if (!(stages & STAGE_APPLY)) hipLaunchKernelGGL(l11_close_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
+      hipLaunchKernelGGL((l11_finish_kernel<T>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(SWG), 0, stream, Y, n, m, ws, sweeps, handoff);
     }
   }
   if (stages & STAGE_APPLY) {
@@ -561,7 +592,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 341; }
+int mlproj_version(void) { return 342; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -591,6 +622,13 @@ int mlproj_trace_end(void) {
   const int n = g_trace.count;
   g_trace = Trace{};
   return n;
+}
+
+int mlproj_set_l11_sweeps(int sweeps) {
+  if (sweeps < 0 || sweeps > MAX_INNER_SWEEPS) return MLPROJ_ERR_BAD_DIMENSION;
+  const int before = g_l11_sweeps;
+  g_l11_sweeps = sweeps;
+  return before;
 }
 
 int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2, size_t* bytes_out) {

@@ -146,6 +146,7 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
   r->search_iters = o.iters;
   r->inner_sweeps = 0;
   r->inner_pending = 0;
+  r->inner_finished = 0;
   if (norm_out) *norm_out = o.total;
 }
 

@@ -221,6 +221,33 @@ def test_stored_trilevel_argument_checks(lib):
         assert tri(storage, ctypes.c_void_p((1 << 20) + 1), FAKE, 2, 2, 2, F(1), FAKE, big, None, None, None, None) == -7
 
 
+def test_l11_sweep_knob(lib):
+    """A plain process-wide integer: 0..16 accepted, the old value comes back, nothing else changes it."""
+    assert lib.mlproj_set_l11_sweeps(3) == 0
+    assert lib.mlproj_set_l11_sweeps(16) == 3
+    assert lib.mlproj_set_l11_sweeps(17) == -2 and lib.mlproj_set_l11_sweeps(-1) == -2
+    assert lib.mlproj_set_l11_sweeps(0) == 16
+    assert lib.mlproj_set_l11_sweeps(0) == 0
+
+
+def test_result_record_layout():
+    """The record is 72 bytes with inner_finished behind inner_pending (read from the header by a C compiler)."""
+    import shutil
+    import subprocess
+    import tempfile
+    if shutil.which("gcc") is None:
+        pytest.skip("gcc not installed")
+    src = ('#include <stdio.h>\n#include <stddef.h>\n#include "mlproj.h"\n'
+           'int main(void) { printf("%zu %zu %zu %zu\\n", sizeof(mlproj_result), offsetof(mlproj_result, inner_sweeps),'
+           ' offsetof(mlproj_result, inner_pending), offsetof(mlproj_result, inner_finished)); return 0; }\n')
+    with tempfile.TemporaryDirectory() as d:
+        open(os.path.join(d, "t.c"), "w").write(src)
+        subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), os.path.join(d, "t.c"), "-o", os.path.join(d, "t")],
+                       check=True)
+        out = subprocess.run([os.path.join(d, "t")], capture_output=True, text=True, check=True).stdout.split()
+    assert [int(x) for x in out] == [72, 52, 56, 60]
+
+
 def test_header_is_plain_c():
     """include/mlproj.h stands on its own as C99 and as C++11 (no HIP or torch types in it)."""
     import shutil

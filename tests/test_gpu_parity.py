@@ -791,6 +791,73 @@ def test_l11_inner_searches_on_adversarial_columns(mp, name):
         assert got["res"]["inner_sweeps"] <= 10
 
 
+@pytest.fixture
+def l11_sweeps(mp):
+    """Set the number of lock-step sweeps for one test; the default comes back afterwards."""
+    def set_to(k):
+        mp.set_l11_sweeps(k)
+    yield set_to
+    mp.set_l11_sweeps(0)
+
+
+@pytest.mark.parametrize("sweeps", [1, 2, 4])
+@pytest.mark.parametrize("family", ["gaussian", "cauchy", "lognormal3", "sparse", "clusters", "constant",
+                                    "integers", "geometric", "uniform"])
+def test_l11_finishing_pass_closes_what_the_sweeps_leave(mp, l11_sweeps, family, sweeps):
+    """With few lock-step sweeps the column-wise finishing pass does most of the work (all of
+    it after one sweep): same thresholds as the oracle's sort, nothing left pending."""
+    rng = np.random.default_rng([len(family), 78, sweeps])
+    n, m = 1037, 301            # ragged in both directions: 1037 = 2*512 + 13 rows, 301 = 18*16 + 13 columns
+    Y = (rng.standard_normal((n, m)) if family == "gaussian" else _hard_family(family, rng, n, m)).astype(np.float32)
+    l11_sweeps(sweeps)
+    finished = 0
+    for frac in (0.001, 0.1, 0.5, 0.95):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert got["res"]["inner_sweeps"] <= sweeps
+        finished += got["res"]["inner_finished"]
+    if sweeps == 1 and family == "gaussian":
+        assert finished > 0, "one sweep cannot close Gaussian columns: the finishing pass must have run"
+
+
+@pytest.mark.parametrize("name", ["binary", "outlier", "pow2", "two_levels", "two_rows", "denormal", "huge", "ramp",
+                                  "mixed_columns"])
+def test_l11_finishing_pass_on_adversarial_columns(mp, l11_sweeps, name):
+    Y = _adversarial_l11_cases()[name]
+    l11_sweeps(1)
+    for frac in (1e-4, 0.3, 0.999):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape", [(1, 1), (3, 17), (70, 4104), (2065, 264), (5000, 40)])
+def test_l11_finishing_pass_on_stored_types_and_odd_shapes(mp, l11_sweeps, storage, shape):
+    Y = stored_input(shape, storage, 35)
+    l11_sweeps(1)
+    for frac in (0.05, 0.6):
+        eta = eta_for(Y, 1, frac)
+        check_stored(run_stored(mp, Y, eta, 1, storage), orc.bilevel_stored(Y, eta, 1, storage), 1, storage)
+    check_stored(run_stored(mp, Y, eta_for(Y, 1, 0.3), 1, storage, offset=1, x_offset=3),
+                 orc.bilevel_stored(Y, eta_for(Y, 1, 0.3), 1, storage), 1, storage)
+
+
+def test_l11_sweep_count_does_not_change_the_result(mp, l11_sweeps):
+    """The thresholds are exact whichever pass closes a column, so X agrees to the last few bits."""
+    Y = workloads.generate((777, 1024), seed=5)
+    eta = eta_for(Y, 1, 0.2)
+    outs = []
+    for k in (1, 3, 16, 0):
+        l11_sweeps(k)
+        outs.append(run_gpu(mp, Y, eta, 1))
+    for o in outs[1:]:
+        np.testing.assert_allclose(o["X"], outs[0]["X"], rtol=0, atol=1e-6)
+        assert np.array_equal(o["X"] != 0, outs[0]["X"] != 0)
+    assert outs[0]["res"]["inner_finished"] > 0 and outs[2]["res"]["inner_finished"] == 0
+
+
 def test_l11_root_exactly_on_repeated_entries(mp):
     """Columns (3,3,3,1,1) with u_j = 6: the inner threshold is exactly 1, the value of two entries."""
     Y = np.tile(np.float32([3, 3, 3, 1, 1])[:, None], (1, 64))
