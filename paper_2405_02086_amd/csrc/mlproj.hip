@@ -382,6 +382,7 @@ static int dispatch_batch(int outer, int variant, int count, const mlproj_proble
 // ------------------------------------------------------------------ host: multi-level driver
 constexpr int ML_MAX_DIMS = 8;
 constexpr long long ML_TARGET_WGS = 1024;
+constexpr long long ML_AGG_SHORT_WGS = 512;  // pipelined aggregate: 2 workgroups per CU
 
 struct MlPlan {
   int ndim;
@@ -437,7 +438,20 @@ static unsigned fibre_grid(long long nf, int seg, int unroll) {
 template <int Q, typename TIN, int VEC>
 static void launch_fibre_agg(const TIN* A, long long nf, long long len, double* V, float* v_out,
                              hipStream_t stream) {
-  const int seg = seg_for(len / VEC);
+  const long long nvec = len / VEC;
+  const int seg = seg_for(nvec);
+  if (nvec <= (long long)seg * AGG_CHUNKS) {
+    // one batch of loads covers a fibre: the pipelined kernel, few enough workgroups that
+    // every wavefront has several batches to overlap
+    const long long per_wg = (long long)WAVES * (WAVE / seg) * AGG_FIBRES;
+    long long wgs = cdiv(nf, per_wg);
+    if (wgs > ML_AGG_SHORT_WGS) wgs = ML_AGG_SHORT_WGS;
+    const dim3 grid((unsigned)wgs), block(WG);
+    if (seg == 4) hipLaunchKernelGGL((fibre_agg_short_kernel<Q, TIN, 4, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+    else if (seg == 16) hipLaunchKernelGGL((fibre_agg_short_kernel<Q, TIN, 16, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+    else hipLaunchKernelGGL((fibre_agg_short_kernel<Q, TIN, 64, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+    return;
+  }
   const dim3 grid(fibre_grid(nf, seg, FIB_UNROLL)), block(WG);
   if (seg == 4) hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 4, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
   else if (seg == 16) hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 16, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
