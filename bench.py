@@ -217,22 +217,24 @@ def bench_small(torch, mp, Y_host, frac, steps, warmup):
     return out
 
 
-def bench_batch(torch, mp, shape, count, frac, steps, warmup):
+def bench_batch(torch, mp, shape, count, frac, steps, warmup, variant="l1inf"):
     """`count` matrices of one shape: one bilevel_proj_batch call against a loop of single calls."""
     import numpy as np
     from paper_2405_02086_amd import workloads
     dev = torch.device("cuda:0")
     Ys = [torch.from_numpy(workloads.generate(shape, "normal", workloads.BASE_SEED + 100 + i)).to(dev) for i in range(count)]
     Xs = [torch.empty_like(Y) for Y in Ys]
-    wss = [mp.Workspace.for_call("l1inf", shape[0], shape[1], device=dev) for _ in Ys]
-    etas = [device_eta(mp, Y, "l1inf", frac, ws) for Y, ws in zip(Ys, wss)]
+    wss = [mp.Workspace.for_call(variant, shape[0], shape[1], device=dev) for _ in Ys]
+    etas = [device_eta(mp, Y, variant, frac, ws) for Y, ws in zip(Ys, wss)]
+    single = getattr(mp, "bilevel_proj_" + variant)
+    q = {"l1inf": "inf", "l11": 1, "l12": 2}[variant]
 
     def loop():
         for Y, X, ws, eta in zip(Ys, Xs, wss, etas):
-            mp.bilevel_proj_l1inf(Y, eta, X=X, workspace=ws)
+            single(Y, eta, X=X, workspace=ws)
 
     def batch():
-        mp.bilevel_proj_batch(Ys, etas, "inf", Xs=Xs, workspaces=wss)
+        mp.bilevel_proj_batch(Ys, etas, q, Xs=Xs, workspaces=wss)
 
     out = {"shape": list(shape), "count": count}
     for name, fn in (("ms_loop_of_single_calls", loop), ("ms_one_batch_call", batch)):
@@ -244,13 +246,15 @@ def bench_batch(torch, mp, shape, count, frac, steps, warmup):
             fn()
         torch.cuda.synchronize()
         out[name] = (time.perf_counter() - t0) * 1e3 / steps
-    # what the GPU spends on one batch call, from the library's own events (aggregate, fold, map)
+    # what the GPU spends on one batch call, from the library's own events
     tr = mp.KernelTrace(8)
     with tr:
         batch()
     d = tr.durations_ms()
     tr.close()
-    out["batch_kernel_ms_event_intervals"] = dict(zip(["colagg", "reduce", "colmap+search"], d))
+    labels = ["colagg", "reduce", "colmap+search"] if variant != "l11" else \
+        ["colagg", "reduce", "seeding+search", "l11_sweeps", "colmap"]
+    out["batch_kernel_ms_event_intervals"] = dict(zip(labels, d))
     return out
 
 
@@ -352,6 +356,8 @@ def main():
         also["batch/16x(256x128)"] = bench_batch(torch, mp, (256, 128), 16, 0.1, 100, 10)
         also["batch/16x(1024x1024)"] = bench_batch(torch, mp, (1024, 1024), 16, 0.1, 100, 10)
         also["batch/6x(4096x4096)"] = bench_batch(torch, mp, (4096, 4096), 6, 0.3, 30, 3)
+        also["batch/16x(256x128)/l11"] = bench_batch(torch, mp, (256, 128), 16, 0.1, 100, 10, "l11")
+        also["batch/16x(1024x1024)/l11"] = bench_batch(torch, mp, (1024, 1024), 16, 0.1, 100, 10, "l11")
         line["also"] = also
     if want_cpu:
         line["cpu_baseline"] = cpu_baseline(Y, head["eta"], x_timed, head["tau"])

@@ -207,10 +207,11 @@ typedef struct mlproj_problem {
 
 /* `count` independent bi-level projections that share storage type, outer norm and variant
  * (the weight matrices a training loop projects after a step, Sec. 6.3), with the results of
- * `count` calls of bilevel_proj_stored, bit for bit.  Matrices of at most 16384 columns with
- * variant MLPROJ_L1INF or MLPROJ_L12 share their kernel launches, 16 matrices at a time (three
- * launches for all of them instead of three each, which is what small matrices cost); the
- * others are enqueued one after another behind them.  `problems` is a host array, read before
+ * `count` calls of bilevel_proj_stored, bit for bit.  Matrices of at most 16384 columns share
+ * their kernel launches, 16 matrices at a time (three launches for all of them instead of
+ * three each, which is what small matrices cost; MLPROJ_L11 shares the launches of its
+ * per-column searches the same way); wider ones are enqueued one after another behind them.
+ * `problems` is a host array, read before
  * the call returns; all of it is checked before anything is enqueued.  Outputs of different
  * problems must not overlap.                                                                 */
 int bilevel_proj_batch(int storage, int outer_norm, int variant, int count,

@@ -4,13 +4,15 @@
 
 #include "aggregate.h"
 #include "common.h"
+#include "l11.h"
 #include "map.h"
 
 namespace mlproj {
 
 // A training loop projects many weight matrices after every step (the use Sec. 6.3 makes of
 // the projection), most of them small enough that the three launches of a call are what it
-// costs.  Up to BATCH_MAX matrices share one aggregate, one fold and one map launch: the
+// costs.  Up to BATCH_MAX matrices share one aggregate, one fold and one map launch (and,
+// for l1,1, one launch per kernel of the inner searches): the
 // problems travel in the kernel arguments, a workgroup finds the problem its number falls
 // into and then runs exactly the code of the single-matrix kernels on it, with the geometry
 // and workspace layout recomputed on the device from (n, m).
@@ -77,12 +79,86 @@ __global__ __launch_bounds__(WG) void colmap_batch_kernel(BatchItems it, BatchGr
   const Ws ws = bind(b.ws, layout_for(g, b.m, Q));
   const T* Y = static_cast<const T*>(b.Y);
   T* X = static_cast<T*>(b.X);
+  const double eta = Q == Q1 ? -1.0 : b.eta;   // l1,1: tau comes from the record, not from a search here
   if (b.wide && b.x_vec)
-    colmap_body<Q, T, WIDE, false, true, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, b.eta, outer, bid);
+    colmap_body<Q, T, WIDE, false, true, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, eta, outer, bid);
   else if (b.wide)
-    colmap_body<Q, T, WIDE, false, false, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, b.eta, outer, bid);
+    colmap_body<Q, T, WIDE, false, false, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, eta, outer, bid);
   else
-    colmap_body<Q, T, WIDE, true, false, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, b.eta, outer, bid);
+    colmap_body<Q, T, WIDE, true, false, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, eta, outer, bid);
+}
+
+// ------------------------------------------------------------------ l1,1: the inner searches
+// The same for the kernels of the per-column threshold searches (l11.h).  Every problem has
+// its own number of lock-step sweeps and hand-over count; a sweep kernel of the batch leaves
+// the problems alone that planned fewer sweeps.
+struct BatchL11Plan {
+  int sweeps[BATCH_MAX];
+  unsigned handoff[BATCH_MAX];
+};
+
+template <typename T, int SC>
+__global__ __launch_bounds__(WG) void l11_init_batch_kernel(BatchItems it, BatchGrid gr, int outer) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  long long bid;
+  const BatchItem& b = it.item[batch_find(gr, it.count, bid)];
+  const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
+  const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
+  l11_init_body<SC>(b.n, b.m, ws, b.eta, outer, bid);
+}
+
+template <typename T>
+__global__ __launch_bounds__(WG) void l11_sweep_batch_kernel(BatchItems it, BatchGrid gr) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  __shared__ SweepLds<WAVE * WIDE> lds;
+  long long bid;
+  const BatchItem& b = it.item[batch_find(gr, it.count, bid)];
+  const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
+  const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
+  const T* Y = static_cast<const T*>(b.Y);
+  if (b.wide) l11_sweep_body<T, WIDE, false>(Y, b.n, b.m, g, ws, bid, lds);
+  else l11_sweep_body<T, WIDE, true>(Y, b.n, b.m, g, ws, bid, lds);
+}
+
+template <typename T>
+__global__ __launch_bounds__(WG) void l11_filter_batch_kernel(BatchItems it, BatchGrid gr,
+                                                              BatchL11Plan plan, int sweep) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  __shared__ FilterLds<WAVE * WIDE> lds;
+  long long bid;
+  const int p = batch_find(gr, it.count, bid);
+  if (sweep >= plan.sweeps[p]) return;
+  const BatchItem& b = it.item[p];
+  const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
+  const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
+  const T* Y = static_cast<const T*>(b.Y);
+  if (b.wide) l11_filter_body<T, WIDE, false>(Y, b.n, b.m, g, ws, sweep, plan.handoff[p], bid, lds);
+  else l11_filter_body<T, WIDE, true>(Y, b.n, b.m, g, ws, sweep, plan.handoff[p], bid, lds);
+}
+
+template <typename T>
+__global__ __launch_bounds__(WG) void l11_update_batch_kernel(BatchItems it, BatchGrid gr,
+                                                              BatchL11Plan plan, int sweep) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  long long bid;
+  const int p = batch_find(gr, it.count, bid);
+  if (sweep >= plan.sweeps[p]) return;
+  const BatchItem& b = it.item[p];
+  const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
+  const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
+  l11_update_body(b.n, b.m, g, ws, sweep, plan.handoff[p], bid);
+}
+
+template <typename T>
+__global__ __launch_bounds__(SWG) void l11_finish_batch_kernel(BatchItems it, BatchGrid gr,
+                                                               BatchL11Plan plan) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  long long bid;
+  const int p = batch_find(gr, it.count, bid);
+  const BatchItem& b = it.item[p];
+  const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
+  const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
+  l11_finish_body<T>(static_cast<const T*>(b.Y), b.n, b.m, ws, plan.sweeps[p], plan.handoff[p], bid);
 }
 
 }  // namespace mlproj

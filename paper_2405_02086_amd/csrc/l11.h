@@ -45,21 +45,32 @@ __device__ __forceinline__ float above(double t) {
 }
 
 // Sweep 0: sum and count of the entries above t = tauj, count above t*(1 + L11_WINDOW).
+// (`bid` is the workgroup's number within its own problem: blockIdx.x for a single matrix.
+// The LDS arrays belong to the kernel, so that a kernel which holds both access forms of a
+// body pays for them once.)
+template <int TILE_W>
+struct SweepLds {
+  double sum[WAVES][TILE_W];
+  unsigned cnt[WAVES][TILE_W];
+  unsigned cnt2[WAVES][TILE_W];
+};
+
 template <typename T, int VEC, bool STRIDED>
-__global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, long long n,
-                                                       long long m, Geometry g, Ws ws) {
+__device__ __forceinline__ void l11_sweep_body(const T* __restrict__ Y, long long n, long long m,
+                                               const Geometry& g, const Ws& ws, long long bid,
+                                               SweepLds<WAVE * VEC>& lds) {
   constexpr int TILE_W = WAVE * VEC;
-  __shared__ double sm_sum[WAVES][TILE_W];
-  __shared__ unsigned sm_cnt[WAVES][TILE_W];
-  __shared__ unsigned sm_cnt2[WAVES][TILE_W];
+  auto& sm_sum = lds.sum;
+  auto& sm_cnt = lds.cnt;
+  auto& sm_cnt2 = lds.cnt2;
 
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
 
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
-  const long long t = blockIdx.x % g.tiles;
-  const long long grp = blockIdx.x / g.tiles;
+  const long long t = bid % g.tiles;
+  const long long grp = bid / g.tiles;
   const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
 
   double sum[VEC];
@@ -124,22 +135,38 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
   }
 }
 
+template <typename T, int VEC, bool STRIDED>
+__global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, long long n,
+                                                       long long m, Geometry g, Ws ws) {
+  __shared__ SweepLds<WAVE * VEC> lds;
+  l11_sweep_body<T, VEC, STRIDED>(Y, n, m, g, ws, blockIdx.x, lds);
+}
+
 // Sweeps 1, 2, ...: sum and count of the entries above hi = tauj, and the entries in
 // (tlo, hi] themselves.  A workgroup stages the window entries of its tile's columns in LDS
 // (FILTER_LDS_SLOTS / TILE_W slots per column), then reserves room in each column's list with
 // one atomic add per column and copies them out.  gcnt ends as the true number of window
 // entries of the column whether or not they all fitted; gflag marks a column some workgroup
 // could not stage completely.
+template <int TILE_W>
+struct FilterLds {
+  double sum[WAVES][TILE_W];
+  unsigned cnt[WAVES][TILE_W];
+  float staged[FILTER_LDS_SLOTS / TILE_W][TILE_W];   // slot-major: the lanes of a wavefront hit different banks
+  unsigned staged_cnt[TILE_W];
+};
+
 template <typename T, int VEC, bool STRIDED>
-__global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y, long long n,
-                                                        long long m, Geometry g, Ws ws,
-                                                        int sweep, unsigned handoff) {
+__device__ __forceinline__ void l11_filter_body(const T* __restrict__ Y, long long n, long long m,
+                                                const Geometry& g, const Ws& ws, int sweep,
+                                                unsigned handoff, long long bid,
+                                                FilterLds<WAVE * VEC>& lds) {
   constexpr int TILE_W = WAVE * VEC;
   constexpr int CAPW = FILTER_LDS_SLOTS / TILE_W;
-  __shared__ double sm_sum[WAVES][TILE_W];
-  __shared__ unsigned sm_cnt[WAVES][TILE_W];
-  __shared__ float staged[CAPW][TILE_W];   // slot-major: the lanes of a wavefront hit different banks
-  __shared__ unsigned staged_cnt[TILE_W];
+  auto& sm_sum = lds.sum;
+  auto& sm_cnt = lds.cnt;
+  auto& staged = lds.staged;
+  auto& staged_cnt = lds.staged_cnt;
 
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
@@ -147,8 +174,8 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
 
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
-  const long long t = blockIdx.x % g.tiles;
-  const long long grp = blockIdx.x / g.tiles;
+  const long long t = bid % g.tiles;
+  const long long grp = bid / g.tiles;
   const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
 
   for (int c = threadIdx.x; c < TILE_W; c += WG) staged_cnt[c] = 0u;
@@ -245,6 +272,14 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
   }
 }
 
+template <typename T, int VEC, bool STRIDED>
+__global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y, long long n,
+                                                        long long m, Geometry g, Ws ws,
+                                                        int sweep, unsigned handoff) {
+  __shared__ FilterLds<WAVE * VEC> lds;
+  l11_filter_body<T, VEC, STRIDED>(Y, n, m, g, ws, sweep, handoff, blockIdx.x, lds);
+}
+
 // Starting points of the inner searches.  Dropped columns get +inf (every entry maps to 0).
 // For a kept column the guess assumes its entries are Gaussian with the scale its l1 norm
 // implies: E|y| = sigma*sqrt(2/pi) = v_j/n and E max(|y| - t, 0) = sigma*h(t/sigma) with
@@ -255,8 +290,8 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
 // search_block) and workgroup 0 files the result record and clears the sweep counters, which
 // takes the one-workgroup search kernel off the critical path; otherwise the record is read.
 template <int SC>
-__global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, Ws ws,
-                                                      double fused_eta, int outer) {
+__device__ __forceinline__ void l11_init_body(long long n, long long m, const Ws& ws,
+                                              double fused_eta, int outer, long long bid) {
   __shared__ PairScratch<WAVES> bs;
   Top top;
   bool nothing_to_do;
@@ -264,7 +299,7 @@ __global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, 
     const SearchOut o = search_block<WG, SC>(ws.v, m, fused_eta, MODE_PROJECT, outer, bs);
     top = top_of(o);
     nothing_to_do = o.inside != 0u || o.active == 0u;
-    if (blockIdx.x == 0) {
+    if (bid == 0) {
       if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
       if (threadIdx.x == 0) write_result(ws, o, nullptr);
     }
@@ -274,7 +309,7 @@ __global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, 
     nothing_to_do = res->inside_ball != 0u || res->n_active == 0u;
   }
   if (nothing_to_do) return;
-  const long long j = (long long)blockIdx.x * WG + threadIdx.x;
+  const long long j = bid * WG + threadIdx.x;
   if (j >= m) return;
   const double vj = ws.v[j];
   const double uj = radius(vj, top);
@@ -301,6 +336,12 @@ __global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, 
   ws.done[j] = uj > 0.0 ? 0u : 1u;
   ws.gcnt[j] = 0u;
   ws.gflag[j] = 0u;
+}
+
+template <int SC>
+__global__ __launch_bounds__(WG) void l11_init_kernel(long long n, long long m, Ws ws,
+                                                      double fused_eta, int outer) {
+  l11_init_body<SC>(n, m, ws, fused_eta, outer, blockIdx.x);
 }
 
 // Root of the local model of f_j - u_j: value fb, slope -kb, entry density rho at the base
@@ -356,8 +397,9 @@ constexpr int UPD_SEG = 16;
 constexpr int UPD_COLS = WG / UPD_SEG;   // columns per workgroup
 static_assert(UPD_SEG == LIST_LANES, "the list capacity is planned for this many lanes per column");
 
-__global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m, Geometry g,
-                                                        Ws ws, int sweep, unsigned handoff) {
+__device__ __forceinline__ void l11_update_body(long long n, long long m, const Geometry& g,
+                                                const Ws& ws, int sweep, unsigned handoff,
+                                                long long bid) {
   __shared__ BlockScratch<WAVES> bs;
   const mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
@@ -365,7 +407,7 @@ __global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m
 
   const int part = threadIdx.x % UPD_SEG;
   const int seg_base = (threadIdx.x & (WAVE - 1)) & ~(UPD_SEG - 1);   // first lane of the segment
-  const long long j = (long long)blockIdx.x * UPD_COLS + threadIdx.x / UPD_SEG;
+  const long long j = bid * UPD_COLS + threadIdx.x / UPD_SEG;
   const bool mine = j < m && ws.done[j] == 0u;
 
   // fold the partial sums and counts of the sweep
@@ -509,8 +551,13 @@ __global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m
   const unsigned wg_open = block_sum_u(open, bs);
   if (threadIdx.x == 0) {
     if (wg_open) atomicAdd(&ws.pending[sweep + 1], wg_open);
-    if (blockIdx.x == 0) ws.res->inner_sweeps = (unsigned)sweep + 1u;
+    if (bid == 0) ws.res->inner_sweeps = (unsigned)sweep + 1u;
   }
+}
+
+__global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m, Geometry g,
+                                                        Ws ws, int sweep, unsigned handoff) {
+  l11_update_body(n, m, g, ws, sweep, handoff, blockIdx.x);
 }
 
 // The finishing pass: whatever the lock-step sweeps left open is closed here, column by
@@ -529,10 +576,12 @@ constexpr int FIN_COLS = 16;
 constexpr int FIN_ROWS = SWG / FIN_COLS;   // rows one trip of the workgroup covers
 constexpr int FIN_UNROLL = 8;              // loads in flight per thread
 
+static_assert(FIN_COLS == UPD_COLS, "a batch launches both kernels on the same grid");
+
 template <typename T>
-__global__ __launch_bounds__(SWG) void l11_finish_kernel(const T* __restrict__ Y, long long n,
-                                                         long long m, Ws ws, int sweeps,
-                                                         unsigned handoff) {
+__device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long long n, long long m,
+                                                const Ws& ws, int sweeps, unsigned handoff,
+                                                long long bid) {
   __shared__ double sm_s[SWAVES][FIN_COLS];
   __shared__ unsigned sm_k[SWAVES][FIN_COLS];
   mlproj_result* res = ws.res;
@@ -540,14 +589,14 @@ __global__ __launch_bounds__(SWG) void l11_finish_kernel(const T* __restrict__ Y
   int stop = 1;   // the sweep at which the lock-step kernels stopped (see `handoff` there)
   while (stop < sweeps && ws.pending[stop] > handoff) ++stop;
   const unsigned left = ws.pending[stop];
-  if (blockIdx.x == 0 && threadIdx.x == 0) res->inner_finished = left;
+  if (bid == 0 && threadIdx.x == 0) res->inner_finished = left;
   if (left == 0u) return;
 
   const int c = threadIdx.x % FIN_COLS;
   const int r = threadIdx.x / FIN_COLS;
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
-  const long long j = (long long)blockIdx.x * FIN_COLS + c;
+  const long long j = bid * FIN_COLS + c;
   const long long jj = j < m ? j : m - 1;   // a column past the end shadows the last one
   const bool mine = j < m && ws.done[jj] == 0u;
   bool open = mine;
@@ -610,6 +659,13 @@ __global__ __launch_bounds__(SWG) void l11_finish_kernel(const T* __restrict__ Y
     ws.tauj[j] = t;
     ws.done[j] = 1u;
   }
+}
+
+template <typename T>
+__global__ __launch_bounds__(SWG) void l11_finish_kernel(const T* __restrict__ Y, long long n,
+                                                         long long m, Ws ws, int sweeps,
+                                                         unsigned handoff) {
+  l11_finish_body<T>(Y, n, m, ws, sweeps, handoff, blockIdx.x);
 }
 
 }  // namespace mlproj

@@ -310,9 +310,9 @@ static int run_trilevel(const T* Y, T* X, long long d0, long long d1, long long 
 
 
 // ------------------------------------------------------------------ host: batches
-// Every problem is checked first (nothing is enqueued if one fails).  Problems whose map pass
-// can search tau itself (q = inf or 2, at most 16384 columns) go through the batch kernels,
-// BATCH_MAX at a time; the others (l1,1, more columns) are enqueued one by one behind them.
+// Every problem is checked first (nothing is enqueued if one fails).  Problems of at most
+// 16384 columns (a workgroup can search tau itself) go through the batch kernels, BATCH_MAX
+// at a time; wider ones are enqueued one by one behind them.
 template <int Q, typename T>
 static int run_batch(int outer, int count, const mlproj_problem* pr, void* stream_) {
   constexpr int WIDE = 16 / (int)sizeof(T);
@@ -324,14 +324,16 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
     if (st != MLPROJ_OK) return st;
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  auto batchable = [&](int i) { return Q != Q1 && pr[i].m <= FUSED_SEARCH_MAX_BIG; };
+  auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG; };
   int i = 0;
   while (i < count) {
     BatchItems it;
-    BatchGrid agg, red, map;
+    BatchGrid agg, red, map, ini, upd;
+    BatchL11Plan plan;
     it.count = 0;
     bool big = false;
-    unsigned a = 0, r = 0, mp = 0;
+    unsigned a = 0, r = 0, mp = 0, in = 0, up = 0;
+    int max_sweeps = 0;
     for (; i < count && it.count < BATCH_MAX; ++i) {
       if (!batchable(i)) continue;
       const mlproj_problem& p = pr[i];
@@ -345,15 +347,33 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
       agg.first[it.count] = a; a += (unsigned)(g.tiles * g.groups);
       red.first[it.count] = r; r += (unsigned)cdiv(p.m, SWG / reduce_parts(g.groups));
       map.first[it.count] = mp; mp += (unsigned)(g.tiles * g.map_groups);
+      ini.first[it.count] = in; in += (unsigned)cdiv(p.m, WG);
+      upd.first[it.count] = up; up += (unsigned)cdiv(p.m, UPD_COLS);
+      plan_l11(p.n, p.m, (int)sizeof(T), &plan.sweeps[it.count], &plan.handoff[it.count]);
+      if (plan.sweeps[it.count] > max_sweeps) max_sweeps = plan.sweeps[it.count];
       big = big || p.m > FUSED_SEARCH_MAX;
       ++it.count;
     }
     if (it.count == 0) break;
     agg.first[it.count] = a; red.first[it.count] = r; map.first[it.count] = mp;
+    ini.first[it.count] = in; upd.first[it.count] = up;
     mark(stream);
     hipLaunchKernelGGL((colagg_batch_kernel<Q, T>), dim3(a), dim3(WG), 0, stream, it, agg);
     mark(stream);
     hipLaunchKernelGGL((reduce_batch_kernel<Q, T>), dim3(r), dim3(SWG), 0, stream, it, red);
+    if constexpr (Q == Q1) {
+      // the inner searches: every kernel of the single-matrix chain once for the whole batch
+      mark(stream);
+      if (big) hipLaunchKernelGGL((l11_init_batch_kernel<T, SEARCH_CACHE_BIG>), dim3(in), dim3(WG), 0, stream, it, ini, outer);
+      else hipLaunchKernelGGL((l11_init_batch_kernel<T, SEARCH_CACHE>), dim3(in), dim3(WG), 0, stream, it, ini, outer);
+      mark(stream);
+      for (int s = 0; s < max_sweeps; ++s) {
+        if (s == 0) hipLaunchKernelGGL((l11_sweep_batch_kernel<T>), dim3(a), dim3(WG), 0, stream, it, agg);
+        else hipLaunchKernelGGL((l11_filter_batch_kernel<T>), dim3(a), dim3(WG), 0, stream, it, agg, plan, s);
+        hipLaunchKernelGGL((l11_update_batch_kernel<T>), dim3(up), dim3(WG), 0, stream, it, upd, plan, s);
+      }
+      hipLaunchKernelGGL((l11_finish_batch_kernel<T>), dim3(up), dim3(SWG), 0, stream, it, upd, plan);
+    }
     mark(stream);
     if (big) hipLaunchKernelGGL((colmap_batch_kernel<Q, T, SEARCH_CACHE_BIG>), dim3(mp), dim3(WG), 0, stream, it, map, outer);
     else hipLaunchKernelGGL((colmap_batch_kernel<Q, T, SEARCH_CACHE>), dim3(mp), dim3(WG), 0, stream, it, map, outer);
