@@ -23,6 +23,15 @@ def mp():
     return binding
 
 
+@pytest.fixture
+def l11_sweeps(mp):
+    """Set the number of lock-step sweeps for one test; the default comes back afterwards."""
+    def set_to(k):
+        mp.set_l11_sweeps(k)
+    yield set_to
+    mp.set_l11_sweeps(0)
+
+
 def run_gpu(mp, Y, eta, q, workspace=None, inplace=False):
     dev = torch.device("cuda:0")
     Yd = torch.from_numpy(Y).to(dev)
@@ -717,6 +726,32 @@ def test_batch_matches_oracle_and_single_calls(mp, q, storage):
         assert torch.equal(single, Xs[i]), "problem %d differs from its single call" % i
 
 
+def test_batch_l11_problems_keep_their_own_sweep_plans(mp, l11_sweeps):
+    """Heights from 3 to 9000 rows plan 1 to 6 lock-step sweeps; heavy tails need the finishing
+    pass for some problems and not for others; all in one batch, and again with a fixed count."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(91)
+    shapes = [(3, 40), (600, 33), (2500, 100), (5000, 64), (9000, 48), (700, 2000), (4097, 17)]
+    Ys = []
+    for i, sh in enumerate(shapes):
+        Y = rng.standard_cauchy(sh) if i % 2 else rng.standard_normal(sh)
+        Ys.append(Y.astype(np.float32))
+    etas = [eta_for(Y, 1, [0.001, 0.3, 0.9][i % 3]) for i, Y in enumerate(Ys)]
+    refs = orc.bilevel_batch(Ys, etas, 1, "f32")
+    for fixed in (0, 2):
+        l11_sweeps(fixed)
+        Yd = [torch.from_numpy(Y).to(dev) for Y in Ys]
+        wss = [mp.Workspace.for_call("l11", *Y.shape, device=dev) for Y in Ys]
+        Xs = mp.bilevel_proj_batch(Yd, etas, 1, workspaces=wss)
+        torch.cuda.synchronize()
+        for i, ref in enumerate(refs):
+            res = wss[i].result()
+            assert res["inner_pending"] == 0
+            np.testing.assert_allclose(Xs[i].cpu().numpy(), ref["X32"], rtol=RTOL, atol=ATOL)
+            assert np.array_equal(Xs[i].cpu().numpy().any(axis=0), ref["mask"])
+            assert torch.equal(mp.bilevel_proj_l11(Yd[i], etas[i]), Xs[i])
+
+
 def test_batch_in_place_and_kernel_count(mp):
     """In place; and the three launches of a small batch, seen through the event trace."""
     dev = torch.device("cuda:0")
@@ -789,15 +824,6 @@ def test_l11_inner_searches_on_adversarial_columns(mp, name):
         got = run_gpu(mp, Y, eta, 1)
         check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
         assert got["res"]["inner_sweeps"] <= 10
-
-
-@pytest.fixture
-def l11_sweeps(mp):
-    """Set the number of lock-step sweeps for one test; the default comes back afterwards."""
-    def set_to(k):
-        mp.set_l11_sweeps(k)
-    yield set_to
-    mp.set_l11_sweeps(0)
 
 
 @pytest.mark.parametrize("sweeps", [1, 2, 4])
