@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (340, 341, 342)   # (341, 342: entry points and l1,1 kernels only; the column kernels are those of 340)
+TRAFFIC_VERSIONS = (340, 341, 342, 343)   # (341-343: entry points, l1,1 and multi-level kernels only; the column kernels are those of 340)
 TRAFFIC_KIB = {"square_4096": 32975.2 * 1.999 + 65559.4, "square_16384": 524911.1 * 1.999 + 1048618.7}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
@@ -184,6 +184,20 @@ def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
             ws3 = mp.Workspace.for_call("tri", *Y_host.shape, device=dev)
             record("trilevel_proj_l1infinf", lambda Y, X: mp.trilevel_proj_l1infinf(Y, eta, X=X, workspace=ws3), ws3, eta)
         record("multilevel_proj/" + name, lambda Y, X: mp.multilevel_proj(Y, norms, eta, X=X, workspace=ws), ws, eta)
+    # the same tensor stored in bf16 (4 bytes per element moved instead of 8)
+    del pairs
+    torch.cuda.empty_cache()
+    Yb = Y0.to(torch.bfloat16)
+    pairs = [(Yb, torch.empty_like(Yb))] + [(Yb.clone(), torch.empty_like(Yb)) for _ in range(2 * npairs - 1)]
+    for name, norms in (("l111", [1, 1]),):
+        ws = mp.Workspace(mp.multilevel_workspace_bytes(Y_host.shape), device=dev)
+        mp.multilevel_proj_stored(pairs[0][0], norms, 3.0e38, X=pairs[0][1], workspace=ws)
+        torch.cuda.synchronize()
+        eta = float(np.float32(frac * ws.result()["norm"]))
+        record("multilevel_proj_stored/" + name + "/bf16",
+               lambda Y, X: mp.multilevel_proj_stored(Y, norms, eta, X=X, workspace=ws), ws, eta)
+        out["multilevel_proj_stored/" + name + "/bf16"]["eff_GBps_rw"] /= 2
+        out["multilevel_proj_stored/" + name + "/bf16"]["frac_of_peak_rw"] /= 2
     del pairs
     torch.cuda.empty_cache()
     return out

@@ -278,6 +278,19 @@ int multilevel_proj_p(int outer_norm, const float* Y, float* X, int ndim, const 
                       const int* norms, float eta, void* workspace, size_t workspace_bytes,
                       float* v_out, float* u_out, void* stream);
 
+/* multilevel_proj_p on a tensor stored in fp32, bf16 or fp16 (a mlproj_storage, as in
+ * bilevel_proj_stored: the 16-bit formats are storage only; every level above the tensor is
+ * kept in fp64 and X is rounded to nearest-even once, on store).  Y and X must be aligned to
+ * the element size; 16-byte aligned pointers and a last axis that is a multiple of 16 bytes
+ * take the wide path.                                                                      */
+int multilevel_proj_stored(int storage, int outer_norm, const void* Y /* device */,
+                           void* X /* device, same size and type */, int ndim,
+                           const long long* dims /* host, ndim */,
+                           const int* norms /* host, ndim-1 */, float eta,
+                           void* workspace /* device */, size_t workspace_bytes,
+                           float* v_out /* device, dims[0]; may be NULL */,
+                           float* u_out /* device, dims[0]; may be NULL */, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -359,3 +359,16 @@ def multilevel(Y, norms, eta, p=1):
             out[idx] = _project_fibre(src[idx], rad[idx], q)
         U[k - 1] = out
     return {"X": U[0].astype(np.float32), "w": w, "u": u, "tau": tau, "V": V, "U": U}
+
+
+def multilevel_stored(Y, norms, eta, storage, p=1):
+    """MP^nu_eta (Def. 5.2, Alg. 6) on a tensor kept in a 16-bit format: the fp32-storage result,
+    with X rounded to the storage format (X32 is the result before that rounding)."""
+    Y = np.asarray(Y)
+    assert Y.dtype == np.float32
+    assert np.array_equal(round_to_storage(Y, storage), Y), "Y must be representable in the storage format"
+    out = dict(multilevel(Y, norms, eta, p=p))
+    out["X32"] = out["X"]
+    out["X"] = round_to_storage(out["X32"], storage)
+    return out
+

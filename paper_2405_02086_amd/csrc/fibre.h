@@ -170,16 +170,20 @@ __global__ __launch_bounds__(WG) void top_radii_kernel(Ws ws, long long d0, doub
   if (u_out) u_out[a] = (float)u;
 }
 
-// fp32 output is the tensor X itself, written once and not read again by the call: streamed
-// past the caches like the bi-level map pass does (dirty lines left behind would be written
-// back under the next kernel's reads).  fp64 output is a level of radii the next kernel reads.
+// Output in the tensor's own element type is X itself, written once and not read again by the
+// call: rounded through fp32 and streamed past the caches like the bi-level map pass does
+// (dirty lines left behind would be written back under the next kernel's reads).  fp64 output
+// is a level of radii the next kernel reads.
 template <typename TOUT, int VEC>
-__device__ __forceinline__ void store_chunk(TOUT* q, const TOUT (&y)[VEC]) {
-  if constexpr (std::is_same<TOUT, float>::value) {
-    store_row_nt<VEC>(q, y);
-  } else {
+__device__ __forceinline__ void store_chunk(TOUT* q, const double (&z)[VEC]) {
+  if constexpr (std::is_same<TOUT, double>::value) {
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) q[k] = y[k];
+    for (int k = 0; k < VEC; ++k) q[k] = z[k];
+  } else {
+    float f[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) f[k] = (float)z[k];
+    store_row_nt<VEC>(q, f);
   }
 }
 
@@ -266,10 +270,10 @@ __global__ __launch_bounds__(WG) void fibre_map_kernel(const TIN* A, long long n
 #pragma unroll
       for (int k = 0; k < MAP_CHUNKS; ++k) {
         const long long ik = i + (long long)k * SEG;
-        TOUT y[VEC];
+        double z[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) y[e] = (TOUT)map_one<Q>((double)x[k].e[e], r, par);
-        if (live && ik < nvec) store_chunk<TOUT, VEC>(q + ik * VEC, y);
+        for (int e = 0; e < VEC; ++e) z[e] = map_one<Q>((double)x[k].e[e], r, par);
+        if (live && ik < nvec) store_chunk<TOUT, VEC>(q + ik * VEC, z);
       }
     }
   }
@@ -367,10 +371,10 @@ __global__ __launch_bounds__(WG) void fibre_map_cached_kernel(const TIN* A, long
 #pragma unroll
       for (int k = 0; k < KREG; ++k) {
         const long long i = sl + (long long)k * SEG;
-        TOUT y[VEC];
+        double z[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) y[e] = (TOUT)map_one<Q>(x[u][k][e], r[u], par[u]);
-        if (live[u] && i < nvec) store_chunk<TOUT, VEC>(out + f[u] * len + i * VEC, y);
+        for (int e = 0; e < VEC; ++e) z[e] = map_one<Q>(x[u][k][e], r[u], par[u]);
+        if (live[u] && i < nvec) store_chunk<TOUT, VEC>(out + f[u] * len + i * VEC, z);
       }
     }
   }

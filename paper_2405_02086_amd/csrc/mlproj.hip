@@ -523,9 +523,11 @@ static int ml_workspace_bytes(int ndim, const long long* dims, size_t* out) {
   return MLPROJ_OK;
 }
 
-static int run_multilevel(int outer, const float* Y, float* X, int ndim, const long long* dims_in,
+template <typename T>
+static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long* dims_in,
                           const int* norms_in, float eta, void* workspace, size_t workspace_bytes,
                           float* v_out, float* u_out, void* stream_) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
   if (!Y || !X || !workspace) return MLPROJ_ERR_NULL_POINTER;
   if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
   MlPlan P;
@@ -557,14 +559,14 @@ static int run_multilevel(int outer, const float* Y, float* X, int ndim, const l
   int norms_inner_first[ML_MAX_DIMS];
   for (int axis = 1; axis < nd; ++axis) norms_inner_first[nd - 1 - axis] = norms[axis];
   if (nd == 2 && norms_inner_first[0] == MLPROJ_NORM_INF && outer == MLPROJ_OUTER_L1)
-    return run_trilevel<float>(Y, X, dims[0], dims[1], 1, eta, workspace, workspace_bytes, v_out, u_out,
-                               nullptr, stream_);
+    return run_trilevel<T>(Y, X, dims[0], dims[1], 1, eta, workspace, workspace_bytes, v_out, u_out,
+                           nullptr, stream_);
   ndim = nd;
   const int* norms_use = norms_inner_first;
   st = ml_plan(ndim, dims, norms_use, &P);
   if (st != MLPROJ_OK) return st;
   if ((st = check_radius(eta)) != MLPROJ_OK) return st;
-  if (!aligned(Y, 4) || !aligned(X, 4)) return MLPROJ_ERR_ALIGNMENT;
+  if (!aligned(Y, sizeof(T)) || !aligned(X, sizeof(T))) return MLPROJ_ERR_ALIGNMENT;
   if (workspace_bytes < P.bytes) return MLPROJ_ERR_WORKSPACE;
   const Ws ws = bind(workspace, P.base);
   char* base = static_cast<char*>(workspace);
@@ -577,14 +579,14 @@ static int run_multilevel(int outer, const float* Y, float* X, int ndim, const l
   V[ndim - 1] = ws.v;  // the top aggregate is the vector the search reads
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const long long len1 = P.len[1];
-  const bool vec4 = len1 % 4 == 0 && aligned(Y, 16) && aligned(X, 16);
+  const bool wide = len1 % WIDE == 0 && aligned(Y, 16) && aligned(X, 16);
 
   // up: aggregate level by level
   mark(stream);
   by_norm(norms_use[0], [&](auto q) {
     float* vo = ndim == 2 ? v_out : nullptr;
-    if (vec4) launch_fibre_agg<decltype(q)::value, float, 4>(Y, P.size[1], len1, V[1], vo, stream);
-    else launch_fibre_agg<decltype(q)::value, float, 1>(Y, P.size[1], len1, V[1], vo, stream);
+    if (wide) launch_fibre_agg<decltype(q)::value, T, WIDE>(Y, P.size[1], len1, V[1], vo, stream);
+    else launch_fibre_agg<decltype(q)::value, T, 1>(Y, P.size[1], len1, V[1], vo, stream);
   });
   for (int k = 2; k < ndim; ++k) {
     by_norm(norms_use[k - 1], [&](auto q) {
@@ -612,8 +614,8 @@ static int run_multilevel(int outer, const float* Y, float* X, int ndim, const l
     });
   }
   by_norm(norms_use[0], [&](auto q) {
-    if (vec4) launch_fibre_map<decltype(q)::value, float, float, 4>(Y, P.size[1], len1, R[1], V[1], X, stream);
-    else launch_fibre_map<decltype(q)::value, float, float, 1>(Y, P.size[1], len1, R[1], V[1], X, stream);
+    if (wide) launch_fibre_map<decltype(q)::value, T, T, WIDE>(Y, P.size[1], len1, R[1], V[1], X, stream);
+    else launch_fibre_map<decltype(q)::value, T, T, 1>(Y, P.size[1], len1, R[1], V[1], X, stream);
   });
   mark(stream);
   return launch_status();
@@ -626,7 +628,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 342; }
+int mlproj_version(void) { return 343; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -775,6 +777,20 @@ int trilevel_proj_stored(int storage, const void* Y, void* X, long long d0, long
       return run_trilevel<bf16_t>(static_cast<const bf16_t*>(Y), static_cast<bf16_t*>(X), d0, d1, d2, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
     case MLPROJ_STORE_F16:
       return run_trilevel<f16_t>(static_cast<const f16_t*>(Y), static_cast<f16_t*>(X), d0, d1, d2, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    default: return MLPROJ_ERR_BAD_VARIANT;
+  }
+}
+
+int multilevel_proj_stored(int storage, int outer_norm, const void* Y, void* X, int ndim,
+                           const long long* dims, const int* norms, float eta, void* workspace,
+                           size_t workspace_bytes, float* v_out, float* u_out, void* stream) {
+  switch (storage) {
+    case MLPROJ_STORE_F32:
+      return run_multilevel<float>(outer_norm, static_cast<const float*>(Y), static_cast<float*>(X), ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream);
+    case MLPROJ_STORE_BF16:
+      return run_multilevel<bf16_t>(outer_norm, static_cast<const bf16_t*>(Y), static_cast<bf16_t*>(X), ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream);
+    case MLPROJ_STORE_F16:
+      return run_multilevel<f16_t>(outer_norm, static_cast<const f16_t*>(Y), static_cast<f16_t*>(X), ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream);
     default: return MLPROJ_ERR_BAD_VARIANT;
   }
 }

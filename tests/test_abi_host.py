@@ -221,6 +221,24 @@ def test_stored_trilevel_argument_checks(lib):
         assert tri(storage, ctypes.c_void_p((1 << 20) + 1), FAKE, 2, 2, 2, F(1), FAKE, big, None, None, None, None) == -7
 
 
+def test_stored_multilevel_argument_checks(lib):
+    big = 1 << 30
+    ml = lib.multilevel_proj_stored
+    dims = (ctypes.c_longlong * 3)(4, 5, 6)
+    bad_dims = (ctypes.c_longlong * 3)(4, 0, 6)
+    norms = (ctypes.c_int * 2)(0, 1)
+    bad_norms = (ctypes.c_int * 2)(0, 7)
+    assert ml(5, 0, FAKE, FAKE, 3, dims, norms, F(1), FAKE, big, None, None, None) == -6
+    for storage in (0, 1, 2):
+        assert ml(storage, 9, FAKE, FAKE, 3, dims, norms, F(1), FAKE, big, None, None, None) == -6
+        assert ml(storage, 0, None, FAKE, 3, dims, norms, F(1), FAKE, big, None, None, None) == -1
+        assert ml(storage, 0, FAKE, FAKE, 3, bad_dims, norms, F(1), FAKE, big, None, None, None) == -2
+        assert ml(storage, 0, FAKE, FAKE, 3, dims, bad_norms, F(1), FAKE, big, None, None, None) == -6
+        assert ml(storage, 0, FAKE, FAKE, 3, dims, norms, F(-1), FAKE, big, None, None, None) == -4
+        assert ml(storage, 0, FAKE, FAKE, 3, dims, norms, F(1), FAKE, 16, None, None, None) == -5
+        assert ml(storage, 0, ctypes.c_void_p((1 << 20) + 1), FAKE, 3, dims, norms, F(1), FAKE, big, None, None, None) == -7
+
+
 def test_l11_sweep_knob(lib):
     """A plain process-wide integer: 0..16 accepted, the old value comes back, nothing else changes it."""
     assert lib.mlproj_set_l11_sweeps(3) == 0

@@ -923,3 +923,57 @@ def test_trilevel_stored_matches_oracle(mp, storage, shape):
         assert np.all((got >= lo) & (got <= hi))
         if storage == "f32":
             assert torch.equal(X, mp.trilevel_proj_l1infinf(Yd, eta))
+
+
+# ------------------------------------------------------------------ multi-level on 16-bit storage
+ML_STORED_CASES = [
+    ((5, 7), [1]), ((300, 33), [2]), ((6, 1032), [1]), ((4, 3, 5), [1, 1]), ((9, 16, 8), ["inf", 1]),
+    ((7, 5, 64), [1, "inf"]), ((3, 40, 264), [1, 1]), ((3, 40, 264), [2, 1]), ((5, 4, 3, 16), [1, 1, 1]),
+    ((5, 4, 3, 6), ["inf", 2, 1]), ((40, 24, 40), ["inf", "inf"]), ((3, 1, 2000), [2, 2]), ((2, 2, 5000), [1, 2]),
+]
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape,norms", ML_STORED_CASES)
+def test_multilevel_stored_matches_oracle(mp, storage, shape, norms):
+    """Wide (last axis a multiple of 16 bytes) and element-wise paths, short and long fibres."""
+    dev = torch.device("cuda:0")
+    dt = getattr(torch, STORE_DTYPES[storage])
+    rng = np.random.default_rng(list(shape) + [len(norms), 5])
+    Y = orc.round_to_storage(rng.standard_normal(shape).astype(np.float32), storage)
+    nrm = nested_norm(Y, norms)
+    for frac, p in ((0.05, 1), (0.5, 1), (1.5, 1), (0.4, 2), (0.4, "inf")):
+        w = orc.multilevel(Y, norms, 1e30)["w"]
+        norm_p = nrm if p == 1 else (float(np.sqrt((w * w).sum())) if p == 2 else float(w.max()))
+        eta = float(np.float32(frac * norm_p))
+        Yd = torch.from_numpy(Y).to(dev).to(dt)
+        assert np.array_equal(Yd.float().cpu().numpy(), Y)
+        v = torch.full((shape[0],), -1.0, device=dev)
+        u = torch.full((shape[0],), -1.0, device=dev)
+        ws = mp.Workspace(mp.multilevel_workspace_bytes(shape), device=dev)
+        X = mp.multilevel_proj_stored(Yd, norms, eta, p=p, workspace=ws, v_out=v, u_out=u)
+        torch.cuda.synchronize()
+        ref = orc.multilevel_stored(Y, norms, eta, storage, p=p)
+        np.testing.assert_allclose(v.cpu().numpy(), ref["w"].astype(np.float32), rtol=2e-7)
+        np.testing.assert_allclose(u.cpu().numpy(), ref["u"].astype(np.float32), rtol=RTOL, atol=ATOL)
+        x = ref["X32"].astype(np.float64)
+        tol = RTOL * np.abs(x) + ATOL
+        lo = orc.round_to_storage((x - tol).astype(np.float32), storage)
+        hi = orc.round_to_storage((x + tol).astype(np.float32), storage)
+        got = X.float().cpu().numpy()
+        assert np.all((got >= lo) & (got <= hi))
+        if storage != "f32":
+            assert np.mean(got != ref["X"]) < 0.02
+        # in place gives the same bits
+        Xi = mp.multilevel_proj_stored(Yd, norms, eta, p=p, X=Yd, workspace=ws)
+        assert torch.equal(Xi, X)
+
+
+def test_multilevel_stored_f32_is_the_fp32_entry_point_bit_for_bit(mp):
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(77)
+    Y = torch.from_numpy(rng.standard_normal((12, 20, 36)).astype(np.float32)).to(dev)
+    for norms in ([1, 1], [2, "inf"], ["inf", "inf"]):
+        eta = float(np.float32(0.3 * nested_norm(Y.cpu().numpy(), norms)))
+        assert torch.equal(mp.multilevel_proj(Y, norms, eta), mp.multilevel_proj_stored(Y, norms, eta))
+

@@ -514,3 +514,21 @@ def test_trilevel_stored_is_the_fp32_result_rounded(storage):
     inside = np.abs(Y) <= np.asarray(ref["u"], dtype=np.float32)[:, None, None]
     assert np.array_equal(out["X"][inside], Y[inside])
     assert np.array_equal(np.abs(out["X"])[~inside], np.broadcast_to(ur[:, None, None], Y.shape)[~inside])
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16"])
+@pytest.mark.parametrize("norms", [[1, 1], [2, "inf"], ["inf", 1], [2]])
+def test_multilevel_stored_is_the_fp32_result_rounded(storage, norms):
+    """Storage only: the stored result is the fp32 result rounded once; entries the projection
+    leaves alone come back exactly, and so does everything when the radius covers the norm."""
+    shape = (5, 4, 8)[: len(norms) + 1]
+    Y = orc.round_to_storage(RNG.standard_normal(shape).astype(np.float32), storage)
+    ref_in = orc.multilevel(Y, norms, 1e9)
+    assert np.array_equal(orc.multilevel_stored(Y, norms, 1e9, storage)["X"], Y) and ref_in["tau"] == 0.0
+    eta = 0.3 * float(np.sum(ref_in["w"]))
+    out = orc.multilevel_stored(Y, norms, eta, storage)
+    ref = orc.multilevel(Y, norms, eta)
+    assert np.array_equal(out["X32"], ref["X"])
+    assert np.array_equal(out["X"], orc.round_to_storage(ref["X"], storage))
+    assert np.all(np.abs(out["X"]) <= np.abs(Y)) and np.all(out["X"] * Y >= 0)   # rounding is monotone and odd
+
