@@ -194,17 +194,45 @@ __device__ __forceinline__ double map_one(double x, double r, double par) {
   else return copysign(fmax(fabs(x) - par, 0.0), x);
 }
 
+// The map of the top level can find the outer threshold itself: with TOP every workgroup runs
+// the search over the nf aggregates redundantly (see search_block; same bits everywhere),
+// takes its fibres' radii from it instead of from R, and workgroup 0 files the result record
+// and the radii u.  That takes the one-workgroup search kernel and its launch off the path.
+struct TopFuse {
+  Ws ws;          // ws.v = the top aggregate (the same array as Vn)
+  double eta;
+  int outer;
+  float* u_out;   // may be NULL
+};
+
+template <bool TOP>
+__device__ __forceinline__ Top top_prologue(const TopFuse& tf, long long nf) {
+  Top top{0.0, 1.0, HUGE_VAL};
+  if constexpr (TOP) {
+    __shared__ PairScratch<WAVES> bs;
+    const SearchOut o = search_block<WG, SEARCH_CACHE>(tf.ws.v, nf, tf.eta, MODE_PROJECT, tf.outer, bs);
+    top = top_of(o);
+    if (blockIdx.x == 0 && threadIdx.x == 0) write_result(tf.ws, o, nullptr);
+    if (tf.u_out)
+      for (long long a = (long long)blockIdx.x * WG + threadIdx.x; a < nf; a += (long long)gridDim.x * WG)
+        tf.u_out[a] = (float)radius(tf.ws.v[a], top);
+  }
+  return top;
+}
+
 // out fibre f = P^q_{R[f]}(fibre f of A), where Vn[f] is that fibre's own q-norm (known from
 // the aggregation): clip (q = inf), rescale by R/Vn (q = 2), or shrink by the fibre's own
 // threshold (q = 1), which the segment finds with the same Newton iteration as everywhere
 // else, re-reading its fibre from cache on every step.  MAP_CHUNKS chunks per lane and trip.
 constexpr int MAP_CHUNKS = 4;
 
-template <int Q, typename TIN, typename TOUT, int SEG, int VEC>
+template <int Q, typename TIN, typename TOUT, int SEG, int VEC, bool TOP = false>
 __global__ __launch_bounds__(WG) void fibre_map_kernel(const TIN* A, long long nf, long long len,
                                                        const double* __restrict__ R,
-                                                       const double* __restrict__ Vn, TOUT* out) {
+                                                       const double* __restrict__ Vn, TOUT* out,
+                                                       TopFuse tf) {
   constexpr int PER_WAVE = WAVE / SEG;
+  const Top top = top_prologue<TOP>(tf, nf);
   const int lane = threadIdx.x & (WAVE - 1);
   const int sl = lane % SEG;
   const long long nvec = len / VEC;
@@ -214,8 +242,8 @@ __global__ __launch_bounds__(WG) void fibre_map_kernel(const TIN* A, long long n
   for (long long f0 = wave_id * PER_WAVE + lane / SEG; f0 - lane / SEG < nf; f0 += step) {
     const bool live = f0 < nf;
     const long long f = live ? f0 : nf - 1;  // idle segments shadow the last fibre, stores off
-    const double r = R[f];
     const double nv = Vn[f];
+    const double r = TOP ? radius(nv, top) : R[f];
     const TIN* p = A + f * len;
     TOUT* q = out + f * len;
     double par = 0.0;  // q = 2: scale; q = 1: threshold
@@ -283,13 +311,14 @@ __global__ __launch_bounds__(WG) void fibre_map_kernel(const TIN* A, long long n
 // per lane): each segment loads FIB_MAP_UNROLL fibres once, searches in registers, and stores.
 constexpr int FIB_MAP_UNROLL = 2;
 
-template <int Q, typename TIN, typename TOUT, int SEG, int VEC, int KREG>
+template <int Q, typename TIN, typename TOUT, int SEG, int VEC, int KREG, bool TOP = false>
 __global__ __launch_bounds__(WG) void fibre_map_cached_kernel(const TIN* A, long long nf,
                                                               long long len,
                                                               const double* __restrict__ R,
                                                               const double* __restrict__ Vn,
-                                                              TOUT* out) {
+                                                              TOUT* out, TopFuse tf) {
   constexpr int PER_WAVE = WAVE / SEG;
+  const Top top = top_prologue<TOP>(tf, nf);
   constexpr int UF = FIB_MAP_UNROLL;
   const int lane = threadIdx.x & (WAVE - 1);
   const int sl = lane % SEG;
@@ -312,8 +341,8 @@ __global__ __launch_bounds__(WG) void fibre_map_cached_kernel(const TIN* A, long
         const long long i = sl + (long long)k * SEG;
         raw[u][k] = load_chunk<TIN, VEC>(A + f[u] * len + (i < nvec ? i : nvec - 1) * VEC);
       }
-      r[u] = R[f[u]];
       nv[u] = Vn[f[u]];
+      r[u] = TOP ? radius(nv[u], top) : R[f[u]];
     }
     __builtin_amdgcn_sched_barrier(0);
     double x[UF][KREG][VEC];

@@ -478,9 +478,10 @@ static void launch_fibre_agg(const TIN* A, long long nf, long long len, double* 
   else hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 64, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
 }
 
-template <int Q, typename TIN, typename TOUT, int VEC>
+template <int Q, typename TIN, typename TOUT, int VEC, bool TOP = false>
 static void launch_fibre_map(const TIN* A, long long nf, long long len, const double* R,
-                             const double* Vn, TOUT* out, hipStream_t stream) {
+                             const double* Vn, TOUT* out, hipStream_t stream,
+                             const TopFuse& tf = TopFuse{}) {
   const long long nvec = len / VEC;
   const int seg = seg_for(nvec);
   if (nvec <= (long long)seg * 4) {
@@ -488,8 +489,8 @@ static void launch_fibre_map(const TIN* A, long long nf, long long len, const do
     const dim3 cgrid(fibre_grid(nf, seg, FIB_MAP_UNROLL)), cblock(WG);
     const int kreg = nvec <= seg ? 1 : (nvec <= 2LL * seg ? 2 : 4);
 #define MLPROJ_LAUNCH_CACHED(SEG_, K_)                                                              \
-  hipLaunchKernelGGL((fibre_map_cached_kernel<Q, TIN, TOUT, SEG_, VEC, K_>), cgrid, cblock, 0, stream, \
-                     A, nf, len, R, Vn, out)
+  hipLaunchKernelGGL((fibre_map_cached_kernel<Q, TIN, TOUT, SEG_, VEC, K_, TOP>), cgrid, cblock, 0, stream, \
+                     A, nf, len, R, Vn, out, tf)
     if (seg == 4) { if (kreg == 1) MLPROJ_LAUNCH_CACHED(4, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(4, 2); else MLPROJ_LAUNCH_CACHED(4, 4); }
     else if (seg == 16) { if (kreg == 1) MLPROJ_LAUNCH_CACHED(16, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(16, 2); else MLPROJ_LAUNCH_CACHED(16, 4); }
     else { if (kreg == 1) MLPROJ_LAUNCH_CACHED(64, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(64, 2); else MLPROJ_LAUNCH_CACHED(64, 4); }
@@ -497,9 +498,9 @@ static void launch_fibre_map(const TIN* A, long long nf, long long len, const do
     return;
   }
   const dim3 grid(fibre_grid(nf, seg, 1)), block(WG);
-  if (seg == 4) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 4, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
-  else if (seg == 16) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 16, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
-  else hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 64, VEC>), grid, block, 0, stream, A, nf, len, R, Vn, out);
+  if (seg == 4) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 4, VEC, TOP>), grid, block, 0, stream, A, nf, len, R, Vn, out, tf);
+  else if (seg == 16) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 16, VEC, TOP>), grid, block, 0, stream, A, nf, len, R, Vn, out, tf);
+  else hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 64, VEC, TOP>), grid, block, 0, stream, A, nf, len, R, Vn, out, tf);
 }
 
 template <typename F>
@@ -594,9 +595,13 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
                                                       k == ndim - 1 ? v_out : nullptr, stream);
     });
   }
-  // top: threshold of the l1-ball projection of the length-d0 vector, then its radii
-  mark(stream);
-  if (dims[0] <= (long long)SWG * SEARCH_CACHE || outer != MLPROJ_OUTER_L1) {
+  // top: threshold of the l1-ball projection of the length-d0 vector, then its radii.  With
+  // three or more axes and at most 4096 groups the map of the top level does this itself.
+  const bool fuse_top = ndim >= 3 && dims[0] <= FUSED_SEARCH_MAX;
+  if (!fuse_top) mark(stream);
+  if (fuse_top) {
+    // nothing here: see the first map below
+  } else if (dims[0] <= (long long)SWG * SEARCH_CACHE || outer != MLPROJ_OUTER_L1) {
     hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
                        outer, (double*)nullptr, 0, R[ndim - 1], u_out);
   } else {
@@ -609,8 +614,13 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
   mark(stream);
   for (int k = ndim - 1; k >= 2; --k) {
     by_norm(norms_use[k - 1], [&](auto q) {
-      launch_fibre_map<decltype(q)::value, double, double, 1>(V[k - 1], P.size[k], P.len[k], R[k], V[k],
-                                                              R[k - 1], stream);
+      if (fuse_top && k == ndim - 1)
+        launch_fibre_map<decltype(q)::value, double, double, 1, true>(V[k - 1], P.size[k], P.len[k], R[k], V[k],
+                                                                      R[k - 1], stream,
+                                                                      TopFuse{ws, (double)eta, outer, u_out});
+      else
+        launch_fibre_map<decltype(q)::value, double, double, 1>(V[k - 1], P.size[k], P.len[k], R[k], V[k],
+                                                                R[k - 1], stream);
     });
   }
   by_norm(norms_use[0], [&](auto q) {
