@@ -122,7 +122,7 @@ int mlproj_trace_end(void);
 
 /* Tuning knob for MLPROJ_L11 (Alg. 3): how many lock-step passes over Y a call enqueues for
  * the per-column threshold searches before the column-wise finishing pass closes whatever is
- * still open.  1..16, or 0 for the default, which grows with the number of rows (1 up to 512
+ * still open.  1..16, or 0 for the default, which grows with the number of rows (none up to 1024
  * rows, 3 at 4096, 6 at 16384, 12 beyond 131072): the finishing pass costs more per column
  * the taller the matrix.  The thresholds are exact for any value; only the time changes.
  * Process-wide and read when a call is enqueued: set it while no other thread is calling.

@@ -108,11 +108,14 @@ __global__ __launch_bounds__(WG) void l11_init_batch_kernel(BatchItems it, Batch
 }
 
 template <typename T>
-__global__ __launch_bounds__(WG) void l11_sweep_batch_kernel(BatchItems it, BatchGrid gr) {
+__global__ __launch_bounds__(WG) void l11_sweep_batch_kernel(BatchItems it, BatchGrid gr,
+                                                             BatchL11Plan plan) {
   constexpr int WIDE = 16 / (int)sizeof(T);
   __shared__ SweepLds<WAVE * WIDE> lds;
   long long bid;
-  const BatchItem& b = it.item[batch_find(gr, it.count, bid)];
+  const int p = batch_find(gr, it.count, bid);
+  if (plan.sweeps[p] < 1) return;
+  const BatchItem& b = it.item[p];
   const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
   const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
   const T* Y = static_cast<const T*>(b.Y);
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(WG) void l11_update_batch_kernel(BatchItems it, Bat
 }
 
 template <typename T>
-__global__ __launch_bounds__(SWG) void l11_finish_batch_kernel(BatchItems it, BatchGrid gr,
+__global__ __launch_bounds__(FIN_WG) void l11_finish_batch_kernel(BatchItems it, BatchGrid gr,
                                                                BatchL11Plan plan) {
   constexpr int WIDE = 16 / (int)sizeof(T);
   long long bid;

@@ -566,15 +566,18 @@ __global__ __launch_bounds__(WG) void l11_update_kernel(long long n, long long m
 // iteration rises monotonically and the active count only shrinks, so it ends after at most n
 // steps (in practice a handful: the bound is already tight) at the exact root, in fp64.
 // A workgroup owns FIN_COLS = 16 neighbouring columns (one 64-byte run of every row) and
-// leaves at once when none of them is open; thread (r, c) reads rows r, r + 64, ... of column
-// c, the four lanes of a wavefront that share a column add up on the crossbar, the sixteen
+// leaves at once when none of them is open; thread (r, c) reads rows r, r + 32, ... of column
+// c, the four lanes of a wavefront that share a column add up on the crossbar, the eight
 // wavefronts through LDS in a fixed order.  The columns are strided in memory, so this pass
 // moves 64 bytes for every 4 it needs from a lone open column: good for stragglers, and no
 // worse than a sweep when many neighbouring columns are open.  It replaces a long tail of
 // lock-step launches that found nothing to do.
 constexpr int FIN_COLS = 16;
-constexpr int FIN_ROWS = SWG / FIN_COLS;   // rows one trip of the workgroup covers
-constexpr int FIN_UNROLL = 8;              // loads in flight per thread
+constexpr int FIN_WG = 512;                // threads: four workgroups fit a CU, so 1024 are resident at once
+constexpr int FIN_WAVES = FIN_WG / WAVE;
+constexpr int FIN_ROWS = FIN_WG / FIN_COLS;  // rows one trip of the workgroup covers
+constexpr int FIN_UNROLL = 16;             // loads in flight per thread
+constexpr int FIN_HELD = 32;               // rows per thread a short matrix keeps in registers
 
 static_assert(FIN_COLS == UPD_COLS, "a batch launches both kernels on the same grid");
 
@@ -582,13 +585,15 @@ template <typename T>
 __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long long n, long long m,
                                                 const Ws& ws, int sweeps, unsigned handoff,
                                                 long long bid) {
-  __shared__ double sm_s[SWAVES][FIN_COLS];
-  __shared__ unsigned sm_k[SWAVES][FIN_COLS];
+  __shared__ double sm_s[FIN_WAVES][FIN_COLS];
+  __shared__ unsigned sm_k[FIN_WAVES][FIN_COLS];
   mlproj_result* res = ws.res;
   if (res->inside_ball != 0u || res->n_active == 0u) return;
+  // (no sweep at all, as planned for very short matrices: every kept column is open, with the
+  // all-active bound of the seeding kernel to start from)
   int stop = 1;   // the sweep at which the lock-step kernels stopped (see `handoff` there)
   while (stop < sweeps && ws.pending[stop] > handoff) ++stop;
-  const unsigned left = ws.pending[stop];
+  const unsigned left = sweeps > 0 ? ws.pending[stop] : res->n_active;
   if (bid == 0 && threadIdx.x == 0) res->inner_finished = left;
   if (left == 0u) return;
 
@@ -603,9 +608,32 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
   if (!__syncthreads_or(open ? 1 : 0)) return;
 
   const double uj = radius(ws.v[jj], top_of(res));
-  double t = ws.lb[jj];
+  // Start: the certified lower bound the sweeps reached.  Without any sweep the first point is
+  // the seeding kernel's guess instead: the fixed-point step from ANY point lands at or left of
+  // the root (see the note at the top), so one evaluation there gives a far better lower bound
+  // than the all-active one, and the iteration is monotone from then on.
+  const double lb = ws.lb[jj];
+  bool first = sweeps == 0;
+  double t = first ? ws.tauj[jj] : lb;
   unsigned kprev = NO_COUNT;
   const T* col = Y + jj;
+  // A short matrix (at most FIN_HELD rows per thread) is read once and iterated in registers.
+  const bool in_regs = n <= (long long)FIN_ROWS * FIN_HELD;
+  float held[FIN_HELD];
+#pragma unroll
+  for (int u = 0; u < FIN_HELD; ++u) held[u] = 0.0f;
+  if (in_regs) {
+    T x[FIN_HELD];
+#pragma unroll
+    for (int u = 0; u < FIN_HELD; ++u) {
+      const long long row = r + (long long)u * FIN_ROWS;
+      x[u] = col[(row < n ? row : n - 1) * m];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < FIN_HELD; ++u)
+      held[u] = r + (long long)u * FIN_ROWS < n ? fabsf((float)x[u]) : 0.0f;   // 0 is never above a threshold
+  }
   for (;;) {
     const float ct = above(t);
     double s = 0.0;
@@ -616,16 +644,25 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
       s += (double)(in ? a : 0.0f);
       k += in ? 1u : 0u;
     };
-    long long i = r;
-    for (; i + (long long)(FIN_UNROLL - 1) * FIN_ROWS < n; i += (long long)FIN_UNROLL * FIN_ROWS) {
-      T x[FIN_UNROLL];
+    if (in_regs) {
 #pragma unroll
-      for (int u = 0; u < FIN_UNROLL; ++u) x[u] = col[(i + (long long)u * FIN_ROWS) * m];
-      __builtin_amdgcn_sched_barrier(0);
+      for (int u = 0; u < FIN_HELD; ++u) {
+        const bool in = held[u] >= ct;
+        s += (double)(in ? held[u] : 0.0f);
+        k += in ? 1u : 0u;
+      }
+    } else {
+      long long i = r;
+      for (; i + (long long)(FIN_UNROLL - 1) * FIN_ROWS < n; i += (long long)FIN_UNROLL * FIN_ROWS) {
+        T x[FIN_UNROLL];
 #pragma unroll
-      for (int u = 0; u < FIN_UNROLL; ++u) visit(x[u]);
+        for (int u = 0; u < FIN_UNROLL; ++u) x[u] = col[(i + (long long)u * FIN_ROWS) * m];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < FIN_UNROLL; ++u) visit(x[u]);
+      }
+      for (; i < n; i += FIN_ROWS) visit(col[i * m]);
     }
-    for (; i < n; i += FIN_ROWS) visit(col[i * m]);
     // lanes c, c + 16, c + 32, c + 48 of a wavefront share the column
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
@@ -639,12 +676,17 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
     double S = sm_s[0][c];
     unsigned K = sm_k[0][c];
 #pragma unroll
-    for (int w = 1; w < SWAVES; ++w) {
+    for (int w = 1; w < FIN_WAVES; ++w) {
       S += sm_s[w][c];
       K += sm_k[w][c];
     }
     if (open) {
-      if (K == 0u || K == kprev) {
+      if (first) {
+        // from the guess: step to its fixed-point image, or back to the bound if it overshot
+        // every entry.  An equal count at the next point still means an equal active set.
+        kprev = K > 0u ? K : NO_COUNT;
+        t = K > 0u ? fmax((S - uj) / (double)K, lb) : lb;
+      } else if (K == 0u || K == kprev) {
         open = false;   // t came from this very active set: it is the root
       } else {
         kprev = K;
@@ -653,6 +695,7 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
         else open = false;   // no move left: t is the root, to rounding
       }
     }
+    first = false;
     if (!__syncthreads_or(open ? 1 : 0)) break;   // (also keeps the LDS rows until all have read them)
   }
   if (r == 0 && mine) {
@@ -662,7 +705,7 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
 }
 
 template <typename T>
-__global__ __launch_bounds__(SWG) void l11_finish_kernel(const T* __restrict__ Y, long long n,
+__global__ __launch_bounds__(FIN_WG) void l11_finish_kernel(const T* __restrict__ Y, long long n,
                                                          long long m, Ws ws, int sweeps,
                                                          unsigned handoff) {
   l11_finish_body<T>(Y, n, m, ws, sweeps, handoff, blockIdx.x);

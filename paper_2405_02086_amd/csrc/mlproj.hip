@@ -127,8 +127,8 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
 // MI355X: a sweep that finds nothing to do costs two launches (3.6 us); one iteration of the
 // finishing pass costs about n/512 us for up to 512 groups of 16 columns, and it needs about
 // four from the bounds the sweeps leave; two sweeps close every column on Gaussian data,
-// heavy tails take up to ten.  So short matrices get few sweeps (finishing is cheap), tall
-// ones more, and where a sweep is dearer than finishing a few hundred stragglers the sweeps
+// heavy tails take up to ten.  So short matrices get few sweeps (finishing is cheap; up to
+// 1024 rows it holds the columns in registers and needs no sweep at all), tall ones more, and where a sweep is dearer than finishing a few hundred stragglers the sweeps
 // stop as soon as no more than that are open.
 static int g_l11_sweeps = 0;  // 0 = automatic
 static void plan_l11(long long n, long long m, int elem_bytes, int* sweeps, unsigned* handoff) {
@@ -136,7 +136,7 @@ static void plan_l11(long long n, long long m, int elem_bytes, int* sweeps, unsi
   const double finish_us = 4.0 * (double)n / 512.0;
   *handoff = sweep_us > finish_us ? 512u : 0u;
   if (g_l11_sweeps > 0) { *sweeps = g_l11_sweeps; return; }
-  *sweeps = n <= 512 ? 1 : n <= 2048 ? 2 : n <= 4096 ? 3 : n <= 8192 ? 4 : n <= 32768 ? 6
+  *sweeps = n <= 1024 ? 0 : n <= 2048 ? 2 : n <= 4096 ? 3 : n <= 8192 ? 4 : n <= 32768 ? 6
           : n <= 131072 ? 8 : 12;
 }
 
@@ -219,7 +219,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
         }
         hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s, handoff);
       }
-      hipLaunchKernelGGL((l11_finish_kernel<T>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(SWG), 0, stream, Y, n, m, ws, sweeps, handoff);
+      hipLaunchKernelGGL((l11_finish_kernel<T>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(FIN_WG), 0, stream, Y, n, m, ws, sweeps, handoff);
     }
   }
   if (stages & STAGE_APPLY) {
@@ -368,11 +368,11 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
       else hipLaunchKernelGGL((l11_init_batch_kernel<T, SEARCH_CACHE>), dim3(in), dim3(WG), 0, stream, it, ini, outer);
       mark(stream);
       for (int s = 0; s < max_sweeps; ++s) {
-        if (s == 0) hipLaunchKernelGGL((l11_sweep_batch_kernel<T>), dim3(a), dim3(WG), 0, stream, it, agg);
+        if (s == 0) hipLaunchKernelGGL((l11_sweep_batch_kernel<T>), dim3(a), dim3(WG), 0, stream, it, agg, plan);
         else hipLaunchKernelGGL((l11_filter_batch_kernel<T>), dim3(a), dim3(WG), 0, stream, it, agg, plan, s);
         hipLaunchKernelGGL((l11_update_batch_kernel<T>), dim3(up), dim3(WG), 0, stream, it, upd, plan, s);
       }
-      hipLaunchKernelGGL((l11_finish_batch_kernel<T>), dim3(up), dim3(SWG), 0, stream, it, upd, plan);
+      hipLaunchKernelGGL((l11_finish_batch_kernel<T>), dim3(up), dim3(FIN_WG), 0, stream, it, upd, plan);
     }
     mark(stream);
     if (big) hipLaunchKernelGGL((colmap_batch_kernel<Q, T, SEARCH_CACHE_BIG>), dim3(mp), dim3(WG), 0, stream, it, map, outer);
