@@ -847,6 +847,22 @@ def test_l11_finishing_pass_closes_what_the_sweeps_leave(mp, l11_sweeps, family,
         assert finished > 0, "one sweep cannot close Gaussian columns: the finishing pass must have run"
 
 
+@pytest.mark.parametrize("n", [37, 600, 1024, 1025, 2049])
+@pytest.mark.parametrize("family", ["gaussian", "cauchy", "lognormal3", "sparse", "clusters", "constant",
+                                    "integers", "geometric", "uniform"])
+def test_l11_default_plan_on_short_matrices(mp, family, n):
+    """Up to 1024 rows the default plan has no lock-step sweep at all (the finishing pass holds
+    the columns in registers and starts from the seeding guess); just above, two and three."""
+    rng = np.random.default_rng([len(family), 79, n])
+    m = 150
+    Y = (rng.standard_normal((n, m)) if family == "gaussian" else _hard_family(family, rng, n, m)).astype(np.float32)
+    for frac in (0.001, 0.1, 0.5, 0.95):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert got["res"]["inner_sweeps"] <= (0 if n <= 1024 else 2 if n <= 2048 else 3)
+
+
 @pytest.mark.parametrize("name", ["binary", "outlier", "pow2", "two_levels", "two_rows", "denormal", "huge", "ramp",
                                   "mixed_columns"])
 def test_l11_finishing_pass_on_adversarial_columns(mp, l11_sweeps, name):
