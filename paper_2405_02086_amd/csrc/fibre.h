@@ -358,13 +358,23 @@ __global__ __launch_bounds__(WG) void fibre_map_cached_kernel(const TIN* A, long
 #pragma unroll
     for (int u = 0; u < UF; ++u) par[u] = (Q == Q2) ? (nv[u] > r[u] ? r[u] / nv[u] : 1.0) : 0.0;
     if constexpr (Q == Q1) {
-      bool open[UF];
+      // The fixed point of the outer search, per fibre, in registers.  The first point is a
+      // guess, the threshold an exponential tail of the fibre's mean magnitude would have,
+      // shortened a little: the step from any point lands at or left of the root, so its image
+      // (or the all-active bound, if larger) is a lower bound far closer than that bound alone,
+      // and the iteration is monotone from there.  It saves about three rounds in eight.
+      bool open[UF], first[UF];
       unsigned kprev[UF];
+      double floor_t[UF];
       bool any_open = false;
 #pragma unroll
       for (int u = 0; u < UF; ++u) {
         open[u] = nv[u] > r[u];
-        par[u] = open[u] ? (nv[u] - r[u]) / (double)len : 0.0;
+        floor_t[u] = open[u] ? (nv[u] - r[u]) / (double)len : 0.0;
+        const float guess = open[u] && r[u] > 0.0
+            ? -0.75f * (float)(nv[u] / (double)len) * __logf((float)(r[u] / nv[u])) : 0.0f;
+        first[u] = (double)guess > floor_t[u];
+        par[u] = first[u] ? (double)guess : floor_t[u];
         kprev[u] = 0xffffffffu;
         any_open = any_open || open[u];
       }
@@ -384,13 +394,18 @@ __global__ __launch_bounds__(WG) void fibre_map_cached_kernel(const TIN* A, long
           s = seg_sum<SEG>(s);
           c = seg_sum_u<SEG>(c);
           if (open[u]) {
-            if (c == 0u || c == kprev[u]) open[u] = false;
-            else {
+            if (first[u]) {
+              kprev[u] = c > 0u ? c : 0xffffffffu;
+              par[u] = c > 0u ? fmax((s - r[u]) / (double)c, floor_t[u]) : floor_t[u];
+            } else if (c == 0u || c == kprev[u]) {
+              open[u] = false;
+            } else {
               kprev[u] = c;
               const double tn = (s - r[u]) / (double)c;
               if (tn > par[u]) par[u] = tn;
             }
           }
+          first[u] = false;
           any_open = any_open || open[u];
         }
       }
