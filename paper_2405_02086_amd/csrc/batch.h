@@ -161,7 +161,10 @@ __global__ __launch_bounds__(FIN_WG) void l11_finish_batch_kernel(BatchItems it,
   const BatchItem& b = it.item[p];
   const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
   const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
-  l11_finish_body<T>(static_cast<const T*>(b.Y), b.n, b.m, ws, plan.sweeps[p], plan.handoff[p], bid);
+  if (b.n <= (long long)FIN_ROWS * FIN_HELD)
+    l11_finish_body<T, true>(static_cast<const T*>(b.Y), b.n, b.m, ws, plan.sweeps[p], plan.handoff[p], bid);
+  else
+    l11_finish_body<T, false>(static_cast<const T*>(b.Y), b.n, b.m, ws, plan.sweeps[p], plan.handoff[p], bid);
 }
 
 }  // namespace mlproj

@@ -578,10 +578,12 @@ constexpr int FIN_WAVES = FIN_WG / WAVE;
 constexpr int FIN_ROWS = FIN_WG / FIN_COLS;  // rows one trip of the workgroup covers
 constexpr int FIN_UNROLL = 16;             // loads in flight per thread
 constexpr int FIN_HELD = 32;               // rows per thread a short matrix keeps in registers
+static_assert(FIN_HELD % FIN_UNROLL == 0, "the held rows are loaded in batches of FIN_UNROLL");
 
 static_assert(FIN_COLS == UPD_COLS, "a batch launches both kernels on the same grid");
 
-template <typename T>
+// HELD: the short-matrix form (n <= FIN_ROWS * FIN_HELD), which keeps its rows in registers.
+template <typename T, bool HELD>
 __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long long n, long long m,
                                                 const Ws& ws, int sweeps, unsigned handoff,
                                                 long long bid) {
@@ -618,21 +620,24 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
   unsigned kprev = NO_COUNT;
   const T* col = Y + jj;
   // A short matrix (at most FIN_HELD rows per thread) is read once and iterated in registers.
-  const bool in_regs = n <= (long long)FIN_ROWS * FIN_HELD;
-  float held[FIN_HELD];
+  constexpr bool in_regs = HELD;
+  float held[HELD ? FIN_HELD : 1];
+  if constexpr (in_regs) {
+    // (in batches of FIN_UNROLL loads: every load needs its own address registers)
 #pragma unroll
-  for (int u = 0; u < FIN_HELD; ++u) held[u] = 0.0f;
-  if (in_regs) {
-    T x[FIN_HELD];
+    for (int u0 = 0; u0 < FIN_HELD; u0 += FIN_UNROLL) {
+      T x[FIN_UNROLL];
 #pragma unroll
-    for (int u = 0; u < FIN_HELD; ++u) {
-      const long long row = r + (long long)u * FIN_ROWS;
-      x[u] = col[(row < n ? row : n - 1) * m];
+      for (int u = 0; u < FIN_UNROLL; ++u) {
+        const long long row = r + (long long)(u0 + u) * FIN_ROWS;
+        x[u] = col[(row < n ? row : n - 1) * m];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < FIN_UNROLL; ++u)
+        held[u0 + u] = r + (long long)(u0 + u) * FIN_ROWS < n ? fabsf((float)x[u]) : 0.0f;   // 0 is never above a threshold
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < FIN_HELD; ++u)
-      held[u] = r + (long long)u * FIN_ROWS < n ? fabsf((float)x[u]) : 0.0f;   // 0 is never above a threshold
   }
   for (;;) {
     const float ct = above(t);
@@ -644,11 +649,13 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
       s += (double)(in ? a : 0.0f);
       k += in ? 1u : 0u;
     };
-    if (in_regs) {
+    if constexpr (in_regs) {
 #pragma unroll
       for (int u = 0; u < FIN_HELD; ++u) {
-        const bool in = held[u] >= ct;
-        s += (double)(in ? held[u] : 0.0f);
+        float h = held[u];
+        asm volatile("" : "+v"(h));   // keeps the widening to fp64 in the loop: hoisted, it doubles the registers
+        const bool in = h >= ct;
+        s += (double)(in ? h : 0.0f);
         k += in ? 1u : 0u;
       }
     } else {
@@ -704,11 +711,13 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(FIN_WG) void l11_finish_kernel(const T* __restrict__ Y, long long n,
-                                                         long long m, Ws ws, int sweeps,
-                                                         unsigned handoff) {
-  l11_finish_body<T>(Y, n, m, ws, sweeps, handoff, blockIdx.x);
+static inline bool finish_held(long long n) { return n <= (long long)FIN_ROWS * FIN_HELD; }
+
+template <typename T, bool HELD>
+__global__ __launch_bounds__(FIN_WG, HELD ? 4 : 8) void l11_finish_kernel(const T* __restrict__ Y, long long n,
+                                                            long long m, Ws ws, int sweeps,
+                                                            unsigned handoff) {
+  l11_finish_body<T, HELD>(Y, n, m, ws, sweeps, handoff, blockIdx.x);
 }
 
 }  // namespace mlproj

@@ -219,7 +219,10 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
         }
         hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s, handoff);
       }
-      hipLaunchKernelGGL((l11_finish_kernel<T>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(FIN_WG), 0, stream, Y, n, m, ws, sweeps, handoff);
+      if (finish_held(n))
+        hipLaunchKernelGGL((l11_finish_kernel<T, true>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(FIN_WG), 0, stream, Y, n, m, ws, sweeps, handoff);
+      else
+        hipLaunchKernelGGL((l11_finish_kernel<T, false>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(FIN_WG), 0, stream, Y, n, m, ws, sweeps, handoff);
     }
   }
   if (stages & STAGE_APPLY) {
