@@ -357,6 +357,10 @@ def main():
         for eta_abs in (0.25, 1.0, 4.0):
             also["paper_1000x10000/l1inf/eta=%g" % eta_abs] = bench_bilevel(torch, mp, Yp, "l1inf", None, 100, 10,
                                                                          eta_abs=eta_abs)
+        # ... and the other two bi-level variants the paper times on it, at the middle radius
+        for variant in ("l11", "l12"):
+            also["paper_1000x10000/%s/eta=1" % variant] = bench_bilevel(torch, mp, Yp, variant, None, 100, 10,
+                                                                       eta_abs=1.0)
         del Yp
         wt, Yt = workloads.make("tensor_256x256x256")
         for k, v in bench_tensor(torch, mp, Yt, wt.eta_frac, 100, 10).items():

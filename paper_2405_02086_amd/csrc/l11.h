@@ -289,6 +289,22 @@ __global__ __launch_bounds__(WG) void l11_filter_kernel(const T* __restrict__ Y,
 // With fused_eta >= 0 every workgroup first runs the outer threshold search itself (see
 // search_block) and workgroup 0 files the result record and clears the sweep counters, which
 // takes the one-workgroup search kernel off the critical path; otherwise the record is read.
+// The guess for a kept column (see above) and the all-active lower bound.
+__device__ __forceinline__ double l11_guess(double vj, double uj, long long n, double& floor_t) {
+  // (fp32 is plenty here: the guess is a statistical estimate, off by percents)
+  const float c = (float)(uj / vj) * 0.79788456f;  // sqrt(2/pi)
+  float z = 0.0f;
+  for (int it = 0; it < 8; ++it) {
+    const float tail = erfcf(z * 0.70710678f);                  // 2*(1 - Phi(z))
+    const float h = 0.79788456f * expf(-0.5f * z * z) - z * tail;
+    if (!(tail > 1e-30f)) break;
+    z += (h - c) / tail;
+  }
+  const double sigma = (vj / (double)n) * 1.2533141373155001;   // sqrt(pi/2)
+  floor_t = fmax((vj - uj) / (double)n, 0.0);
+  return fmax(sigma * (double)z, floor_t);  // never below the all-active bound
+}
+
 template <int SC>
 __device__ __forceinline__ void l11_init_body(long long n, long long m, const Ws& ws,
                                               double fused_eta, int outer, long long bid) {
@@ -314,20 +330,7 @@ __device__ __forceinline__ void l11_init_body(long long n, long long m, const Ws
   const double vj = ws.v[j];
   const double uj = radius(vj, top);
   double tj = HUGE_VAL, floor_t = HUGE_VAL;
-  if (uj > 0.0) {
-    // (fp32 is plenty here: the guess is a statistical estimate, off by percents)
-    const float c = (float)(uj / vj) * 0.79788456f;  // sqrt(2/pi)
-    float z = 0.0f;
-    for (int it = 0; it < 8; ++it) {
-      const float tail = erfcf(z * 0.70710678f);                  // 2*(1 - Phi(z))
-      const float h = 0.79788456f * expf(-0.5f * z * z) - z * tail;
-      if (!(tail > 1e-30f)) break;
-      z += (h - c) / tail;
-    }
-    const double sigma = (vj / (double)n) * 1.2533141373155001;   // sqrt(pi/2)
-    floor_t = fmax((vj - uj) / (double)n, 0.0);
-    tj = fmax(sigma * (double)z, floor_t);  // never below the all-active bound
-  }
+  if (uj > 0.0) tj = l11_guess(vj, uj, n, floor_t);
   ws.tauj[j] = tj;
   ws.tlo[j] = tj;
   ws.lb[j] = floor_t;
@@ -583,40 +586,66 @@ static_assert(FIN_HELD % FIN_UNROLL == 0, "the held rows are loaded in batches o
 static_assert(FIN_COLS == UPD_COLS, "a batch launches both kernels on the same grid");
 
 // HELD: the short-matrix form (n <= FIN_ROWS * FIN_HELD), which keeps its rows in registers.
-template <typename T, bool HELD>
+// When no sweep ran (sweeps == 0) the pass can also stand in for the seeding kernel: with
+// seed_eta >= 0 every workgroup runs the outer threshold search itself (SC values of v per
+// thread in registers), workgroup 0 files the result record, and the columns' guesses and
+// bounds are computed here instead of read: one launch less.
+template <typename T, bool HELD, int SC = 1>
 __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long long n, long long m,
                                                 const Ws& ws, int sweeps, unsigned handoff,
-                                                long long bid) {
+                                                long long bid, double seed_eta = -1.0,
+                                                int outer = MLPROJ_OUTER_L1) {
   __shared__ double sm_s[FIN_WAVES][FIN_COLS];
   __shared__ unsigned sm_k[FIN_WAVES][FIN_COLS];
+  __shared__ PairScratch<FIN_WAVES> bs;
   mlproj_result* res = ws.res;
-  if (res->inside_ball != 0u || res->n_active == 0u) return;
-  // (no sweep at all, as planned for very short matrices: every kept column is open, with the
-  // all-active bound of the seeding kernel to start from)
-  int stop = 1;   // the sweep at which the lock-step kernels stopped (see `handoff` there)
-  while (stop < sweeps && ws.pending[stop] > handoff) ++stop;
-  const unsigned left = sweeps > 0 ? ws.pending[stop] : res->n_active;
-  if (bid == 0 && threadIdx.x == 0) res->inner_finished = left;
-  if (left == 0u) return;
-
   const int c = threadIdx.x % FIN_COLS;
   const int r = threadIdx.x / FIN_COLS;
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x / WAVE;
   const long long j = bid * FIN_COLS + c;
   const long long jj = j < m ? j : m - 1;   // a column past the end shadows the last one
-  const bool mine = j < m && ws.done[jj] == 0u;
+  const bool seeded = seed_eta >= 0.0;
+  Top top;
+  bool mine;
+  if (seeded) {
+    const SearchOut o = search_block<FIN_WG, SC>(ws.v, m, seed_eta, MODE_PROJECT, outer, bs);
+    top = top_of(o);
+    if (bid == 0 && threadIdx.x == 0) {
+      write_result(ws, o, nullptr);
+      res->inner_finished = (o.inside != 0u) ? 0u : o.active;
+    }
+    if (o.inside != 0u || o.active == 0u) return;
+    mine = j < m && radius(ws.v[jj], top) > 0.0;
+  } else {
+    if (res->inside_ball != 0u || res->n_active == 0u) return;
+    // (no sweep at all, as planned for short matrices: every kept column is open, with the
+    // all-active bound of the seeding kernel to start from)
+    int stop = 1;   // the sweep at which the lock-step kernels stopped (see `handoff` there)
+    while (stop < sweeps && ws.pending[stop] > handoff) ++stop;
+    const unsigned left = sweeps > 0 ? ws.pending[stop] : res->n_active;
+    if (bid == 0 && threadIdx.x == 0) res->inner_finished = left;
+    if (left == 0u) return;
+    top = top_of(res);
+    mine = j < m && ws.done[jj] == 0u;
+  }
   bool open = mine;
   if (!__syncthreads_or(open ? 1 : 0)) return;
 
-  const double uj = radius(ws.v[jj], top_of(res));
+  const double uj = radius(ws.v[jj], top);
   // Start: the certified lower bound the sweeps reached.  Without any sweep the first point is
-  // the seeding kernel's guess instead: the fixed-point step from ANY point lands at or left of
-  // the root (see the note at the top), so one evaluation there gives a far better lower bound
+  // the seeding guess instead: the fixed-point step from ANY point lands at or left of the
+  // root (see the note at the top), so one evaluation there gives a far better lower bound
   // than the all-active one, and the iteration is monotone from then on.
-  const double lb = ws.lb[jj];
+  double lb, t;
   bool first = sweeps == 0;
-  double t = first ? ws.tauj[jj] : lb;
+  if (seeded) {
+    lb = 0.0;
+    t = mine ? l11_guess(ws.v[jj], uj, n, lb) : 0.0;
+  } else {
+    lb = ws.lb[jj];
+    t = first ? ws.tauj[jj] : lb;
+  }
   unsigned kprev = NO_COUNT;
   const T* col = Y + jj;
   // A short matrix (at most FIN_HELD rows per thread) is read once and iterated in registers.
@@ -718,6 +747,17 @@ __global__ __launch_bounds__(FIN_WG, HELD ? 4 : 8) void l11_finish_kernel(const 
                                                             long long m, Ws ws, int sweeps,
                                                             unsigned handoff) {
   l11_finish_body<T, HELD>(Y, n, m, ws, sweeps, handoff, blockIdx.x);
+}
+
+// The seeded form (no sweep, no seeding kernel before it): short matrices of at most 4096
+// columns only.
+constexpr int FIN_SEARCH_CACHE = (int)(FUSED_SEARCH_MAX / FIN_WG);   // up to 4096 columns in registers
+
+template <typename T, int SC>
+__global__ __launch_bounds__(FIN_WG, 4) void l11_finish_seeded_kernel(const T* __restrict__ Y, long long n,
+                                                                      long long m, Ws ws, double eta,
+                                                                      int outer) {
+  l11_finish_body<T, true, SC>(Y, n, m, ws, 0, 0u, blockIdx.x, eta, outer);
 }
 
 }  // namespace mlproj

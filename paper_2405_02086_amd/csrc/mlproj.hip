@@ -197,32 +197,41 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     }
     if (mode == MODE_NORM) { mark(stream); return launch_status(); }
     if constexpr (Q == Q1) {
-      mark(stream);
-      const dim3 igrid((unsigned)cdiv(m, WG));
-      if (!fuse_l11)
-        hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, -1.0, outer);
-      else if (m > FUSED_SEARCH_MAX)
-        hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE_BIG>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
-      else
-        hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
-      if (fuse_l11) mark(stream);   // (keeps one interval for search + seeding, one for the sweeps)
       int sweeps;
       unsigned handoff;
       plan_l11(n, m, (int)sizeof(T), &sweeps, &handoff);
-      for (int s = 0; s < sweeps; ++s) {
-        if (s == 0) {
-          if (wide) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws);
-          else hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws);
-        } else {
-          if (wide) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
-          else hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
+      const dim3 fgrid((unsigned)cdiv(m, FIN_COLS)), fblock(FIN_WG);
+      mark(stream);
+      if (sweeps == 0 && fuse_l11 && finish_held(n) && m <= FUSED_SEARCH_MAX) {
+        // a short matrix of few columns: the finishing pass seeds itself and runs the outer
+        // search too (with more columns the search repeated in every workgroup costs more than
+        // the seeding kernel it saves: 61 against 56 us at 1000 x 10000)
+        hipLaunchKernelGGL((l11_finish_seeded_kernel<T, FIN_SEARCH_CACHE>), fgrid, fblock, 0, stream, Y, n, m, ws, (double)eta, outer);
+        mark(stream);   // (the same number of intervals as the longer chain: this one is empty)
+      } else {
+        const dim3 igrid((unsigned)cdiv(m, WG));
+        if (!fuse_l11)
+          hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, -1.0, outer);
+        else if (m > FUSED_SEARCH_MAX)
+          hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE_BIG>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
+        else
+          hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
+        if (fuse_l11) mark(stream);   // (keeps one interval for search + seeding, one for the sweeps)
+        for (int s = 0; s < sweeps; ++s) {
+          if (s == 0) {
+            if (wide) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws);
+            else hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws);
+          } else {
+            if (wide) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
+            else hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
+          }
+          hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s, handoff);
         }
-        hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s, handoff);
+        if (finish_held(n))
+          hipLaunchKernelGGL((l11_finish_kernel<T, true>), fgrid, fblock, 0, stream, Y, n, m, ws, sweeps, handoff);
+        else
+          hipLaunchKernelGGL((l11_finish_kernel<T, false>), fgrid, fblock, 0, stream, Y, n, m, ws, sweeps, handoff);
       }
-      if (finish_held(n))
-        hipLaunchKernelGGL((l11_finish_kernel<T, true>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(FIN_WG), 0, stream, Y, n, m, ws, sweeps, handoff);
-      else
-        hipLaunchKernelGGL((l11_finish_kernel<T, false>), dim3((unsigned)cdiv(m, FIN_COLS)), dim3(FIN_WG), 0, stream, Y, n, m, ws, sweeps, handoff);
     }
   }
   if (stages & STAGE_APPLY) {
