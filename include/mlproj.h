@@ -15,9 +15,9 @@
  *    current HIP device; `stream` is a hipStream_t passed as void* (NULL = the
  *    default stream).  Calls only enqueue work on `stream` and return; they never
  *    synchronise, never copy to the host and never allocate or free memory.
- *  - Matrices are dense row-major fp32 (bilevel_proj_stored also takes bf16 and
- *    fp16): element (i, j) of an n x m matrix is Y[i*m + j].  Tensors are dense
- *    C-order fp32.
+ *  - Matrices are dense row-major fp32 (the *_stored entry points also take
+ *    bf16 and fp16): element (i, j) of an n x m matrix is Y[i*m + j].  Tensors
+ *    are dense C-order, of the same element types.
  *  - The caller owns every buffer.  X may alias Y exactly (in-place); any other
  *    overlap between buffers is undefined.  Y must hold finite values.
  *  - `workspace`: device scratch of at least mlproj_workspace_bytes(...) bytes,

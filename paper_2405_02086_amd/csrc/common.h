@@ -20,7 +20,7 @@ constexpr int RBLK = WAVES * UNROLL;     // rows one workgroup consumes per trip
 constexpr int SWG = 1024;                // threads of the search / reduce workgroups
 constexpr int SWAVES = SWG / WAVE;
 constexpr int SEARCH_CACHE = 16;         // values of v per search thread kept in registers
-constexpr int MAX_INNER_SWEEPS = 16;     // l1,1: passes over Y allowed to the inner searches
+constexpr int MAX_INNER_SWEEPS = 16;     // l1,1: most lock-step passes over Y a call may plan for the inner searches
 constexpr double L11_WINDOW = 1.0 / 16;  // l1,1: relative width of the window that samples the density
 constexpr int FILTER_LDS_SLOTS = 8192;   // l1,1: entries a workgroup can stage for its tile (32 KiB of LDS)
 constexpr int FILTER_MAX_LIST = 256;     // l1,1: entries kept per column
