@@ -27,8 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (340, 341, 342, 343)   # (341-343: entry points, l1,1 and multi-level kernels only; the column kernels are those of 340)
-TRAFFIC_KIB = {"square_4096": 32975.2 * 1.999 + 65559.4, "square_16384": 524911.1 * 1.999 + 1048618.7}
+TRAFFIC_VERSIONS = (343,)   # the library version the counters in profiles/ were taken with
+TRAFFIC_KIB = {"square_4096": 32971.6 * 1.999 + 65558.1, "square_16384": 524919.6 * 1.999 + 1048613.8}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 
