@@ -259,6 +259,51 @@ def test_workload_square_16384(mp, big_square, q):
     assert mp.norm_l1q(Xd, QNAME[q]) == pytest.approx(eta, rel=1e-5)
 
 
+@pytest.fixture(scope="module")
+def beyond_int32():
+    """132000 x 16384 fp32: 2 162 688 000 elements, more than 2^31 (8.6 GB; the tail rows sit past
+    element 2^31).  Uniform entries, generated in row chunks from one seeded stream."""
+    n, m = 132000, 16384
+    rng = np.random.default_rng(2405_02086)
+    Y = np.empty((n, m), dtype=np.float32)
+    for r0 in range(0, n, 8250):
+        Y[r0:r0 + 8250] = rng.random((8250, m), dtype=np.float32) - np.float32(0.5)
+    return Y
+
+
+@pytest.mark.parametrize("q", ["inf", 1])
+def test_more_than_2_to_the_31_elements(mp, beyond_int32, q):
+    """Every index is 64-bit: the aggregate is compared in full, X on sampled columns over all
+    rows (the oracle computes those one by one), and the tail rows on their own."""
+    Y = beyond_int32
+    n, m = Y.shape
+    assert n * m > 2 ** 31
+    v = orc.column_norms(Y, q).astype(np.float64)
+    eta = float(np.float32(0.25 * v.sum()))
+    got = run_gpu(mp, Y, eta, q)
+    rng = np.random.default_rng(31)
+    cols = np.sort(rng.choice(m, size=24, replace=False))
+    ref = orc.bilevel(Y, eta, q, columns=cols)
+    check_against_oracle(got, ref, q, columns=cols)
+    X = got["X"]
+    tail = slice(n - 700, n)        # rows whose elements all sit past 2^31
+    assert (n - 700) * m > 2 ** 31
+    assert np.all(np.abs(X[tail]) <= np.abs(Y[tail])) and np.all(X[tail] * Y[tail] >= 0)
+    if q == "inf":
+        u = got["u"]
+        assert np.array_equal(X[tail], np.sign(Y[tail]) * np.minimum(np.abs(Y[tail]), u[None, :]))
+        assert np.array_equal(np.abs(X).max(axis=0), u)
+
+
+def test_trilevel_more_than_2_to_the_31_elements(mp, beyond_int32):
+    """The same buffer seen as a 132 x 16384 x 1000 tensor: slabs of 16 384 000 elements, the last
+    ones past element 2^31; compared with the oracle in full."""
+    Y = beyond_int32.reshape(132, 16384, 1000)
+    w = np.abs(Y.reshape(132, -1)).max(axis=1).astype(np.float64)
+    eta = float(np.float32(0.3 * w.sum()))
+    check_tri(run_tri(mp, Y, eta), orc.trilevel_l1infinf(Y, eta))
+
+
 # ------------------------------------------------------------------ API corners
 @pytest.mark.parametrize("q", ["inf", 1, 2])
 def test_unaligned_pointers_take_the_narrow_paths(mp, q):
