@@ -18,7 +18,8 @@
 // (the one exception, the search over more than 16384 groups, meets at a barrier made of
 // device-scope atomics alone).  The tri-level form uses the same chain with groups that are
 // contiguous slabs; the generic multi-level form works on contiguous fibres, level by level;
-// a batch of matrices shares the three launches of the chain.
+// a batch of matrices shares the three launches of the chain; a matrix of at most 128 KiB takes
+// one kernel in which every workgroup holds all of Y (tiny.h).
 //
 // This file is the one translation unit: the kernels live in the headers it includes (one per
 // pass), the host code below checks arguments, plans the launch geometry and enqueues.
@@ -31,6 +32,7 @@
 #include "slab.h"
 #include "fibre.h"
 #include "batch.h"
+#include "tiny.h"
 
 namespace mlproj {
 
@@ -181,6 +183,18 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   const bool fuse_big = fuse && m > FUSED_SEARCH_MAX;
   const double fused_eta = fuse ? (double)eta : -1.0;
 
+  if constexpr (Q == QINF) {
+    // a matrix of at most 128 KiB that is not projected in place: one kernel does it all
+    TinyPlan tp;
+    const bool apart = X && (X + n * m <= Y || Y + n * m <= X);
+    if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && apart && tiny_plan(n, m, WIDE, &tp)) {
+      mark(stream);
+      hipLaunchKernelGGL((tiny_kernel<Q, T, WIDE>), dim3((unsigned)tp.slots), dim3(TINY_WG), 0, stream, Y, X, n, m,
+                         (double)eta, outer, tp.cw, ws, v_out, u_out, mask_out);
+      mark(stream);
+      return launch_status();
+    }
+  }
   if (stages & STAGE_AGGREGATE) {
     mark(stream);
     if (wide)

@@ -36,11 +36,15 @@ __device__ __forceinline__ double radius(double v, const Top& t) {
 __device__ __forceinline__ Top top_of(const SearchOut& o) { return Top{o.tau, o.scale, o.cap}; }
 __device__ __forceinline__ Top top_of(const mlproj_result* r) { return Top{r->tau, r->scale, r->cap}; }
 
-template <int NT, int CACHE = SEARCH_CACHE>
+// NTHREADS > NT: a larger workgroup runs the search of an NT-thread one; the threads beyond
+// NT hold nothing and add zeros, so the result has the bits the NT-thread workgroup gets.
+template <int NT, int CACHE = SEARCH_CACHE, int NTHREADS = NT>
 __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, long long ngroups,
                                                   double eta, int mode, int outer,
-                                                  PairScratch<NT / WAVE>& s) {
-  const int tid = threadIdx.x;
+                                                  PairScratch<NTHREADS / WAVE>& s) {
+  static_assert(NTHREADS >= NT && NTHREADS % WAVE == 0, "whole wavefronts, at least NT threads");
+  // (a thread beyond NT starts past the end of v: every bound check below leaves it idle)
+  const long long tid = (NTHREADS == NT || threadIdx.x < NT) ? (long long)threadIdx.x : ngroups;
   double vr[CACHE];
   double a = 0.0, mx = 0.0;
 #pragma unroll

@@ -1038,3 +1038,36 @@ def test_multilevel_stored_f32_is_the_fp32_entry_point_bit_for_bit(mp):
         eta = float(np.float32(0.3 * nested_norm(Y.cpu().numpy(), norms)))
         assert torch.equal(mp.multilevel_proj(Y, norms, eta), mp.multilevel_proj_stored(Y, norms, eta))
 
+
+# ------------------------------------------------------------------ matrices of at most 128 KiB (one kernel)
+TINY_SHAPES = {"f32": [(256, 128), (16, 2048), (1, 2048), (8, 2048), (64, 512), (100, 64), (3, 8), (16, 4), (512, 4),
+                       (255, 124), (17, 1000)],
+               "bf16": [(128, 512), (256, 256), (16, 4096), (40, 1000), (2, 8)],
+               "f16": [(128, 512), (100, 24)]}
+
+
+@pytest.mark.parametrize("storage,shape", [(st, sh) for st, shapes in TINY_SHAPES.items() for sh in shapes])
+def test_tiny_matrices_one_kernel_path(mp, storage, shape):
+    """l1,inf on a matrix small enough for the single-kernel path: the oracle's result, the
+    bits of the three-kernel chain (which an in-place call still takes), one kernel in the trace."""
+    dev = torch.device("cuda:0")
+    dt = getattr(torch, STORE_DTYPES[storage])
+    Y = stored_input(shape, storage, 71)
+    for frac, p in ((0.05, 1), (0.6, 1), (1.5, 1), (0.0, 1), (0.4, 2), (0.4, "inf")):
+        v = orc.column_norms(Y, "inf").astype(np.float64)
+        norm_p = v.sum() if p == 1 else (np.sqrt((v * v).sum()) if p == 2 else v.max())
+        eta = float(np.float32(frac * norm_p))
+        got = run_stored(mp, Y, eta, "inf", storage, p=p)
+        check_stored(got, orc.bilevel_stored(Y, eta, "inf", storage, p=p), "inf", storage)
+        chain = torch.from_numpy(Y).to(dev).to(dt)
+        mp.bilevel_proj_stored(chain, eta, "inf", p=p, X=chain)          # in place: the three-kernel chain
+        assert np.array_equal(chain.float().cpu().numpy(), got["X"])
+    Yd = torch.from_numpy(Y).to(dev).to(dt)
+    ws = mp.Workspace.for_call("l1inf", *shape, device=dev)
+    tr = mp.KernelTrace(8)
+    with tr:
+        mp.bilevel_proj_stored(Yd, eta, "inf", workspace=ws)
+    tr.durations_ms()
+    tr.close()
+    assert tr.count == 2, "one kernel and the closing event"
+
