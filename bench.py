@@ -266,8 +266,9 @@ def bench_batch(torch, mp, shape, count, frac, steps, warmup, variant="l1inf"):
         batch()
     d = tr.durations_ms()
     tr.close()
-    labels = ["colagg", "reduce", "colmap+search"] if variant != "l11" else \
-        ["colagg", "reduce", "seeding+search", "l11_sweeps", "colmap"]
+    labels = {1: ["tiny_batch (one kernel for all)"], 3: ["colagg", "reduce", "colmap+search"],
+              5: ["colagg", "reduce", "seeding+search", "l11_sweeps", "colmap"]}.get(
+                  len(d), ["interval_%d" % k for k in range(len(d))])
     out["batch_kernel_ms_event_intervals"] = dict(zip(labels, d))
     return out
 

@@ -31,8 +31,8 @@
 #include "l11.h"
 #include "slab.h"
 #include "fibre.h"
-#include "batch.h"
 #include "tiny.h"
+#include "batch.h"
 
 namespace mlproj {
 
@@ -350,7 +350,44 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
     if (st != MLPROJ_OK) return st;
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG; };
+  // l1,inf matrices of at most 128 KiB that are not projected in place: one kernel for all
+  auto tinyable = [&](int i) {
+    if (Q != QINF) return false;
+    const mlproj_problem& p = pr[i];
+    const T* Yp = static_cast<const T*>(p.Y);
+    const T* Xp = static_cast<const T*>(p.X);
+    TinyPlan tp;
+    return pick_vec(p.Y, p.m, (int)sizeof(T)) == WIDE && aligned(p.X, 16) &&
+           (Xp + p.n * p.m <= Yp || Yp + p.n * p.m <= Xp) && tiny_plan(p.n, p.m, WIDE, &tp);
+  };
+  auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG && !tinyable(i); };
+  if constexpr (Q == QINF) {
+    int k = 0;
+    while (k < count) {
+      BatchItems it;
+      BatchGrid tg;
+      it.count = 0;
+      unsigned wgs = 0;
+      for (; k < count && it.count < BATCH_MAX; ++k) {
+        if (!tinyable(k)) continue;
+        const mlproj_problem& p = pr[k];
+        BatchItem& b = it.item[it.count];
+        b.Y = p.Y; b.X = p.X; b.ws = p.workspace;
+        b.v_out = p.v_out; b.u_out = p.u_out; b.mask_out = p.mask_out;
+        b.n = p.n; b.m = p.m; b.eta = (double)p.eta;
+        b.wide = 1; b.x_vec = 1;
+        TinyPlan tp;
+        tiny_plan(p.n, p.m, WIDE, &tp);
+        tg.first[it.count] = wgs; wgs += (unsigned)tp.slots;
+        ++it.count;
+      }
+      if (it.count == 0) break;
+      tg.first[it.count] = wgs;
+      mark(stream);
+      hipLaunchKernelGGL((tiny_batch_kernel<T>), dim3(wgs), dim3(TINY_WG), 0, stream, it, tg, outer);
+      mark(stream);
+    }
+  }
   int i = 0;
   while (i < count) {
     BatchItems it;
@@ -407,7 +444,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
   }
   int st = launch_status();
   for (int k = 0; k < count && st == MLPROJ_OK; ++k) {
-    if (batchable(k)) continue;
+    if (batchable(k) || tinyable(k)) continue;
     st = run_bilevel<Q, T>(static_cast<const T*>(pr[k].Y), static_cast<T*>(pr[k].X), pr[k].n, pr[k].m, pr[k].eta,
                            pr[k].workspace, pr[k].workspace_bytes, pr[k].v_out, pr[k].u_out, stream_,
                            MODE_PROJECT, nullptr, STAGE_ALL, outer, pr[k].mask_out);

@@ -35,7 +35,7 @@ struct TinyPlan {
 };
 
 // Whether an n x m matrix with `vec` elements per 16-byte chunk fits, and how.
-static inline bool tiny_plan(long long n, long long m, int vec, TinyPlan* p) {
+__host__ __device__ static inline bool tiny_plan(long long n, long long m, int vec, TinyPlan* p) {
   if (m % vec != 0 || m > FUSED_SEARCH_MAX) return false;
   const long long cpr = m / vec;
   if (cpr > TINY_WG) return false;
@@ -50,13 +50,12 @@ static inline bool tiny_plan(long long n, long long m, int vec, TinyPlan* p) {
   return true;
 }
 
+// (`bid` is the workgroup's number within its own problem: blockIdx.x for a single matrix.)
 template <int Q, typename T, int VEC>
-__global__ __launch_bounds__(TINY_WG) void tiny_kernel(const T* __restrict__ Y, T* __restrict__ X,
-                                                       long long n, long long m, double eta,
-                                                       int outer, int cw, Ws ws,
-                                                       float* __restrict__ v_out,
-                                                       float* __restrict__ u_out,
-                                                       unsigned char* __restrict__ mask_out) {
+__device__ __forceinline__ void tiny_body(const T* __restrict__ Y, T* __restrict__ X, long long n,
+                                          long long m, double eta, int outer, int cw, const Ws& ws,
+                                          float* __restrict__ v_out, float* __restrict__ u_out,
+                                          unsigned char* __restrict__ mask_out, long long bid) {
   using Acc = typename AccOf<Q>::type;
   __shared__ Acc sm_part[TINY_WG * VEC];   // [row lane][column]
   __shared__ double sm_v[TINY_WG * VEC];   // v, zero beyond column m
@@ -101,7 +100,7 @@ __global__ __launch_bounds__(TINY_WG) void tiny_kernel(const T* __restrict__ Y, 
   // as in the three-kernel chain and in a batch)
   const SearchOut o = search_block<WG, SEARCH_CACHE, TINY_WG>(sm_v, m, eta, MODE_PROJECT, outer, bs);
   const Top top = top_of(o);
-  if (blockIdx.x == 0) {
+  if (bid == 0) {
     if (threadIdx.x == 0) write_result(ws, o, nullptr);
     for (long long c = threadIdx.x; c < m; c += TINY_WG) {
       const double uj = radius(sm_v[c], top);
@@ -121,10 +120,10 @@ __global__ __launch_bounds__(TINY_WG) void tiny_kernel(const T* __restrict__ Y, 
     uf[e] = (float)uj;
     par[e] = (Q == Q2 && vj > 0.0) ? uj / vj : 0.0;
   }
-  // this workgroup's rows: slot blockIdx.x of every thread
+  // this workgroup's rows: slot `bid` of every thread
 #pragma unroll
   for (int k = 0; k < TINY_SLOTS; ++k) {
-    if (k == (int)blockIdx.x) {
+    if (k == (int)bid) {
       const long long row = tr + (long long)k * rl;
       if (row < n) {
         float f[VEC];
@@ -138,6 +137,16 @@ __global__ __launch_bounds__(TINY_WG) void tiny_kernel(const T* __restrict__ Y, 
       }
     }
   }
+}
+
+template <int Q, typename T, int VEC>
+__global__ __launch_bounds__(TINY_WG) void tiny_kernel(const T* __restrict__ Y, T* __restrict__ X,
+                                                       long long n, long long m, double eta,
+                                                       int outer, int cw, Ws ws,
+                                                       float* __restrict__ v_out,
+                                                       float* __restrict__ u_out,
+                                                       unsigned char* __restrict__ mask_out) {
+  tiny_body<Q, T, VEC>(Y, X, n, m, eta, outer, cw, ws, v_out, u_out, mask_out, blockIdx.x);
 }
 
 }  // namespace mlproj
