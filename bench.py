@@ -250,8 +250,11 @@ def bench_batch(torch, mp, shape, count, frac, steps, warmup, variant="l1inf"):
     def batch():
         mp.bilevel_proj_batch(Ys, etas, q, Xs=Xs, workspaces=wss)
 
+    prepared = mp.PreparedBatch(Ys, etas, q, Xs=Xs, workspaces=wss)   # argument block marshalled once
+
     out = {"shape": list(shape), "count": count}
-    for name, fn in (("ms_loop_of_single_calls", loop), ("ms_one_batch_call", batch)):
+    for name, fn in (("ms_loop_of_single_calls", loop), ("ms_one_batch_call", batch),
+                     ("ms_one_prepared_batch_call", prepared)):
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()

@@ -299,39 +299,57 @@ def trilevel_proj_stored(Y, eta, X=None, workspace=None, v_out=None, u_out=None,
     return X
 
 
+class PreparedBatch:
+    """The argument block of a bilevel_proj_batch call, marshalled once: a training loop projects
+    the same buffers after every step, and filling the block costs more host time than the
+    call.  Calling the object enqueues the batch; `.X` lists the output tensors.  It keeps every
+    tensor it points to alive."""
+
+    def __init__(self, Ys, etas, q, p=1, Xs=None, workspaces=None, v_outs=None, u_outs=None, mask_outs=None):
+        import torch
+        storages = {torch.float32: STORE_F32, torch.bfloat16: STORE_BF16, torch.float16: STORE_F16}
+        count = len(Ys)
+        assert count > 0 and len(etas) == count
+        self.variant = {"inf": L1INF, 1: L11, 2: L12}[q]
+        self.outer = _OUTERS[p]
+        self.count = count
+        pick = lambda lst, i: None if lst is None else lst[i]
+        self.problems = (Problem * count)()
+        self.X = []
+        self.keep = [Ys, v_outs, u_outs, mask_outs]   # every buffer the block points to
+        for i, Y in enumerate(Ys):
+            assert Y.is_cuda and Y.dim() == 2 and Y.is_contiguous() and Y.dtype == Ys[0].dtype and Y.dtype in storages
+            n, m = Y.shape
+            X = pick(Xs, i)
+            if X is None:
+                X = torch.empty_like(Y)
+            assert X.is_cuda and X.dtype == Y.dtype and X.is_contiguous() and X.shape == Y.shape
+            # every problem needs a workspace of its own
+            ws = pick(workspaces, i) or Workspace.for_call(self.variant, n, m, device=Y.device)
+            self.keep.append(ws)
+            self.X.append(X)
+            pr = self.problems[i]
+            pr.Y, pr.X, pr.n, pr.m, pr.eta = Y.data_ptr(), X.data_ptr(), n, m, float(etas[i])
+            pr.workspace, pr.workspace_bytes = ws.buf.data_ptr(), ws.nbytes
+            for field, lst in (("v_out", v_outs), ("u_out", u_outs), ("mask_out", mask_outs)):
+                t = pick(lst, i)
+                setattr(pr, field, None if t is None else t.data_ptr())
+        self.storage = storages[Ys[0].dtype]
+
+    def __call__(self, stream=None):
+        st = lib().bilevel_proj_batch(self.storage, self.outer, self.variant, self.count, self.problems,
+                                      _stream(stream))
+        _check(st, "bilevel_proj_batch")
+        return self.X
+
+
 def bilevel_proj_batch(Ys, etas, q, p=1, Xs=None, workspaces=None, v_outs=None, u_outs=None, mask_outs=None,
                        stream=None):
     """Independent BP^{p,q} projections of the matrices in Ys (same dtype, any shapes) with radii
     etas, through bilevel_proj_batch; returns the list of X tensors.  Optional lists give the
     per-problem X, workspace, v_out, u_out and mask_out."""
-    import torch
-    storages = {torch.float32: STORE_F32, torch.bfloat16: STORE_BF16, torch.float16: STORE_F16}
-    count = len(Ys)
-    assert count > 0 and len(etas) == count
-    variant = {"inf": L1INF, 1: L11, 2: L12}[q]
-    pick = lambda lst, i: None if lst is None else lst[i]
-    problems = (Problem * count)()
-    out = []
-    alive = []   # every problem needs a workspace of its own until the batch has been enqueued
-    for i, Y in enumerate(Ys):
-        assert Y.is_cuda and Y.dim() == 2 and Y.is_contiguous() and Y.dtype == Ys[0].dtype and Y.dtype in storages
-        n, m = Y.shape
-        X = pick(Xs, i)
-        if X is None:
-            X = torch.empty_like(Y)
-        assert X.is_cuda and X.dtype == Y.dtype and X.is_contiguous() and X.shape == Y.shape
-        ws = pick(workspaces, i) or Workspace.for_call(variant, n, m, device=Y.device, stream=stream)
-        alive.append(ws)
-        out.append(X)
-        pr = problems[i]
-        pr.Y, pr.X, pr.n, pr.m, pr.eta = Y.data_ptr(), X.data_ptr(), n, m, float(etas[i])
-        pr.workspace, pr.workspace_bytes = ws.buf.data_ptr(), ws.nbytes
-        for field, lst in (("v_out", v_outs), ("u_out", u_outs), ("mask_out", mask_outs)):
-            t = pick(lst, i)
-            setattr(pr, field, None if t is None else t.data_ptr())
-    st = lib().bilevel_proj_batch(storages[Ys[0].dtype], _OUTERS[p], variant, count, problems, _stream(stream))
-    _check(st, "bilevel_proj_batch")
-    return out
+    return PreparedBatch(Ys, etas, q, p=p, Xs=Xs, workspaces=workspaces, v_outs=v_outs, u_outs=u_outs,
+                         mask_outs=mask_outs)(stream)
 
 
 NORM_INF, NORM_L1, NORM_L2 = 0, 1, 2

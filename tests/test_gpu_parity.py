@@ -797,6 +797,25 @@ def test_batch_l11_problems_keep_their_own_sweep_plans(mp, l11_sweeps):
             assert torch.equal(mp.bilevel_proj_l11(Yd[i], etas[i]), Xs[i])
 
 
+def test_prepared_batch_can_be_called_again_on_new_contents(mp):
+    """The argument block is marshalled once; the buffers it points to may change between calls."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(17)
+    shapes = [(256, 128), (40, 1000), (700, 300), (64, 64)]
+    Ys = [rng.standard_normal(sh).astype(np.float32) for sh in shapes]
+    Yd = [torch.from_numpy(Y).to(dev) for Y in Ys]
+    etas = [eta_for(Y, "inf", 0.2) for Y in Ys]
+    batch = mp.PreparedBatch(Yd, etas, "inf")
+    for rep in range(3):
+        Xs = batch()
+        torch.cuda.synchronize()
+        for Y, eta, X in zip(Ys, etas, Xs):
+            np.testing.assert_allclose(X.cpu().numpy(), orc.bilevel(Y, eta, "inf")["X"], rtol=RTOL, atol=ATOL)
+        Ys = [np.float32(0.5) * Y + np.float32(rep) for Y in Ys]     # new contents, same buffers
+        for d, Y in zip(Yd, Ys):
+            d.copy_(torch.from_numpy(Y))
+
+
 def test_batch_in_place_and_kernel_count(mp):
     """In place; and the three launches of a small batch, seen through the event trace."""
     dev = torch.device("cuda:0")
