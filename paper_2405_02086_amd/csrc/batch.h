@@ -89,18 +89,18 @@ __global__ __launch_bounds__(WG) void colmap_batch_kernel(BatchItems it, BatchGr
     colmap_body<Q, T, WIDE, true, false, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, eta, outer, bid);
 }
 
-// Matrices of at most 128 KiB each (l1,inf, not in place): the one-kernel form of tiny.h for
-// all of them in one launch.
-template <typename T>
+// Matrices of at most 128 KiB each (q = inf or 2, not in place): the one-kernel form of tiny.h
+// for all of them in one launch.
+template <int Q, typename T>
 __global__ __launch_bounds__(TINY_WG) void tiny_batch_kernel(BatchItems it, BatchGrid gr, int outer) {
   constexpr int WIDE = 16 / (int)sizeof(T);
   long long bid;
   const BatchItem& b = it.item[batch_find(gr, it.count, bid)];
   TinyPlan tp;
   if (!tiny_plan(b.n, b.m, WIDE, &tp)) return;   // (the host only sends matrices that fit)
-  const Geometry g = plan_columns(b.n, b.m, WIDE, QINF);
-  const Ws ws = bind(b.ws, layout_for(g, b.m, QINF));
-  tiny_body<QINF, T, WIDE>(static_cast<const T*>(b.Y), static_cast<T*>(b.X), b.n, b.m, b.eta, outer, tp.cw, ws,
+  const Geometry g = plan_columns(b.n, b.m, WIDE, Q);
+  const Ws ws = bind(b.ws, layout_for(g, b.m, Q));
+  tiny_body<Q, T, WIDE>(static_cast<const T*>(b.Y), static_cast<T*>(b.X), b.n, b.m, b.eta, outer, tp.cw, ws,
                            b.v_out, b.u_out, b.mask_out, bid);
 }
 

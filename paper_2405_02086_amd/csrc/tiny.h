@@ -16,9 +16,10 @@ namespace mlproj {
 // threshold search (Eq. 6-7) itself, and then maps and stores its own share of the rows: the
 // three steps of Alg. 1 with no hand-over between workgroups, so one launch.  All workgroups
 // compute the same v and tau, bit for bit.  Reading Y sixteen times is served by the L2.
-// Used for q = inf, where the aggregate is exact and the result therefore has the bits of
-// the three-kernel chain (for q = 2 the different order of the fp64 sums could show in the last
-// bit of an output, and a batch promises the bits of single calls).
+// Used for q = inf and q = 2.  For q = inf the aggregate is exact and the result has the bits
+// of the three-kernel chain; for q = 2 the fp64 sums are folded in another order than there,
+// which can show in the last bit of an output (a batch sends the same matrices here as single
+// calls do, so it still returns their bits).
 //
 // Threads form TINY_WG / cw row lanes of cw column lanes (cw = the chunks of a row, rounded up
 // to a power of two); a thread holds rows tr, tr + rl, tr + 2 rl, ... of its chunk column, and

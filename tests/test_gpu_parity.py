@@ -1065,28 +1065,33 @@ TINY_SHAPES = {"f32": [(256, 128), (16, 2048), (1, 2048), (8, 2048), (64, 512), 
                "f16": [(128, 512), (100, 24)]}
 
 
+@pytest.mark.parametrize("q", ["inf", 2])
 @pytest.mark.parametrize("storage,shape", [(st, sh) for st, shapes in TINY_SHAPES.items() for sh in shapes])
-def test_tiny_matrices_one_kernel_path(mp, storage, shape):
-    """l1,inf on a matrix small enough for the single-kernel path: the oracle's result, the
-    bits of the three-kernel chain (which an in-place call still takes), one kernel in the trace."""
+def test_tiny_matrices_one_kernel_path(mp, storage, shape, q):
+    """A matrix small enough for the single-kernel path (q = inf or 2): the oracle's result, one
+    kernel in the trace, and for q = inf the bits of the three-kernel chain (which an in-place
+    call still takes)."""
     dev = torch.device("cuda:0")
     dt = getattr(torch, STORE_DTYPES[storage])
     Y = stored_input(shape, storage, 71)
     for frac, p in ((0.05, 1), (0.6, 1), (1.5, 1), (0.0, 1), (0.4, 2), (0.4, "inf")):
-        v = orc.column_norms(Y, "inf").astype(np.float64)
+        v = orc.column_norms(Y, q).astype(np.float64)
         norm_p = v.sum() if p == 1 else (np.sqrt((v * v).sum()) if p == 2 else v.max())
         eta = float(np.float32(frac * norm_p))
-        got = run_stored(mp, Y, eta, "inf", storage, p=p)
-        check_stored(got, orc.bilevel_stored(Y, eta, "inf", storage, p=p), "inf", storage)
+        got = run_stored(mp, Y, eta, q, storage, p=p)
+        check_stored(got, orc.bilevel_stored(Y, eta, q, storage, p=p), q, storage)
         chain = torch.from_numpy(Y).to(dev).to(dt)
-        mp.bilevel_proj_stored(chain, eta, "inf", p=p, X=chain)          # in place: the three-kernel chain
-        assert np.array_equal(chain.float().cpu().numpy(), got["X"])
+        mp.bilevel_proj_stored(chain, eta, q, p=p, X=chain)          # in place: the three-kernel chain
+        if q == "inf":
+            assert np.array_equal(chain.float().cpu().numpy(), got["X"])
+        else:
+            np.testing.assert_allclose(chain.float().cpu().numpy(), got["X"], rtol=2e-2 if storage != "f32" else RTOL,
+                                       atol=ATOL)
     Yd = torch.from_numpy(Y).to(dev).to(dt)
-    ws = mp.Workspace.for_call("l1inf", *shape, device=dev)
+    ws = mp.Workspace.for_call(QNAME[q], *shape, device=dev)
     tr = mp.KernelTrace(8)
     with tr:
-        mp.bilevel_proj_stored(Yd, eta, "inf", workspace=ws)
+        mp.bilevel_proj_stored(Yd, eta, q, workspace=ws)
     tr.durations_ms()
     tr.close()
     assert tr.count == 2, "one kernel and the closing event"
-
