@@ -20,6 +20,7 @@ constexpr int RBLK = WAVES * UNROLL;     // rows one workgroup consumes per trip
 constexpr int SWG = 1024;                // threads of the search / reduce workgroups
 constexpr int SWAVES = SWG / WAVE;
 constexpr int SEARCH_CACHE = 16;         // values of v per search thread kept in registers
+constexpr int SEARCH_CACHE_ONE_WG = 32;  // ... in the stand-alone one-workgroup search of 16385..32768 groups
 constexpr int MAX_INNER_SWEEPS = 16;     // l1,1: most lock-step passes over Y a call may plan for the inner searches
 constexpr double L11_WINDOW = 1.0 / 16;  // l1,1: relative width of the window that samples the density
 constexpr int FILTER_LDS_SLOTS = 8192;   // l1,1: entries a workgroup can stage for its tile (32 KiB of LDS)

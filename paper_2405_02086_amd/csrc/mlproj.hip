@@ -107,20 +107,26 @@ static inline void mark(hipStream_t stream) {
     (void)hipEventRecord(g_trace.events[g_trace.count++], stream);
 }
 
-// The stand-alone search: one workgroup when v fits its registers, the grid-wide form beyond
-// that, followed by the one-workgroup kernel as a fallback that returns at once unless the
-// grid-wide one gave up.
+// The stand-alone search: one workgroup of 1024 threads while v fits its registers (16 values
+// per thread up to 16384 groups, 32 up to 32768), the grid-wide form beyond that, followed by the one-workgroup kernel as a fallback that returns at once unless
+// the grid-wide one gave up.
 static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, int outer,
                           double* norm_out, hipStream_t stream) {
   int only_as_fallback = 0;
   // (the l2 and l_inf outer projections need no iteration: one workgroup reads v once)
-  if (ngroups > (long long)SWG * SEARCH_CACHE && (outer == MLPROJ_OUTER_L1 || mode == MODE_NORM)) {
+  const bool iterates = outer == MLPROJ_OUTER_L1 || mode == MODE_NORM;
+  if (ngroups > (long long)SWG * SEARCH_CACHE && ngroups <= (long long)SWG * SEARCH_CACHE_ONE_WG && iterates) {
+    hipLaunchKernelGGL(search_kernel<SEARCH_CACHE_ONE_WG>, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode,
+                       outer, norm_out, 0, (double*)nullptr, (float*)nullptr);
+    return;
+  }
+  if (ngroups > (long long)SWG * SEARCH_CACHE && iterates) {
     long long nwg = cdiv(ngroups, (long long)SWG * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
     hipLaunchKernelGGL(search_wide_kernel, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
     only_as_fallback = 1;
   }
-  hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
+  hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
                      only_as_fallback, (double*)nullptr, (float*)nullptr);
 }
 
@@ -665,7 +671,7 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
   if (fuse_top) {
     // nothing here: see the first map below
   } else if (dims[0] <= (long long)SWG * SEARCH_CACHE || outer != MLPROJ_OUTER_L1) {
-    hipLaunchKernelGGL(search_kernel, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
+    hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
                        outer, (double*)nullptr, 0, R[ndim - 1], u_out);
   } else {
     hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WAVE), 0, stream, ws);

@@ -155,6 +155,9 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
 }
 
 // radii / u_out (optional): also write u_j = max(v_j - tau, 0) for every group.
+// CACHE values of v per thread in registers: 16 (up to 16384 groups) or 32 (up to 32768; 64 would
+// not fit the 128 registers a 1024-thread workgroup leaves each thread).
+template <int CACHE>
 __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
                                                      int mode, int outer,
                                                      double* __restrict__ norm_out,
@@ -163,7 +166,7 @@ __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, d
                                                      float* __restrict__ u_out) {
   __shared__ PairScratch<SWAVES> s;
   if (only_as_fallback && ws.flags[1] == 0u) return;
-  const SearchOut o = search_block<SWG>(ws.v, ngroups, eta, mode, outer, s);
+  const SearchOut o = search_block<SWG, CACHE>(ws.v, ngroups, eta, mode, outer, s);
   if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
   if (threadIdx.x == 0) write_result(ws, o, norm_out);
   if (radii) {

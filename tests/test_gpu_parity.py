@@ -85,9 +85,10 @@ def test_bilevel_matches_oracle_on_ragged_shapes(mp, q, shape):
 
 
 @pytest.mark.parametrize("q", ["inf", 1, 2])
-@pytest.mark.parametrize("shape", [(3, 40001), (8, 70000), (2, 16388), (40, 300000)])
+@pytest.mark.parametrize("shape", [(3, 40001), (8, 70000), (2, 16388), (40, 300000), (5, 65536), (5, 65540)])
 def test_many_columns_use_the_grid_wide_search(mp, q, shape):
-    """More columns than one workgroup can search from registers (m > 16384)."""
+    """More columns than a map workgroup can search itself (m > 16384): the one-workgroup search
+    with 64 values per thread up to 65536 columns, the grid-wide search beyond."""
     rng = np.random.default_rng([shape[0], shape[1], 99])
     Y = rng.laplace(size=shape).astype(np.float32)
     nrm = orc.norm_l1q(Y, q)
