@@ -89,8 +89,8 @@ __global__ __launch_bounds__(WG) void colmap_batch_kernel(BatchItems it, BatchGr
     colmap_body<Q, T, WIDE, true, false, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, eta, outer, bid);
 }
 
-// Matrices of at most 128 KiB each (q = inf or 2, not in place): the one-kernel form of tiny.h
-// for all of them in one launch.
+// Matrices of at most 128 KiB each (not in place): the one-kernel form of tiny.h for all of
+// them in one launch.
 template <int Q, typename T>
 __global__ __launch_bounds__(TINY_WG) void tiny_batch_kernel(BatchItems it, BatchGrid gr, int outer) {
   constexpr int WIDE = 16 / (int)sizeof(T);

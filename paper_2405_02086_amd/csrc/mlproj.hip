@@ -189,7 +189,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   const bool fuse_big = fuse && m > FUSED_SEARCH_MAX;
   const double fused_eta = fuse ? (double)eta : -1.0;
 
-  if constexpr (Q != Q1) {
+  if constexpr (tiny_built<Q, T>()) {
     // a matrix of at most 128 KiB that is not projected in place: one kernel does it all
     TinyPlan tp;
     const bool apart = X && (X + n * m <= Y || Y + n * m <= X);
@@ -356,9 +356,9 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
     if (st != MLPROJ_OK) return st;
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  // matrices of at most 128 KiB that are not projected in place (q = inf or 2): one kernel for all
+  // matrices of at most 128 KiB that are not projected in place: one kernel for all
   auto tinyable = [&](int i) {
-    if (Q == Q1) return false;
+    if (!tiny_built<Q, T>()) return false;
     const mlproj_problem& p = pr[i];
     const T* Yp = static_cast<const T*>(p.Y);
     const T* Xp = static_cast<const T*>(p.X);
@@ -367,7 +367,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
            (Xp + p.n * p.m <= Yp || Yp + p.n * p.m <= Xp) && tiny_plan(p.n, p.m, WIDE, &tp);
   };
   auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG && !tinyable(i); };
-  if constexpr (Q != Q1) {
+  if constexpr (tiny_built<Q, T>()) {
     int k = 0;
     while (k < count) {
       BatchItems it;
