@@ -4,7 +4,6 @@
 
 #include "aggregate.h"
 #include "common.h"
-#include "l11.h"
 #include "reduce.h"
 #include "search.h"
 
@@ -18,22 +17,21 @@ namespace mlproj {
 // three steps of Alg. 1 with no hand-over between workgroups, so one launch.  All workgroups
 // compute the same v and tau, bit for bit.  Reading Y sixteen times is served by the L2.
 // For q = inf the aggregate is exact and the result has the bits of the three-kernel chain; for
-// q = 2 and q = 1 the fp64 sums are folded in another order than there, which can show in the
-// last bit of an output (a batch sends the same matrices here as single calls do, so it still
-// returns their bits).  For q = 1 every workgroup also runs the per-column threshold searches
-// of Alg. 3 on the registers it holds: the fixed point of the outer search per column, from the
-// seeding guess (see l11.h), with the row lanes' sums and counts meeting in LDS every round.
+// q = 2 the fp64 sums are folded in another order than there, which can show in the last bit of
+// an output (a batch sends the same matrices here as single calls do, so it still returns
+// their bits).
 //
 // Threads form TINY_WG / cw row lanes of cw column lanes (cw = the chunks of a row, rounded up
 // to a power of two); a thread holds rows tr, tr + rl, tr + 2 rl, ... of its chunk column, and
 // workgroup b stores the rows of slot b.  X must not overlap Y: a workgroup still reading Y
 // would see rows another has already written.
-// Which forms are built.  The q = 1 form on 16-bit storage (8 columns per lane) is not: it needs
-// 82 KB of LDS, all 256 registers and scratch memory besides, and its one run on an MI355X ended
-// in a memory aperture fault whose cause has not been established; those matrices take the
-// kernels of the general path instead.
+// Which forms are built: q = inf and q = 2.  (A q = 1 form, with the per-column searches of
+// Alg. 3 run on the held registers, was built and dropped: on fp32 storage it took 43 us for a
+// 256 x 128 matrix against 23 us for the general path, whose finishing pass spreads the columns
+// over many workgroups instead of repeating every search in each; on 16-bit storage it needed 82 KB
+// of LDS, all 256 registers and scratch memory, and its one run ended in a memory aperture fault.)
 template <int Q, typename T>
-constexpr bool tiny_built() { return Q != Q1 || sizeof(T) == 4; }
+constexpr bool tiny_built() { return Q != Q1; }
 
 constexpr int TINY_WG = 512;
 constexpr int TINY_WAVES = TINY_WG / WAVE;
@@ -121,7 +119,7 @@ __device__ __forceinline__ void tiny_body(const T* __restrict__ Y, T* __restrict
     }
   }
   float uf[VEC];
-  double par[VEC];   // q = 2: scale u_j / v_j;  q = 1: inner threshold tau_j
+  double par[VEC];   // q = 2: scale u_j / v_j
 #pragma unroll
   for (int e = 0; e < VEC; ++e) {
     const double vj = sm_v[tc * VEC + e];
@@ -129,84 +127,7 @@ __device__ __forceinline__ void tiny_body(const T* __restrict__ Y, T* __restrict
     uf[e] = (float)uj;
     par[e] = (Q == Q2 && vj > 0.0) ? uj / vj : 0.0;
   }
-  if constexpr (Q == Q1) {
-    __shared__ unsigned sm_cnt[TINY_WG * VEC];
-    const bool searching = o.inside == 0u && o.active != 0u;   // the same in every thread
-    if (bid == 0 && threadIdx.x == 0) ws.res->inner_finished = searching ? o.active : 0u;
-    bool open[VEC], first[VEC];
-    double t[VEC], floor_t[VEC], uj[VEC];
-    unsigned kprev[VEC];
-    bool any_open = false;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const double vj = sm_v[tc * VEC + e];
-      uj[e] = radius(vj, top);
-      open[e] = searching && col_ok && uj[e] > 0.0;
-      floor_t[e] = 0.0;
-      t[e] = open[e] ? l11_guess(vj, uj[e], n, floor_t[e]) : 0.0;
-      first[e] = true;
-      kprev[e] = NO_COUNT;
-      any_open = any_open || open[e];
-      // kept columns get their threshold below; dropped ones map to 0; inside the ball X = Y
-      par[e] = searching ? (uj[e] > 0.0 ? 0.0 : HUGE_VAL) : (o.inside != 0u ? 0.0 : HUGE_VAL);
-    }
-    while (__syncthreads_or(any_open ? 1 : 0)) {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        const float ct = above(t[e]);
-        double sum = 0.0;
-        unsigned cnt = 0u;
-#pragma unroll
-        for (int k = 0; k < TINY_SLOTS; ++k) {
-          float a = fabsf((float)raw[k].e[e]);
-          asm volatile("" : "+v"(a));   // keeps the widening to fp64 in the loop (see l11_finish_body)
-          const bool in = tr + (long long)k * rl < n && a >= ct;
-          sum += (double)(in ? a : 0.0f);
-          cnt += in ? 1u : 0u;
-        }
-        sm_part[tr * width + tc * VEC + e] = sum;
-        sm_cnt[tr * width + tc * VEC + e] = cnt;
-      }
-      __syncthreads();
-      any_open = false;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        double S = sm_part[tc * VEC + e];
-        unsigned K = sm_cnt[tc * VEC + e];
-        for (int r = 1; r < rl; ++r) {
-          S += sm_part[r * width + tc * VEC + e];
-          K += sm_cnt[r * width + tc * VEC + e];
-        }
-        if (open[e]) {
-          if (first[e]) {
-            kprev[e] = K > 0u ? K : NO_COUNT;
-            t[e] = K > 0u ? fmax((S - uj[e]) / (double)K, floor_t[e]) : floor_t[e];
-          } else if (K == 0u || K == kprev[e]) {
-            open[e] = false;
-          } else {
-            kprev[e] = K;
-            const double tn = (S - uj[e]) / (double)K;
-            if (tn > t[e]) t[e] = tn;
-            else open[e] = false;
-          }
-        }
-        first[e] = false;
-        any_open = any_open || open[e];
-      }
-      // (the barrier at the head of the loop also keeps the LDS rows until all have read them)
-    }
-#pragma unroll
-    for (int e = 0; e < VEC; ++e)
-      if (searching && uj[e] > 0.0) par[e] = t[e];
-  }
   if (!col_ok) return;
-  // q = 1: tau_j as an unevaluated fp32 pair, as in the map kernel of the chain
-  float th[VEC], tl[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) {
-    th[e] = (float)par[e];
-    tl[e] = (Q == Q1 && par[e] < HUGE_VAL) ? (float)(par[e] - (double)th[e]) : 0.0f;
-  }
   // this workgroup's rows: slot `bid` of every thread
 #pragma unroll
   for (int k = 0; k < TINY_SLOTS; ++k) {
@@ -218,8 +139,7 @@ __device__ __forceinline__ void tiny_body(const T* __restrict__ Y, T* __restrict
         for (int e = 0; e < VEC; ++e) {
           const float y = (float)raw[k].e[e];
           if constexpr (Q == QINF) f[e] = copysignf(fminf(fabsf(y), uf[e]), y);
-          else if constexpr (Q == Q2) f[e] = (float)((double)y * par[e]);
-          else f[e] = copysignf(fmaxf((fabsf(y) - th[e]) - tl[e], 0.0f), y);
+          else f[e] = (float)((double)y * par[e]);
         }
         store_row_nt<VEC>(X + row * m + at, f);
       }

@@ -1066,7 +1066,7 @@ TINY_SHAPES = {"f32": [(256, 128), (16, 2048), (1, 2048), (8, 2048), (64, 512), 
                "f16": [(128, 512), (100, 24)]}
 
 
-@pytest.mark.parametrize("q", ["inf", 2, 1])
+@pytest.mark.parametrize("q", ["inf", 2, 1])   # (q = 1 has no one-kernel form: the general path)
 @pytest.mark.parametrize("storage,shape", [(st, sh) for st, shapes in TINY_SHAPES.items() for sh in shapes])
 def test_tiny_matrices_one_kernel_path(mp, storage, shape, q):
     """A matrix small enough for the single-kernel path: the oracle's result, one kernel in the
@@ -1094,5 +1094,5 @@ def test_tiny_matrices_one_kernel_path(mp, storage, shape, q):
         mp.bilevel_proj_stored(Yd, eta, q, workspace=ws)
     tr.durations_ms()
     tr.close()
-    if q != 1 or storage == "f32":      # (the q = 1 form is not built for 16-bit storage: those take the general path)
+    if q != 1:
         assert tr.count == 2, "one kernel and the closing event"
