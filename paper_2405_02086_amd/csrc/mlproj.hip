@@ -707,7 +707,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 343; }
+int mlproj_version(void) { return 344; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
