@@ -279,3 +279,12 @@ def test_header_is_plain_c():
         assert proc.returncode == 0, proc.stderr
     text = open(header).read()
     assert "hip" not in re.sub(r"/\*.*?\*/", "", text, flags=re.S).lower() and "torch" not in text.lower()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching any device."""
+    import subprocess
+    import sys
+    proc = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert proc.returncode != 0
+    assert "one GPU" in (proc.stdout + proc.stderr)
