@@ -15,7 +15,7 @@
 //   colmap    Y, v, tau -> X                                  (reads Y again, writes X once)
 // Workgroups never wait for one another inside a kernel: on this GPU a device-scope fence
 // costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only
-// (the one exception, the search over more than 16384 groups, meets at a barrier made of
+// (the one exception, the search over more than 32768 groups, meets at a barrier made of
 // device-scope atomics alone).  The tri-level form uses the same chain with groups that are
 // contiguous slabs; the generic multi-level form works on contiguous fibres, level by level;
 // a batch of matrices shares the three launches of the chain; a matrix of at most 128 KiB takes
@@ -108,8 +108,8 @@ static inline void mark(hipStream_t stream) {
 }
 
 // The stand-alone search: one workgroup of 1024 threads while v fits its registers (16 values
-// per thread up to 16384 groups, 32 up to 32768), the grid-wide form beyond that, followed by the one-workgroup kernel as a fallback that returns at once unless
-// the grid-wide one gave up.
+// per thread up to 16384 groups, 32 up to 32768), the grid-wide form beyond that, followed by
+// the one-workgroup kernel as a fallback that returns at once unless the grid-wide one gave up.
 static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, int outer,
                           double* norm_out, hipStream_t stream) {
   int only_as_fallback = 0;
