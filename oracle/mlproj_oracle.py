@@ -98,6 +98,38 @@ def project_l1_ball_nonneg(v, eta):
     return u, tau
 
 
+def project_weighted_l1_ball_nonneg(v, w, eta):
+    """Euclidean projection of v >= 0 onto the weighted l1 ball {u : sum_j w_j |u_j| <= eta},
+    w_j > 0 (the l_w1 ball Sec. 3 names beside l1, l2 and l_inf), in fp64.  Returns (u, tau).
+
+    The Lagrangian of min ||u - v||^2 / 2 s.t. sum w_j u_j <= eta, u >= 0 gives
+    u_j = max(v_j - tau w_j, 0) with tau = 0 if sum w_j v_j <= eta, and otherwise the unique
+    tau > 0 with sum_j w_j max(v_j - tau w_j, 0) = eta.  With the ratios rho_j = v_j / w_j sorted
+    in decreasing order the active set is a prefix: K = max{k : rho_(k) > tau_k},
+    tau_k = (sum_{i<=k} w_i v_i - eta) / sum_{i<=k} w_i^2, tau = tau_K.
+    """
+    v = np.asarray(v, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    assert v.ndim == 1 and v.shape == w.shape and np.all(v >= 0.0) and np.all(w > 0.0)
+    eta = float(eta)
+    assert eta >= 0.0
+    if v.size == 0:
+        return v.copy(), 0.0
+    rho = v / w
+    if eta == 0.0:
+        return np.zeros_like(v), float(np.max(rho))
+    if float(np.sum(w * v)) <= eta:
+        return v.copy(), 0.0
+    order = np.argsort(-rho, kind="stable")
+    num = np.cumsum((w * v)[order]) - eta
+    den = np.cumsum((w * w)[order])
+    cand = num / den
+    K = int(np.nonzero(rho[order] > cand)[0][-1]) + 1
+    tau = float(cand[K - 1])
+    u = np.maximum(v - tau * w, 0.0)
+    return u, tau
+
+
 def project_l1_ball(y, r):
     """P^1_r(y) for a signed vector: sign(y) * P^1_r(|y|).  Returns (x, tau)."""
     y = np.asarray(y, dtype=np.float64)
@@ -130,10 +162,13 @@ def project_l2_ball(y, r, norm=None):
 
 
 def project_outer(v, eta, p=1):
-    """u = P^p_eta(v) for the non-negative aggregate vector v (Eq. 6-7), p in {1, 2, "inf"}:
-    the l1-ball projection above, the rescale onto the l2 ball, or the clip to [0, eta].
-    Returns (u, tau); tau is the l1 threshold and 0 for the other two norms."""
+    """u = P^p_eta(v) for the non-negative aggregate vector v (Eq. 6-7), p in {1, 2, "inf"} or
+    ("w1", weights): the l1-ball projection above, the rescale onto the l2 ball, the clip to
+    [0, eta], or the projection onto the weighted l1 ball.
+    Returns (u, tau); tau is the (weighted) l1 threshold and 0 for the other two norms."""
     v = np.asarray(v, dtype=np.float64)
+    if isinstance(p, tuple) and p[0] == "w1":
+        return project_weighted_l1_ball_nonneg(v, np.asarray(p[1], dtype=np.float64), eta)
     if p == 1:
         return project_l1_ball_nonneg(v, eta)
     if p == 2:

@@ -532,3 +532,81 @@ def test_multilevel_stored_is_the_fp32_result_rounded(storage, norms):
     assert np.array_equal(out["X"], orc.round_to_storage(ref["X"], storage))
     assert np.all(np.abs(out["X"]) <= np.abs(Y)) and np.all(out["X"] * Y >= 0)   # rounding is monotone and odd
 
+
+# --------------------------------------------------------------------------
+# weighted l1 ball (the l_w1 outer norm Sec. 3 names)
+# --------------------------------------------------------------------------
+def test_weighted_l1_with_unit_weights_is_the_plain_l1_projection():
+    v = np.abs(RNG.standard_normal(200))
+    for eta in (0.0, 0.5, 10.0, 1e6):
+        u, tau = orc.project_weighted_l1_ball_nonneg(v, np.ones_like(v), eta)
+        u0, tau0 = orc.project_l1_ball_nonneg(v, eta)
+        assert np.allclose(u, u0, rtol=0, atol=1e-14) and tau == pytest.approx(tau0, abs=1e-14)
+
+
+def test_weighted_l1_optimality_certificate():
+    """KKT: u_j > 0 => (v_j - u_j) / w_j = tau; u_j = 0 => v_j / w_j <= tau; sum w_j u_j = eta."""
+    for seed in range(20):
+        rng = np.random.default_rng([seed, 5150])
+        m = int(rng.integers(1, 300))
+        v = np.abs(rng.standard_normal(m)) * rng.choice([0.0, 1.0, 5.0], m)
+        w = np.exp(rng.uniform(-2, 2, m))
+        total = float(np.sum(w * v))
+        if total == 0.0:
+            continue
+        eta = total * float(rng.uniform(0.01, 0.99))
+        u, tau = orc.project_weighted_l1_ball_nonneg(v, w, eta)
+        assert tau > 0 and np.all(u >= 0) and np.sum(w * u) == pytest.approx(eta, rel=1e-12)
+        act = u > 0
+        assert np.allclose((v[act] - u[act]) / w[act], tau, rtol=1e-12, atol=0)
+        assert np.all(v[~act] / w[~act] <= tau * (1 + 1e-12))
+        # inside the ball nothing moves
+        u_in, tau_in = orc.project_weighted_l1_ball_nonneg(v, w, total * 1.01)
+        assert np.array_equal(u_in, v) and tau_in == 0.0
+
+
+def test_weighted_l1_against_a_constrained_minimiser_and_brute_force():
+    """scipy's SLSQP on min ||u - v||^2 s.t. sum w u <= eta, u >= 0 (small sizes), and brute
+    force over all active sets (tiny sizes): two routes that share nothing with the sort."""
+    from itertools import combinations
+    from scipy.optimize import minimize
+    for seed in range(6):
+        rng = np.random.default_rng([seed, 909])
+        m = 6
+        v = np.abs(rng.standard_normal(m)) + 0.1
+        w = np.exp(rng.uniform(-1, 1, m))
+        eta = 0.4 * float(np.sum(w * v))
+        u, tau = orc.project_weighted_l1_ball_nonneg(v, w, eta)
+        res = minimize(lambda x: 0.5 * np.sum((x - v) ** 2), np.zeros(m), jac=lambda x: x - v, method="SLSQP",
+                       bounds=[(0, None)] * m, constraints=[{"type": "ineq", "fun": lambda x: eta - np.dot(w, x),
+                                                             "jac": lambda x: -w}], options={"ftol": 1e-14, "maxiter": 500})
+        assert res.success and np.allclose(res.x, u, atol=1e-6)
+        best, best_d = None, np.inf
+        for k in range(1, m + 1):
+            for A in combinations(range(m), k):
+                A = list(A)
+                t = (np.dot(w[A], v[A]) - eta) / np.dot(w[A], w[A])
+                cand = np.zeros(m)
+                cand[A] = v[A] - t * w[A]
+                if t >= 0 and np.all(cand >= 0) and np.dot(w, cand) <= eta * (1 + 1e-12):
+                    d = np.sum((cand - v) ** 2)
+                    if d < best_d:
+                        best, best_d = cand, d
+        assert np.allclose(best, u, atol=1e-12)
+
+
+def test_bilevel_with_weighted_outer_norm():
+    """Alg. 1 with the weighted l1 ball as outer norm: the radii come from the weighted projection of
+    the aggregate, every column lands on (or inside) its own ball, the weighted norm of the result is eta."""
+    Y = RNG.standard_normal((30, 12)).astype(np.float32)
+    w = np.exp(RNG.uniform(-1, 1, 12))
+    for q in ("inf", 1, 2):
+        v = orc.column_norms(Y, q).astype(np.float64)
+        eta = 0.3 * float(np.sum(w * v))
+        out = orc.bilevel(Y, eta, q, p=("w1", w))
+        u, tau = orc.project_weighted_l1_ball_nonneg(v, w, eta)
+        assert np.allclose(np.asarray(out["u"], dtype=np.float64), u, rtol=1e-6) and out["tau"] == tau
+        vx = orc.column_norms(out["X"], q).astype(np.float64)
+        assert np.allclose(vx, u, rtol=1e-5, atol=1e-6)
+        assert np.dot(w, vx) == pytest.approx(eta, rel=1e-5)
+
