@@ -93,9 +93,11 @@ def time_kernels(torch, mp, fn, pairs, steps, warmup):
 
 
 def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, eta_abs=None, storage="f32",
-                  keep_output=False):
+                  keep_output=False, weighted=False):
     """storage "bf16" / "f16": the same matrix rounded to 16 bits, through bilevel_proj_stored
-    (half the bytes: 4 per element instead of 8 in the effective figures)."""
+    (half the bytes: 4 per element instead of 8 in the effective figures).
+    weighted: the weighted l1 ball as outer norm (fp32 storage), weights exp(U(-1, 1)) seeded by
+    the shape, eta = frac * sum_j w_j v_j."""
     import numpy as np
     dev = torch.device("cuda:0")
     n, m = Y_host.shape
@@ -111,6 +113,13 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
         eta = device_eta(mp, Y0.float(), variant, frac, ws) if eta_abs is None else float(eta_abs)
         q = {"l1inf": "inf", "l11": 1, "l12": 2}[variant]
         fn = lambda Y, eta, X, workspace, v_out=None: mp.bilevel_proj_stored(Y, eta, q, X=X, workspace=workspace, v_out=v_out)
+    elif weighted:
+        q = {"l1inf": "inf", "l11": 1, "l12": 2}[variant]
+        wts = torch.from_numpy(np.exp(np.random.default_rng([n, m, 17]).uniform(-1, 1, m)).astype(np.float32)).to(dev)
+        vbuf = torch.empty(m, dtype=torch.float32, device=dev)
+        mp.bilevel_proj_stored(Y0, 1.0, q, workspace=ws, v_out=vbuf)      # (only for v)
+        eta = float(np.float32(frac * float((wts.double() * vbuf.double()).sum().item())))
+        fn = lambda Y, eta, X, workspace, v_out=None: mp.bilevel_proj_weighted(Y, eta, q, wts, X=X, workspace=workspace, v_out=v_out)
     else:
         eta = device_eta(mp, Y0, variant, frac, ws) if eta_abs is None else float(eta_abs)
         fn = getattr(mp, "bilevel_proj_" + variant)
@@ -122,7 +131,8 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
     # against fp64 summation-order differences as long as this is far above 1e-13
     vbuf = torch.empty(m, dtype=torch.float32, device=dev)
     fn(pairs[0][0], eta, X=pairs[0][1], workspace=ws, v_out=vbuf)
-    margin = float(((vbuf.double() - res["tau"]).abs().min() / res["tau"]).item()) if res["tau"] > 0 else None
+    ratio = vbuf.double() / wts.double() if weighted else vbuf.double()    # column j is kept when v_j / w_j > tau
+    margin = float(((ratio - res["tau"]).abs().min() / res["tau"]).item()) if res["tau"] > 0 else None
     k_raw = time_kernels(torch, mp, lambda Y, X: fn(Y, eta, X=X, workspace=ws), pairs, min(steps, 100), min(warmup, 10))
     # Bracketing every kernel with events drains the queue around it, which adds the same
     # dispatch-from-idle latency to every interval; the untraced loop above has none of it.
@@ -355,6 +365,9 @@ def main():
         also["square_4096/l1inf/bf16"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, storage="bf16")
         also["square_4096/l12"] = bench_bilevel(torch, mp, Y, "l12", w.eta_frac, 100, 10)
         also["square_4096/l11"] = bench_bilevel(torch, mp, Y, "l11", w.eta_frac, 50, 5)
+        # the weighted l1 ball as outer norm (its own one-workgroup search kernel, nothing fused)
+        also["square_4096/l1inf/weighted"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, weighted=True)
+        also["square_4096/l11/weighted"] = bench_bilevel(torch, mp, Y, "l11", w.eta_frac, 50, 5, weighted=True)
         del Yb
         # the shape and distribution of the paper's own timing runs (Sec. 6.1): time against the radius
         wp, Yp = workloads.make("paper_1000x10000")

@@ -192,6 +192,27 @@ int bilevel_proj_stored(int storage, int outer_norm, int variant,
                         float* u_out /* device, m; may be NULL */,
                         unsigned char* mask_out /* device, m; may be NULL */, void* stream);
 
+/* BP^{p,q}_eta with the weighted l1 ball as outer norm, p = l_w1 (Sec. 3 lists it beside l1, l2
+ * and l_inf as an outer projection with a linear-time algorithm): v_j = ||y_j||_q as in
+ * bilevel_proj_stored, u = the Euclidean projection of v onto {u : sum_j w_j |u_j| <= eta}, that
+ * is u_j = max(v_j - tau w_j, 0) with tau = 0 when sum_j w_j v_j <= eta and otherwise the root of
+ * sum_j w_j max(v_j - tau w_j, 0) = eta; then x_j = P^q_{u_j}(y_j) (Eq. 8-9).  A larger w_j makes
+ * column j dearer to keep.  weights: m floats in device memory, read only, every one positive
+ * and finite (not checked: the call still ends with other values, with an unspecified result).
+ * The result record holds tau, norm = sum_j w_j v_j, vmax = max v_j, n_active = #{u_j > 0}; with
+ * eta = 0, tau = max_j v_j / w_j and X = 0.  All other arguments, the workspace size, alignment
+ * rules and error codes are those of bilevel_proj_stored; a NULL weights pointer is
+ * MLPROJ_ERR_NULL_POINTER.  With all weights 1 the result equals the plain l1 outer norm's to
+ * rounding (the threshold search sums in another order).                                    */
+int bilevel_proj_weighted(int storage, int variant,
+                          const void* Y /* device, n*m elements */, void* X /* device, n*m elements */,
+                          long long n, long long m, float eta,
+                          const float* weights /* device, m */,
+                          void* workspace /* device */, size_t workspace_bytes,
+                          float* v_out /* device, m; may be NULL */,
+                          float* u_out /* device, m; may be NULL */,
+                          unsigned char* mask_out /* device, m; may be NULL */, void* stream);
+
 /* One problem of a batch: the arguments of bilevel_proj_stored for one matrix. */
 typedef struct mlproj_problem {
   const void* Y;              /* device, n*m elements                               */

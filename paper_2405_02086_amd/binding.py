@@ -99,6 +99,8 @@ def lib():
     L.bilevel_proj_stored.argtypes = [c_i, c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.bilevel_proj_batch.restype = c_i
     L.bilevel_proj_batch.argtypes = [c_i, c_i, c_i, c_i, ctypes.POINTER(Problem), c_vp]
+    L.bilevel_proj_weighted.restype = c_i
+    L.bilevel_proj_weighted.argtypes = [c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.trilevel_proj_stored.restype = c_i
     L.trilevel_proj_stored.argtypes = [c_i, c_vp, c_vp, c_ll, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.trilevel_proj_l1infinf.restype = c_i
@@ -120,7 +122,7 @@ EXPORTS = (
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
     "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored", "mlproj_set_l11_sweeps",
-    "multilevel_proj_stored",
+    "multilevel_proj_stored", "bilevel_proj_weighted",
 )
 
 
@@ -278,6 +280,29 @@ def bilevel_proj_stored(Y, eta, q, p=1, X=None, workspace=None, v_out=None, u_ou
                                    ctypes.c_float(eta), _ptr(workspace.buf), workspace.nbytes, _ptr(v_out),
                                    _ptr(u_out), _ptr(mask_out), _stream(stream))
     _check(st, "bilevel_proj_stored")
+    return X
+
+
+def bilevel_proj_weighted(Y, eta, q, weights, X=None, workspace=None, v_out=None, u_out=None, mask_out=None,
+                          stream=None):
+    """BP^{p,q} with the weighted l1 ball {u : sum_j w_j |u_j| <= eta} as outer norm, on a contiguous
+    fp32, bf16 or fp16 device matrix; weights is an fp32 device tensor of m positive entries."""
+    import torch
+    storages = {torch.float32: STORE_F32, torch.bfloat16: STORE_BF16, torch.float16: STORE_F16}
+    assert Y.is_cuda and Y.dim() == 2 and Y.is_contiguous() and Y.dtype in storages
+    n, m = Y.shape
+    assert weights.is_cuda and weights.dtype == torch.float32 and weights.is_contiguous() and weights.numel() == m
+    if X is None:
+        X = torch.empty_like(Y)
+    assert X.is_cuda and X.dtype == Y.dtype and X.is_contiguous() and X.shape == Y.shape
+    assert mask_out is None or (mask_out.dtype == torch.uint8 and mask_out.numel() >= m)
+    variant = {"inf": L1INF, 1: L11, 2: L12}[q]
+    if workspace is None:
+        workspace = Workspace.for_call(variant, n, m, device=Y.device, stream=stream)
+    st = lib().bilevel_proj_weighted(storages[Y.dtype], variant, _ptr(Y), _ptr(X), n, m, ctypes.c_float(eta),
+                                     _ptr(weights), _ptr(workspace.buf), workspace.nbytes, _ptr(v_out),
+                                     _ptr(u_out), _ptr(mask_out), _stream(stream))
+    _check(st, "bilevel_proj_weighted")
     return X
 
 

@@ -57,7 +57,7 @@ struct Ws {
   mlproj_result* res;
   unsigned* pending;       // [MAX_INNER_SWEEPS + 1] l1,1: columns still searching before sweep s
   double* coop_d;          // [2][COOP_MAX_WGS] grid-wide search: per-workgroup sums, by parity
-  double* coop_m;          // [COOP_MAX_WGS]    per-workgroup maxima
+  double* coop_m;          // [4][COOP_MAX_WGS] per-workgroup maxima; weighted search: sums of w^2 (first round, then by parity)
   unsigned* coop_u;        // [2][COOP_MAX_WGS] per-workgroup counts, by parity
   unsigned* flags;         // [0] arrivals at the grid-wide search's barrier, [1] that search gave up
   double* v;               // [groups] aggregate, fp64 (exact for q = inf)
@@ -74,6 +74,7 @@ struct Ws {
   void* partial;           // [tiles][groups][tile_w] float (q = inf) or double
   unsigned* partial_cnt;   // [tiles][groups][tile_w] l1,1: entries above t
   unsigned* partial_cnt2;  // [tiles][groups][tile_w] l1,1: entries above t*(1 + L11_WINDOW)
+  const float* wts;        // [groups] weights of a weighted l1 ball as outer norm; null: the plain norms
 };
 
 struct Layout {
@@ -141,7 +142,7 @@ __host__ __device__ static inline Layout layout_for(const Geometry& g, long long
   size_t o = align_up(sizeof(mlproj_result), 256);
   L.off_pending = o;       o = align_up(o + (MAX_INNER_SWEEPS + 1) * 4, 256);
   L.off_coop_d = o;        o = align_up(o + 2 * COOP_MAX_WGS * 8, 256);
-  L.off_coop_m = o;        o = align_up(o + COOP_MAX_WGS * 8, 256);
+  L.off_coop_m = o;        o = align_up(o + 4 * COOP_MAX_WGS * 8, 256);
   L.off_coop_u = o;        o = align_up(o + 2 * COOP_MAX_WGS * 4, 256);
   L.off_flags = o;         o += 256;
   L.off_v = o;             o = align_up(o + (size_t)ngroups * 8, 256);
@@ -184,6 +185,7 @@ __host__ __device__ static inline Ws bind(void* workspace, const Layout& L) {
   w.partial = b + L.off_partial;
   w.partial_cnt = reinterpret_cast<unsigned*>(b + L.off_partial_cnt);
   w.partial_cnt2 = reinterpret_cast<unsigned*>(b + L.off_partial_cnt2);
+  w.wts = nullptr;
   w.tlo = reinterpret_cast<double*>(b + L.off_tlo);
   w.lb = reinterpret_cast<double*>(b + L.off_lb);
   w.ub = reinterpret_cast<double*>(b + L.off_ub);

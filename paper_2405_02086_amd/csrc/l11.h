@@ -328,7 +328,7 @@ __device__ __forceinline__ void l11_init_body(long long n, long long m, const Ws
   const long long j = bid * WG + threadIdx.x;
   if (j >= m) return;
   const double vj = ws.v[j];
-  const double uj = radius(vj, top);
+  const double uj = radius_of(ws, j, vj, top);
   double tj = HUGE_VAL, floor_t = HUGE_VAL;
   if (uj > 0.0) tj = l11_guess(vj, uj, n, floor_t);
   ws.tauj[j] = tj;
@@ -462,7 +462,7 @@ __device__ __forceinline__ void l11_update_body(long long n, long long m, const 
   double tau = 0.0, uj = 0.0, lo = 0.0, lb = 0.0, ub = 0.0;
   Window w{0.0, 0.0, NO_COUNT};
   if (mine) {
-    uj = radius(ws.v[j], top_of(res));
+    uj = radius_of(ws, j, ws.v[j], top_of(res));
     const double hi = ws.tauj[j];
     lo = ws.tlo[j];
     lb = ws.lb[j];
@@ -616,7 +616,7 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
       res->inner_finished = (o.inside != 0u) ? 0u : o.active;
     }
     if (o.inside != 0u || o.active == 0u) return;
-    mine = j < m && radius(ws.v[jj], top) > 0.0;
+    mine = j < m && radius_of(ws, jj, ws.v[jj], top) > 0.0;
   } else {
     if (res->inside_ball != 0u || res->n_active == 0u) return;
     // (no sweep at all, as planned for short matrices: every kept column is open, with the
@@ -632,7 +632,7 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
   bool open = mine;
   if (!__syncthreads_or(open ? 1 : 0)) return;
 
-  const double uj = radius(ws.v[jj], top);
+  const double uj = radius_of(ws, jj, ws.v[jj], top);
   // Start: the certified lower bound the sweeps reached.  Without any sweep the first point is
   // the seeding guess instead: the fixed-point step from ANY point lands at or left of the
   // root (see the note at the top), so one evaluation there gives a far better lower bound

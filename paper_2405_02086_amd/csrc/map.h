@@ -9,7 +9,7 @@
 namespace mlproj {
 
 // ------------------------------------------------------------------ per-column map
-// x_j = P^q_{u_j}(y_j) (Eq. 8-9) with u_j = max(v_j - tau, 0):
+// x_j = P^q_{u_j}(y_j) (Eq. 8-9) with u_j = max(v_j - tau, 0) (tau w_j for a weighted l1 ball):
 //   q = inf : X = sign(Y) min(|Y|, u_j)          (the symmetric clip; Sec. 4.1)
 //   q = 2   : X = Y * u_j / v_j
 //   q = 1   : X = sign(Y) max(|Y| - tau_j, 0)    with tau_j from the inner searches
@@ -68,7 +68,7 @@ __device__ __forceinline__ void colmap_body(const T* Y, T* X, long long n, long 
 #pragma unroll
   for (int k = 0; k < VEC; ++k) {
     const double vj = lc.ok[k] ? ws.v[lc.col(k)] : 0.0;
-    const double uj = radius(vj, top);
+    const double uj = lc.ok[k] ? radius_of(ws, lc.col(k), vj, top) : 0.0;
     uf[k] = (float)uj;
     if constexpr (Q == Q2) par[k] = vj > 0.0 ? uj / vj : 0.0;
     else if constexpr (Q == Q1) par[k] = inside ? 0.0 : ((uj > 0.0 && lc.ok[k]) ? ws.tauj[lc.col(k)] : HUGE_VAL);
@@ -92,7 +92,7 @@ __device__ __forceinline__ void colmap_body(const T* Y, T* X, long long n, long 
     if (mask_out) {  // the kept columns, decided where the radius is: in fp64
 #pragma unroll
       for (int k = 0; k < VEC; ++k)
-        if (lc.ok[k]) mask_out[lc.col(k)] = radius(ws.v[lc.col(k)], top) > 0.0 ? 1 : 0;
+        if (lc.ok[k]) mask_out[lc.col(k)] = radius_of(ws, lc.col(k), ws.v[lc.col(k)], top) > 0.0 ? 1 : 0;
     }
   }
 

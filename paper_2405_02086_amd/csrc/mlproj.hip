@@ -123,7 +123,7 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
   if (ngroups > (long long)SWG * SEARCH_CACHE && iterates) {
     long long nwg = cdiv(ngroups, (long long)SWG * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-    hipLaunchKernelGGL(search_wide_kernel, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
+    hipLaunchKernelGGL(search_wide_kernel<false>, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
     only_as_fallback = 1;
   }
   hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
@@ -154,9 +154,11 @@ template <int Q, typename T = float>
 static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
                        void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
                        void* stream_, int mode, double* norm_out, int stages, int outer,
-                       unsigned char* mask_out = nullptr, bool check_only = false) {
+                       unsigned char* mask_out = nullptr, bool check_only = false,
+                       const float* weights = nullptr) {
   constexpr int WIDE = 16 / (int)sizeof(T);
   if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
+  if (weights && (outer != MLPROJ_OUTER_L1 || mode != MODE_PROJECT || stages != STAGE_ALL)) return MLPROJ_ERR_BAD_VARIANT;
   const bool need_x = mode == MODE_PROJECT && (stages & STAGE_APPLY);
   if (!Y || !workspace || (need_x && !X)) return MLPROJ_ERR_NULL_POINTER;
   int st = check_dims(n, m, 1);
@@ -176,7 +178,8 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   const Layout L = layout_for(g, m, Q);
   if (workspace_bytes < L.bytes) return MLPROJ_ERR_WORKSPACE;
   if (check_only) return MLPROJ_OK;
-  const Ws ws = bind(workspace, L);
+  Ws ws = bind(workspace, L);
+  ws.wts = weights;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
   const dim3 mgrid((unsigned)(g.tiles * g.map_groups));
@@ -185,7 +188,8 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   // A whole call on few enough groups lets every map workgroup find tau by itself, which
   // takes the one-workgroup search kernel off the critical path (16 values of v per thread
   // up to 4096 groups, 64 per thread up to 16384).
-  const bool fuse = mode == MODE_PROJECT && stages == STAGE_ALL && Q != Q1 && m <= FUSED_SEARCH_MAX_BIG;
+  // (A weighted outer ball has its own search kernel: nothing is fused and no one-kernel form.)
+  const bool fuse = mode == MODE_PROJECT && stages == STAGE_ALL && Q != Q1 && m <= FUSED_SEARCH_MAX_BIG && !weights;
   const bool fuse_big = fuse && m > FUSED_SEARCH_MAX;
   const double fused_eta = fuse ? (double)eta : -1.0;
 
@@ -193,7 +197,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     // a matrix of at most 128 KiB that is not projected in place: one kernel does it all
     TinyPlan tp;
     const bool apart = X && (X + n * m <= Y || Y + n * m <= X);
-    if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && apart && tiny_plan(n, m, WIDE, &tp)) {
+    if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && apart && !weights && tiny_plan(n, m, WIDE, &tp)) {
       mark(stream);
       hipLaunchKernelGGL((tiny_kernel<Q, T, WIDE>), dim3((unsigned)tp.slots), dim3(TINY_WG), 0, stream, Y, X, n, m,
                          (double)eta, outer, tp.cw, ws, v_out, u_out, mask_out);
@@ -210,8 +214,26 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     mark(stream);
     hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
     // (l1,1: the kernel that seeds the inner searches runs the outer search the same way)
-    const bool fuse_l11 = Q == Q1 && mode == MODE_PROJECT && m <= FUSED_SEARCH_MAX_BIG;
-    if (!fuse && !fuse_l11) {
+    const bool fuse_l11 = Q == Q1 && mode == MODE_PROJECT && m <= FUSED_SEARCH_MAX_BIG && !weights;
+    if (weights) {
+      mark(stream);
+      // (one workgroup re-reads what its registers do not hold in every round: beyond 32768
+      // columns the grid-wide form goes first, with this one as its fallback)
+      int only_as_fallback = 0;
+      if (m > 32768) {
+        long long nwg = cdiv(m, (long long)SWG * COOP_VALUES);
+        if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
+        hipLaunchKernelGGL(search_wide_kernel<true>, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, m, (double)eta,
+                           (int)MODE_PROJECT, (double*)nullptr);
+        only_as_fallback = 1;
+      }
+      if (m <= 4096)
+        hipLaunchKernelGGL((search_weighted_kernel<256, 16>), dim3(1), dim3(256), 0, stream, ws, m, (double)eta, only_as_fallback);
+      else if (m <= 16384)
+        hipLaunchKernelGGL((search_weighted_kernel<256, 64>), dim3(1), dim3(256), 0, stream, ws, m, (double)eta, only_as_fallback);
+      else
+        hipLaunchKernelGGL((search_weighted_kernel<SWG, 16>), dim3(1), dim3(SWG), 0, stream, ws, m, (double)eta, only_as_fallback);
+    } else if (!fuse && !fuse_l11) {
       mark(stream);
       launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
     }
@@ -707,7 +729,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 344; }
+int mlproj_version(void) { return 345; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -824,6 +846,25 @@ int bilevel_proj_stored(int storage, int outer_norm, int variant, const void* Y,
       return dispatch_stored<bf16_t>(outer_norm, variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
     case MLPROJ_STORE_F16:
       return dispatch_stored<f16_t>(outer_norm, variant, Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, mask_out, stream);
+    default: return MLPROJ_ERR_BAD_VARIANT;
+  }
+}
+
+int bilevel_proj_weighted(int storage, int variant, const void* Y, void* X, long long n, long long m,
+                          float eta, const float* weights, void* workspace, size_t workspace_bytes,
+                          float* v_out, float* u_out, unsigned char* mask_out, void* stream) {
+  if (!weights) return MLPROJ_ERR_NULL_POINTER;
+  if (!aligned(weights, sizeof(float))) return MLPROJ_ERR_ALIGNMENT;
+  auto go = [&](auto tag) {
+    using T = decltype(tag);
+    return dispatch_q(variant, static_cast<const T*>(Y), static_cast<T*>(X), n, m, eta, workspace,
+                      workspace_bytes, v_out, u_out, stream, MODE_PROJECT, (double*)nullptr, STAGE_ALL,
+                      (int)MLPROJ_OUTER_L1, mask_out, false, weights);
+  };
+  switch (storage) {
+    case MLPROJ_STORE_F32: return go(float{});
+    case MLPROJ_STORE_BF16: return go(bf16_t{});
+    case MLPROJ_STORE_F16: return go(f16_t{});
     default: return MLPROJ_ERR_BAD_VARIANT;
   }
 }

@@ -110,14 +110,15 @@ struct PairScratch {
   double b[NW];
   unsigned u[NW];
 };
-template <int NW>
+// (AT_ONCE: how many waves' pairs are fetched together; fewer where registers are short)
+template <int NW, int AT_ONCE = NW>
 __device__ __forceinline__ void block_sum_max(double& sum, double& mx, PairScratch<NW>& s) {
   sum = wave_sum(sum);
   mx = wave_max(mx);
   if ((threadIdx.x & (WAVE - 1)) == 0) { s.a[threadIdx.x / WAVE] = sum; s.b[threadIdx.x / WAVE] = mx; }
   __syncthreads();
   double r = 0.0, q = 0.0;
-#pragma unroll
+#pragma unroll AT_ONCE
   for (int w = 0; w < NW; ++w) { r += s.a[w]; q = fmax(q, s.b[w]); }
   __syncthreads();
   sum = r;
@@ -135,6 +136,26 @@ __device__ __forceinline__ void block_sum_count(double& sum, unsigned& cnt, Pair
   for (int w = 0; w < NW; ++w) { r += s.a[w]; c += s.u[w]; }
   __syncthreads();
   sum = r;
+  cnt = c;
+}
+
+// ... and (sum, sum, count), for the weighted threshold search.
+template <int NW>
+__device__ __forceinline__ void block_sum2_count(double& sum, double& sum2, unsigned& cnt, PairScratch<NW>& s) {
+  sum = wave_sum(sum);
+  sum2 = wave_sum(sum2);
+  cnt = wave_sum_u(cnt);
+  if ((threadIdx.x & (WAVE - 1)) == 0) {
+    s.a[threadIdx.x / WAVE] = sum; s.b[threadIdx.x / WAVE] = sum2; s.u[threadIdx.x / WAVE] = cnt;
+  }
+  __syncthreads();
+  double r = 0.0, q = 0.0;
+  unsigned c = 0;
+#pragma unroll 4   // (all 16 triples at once would take 80 registers)
+  for (int w = 0; w < NW; ++w) { r += s.a[w]; q += s.b[w]; c += s.u[w]; }
+  __syncthreads();
+  sum = r;
+  sum2 = q;
   cnt = c;
 }
 

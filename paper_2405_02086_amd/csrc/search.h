@@ -33,6 +33,13 @@ struct Top {
 __device__ __forceinline__ double radius(double v, const Top& t) {
   return fmin(t.cap, t.scale * fmax(v - t.tau, 0.0));
 }
+// The weighted l1 ball {u : sum_j w_j |u_j| <= eta} (the l_w1 norm Sec. 3 lists beside them)
+// shrinks group j by tau * w_j instead (scale is 1 there, except 0 with eta = 0: tau = max v_j / w_j
+// is a rounded quotient, and v_j - tau w_j could otherwise come out a rounding error above 0).
+// Without weights this is radius() above, bit for bit.
+__device__ __forceinline__ double radius_of(const Ws& ws, long long j, double v, const Top& t) {
+  return ws.wts ? t.scale * fmax(v - t.tau * (double)ws.wts[j], 0.0) : radius(v, t);
+}
 __device__ __forceinline__ Top top_of(const SearchOut& o) { return Top{o.tau, o.scale, o.cap}; }
 __device__ __forceinline__ Top top_of(const mlproj_result* r) { return Top{r->tau, r->scale, r->cap}; }
 
@@ -179,6 +186,109 @@ __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, d
   }
 }
 
+// ------------------------------------------------------------------ weighted threshold search
+// Euclidean projection of v >= 0 onto the weighted l1 ball {u : sum_j w_j u_j <= eta}, w > 0:
+// u_j = max(v_j - tau w_j, 0), with tau = 0 when sum w_j v_j <= eta and otherwise the root of
+// g(tau) = sum_j w_j max(v_j - tau w_j, 0) = eta.  g is convex, decreasing and piecewise linear,
+// and the fixed point tau <- (sum_A w_j v_j - eta) / sum_A w_j^2 over A = {v_j > tau w_j} is
+// Newton's step on it: started from the all-active value (a lower bound on the root) tau rises
+// monotonically, A only shrinks, and when it stops shrinking tau is exact for the final A.
+// One workgroup of NT threads; CACHE pairs (v_j, w_j) per thread stay in registers, longer
+// vectors are re-read from memory (the L2) in every round; beyond 32768 groups the host
+// enqueues the grid-wide form below first and this one as its fallback.  A round costs what the
+// workgroup issues, every wavefront repeating the last fold: 256 threads (one wavefront per
+// SIMD) take a third of the time of 1024 per round, so the host picks few threads with many
+// pairs each: 256 x 16 up to 4096 groups, 256 x 64 up to 16384 (6 and 14 us on an MI355X for
+// four rounds), 1024 x 16 beyond (512 x 64 spills).
+// The record gets norm = sum w_j v_j and vmax = max v_j; with eta = 0, tau = max v_j / w_j.
+template <int NT, int CACHE>
+__global__ __launch_bounds__(NT) void search_weighted_kernel(Ws ws, long long ngroups, double eta,
+                                                              int only_as_fallback) {
+  __shared__ PairScratch<NT / WAVE> s;
+  if (only_as_fallback && ws.flags[1] == 0u) return;
+  const long long tid = threadIdx.x;
+  const float* __restrict__ wts = ws.wts;
+  const double* __restrict__ v = ws.v;
+  double vr[CACHE];
+  float wr[CACHE];   // (as stored: widened where used, which keeps the pairs within the registers)
+  // every load is unconditional (a slot past the end re-reads the last pair and is then blanked),
+  // so all of them are in flight together
+#pragma unroll
+  for (int k = 0; k < CACHE; ++k) {
+    const long long i = tid + (long long)k * NT;
+    const long long ii = i < ngroups ? i : ngroups - 1;
+    vr[k] = v[ii];
+    wr[k] = wts[ii];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  double num = 0.0, den = 0.0, vmax = 0.0;
+#pragma unroll
+  for (int k = 0; k < CACHE; ++k) {
+    const bool ok = tid + (long long)k * NT < ngroups;
+    if (!ok) { vr[k] = 0.0; wr[k] = 1.0f; }   // 0 is never active: tau >= 0, w > 0 and the test is strict
+    const double w = (double)wr[k];
+    num = fma(w, vr[k], num);
+    den = ok ? fma(w, w, den) : den;
+    vmax = fmax(vmax, vr[k]);
+  }
+  for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
+    const double x = v[i], w = (double)wts[i];
+    num = fma(w, x, num);
+    den = fma(w, w, den);
+    vmax = fmax(vmax, x);
+  }
+  block_sum_max<NT / WAVE, 4>(num, vmax, s);
+  double none = 0.0;
+  block_sum_max<NT / WAVE, 4>(den, none, s);
+  SearchOut o;
+  o.total = num;
+  o.norm = num;
+  o.vmax = vmax;
+  o.tau = 0.0;
+  o.scale = 1.0;
+  o.cap = HUGE_VAL;
+  o.active = 0;
+  o.iters = 0;
+  o.inside = 0;
+  if (eta == 0.0) {
+    double rmax = 0.0, zero = 0.0;   // tau = max v_j / w_j: v_j - tau w_j <= 0 for every j
+    for (long long i = tid; i < ngroups; i += NT) rmax = fmax(rmax, v[i] / (double)wts[i]);
+    block_sum_max<NT / WAVE, 4>(zero, rmax, s);
+    o.tau = rmax;
+    o.scale = 0.0;   // (see radius_of)
+  } else {
+    const bool inside = num <= eta;
+    double tau = inside ? 0.0 : (num - eta) / den;
+    unsigned kprev = 0xffffffffu;
+    for (;;) {
+      double sn = 0.0, sd = 0.0;
+      unsigned cnt = 0;
+#pragma unroll
+      for (int k = 0; k < CACHE; ++k) {
+        float wf = wr[k];
+        asm volatile("" : "+v"(wf));   // (keeps the widening inside the loop: hoisted, the doubles spill)
+        const double w = (double)wf;
+        if (vr[k] > tau * w) { sn = fma(w, vr[k], sn); sd = fma(w, w, sd); ++cnt; }
+      }
+      for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
+        const double x = v[i], w = (double)wts[i];
+        if (x > tau * w) { sn = fma(w, x, sn); sd = fma(w, w, sd); ++cnt; }
+      }
+      block_sum2_count(sn, sd, cnt, s);
+      o.active = cnt;
+      if (inside || cnt == 0u || cnt == kprev) break;  // inside: one round, just to count
+      kprev = cnt;
+      const double t = (sn - eta) / sd;
+      if (t > tau) tau = t;
+      ++o.iters;
+    }
+    o.tau = tau;
+    o.inside = inside ? 1u : 0u;
+  }
+  if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
+  if (threadIdx.x == 0) write_result(ws, o, nullptr);
+}
+
 // The same search for very long v (more groups than one workgroup holds in registers): up to
 // 64 workgroups, each keeping its slice of v in registers.  Every round each workgroup files
 // the sum and count of its slice above tau, all wait at a barrier, and every workgroup adds up
@@ -225,6 +335,9 @@ __device__ __forceinline__ double get_f64(const double* p) {
       reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
 
+// WEIGHTED: the weighted l1 ball (see search_weighted_kernel): slices hold (v_j, w_j) pairs and
+// file a third number per round, the sum of w_j^2 over their active entries.
+template <bool WEIGHTED>
 __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngroups, double eta,
                                                           int mode, double* __restrict__ norm_out) {
   __shared__ PairScratch<SWAVES> s;
@@ -234,22 +347,66 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
   const long long chunk = (ngroups + nwg - 1) / nwg;
   const long long lo = (long long)wg * chunk;
   const long long hi = (lo + chunk < ngroups) ? lo + chunk : ngroups;
+  // coop_m: [0] maxima, [1] weighted: sums of w^2 (with eta = 0: maxima of v/w) of the first
+  // round, [2 + parity] weighted: per-round sums of w^2
+  double* const coop_w = ws.coop_m + COOP_MAX_WGS;
+  const double* __restrict__ v = ws.v;
+  const float* __restrict__ wts = ws.wts;
 
   double vr[COOP_VALUES];
-  double a = 0.0, mx = 0.0;
+  float wr[WEIGHTED ? COOP_VALUES : 1];
+  double a = 0.0, mx = 0.0, den = 0.0;   // a: sum of v, weighted: of w v
+  if constexpr (WEIGHTED) {
+    // every load is unconditional (a slot past the slice re-reads its last pair, or pair 0 for
+    // an empty slice, and is then blanked), so all of them are in flight together
+    const long long last = hi > lo ? hi - 1 : 0;
 #pragma unroll
-  for (int k = 0; k < COOP_VALUES; ++k) {
-    const long long i = lo + tid + (long long)k * SWG;
-    vr[k] = i < hi ? ws.v[i] : 0.0;
-    a += vr[k];
-    mx = fmax(mx, vr[k]);
+    for (int k = 0; k < COOP_VALUES; ++k) {
+      const long long i = lo + tid + (long long)k * SWG;
+      const long long ii = i < hi ? i : last;
+      vr[k] = v[ii];
+      wr[k] = wts[ii];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < COOP_VALUES; ++k) {
+      const bool ok = lo + tid + (long long)k * SWG < hi;
+      if (!ok) { vr[k] = 0.0; wr[k] = 1.0f; }
+      const double w = (double)wr[k];
+      a = fma(w, vr[k], a);
+      den = ok ? fma(w, w, den) : den;
+      mx = fmax(mx, vr[k]);
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < COOP_VALUES; ++k) {
+      const long long i = lo + tid + (long long)k * SWG;
+      vr[k] = i < hi ? v[i] : 0.0;
+      a += vr[k];
+      mx = fmax(mx, vr[k]);
+    }
   }
   for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
-    const double x = ws.v[i];
-    a += x;
+    const double x = v[i];
+    if constexpr (WEIGHTED) {
+      const double w = (double)wts[i];
+      a = fma(w, x, a);
+      den = fma(w, w, den);
+    } else {
+      a += x;
+    }
     mx = fmax(mx, x);
   }
   block_sum_max(a, mx, s);
+  if constexpr (WEIGHTED) {
+    double rmax = 0.0;
+    if (eta == 0.0) {   // then tau = max v_j / w_j, and the sum of w^2 is not needed
+      // (read again rather than taken from the registers: unrolled, the divisions spill)
+      for (long long i = lo + tid; i < hi; i += SWG) rmax = fmax(rmax, v[i] / (double)wts[i]);
+    }
+    block_sum_max<SWAVES, 4>(den, rmax, s);
+    if (tid == 0) put_f64(&coop_w[wg], eta == 0.0 ? rmax : den);
+  }
   if (tid == 0) { put_f64(&ws.coop_d[wg], a); put_f64(&ws.coop_m[wg], mx); }
   unsigned round = 1;  // barrier rounds so far; parity 0 carries the totals
   if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
@@ -257,6 +414,12 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
   o.total = tid < nwg ? get_f64(&ws.coop_d[tid]) : 0.0;
   o.vmax = tid < nwg ? get_f64(&ws.coop_m[tid]) : 0.0;
   block_sum_max(o.total, o.vmax, s);
+  double den_all = 0.0, rmax_all = 0.0;
+  if constexpr (WEIGHTED) {
+    den_all = tid < nwg ? get_f64(&coop_w[tid]) : 0.0;
+    rmax_all = den_all;
+    block_sum_max<SWAVES, 4>(den_all, rmax_all, s);
+  }
   o.norm = o.total;
   o.tau = 0.0;
   o.scale = 1.0;
@@ -266,37 +429,60 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
   o.inside = 0;
   if (mode == MODE_NORM) {
   } else if (eta == 0.0) {
-    o.tau = o.vmax;
+    o.tau = WEIGHTED ? rmax_all : o.vmax;
+    if (WEIGHTED) o.scale = 0.0;   // (see radius_of)
   } else {
     const bool inside = o.total <= eta;
-    double tau = inside ? 0.0 : fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
+    double tau = inside ? 0.0
+               : WEIGHTED ? (o.total - eta) / den_all
+                          : fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
     unsigned kprev = 0xffffffffu;
     for (;;) {
-      double sum = 0.0;
+      double sum = 0.0, sd = 0.0;
       unsigned cnt = 0;
 #pragma unroll
       for (int k = 0; k < COOP_VALUES; ++k) {
-        if (vr[k] > tau) { sum += vr[k]; ++cnt; }
+        if constexpr (WEIGHTED) {
+          float wf = wr[k];
+          asm volatile("" : "+v"(wf));   // (keeps the widening inside the loop)
+          const double w = (double)wf;
+          if (vr[k] > tau * w) { sum = fma(w, vr[k], sum); sd = fma(w, w, sd); ++cnt; }
+        } else {
+          if (vr[k] > tau) { sum += vr[k]; ++cnt; }
+        }
       }
       for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
-        const double x = ws.v[i];
-        if (x > tau) { sum += x; ++cnt; }
+        const double x = v[i];
+        if constexpr (WEIGHTED) {
+          const double w = (double)wts[i];
+          if (x > tau * w) { sum = fma(w, x, sum); sd = fma(w, w, sd); ++cnt; }
+        } else {
+          if (x > tau) { sum += x; ++cnt; }
+        }
       }
-      block_sum_count(sum, cnt, s);
+      if constexpr (WEIGHTED) block_sum2_count(sum, sd, cnt, s);
+      else block_sum_count(sum, cnt, s);
       const unsigned par = round & 1u;
       if (tid == 0) {
         put_f64(&ws.coop_d[par * COOP_MAX_WGS + wg], sum);
+        if constexpr (WEIGHTED) put_f64(&coop_w[(1 + par) * COOP_MAX_WGS + wg], sd);
         __hip_atomic_exchange(&ws.coop_u[par * COOP_MAX_WGS + wg], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
       ++round;
       if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
       double S = tid < nwg ? get_f64(&ws.coop_d[par * COOP_MAX_WGS + tid]) : 0.0;
+      double D = 0.0;
       unsigned K = tid < nwg ? __hip_atomic_load(&ws.coop_u[par * COOP_MAX_WGS + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-      block_sum_count(S, K, s);
+      if constexpr (WEIGHTED) {
+        D = tid < nwg ? get_f64(&coop_w[(1 + par) * COOP_MAX_WGS + tid]) : 0.0;
+        block_sum2_count(S, D, K, s);
+      } else {
+        block_sum_count(S, K, s);
+      }
       o.active = K;
       if (inside || K == 0u || K == kprev) break;  // inside: one round, just to count
       kprev = K;
-      const double t = (S - eta) / (double)K;
+      const double t = WEIGHTED ? (S - eta) / D : (S - eta) / (double)K;
       if (t > tau) tau = t;
       ++o.iters;
     }

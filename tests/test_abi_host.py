@@ -157,6 +157,22 @@ def test_stored_entry_point_argument_checks(lib):
     assert st(0, 0, 0, odd2, FAKE, 4, 4, F(1), FAKE, big, None, None, None, None) == -7      # fp32 wants 4 bytes
 
 
+def test_weighted_entry_point_argument_checks(lib):
+    big = 1 << 30
+    wt = lib.bilevel_proj_weighted
+    odd2 = ctypes.c_void_p((1 << 20) + 2)
+    assert wt(0, 0, FAKE, FAKE, 4, 4, F(1), None, FAKE, big, None, None, None, None) == -1     # no weights
+    assert wt(0, 0, FAKE, FAKE, 4, 4, F(1), odd2, FAKE, big, None, None, None, None) == -7
+    assert wt(5, 0, FAKE, FAKE, 4, 4, F(1), FAKE, FAKE, big, None, None, None, None) == -6     # unknown storage
+    for storage in (0, 1, 2):
+        assert wt(storage, 0, None, FAKE, 4, 4, F(1), FAKE, FAKE, big, None, None, None, None) == -1
+        assert wt(storage, 0, FAKE, None, 4, 4, F(1), FAKE, FAKE, big, None, None, None, None) == -1
+        assert wt(storage, 3, FAKE, FAKE, 4, 4, F(1), FAKE, FAKE, big, None, None, None, None) == -6
+        assert wt(storage, 0, FAKE, FAKE, 0, 4, F(1), FAKE, FAKE, big, None, None, None, None) == -2
+        assert wt(storage, 1, FAKE, FAKE, 4, 4, F(float("nan")), FAKE, FAKE, big, None, None, None, None) == -4
+        assert wt(storage, 2, FAKE, FAKE, 4, 4, F(1), FAKE, FAKE, 64, None, None, None, None) == -5
+
+
 def test_batch_argument_checks(lib):
     big = 1 << 30
     bt = lib.bilevel_proj_batch

@@ -669,6 +669,125 @@ def test_stored_inplace_unaligned_outer_norms_and_degenerate(mp, storage, q):
     assert not got["X"].any() and not got["mask"].any()
 
 
+# ------------------------------------------------------------------ weighted l1 ball as outer norm
+def run_weighted(mp, Y, eta, q, storage, w, inplace=False, offset=0):
+    dev = torch.device("cuda:0")
+    dt = getattr(torch, STORE_DTYPES[storage])
+    n, m = Y.shape
+    ybuf = torch.zeros(n * m + 16, dtype=dt, device=dev)
+    Yd = ybuf[offset:offset + n * m].view(n, m)
+    Yd.copy_(torch.from_numpy(Y).to(dev))
+    v = torch.full((m,), -1.0, dtype=torch.float32, device=dev)
+    u = torch.full((m,), -1.0, dtype=torch.float32, device=dev)
+    mask = torch.full((m,), 7, dtype=torch.uint8, device=dev)
+    ws = mp.Workspace.for_call(QNAME[q], n, m, device=dev)
+    wd = torch.from_numpy(w).to(dev)
+    X = mp.bilevel_proj_weighted(Yd, eta, q, wd, X=Yd if inplace else None, workspace=ws, v_out=v, u_out=u,
+                                 mask_out=mask)
+    torch.cuda.synchronize()
+    assert np.array_equal(wd.cpu().numpy(), w), "the weights are read only"
+    return {"X": X.float().cpu().numpy(), "v": v.cpu().numpy(), "u": u.cpu().numpy(),
+            "mask": mask.cpu().numpy(), "res": ws.result()}
+
+
+def weights_for(m, seed, spread=1.0):
+    rng = np.random.default_rng([m, seed, 77])
+    return np.exp(rng.uniform(-spread, spread, m)).astype(np.float32)
+
+
+def weighted_eta(Y, q, w, frac):
+    v = orc.column_norms(Y, q).astype(np.float64)
+    return float(np.float32(frac * np.dot(w.astype(np.float64), v)))
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+@pytest.mark.parametrize("shape", [(1, 1), (9, 7), (256, 128), (300, 257), (2065, 264), (131, 1032), (40, 5000),
+                                   (1000, 1024), (5, 16388), (3, 40001), (2500, 260), (2, 70000), (3, 300001)])
+def test_weighted_outer_norm_matches_oracle(mp, storage, q, shape):
+    """Alg. 1 with the weighted l1 ball as outer norm (Sec. 3), against the sort-based oracle."""
+    Y = stored_input(shape, storage, 41)
+    w = weights_for(shape[1], 1)
+    for frac in (0.04, 0.5, 0.98):
+        eta = weighted_eta(Y, q, w, frac)
+        ref = orc.bilevel_stored(Y, eta, q, storage, p=("w1", w))
+        got = run_weighted(mp, Y, eta, q, storage, w)
+        check_stored(got, ref, q, storage)
+        assert got["res"]["norm"] == pytest.approx(np.dot(w.astype(np.float64), ref["v"].astype(np.float64)), rel=1e-6)
+
+
+@pytest.mark.parametrize("q", ["inf", 1, 2])
+def test_weighted_outer_norm_special_cases(mp, q):
+    Y = stored_input((333, 520), "f32", 42)
+    w = weights_for(520, 2, spread=3.0)         # weights over a range of 400 : 1
+    v = orc.column_norms(Y, q).astype(np.float64)
+    total = float(np.dot(w.astype(np.float64), v))
+    eta = float(np.float32(0.3 * total))
+    ref = orc.bilevel_stored(Y, eta, q, "f32", p=("w1", w))
+    check_stored(run_weighted(mp, Y, eta, q, "f32", w), ref, q, "f32")
+    check_stored(run_weighted(mp, Y, eta, q, "f32", w, inplace=True), ref, q, "f32")
+    check_stored(run_weighted(mp, Y, eta, q, "f32", w, offset=1), ref, q, "f32")       # the element-wise path
+    # inside the ball: nothing moves; radius 0: everything goes, tau = max v_j / w_j
+    got = run_weighted(mp, Y, float(np.float32(1.5 * total)), q, "f32", w)
+    assert np.array_equal(got["X"], Y) and got["mask"].all() and got["res"]["inside_ball"] and got["res"]["tau"] == 0.0
+    got = run_weighted(mp, Y, 0.0, q, "f32", w)
+    assert not got["X"].any() and not got["mask"].any()
+    assert got["res"]["tau"] == pytest.approx(np.max(v / w.astype(np.float64)), rel=1e-12)
+    # unit weights: the plain l1 outer norm (another summation order in the search: not bit for bit)
+    one = np.ones(520, dtype=np.float32)
+    eta = eta_for(Y, q, 0.3)
+    check_stored(run_weighted(mp, Y, eta, q, "f32", one), orc.bilevel_stored(Y, eta, q, "f32"), q, "f32")
+    # a tiny radius keeps the one column with the largest v_j / w_j
+    j = int(np.argmax(v / w.astype(np.float64)))
+    eta = float(np.float32(1e-4 * w[j] * v[j]))
+    got = run_weighted(mp, Y, eta, q, "f32", w)
+    check_stored(got, orc.bilevel_stored(Y, eta, q, "f32", p=("w1", w)), q, "f32")
+    assert got["mask"].sum() == 1 and got["mask"][j] == 1
+
+
+def test_weighted_outer_norm_special_cases_with_many_columns(mp):
+    """The grid-wide form of the weighted search (more than 32768 columns): inside the ball, radius 0,
+    a radius that keeps one column, unit weights."""
+    Y = stored_input((4, 100003), "f32", 43)
+    m = Y.shape[1]
+    w = weights_for(m, 3, spread=2.0)
+    for q in ("inf", 1):
+        v = orc.column_norms(Y, q).astype(np.float64)
+        total = float(np.dot(w.astype(np.float64), v))
+        got = run_weighted(mp, Y, float(np.float32(1.1 * total)), q, "f32", w)
+        assert np.array_equal(got["X"], Y) and got["mask"].all() and got["res"]["inside_ball"]
+        got = run_weighted(mp, Y, 0.0, q, "f32", w)
+        assert not got["X"].any() and not got["mask"].any()
+        assert got["res"]["tau"] == pytest.approx(np.max(v / w.astype(np.float64)), rel=1e-12)
+        j = int(np.argmax(v / w.astype(np.float64)))
+        eta = float(np.float32(1e-3 * w[j] * v[j]))
+        got = run_weighted(mp, Y, eta, q, "f32", w)
+        check_stored(got, orc.bilevel_stored(Y, eta, q, "f32", p=("w1", w)), q, "f32")
+        assert got["mask"].sum() == 1 and got["mask"][j] == 1
+        eta = eta_for(Y, q, 0.2)
+        one = np.ones(m, dtype=np.float32)
+        check_stored(run_weighted(mp, Y, eta, q, "f32", one), orc.bilevel_stored(Y, eta, q, "f32"), q, "f32")
+
+
+def test_weighted_outer_norm_random_cases(mp):
+    """Seeded random shapes, radii, value and weight distributions."""
+    for seed in range(40):
+        rng = np.random.default_rng([seed, 4242])
+        n, m = int(rng.integers(1, 700)), int(rng.integers(1, 3000))
+        q = ["inf", 1, 2][seed % 3]
+        kind = seed % 4
+        Y = (rng.standard_normal((n, m)) if kind < 2 else rng.laplace(size=(n, m)) ** 3).astype(np.float32)
+        if kind == 1:
+            Y *= (rng.random((1, m)) < 0.3)          # mostly empty columns
+        w = np.exp(rng.uniform(-2, 2, m)).astype(np.float32)
+        v = orc.column_norms(Y, q).astype(np.float64)
+        total = float(np.dot(w.astype(np.float64), v))
+        if total == 0.0:
+            continue
+        eta = float(np.float32(total * 10.0 ** rng.uniform(-4, 0)))
+        check_stored(run_weighted(mp, Y, eta, q, "f32", w), orc.bilevel_stored(Y, eta, q, "f32", p=("w1", w)), q, "f32")
+
+
 def test_stored_f32_is_the_fp32_entry_point_bit_for_bit(mp):
     dev = torch.device("cuda:0")
     for q in ("inf", 1, 2):
