@@ -213,6 +213,60 @@ def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
     return out
 
 
+def linear_fit(sizes, times_ms):
+    """Least squares time = a + b * elements: (a in us, b in ns per 1000 elements, R^2)."""
+    import numpy as np
+    x, y = np.asarray(sizes, dtype=np.float64), np.asarray(times_ms, dtype=np.float64) * 1e3
+    b, a = np.polyfit(x, y, 1)
+    r2 = 1.0 - float(((y - (a + b * x)) ** 2).sum() / ((y - y.mean()) ** 2).sum())
+    return {"intercept_us": float(a), "ns_per_1000_elements": float(b) * 1e6, "r2": r2}
+
+
+def bench_size_sweep(torch, mp, workloads, steps, warmup):
+    """The size sweeps of the paper's timing figures (Sec. 6.1) on U(0,1) entries: the bi-level
+    l1,inf projection at eta = 1 with 1000 columns and a growing number of rows, with 1000 rows and
+    a growing number of columns, and the tri-level l1,inf,inf and l1,1,1 projections of a tensor
+    of 32 channels x 1000 x m (here C-order (m, 1000, 32): groups on the first axis, the channel
+    axis innermost), eta = 0.2 * norm.  Cold timing (rotating buffers), with a straight-line fit."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    out = {}
+    for key, shapes in (("bilevel_l1inf/rows_x_1000", [(k * 1000, 1000) for k in (1, 2, 4, 8, 16, 32)]),
+                        ("bilevel_l1inf/1000_x_columns", [(1000, k * 1000) for k in (1, 2, 4, 8, 16, 32)])):
+        rows = []
+        for i, shape in enumerate(shapes):
+            Y = workloads.generate(shape, "uniform", workloads.BASE_SEED + 100 + i)
+            Y0 = torch.from_numpy(Y).to(dev)
+            npairs = max(2, -(-3 * INFINITY_CACHE_BYTES // (2 * Y.nbytes)))
+            pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
+            ws = mp.Workspace.for_call("l1inf", shape[0], shape[1], device=dev)
+            ms = time_calls(torch, lambda Yd, Xd: mp.bilevel_proj_l1inf(Yd, 1.0, X=Xd, workspace=ws), pairs, steps, warmup)
+            rows.append({"shape": list(shape), "ms": ms, "n_active": ws.result()["n_active"]})
+            del pairs, Y0
+            torch.cuda.empty_cache()
+        out[key] = {"eta": 1.0, "rows": rows,
+                    "fit": linear_fit([r["shape"][0] * r["shape"][1] for r in rows], [r["ms"] for r in rows])}
+    for name, norms in (("l1infinf", ["inf", "inf"]), ("l111", [1, 1])):
+        rows = []
+        for i, m in enumerate((250, 500, 1000, 2000)):
+            shape = (m, 1000, 32)
+            Y = workloads.generate(shape, "uniform", workloads.BASE_SEED + 200 + i)
+            Y0 = torch.from_numpy(Y).to(dev)
+            npairs = max(2, -(-3 * INFINITY_CACHE_BYTES // (2 * Y.nbytes)))
+            pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
+            ws = mp.Workspace(mp.multilevel_workspace_bytes(shape), device=dev)
+            mp.multilevel_proj(pairs[0][0], norms, 3.0e38, X=pairs[0][1], workspace=ws)
+            torch.cuda.synchronize()
+            eta = float(np.float32(0.2 * ws.result()["norm"]))
+            ms = time_calls(torch, lambda Yd, Xd: mp.multilevel_proj(Yd, norms, eta, X=Xd, workspace=ws), pairs, steps, warmup)
+            rows.append({"shape": list(shape), "eta": eta, "ms": ms, "n_active": ws.result()["n_active"]})
+            del pairs, Y0
+            torch.cuda.empty_cache()
+        out["trilevel_" + name + "/m_x_1000_x_32"] = {
+            "rows": rows, "fit": linear_fit([r["shape"][0] * 32000 for r in rows], [r["ms"] for r in rows])}
+    return out
+
+
 def bench_small(torch, mp, Y_host, frac, steps, warmup):
     """The small workload is launch-bound: eager calls against replays of one call captured in a
     HIP graph (what the three kernels cost once the host is out of the way)."""
@@ -393,6 +447,7 @@ def main():
         also["batch/6x(4096x4096)"] = bench_batch(torch, mp, (4096, 4096), 6, 0.3, 30, 3)
         also["batch/16x(256x128)/l11"] = bench_batch(torch, mp, (256, 128), 16, 0.1, 100, 10, "l11")
         also["batch/16x(1024x1024)/l11"] = bench_batch(torch, mp, (1024, 1024), 16, 0.1, 100, 10, "l11")
+        also["paper_size_sweep"] = bench_size_sweep(torch, mp, workloads, 50, 5)
         line["also"] = also
     if want_cpu:
         line["cpu_baseline"] = cpu_baseline(Y, head["eta"], x_timed, head["tau"])
