@@ -93,7 +93,7 @@ __device__ __forceinline__ void reduce_body(const void* __restrict__ partial_, l
                                             unsigned* __restrict__ flags, long long bid) {
   using Acc = typename AccOf<Q>::type;
   __shared__ Acc sm[SWG];
-  if (bid == 0 && threadIdx.x < 2) flags[threadIdx.x] = 0u;  // for the grid-wide search
+  if (bid == 0) clear_meeting_area(flags);  // for the grid-wide search
   const int cols = SWG / parts;
   const int c_local = threadIdx.x % cols;
   const int part = threadIdx.x / cols;

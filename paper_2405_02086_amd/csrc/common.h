@@ -33,8 +33,12 @@ constexpr int MAP_RBLK = WAVES * MAP_UNROLL;
 constexpr long long TARGET_WGS = 512;    // workgroups of a read-only pass on 256 CUs (2 per CU)
 constexpr long long TARGET_WGS_MAP = 256;  // workgroups of the read+write pass (1 per CU)
 constexpr int COOP_MAX_WGS = 64;         // workgroups of the grid-wide search (far fewer than CUs)
-constexpr int COOP_VALUES = 8;           // values of v per thread there
-constexpr unsigned SPIN_LIMIT = 1u << 22; // polls before a waiting workgroup gives up (~0.1 s)
+constexpr int COOP_THREADS = 256;        // threads of each of them
+constexpr int COOP_VALUES = 32;          // values of v per thread there
+constexpr unsigned SPIN_LIMIT = 1u << 22; // polls before a waiting workgroup gives up (seconds)
+constexpr int COOP_WORDS = 6;            // 64-bit words a workgroup posts per round there (tag and 32 bits of payload each)
+constexpr int COOP_SLOT_WORDS = 2 * COOP_WORDS * COOP_MAX_WGS;
+constexpr int COOP_FLAG_BYTES = 256;
 constexpr long long FUSED_SEARCH_MAX = (long long)WG * SEARCH_CACHE;  // groups a map workgroup can search in registers
 constexpr int SEARCH_CACHE_BIG = 64;     // ... the same with four times the registers, for up to 16384 groups
 constexpr long long FUSED_SEARCH_MAX_BIG = (long long)WG * SEARCH_CACHE_BIG;
@@ -56,10 +60,8 @@ struct Geometry {
 struct Ws {
   mlproj_result* res;
   unsigned* pending;       // [MAX_INNER_SWEEPS + 1] l1,1: columns still searching before sweep s
-  double* coop_d;          // [2][COOP_MAX_WGS] grid-wide search: per-workgroup sums, by parity
-  double* coop_m;          // [4][COOP_MAX_WGS] per-workgroup maxima; weighted search: sums of w^2 (first round, then by parity)
-  unsigned* coop_u;        // [2][COOP_MAX_WGS] per-workgroup counts, by parity
-  unsigned* flags;         // [0] arrivals at the grid-wide search's barrier, [1] that search gave up
+  unsigned* flags;         // [1] the grid-wide search gave up ([0] spare); 256 bytes, and right behind them:
+  unsigned long long* coop_q;  // [2][COOP_WORDS][COOP_MAX_WGS] grid-wide search: what the workgroups post per round, by parity
   double* v;               // [groups] aggregate, fp64 (exact for q = inf)
   double* tauj;            // [m] l1,1 inner thresholds: the point the next sweep evaluates, then the result
   double* tlo;             // [m] l1,1: lower end of the window whose entries the next sweep lists
@@ -78,7 +80,7 @@ struct Ws {
 };
 
 struct Layout {
-  size_t off_pending, off_coop_d, off_coop_m, off_coop_u, off_flags, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, off_partial_cnt2, bytes;
+  size_t off_pending, off_flags, off_coop_q, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, off_partial_cnt2, bytes;
   size_t off_tlo, off_lb, off_ub, off_done, off_gcnt, off_gflag, off_cand;
   int list_cap;
 };
@@ -141,10 +143,8 @@ __host__ __device__ static inline Layout layout_for(const Geometry& g, long long
   Layout L{};
   size_t o = align_up(sizeof(mlproj_result), 256);
   L.off_pending = o;       o = align_up(o + (MAX_INNER_SWEEPS + 1) * 4, 256);
-  L.off_coop_d = o;        o = align_up(o + 2 * COOP_MAX_WGS * 8, 256);
-  L.off_coop_m = o;        o = align_up(o + 4 * COOP_MAX_WGS * 8, 256);
-  L.off_coop_u = o;        o = align_up(o + 2 * COOP_MAX_WGS * 4, 256);
-  L.off_flags = o;         o += 256;
+  L.off_flags = o;         o += COOP_FLAG_BYTES;
+  L.off_coop_q = o;        o = align_up(o + (size_t)COOP_SLOT_WORDS * 8, 256);   // (must follow the flags: see clear_meeting_area)
   L.off_v = o;             o = align_up(o + (size_t)ngroups * 8, 256);
   L.off_tauj = o;          o = align_up(o + (variant == Q1 ? (size_t)ngroups * 8 : 0), 256);
   L.off_kprev = o;         o = align_up(o + (variant == Q1 ? (size_t)ngroups * 4 : 0), 256);
@@ -175,9 +175,7 @@ __host__ __device__ static inline Ws bind(void* workspace, const Layout& L) {
   Ws w;
   w.res = reinterpret_cast<mlproj_result*>(b);
   w.pending = reinterpret_cast<unsigned*>(b + L.off_pending);
-  w.coop_d = reinterpret_cast<double*>(b + L.off_coop_d);
-  w.coop_m = reinterpret_cast<double*>(b + L.off_coop_m);
-  w.coop_u = reinterpret_cast<unsigned*>(b + L.off_coop_u);
+  w.coop_q = reinterpret_cast<unsigned long long*>(b + L.off_coop_q);
   w.flags = reinterpret_cast<unsigned*>(b + L.off_flags);
   w.v = reinterpret_cast<double*>(b + L.off_v);
   w.tauj = reinterpret_cast<double*>(b + L.off_tauj);
@@ -195,6 +193,15 @@ __host__ __device__ static inline Ws bind(void* workspace, const Layout& L) {
   w.cand = reinterpret_cast<float*>(b + L.off_cand);
   w.list_cap = L.list_cap;
   return w;
+}
+
+// The grid-wide search's meeting area: the flags, and behind them the slots its workgroups post
+// into.  Cleared by one whole workgroup of a kernel that runs before the search in every call
+// (a stale tag from an earlier call would pass for a posted word).
+__device__ __forceinline__ void clear_meeting_area(unsigned* flags) {
+  if (threadIdx.x < 2) flags[threadIdx.x] = 0u;
+  unsigned long long* q = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(flags) + COOP_FLAG_BYTES);
+  for (int i = threadIdx.x; i < COOP_SLOT_WORDS; i += blockDim.x) q[i] = 0ull;
 }
 
 // ------------------------------------------------------------------ device helpers

@@ -156,9 +156,7 @@ __global__ __launch_bounds__(WG) void fibre_agg_short_kernel(const TIN* __restri
   }
 }
 
-__global__ void clear_flags_kernel(Ws ws) {
-  if (threadIdx.x < 2) ws.flags[threadIdx.x] = 0u;
-}
+__global__ void clear_flags_kernel(Ws ws) { clear_meeting_area(ws.flags); }
 
 // Radii of the top level from the threshold: R[a] = max(w[a] - tau, 0).
 __global__ __launch_bounds__(WG) void top_radii_kernel(Ws ws, long long d0, double* __restrict__ R,

@@ -121,9 +121,9 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
     return;
   }
   if (ngroups > (long long)SWG * SEARCH_CACHE && iterates) {
-    long long nwg = cdiv(ngroups, (long long)SWG * COOP_VALUES);
+    long long nwg = cdiv(ngroups, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-    hipLaunchKernelGGL(search_wide_kernel<false>, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, ngroups, eta, mode, norm_out);
+    hipLaunchKernelGGL((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, ngroups, eta, mode, norm_out);
     only_as_fallback = 1;
   }
   hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
@@ -221,10 +221,10 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       // columns the grid-wide form goes first, with this one as its fallback)
       int only_as_fallback = 0;
       if (m > 32768) {
-        long long nwg = cdiv(m, (long long)SWG * COOP_VALUES);
+        long long nwg = cdiv(m, (long long)COOP_THREADS * COOP_VALUES);
         if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-        hipLaunchKernelGGL(search_wide_kernel<true>, dim3((unsigned)nwg), dim3(SWG), 0, stream, ws, m, (double)eta,
-                           (int)MODE_PROJECT, (double*)nullptr);
+        hipLaunchKernelGGL((search_wide_kernel<true, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, m,
+                           (double)eta, (int)MODE_PROJECT, (double*)nullptr);
         only_as_fallback = 1;
       }
       if (m <= 4096)
@@ -696,7 +696,7 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
     hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
                        outer, (double*)nullptr, 0, R[ndim - 1], u_out);
   } else {
-    hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WAVE), 0, stream, ws);
+    hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WG), 0, stream, ws);
     launch_search(ws, dims[0], (double)eta, MODE_PROJECT, outer, nullptr, stream);
     hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
                        dims[0], R[ndim - 1], u_out);
@@ -729,7 +729,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 345; }
+int mlproj_version(void) { return 346; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

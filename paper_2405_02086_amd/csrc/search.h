@@ -290,103 +290,123 @@ __global__ __launch_bounds__(NT) void search_weighted_kernel(Ws ws, long long ng
 }
 
 // The same search for very long v (more groups than one workgroup holds in registers): up to
-// 64 workgroups, each keeping its slice of v in registers.  Every round each workgroup files
-// the sum and count of its slice above tau, all wait at a barrier, and every workgroup adds up
-// all slices in the same fixed order, so all of them step tau identically and leave the loop
-// together.  Slots alternate by round parity so that a fast workgroup never overwrites what a
-// slow one is still reading.
+// 64 workgroups of NT threads, each keeping its slice of v in registers (VALUES per thread).
+// As in the one-workgroup kernels a round costs what a workgroup issues, so the host launches
+// 256 threads with 32 values each rather than 1024 with 8.
+// Every round each workgroup posts the sum and count of its slice above tau, every workgroup
+// collects all the posts and adds them up in the same fixed order, so all of them step tau
+// identically and leave the loop together.
 //
-// The barrier is built for this GPU, where a device-scope fence means an L2 write-back
-// (microseconds, and it serialises): everything the workgroups exchange -- the slots and the
-// arrival counter -- is written with device-scope atomic read-modify-writes, which are
-// performed at the memory side, and read with device-scope atomic loads, which bypass the
-// per-XCD L2; "s_waitcnt vmcnt(0)" makes a wavefront's slot writes complete before its
-// arrival is counted.  No ordinary load or store takes part, so no cache has to be flushed.
-// The grid is far smaller than the chip, so all workgroups become resident; a workgroup that
-// nevertheless waits SPIN_LIMIT polls raises flags[1] and everybody leaves: the kernel always
-// ends, and the one-workgroup search_kernel queued behind it then does the work instead.
-__device__ __forceinline__ bool wide_barrier(unsigned* flags, unsigned target, unsigned* lds_ok) {
-  if (threadIdx.x == 0) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __hip_atomic_fetch_add(&flags[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned spins = 0, ok = 1;
-    while (__hip_atomic_load(&flags[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      if (__hip_atomic_load(&flags[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u || ++spins > SPIN_LIMIT) {
-        ok = 0;
+// The exchange is built for this GPU, where a device-scope fence means an L2 write-back
+// (microseconds, and it serialises).  A post is a handful of 64-bit words, each carrying the
+// round number in its upper half and 32 bits of payload in its lower half, written with
+// device-scope atomic exchanges (performed at the memory side) and never waited for; lane g of
+// the first wavefront polls workgroup g's words with device-scope atomic loads (which bypass
+// the per-XCD L2) until every one carries the current round number.  A word is complete or
+// absent, so neither an arrival counter nor an ordering between the words is needed, and a
+// round costs one write and one read latency.  Slots alternate by round parity: a workgroup can
+// post round r + 2 only after it has collected round r + 1, which every workgroup posts only
+// after collecting round r, so nobody overwrites what another still reads.  The slots start
+// cleared (clear_meeting_area, in a kernel that precedes this one in every call).
+// The grid is far smaller than the chip, so all workgroups become resident; a lane that
+// nevertheless polls SPIN_LIMIT times raises flags[1], every poller sees that and everybody
+// leaves: the kernel always ends, and the one-workgroup kernel queued behind it then does the
+// work instead.
+__device__ __forceinline__ void post_word(unsigned long long* q, unsigned round, unsigned payload) {
+  __hip_atomic_exchange(q, ((unsigned long long)round << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned lo32(double x) { return (unsigned)(unsigned long long)__double_as_longlong(x); }
+__device__ __forceinline__ unsigned hi32(double x) { return (unsigned)((unsigned long long)__double_as_longlong(x) >> 32); }
+__device__ __forceinline__ double from32(unsigned lo, unsigned hi) {
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// Collect W words of every workgroup's post of this round into pay[] of lane g (zeros in the
+// other lanes).  False, for every thread of the workgroup alike, when the search gives up.
+template <int W>
+__device__ __forceinline__ bool collect(const unsigned long long* q, unsigned* flags, unsigned round,
+                                        int nwg, unsigned (&pay)[W], unsigned* lds_ok) {
+  if (threadIdx.x == 0) *lds_ok = 1u;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < W; ++w) pay[w] = 0u;
+  if ((int)threadIdx.x < nwg) {
+    unsigned spins = 0;
+    bool ok = true;
+    for (;;) {
+      bool all = true;
+#pragma unroll
+      for (int w = 0; w < W; ++w) {
+        const unsigned long long x = __hip_atomic_load(&q[w * COOP_MAX_WGS + threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        all = all && (unsigned)(x >> 32) == round;
+        pay[w] = (unsigned)x;
+      }
+      if (all) break;
+      if ((++spins & 63u) == 0u &&
+          (spins > SPIN_LIMIT || __hip_atomic_load(&flags[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
+        ok = false;
         break;
       }
       __builtin_amdgcn_s_sleep(1);
     }
-    if (!ok) __hip_atomic_exchange(&flags[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *lds_ok = ok;
+    if (!ok) {
+      __hip_atomic_exchange(&flags[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *lds_ok = 0u;
+    }
   }
   __syncthreads();
   const bool ok = *lds_ok != 0u;
   __syncthreads();
   return ok;
 }
-__device__ __forceinline__ void put_f64(double* p, double x) {
-  __hip_atomic_exchange(reinterpret_cast<unsigned long long*>(p),
-                        (unsigned long long)__double_as_longlong(x), __ATOMIC_RELAXED,
-                        __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ double get_f64(const double* p) {
-  return __longlong_as_double((long long)__hip_atomic_load(
-      reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-}
 
 // WEIGHTED: the weighted l1 ball (see search_weighted_kernel): slices hold (v_j, w_j) pairs and
-// file a third number per round, the sum of w_j^2 over their active entries.
-template <bool WEIGHTED>
-__global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngroups, double eta,
+// post a third number per round, the sum of w_j^2 over their active entries.
+template <bool WEIGHTED, int NT, int VALUES>
+__global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroups, double eta,
                                                           int mode, double* __restrict__ norm_out) {
-  __shared__ PairScratch<SWAVES> s;
+  static_assert(NT >= COOP_MAX_WGS, "one lane per workgroup collects its post");
+  __shared__ PairScratch<NT / WAVE> s;
   __shared__ unsigned lds_ok;
   const int tid = threadIdx.x;
   const int nwg = (int)gridDim.x, wg = (int)blockIdx.x;
   const long long chunk = (ngroups + nwg - 1) / nwg;
   const long long lo = (long long)wg * chunk;
   const long long hi = (lo + chunk < ngroups) ? lo + chunk : ngroups;
-  // coop_m: [0] maxima, [1] weighted: sums of w^2 (with eta = 0: maxima of v/w) of the first
-  // round, [2 + parity] weighted: per-round sums of w^2
-  double* const coop_w = ws.coop_m + COOP_MAX_WGS;
   const double* __restrict__ v = ws.v;
   const float* __restrict__ wts = ws.wts;
+  // word w of workgroup g in the slots of parity p
+  auto slot = [&](unsigned p, int w, int g) { return ws.coop_q + ((size_t)p * COOP_WORDS + w) * COOP_MAX_WGS + g; };
 
-  double vr[COOP_VALUES];
-  float wr[WEIGHTED ? COOP_VALUES : 1];
+  double vr[VALUES];
+  float wr[WEIGHTED ? VALUES : 1];
   double a = 0.0, mx = 0.0, den = 0.0;   // a: sum of v, weighted: of w v
-  if constexpr (WEIGHTED) {
-    // every load is unconditional (a slot past the slice re-reads its last pair, or pair 0 for
-    // an empty slice, and is then blanked), so all of them are in flight together
-    const long long last = hi > lo ? hi - 1 : 0;
+  // every load is unconditional (a slot past the slice re-reads its last entry, or entry 0 for
+  // an empty slice, and is then blanked), so all of them are in flight together
+  const long long last = hi > lo ? hi - 1 : 0;
 #pragma unroll
-    for (int k = 0; k < COOP_VALUES; ++k) {
-      const long long i = lo + tid + (long long)k * SWG;
-      const long long ii = i < hi ? i : last;
-      vr[k] = v[ii];
-      wr[k] = wts[ii];
-    }
-    __builtin_amdgcn_sched_barrier(0);
+  for (int k = 0; k < VALUES; ++k) {
+    const long long i = lo + tid + (long long)k * NT;
+    const long long ii = i < hi ? i : last;
+    vr[k] = v[ii];
+    if constexpr (WEIGHTED) wr[k] = wts[ii];
+  }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int k = 0; k < COOP_VALUES; ++k) {
-      const bool ok = lo + tid + (long long)k * SWG < hi;
-      if (!ok) { vr[k] = 0.0; wr[k] = 1.0f; }
+  for (int k = 0; k < VALUES; ++k) {
+    const bool ok = lo + tid + (long long)k * NT < hi;
+    if (!ok) vr[k] = 0.0;
+    if constexpr (WEIGHTED) {
+      if (!ok) wr[k] = 1.0f;
       const double w = (double)wr[k];
       a = fma(w, vr[k], a);
       den = ok ? fma(w, w, den) : den;
-      mx = fmax(mx, vr[k]);
-    }
-  } else {
-#pragma unroll
-    for (int k = 0; k < COOP_VALUES; ++k) {
-      const long long i = lo + tid + (long long)k * SWG;
-      vr[k] = i < hi ? v[i] : 0.0;
+    } else {
       a += vr[k];
-      mx = fmax(mx, vr[k]);
     }
+    mx = fmax(mx, vr[k]);
   }
-  for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
+  for (long long i = lo + tid + (long long)VALUES * NT; i < hi; i += NT) {
     const double x = v[i];
     if constexpr (WEIGHTED) {
       const double w = (double)wts[i];
@@ -398,27 +418,40 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
     mx = fmax(mx, x);
   }
   block_sum_max(a, mx, s);
+  double third = 0.0;   // weighted: the slice's sum of w^2, or with eta = 0 its maximum of v/w
   if constexpr (WEIGHTED) {
     double rmax = 0.0;
     if (eta == 0.0) {   // then tau = max v_j / w_j, and the sum of w^2 is not needed
       // (read again rather than taken from the registers: unrolled, the divisions spill)
-      for (long long i = lo + tid; i < hi; i += SWG) rmax = fmax(rmax, v[i] / (double)wts[i]);
+      for (long long i = lo + tid; i < hi; i += NT) rmax = fmax(rmax, v[i] / (double)wts[i]);
     }
-    block_sum_max<SWAVES, 4>(den, rmax, s);
-    if (tid == 0) put_f64(&coop_w[wg], eta == 0.0 ? rmax : den);
+    block_sum_max<NT / WAVE, 4>(den, rmax, s);
+    third = eta == 0.0 ? rmax : den;
   }
-  if (tid == 0) { put_f64(&ws.coop_d[wg], a); put_f64(&ws.coop_m[wg], mx); }
-  unsigned round = 1;  // barrier rounds so far; parity 0 carries the totals
-  if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
+  unsigned round = 1;  // the first round carries the totals
+  if (tid == 0) {
+    post_word(slot(1u, 0, wg), round, lo32(a));
+    post_word(slot(1u, 1, wg), round, hi32(a));
+    post_word(slot(1u, 2, wg), round, lo32(mx));
+    post_word(slot(1u, 3, wg), round, hi32(mx));
+    if constexpr (WEIGHTED) {
+      post_word(slot(1u, 4, wg), round, lo32(third));
+      post_word(slot(1u, 5, wg), round, hi32(third));
+    }
+  }
   SearchOut o;
-  o.total = tid < nwg ? get_f64(&ws.coop_d[tid]) : 0.0;
-  o.vmax = tid < nwg ? get_f64(&ws.coop_m[tid]) : 0.0;
-  block_sum_max(o.total, o.vmax, s);
   double den_all = 0.0, rmax_all = 0.0;
-  if constexpr (WEIGHTED) {
-    den_all = tid < nwg ? get_f64(&coop_w[tid]) : 0.0;
-    rmax_all = den_all;
-    block_sum_max<SWAVES, 4>(den_all, rmax_all, s);
+  {
+    unsigned pay[WEIGHTED ? 6 : 4];
+    if (!collect(slot(1u, 0, 0), ws.flags, round, nwg, pay, &lds_ok)) return;
+    o.total = from32(pay[0], pay[1]);
+    o.vmax = from32(pay[2], pay[3]);
+    block_sum_max(o.total, o.vmax, s);
+    if constexpr (WEIGHTED) {
+      den_all = from32(pay[4], pay[5]);
+      rmax_all = den_all;
+      block_sum_max<NT / WAVE, 4>(den_all, rmax_all, s);
+    }
   }
   o.norm = o.total;
   o.tau = 0.0;
@@ -441,7 +474,7 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
       double sum = 0.0, sd = 0.0;
       unsigned cnt = 0;
 #pragma unroll
-      for (int k = 0; k < COOP_VALUES; ++k) {
+      for (int k = 0; k < VALUES; ++k) {
         if constexpr (WEIGHTED) {
           float wf = wr[k];
           asm volatile("" : "+v"(wf));   // (keeps the widening inside the loop)
@@ -451,7 +484,7 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
           if (vr[k] > tau) { sum += vr[k]; ++cnt; }
         }
       }
-      for (long long i = lo + tid + (long long)COOP_VALUES * SWG; i < hi; i += SWG) {
+      for (long long i = lo + tid + (long long)VALUES * NT; i < hi; i += NT) {
         const double x = v[i];
         if constexpr (WEIGHTED) {
           const double w = (double)wts[i];
@@ -462,19 +495,23 @@ __global__ __launch_bounds__(SWG) void search_wide_kernel(Ws ws, long long ngrou
       }
       if constexpr (WEIGHTED) block_sum2_count(sum, sd, cnt, s);
       else block_sum_count(sum, cnt, s);
+      ++round;
       const unsigned par = round & 1u;
       if (tid == 0) {
-        put_f64(&ws.coop_d[par * COOP_MAX_WGS + wg], sum);
-        if constexpr (WEIGHTED) put_f64(&coop_w[(1 + par) * COOP_MAX_WGS + wg], sd);
-        __hip_atomic_exchange(&ws.coop_u[par * COOP_MAX_WGS + wg], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        post_word(slot(par, 0, wg), round, lo32(sum));
+        post_word(slot(par, 1, wg), round, hi32(sum));
+        post_word(slot(par, 2, wg), round, cnt);
+        if constexpr (WEIGHTED) {
+          post_word(slot(par, 3, wg), round, lo32(sd));
+          post_word(slot(par, 4, wg), round, hi32(sd));
+        }
       }
-      ++round;
-      if (!wide_barrier(ws.flags, round * (unsigned)nwg, &lds_ok)) return;
-      double S = tid < nwg ? get_f64(&ws.coop_d[par * COOP_MAX_WGS + tid]) : 0.0;
-      double D = 0.0;
-      unsigned K = tid < nwg ? __hip_atomic_load(&ws.coop_u[par * COOP_MAX_WGS + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      unsigned pay[WEIGHTED ? 5 : 3];
+      if (!collect(slot(par, 0, 0), ws.flags, round, nwg, pay, &lds_ok)) return;
+      double S = from32(pay[0], pay[1]), D = 0.0;
+      unsigned K = pay[2];
       if constexpr (WEIGHTED) {
-        D = tid < nwg ? get_f64(&coop_w[(1 + par) * COOP_MAX_WGS + tid]) : 0.0;
+        D = from32(pay[3], pay[4]);
         block_sum2_count(S, D, K, s);
       } else {
         block_sum_count(S, K, s);
