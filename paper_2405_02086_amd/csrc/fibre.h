@@ -248,8 +248,10 @@ __global__ __launch_bounds__(WG) void fibre_map_kernel(const TIN* A, long long n
     if constexpr (Q == Q2) par = nv > r ? r / nv : 1.0;
     if constexpr (Q == Q1) {
       // all lanes of the wavefront stay in the loop until every segment is done
-      bool open = nv > r;
-      double t = open ? (nv - r) / (double)len : 0.0;  // every entry active: a lower bound
+      // (radius 0: the fibre goes to zero whatever its entries, no search)
+      bool open = nv > r && r > 0.0;
+      double t = open ? (nv - r) / (double)len   // every entry active: a lower bound
+               : (nv > r ? HUGE_VAL : 0.0);
       unsigned kprev = 0xffffffffu;
       while (__any(open)) {
         double s = 0.0;
@@ -367,12 +369,13 @@ __global__ __launch_bounds__(WG) void fibre_map_cached_kernel(const TIN* A, long
       bool any_open = false;
 #pragma unroll
       for (int u = 0; u < UF; ++u) {
-        open[u] = nv[u] > r[u];
+        open[u] = nv[u] > r[u] && r[u] > 0.0;   // (radius 0: everything goes to zero, no search)
         floor_t[u] = open[u] ? (nv[u] - r[u]) / (double)len : 0.0;
-        const float guess = open[u] && r[u] > 0.0
+        const float guess = open[u]
             ? -0.75f * (float)(nv[u] / (double)len) * __logf((float)(r[u] / nv[u])) : 0.0f;
         first[u] = (double)guess > floor_t[u];
         par[u] = first[u] ? (double)guess : floor_t[u];
+        if (nv[u] > r[u] && !(r[u] > 0.0)) par[u] = HUGE_VAL;
         kprev[u] = 0xffffffffu;
         any_open = any_open || open[u];
       }

@@ -448,6 +448,24 @@ def test_multilevel_matches_oracle(mp, shape, norms):
         check_multi(run_multi(mp, Y, norms, eta), orc.multilevel(Y, norms, eta))
 
 
+@pytest.mark.parametrize("shape,norms", [((40, 30, 64), [1, 1]), ((12, 8, 3000), [1, 1]), ((64, 9, 5, 32), [1, "inf", 1]),
+                                         ((30, 2000), [1]), ((50, 20, 256), [2, 1])])
+def test_multilevel_sparse_radius_zeroes_most_groups(mp, shape, norms):
+    """Groups of very different sizes and a small radius: most groups (and, one level down, many
+    fibres of the kept ones) get radius 0, which the l1 fibre searches skip."""
+    rng = np.random.default_rng(list(shape) + [77])
+    Y = rng.standard_normal(shape).astype(np.float32)
+    Y *= np.power(10.0, rng.uniform(-2.5, 0.0, shape[0])).astype(np.float32).reshape((-1,) + (1,) * (len(shape) - 1))
+    if len(shape) > 2:
+        Y *= (rng.random(shape[:2]) < 0.5).astype(np.float32).reshape(shape[:2] + (1,) * (len(shape) - 2))
+    nrm = nested_norm(Y, norms)
+    for frac in (0.002, 0.03):
+        eta = float(np.float32(frac * nrm))
+        ref = orc.multilevel(Y, norms, eta)
+        assert 0 < (ref["u"] > 0).sum() < shape[0] * 0.7
+        check_multi(run_multi(mp, Y, norms, eta), ref)
+
+
 def test_multilevel_inf_inf_equals_the_trilevel_entry_point(mp):
     rng = np.random.default_rng(31)
     Y = rng.standard_normal((40, 24, 36)).astype(np.float32)
@@ -467,7 +485,7 @@ def test_workload_tensor_256_multilevel(mp, norms):
 # ------------------------------------------------------------------ repeatability, concurrency
 def test_results_repeat_bit_for_bit(mp):
     """Fixed reduction orders everywhere: every repetition gives the same bits, including the
-    grid-wide search (m > 16384) whose workgroups meet at a barrier."""
+    grid-wide search (m > 32768) whose workgroups exchange their sums every round."""
     rng = np.random.default_rng(41)
     dev = torch.device("cuda:0")
     for q, shape in (("inf", (64, 50000)), (1, (512, 1536)), (2, (1500, 700)), ("inf", (1500, 700))):
