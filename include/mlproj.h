@@ -213,6 +213,21 @@ int bilevel_proj_weighted(int storage, int variant,
                           float* u_out /* device, m; may be NULL */,
                           unsigned char* mask_out /* device, m; may be NULL */, void* stream);
 
+/* MP^nu_eta (Sec. 5.2, Def. 5.2, Alg. 6) with the weighted l1 ball as outermost norm: the
+ * multi-level projection of multilevel_proj_stored, except that the top aggregate w (one entry
+ * per group of axis 0) is projected onto {u : sum_a weights[a] |u_a| <= eta} as in
+ * bilevel_proj_weighted (Sec. 3): u_a = max(w_a - tau weights[a], 0).  weights: dims[0] floats in
+ * device memory, read only, positive and finite (not checked).  Covers the tri-level l1,inf,inf
+ * projection as norms = {INF, INF}.  All other arguments, the workspace size
+ * (mlproj_multilevel_workspace_bytes), alignment rules and error codes are those of
+ * multilevel_proj_stored; a NULL weights pointer is MLPROJ_ERR_NULL_POINTER.               */
+int multilevel_proj_weighted(int storage, const void* Y /* device */, void* X /* device */, int ndim,
+                             const long long* dims /* host, ndim */, const int* norms /* host, ndim-1, innermost first */,
+                             float eta, const float* weights /* device, dims[0] */,
+                             void* workspace /* device */, size_t workspace_bytes,
+                             float* v_out /* device, dims[0]; may be NULL */,
+                             float* u_out /* device, dims[0]; may be NULL */, void* stream);
+
 /* One problem of a batch: the arguments of bilevel_proj_stored for one matrix. */
 typedef struct mlproj_problem {
   const void* Y;              /* device, n*m elements                               */

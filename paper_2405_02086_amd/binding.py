@@ -99,6 +99,9 @@ def lib():
     L.bilevel_proj_stored.argtypes = [c_i, c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.bilevel_proj_batch.restype = c_i
     L.bilevel_proj_batch.argtypes = [c_i, c_i, c_i, c_i, ctypes.POINTER(Problem), c_vp]
+    L.multilevel_proj_weighted.restype = c_i
+    L.multilevel_proj_weighted.argtypes = [c_i, c_vp, c_vp, c_i, ctypes.POINTER(c_ll), ctypes.POINTER(c_i), c_f, c_vp,
+                                           c_vp, c_sz, c_vp, c_vp, c_vp]
     L.bilevel_proj_weighted.restype = c_i
     L.bilevel_proj_weighted.argtypes = [c_i, c_i, c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_vp, c_sz, c_vp, c_vp, c_vp, c_vp]
     L.trilevel_proj_stored.restype = c_i
@@ -122,7 +125,7 @@ EXPORTS = (
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
     "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored", "mlproj_set_l11_sweeps",
-    "multilevel_proj_stored", "bilevel_proj_weighted",
+    "multilevel_proj_stored", "bilevel_proj_weighted", "multilevel_proj_weighted",
 )
 
 
@@ -427,6 +430,29 @@ def multilevel_proj_stored(Y, norms, eta, p=1, X=None, workspace=None, v_out=Non
                                       ctypes.c_float(eta), _ptr(workspace.buf), workspace.nbytes, _ptr(v_out),
                                       _ptr(u_out), _stream(stream))
     _check(st, "multilevel_proj_stored")
+    return X
+
+
+def multilevel_proj_weighted(Y, norms, eta, weights, X=None, workspace=None, v_out=None, u_out=None, stream=None):
+    """multilevel_proj_stored with the weighted l1 ball {u : sum_a w_a |u_a| <= eta} as outermost norm;
+    weights is an fp32 device tensor with one positive entry per group of axis 0."""
+    import torch
+    storages = {torch.float32: STORE_F32, torch.bfloat16: STORE_BF16, torch.float16: STORE_F16}
+    assert Y.is_cuda and Y.is_contiguous() and Y.dtype in storages
+    shape = tuple(Y.shape)
+    assert weights.is_cuda and weights.dtype == torch.float32 and weights.is_contiguous() and weights.numel() == shape[0]
+    if X is None:
+        X = torch.empty_like(Y)
+    assert X.is_cuda and X.dtype == Y.dtype and X.is_contiguous() and X.shape == Y.shape
+    assert len(norms) == len(shape) - 1
+    if workspace is None:
+        workspace = Workspace(multilevel_workspace_bytes(shape), device=Y.device)
+    dims = (ctypes.c_longlong * len(shape))(*shape)
+    nrm = (ctypes.c_int * len(norms))(*[_NORMS[q] for q in norms])
+    st = lib().multilevel_proj_weighted(storages[Y.dtype], _ptr(Y), _ptr(X), len(shape), dims, nrm,
+                                        ctypes.c_float(eta), _ptr(weights), _ptr(workspace.buf), workspace.nbytes,
+                                        _ptr(v_out), _ptr(u_out), _stream(stream))
+    _check(st, "multilevel_proj_weighted")
     return X
 
 

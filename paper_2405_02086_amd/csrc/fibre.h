@@ -158,12 +158,13 @@ __global__ __launch_bounds__(WG) void fibre_agg_short_kernel(const TIN* __restri
 
 __global__ void clear_flags_kernel(Ws ws) { clear_meeting_area(ws.flags); }
 
-// Radii of the top level from the threshold: R[a] = max(w[a] - tau, 0).
+// Radii of the top level from the threshold: R[a] = max(w[a] - tau, 0) (tau * weight[a] for a
+// weighted l1 ball).
 __global__ __launch_bounds__(WG) void top_radii_kernel(Ws ws, long long d0, double* __restrict__ R,
                                                        float* __restrict__ u_out) {
   const long long a = (long long)blockIdx.x * WG + threadIdx.x;
   if (a >= d0) return;
-  const double u = radius(ws.v[a], top_of(ws.res));
+  const double u = radius_of(ws, a, ws.v[a], top_of(ws.res));
   R[a] = u;
   if (u_out) u_out[a] = (float)u;
 }

@@ -130,6 +130,26 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
                      only_as_fallback, (double*)nullptr, (float*)nullptr);
 }
 
+// The search for a weighted l1 ball as outer norm (ws.wts set).  One workgroup re-reads what its
+// registers do not hold in every round: beyond 32768 groups the grid-wide form goes first, with
+// the one-workgroup kernel as its fallback.
+static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStream_t stream) {
+  int only_as_fallback = 0;
+  if (m > 32768) {
+    long long nwg = cdiv(m, (long long)COOP_THREADS * COOP_VALUES);
+    if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
+    hipLaunchKernelGGL((search_wide_kernel<true, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, m,
+                       eta, (int)MODE_PROJECT, (double*)nullptr);
+    only_as_fallback = 1;
+  }
+  if (m <= 4096)
+    hipLaunchKernelGGL((search_weighted_kernel<256, 16>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback);
+  else if (m <= 16384)
+    hipLaunchKernelGGL((search_weighted_kernel<256, 64>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback);
+  else
+    hipLaunchKernelGGL((search_weighted_kernel<SWG, 16>), dim3(1), dim3(SWG), 0, stream, ws, m, eta, only_as_fallback);
+}
+
 // l1,1: how many lock-step sweeps to enqueue before the finishing pass, and the number of
 // open columns at which the remaining sweeps hand over to it (see l11.h).  Measured on an
 // MI355X: a sweep that finds nothing to do costs two launches (3.6 us); one iteration of the
@@ -217,22 +237,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     const bool fuse_l11 = Q == Q1 && mode == MODE_PROJECT && m <= FUSED_SEARCH_MAX_BIG && !weights;
     if (weights) {
       mark(stream);
-      // (one workgroup re-reads what its registers do not hold in every round: beyond 32768
-      // columns the grid-wide form goes first, with this one as its fallback)
-      int only_as_fallback = 0;
-      if (m > 32768) {
-        long long nwg = cdiv(m, (long long)COOP_THREADS * COOP_VALUES);
-        if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-        hipLaunchKernelGGL((search_wide_kernel<true, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, m,
-                           (double)eta, (int)MODE_PROJECT, (double*)nullptr);
-        only_as_fallback = 1;
-      }
-      if (m <= 4096)
-        hipLaunchKernelGGL((search_weighted_kernel<256, 16>), dim3(1), dim3(256), 0, stream, ws, m, (double)eta, only_as_fallback);
-      else if (m <= 16384)
-        hipLaunchKernelGGL((search_weighted_kernel<256, 64>), dim3(1), dim3(256), 0, stream, ws, m, (double)eta, only_as_fallback);
-      else
-        hipLaunchKernelGGL((search_weighted_kernel<SWG, 16>), dim3(1), dim3(SWG), 0, stream, ws, m, (double)eta, only_as_fallback);
+      launch_weighted_search(ws, m, (double)eta, stream);
     } else if (!fuse && !fuse_l11) {
       mark(stream);
       launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
@@ -618,10 +623,11 @@ static int ml_workspace_bytes(int ndim, const long long* dims, size_t* out) {
 template <typename T>
 static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long* dims_in,
                           const int* norms_in, float eta, void* workspace, size_t workspace_bytes,
-                          float* v_out, float* u_out, void* stream_) {
+                          float* v_out, float* u_out, void* stream_, const float* weights = nullptr) {
   constexpr int WIDE = 16 / (int)sizeof(T);
   if (!Y || !X || !workspace) return MLPROJ_ERR_NULL_POINTER;
   if (outer < MLPROJ_OUTER_L1 || outer > MLPROJ_OUTER_LINF) return MLPROJ_ERR_BAD_VARIANT;
+  if (weights && outer != MLPROJ_OUTER_L1) return MLPROJ_ERR_BAD_VARIANT;
   MlPlan P;
   int st = ml_plan(ndim, dims_in, norms_in, &P);   // checks the arguments as given
   if (st != MLPROJ_OK) return st;
@@ -650,7 +656,7 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
   // norms[] above is indexed by axis (1..nd-1); ml_plan wants it innermost first
   int norms_inner_first[ML_MAX_DIMS];
   for (int axis = 1; axis < nd; ++axis) norms_inner_first[nd - 1 - axis] = norms[axis];
-  if (nd == 2 && norms_inner_first[0] == MLPROJ_NORM_INF && outer == MLPROJ_OUTER_L1)
+  if (nd == 2 && norms_inner_first[0] == MLPROJ_NORM_INF && outer == MLPROJ_OUTER_L1 && !weights)
     return run_trilevel<T>(Y, X, dims[0], dims[1], 1, eta, workspace, workspace_bytes, v_out, u_out,
                            nullptr, stream_);
   ndim = nd;
@@ -660,7 +666,8 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
   if ((st = check_radius(eta)) != MLPROJ_OK) return st;
   if (!aligned(Y, sizeof(T)) || !aligned(X, sizeof(T))) return MLPROJ_ERR_ALIGNMENT;
   if (workspace_bytes < P.bytes) return MLPROJ_ERR_WORKSPACE;
-  const Ws ws = bind(workspace, P.base);
+  Ws ws = bind(workspace, P.base);
+  ws.wts = weights;   // (a weighted l1 ball as outer norm: its own search kernel, nothing fused)
   char* base = static_cast<char*>(workspace);
   double* V[ML_MAX_DIMS];
   double* R[ML_MAX_DIMS];
@@ -688,10 +695,15 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
   }
   // top: threshold of the l1-ball projection of the length-d0 vector, then its radii.  With
   // three or more axes and at most 4096 groups the map of the top level does this itself.
-  const bool fuse_top = ndim >= 3 && dims[0] <= FUSED_SEARCH_MAX;
+  const bool fuse_top = ndim >= 3 && dims[0] <= FUSED_SEARCH_MAX && !weights;
   if (!fuse_top) mark(stream);
   if (fuse_top) {
     // nothing here: see the first map below
+  } else if (weights) {
+    hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WG), 0, stream, ws);
+    launch_weighted_search(ws, dims[0], (double)eta, stream);
+    hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
+                       dims[0], R[ndim - 1], u_out);
   } else if (dims[0] <= (long long)SWG * SEARCH_CACHE || outer != MLPROJ_OUTER_L1) {
     hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
                        outer, (double*)nullptr, 0, R[ndim - 1], u_out);
@@ -729,7 +741,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 346; }
+int mlproj_version(void) { return 347; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -865,6 +877,23 @@ int bilevel_proj_weighted(int storage, int variant, const void* Y, void* X, long
     case MLPROJ_STORE_F32: return go(float{});
     case MLPROJ_STORE_BF16: return go(bf16_t{});
     case MLPROJ_STORE_F16: return go(f16_t{});
+    default: return MLPROJ_ERR_BAD_VARIANT;
+  }
+}
+
+int multilevel_proj_weighted(int storage, const void* Y, void* X, int ndim, const long long* dims,
+                             const int* norms, float eta, const float* weights, void* workspace,
+                             size_t workspace_bytes, float* v_out, float* u_out, void* stream) {
+  if (!weights) return MLPROJ_ERR_NULL_POINTER;
+  if (!aligned(weights, sizeof(float))) return MLPROJ_ERR_ALIGNMENT;
+  const int outer = (int)MLPROJ_OUTER_L1;
+  switch (storage) {
+    case MLPROJ_STORE_F32:
+      return run_multilevel<float>(outer, static_cast<const float*>(Y), static_cast<float*>(X), ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream, weights);
+    case MLPROJ_STORE_BF16:
+      return run_multilevel<bf16_t>(outer, static_cast<const bf16_t*>(Y), static_cast<bf16_t*>(X), ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream, weights);
+    case MLPROJ_STORE_F16:
+      return run_multilevel<f16_t>(outer, static_cast<const f16_t*>(Y), static_cast<f16_t*>(X), ndim, dims, norms, eta, workspace, workspace_bytes, v_out, u_out, stream, weights);
     default: return MLPROJ_ERR_BAD_VARIANT;
   }
 }

@@ -173,6 +173,22 @@ def test_weighted_entry_point_argument_checks(lib):
         assert wt(storage, 2, FAKE, FAKE, 4, 4, F(1), FAKE, FAKE, 64, None, None, None, None) == -5
 
 
+def test_weighted_multilevel_argument_checks(lib):
+    big = 1 << 30
+    LL, I = ctypes.c_longlong, ctypes.c_int
+    dims, norms = (LL * 3)(4, 5, 6), (I * 2)(0, 1)
+    mw = lib.multilevel_proj_weighted
+    assert mw(0, FAKE, FAKE, 3, dims, norms, F(1), None, FAKE, big, None, None, None) == -1       # no weights
+    assert mw(0, FAKE, FAKE, 3, dims, norms, F(1), ctypes.c_void_p((1 << 20) + 2), FAKE, big, None, None, None) == -7
+    assert mw(4, FAKE, FAKE, 3, dims, norms, F(1), FAKE, FAKE, big, None, None, None) == -6       # unknown storage
+    for storage in (0, 1, 2):
+        assert mw(storage, None, FAKE, 3, dims, norms, F(1), FAKE, FAKE, big, None, None, None) == -1
+        assert mw(storage, FAKE, FAKE, 3, dims, None, F(1), FAKE, FAKE, big, None, None, None) == -1
+        assert mw(storage, FAKE, FAKE, 3, dims, (I * 2)(0, 9), F(1), FAKE, FAKE, big, None, None, None) == -6
+        assert mw(storage, FAKE, FAKE, 3, dims, norms, F(-1), FAKE, FAKE, big, None, None, None) == -4
+        assert mw(storage, FAKE, FAKE, 3, dims, norms, F(1), FAKE, FAKE, 64, None, None, None) == -5
+
+
 def test_batch_argument_checks(lib):
     big = 1 << 30
     bt = lib.bilevel_proj_batch

@@ -466,6 +466,41 @@ def test_multilevel_sparse_radius_zeroes_most_groups(mp, shape, norms):
         check_multi(run_multi(mp, Y, norms, eta), ref)
 
 
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,norms", [((5, 7), [1]), ((300, 33), ["inf"]), ((4, 3, 5), [1, 1]), ((40, 30, 64), ["inf", "inf"]),
+                                         ((9, 16, 3), [1, 2]), ((7, 5, 260), [2, 1]), ((5, 4, 3, 6), ["inf", 2, 1]),
+                                         ((5000, 2, 4), [1, 1]), ((40000, 8), ["inf"]), ((33000, 2, 4), ["inf", "inf"]),
+                                         ((1, 1, 1), [1, 1])])
+def test_multilevel_weighted_outer_norm_matches_oracle(mp, storage, shape, norms):
+    """The multi-level projection with the weighted l1 ball on top (Sec. 3, Sec. 5.2)."""
+    rng = np.random.default_rng(list(shape) + [len(norms), 5])
+    Y = orc.round_to_storage(rng.standard_normal(shape).astype(np.float32), storage)
+    w = np.exp(rng.uniform(-1.5, 1.5, shape[0])).astype(np.float32)
+    dev = torch.device("cuda:0")
+    top = orc.multilevel(Y, norms, 3.0e38)["w"]
+    total = float(np.dot(w.astype(np.float64), top))
+    for frac in (0.03, 0.5, 1.2, 0.0):
+        eta = float(np.float32(frac * total))
+        ref = orc.multilevel_stored(Y, norms, eta, storage, p=("w1", w))
+        Yd = torch.from_numpy(Y).to(dev).to(getattr(torch, STORE_DTYPES[storage]))
+        ws = mp.Workspace(mp.multilevel_workspace_bytes(shape), device=dev)
+        v = torch.full((shape[0],), -1.0, dtype=torch.float32, device=dev)
+        u = torch.full((shape[0],), -1.0, dtype=torch.float32, device=dev)
+        X = mp.multilevel_proj_weighted(Yd, norms, eta, torch.from_numpy(w).to(dev), workspace=ws, v_out=v, u_out=u)
+        torch.cuda.synchronize()
+        got = {"X": X.float().cpu().numpy(), "v": v.cpu().numpy(), "u": u.cpu().numpy(), "res": ws.result()}
+        np.testing.assert_allclose(got["v"], ref["w"].astype(np.float32), rtol=2e-7)
+        np.testing.assert_allclose(got["u"], ref["u"].astype(np.float32), rtol=RTOL, atol=ATOL)
+        assert np.array_equal(got["u"] == 0, ref["u"] == 0)
+        if frac > 0:
+            assert got["res"]["tau"] == pytest.approx(ref["tau"], rel=1e-9, abs=1e-300)
+        x = ref["X32"].astype(np.float64)
+        tol = RTOL * np.abs(x) + ATOL
+        lo = orc.round_to_storage((x - tol).astype(np.float32), storage)
+        hi = orc.round_to_storage((x + tol).astype(np.float32), storage)
+        assert np.all((got["X"] >= lo) & (got["X"] <= hi))
+
+
 def test_multilevel_inf_inf_equals_the_trilevel_entry_point(mp):
     rng = np.random.default_rng(31)
     Y = rng.standard_normal((40, 24, 36)).astype(np.float32)
