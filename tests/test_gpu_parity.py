@@ -822,6 +822,22 @@ def test_weighted_outer_norm_special_cases_with_many_columns(mp):
         check_stored(run_weighted(mp, Y, eta, q, "f32", one), orc.bilevel_stored(Y, eta, q, "f32"), q, "f32")
 
 
+def test_weighted_outer_norm_on_the_headline_matrix(mp):
+    """The 4096 x 4096 workload with the weights bench.py draws for it, q = inf in full and q = 1 on
+    sampled columns."""
+    w_, Y = workloads.make("square_4096")
+    n, m = Y.shape
+    w = np.exp(np.random.default_rng([n, m, 17]).uniform(-1, 1, m)).astype(np.float32)
+    eta = weighted_eta(Y, "inf", w, w_.eta_frac)
+    check_stored(run_weighted(mp, Y, eta, "inf", "f32", w), orc.bilevel_stored(Y, eta, "inf", "f32", p=("w1", w)), "inf", "f32")
+    eta = weighted_eta(Y, 1, w, w_.eta_frac)
+    cols = np.sort(np.random.default_rng(8).choice(m, size=96, replace=False))
+    got = run_weighted(mp, Y, eta, 1, "f32", w)
+    ref = orc.bilevel_l11(Y, eta, columns=cols, p=("w1", w))
+    check_against_oracle(got, ref, 1, columns=cols)
+    assert np.array_equal(got["mask"], (np.asarray(ref["u"]) > 0).astype(np.uint8))
+
+
 def test_weighted_outer_norm_random_cases(mp):
     """Seeded random shapes, radii, value and weight distributions."""
     for seed in range(40):
