@@ -129,6 +129,15 @@ int mlproj_trace_end(void);
  * Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value outside 0..16.       */
 int mlproj_set_l11_sweeps(int sweeps);
 
+/* Vectors of more than 32768 groups are searched (Eq. 6-7) by several workgroups that exchange
+ * their sums every round; a workgroup that has polled `polls` times for another's numbers gives
+ * up, everybody leaves, and a one-workgroup kernel enqueued behind does the search instead
+ * (every kernel ends either way, and the result is the same).  This sets that bound: 0 makes
+ * the several-workgroup search give up at once (which exercises the kernel behind it), the
+ * default is 4194304 (seconds of polling).  Process-wide and read when a call is enqueued.
+ * Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value outside 0..4194304.   */
+int mlproj_set_search_spin_limit(int polls);
+
 /* Bytes of workspace a call of `variant` on dims (d0, d1, d2) needs; bi-level
  * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.  The size is a few
  * MiB plus 8-16 bytes per column; MLPROJ_L11 adds up to about 1 KiB per column for the

@@ -72,6 +72,8 @@ def lib():
     L.mlproj_trace_end.argtypes = []
     L.mlproj_set_l11_sweeps.restype = c_i
     L.mlproj_set_l11_sweeps.argtypes = [c_i]
+    L.mlproj_set_search_spin_limit.restype = c_i
+    L.mlproj_set_search_spin_limit.argtypes = [c_i]
     L.mlproj_norm_l1q.restype = c_i
     L.mlproj_norm_l1q.argtypes = [c_vp, c_ll, c_ll, c_i, c_vp, c_sz, c_vp, c_vp, c_vp]
     for name in ("bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12"):
@@ -125,13 +127,21 @@ EXPORTS = (
     "trilevel_proj_l1infinf", "bilevel_radii", "bilevel_apply",
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
     "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored", "mlproj_set_l11_sweeps",
-    "multilevel_proj_stored", "bilevel_proj_weighted", "multilevel_proj_weighted",
+    "multilevel_proj_stored", "bilevel_proj_weighted", "multilevel_proj_weighted", "mlproj_set_search_spin_limit",
 )
 
 
 def _check(status, where):
     if status != 0:
         raise MlprojError(status, where)
+
+
+def set_search_spin_limit(polls):
+    """Polls after which the several-workgroup search gives up (0 = at once); returns the old value."""
+    before = lib().mlproj_set_search_spin_limit(int(polls))
+    if before < 0:
+        raise MlprojError(int(before), "mlproj_set_search_spin_limit")
+    return int(before)
 
 
 def set_l11_sweeps(sweeps):

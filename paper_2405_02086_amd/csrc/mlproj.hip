@@ -107,6 +107,10 @@ static inline void mark(hipStream_t stream) {
     (void)hipEventRecord(g_trace.events[g_trace.count++], stream);
 }
 
+// Polls a lane of the grid-wide search may spend waiting for another workgroup's post before the
+// search gives up and the one-workgroup kernel behind it takes over (0: give up at once).
+static unsigned g_spin_limit = SPIN_LIMIT;
+
 // The stand-alone search: one workgroup of 1024 threads while v fits its registers (16 values
 // per thread up to 16384 groups, 32 up to 32768), the grid-wide form beyond that, followed by
 // the one-workgroup kernel as a fallback that returns at once unless the grid-wide one gave up.
@@ -123,7 +127,7 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
   if (ngroups > (long long)SWG * SEARCH_CACHE && iterates) {
     long long nwg = cdiv(ngroups, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-    hipLaunchKernelGGL((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, ngroups, eta, mode, norm_out);
+    hipLaunchKernelGGL((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, ngroups, eta, mode, norm_out, g_spin_limit);
     only_as_fallback = 1;
   }
   hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
@@ -139,7 +143,7 @@ static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStr
     long long nwg = cdiv(m, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
     hipLaunchKernelGGL((search_wide_kernel<true, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, m,
-                       eta, (int)MODE_PROJECT, (double*)nullptr);
+                       eta, (int)MODE_PROJECT, (double*)nullptr, g_spin_limit);
     only_as_fallback = 1;
   }
   if (m <= 4096)
@@ -741,7 +745,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 347; }
+int mlproj_version(void) { return 348; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -777,6 +781,13 @@ int mlproj_set_l11_sweeps(int sweeps) {
   if (sweeps < 0 || sweeps > MAX_INNER_SWEEPS) return MLPROJ_ERR_BAD_DIMENSION;
   const int before = g_l11_sweeps;
   g_l11_sweeps = sweeps;
+  return before;
+}
+
+int mlproj_set_search_spin_limit(int polls) {
+  if (polls < 0 || polls > (int)SPIN_LIMIT) return MLPROJ_ERR_BAD_DIMENSION;
+  const int before = (int)g_spin_limit;
+  g_spin_limit = (unsigned)polls;
   return before;
 }
 

@@ -323,17 +323,19 @@ __device__ __forceinline__ double from32(unsigned lo, unsigned hi) {
 
 // Collect W words of every workgroup's post of this round into pay[] of lane g (zeros in the
 // other lanes).  False, for every thread of the workgroup alike, when the search gives up.
+// spin_limit: polls a lane may spend waiting (checked every 64th); 0 = give up without polling,
+// which the host uses to exercise the fallback.
 template <int W>
 __device__ __forceinline__ bool collect(const unsigned long long* q, unsigned* flags, unsigned round,
-                                        int nwg, unsigned (&pay)[W], unsigned* lds_ok) {
+                                        int nwg, unsigned spin_limit, unsigned (&pay)[W], unsigned* lds_ok) {
   if (threadIdx.x == 0) *lds_ok = 1u;
   __syncthreads();
 #pragma unroll
   for (int w = 0; w < W; ++w) pay[w] = 0u;
   if ((int)threadIdx.x < nwg) {
     unsigned spins = 0;
-    bool ok = true;
-    for (;;) {
+    bool ok = spin_limit != 0u;
+    while (ok) {
       bool all = true;
 #pragma unroll
       for (int w = 0; w < W; ++w) {
@@ -343,7 +345,7 @@ __device__ __forceinline__ bool collect(const unsigned long long* q, unsigned* f
       }
       if (all) break;
       if ((++spins & 63u) == 0u &&
-          (spins > SPIN_LIMIT || __hip_atomic_load(&flags[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
+          (spins > spin_limit || __hip_atomic_load(&flags[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
         ok = false;
         break;
       }
@@ -364,7 +366,8 @@ __device__ __forceinline__ bool collect(const unsigned long long* q, unsigned* f
 // post a third number per round, the sum of w_j^2 over their active entries.
 template <bool WEIGHTED, int NT, int VALUES>
 __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroups, double eta,
-                                                          int mode, double* __restrict__ norm_out) {
+                                                          int mode, double* __restrict__ norm_out,
+                                                          unsigned spin_limit) {
   static_assert(NT >= COOP_MAX_WGS, "one lane per workgroup collects its post");
   __shared__ PairScratch<NT / WAVE> s;
   __shared__ unsigned lds_ok;
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
   double den_all = 0.0, rmax_all = 0.0;
   {
     unsigned pay[WEIGHTED ? 6 : 4];
-    if (!collect(slot(1u, 0, 0), ws.flags, round, nwg, pay, &lds_ok)) return;
+    if (!collect(slot(1u, 0, 0), ws.flags, round, nwg, spin_limit, pay, &lds_ok)) return;
     o.total = from32(pay[0], pay[1]);
     o.vmax = from32(pay[2], pay[3]);
     block_sum_max(o.total, o.vmax, s);
@@ -507,7 +510,7 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
         }
       }
       unsigned pay[WEIGHTED ? 5 : 3];
-      if (!collect(slot(par, 0, 0), ws.flags, round, nwg, pay, &lds_ok)) return;
+      if (!collect(slot(par, 0, 0), ws.flags, round, nwg, spin_limit, pay, &lds_ok)) return;
       double S = from32(pay[0], pay[1]), D = 0.0;
       unsigned K = pay[2];
       if constexpr (WEIGHTED) {

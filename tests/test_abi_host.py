@@ -173,6 +173,15 @@ def test_weighted_entry_point_argument_checks(lib):
         assert wt(storage, 2, FAKE, FAKE, 4, 4, F(1), FAKE, FAKE, 64, None, None, None, None) == -5
 
 
+def test_search_spin_limit_knob(lib):
+    default = lib.mlproj_set_search_spin_limit(0)
+    assert default == 1 << 22
+    assert lib.mlproj_set_search_spin_limit(64) == 0
+    assert lib.mlproj_set_search_spin_limit(-1) == -2 and lib.mlproj_set_search_spin_limit((1 << 22) + 1) == -2
+    assert lib.mlproj_set_search_spin_limit(default) == 64
+    assert lib.mlproj_set_search_spin_limit(default) == default
+
+
 def test_weighted_multilevel_argument_checks(lib):
     big = 1 << 30
     LL, I = ctypes.c_longlong, ctypes.c_int

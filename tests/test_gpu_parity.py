@@ -96,6 +96,29 @@ def test_many_columns_use_the_grid_wide_search(mp, q, shape):
         check_against_oracle(run_gpu(mp, Y, eta, q), orc.bilevel(Y, eta, q), q)
 
 
+@pytest.mark.parametrize("limit", [0, 64])
+def test_grid_wide_search_gives_up_and_the_kernel_behind_it_takes_over(mp, limit):
+    """With a poll limit of 0 the several-workgroup search leaves at once and the one-workgroup
+    kernel enqueued behind it does the work; with 64 some workgroups may give up half way.  Every
+    kernel ends either way and the result is the same."""
+    rng = np.random.default_rng(97)
+    dev = torch.device("cuda:0")
+    Y = rng.laplace(size=(3, 300001)).astype(np.float32)
+    w = weights_for(300001, 9)
+    before = mp.set_search_spin_limit(limit)
+    try:
+        for q in ("inf", 1):
+            eta = eta_for(Y, q, 0.2)
+            check_against_oracle(run_gpu(mp, Y, eta, q), orc.bilevel(Y, eta, q), q)
+            eta = weighted_eta(Y, q, w, 0.2)
+            check_stored(run_weighted(mp, Y, eta, q, "f32", w), orc.bilevel_stored(Y, eta, q, "f32", p=("w1", w)), q, "f32")
+        T = rng.standard_normal((40000, 2, 4)).astype(np.float32)      # multi-level with a long top vector
+        eta = float(np.float32(0.3 * nested_norm(T, [1, 1])))
+        check_multi(run_multi(mp, T, [1, 1], eta), orc.multilevel(T, [1, 1], eta))
+    finally:
+        assert mp.set_search_spin_limit(before) == limit
+
+
 @pytest.mark.parametrize("q", ["inf", 1, 2])
 @pytest.mark.parametrize("shape", [(50000, 3), (100000, 1), (1, 100000), (2, 20000), (70001, 65)])
 def test_very_tall_and_single_row_shapes(mp, q, shape):
