@@ -123,7 +123,8 @@ int mlproj_trace_end(void);
 /* Tuning knob for MLPROJ_L11 (Alg. 3): how many lock-step passes over Y a call enqueues for
  * the per-column threshold searches before the column-wise finishing pass closes whatever is
  * still open.  1..16, or 0 for the default, which grows with the number of rows (none up to 1024
- * rows, 3 at 4096, 6 at 16384, 12 beyond 131072): the finishing pass costs more per column
+ * rows, or up to 4096 rows when the matrix has at most 4M elements; else 3 at 4096, 6 at 16384,
+ * 12 beyond 131072): the finishing pass costs more per column
  * the taller the matrix.  The thresholds are exact for any value; only the time changes.
  * Process-wide and read when a call is enqueued: set it while no other thread is calling.
  * Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value outside 0..16.       */
