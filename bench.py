@@ -268,8 +268,8 @@ def bench_size_sweep(torch, mp, workloads, steps, warmup):
 
 
 def bench_small(torch, mp, Y_host, frac, steps, warmup):
-    """The small workload is launch-bound: eager calls against replays of one call captured in a
-    HIP graph (what the three kernels cost once the host is out of the way)."""
+    """The small workload is launch-bound: eager calls (out of place, and in place as a training
+    loop calls it) against replays of one call captured in a HIP graph."""
     dev = torch.device("cuda:0")
     n, m = Y_host.shape
     Y = torch.from_numpy(Y_host).to(dev)
@@ -282,8 +282,14 @@ def bench_small(torch, mp, Y_host, frac, steps, warmup):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         call()
+    # in place, as a training loop calls it: a fresh copy of Y for every call (a projected matrix
+    # lies in the ball already, and projecting it again would be less work)
+    fresh = iter([Y.clone() for _ in range(steps + warmup)])
+    def in_place():
+        Z = next(fresh)
+        mp.bilevel_proj_l1inf(Z, eta, X=Z, workspace=ws)
     out = {"shape": [n, m]}
-    for name, fn in (("ms_eager", call), ("ms_graph_replay", graph.replay)):
+    for name, fn in (("ms_eager", call), ("ms_eager_in_place", in_place), ("ms_graph_replay", graph.replay)):
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
@@ -315,10 +321,17 @@ def bench_batch(torch, mp, shape, count, frac, steps, warmup, variant="l1inf"):
         mp.bilevel_proj_batch(Ys, etas, q, Xs=Xs, workspaces=wss)
 
     prepared = mp.PreparedBatch(Ys, etas, q, Xs=Xs, workspaces=wss)   # argument block marshalled once
+    # X = Y, as a training loop projects: fresh copies for every call (a projected matrix lies in the
+    # ball already, and projecting it again would be less work)
+    def one_in_place():
+        Zs = [Y.clone() for Y in Ys]
+        return mp.PreparedBatch(Zs, etas, q, Xs=Zs, workspaces=wss)
+    fresh = iter([one_in_place() for _ in range(steps + warmup)])
+    prepared_in_place = lambda: next(fresh)()
 
     out = {"shape": list(shape), "count": count}
     for name, fn in (("ms_loop_of_single_calls", loop), ("ms_one_batch_call", batch),
-                     ("ms_one_prepared_batch_call", prepared)):
+                     ("ms_one_prepared_batch_call", prepared), ("ms_one_prepared_batch_call_in_place", prepared_in_place)):
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()

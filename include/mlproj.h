@@ -257,7 +257,7 @@ typedef struct mlproj_problem {
  * their kernel launches, 16 matrices at a time (three launches for all of them instead of
  * three each, which is what small matrices cost; MLPROJ_L11 shares the launches of its
  * per-column searches the same way; MLPROJ_L1INF and MLPROJ_L12 matrices of at most 128 KiB
- * that are not projected in place take a single launch for all of them); wider ones are enqueued one after
+ * take a single launch for all of them, in place or not); wider ones are enqueued one after
  * another behind them.
  * `problems` is a host array, read before
  * the call returns; all of it is checked before anything is enqueued.  Outputs of different

@@ -30,6 +30,7 @@ struct BatchItem {
   double eta;
   int wide;   // rows are 16-byte aligned: the wide form of LaneCols
   int x_vec;  // ... and so is X: 16-byte stores
+  int whole;  // one-kernel form: X overlaps Y, one workgroup does the whole matrix
 };
 
 struct BatchItems {
@@ -89,8 +90,8 @@ __global__ __launch_bounds__(WG) void colmap_batch_kernel(BatchItems it, BatchGr
     colmap_body<Q, T, WIDE, true, false, SC>(Y, X, b.n, b.m, g, ws, b.u_out, b.mask_out, eta, outer, bid);
 }
 
-// Matrices of at most 128 KiB each (not in place): the one-kernel form of tiny.h for all of
-// them in one launch.
+// Matrices of at most 128 KiB each: the one-kernel form of tiny.h for all of them in one launch
+// (up to 16 workgroups for a matrix whose X lies apart from Y, one for a matrix projected in place).
 template <int Q, typename T>
 __global__ __launch_bounds__(TINY_WG) void tiny_batch_kernel(BatchItems it, BatchGrid gr, int outer) {
   constexpr int WIDE = 16 / (int)sizeof(T);
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(TINY_WG) void tiny_batch_kernel(BatchItems it, Batc
   const Geometry g = plan_columns(b.n, b.m, WIDE, Q);
   const Ws ws = bind(b.ws, layout_for(g, b.m, Q));
   tiny_body<Q, T, WIDE>(static_cast<const T*>(b.Y), static_cast<T*>(b.X), b.n, b.m, b.eta, outer, tp.cw, ws,
-                           b.v_out, b.u_out, b.mask_out, bid);
+                           b.v_out, b.u_out, b.mask_out, bid, b.whole != 0);
 }
 
 // ------------------------------------------------------------------ l1,1: the inner searches

@@ -222,13 +222,14 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   const double fused_eta = fuse ? (double)eta : -1.0;
 
   if constexpr (tiny_built<Q, T>()) {
-    // a matrix of at most 128 KiB that is not projected in place: one kernel does it all
+    // a matrix of at most 128 KiB: one kernel does it all (up to 16 workgroups when X lies apart
+    // from Y, a single one when they overlap)
     TinyPlan tp;
     const bool apart = X && (X + n * m <= Y || Y + n * m <= X);
-    if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && apart && !weights && tiny_plan(n, m, WIDE, &tp)) {
+    if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && !weights && tiny_plan(n, m, WIDE, &tp)) {
       mark(stream);
-      hipLaunchKernelGGL((tiny_kernel<Q, T, WIDE>), dim3((unsigned)tp.slots), dim3(TINY_WG), 0, stream, Y, X, n, m,
-                         (double)eta, outer, tp.cw, ws, v_out, u_out, mask_out);
+      hipLaunchKernelGGL((tiny_kernel<Q, T, WIDE>), dim3(apart ? (unsigned)tp.slots : 1u), dim3(TINY_WG), 0, stream, Y, X, n, m,
+                         (double)eta, outer, tp.cw, ws, v_out, u_out, mask_out, apart ? 0 : 1);
       mark(stream);
       return launch_status();
     }
@@ -391,15 +392,18 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
     if (st != MLPROJ_OK) return st;
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  // matrices of at most 128 KiB that are not projected in place: one kernel for all
-  auto tinyable = [&](int i) {
-    if (!tiny_built<Q, T>()) return false;
+  // matrices of at most 128 KiB: one kernel for all
+  auto apart = [&](int i) {
     const mlproj_problem& p = pr[i];
     const T* Yp = static_cast<const T*>(p.Y);
     const T* Xp = static_cast<const T*>(p.X);
+    return Xp + p.n * p.m <= Yp || Yp + p.n * p.m <= Xp;
+  };
+  auto tinyable = [&](int i) {
+    if (!tiny_built<Q, T>()) return false;
+    const mlproj_problem& p = pr[i];
     TinyPlan tp;
-    return pick_vec(p.Y, p.m, (int)sizeof(T)) == WIDE && aligned(p.X, 16) &&
-           (Xp + p.n * p.m <= Yp || Yp + p.n * p.m <= Xp) && tiny_plan(p.n, p.m, WIDE, &tp);
+    return pick_vec(p.Y, p.m, (int)sizeof(T)) == WIDE && aligned(p.X, 16) && tiny_plan(p.n, p.m, WIDE, &tp);
   };
   auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG && !tinyable(i); };
   if constexpr (tiny_built<Q, T>()) {
@@ -417,9 +421,10 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
         b.v_out = p.v_out; b.u_out = p.u_out; b.mask_out = p.mask_out;
         b.n = p.n; b.m = p.m; b.eta = (double)p.eta;
         b.wide = 1; b.x_vec = 1;
+        b.whole = apart(k) ? 0 : 1;
         TinyPlan tp;
         tiny_plan(p.n, p.m, WIDE, &tp);
-        tg.first[it.count] = wgs; wgs += (unsigned)tp.slots;
+        tg.first[it.count] = wgs; wgs += b.whole ? 1u : (unsigned)tp.slots;
         ++it.count;
       }
       if (it.count == 0) break;
@@ -447,6 +452,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
       b.n = p.n; b.m = p.m; b.eta = (double)p.eta;
       b.wide = pick_vec(p.Y, p.m, (int)sizeof(T)) == WIDE ? 1 : 0;
       b.x_vec = aligned(p.X, 16) ? 1 : 0;
+      b.whole = 0;
       const Geometry g = plan_columns(p.n, p.m, WIDE, Q);
       agg.first[it.count] = a; a += (unsigned)(g.tiles * g.groups);
       red.first[it.count] = r; r += (unsigned)cdiv(p.m, SWG / reduce_parts(g.groups));
@@ -749,7 +755,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 349; }
+int mlproj_version(void) { return 350; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

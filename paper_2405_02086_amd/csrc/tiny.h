@@ -23,8 +23,11 @@ namespace mlproj {
 //
 // Threads form TINY_WG / cw row lanes of cw column lanes (cw = the chunks of a row, rounded up
 // to a power of two); a thread holds rows tr, tr + rl, tr + 2 rl, ... of its chunk column, and
-// workgroup b stores the rows of slot b.  X must not overlap Y: a workgroup still reading Y
-// would see rows another has already written.
+// workgroup b stores the rows of slot b.  That needs X apart from Y: a workgroup still reading Y
+// would see rows another has already written.  When X overlaps Y (a projection in place, the
+// usual call of a training loop) ONE workgroup does the whole matrix (`whole`): it has read all
+// of Y into its registers before its first store, so any overlap is harmless, and the 128 KiB
+// it then stores alone cost little beside the launches saved.
 // Which forms are built: q = inf and q = 2.  (A q = 1 form, with the per-column searches of
 // Alg. 3 run on the held registers, was built and dropped: on fp32 storage it took 43 us for a
 // 256 x 128 matrix against 23 us for the general path, whose finishing pass spreads the columns
@@ -61,10 +64,11 @@ __host__ __device__ static inline bool tiny_plan(long long n, long long m, int v
 
 // (`bid` is the workgroup's number within its own problem: blockIdx.x for a single matrix.)
 template <int Q, typename T, int VEC>
-__device__ __forceinline__ void tiny_body(const T* __restrict__ Y, T* __restrict__ X, long long n,
+__device__ __forceinline__ void tiny_body(const T* Y, T* X, long long n,
                                           long long m, double eta, int outer, int cw, const Ws& ws,
                                           float* __restrict__ v_out, float* __restrict__ u_out,
-                                          unsigned char* __restrict__ mask_out, long long bid) {
+                                          unsigned char* __restrict__ mask_out, long long bid,
+                                          bool whole) {
   using Acc = typename AccOf<Q>::type;
   __shared__ Acc sm_part[TINY_WG * VEC];   // [row lane][column]
   __shared__ double sm_v[TINY_WG * VEC];   // v, zero beyond column m
@@ -128,10 +132,10 @@ __device__ __forceinline__ void tiny_body(const T* __restrict__ Y, T* __restrict
     par[e] = (Q == Q2 && vj > 0.0) ? uj / vj : 0.0;
   }
   if (!col_ok) return;
-  // this workgroup's rows: slot `bid` of every thread
+  // this workgroup's rows: slot `bid` of every thread (every slot when it works alone)
 #pragma unroll
   for (int k = 0; k < TINY_SLOTS; ++k) {
-    if (k == (int)bid) {
+    if (whole || k == (int)bid) {
       const long long row = tr + (long long)k * rl;
       if (row < n) {
         float f[VEC];
@@ -148,13 +152,14 @@ __device__ __forceinline__ void tiny_body(const T* __restrict__ Y, T* __restrict
 }
 
 template <int Q, typename T, int VEC>
-__global__ __launch_bounds__(TINY_WG) void tiny_kernel(const T* __restrict__ Y, T* __restrict__ X,
+__global__ __launch_bounds__(TINY_WG) void tiny_kernel(const T* Y, T* X,
                                                        long long n, long long m, double eta,
                                                        int outer, int cw, Ws ws,
                                                        float* __restrict__ v_out,
                                                        float* __restrict__ u_out,
-                                                       unsigned char* __restrict__ mask_out) {
-  tiny_body<Q, T, VEC>(Y, X, n, m, eta, outer, cw, ws, v_out, u_out, mask_out, blockIdx.x);
+                                                       unsigned char* __restrict__ mask_out,
+                                                       int whole) {
+  tiny_body<Q, T, VEC>(Y, X, n, m, eta, outer, cw, ws, v_out, u_out, mask_out, blockIdx.x, whole != 0);
 }
 
 }  // namespace mlproj

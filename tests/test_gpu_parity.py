@@ -1029,7 +1029,8 @@ def test_prepared_batch_can_be_called_again_on_new_contents(mp):
 
 
 def test_batch_in_place_and_kernel_count(mp):
-    """In place; and the three launches of a small batch, seen through the event trace."""
+    """In place; and the launches of a small batch, seen through the event trace: one for the matrices
+    of at most 128 KiB (one workgroup each when in place), three for the others."""
     dev = torch.device("cuda:0")
     Ys = [stored_input(sh, "f32", 60 + i) for i, sh in enumerate(BATCH_SHAPES[:8])]
     etas = [eta_for(Y, "inf", 0.3) for Y in Ys]
@@ -1039,9 +1040,23 @@ def test_batch_in_place_and_kernel_count(mp):
         mp.bilevel_proj_batch(Yd, etas, "inf", Xs=Yd)
     tr.durations_ms()
     tr.close()
-    assert tr.count == 4                                   # aggregate, fold, map and the closing event
+    assert tr.count == 6          # the one-kernel form and its closing event; aggregate, fold, map and the closing event
     for Y, eta, X in zip(Ys, etas, Yd):
         np.testing.assert_allclose(X.cpu().numpy(), orc.bilevel(Y, eta, "inf")["X"], rtol=RTOL, atol=ATOL)
+        assert torch.equal(X, mp.bilevel_proj_stored(torch.from_numpy(Y).to(dev), eta, "inf")), "differs from the single call"
+    # sixteen small matrices in place, as a training loop would: one launch, one workgroup each
+    Ys = [stored_input((256, 128), "f32", 80 + i) for i in range(16)]
+    etas = [eta_for(Y, 2, 0.2) for Y in Ys]
+    Yd = [torch.from_numpy(Y).to(dev) for Y in Ys]
+    tr = mp.KernelTrace(16)
+    with tr:
+        mp.bilevel_proj_batch(Yd, etas, 2, Xs=Yd)
+    tr.durations_ms()
+    tr.close()
+    assert tr.count == 2
+    for Y, eta, X in zip(Ys, etas, Yd):
+        np.testing.assert_allclose(X.cpu().numpy(), orc.bilevel(Y, eta, 2)["X"], rtol=RTOL, atol=ATOL)
+        assert torch.equal(X, mp.bilevel_proj_stored(torch.from_numpy(Y).to(dev), eta, 2))
 
 
 # ------------------------------------------------------------------ seeded random cases
@@ -1281,7 +1296,8 @@ TINY_SHAPES = {"f32": [(256, 128), (16, 2048), (1, 2048), (8, 2048), (64, 512), 
 @pytest.mark.parametrize("storage,shape", [(st, sh) for st, shapes in TINY_SHAPES.items() for sh in shapes])
 def test_tiny_matrices_one_kernel_path(mp, storage, shape, q):
     """A matrix small enough for the single-kernel path: the oracle's result, one kernel in the
-    trace, and for q = inf the bits of the three-kernel chain (which an in-place call still takes)."""
+    trace, for q = inf the bits of the three-kernel chain (which a call on misaligned rows still
+    takes), and the same bits again when projected in place (one workgroup does the whole matrix)."""
     dev = torch.device("cuda:0")
     dt = getattr(torch, STORE_DTYPES[storage])
     Y = stored_input(shape, storage, 71)
@@ -1291,19 +1307,21 @@ def test_tiny_matrices_one_kernel_path(mp, storage, shape, q):
         eta = float(np.float32(frac * norm_p))
         got = run_stored(mp, Y, eta, q, storage, p=p)
         check_stored(got, orc.bilevel_stored(Y, eta, q, storage, p=p), q, storage)
-        chain = torch.from_numpy(Y).to(dev).to(dt)
-        mp.bilevel_proj_stored(chain, eta, q, p=p, X=chain)          # in place: the three-kernel chain
+        chain = run_stored(mp, Y, eta, q, storage, p=p, offset=1)["X"]          # rows not 16-byte aligned: the chain
         if q == "inf":
-            assert np.array_equal(chain.float().cpu().numpy(), got["X"])
+            assert np.array_equal(chain, got["X"])
         else:
-            np.testing.assert_allclose(chain.float().cpu().numpy(), got["X"], rtol=2e-2 if storage != "f32" else RTOL,
-                                       atol=ATOL)
-    Yd = torch.from_numpy(Y).to(dev).to(dt)
-    ws = mp.Workspace.for_call(QNAME[q], *shape, device=dev)
-    tr = mp.KernelTrace(8)
-    with tr:
-        mp.bilevel_proj_stored(Yd, eta, q, workspace=ws)
-    tr.durations_ms()
-    tr.close()
-    if q != 1:
-        assert tr.count == 2, "one kernel and the closing event"
+            np.testing.assert_allclose(chain, got["X"], rtol=2e-2 if storage != "f32" else RTOL, atol=ATOL)
+        inplace = torch.from_numpy(Y).to(dev).to(dt)
+        mp.bilevel_proj_stored(inplace, eta, q, p=p, X=inplace)
+        assert np.array_equal(inplace.float().cpu().numpy(), got["X"]), "in place differs from out of place"
+    for inplace in (False, True):
+        Yd = torch.from_numpy(Y).to(dev).to(dt)
+        ws = mp.Workspace.for_call(QNAME[q], *shape, device=dev)
+        tr = mp.KernelTrace(8)
+        with tr:
+            mp.bilevel_proj_stored(Yd, eta, q, X=Yd if inplace else None, workspace=ws)
+        tr.durations_ms()
+        tr.close()
+        if q != 1:
+            assert tr.count == 2, "one kernel and the closing event"
