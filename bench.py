@@ -194,6 +194,12 @@ def bench_tensor(torch, mp, Y_host, frac, steps, warmup):
             ws3 = mp.Workspace.for_call("tri", *Y_host.shape, device=dev)
             record("trilevel_proj_l1infinf", lambda Y, X: mp.trilevel_proj_l1infinf(Y, eta, X=X, workspace=ws3), ws3, eta)
         record("multilevel_proj/" + name, lambda Y, X: mp.multilevel_proj(Y, norms, eta, X=X, workspace=ws), ws, eta)
+        if name == "l111":
+            # the weighted l1 ball on top: weights exp(U(-1, 1)) seeded by the shape, eta = frac * sum_a w_a v_a
+            wts = torch.from_numpy(np.exp(np.random.default_rng(list(Y_host.shape) + [17]).uniform(-1, 1, d0)).astype(np.float32)).to(dev)
+            eta_w = float(np.float32(frac * float((wts.double() * v.double()).sum().item())))
+            record("multilevel_proj_weighted/" + name,
+                   lambda Y, X: mp.multilevel_proj_weighted(Y, norms, eta_w, wts, X=X, workspace=ws), ws, eta_w)
     # the same tensor stored in bf16 (4 bytes per element moved instead of 8)
     del pairs
     torch.cuda.empty_cache()
