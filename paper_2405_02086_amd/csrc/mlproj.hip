@@ -137,7 +137,8 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
 // The search for a weighted l1 ball as outer norm (ws.wts set).  One workgroup re-reads what its
 // registers do not hold in every round: beyond 32768 groups the grid-wide form goes first, with
 // the one-workgroup kernel as its fallback.
-static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStream_t stream) {
+static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStream_t stream,
+                                   double* radii = nullptr, float* u_out = nullptr) {
   int only_as_fallback = 0;
   if (m > 32768) {
     long long nwg = cdiv(m, (long long)COOP_THREADS * COOP_VALUES);
@@ -147,11 +148,11 @@ static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStr
     only_as_fallback = 1;
   }
   if (m <= 4096)
-    hipLaunchKernelGGL((search_weighted_kernel<256, 16>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback);
+    hipLaunchKernelGGL((search_weighted_kernel<256, 16>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback, radii, u_out);
   else if (m <= 16384)
-    hipLaunchKernelGGL((search_weighted_kernel<256, 64>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback);
+    hipLaunchKernelGGL((search_weighted_kernel<256, 64>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback, radii, u_out);
   else
-    hipLaunchKernelGGL((search_weighted_kernel<SWG, 16>), dim3(1), dim3(SWG), 0, stream, ws, m, eta, only_as_fallback);
+    hipLaunchKernelGGL((search_weighted_kernel<SWG, 16>), dim3(1), dim3(SWG), 0, stream, ws, m, eta, only_as_fallback, radii, u_out);
 }
 
 // l1,1: how many lock-step sweeps to enqueue before the finishing pass, and the number of
@@ -713,6 +714,9 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
   if (!fuse_top) mark(stream);
   if (fuse_top) {
     // nothing here: see the first map below
+  } else if (weights && dims[0] <= 32768) {
+    // (one workgroup: it writes the radii too, and nothing has to be cleared for it)
+    launch_weighted_search(ws, dims[0], (double)eta, stream, R[ndim - 1], u_out);
   } else if (weights) {
     hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WG), 0, stream, ws);
     launch_weighted_search(ws, dims[0], (double)eta, stream);
@@ -755,7 +759,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 350; }
+int mlproj_version(void) { return 351; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

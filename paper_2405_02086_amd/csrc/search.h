@@ -203,7 +203,9 @@ __global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, d
 // The record gets norm = sum w_j v_j and vmax = max v_j; with eta = 0, tau = max v_j / w_j.
 template <int NT, int CACHE>
 __global__ __launch_bounds__(NT) void search_weighted_kernel(Ws ws, long long ngroups, double eta,
-                                                              int only_as_fallback) {
+                                                              int only_as_fallback,
+                                                              double* __restrict__ radii,
+                                                              float* __restrict__ u_out) {
   __shared__ PairScratch<NT / WAVE> s;
   if (only_as_fallback && ws.flags[1] == 0u) return;
   const long long tid = threadIdx.x;
@@ -287,6 +289,14 @@ __global__ __launch_bounds__(NT) void search_weighted_kernel(Ws ws, long long ng
   }
   if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
   if (threadIdx.x == 0) write_result(ws, o, nullptr);
+  if (radii) {   // (optional) also the radii u_j = max(v_j - tau w_j, 0) of every group
+    const Top top = top_of(o);
+    for (long long i = tid; i < ngroups; i += NT) {
+      const double u = radius_of(ws, i, v[i], top);
+      radii[i] = u;
+      if (u_out) u_out[i] = (float)u;
+    }
+  }
 }
 
 // The same search for very long v (more groups than one workgroup holds in registers): up to
