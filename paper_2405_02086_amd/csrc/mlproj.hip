@@ -15,8 +15,8 @@
 //   colmap    Y, v, tau -> X                                  (reads Y again, writes X once)
 // Workgroups never wait for one another inside a kernel: on this GPU a device-scope fence
 // costs an L2 write-back, so cross-workgroup results travel across kernel boundaries only
-// (the one exception, the search over more than 32768 groups, meets at a barrier made of
-// device-scope atomics alone).  The tri-level form uses the same chain with groups that are
+// (the one exception, the search over more than 32768 groups, exchanges a few words per round
+// through device-scope atomics alone).  The tri-level form uses the same chain with groups that are
 // contiguous slabs; the generic multi-level form works on contiguous fibres, level by level;
 // a batch of matrices shares the three launches of the chain; a matrix of at most 128 KiB takes
 // one kernel in which every workgroup holds all of Y (tiny.h).
