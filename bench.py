@@ -93,11 +93,12 @@ def time_kernels(torch, mp, fn, pairs, steps, warmup):
 
 
 def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, eta_abs=None, storage="f32",
-                  keep_output=False, weighted=False):
+                  keep_output=False, weighted=False, outer=1):
     """storage "bf16" / "f16": the same matrix rounded to 16 bits, through bilevel_proj_stored
     (half the bytes: 4 per element instead of 8 in the effective figures).
     weighted: the weighted l1 ball as outer norm (fp32 storage), weights exp(U(-1, 1)) seeded by
-    the shape, eta = frac * sum_j w_j v_j."""
+    the shape, eta = frac * sum_j w_j v_j.  outer = 2 or "inf": the l2 or l_inf ball as outer norm
+    (fp32 storage), eta = frac * ||v||_2 or frac * max v."""
     import numpy as np
     dev = torch.device("cuda:0")
     n, m = Y_host.shape
@@ -120,6 +121,13 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
         mp.bilevel_proj_stored(Y0, 1.0, q, workspace=ws, v_out=vbuf)      # (only for v)
         eta = float(np.float32(frac * float((wts.double() * vbuf.double()).sum().item())))
         fn = lambda Y, eta, X, workspace, v_out=None: mp.bilevel_proj_weighted(Y, eta, q, wts, X=X, workspace=workspace, v_out=v_out)
+    elif outer != 1:
+        q = {"l1inf": "inf", "l11": 1, "l12": 2}[variant]
+        vbuf = torch.empty(m, dtype=torch.float32, device=dev)
+        mp.bilevel_proj_stored(Y0, 1.0, q, workspace=ws, v_out=vbuf)      # (only for v)
+        norm_p = float(vbuf.double().norm().item()) if outer == 2 else float(vbuf.max().item())
+        eta = float(np.float32(frac * norm_p))
+        fn = lambda Y, eta, X, workspace, v_out=None: mp.bilevel_proj_stored(Y, eta, q, p=outer, X=X, workspace=workspace, v_out=v_out)
     else:
         eta = device_eta(mp, Y0, variant, frac, ws) if eta_abs is None else float(eta_abs)
         fn = getattr(mp, "bilevel_proj_" + variant)
@@ -438,6 +446,9 @@ def main():
         also["square_4096/l1inf/bf16"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, storage="bf16")
         also["square_4096/l12"] = bench_bilevel(torch, mp, Y, "l12", w.eta_frac, 100, 10)
         also["square_4096/l11"] = bench_bilevel(torch, mp, Y, "l11", w.eta_frac, 50, 5)
+        # the l2 and l_inf balls as outer norm (no iteration in the search)
+        also["square_4096/l1inf/outer_l2"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, outer=2)
+        also["square_4096/l1inf/outer_linf"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, outer="inf")
         # the weighted l1 ball as outer norm (its own one-workgroup search kernel, nothing fused)
         also["square_4096/l1inf/weighted"] = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, 100, 10, weighted=True)
         also["square_4096/l11/weighted"] = bench_bilevel(torch, mp, Y, "l11", w.eta_frac, 50, 5, weighted=True)
