@@ -88,7 +88,9 @@ typedef enum mlproj_storage {
 } mlproj_storage;
 
 /* Record left at offset 0 of the workspace by every projection / norm call.
- * The outer projection acts on every aggregate as u_j = min(cap, scale * max(v_j - tau, 0)). */
+ * The outer projection acts on every aggregate as u_j = min(cap, scale * max(v_j - tau, 0));
+ * with a weighted l1 ball as outer norm (the *_weighted entry points) as
+ * u_j = scale * max(v_j - tau w_j, 0), where norm = sum_j w_j v_j and scale is 1, or 0 with eta = 0. */
 typedef struct mlproj_result {
   double tau;            /* p = 1: threshold of u = P^1_eta(v); 0 inside the ball and for p = 2, inf */
   double norm;           /* ||Y||_{p,q} of the input (fp64); mlproj_norm_l1q: sum_j v_j              */
@@ -105,7 +107,7 @@ typedef struct mlproj_result {
   uint32_t reserved[2];
 } mlproj_result;
 
-/* Library version: major*10000 + minor*100 + patch. */
+/* Library version: a number that grows with every change of the kernels. */
 int mlproj_version(void);
 
 /* Static, human-readable text for a status code. */
