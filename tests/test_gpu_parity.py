@@ -664,6 +664,53 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(mp):
             assert torch.equal(Xg, eager), (q, rep)
 
 
+def test_graph_replay_of_the_other_launch_chains(mp):
+    """The same for the chains with kernels of their own: the several-workgroup search (its
+    slots are cleared by a kernel of the same call, so every replay starts clean), the weighted
+    outer norm, the one-kernel form of a small matrix, a batch in place, and a multi-level call."""
+    rng = np.random.default_rng(52)
+    dev = torch.device("cuda:0")
+
+    def check(make_call, out, refresh, reps=4):
+        eager = make_call(None).clone()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            make_call(out)
+        for rep in range(reps):
+            out.zero_()
+            if rep == 2:
+                refresh()
+                eager = make_call(None).clone()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), rep
+
+    # more than 32768 columns: the several-workgroup search
+    Y = torch.from_numpy(rng.laplace(size=(4, 70000)).astype(np.float32)).to(dev)
+    ws = mp.Workspace.for_call("l1inf", 4, 70000, device=dev)
+    eta = eta_for(Y.cpu().numpy(), "inf", 0.1)
+    check(lambda X: mp.bilevel_proj_l1inf(Y, eta, X=X, workspace=ws), torch.zeros_like(Y), lambda: Y.mul_(0.5))
+    # weighted outer norm, with more than 32768 columns and with few
+    for shape in ((4, 70000), (300, 520)):
+        Y = torch.from_numpy(rng.standard_normal(shape).astype(np.float32)).to(dev)
+        w = torch.from_numpy(weights_for(shape[1], 4)).to(dev)
+        ws = mp.Workspace.for_call("l1inf", *shape, device=dev)
+        eta = weighted_eta(Y.cpu().numpy(), "inf", w.cpu().numpy(), 0.2)
+        check(lambda X: mp.bilevel_proj_weighted(Y, eta, "inf", w, X=X, workspace=ws), torch.zeros_like(Y), lambda: Y.mul_(0.5))
+    # the one-kernel form of a small matrix
+    Y = torch.from_numpy(rng.standard_normal((256, 128)).astype(np.float32)).to(dev)
+    ws = mp.Workspace.for_call("l12", 256, 128, device=dev)
+    eta = eta_for(Y.cpu().numpy(), 2, 0.3)
+    check(lambda X: mp.bilevel_proj_l12(Y, eta, X=X, workspace=ws), torch.zeros_like(Y), lambda: Y.mul_(0.5))
+    # a multi-level call
+    T = torch.from_numpy(rng.standard_normal((20, 30, 64)).astype(np.float32)).to(dev)
+    ws = mp.Workspace(mp.multilevel_workspace_bytes(T.shape), device=dev)
+    eta = float(np.float32(0.2 * nested_norm(T.cpu().numpy(), [1, 1])))
+    check(lambda X: mp.multilevel_proj(T, [1, 1], eta, X=X, workspace=ws), torch.zeros_like(T), lambda: T.mul_(0.5))
+
+
 # ------------------------------------------------------------------ 16-bit storage
 STORE_DTYPES = {"bf16": "bfloat16", "f16": "float16", "f32": "float32"}
 
