@@ -567,7 +567,8 @@ def test_two_streams_two_workspaces(mp):
     rng = np.random.default_rng(42)
     dev = torch.device("cuda:0")
     jobs = []
-    for q, shape in (("inf", (2048, 1024)), (2, (1024, 2048)), (1, (600, 900)), ("inf", (16, 30000))):
+    # (the last two run the several-workgroup search side by side, each on its own slots)
+    for q, shape in (("inf", (2048, 1024)), (2, (1024, 2048)), (1, (600, 900)), ("inf", (16, 70000)), (2, (8, 150000))):
         Y = rng.standard_normal(shape).astype(np.float32)
         eta = eta_for(Y, q, 0.3)
         jobs.append((q, Y, eta, torch.from_numpy(Y).to(dev), mp.Workspace.for_call(QNAME[q], *shape, device=dev),
