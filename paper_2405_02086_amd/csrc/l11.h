@@ -667,6 +667,27 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
         held[u0 + u] = r + (long long)(u0 + u) * FIN_ROWS < n ? fabsf((float)x[u]) : 0.0f;   // 0 is never above a threshold
       __builtin_amdgcn_sched_barrier(0);
     }
+    // With the rows at hand the column's largest entry costs one fold, and it gives a second
+    // certified bound: the largest entry alone already sums to a_max - t, so the root is at
+    // least a_max - u_j.  Where the radius is small beside the entries (the sparse results the
+    // projection is used for) that bound is next to the root, while the climb from the
+    // all-active bound takes a dozen rounds (and the Gaussian guess may lie beyond a_max).
+    float hm = 0.0f;
+#pragma unroll
+    for (int u = 0; u < FIN_HELD; ++u) hm = fmaxf(hm, held[u]);
+    hm = fmaxf(hm, __shfl_xor(hm, 16));
+    hm = fmaxf(hm, __shfl_xor(hm, 32));
+    if (lane < FIN_COLS) sm_s[wave][c] = (double)hm;
+    __syncthreads();
+    double amax = sm_s[0][c];
+#pragma unroll
+    for (int w = 1; w < FIN_WAVES; ++w) amax = fmax(amax, sm_s[w][c]);
+    __syncthreads();   // (the rows of sm_s are written again in the first round)
+    if (amax - uj > lb) lb = amax - uj;
+    if (first ? (t <= lb || t >= amax) : true) {
+      t = lb;          // the guess is no better than the bound (or beyond every entry): start from the bound
+      first = false;
+    }
   }
   for (;;) {
     const float ct = above(t);

@@ -759,7 +759,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 351; }
+int mlproj_version(void) { return 352; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
