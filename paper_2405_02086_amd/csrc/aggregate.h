@@ -82,19 +82,23 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, lon
   colagg_body<Q, T, VEC, STRIDED>(Y, n, m, g, partial_, blockIdx.x);
 }
 
-// v_j from the partials of its tile, folded in a fixed order.  A workgroup of 1024 threads
-// covers 1024/parts groups with `parts` threads each (parts = 1..16, a power of two chosen on
+// v_j from the partials of its tile, folded in a fixed order.  A workgroup of NT threads
+// covers NT/parts groups with `parts` threads each (parts = 1..NT/64, a power of two chosen on
 // the host from the number of partials per group); every thread keeps 8 loads in flight.
 // Serves columns (tile_w = 64*vec) and slabs (tile_w = 1) alike.
-template <int Q>
+// NT = 1024 or 256.  The kernel is a launch, one load latency and a fold, so for 16 to 64
+// partials per group four wavefronts with a few loads each are in and out sooner than sixteen
+// (4096 x 4096: 37.2 -> 36.7 us per projection, 25.1 -> 24.3 on bf16 storage); with hundreds of
+// partials per group (a tall matrix) the sixteen shorter chains win (130 against 133 us).
+template <int Q, int NT = SWG>
 __device__ __forceinline__ void reduce_body(const void* __restrict__ partial_, long long ngroups,
                                             const Geometry& g, int parts, double* __restrict__ v,
                                             float* __restrict__ v_out,
                                             unsigned* __restrict__ flags, long long bid) {
   using Acc = typename AccOf<Q>::type;
-  __shared__ Acc sm[SWG];
+  __shared__ Acc sm[NT];
   if (bid == 0) clear_meeting_area(flags);  // for the grid-wide search
-  const int cols = SWG / parts;
+  const int cols = NT / parts;
   const int c_local = threadIdx.x % cols;
   const int part = threadIdx.x / cols;
   const long long j = bid * cols + c_local;
@@ -123,13 +127,13 @@ __device__ __forceinline__ void reduce_body(const void* __restrict__ partial_, l
   }
 }
 
-template <int Q>
-__global__ __launch_bounds__(SWG) void reduce_kernel(const void* __restrict__ partial_,
+template <int Q, int NT = SWG>
+__global__ __launch_bounds__(NT) void reduce_kernel(const void* __restrict__ partial_,
                                                      long long ngroups, Geometry g, int parts,
                                                      double* __restrict__ v,
                                                      float* __restrict__ v_out,
                                                      unsigned* __restrict__ flags) {
-  reduce_body<Q>(partial_, ngroups, g, parts, v, v_out, flags, blockIdx.x);
+  reduce_body<Q, NT>(partial_, ngroups, g, parts, v, v_out, flags, blockIdx.x);
 }
 
 }  // namespace mlproj

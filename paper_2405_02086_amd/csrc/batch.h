@@ -69,7 +69,7 @@ __global__ __launch_bounds__(SWG) void reduce_batch_kernel(BatchItems it, BatchG
   const BatchItem& b = it.item[batch_find(gr, it.count, bid)];
   const Geometry g = plan_columns(b.n, b.m, WIDE, Q);
   const Ws ws = bind(b.ws, layout_for(g, b.m, Q));
-  reduce_body<Q>(ws.partial, b.m, g, reduce_parts(g.groups), ws.v, b.v_out, ws.flags, bid);
+  reduce_body<Q>(ws.partial, b.m, g, reduce_parts(g.groups, fold_threads(g.groups)), ws.v, b.v_out, ws.flags, bid);
 }
 
 template <int Q, typename T, int SC>

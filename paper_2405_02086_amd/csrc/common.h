@@ -130,9 +130,16 @@ static Geometry plan_slabs(long long d0, long long len, int vec) {
 
 // Threads per group in the kernels that fold per-(tile, row group) partials: a power of two,
 // at most 16, chosen from the number of partials per group.
-__host__ __device__ static inline int reduce_parts(long long partials_per_group) {
+// The fold kernel's workgroup size for a matrix with `groups` partials per group (see
+// reduce_body).  A batch folds with 1024 threads throughout but with the `parts` this size
+// gives, so that its sums associate as in the single call and return its bits.
+__host__ __device__ static inline int fold_threads(long long groups) {
+  return (groups >= 16 && groups <= 64) ? 256 : SWG;
+}
+// (`threads`: the fold kernel's workgroup size, 1024 or 256.)
+__host__ __device__ static inline int reduce_parts(long long partials_per_group, int threads = SWG) {
   int parts = 1;
-  while (parts < SWAVES && parts < partials_per_group) parts *= 2;
+  while (parts < threads / WAVE && parts < partials_per_group) parts *= 2;
   return parts;
 }
 

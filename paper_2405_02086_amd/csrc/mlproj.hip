@@ -111,26 +111,37 @@ static inline void mark(hipStream_t stream) {
 // search gives up and the one-workgroup kernel behind it takes over (0: give up at once).
 static unsigned g_spin_limit = SPIN_LIMIT;
 
-// The stand-alone search: one workgroup of 1024 threads while v fits its registers (16 values
-// per thread up to 16384 groups, 32 up to 32768), the grid-wide form beyond that, followed by
-// the one-workgroup kernel as a fallback that returns at once unless the grid-wide one gave up.
+// The stand-alone search: up to 16384 groups one workgroup running the search of the map
+// kernels' prologue (so a split call returns the whole call's bits), one workgroup of 1024
+// threads with 32 values each up to 32768, the several-workgroup form beyond that, followed by
+// a one-workgroup kernel as a fallback that returns at once unless that form gave up.
 static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, int outer,
                           double* norm_out, hipStream_t stream) {
+  if (ngroups <= FUSED_SEARCH_MAX) {
+    hipLaunchKernelGGL((search_kernel<WG, SEARCH_CACHE>), dim3(1), dim3(WG), 0, stream, ws, ngroups, eta, mode, outer,
+                       norm_out, 0, (double*)nullptr, (float*)nullptr);
+    return;
+  }
+  if (ngroups <= FUSED_SEARCH_MAX_BIG) {
+    hipLaunchKernelGGL((search_kernel<WG, SEARCH_CACHE_BIG>), dim3(1), dim3(WG), 0, stream, ws, ngroups, eta, mode, outer,
+                       norm_out, 0, (double*)nullptr, (float*)nullptr);
+    return;
+  }
   int only_as_fallback = 0;
   // (the l2 and l_inf outer projections need no iteration: one workgroup reads v once)
   const bool iterates = outer == MLPROJ_OUTER_L1 || mode == MODE_NORM;
-  if (ngroups > (long long)SWG * SEARCH_CACHE && ngroups <= (long long)SWG * SEARCH_CACHE_ONE_WG && iterates) {
-    hipLaunchKernelGGL(search_kernel<SEARCH_CACHE_ONE_WG>, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode,
+  if (ngroups <= (long long)SWG * SEARCH_CACHE_ONE_WG && iterates) {
+    hipLaunchKernelGGL((search_kernel<SWG, SEARCH_CACHE_ONE_WG>), dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode,
                        outer, norm_out, 0, (double*)nullptr, (float*)nullptr);
     return;
   }
-  if (ngroups > (long long)SWG * SEARCH_CACHE && iterates) {
+  if (iterates) {
     long long nwg = cdiv(ngroups, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
     hipLaunchKernelGGL((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, ngroups, eta, mode, norm_out, g_spin_limit);
     only_as_fallback = 1;
   }
-  hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
+  hipLaunchKernelGGL((search_kernel<SWG, SEARCH_CACHE>), dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
                      only_as_fallback, (double*)nullptr, (float*)nullptr);
 }
 
@@ -212,8 +223,9 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
   const dim3 mgrid((unsigned)(g.tiles * g.map_groups));
-  const int parts = reduce_parts(g.groups);
-  const dim3 rgrid((unsigned)cdiv(m, SWG / parts)), rblock(SWG);
+  const int rthreads = fold_threads(g.groups);
+  const int parts = reduce_parts(g.groups, rthreads);
+  const dim3 rgrid((unsigned)cdiv(m, rthreads / parts)), rblock(rthreads);
   // A whole call on few enough groups lets every map workgroup find tau by itself, which
   // takes the one-workgroup search kernel off the critical path (16 values of v per thread
   // up to 4096 groups, 64 per thread up to 16384).
@@ -242,7 +254,10 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     else
       hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws.partial);
     mark(stream);
-    hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+    if (rthreads == 256)
+      hipLaunchKernelGGL((reduce_kernel<Q, 256>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+    else
+      hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
     // (l1,1: the kernel that seeds the inner searches runs the outer search the same way)
     const bool fuse_l11 = Q == Q1 && mode == MODE_PROJECT && m <= FUSED_SEARCH_MAX_BIG && !weights;
     if (weights) {
@@ -456,7 +471,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
       b.whole = 0;
       const Geometry g = plan_columns(p.n, p.m, WIDE, Q);
       agg.first[it.count] = a; a += (unsigned)(g.tiles * g.groups);
-      red.first[it.count] = r; r += (unsigned)cdiv(p.m, SWG / reduce_parts(g.groups));
+      red.first[it.count] = r; r += (unsigned)cdiv(p.m, SWG / reduce_parts(g.groups, fold_threads(g.groups)));
       map.first[it.count] = mp; mp += (unsigned)(g.tiles * g.map_groups);
       ini.first[it.count] = in; in += (unsigned)cdiv(p.m, WG);
       upd.first[it.count] = up; up += (unsigned)cdiv(p.m, UPD_COLS);
@@ -723,7 +738,7 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
     hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
                        dims[0], R[ndim - 1], u_out);
   } else if (dims[0] <= (long long)SWG * SEARCH_CACHE || outer != MLPROJ_OUTER_L1) {
-    hipLaunchKernelGGL(search_kernel<SEARCH_CACHE>, dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
+    hipLaunchKernelGGL((search_kernel<SWG, SEARCH_CACHE>), dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
                        outer, (double*)nullptr, 0, R[ndim - 1], u_out);
   } else {
     hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WG), 0, stream, ws);
@@ -759,7 +774,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 352; }
+int mlproj_version(void) { return 353; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -162,23 +162,27 @@ __device__ __forceinline__ void write_result(const Ws& ws, const SearchOut& o,
 }
 
 // radii / u_out (optional): also write u_j = max(v_j - tau, 0) for every group.
-// CACHE values of v per thread in registers: 16 (up to 16384 groups) or 32 (up to 32768; 64 would
-// not fit the 128 registers a 1024-thread workgroup leaves each thread).
-template <int CACHE>
-__global__ __launch_bounds__(SWG) void search_kernel(Ws ws, long long ngroups, double eta,
-                                                     int mode, int outer,
-                                                     double* __restrict__ norm_out,
-                                                     int only_as_fallback,
-                                                     double* __restrict__ radii,
-                                                     float* __restrict__ u_out) {
-  __shared__ PairScratch<SWAVES> s;
+// NT threads with CACHE values of v per thread in registers.  Up to 16384 groups the host
+// launches the very search the map kernels run in their prologue (256 threads, 16 or 64
+// values), so that a split call (radii first, map later) finds tau with the bits of the whole
+// call; 1024 threads with 32 values serve 16385-32768 groups (64 would not fit the 128
+// registers a 1024-thread workgroup leaves each thread), 1024 x 16 stands behind the
+// several-workgroup search.
+template <int NT, int CACHE>
+__global__ __launch_bounds__(NT) void search_kernel(Ws ws, long long ngroups, double eta,
+                                                    int mode, int outer,
+                                                    double* __restrict__ norm_out,
+                                                    int only_as_fallback,
+                                                    double* __restrict__ radii,
+                                                    float* __restrict__ u_out) {
+  __shared__ PairScratch<NT / WAVE> s;
   if (only_as_fallback && ws.flags[1] == 0u) return;
-  const SearchOut o = search_block<SWG, CACHE>(ws.v, ngroups, eta, mode, outer, s);
+  const SearchOut o = search_block<NT, CACHE>(ws.v, ngroups, eta, mode, outer, s);
   if (threadIdx.x <= MAX_INNER_SWEEPS) ws.pending[threadIdx.x] = 0u;
   if (threadIdx.x == 0) write_result(ws, o, norm_out);
   if (radii) {
     const Top top = top_of(o);
-    for (long long i = threadIdx.x; i < ngroups; i += SWG) {
+    for (long long i = threadIdx.x; i < ngroups; i += NT) {
       const double u = radius(ws.v[i], top);
       radii[i] = u;
       if (u_out) u_out[i] = (float)u;
