@@ -27,8 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (352,)   # the library version the counters in profiles/ were taken with
-TRAFFIC_KIB = {"square_4096": 32981.1 * 1.999 + 65561.7, "square_16384": 524925.6 * 1.999 + 1048623.0}
+TRAFFIC_VERSIONS = (353,)   # the library version the counters in profiles/ were taken with
+TRAFFIC_KIB = {"square_4096": 32975.6 * 1.999 + 65603.6, "square_16384": 524925.6 * 1.999 + 1048621.6}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 
