@@ -4,13 +4,16 @@
 A "step" is one whole projection (aggregate, threshold search, clip) of one matrix that is
 already resident in HBM.  The headline workload is the 4096 x 4096 fp32 matrix; the timed loop
 rotates through enough (Y, X) buffer pairs that the 256 MB Infinity Cache cannot serve the
-first read of Y (a cold measurement).  One JSON line goes to stdout:
+first read of Y (a cold measurement).  Two JSON lines go to stdout: first everything bulky
+({"detail": ...}: per-kernel intervals, the other workloads and variants, sweeps, batches; also
+written to gpurun_out/bench_detail.json), then, LAST, one compact record (under 2 KB):
 
   value          effective GB/s = 8 bytes/element * n*m / time  (read Y once, write X once)
   ms_per_step    milliseconds per projection
   roofline       the dominant kernel against the 8 TB/s HBM peak, timed with HIP events
-  cpu_baseline   the CPU oracle on the same workload on this host
-  also           the same figures for the 1 GiB workload and the other variants (--quick skips)
+  cpu_baseline   the CPU oracle on the same workload on this host: one thread, and all usable
+                 cores with the columns split over worker processes (Sec. 6.2's decomposition)
+  other_workloads  ms and fraction of the peak for the other configurations (--quick skips)
 """
 import argparse
 import json
@@ -367,7 +370,86 @@ def bench_batch(torch, mp, shape, count, frac, steps, warmup, variant="l1inf"):
     return out
 
 
-def cpu_baseline(Y_host, eta, x_timed, tau_gpu, budget_s=20.0):
+def host_description():
+    """Logical CPUs this process may use, and the CPU model string of the host."""
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.lower().startswith("model name"):
+                    model = ln.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return usable, os.cpu_count() or usable, model
+
+
+# ---- the all-cores leg of the CPU baseline: the paper's own decomposition (Sec. 6.2: a pool of
+# workers over blocks of columns for the aggregate and for the per-column map, the vector
+# projection in between on the main thread).  Worker processes are forked BEFORE this process
+# touches the GPU and run nothing but the oracle's functions on their block of columns.
+_POOL_Y = None      # the workload matrix, inherited by the forked workers
+_POOL_X = None      # shared output buffer (multiprocessing.RawArray), inherited too
+
+
+def _pool_aggregate(block):
+    from oracle import mlproj_oracle as orc
+    a, b = block
+    return a, orc.column_norms(_POOL_Y[:, a:b], "inf")
+
+
+def _pool_map(task):
+    import numpy as np
+    from oracle import mlproj_oracle as orc
+    a, b, u = task
+    n, m = _POOL_Y.shape
+    X = np.frombuffer(_POOL_X, dtype=np.float32).reshape(n, m)
+    for j in range(a, b):                      # x_j = P^inf_{u_j}(y_j), column by column
+        X[:, j] = orc.project_linf_ball(_POOL_Y[:, j], u[j - a])
+    return a
+
+
+def cpu_all_cores(Y_host, eta, budget_s=12.0):
+    """The oracle's three steps with the columns split over a pool of worker processes, one per
+    usable core (the thread-pool decomposition of Sec. 6.2); the vector projection stays serial.
+    Must run before the GPU is initialised (it forks).  Returns the timing record and X."""
+    import multiprocessing as mp_
+    import numpy as np
+    from oracle import mlproj_oracle as orc
+    global _POOL_Y, _POOL_X
+    usable, _, _ = host_description()
+    cap = os.environ.get("OMP_NUM_THREADS")
+    workers = max(1, min(usable, int(cap)) if cap and cap.isdigit() else usable)
+    n, m = Y_host.shape
+    _POOL_Y = Y_host
+    _POOL_X = mp_.RawArray("f", n * m)
+    edges = [round(k * m / (4 * workers)) for k in range(4 * workers + 1)]   # four blocks per worker
+    blocks = [(a, b) for a, b in zip(edges[:-1], edges[1:]) if b > a]
+    times = []
+    with mp_.get_context("fork").Pool(workers) as pool:
+        t_all = time.perf_counter()
+        while len(times) < 5 and (time.perf_counter() - t_all) < budget_s:
+            t0 = time.perf_counter()
+            v = np.empty(m, dtype=np.float32)
+            for a, part in pool.imap_unordered(_pool_aggregate, blocks):       # step 1, parallel
+                v[a:a + part.size] = part
+            u64, tau = orc.project_l1_ball_nonneg(v, eta)                      # step 2, serial
+            u = u64.astype(np.float32)
+            for _ in pool.imap_unordered(_pool_map, [(a, b, u[a:b]) for a, b in blocks]):   # step 3, parallel
+                pass
+            times.append(time.perf_counter() - t0)
+    X = np.frombuffer(_POOL_X, dtype=np.float32).reshape(n, m).copy()
+    _POOL_Y = _POOL_X = None
+    t = statistics.median(times)
+    return {"cores_all": workers, "ms_all_cores": t * 1e3, "value_all_cores": 8.0 * n * m / t / 1e9,
+            "runs_all_cores": len(times), "tau_all_cores": tau}, X
+
+
+def cpu_baseline(Y_host, eta, x_timed, tau_gpu, budget_s=15.0):
     """The oracle as it stands, single numpy thread, on the headline workload with the radius
     the GPU runs used; its result also checks the X the last timed GPU step produced."""
     import numpy as np
@@ -382,13 +464,23 @@ def cpu_baseline(Y_host, eta, x_timed, tau_gpu, budget_s=20.0):
     n, m = Y_host.shape
     err = np.abs(x_timed.astype(np.float64) - ref["X"])
     bar = 1e-5 * np.abs(ref["X"]) + 1e-6
-    parity = {"checked": "X of the last timed step against the oracle, element by element",
-              "max_abs_err": float(err.max()), "within_rtol1e-5_atol1e-6": bool((err <= bar).all()),
+    parity = {"max_abs_err": float(err.max()), "within_rtol1e-5_atol1e-6": bool((err <= bar).all()),
               "support_identical": bool(np.array_equal(np.abs(x_timed).max(axis=0) > 0, np.asarray(ref["u"]) > 0)),
               "tau_rel_err": abs(tau_gpu - ref["tau"]) / ref["tau"] if ref["tau"] > 0 else 0.0}
+    usable, logical, model = host_description()
     return {"value": 8.0 * n * m / t / 1e9, "unit": "GB/s", "ms": t * 1e3, "cores": 1, "kind": "oracle",
             "sample": "full %dx%d workload, median of %d runs of oracle.bilevel_l1inf (numpy, one thread)"
-                      % (n, m, len(times)), "parity_of_timed_output": parity}
+                      % (n, m, len(times)),
+            "nproc": usable, "logical_cpus": logical, "cpu_model": model,
+            "timed_gpu_output_vs_oracle": parity}, ref["X"]
+
+
+def summary_of(rec):
+    """ms and fraction of the HBM peak (8 B/element model) of one detailed record."""
+    out = {"ms": round(rec["ms"], 5)}
+    if "frac_of_peak_rw" in rec:
+        out["frac"] = round(rec["frac_of_peak_rw"], 4)
+    return out
 
 
 def main():
@@ -397,44 +489,55 @@ def main():
         print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
-    import torch
-    from paper_2405_02086_amd import binding as mp, workloads
-    mp.lib()   # fail loudly if the HIP library is missing
+    from paper_2405_02086_amd import workloads
 
     w, Y = workloads.make(args.workload)
     want_cpu = not (args.quick or args.no_cpu)
+    all_cores = x_all = None
+    if want_cpu:
+        # first, while this process has not touched the GPU: the leg that forks worker processes
+        from oracle import mlproj_oracle as orc
+        eta_cpu = float(np.float32(w.eta_frac * orc.norm_l1q(Y, "inf")))
+        all_cores, x_all = cpu_all_cores(Y, eta_cpu)
+        all_cores["eta_all_cores"] = eta_cpu
+
+    import torch
+    from paper_2405_02086_amd import binding as mp
+    mp.lib()   # fail loudly if the HIP library is missing
+
     head = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
     x_timed = head.pop("_x_timed", None)
     n, m = Y.shape
     elems = n * m
-    # the dominant kernel is the map pass: it reads Y once and writes X once (8 B/element)
+    # the dominant kernel: the one that reads Y and writes X (8 B/element)
     kms = head["kernel_ms"]
-    map_name = [k for k in kms if k.startswith("colmap")][0]
-    map_ms = kms[map_name]
+    dom = max(kms, key=kms.get)
+    dom_ms = kms[dom]
+    traffic_ok = args.workload in TRAFFIC_KIB and mp.lib().mlproj_version() in TRAFFIC_VERSIONS
     roofline = {
-        "bound": "hbm", "kernel": "colmap_kernel<l1inf> (%s; reads Y, writes X: 8 B/element)" % map_name,
-        "achieved": 8.0 * elems / map_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": 8.0 * elems / map_ms / 1e6 / HBM_PEAK_GBS,
-        "traffic": (TRAFFIC_KIB[args.workload] * 1024.0
-                    if args.workload in TRAFFIC_KIB and mp.lib().mlproj_version() in TRAFFIC_VERSIONS else None),
+        "bound": "hbm", "kernel": "%s (l1,inf; 8 B/element: reads Y, writes X)" % dom,
+        "achieved": 8.0 * elems / dom_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": 8.0 * elems / dom_ms / 1e6 / HBM_PEAK_GBS,
+        "traffic": TRAFFIC_KIB[args.workload] * 1024.0 if traffic_ok else None,
+        "traffic_source": ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (library version %d)"
+                           % mp.lib().mlproj_version()) if traffic_ok else None,
         "algorithmic_bytes": 8.0 * elems,
-        "kernel_ms": map_ms,
-        "other_kernels": {"colagg_kernel<l1inf> (reads Y: 4 B/element)": {
-            "kernel_ms": kms["colagg"], "achieved": 4.0 * elems / kms["colagg"] / 1e6}},
+        "kernel_ms": dom_ms,
+        "all_kernels_ms": {k: round(v, 5) for k, v in kms.items()},
     }
     line = {
         "metric": "effective HBM GB/s of one bi-level l1,inf projection (8 B/element: read Y, write X), cold caches",
         "value": head["eff_GBps_rw"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %dx%d fp32 row-major, entries %s, eta=%.2f*||Y||_1,inf"
-                               % (args.workload, n, m, DIST_TEXT[w.dist], w.eta_frac),
-                   "buffer_pairs": head["buffer_pairs"], "timing": "cold (rotating buffers > Infinity Cache)",
-                   "generator": "numpy Generator(PCG64(%d)), see paper_2405_02086_amd/workloads.py" % w.seed,
+        "config": {"workload": "%s: %dx%d fp32 row-major, entries %s, eta=%.2f*||Y||_1,inf; cold (%d rotating buffer pairs)"
+                               % (args.workload, n, m, DIST_TEXT[w.dist], w.eta_frac, head["buffer_pairs"]),
                    "input_crc32": "%08x" % zlib.crc32(Y.tobytes())},
         "frac_of_hbm_peak": head["frac_of_peak_rw"], "ms_per_step_warm": head["ms_warm"],
-        "detail": head, "roofline": roofline,
+        "roofline": roofline,
     }
+    detail = {"headline": head,
+              "generator": "numpy Generator(PCG64(%d)), see paper_2405_02086_amd/workloads.py" % w.seed}
     if not args.quick:
         also = {}
         wb, Yb = workloads.make("square_16384")
@@ -478,9 +581,36 @@ def main():
         also["batch/16x(256x128)/l11"] = bench_batch(torch, mp, (256, 128), 16, 0.1, 100, 10, "l11")
         also["batch/16x(1024x1024)/l11"] = bench_batch(torch, mp, (1024, 1024), 16, 0.1, 100, 10, "l11")
         also["paper_size_sweep"] = bench_size_sweep(torch, mp, workloads, 50, 5)
-        line["also"] = also
+        detail["also"] = also
+        # the other workloads of the parity suite in the last line: ms per projection and the
+        # fraction of the 8 TB/s peak on the 8 B/element model
+        line["other_workloads"] = {
+            "square_16384_l1inf": summary_of(also["square_16384/l1inf"]),
+            "square_16384_l12": summary_of(also["square_16384/l12"]),
+            "square_16384_l11": summary_of(also["square_16384/l11"]),
+            "tall_262144x256": summary_of(also["tall_262144x256/l1inf"]),
+            "wide_256x262144": summary_of(also["wide_256x262144/l1inf"]),
+            "tensor_256x256x256": summary_of(also["tensor_256x256x256/trilevel_proj_l1infinf"]),
+            "small_256x128": {"ms": round(also["small_256x128/l1inf"]["ms_eager"], 5)},
+        }
     if want_cpu:
-        line["cpu_baseline"] = cpu_baseline(Y, head["eta"], x_timed, head["tau"])
+        base, x_ref = cpu_baseline(Y, head["eta"], x_timed, head["tau"])
+        base.update(all_cores)
+        if all_cores["eta_all_cores"] == head["eta"]:
+            base["all_cores_output_equals_one_thread_output"] = bool(np.array_equal(x_all, x_ref))
+        line["cpu_baseline"] = base
+    # Everything bulky first (its own stdout line, and a file where a results folder exists); the
+    # LAST line is the compact record.
+    blob = json.dumps({"detail": detail})
+    print(blob)
+    try:
+        out_dir = os.path.join(ROOT, "gpurun_out")
+        os.makedirs(out_dir, exist_ok=True)
+        with open(os.path.join(out_dir, "bench_detail.json"), "w") as f:
+            f.write(blob + "\n")
+    except OSError:
+        pass
+    sys.stdout.flush()
     print(json.dumps(line))
 
 

@@ -53,7 +53,7 @@ typedef enum mlproj_status {
   MLPROJ_ERR_WORKSPACE = -5,      /* workspace too small or misaligned                */
   MLPROJ_ERR_BAD_VARIANT = -6,    /* unknown variant / norm selector                  */
   MLPROJ_ERR_ALIGNMENT = -7,      /* Y or X not aligned to the element size            */
-  MLPROJ_ERR_LAUNCH = -8          /* the HIP runtime refused a launch (see hipGetLastError) */
+  MLPROJ_ERR_LAUNCH = -8          /* the HIP runtime refused a kernel launch of this call  */
 } mlproj_status;
 
 /* Which projection a workspace is sized for. */
@@ -122,23 +122,31 @@ const char* mlproj_status_string(int status);
 int mlproj_trace_begin(void** events /* host array of hipEvent_t */, int capacity);
 int mlproj_trace_end(void);
 
-/* Tuning knob for MLPROJ_L11 (Alg. 3): how many lock-step passes over Y a call enqueues for
- * the per-column threshold searches before the column-wise finishing pass closes whatever is
+/* TEST AND TUNING HOOKS -- not part of the projection interface.  The two setters below change a
+ * process-wide value (an atomic, read once when a call is enqueued; calls already enqueued keep
+ * what they read).  Neither changes any result: both only move time around.  A caller that never
+ * calls them gets the defaults, and the projection entry points themselves keep no state.
+ *
+ * mlproj_set_l11_sweeps -- MLPROJ_L11 (Alg. 3): how many lock-step passes over Y a call enqueues
+ * for the per-column threshold searches before the column-wise finishing pass closes whatever is
  * still open.  1..16, or 0 for the default, which grows with the number of rows (none up to 1024
  * rows, or up to 4096 rows when the matrix has at most 4M elements; else 3 at 4096, 6 at 16384,
- * 12 beyond 131072): the finishing pass costs more per column
- * the taller the matrix.  The thresholds are exact for any value; only the time changes.
- * Process-wide and read when a call is enqueued: set it while no other thread is calling.
- * Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value outside 0..16.       */
+ * 12 beyond 131072): the finishing pass costs more per column the taller the matrix.  The
+ * thresholds are exact for any value.  Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION
+ * for a value outside 0..16.                                                                */
 int mlproj_set_l11_sweeps(int sweeps);
 
-/* Vectors of more than 32768 groups are searched (Eq. 6-7) by several workgroups that exchange
- * their sums every round; a workgroup that has polled `polls` times for another's numbers gives
- * up, everybody leaves, and a one-workgroup kernel enqueued behind does the search instead
- * (every kernel ends either way, and the result is the same).  This sets that bound: 0 makes
- * the several-workgroup search give up at once (which exercises the kernel behind it), the
- * default is 4194304 (seconds of polling).  Process-wide and read when a call is enqueued.
- * Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value outside 0..4194304.   */
+/* mlproj_set_search_spin_limit -- vectors of more than 32768 groups are searched (Eq. 6-7) by up
+ * to 64 workgroups that exchange their sums every round, which needs all of them running at
+ * once.  On an idle GPU they are; on a GPU that other streams keep full some may have to wait
+ * for a free compute unit.  So the exchange is bounded: a workgroup that has polled `polls`
+ * times for another's numbers gives up, everybody leaves, and a one-workgroup kernel enqueued
+ * behind does the search instead -- every kernel ends either way and the result is the same.
+ * What a caller on a shared GPU sees is a call that takes a fraction of a millisecond longer
+ * (the default, 256 polls of 1-2 us each, plus the one-workgroup search), never a stall.
+ * 0 makes the several-workgroup search give up at once (which is how the tests exercise the
+ * kernel behind it).  Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value
+ * outside 0..4194304.                                                                        */
 int mlproj_set_search_spin_limit(int polls);
 
 /* Bytes of workspace a call of `variant` on dims (d0, d1, d2) needs; bi-level

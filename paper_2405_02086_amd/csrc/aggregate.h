@@ -28,10 +28,15 @@ __device__ __forceinline__ typename AccOf<Q>::type combine(typename AccOf<Q>::ty
 // squares (both in fp64).  Every lane owns VEC columns of the tile (see LaneCols); the four
 // wavefronts of a workgroup take rows r, r+1, r+2, r+3 (mod 4) of each row block.
 // `bid` is the workgroup's number within its own problem (blockIdx.x for a single matrix).
-template <int Q, typename T, int VEC, bool STRIDED>
+// DIRECT (only with one row group per tile, so that a workgroup's partial is the whole column):
+// the workgroup writes v_j (and v_out) itself and workgroup 0 clears the meeting area of the
+// grid-wide search, which is all the fold kernel would have done; the host then skips that launch.
+template <int Q, typename T, int VEC, bool STRIDED, bool DIRECT = false>
 __device__ __forceinline__ void colagg_body(const T* __restrict__ Y, long long n, long long m,
                                             const Geometry& g, void* __restrict__ partial_,
-                                            long long bid) {
+                                            long long bid, double* __restrict__ v = nullptr,
+                                            float* __restrict__ v_out = nullptr,
+                                            unsigned* __restrict__ flags = nullptr) {
   using Acc = typename AccOf<Q>::type;
   constexpr int TILE_W = WAVE * VEC;
   __shared__ Acc sm[WAVES][TILE_W];
@@ -71,7 +76,19 @@ __device__ __forceinline__ void colagg_body(const T* __restrict__ Y, long long n
     Acc a = sm[0][c];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) a = combine<Q>(a, sm[w][c]);
-    static_cast<Acc*>(partial_)[((size_t)t * g.groups + grp) * TILE_W + c] = a;
+    if constexpr (DIRECT) {
+      const long long j = t * TILE_W + c;
+      if (j < m) {
+        const double vj = (Q == Q2) ? sqrt((double)a) : (double)a;
+        v[j] = vj;
+        if (v_out) v_out[j] = (float)vj;
+      }
+    } else {
+      static_cast<Acc*>(partial_)[((size_t)t * g.groups + grp) * TILE_W + c] = a;
+    }
+  }
+  if constexpr (DIRECT) {
+    if (bid == 0) clear_meeting_area(flags);
   }
 }
 
@@ -80,6 +97,16 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, lon
                                                     long long m, Geometry g,
                                                     void* __restrict__ partial_) {
   colagg_body<Q, T, VEC, STRIDED>(Y, n, m, g, partial_, blockIdx.x);
+}
+
+// One row group per tile (a wide or very short matrix): the aggregate pass finishes v itself.
+template <int Q, typename T, int VEC, bool STRIDED>
+__global__ __launch_bounds__(WG) void colagg_direct_kernel(const T* __restrict__ Y, long long n,
+                                                           long long m, Geometry g,
+                                                           double* __restrict__ v,
+                                                           float* __restrict__ v_out,
+                                                           unsigned* __restrict__ flags) {
+  colagg_body<Q, T, VEC, STRIDED, true>(Y, n, m, g, nullptr, blockIdx.x, v, v_out, flags);
 }
 
 // v_j from the partials of its tile, folded in a fixed order.  A workgroup of NT threads

@@ -35,7 +35,13 @@ constexpr long long TARGET_WGS_MAP = 256;  // workgroups of the read+write pass 
 constexpr int COOP_MAX_WGS = 64;         // workgroups of the grid-wide search (far fewer than CUs)
 constexpr int COOP_THREADS = 256;        // threads of each of them
 constexpr int COOP_VALUES = 32;          // values of v per thread there
-constexpr unsigned SPIN_LIMIT = 1u << 22; // polls before a waiting workgroup gives up (seconds)
+// Polls a lane of the grid-wide search spends on another workgroup's post before the search gives
+// up and the one-workgroup kernel behind it takes over.  A poll is one round trip to the memory
+// side (1-2 us) and every workgroup posts within microseconds of starting, so the default is a
+// fraction of a millisecond: on a GPU that other work keeps full (not every workgroup resident)
+// the call pays that once, never seconds.
+constexpr unsigned SPIN_LIMIT = 256;
+constexpr unsigned SPIN_LIMIT_MAX = 1u << 22;   // the most the test hook accepts
 constexpr int COOP_WORDS = 6;            // 64-bit words a workgroup posts per round there (tag and 32 bits of payload each)
 constexpr int COOP_SLOT_WORDS = 2 * COOP_WORDS * COOP_MAX_WGS;
 constexpr int COOP_FLAG_BYTES = 256;

@@ -23,6 +23,10 @@
 //
 // This file is the one translation unit: the kernels live in the headers it includes (one per
 // pass), the host code below checks arguments, plans the launch geometry and enqueues.
+#include <atomic>
+#include <tuple>
+#include <utility>
+
 #include "common.h"
 #include "reduce.h"
 #include "aggregate.h"
@@ -91,7 +95,32 @@ static int check_radius(float eta) {
   return MLPROJ_OK;
 }
 
-static int launch_status() { return hipGetLastError() == hipSuccess ? MLPROJ_OK : MLPROJ_ERR_LAUNCH; }
+// Every kernel goes out through hipLaunchKernel, whose return value is the status of that launch
+// alone: the process-wide "last error" of the HIP runtime, which an unrelated earlier call of the
+// application may have set, is neither read nor cleared.  A refused launch is remembered for the
+// calling thread until the entry point returns (launch_status), which also stops what the call
+// had still to enqueue from going out behind it.
+static thread_local bool g_launch_refused = false;
+
+template <typename... KArgs, typename... Args>
+static inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream, Args&&... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+  if (g_launch_refused) return;
+  std::tuple<std::decay_t<KArgs>...> held(static_cast<std::decay_t<KArgs>>(args)...);
+  const hipError_t e = std::apply(
+      [&](auto&... a) {
+        void* ptrs[] = {static_cast<void*>(&a)...};
+        return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
+      },
+      held);
+  if (e != hipSuccess) g_launch_refused = true;
+}
+
+static int launch_status() {
+  const bool refused = g_launch_refused;
+  g_launch_refused = false;
+  return refused ? MLPROJ_ERR_LAUNCH : MLPROJ_OK;
+}
 
 // Optional per-kernel timing: while a trace is open on the calling thread, an event is
 // recorded on the stream before every kernel of a call and after its last one.
@@ -109,7 +138,9 @@ static inline void mark(hipStream_t stream) {
 
 // Polls a lane of the grid-wide search may spend waiting for another workgroup's post before the
 // search gives up and the one-workgroup kernel behind it takes over (0: give up at once).
-static unsigned g_spin_limit = SPIN_LIMIT;
+// (a test hook, see mlproj_set_search_spin_limit; atomic, so a thread that enqueues while another
+// sets it reads one value or the other)
+static std::atomic<unsigned> g_spin_limit{SPIN_LIMIT};
 
 // The stand-alone search: up to 16384 groups one workgroup running the search of the map
 // kernels' prologue (so a split call returns the whole call's bits), one workgroup of 1024
@@ -118,12 +149,12 @@ static unsigned g_spin_limit = SPIN_LIMIT;
 static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, int outer,
                           double* norm_out, hipStream_t stream) {
   if (ngroups <= FUSED_SEARCH_MAX) {
-    hipLaunchKernelGGL((search_kernel<WG, SEARCH_CACHE>), dim3(1), dim3(WG), 0, stream, ws, ngroups, eta, mode, outer,
+    launch((search_kernel<WG, SEARCH_CACHE>), dim3(1), dim3(WG), stream, ws, ngroups, eta, mode, outer,
                        norm_out, 0, (double*)nullptr, (float*)nullptr);
     return;
   }
   if (ngroups <= FUSED_SEARCH_MAX_BIG) {
-    hipLaunchKernelGGL((search_kernel<WG, SEARCH_CACHE_BIG>), dim3(1), dim3(WG), 0, stream, ws, ngroups, eta, mode, outer,
+    launch((search_kernel<WG, SEARCH_CACHE_BIG>), dim3(1), dim3(WG), stream, ws, ngroups, eta, mode, outer,
                        norm_out, 0, (double*)nullptr, (float*)nullptr);
     return;
   }
@@ -131,17 +162,17 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
   // (the l2 and l_inf outer projections need no iteration: one workgroup reads v once)
   const bool iterates = outer == MLPROJ_OUTER_L1 || mode == MODE_NORM;
   if (ngroups <= (long long)SWG * SEARCH_CACHE_ONE_WG && iterates) {
-    hipLaunchKernelGGL((search_kernel<SWG, SEARCH_CACHE_ONE_WG>), dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode,
+    launch((search_kernel<SWG, SEARCH_CACHE_ONE_WG>), dim3(1), dim3(SWG), stream, ws, ngroups, eta, mode,
                        outer, norm_out, 0, (double*)nullptr, (float*)nullptr);
     return;
   }
   if (iterates) {
     long long nwg = cdiv(ngroups, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-    hipLaunchKernelGGL((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, ngroups, eta, mode, norm_out, g_spin_limit);
+    launch((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), stream, ws, ngroups, eta, mode, norm_out, g_spin_limit.load(std::memory_order_relaxed));
     only_as_fallback = 1;
   }
-  hipLaunchKernelGGL((search_kernel<SWG, SEARCH_CACHE>), dim3(1), dim3(SWG), 0, stream, ws, ngroups, eta, mode, outer, norm_out,
+  launch((search_kernel<SWG, SEARCH_CACHE>), dim3(1), dim3(SWG), stream, ws, ngroups, eta, mode, outer, norm_out,
                      only_as_fallback, (double*)nullptr, (float*)nullptr);
 }
 
@@ -154,16 +185,16 @@ static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStr
   if (m > 32768) {
     long long nwg = cdiv(m, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-    hipLaunchKernelGGL((search_wide_kernel<true, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), 0, stream, ws, m,
-                       eta, (int)MODE_PROJECT, (double*)nullptr, g_spin_limit);
+    launch((search_wide_kernel<true, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), stream, ws, m,
+                       eta, (int)MODE_PROJECT, (double*)nullptr, g_spin_limit.load(std::memory_order_relaxed));
     only_as_fallback = 1;
   }
   if (m <= 4096)
-    hipLaunchKernelGGL((search_weighted_kernel<256, 16>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback, radii, u_out);
+    launch((search_weighted_kernel<256, 16>), dim3(1), dim3(256), stream, ws, m, eta, only_as_fallback, radii, u_out);
   else if (m <= 16384)
-    hipLaunchKernelGGL((search_weighted_kernel<256, 64>), dim3(1), dim3(256), 0, stream, ws, m, eta, only_as_fallback, radii, u_out);
+    launch((search_weighted_kernel<256, 64>), dim3(1), dim3(256), stream, ws, m, eta, only_as_fallback, radii, u_out);
   else
-    hipLaunchKernelGGL((search_weighted_kernel<SWG, 16>), dim3(1), dim3(SWG), 0, stream, ws, m, eta, only_as_fallback, radii, u_out);
+    launch((search_weighted_kernel<SWG, 16>), dim3(1), dim3(SWG), stream, ws, m, eta, only_as_fallback, radii, u_out);
 }
 
 // l1,1: how many lock-step sweeps to enqueue before the finishing pass, and the number of
@@ -174,12 +205,13 @@ static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStr
 // heavy tails take up to ten.  So short matrices get few sweeps (finishing is cheap; up to
 // 1024 rows it holds the columns in registers and needs no sweep at all), tall ones more, and where a sweep is dearer than finishing a few hundred stragglers the sweeps
 // stop as soon as no more than that are open.
-static int g_l11_sweeps = 0;  // 0 = automatic
+static std::atomic<int> g_l11_sweeps{0};  // 0 = automatic (a tuning and test hook, see mlproj_set_l11_sweeps)
 static void plan_l11(long long n, long long m, int elem_bytes, int* sweeps, unsigned* handoff) {
   const double sweep_us = (double)n * (double)m * elem_bytes / 4e6 + 6.0;
   const double finish_us = 4.0 * (double)n / 512.0;
   *handoff = sweep_us > finish_us ? 512u : 0u;
-  if (g_l11_sweeps > 0) { *sweeps = g_l11_sweeps; return; }
+  const int forced = g_l11_sweeps.load(std::memory_order_relaxed);
+  if (forced > 0) { *sweeps = forced; return; }
   // (up to 4096 rows and 4M elements the finishing pass alone is also faster than the six or more
   // launches of the sweeps: 42 against 54 us at 2048 x 2048, 50 against 58 at 4096 x 1024; at
   // 1536 x 4096 the two are level, beyond that the sweeps win: 92 against 121 us at 4096 x 4096)
@@ -241,7 +273,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     const bool apart = X && (X + n * m <= Y || Y + n * m <= X);
     if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && !weights && tiny_plan(n, m, WIDE, &tp)) {
       mark(stream);
-      hipLaunchKernelGGL((tiny_kernel<Q, T, WIDE>), dim3(apart ? (unsigned)tp.slots : 1u), dim3(TINY_WG), 0, stream, Y, X, n, m,
+      launch((tiny_kernel<Q, T, WIDE>), dim3(apart ? (unsigned)tp.slots : 1u), dim3(TINY_WG), stream, Y, X, n, m,
                          (double)eta, outer, tp.cw, ws, v_out, u_out, mask_out, apart ? 0 : 1);
       mark(stream);
       return launch_status();
@@ -249,15 +281,24 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   }
   if (stages & STAGE_AGGREGATE) {
     mark(stream);
-    if (wide)
-      hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws.partial);
-    else
-      hipLaunchKernelGGL((colagg_kernel<Q, T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws.partial);
-    mark(stream);
-    if (rthreads == 256)
-      hipLaunchKernelGGL((reduce_kernel<Q, 256>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
-    else
-      hipLaunchKernelGGL((reduce_kernel<Q>), rgrid, rblock, 0, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+    if (g.groups == 1) {
+      // one row group per tile: the aggregate pass writes v itself, there is nothing to fold
+      if (wide)
+        launch((colagg_direct_kernel<Q, T, WIDE, false>), grid, block, stream, Y, n, m, g, ws.v, v_out, ws.flags);
+      else
+        launch((colagg_direct_kernel<Q, T, WIDE, true>), grid, block, stream, Y, n, m, g, ws.v, v_out, ws.flags);
+      mark(stream);   // (the same number of intervals as the longer chain: the fold's is empty)
+    } else {
+      if (wide)
+        launch((colagg_kernel<Q, T, WIDE, false>), grid, block, stream, Y, n, m, g, ws.partial);
+      else
+        launch((colagg_kernel<Q, T, WIDE, true>), grid, block, stream, Y, n, m, g, ws.partial);
+      mark(stream);
+      if (rthreads == 256)
+        launch((reduce_kernel<Q, 256>), rgrid, rblock, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+      else
+        launch((reduce_kernel<Q>), rgrid, rblock, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+    }
     // (l1,1: the kernel that seeds the inner searches runs the outer search the same way)
     const bool fuse_l11 = Q == Q1 && mode == MODE_PROJECT && m <= FUSED_SEARCH_MAX_BIG && !weights;
     if (weights) {
@@ -278,48 +319,48 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
         // a short matrix of few columns: the finishing pass seeds itself and runs the outer
         // search too (with more columns the search repeated in every workgroup costs more than
         // the seeding kernel it saves: 61 against 56 us at 1000 x 10000)
-        hipLaunchKernelGGL((l11_finish_seeded_kernel<T, FIN_SEARCH_CACHE>), fgrid, fblock, 0, stream, Y, n, m, ws, (double)eta, outer);
+        launch((l11_finish_seeded_kernel<T, FIN_SEARCH_CACHE>), fgrid, fblock, stream, Y, n, m, ws, (double)eta, outer);
         mark(stream);   // (the same number of intervals as the longer chain: this one is empty)
       } else {
         const dim3 igrid((unsigned)cdiv(m, WG));
         if (!fuse_l11)
-          hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, -1.0, outer);
+          launch((l11_init_kernel<SEARCH_CACHE>), igrid, block, stream, n, m, ws, -1.0, outer);
         else if (m > FUSED_SEARCH_MAX)
-          hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE_BIG>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
+          launch((l11_init_kernel<SEARCH_CACHE_BIG>), igrid, block, stream, n, m, ws, (double)eta, outer);
         else
-          hipLaunchKernelGGL((l11_init_kernel<SEARCH_CACHE>), igrid, block, 0, stream, n, m, ws, (double)eta, outer);
+          launch((l11_init_kernel<SEARCH_CACHE>), igrid, block, stream, n, m, ws, (double)eta, outer);
         if (fuse_l11) mark(stream);   // (keeps one interval for search + seeding, one for the sweeps)
         for (int s = 0; s < sweeps; ++s) {
           if (s == 0) {
-            if (wide) hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws);
-            else hipLaunchKernelGGL((l11_sweep_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws);
+            if (wide) launch((l11_sweep_kernel<T, WIDE, false>), grid, block, stream, Y, n, m, g, ws);
+            else launch((l11_sweep_kernel<T, WIDE, true>), grid, block, stream, Y, n, m, g, ws);
           } else {
-            if (wide) hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, false>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
-            else hipLaunchKernelGGL((l11_filter_kernel<T, WIDE, true>), grid, block, 0, stream, Y, n, m, g, ws, s, handoff);
+            if (wide) launch((l11_filter_kernel<T, WIDE, false>), grid, block, stream, Y, n, m, g, ws, s, handoff);
+            else launch((l11_filter_kernel<T, WIDE, true>), grid, block, stream, Y, n, m, g, ws, s, handoff);
           }
-          hipLaunchKernelGGL(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, 0, stream, n, m, g, ws, s, handoff);
+          launch(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, stream, n, m, g, ws, s, handoff);
         }
         if (finish_held(n))
-          hipLaunchKernelGGL((l11_finish_kernel<T, true>), fgrid, fblock, 0, stream, Y, n, m, ws, sweeps, handoff);
+          launch((l11_finish_kernel<T, true>), fgrid, fblock, stream, Y, n, m, ws, sweeps, handoff);
         else
-          hipLaunchKernelGGL((l11_finish_kernel<T, false>), fgrid, fblock, 0, stream, Y, n, m, ws, sweeps, handoff);
+          launch((l11_finish_kernel<T, false>), fgrid, fblock, stream, Y, n, m, ws, sweeps, handoff);
       }
     }
   }
   if (stages & STAGE_APPLY) {
     mark(stream);
     if (fuse_big && wide && x_vec)
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, true, SEARCH_CACHE_BIG>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+      launch((colmap_kernel<Q, T, WIDE, false, true, SEARCH_CACHE_BIG>), mgrid, block, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else if (fuse_big && wide)
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, false, SEARCH_CACHE_BIG>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+      launch((colmap_kernel<Q, T, WIDE, false, false, SEARCH_CACHE_BIG>), mgrid, block, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else if (fuse_big)
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, true, false, SEARCH_CACHE_BIG>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+      launch((colmap_kernel<Q, T, WIDE, true, false, SEARCH_CACHE_BIG>), mgrid, block, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else if (wide && x_vec)
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, true>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+      launch((colmap_kernel<Q, T, WIDE, false, true>), mgrid, block, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else if (wide)
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, false, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+      launch((colmap_kernel<Q, T, WIDE, false, false>), mgrid, block, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
     else
-      hipLaunchKernelGGL((colmap_kernel<Q, T, WIDE, true, false>), mgrid, block, 0, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
+      launch((colmap_kernel<Q, T, WIDE, true, false>), mgrid, block, stream, Y, X, n, m, g, ws, u_out, mask_out, fused_eta, outer);
   }
   mark(stream);
   return launch_status();
@@ -371,10 +412,10 @@ static int run_trilevel(const T* Y, T* X, long long d0, long long d1, long long 
   const dim3 rgrid((unsigned)cdiv(d0, SWG / parts)), rblock(SWG);
   float* partial = static_cast<float*>(ws.partial);
   mark(stream);
-  if (vec == WIDE) hipLaunchKernelGGL((slabagg_kernel<T, WIDE>), grid, block, 0, stream, Y, len, g, partial);
-  else hipLaunchKernelGGL((slabagg_kernel<T, 1>), grid, block, 0, stream, Y, len, g, partial);
+  if (vec == WIDE) launch((slabagg_kernel<T, WIDE>), grid, block, stream, Y, len, g, partial);
+  else launch((slabagg_kernel<T, 1>), grid, block, stream, Y, len, g, partial);
   mark(stream);
-  hipLaunchKernelGGL((reduce_kernel<QINF>), rgrid, rblock, 0, stream, ws.partial, d0, g, parts, ws.v, v_out, ws.flags);
+  launch((reduce_kernel<QINF>), rgrid, rblock, stream, ws.partial, d0, g, parts, ws.v, v_out, ws.flags);
   const bool fuse = d0 <= FUSED_SEARCH_MAX;
   const double fused_eta = fuse ? (double)eta : -1.0;
   if (!fuse) {
@@ -383,11 +424,11 @@ static int run_trilevel(const T* Y, T* X, long long d0, long long d1, long long 
   }
   mark(stream);
   if (vec == WIDE && x_vec)
-    hipLaunchKernelGGL((slabmap_kernel<T, WIDE, true>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
+    launch((slabmap_kernel<T, WIDE, true>), grid, block, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
   else if (vec == WIDE)
-    hipLaunchKernelGGL((slabmap_kernel<T, WIDE, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
+    launch((slabmap_kernel<T, WIDE, false>), grid, block, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
   else
-    hipLaunchKernelGGL((slabmap_kernel<T, 1, false>), grid, block, 0, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
+    launch((slabmap_kernel<T, 1, false>), grid, block, stream, Y, X, d0, len, g, ws, u_out, mask_out, fused_eta);
   mark(stream);
   return launch_status();
 }
@@ -446,7 +487,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
       if (it.count == 0) break;
       tg.first[it.count] = wgs;
       mark(stream);
-      hipLaunchKernelGGL((tiny_batch_kernel<Q, T>), dim3(wgs), dim3(TINY_WG), 0, stream, it, tg, outer);
+      launch((tiny_batch_kernel<Q, T>), dim3(wgs), dim3(TINY_WG), stream, it, tg, outer);
       mark(stream);
     }
   }
@@ -484,25 +525,25 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
     agg.first[it.count] = a; red.first[it.count] = r; map.first[it.count] = mp;
     ini.first[it.count] = in; upd.first[it.count] = up;
     mark(stream);
-    hipLaunchKernelGGL((colagg_batch_kernel<Q, T>), dim3(a), dim3(WG), 0, stream, it, agg);
+    launch((colagg_batch_kernel<Q, T>), dim3(a), dim3(WG), stream, it, agg);
     mark(stream);
-    hipLaunchKernelGGL((reduce_batch_kernel<Q, T>), dim3(r), dim3(SWG), 0, stream, it, red);
+    launch((reduce_batch_kernel<Q, T>), dim3(r), dim3(SWG), stream, it, red);
     if constexpr (Q == Q1) {
       // the inner searches: every kernel of the single-matrix chain once for the whole batch
       mark(stream);
-      if (big) hipLaunchKernelGGL((l11_init_batch_kernel<T, SEARCH_CACHE_BIG>), dim3(in), dim3(WG), 0, stream, it, ini, outer);
-      else hipLaunchKernelGGL((l11_init_batch_kernel<T, SEARCH_CACHE>), dim3(in), dim3(WG), 0, stream, it, ini, outer);
+      if (big) launch((l11_init_batch_kernel<T, SEARCH_CACHE_BIG>), dim3(in), dim3(WG), stream, it, ini, outer);
+      else launch((l11_init_batch_kernel<T, SEARCH_CACHE>), dim3(in), dim3(WG), stream, it, ini, outer);
       mark(stream);
       for (int s = 0; s < max_sweeps; ++s) {
-        if (s == 0) hipLaunchKernelGGL((l11_sweep_batch_kernel<T>), dim3(a), dim3(WG), 0, stream, it, agg, plan);
-        else hipLaunchKernelGGL((l11_filter_batch_kernel<T>), dim3(a), dim3(WG), 0, stream, it, agg, plan, s);
-        hipLaunchKernelGGL((l11_update_batch_kernel<T>), dim3(up), dim3(WG), 0, stream, it, upd, plan, s);
+        if (s == 0) launch((l11_sweep_batch_kernel<T>), dim3(a), dim3(WG), stream, it, agg, plan);
+        else launch((l11_filter_batch_kernel<T>), dim3(a), dim3(WG), stream, it, agg, plan, s);
+        launch((l11_update_batch_kernel<T>), dim3(up), dim3(WG), stream, it, upd, plan, s);
       }
-      hipLaunchKernelGGL((l11_finish_batch_kernel<T>), dim3(up), dim3(FIN_WG), 0, stream, it, upd, plan);
+      launch((l11_finish_batch_kernel<T>), dim3(up), dim3(FIN_WG), stream, it, upd, plan);
     }
     mark(stream);
-    if (big) hipLaunchKernelGGL((colmap_batch_kernel<Q, T, SEARCH_CACHE_BIG>), dim3(mp), dim3(WG), 0, stream, it, map, outer);
-    else hipLaunchKernelGGL((colmap_batch_kernel<Q, T, SEARCH_CACHE>), dim3(mp), dim3(WG), 0, stream, it, map, outer);
+    if (big) launch((colmap_batch_kernel<Q, T, SEARCH_CACHE_BIG>), dim3(mp), dim3(WG), stream, it, map, outer);
+    else launch((colmap_batch_kernel<Q, T, SEARCH_CACHE>), dim3(mp), dim3(WG), stream, it, map, outer);
     mark(stream);
   }
   int st = launch_status();
@@ -593,15 +634,15 @@ static void launch_fibre_agg(const TIN* A, long long nf, long long len, double* 
     long long wgs = cdiv(nf, per_wg);
     if (wgs > ML_AGG_SHORT_WGS) wgs = ML_AGG_SHORT_WGS;
     const dim3 grid((unsigned)wgs), block(WG);
-    if (seg == 4) hipLaunchKernelGGL((fibre_agg_short_kernel<Q, TIN, 4, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
-    else if (seg == 16) hipLaunchKernelGGL((fibre_agg_short_kernel<Q, TIN, 16, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
-    else hipLaunchKernelGGL((fibre_agg_short_kernel<Q, TIN, 64, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+    if (seg == 4) launch((fibre_agg_short_kernel<Q, TIN, 4, VEC>), grid, block, stream, A, nf, len, V, v_out);
+    else if (seg == 16) launch((fibre_agg_short_kernel<Q, TIN, 16, VEC>), grid, block, stream, A, nf, len, V, v_out);
+    else launch((fibre_agg_short_kernel<Q, TIN, 64, VEC>), grid, block, stream, A, nf, len, V, v_out);
     return;
   }
   const dim3 grid(fibre_grid(nf, seg, FIB_UNROLL)), block(WG);
-  if (seg == 4) hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 4, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
-  else if (seg == 16) hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 16, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
-  else hipLaunchKernelGGL((fibre_agg_kernel<Q, TIN, 64, VEC>), grid, block, 0, stream, A, nf, len, V, v_out);
+  if (seg == 4) launch((fibre_agg_kernel<Q, TIN, 4, VEC>), grid, block, stream, A, nf, len, V, v_out);
+  else if (seg == 16) launch((fibre_agg_kernel<Q, TIN, 16, VEC>), grid, block, stream, A, nf, len, V, v_out);
+  else launch((fibre_agg_kernel<Q, TIN, 64, VEC>), grid, block, stream, A, nf, len, V, v_out);
 }
 
 template <int Q, typename TIN, typename TOUT, int VEC, bool TOP = false>
@@ -615,7 +656,7 @@ static void launch_fibre_map(const TIN* A, long long nf, long long len, const do
     const dim3 cgrid(fibre_grid(nf, seg, FIB_MAP_UNROLL)), cblock(WG);
     const int kreg = nvec <= seg ? 1 : (nvec <= 2LL * seg ? 2 : 4);
 #define MLPROJ_LAUNCH_CACHED(SEG_, K_)                                                              \
-  hipLaunchKernelGGL((fibre_map_cached_kernel<Q, TIN, TOUT, SEG_, VEC, K_, TOP>), cgrid, cblock, 0, stream, \
+  launch((fibre_map_cached_kernel<Q, TIN, TOUT, SEG_, VEC, K_, TOP>), cgrid, cblock, stream, \
                      A, nf, len, R, Vn, out, tf)
     if (seg == 4) { if (kreg == 1) MLPROJ_LAUNCH_CACHED(4, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(4, 2); else MLPROJ_LAUNCH_CACHED(4, 4); }
     else if (seg == 16) { if (kreg == 1) MLPROJ_LAUNCH_CACHED(16, 1); else if (kreg == 2) MLPROJ_LAUNCH_CACHED(16, 2); else MLPROJ_LAUNCH_CACHED(16, 4); }
@@ -624,9 +665,9 @@ static void launch_fibre_map(const TIN* A, long long nf, long long len, const do
     return;
   }
   const dim3 grid(fibre_grid(nf, seg, 1)), block(WG);
-  if (seg == 4) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 4, VEC, TOP>), grid, block, 0, stream, A, nf, len, R, Vn, out, tf);
-  else if (seg == 16) hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 16, VEC, TOP>), grid, block, 0, stream, A, nf, len, R, Vn, out, tf);
-  else hipLaunchKernelGGL((fibre_map_kernel<Q, TIN, TOUT, 64, VEC, TOP>), grid, block, 0, stream, A, nf, len, R, Vn, out, tf);
+  if (seg == 4) launch((fibre_map_kernel<Q, TIN, TOUT, 4, VEC, TOP>), grid, block, stream, A, nf, len, R, Vn, out, tf);
+  else if (seg == 16) launch((fibre_map_kernel<Q, TIN, TOUT, 16, VEC, TOP>), grid, block, stream, A, nf, len, R, Vn, out, tf);
+  else launch((fibre_map_kernel<Q, TIN, TOUT, 64, VEC, TOP>), grid, block, stream, A, nf, len, R, Vn, out, tf);
 }
 
 template <typename F>
@@ -733,17 +774,17 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
     // (one workgroup: it writes the radii too, and nothing has to be cleared for it)
     launch_weighted_search(ws, dims[0], (double)eta, stream, R[ndim - 1], u_out);
   } else if (weights) {
-    hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WG), 0, stream, ws);
+    launch(clear_flags_kernel, dim3(1), dim3(WG), stream, ws);
     launch_weighted_search(ws, dims[0], (double)eta, stream);
-    hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
+    launch(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), stream, ws,
                        dims[0], R[ndim - 1], u_out);
   } else if (dims[0] <= (long long)SWG * SEARCH_CACHE || outer != MLPROJ_OUTER_L1) {
-    hipLaunchKernelGGL((search_kernel<SWG, SEARCH_CACHE>), dim3(1), dim3(SWG), 0, stream, ws, dims[0], (double)eta, MODE_PROJECT,
+    launch((search_kernel<SWG, SEARCH_CACHE>), dim3(1), dim3(SWG), stream, ws, dims[0], (double)eta, MODE_PROJECT,
                        outer, (double*)nullptr, 0, R[ndim - 1], u_out);
   } else {
-    hipLaunchKernelGGL(clear_flags_kernel, dim3(1), dim3(WG), 0, stream, ws);
+    launch(clear_flags_kernel, dim3(1), dim3(WG), stream, ws);
     launch_search(ws, dims[0], (double)eta, MODE_PROJECT, outer, nullptr, stream);
-    hipLaunchKernelGGL(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), 0, stream, ws,
+    launch(top_radii_kernel, dim3((unsigned)cdiv(dims[0], WG)), dim3(WG), stream, ws,
                        dims[0], R[ndim - 1], u_out);
   }
   // down: project the fibres of every level onto the balls of the level above
@@ -808,16 +849,12 @@ int mlproj_trace_end(void) {
 
 int mlproj_set_l11_sweeps(int sweeps) {
   if (sweeps < 0 || sweeps > MAX_INNER_SWEEPS) return MLPROJ_ERR_BAD_DIMENSION;
-  const int before = g_l11_sweeps;
-  g_l11_sweeps = sweeps;
-  return before;
+  return g_l11_sweeps.exchange(sweeps, std::memory_order_relaxed);
 }
 
 int mlproj_set_search_spin_limit(int polls) {
-  if (polls < 0 || polls > (int)SPIN_LIMIT) return MLPROJ_ERR_BAD_DIMENSION;
-  const int before = (int)g_spin_limit;
-  g_spin_limit = (unsigned)polls;
-  return before;
+  if (polls < 0 || polls > (int)SPIN_LIMIT_MAX) return MLPROJ_ERR_BAD_DIMENSION;
+  return (int)g_spin_limit.exchange((unsigned)polls, std::memory_order_relaxed);
 }
 
 int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2, size_t* bytes_out) {

@@ -175,7 +175,7 @@ def test_weighted_entry_point_argument_checks(lib):
 
 def test_search_spin_limit_knob(lib):
     default = lib.mlproj_set_search_spin_limit(0)
-    assert default == 1 << 22
+    assert default == 256      # a fraction of a millisecond of polling, not seconds
     assert lib.mlproj_set_search_spin_limit(64) == 0
     assert lib.mlproj_set_search_spin_limit(-1) == -2 and lib.mlproj_set_search_spin_limit((1 << 22) + 1) == -2
     assert lib.mlproj_set_search_spin_limit(default) == 64
