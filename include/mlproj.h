@@ -53,7 +53,8 @@ typedef enum mlproj_status {
   MLPROJ_ERR_WORKSPACE = -5,      /* workspace too small or misaligned                */
   MLPROJ_ERR_BAD_VARIANT = -6,    /* unknown variant / norm selector                  */
   MLPROJ_ERR_ALIGNMENT = -7,      /* Y or X not aligned to the element size            */
-  MLPROJ_ERR_LAUNCH = -8          /* the HIP runtime refused a kernel launch of this call  */
+  MLPROJ_ERR_LAUNCH = -8,         /* the HIP runtime refused a kernel launch of this call  */
+  MLPROJ_ERR_NO_ALLOC_LIMIT = -9  /* bilevel_proj_l1inf_no_alloc: the input needs more scratch than the built-in buffer */
 } mlproj_status;
 
 /* Which projection a workspace is sized for. */
@@ -171,6 +172,29 @@ int bilevel_proj_l1inf(const float* Y /* device, n*m */, float* X /* device, n*m
                        void* workspace /* device */, size_t workspace_bytes,
                        float* v_out /* device, m; may be NULL */,
                        float* u_out /* device, m; may be NULL */, void* stream);
+
+/* bilevel_proj_l1inf for callers that cannot allocate device memory and so cannot bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The same kernels and the same results as bilevel_proj_l1inf, bit for bit, with the workspace
+ * taken from a fixed buffer of MLPROJ_NO_ALLOC_SCRATCH_BYTES inside the library's device image
+ * (each GPU the library is used on holds that buffer until the process ends).  The call itself
+ * allocates and frees nothing, on the host or on the device; the first call on a device looks
+ * the buffer's address up once.
+ *  - Limit: inputs whose workspace (mlproj_workspace_bytes(MLPROJ_L1INF, n, m, 1): about
+ *    16 bytes per column plus at most 1 MiB) exceeds the buffer are refused with
+ *    MLPROJ_ERR_NO_ALLOC_LIMIT before anything is enqueued.  Every matrix of up to 262144
+ *    columns fits, whatever its number of rows.
+ *  - The device that `stream` belongs to must be the current device of the calling thread.
+ *  - All calls on one GPU share the one buffer: calls that may overlap on the GPU (different
+ *    streams, or graphs replayed side by side) race on it.  Order them, or use
+ *    bilevel_proj_l1inf with a workspace each.  Nothing in the buffer has to be cleared between
+ *    calls; the result record of the last call is not exposed.
+ *  - Y, X, v_out, u_out, eta and the other error codes: as bilevel_proj_l1inf.               */
+#define MLPROJ_NO_ALLOC_SCRATCH_BYTES (6u << 20)
+int bilevel_proj_l1inf_no_alloc(const float* Y /* device, n*m */, float* X /* device, n*m */,
+                                long long n, long long m, float eta,
+                                float* v_out /* device, m; may be NULL */,
+                                float* u_out /* device, m; may be NULL */, void* stream);
 
 /* BP^{1,1}_eta (Sec. 4.3.1, Eq. 14, Alg. 3): v_j = sum_i |Y_ij|, u = P^1_eta(v),
  * x_j = P^1_{u_j}(y_j), i.e. X_ij = sign(Y_ij) * max(|Y_ij| - tau_j, 0) with the

@@ -80,6 +80,8 @@ def lib():
         fn = getattr(L, name)
         fn.restype = c_i
         fn.argtypes = [c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp, c_vp]
+    L.bilevel_proj_l1inf_no_alloc.restype = c_i
+    L.bilevel_proj_l1inf_no_alloc.argtypes = [c_vp, c_vp, c_ll, c_ll, c_f, c_vp, c_vp, c_vp]
     L.bilevel_radii.restype = c_i
     L.bilevel_radii.argtypes = [c_i, c_vp, c_ll, c_ll, c_f, c_vp, c_sz, c_vp, c_vp]
     L.bilevel_apply.restype = c_i
@@ -128,6 +130,7 @@ EXPORTS = (
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
     "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored", "mlproj_set_l11_sweeps",
     "multilevel_proj_stored", "bilevel_proj_weighted", "multilevel_proj_weighted", "mlproj_set_search_spin_limit",
+    "bilevel_proj_l1inf_no_alloc",
 )
 
 
@@ -215,6 +218,18 @@ def _bilevel(name, variant, Y, eta, X, workspace, v_out, u_out, stream):
 
 def bilevel_proj_l1inf(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):
     return _bilevel("bilevel_proj_l1inf", L1INF, Y, eta, X, workspace, v_out, u_out, stream)
+
+
+def bilevel_proj_l1inf_no_alloc(Y, eta, X, v_out=None, u_out=None, stream=None):
+    """bilevel_proj_l1inf on the library's built-in scratch buffer: the call allocates nothing,
+    so X is the caller's (and there is no workspace to pass)."""
+    assert Y.dim() == 2 and X is not None
+    n, m = Y.shape
+    assert _prep(Y, X) is X
+    st = lib().bilevel_proj_l1inf_no_alloc(_ptr(Y), _ptr(X), n, m, ctypes.c_float(eta), _ptr(v_out), _ptr(u_out),
+                                           _stream(stream))
+    _check(st, "bilevel_proj_l1inf_no_alloc")
+    return X
 
 
 def bilevel_proj_l11(Y, eta, X=None, workspace=None, v_out=None, u_out=None, stream=None):

@@ -24,6 +24,7 @@
 // This file is the one translation unit: the kernels live in the headers it includes (one per
 // pass), the host code below checks arguments, plans the launch geometry and enqueues.
 #include <atomic>
+#include <mutex>
 #include <tuple>
 #include <utility>
 
@@ -808,6 +809,32 @@ static int run_multilevel(int outer, const T* Y, T* X, int ndim, const long long
   return launch_status();
 }
 
+// ------------------------------------------------------------------ host: the built-in scratch
+// For callers that cannot allocate (see bilevel_proj_l1inf_no_alloc): the workspace of such a
+// call is this array in the library's own device image.  Every GPU the library runs on holds a
+// copy of it, at its own address, until the process ends.  In host code the array's name is only
+// a handle for hipGetSymbolAddress: the address a kernel can use is asked for once per device,
+// with that device current, and kept; from then on only that pointer is used.
+constexpr size_t NO_ALLOC_SCRATCH_BYTES = (size_t)MLPROJ_NO_ALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[NO_ALLOC_SCRATCH_BYTES];
+
+constexpr int NO_ALLOC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[NO_ALLOC_MAX_DEVICES];   // per device: where its copy of `scratch` lives
+
+static int scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NO_ALLOC_MAX_DEVICES) return MLPROJ_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MLPROJ_ERR_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MLPROJ_OK;
+}
+
 }  // namespace mlproj
 
 // ------------------------------------------------------------------ C ABI
@@ -828,6 +855,7 @@ const char* mlproj_status_string(int status) {
     case MLPROJ_ERR_BAD_VARIANT: return "unknown variant";
     case MLPROJ_ERR_ALIGNMENT: return "Y and X must be aligned to their element size";
     case MLPROJ_ERR_LAUNCH: return "HIP refused a kernel launch";
+    case MLPROJ_ERR_NO_ALLOC_LIMIT: return "input needs more scratch memory than the built-in buffer of the no-allocation entry point holds";
     default: return "unknown status";
   }
 }
@@ -871,6 +899,22 @@ int bilevel_proj_l1inf(const float* Y, float* X, long long n, long long m, float
                        void* workspace, size_t workspace_bytes, float* v_out, float* u_out,
                        void* stream) {
   return run_bilevel<QINF>(Y, X, n, m, eta, workspace, workspace_bytes, v_out, u_out, stream,
+                           MODE_PROJECT, nullptr, STAGE_ALL, (int)MLPROJ_OUTER_L1);
+}
+
+int bilevel_proj_l1inf_no_alloc(const float* Y, float* X, long long n, long long m, float eta,
+                                float* v_out, float* u_out, void* stream) {
+  // every check that needs no GPU first, so that a refused call has touched nothing
+  if (!Y || !X) return MLPROJ_ERR_NULL_POINTER;
+  size_t need = 0;
+  int st = workspace_bytes_impl(MLPROJ_L1INF, n, m, 1, &need);
+  if (st != MLPROJ_OK) return st;
+  if ((st = check_radius(eta)) != MLPROJ_OK) return st;
+  if (need > NO_ALLOC_SCRATCH_BYTES) return MLPROJ_ERR_NO_ALLOC_LIMIT;
+  void* ws = nullptr;
+  if ((st = scratch_of_current_device(&ws)) != MLPROJ_OK) return st;
+  // (the chain initialises what it needs in the workspace itself: nothing to clear between calls)
+  return run_bilevel<QINF>(Y, X, n, m, eta, ws, NO_ALLOC_SCRATCH_BYTES, v_out, u_out, stream,
                            MODE_PROJECT, nullptr, STAGE_ALL, (int)MLPROJ_OUTER_L1);
 }
 

@@ -35,8 +35,8 @@ def test_every_declared_function_is_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert lib.mlproj_version() >= 200
-    seen = {lib.mlproj_status_string(s) for s in range(0, -9, -1)}
-    assert len(seen) == 9 and b"unknown status" not in seen
+    seen = {lib.mlproj_status_string(s) for s in range(0, -10, -1)}
+    assert len(seen) == 10 and b"unknown status" not in seen
     assert lib.mlproj_status_string(-99) == b"unknown status"
 
 
@@ -171,6 +171,27 @@ def test_weighted_entry_point_argument_checks(lib):
         assert wt(storage, 0, FAKE, FAKE, 0, 4, F(1), FAKE, FAKE, big, None, None, None, None) == -2
         assert wt(storage, 1, FAKE, FAKE, 4, 4, F(float("nan")), FAKE, FAKE, big, None, None, None, None) == -4
         assert wt(storage, 2, FAKE, FAKE, 4, 4, F(1), FAKE, FAKE, 64, None, None, None, None) == -5
+
+
+def test_no_alloc_entry_point_checks_before_touching_the_gpu(lib):
+    """Everything that can be refused is refused on the host, the size limit of the built-in
+    scratch buffer included (this container has no GPU: a call that got past the checks would
+    come back with the launch status instead)."""
+    na = lib.bilevel_proj_l1inf_no_alloc
+    assert na(None, FAKE, 4, 4, F(1), None, None, None) == -1
+    assert na(FAKE, None, 4, 4, F(1), None, None, None) == -1
+    assert na(FAKE, FAKE, 0, 4, F(1), None, None, None) == -2
+    assert na(FAKE, FAKE, 4, -1, F(1), None, None, None) == -2
+    assert na(FAKE, FAKE, 1 << 41, 4, F(1), None, None, None) == -3
+    assert na(FAKE, FAKE, 4, 4, F(-1), None, None, None) == -4
+    assert na(FAKE, FAKE, 4, 4, F(float("nan")), None, None, None) == -4
+    # the limit: the workspace of the call must fit the 6 MiB buffer
+    limit = 6 << 20
+    assert binding.workspace_bytes("l1inf", 100000, 262144) <= limit
+    assert binding.workspace_bytes("l1inf", 16384, 16384) <= limit
+    assert binding.workspace_bytes("l1inf", 4, 1 << 20) > limit
+    assert na(FAKE, FAKE, 4, 1 << 20, F(1), None, None, None) == -9
+    assert b"scratch" in lib.mlproj_status_string(-9)
 
 
 def test_search_spin_limit_knob(lib):
