@@ -83,11 +83,12 @@ struct Ws {
   unsigned* partial_cnt;   // [tiles][groups][tile_w] l1,1: entries above t
   unsigned* partial_cnt2;  // [tiles][groups][tile_w] l1,1: entries above t*(1 + L11_WINDOW)
   const float* wts;        // [groups] weights of a weighted l1 ball as outer norm; null: the plain norms
+  unsigned* posts;         // [HELD_POST_WORDS] one-pass tri-level kernel: what its workgroups post to one another
 };
 
 struct Layout {
   size_t off_pending, off_flags, off_coop_q, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, off_partial_cnt2, bytes;
-  size_t off_tlo, off_lb, off_ub, off_done, off_gcnt, off_gflag, off_cand;
+  size_t off_tlo, off_lb, off_ub, off_done, off_gcnt, off_gflag, off_cand, off_posts;
   int list_cap;
 };
 
@@ -149,6 +150,8 @@ __host__ __device__ static inline int reduce_parts(long long partials_per_group,
   return parts;
 }
 
+constexpr int HELD_POST_WORDS = 256;     // one-pass tri-level kernel: one posted word per workgroup
+
 constexpr int LIST_PER_THREAD = 16;      // l1,1: listed entries one lane of the update kernel holds in registers
 constexpr int LIST_LANES = 16;           // ... and the lanes that share a column there
 
@@ -179,6 +182,7 @@ __host__ __device__ static inline Layout layout_for(const Geometry& g, long long
   L.off_gcnt = o;          o = align_up(o + per_col4, 256);
   L.off_gflag = o;         o = align_up(o + per_col4, 256);
   L.off_cand = o;          o = align_up(o + per_col4 * (size_t)L.list_cap, 256);
+  L.off_posts = o;         o = align_up(o + (variant == MLPROJ_L1INFINF ? (size_t)HELD_POST_WORDS * 4 : 0), 256);
   L.bytes = o;
   return L;
 }
@@ -205,6 +209,7 @@ __host__ __device__ static inline Ws bind(void* workspace, const Layout& L) {
   w.gflag = reinterpret_cast<unsigned*>(b + L.off_gflag);
   w.cand = reinterpret_cast<float*>(b + L.off_cand);
   w.list_cap = L.list_cap;
+  w.posts = reinterpret_cast<unsigned*>(b + L.off_posts);
   return w;
 }
 

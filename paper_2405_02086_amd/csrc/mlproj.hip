@@ -37,6 +37,7 @@
 #include "slab.h"
 #include "fibre.h"
 #include "tiny.h"
+#include "held.h"
 #include "batch.h"
 
 namespace mlproj {
@@ -121,6 +122,14 @@ static int launch_status() {
   const bool refused = g_launch_refused;
   g_launch_refused = false;
   return refused ? MLPROJ_ERR_LAUNCH : MLPROJ_OK;
+}
+
+// Compute units of the current device (0 when there is none to ask).
+static int compute_units() {
+  int dev = -1, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return cus;
 }
 
 // Optional per-kernel timing: while a trace is open on the calling thread, an event is
@@ -408,6 +417,24 @@ static int run_trilevel(const T* Y, T* X, long long d0, long long d1, long long 
   if (workspace_bytes < L.bytes) return MLPROJ_ERR_WORKSPACE;
   const Ws ws = bind(workspace, L);
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  // A tensor that the register files hold (at most 256 KiB per CU, 16-byte aligned slabs, from
+  // 1 MiB on): one pass over memory, see held.h.  The plan needs the number of CUs.
+  if (vec == WIDE && d0 * len * (long long)sizeof(T) >= (1LL << 20)) {
+    HeldPlan hp;
+    if (held_plan_slabs(d0, len, (int)sizeof(T), compute_units(), &hp)) {
+      const unsigned limit = g_spin_limit.load(std::memory_order_relaxed);
+      const unsigned patience = limit < HELD_PATIENCE ? limit : HELD_PATIENCE;
+      mark(stream);
+      launch(held_clear_kernel, dim3(1), dim3(WG), stream, ws.posts);
+      mark(stream);
+      if (x_vec)
+        launch((held_slab_kernel<T, true>), dim3((unsigned)hp.nwg), dim3(HELD_WG), stream, Y, X, d0, len, hp, (double)eta, ws, ws.posts, v_out, u_out, mask_out, patience);
+      else
+        launch((held_slab_kernel<T, false>), dim3((unsigned)hp.nwg), dim3(HELD_WG), stream, Y, X, d0, len, hp, (double)eta, ws, ws.posts, v_out, u_out, mask_out, patience);
+      mark(stream);
+      return launch_status();
+    }
+  }
   const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
   const int parts = reduce_parts(g.groups);
   const dim3 rgrid((unsigned)cdiv(d0, SWG / parts)), rblock(SWG);
@@ -842,7 +869,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 353; }
+int mlproj_version(void) { return 360; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

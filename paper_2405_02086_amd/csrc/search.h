@@ -45,8 +45,10 @@ __device__ __forceinline__ Top top_of(const mlproj_result* r) { return Top{r->ta
 
 // NTHREADS > NT: a larger workgroup runs the search of an NT-thread one; the threads beyond
 // NT hold nothing and add zeros, so the result has the bits the NT-thread workgroup gets.
-template <int NT, int CACHE = SEARCH_CACHE, int NTHREADS = NT>
-__device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, long long ngroups,
+// VT: the type v is stored in where the search reads it (fp64 in the workspace; fp32 for exact
+// l_inf aggregates staged in LDS); every value is widened exactly before it is used.
+template <int NT, int CACHE = SEARCH_CACHE, int NTHREADS = NT, typename VT = double>
+__device__ __forceinline__ SearchOut search_block(const VT* __restrict__ v, long long ngroups,
                                                   double eta, int mode, int outer,
                                                   PairScratch<NTHREADS / WAVE>& s) {
   static_assert(NTHREADS >= NT && NTHREADS % WAVE == 0, "whole wavefronts, at least NT threads");
@@ -57,12 +59,12 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
 #pragma unroll
   for (int k = 0; k < CACHE; ++k) {
     const long long i = tid + (long long)k * NT;
-    vr[k] = i < ngroups ? v[i] : 0.0;  // 0 is never active: tau >= 0 and the test is strict
+    vr[k] = i < ngroups ? (double)v[i] : 0.0;  // 0 is never active: tau >= 0 and the test is strict
     a += vr[k];
     mx = fmax(mx, vr[k]);
   }
   for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
-    const double x = v[i];
+    const double x = (double)v[i];
     a += x;
     mx = fmax(mx, x);
   }
@@ -86,7 +88,7 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
 #pragma unroll
     for (int k = 0; k < CACHE; ++k) { sq = fma(vr[k], vr[k], sq); c += vr[k] > 0.0 ? 1u : 0u; }
     for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
-      const double x = v[i];
+      const double x = (double)v[i];
       sq = fma(x, x, sq);
       c += x > 0.0 ? 1u : 0u;
     }
@@ -110,7 +112,7 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
 #pragma unroll
     for (int k = 0; k < CACHE; ++k) c += vr[k] > 0.0 ? 1u : 0u;
     for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT)
-      c += v[i] > 0.0 ? 1u : 0u;
+      c += (double)v[i] > 0.0 ? 1u : 0u;
     double zero = 0.0;
     block_sum_count(zero, c, s);
     o.active = c;
@@ -126,7 +128,7 @@ __device__ __forceinline__ SearchOut search_block(const double* __restrict__ v, 
         if (vr[k] > tau) { sum += vr[k]; ++cnt; }
       }
       for (long long i = tid + (long long)CACHE * NT; i < ngroups; i += NT) {
-        const double x = v[i];
+        const double x = (double)v[i];
         if (x > tau) { sum += x; ++cnt; }
       }
       block_sum_count(sum, cnt, s);

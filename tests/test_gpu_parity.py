@@ -259,6 +259,82 @@ def test_trilevel_matches_oracle(mp, shape):
         check_tri(run_tri(mp, Y, eta), orc.trilevel_l1infinf(Y, eta))
 
 
+# Tensors of at least 1 MiB that the register files hold take the one-pass kernel: one piece of a
+# slab per workgroup, up to 256 of them.  The shapes cover one piece per slab and several, a ragged
+# last piece, pieces shorter than a workgroup's 512 chunks, 256 slabs, one slab, and a slab length
+# that is not a multiple of 16 bytes (which takes the three-kernel chain).
+HELD_SHAPES = [(256, 32, 40), (256, 256, 64), (7, 300, 1000), (1, 1000, 1000), (3, 1, 4000004), (100, 50, 1004),
+               (33, 77, 129), (16, 1024, 1024), (64, 1000, 33)]
+
+
+@pytest.mark.parametrize("shape", HELD_SHAPES)
+def test_trilevel_one_pass_matches_oracle(mp, shape):
+    rng = np.random.default_rng(list(shape))
+    Y = rng.standard_normal(shape).astype(np.float32)
+    Y *= np.power(10.0, rng.uniform(-1.0, 0.0, shape[0])).astype(np.float32)[:, None, None]
+    w = np.abs(Y).reshape(shape[0], -1).max(axis=1).astype(np.float64)
+    for frac in (0.05, 0.5, 1.5, 0.0):
+        eta = float(np.float32(frac * w.sum()))
+        check_tri(run_tri(mp, Y, eta), orc.trilevel_l1infinf(Y, eta))
+
+
+@pytest.mark.parametrize("limit", [0, 1])
+@pytest.mark.parametrize("shape", [(256, 32, 40), (7, 300, 1000), (16, 512, 1024)])
+def test_trilevel_one_pass_when_workgroups_do_not_wait_for_one_another(mp, shape, limit):
+    """With no patience (poll limit 0 or 1) every workgroup computes the maxima it does not find
+    posted itself, as it would on a GPU too busy to run all of them at once: same result, out of
+    place and in place, and every kernel ends."""
+    rng = np.random.default_rng(list(shape) + [limit])
+    dev = torch.device("cuda:0")
+    Y = rng.standard_normal(shape).astype(np.float32)
+    w = np.abs(Y).reshape(shape[0], -1).max(axis=1).astype(np.float64)
+    eta = float(np.float32(0.3 * w.sum()))
+    ref = orc.trilevel_l1infinf(Y, eta)
+    before = mp.set_search_spin_limit(limit)
+    try:
+        check_tri(run_tri(mp, Y, eta), ref)
+        Z = torch.from_numpy(Y).to(dev)
+        ws = mp.Workspace.for_call("tri", *shape, device=dev)
+        mp.trilevel_proj_l1infinf(Z, eta, X=Z, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(Z.cpu().numpy(), ref["X"], rtol=RTOL, atol=ATOL)
+        assert ws.result()["tau"] == pytest.approx(ref["tau"], rel=1e-9)
+    finally:
+        assert mp.set_search_spin_limit(before) == limit
+
+
+def test_trilevel_one_pass_in_place_unaligned_output_and_repeats(mp):
+    """X = Y, an X that starts 4 bytes into its allocation (element-wise stores), and 30 calls in a
+    row on one workspace (the posted words are cleared by every call): always the same bits."""
+    rng = np.random.default_rng(77)
+    dev = torch.device("cuda:0")
+    shape = (40, 100, 200)
+    Y = rng.standard_normal(shape).astype(np.float32)
+    w = np.abs(Y).reshape(shape[0], -1).max(axis=1).astype(np.float64)
+    eta = float(np.float32(0.4 * w.sum()))
+    ref = orc.trilevel_l1infinf(Y, eta)
+    Yd = torch.from_numpy(Y).to(dev)
+    ws = mp.Workspace.for_call("tri", *shape, device=dev)
+    first = None
+    for rep in range(30):
+        X = mp.trilevel_proj_l1infinf(Yd, eta, workspace=ws)
+        torch.cuda.synchronize()
+        if first is None:
+            first = X.clone()
+            np.testing.assert_allclose(X.cpu().numpy(), ref["X"], rtol=RTOL, atol=ATOL)
+        else:
+            assert torch.equal(X, first)
+    buf = torch.zeros(Y.size + 4, dtype=torch.float32, device=dev)
+    Xo = buf[1:1 + Y.size].view(shape)
+    mp.trilevel_proj_l1infinf(Yd, eta, X=Xo, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Xo, first) and float(buf[0]) == 0.0 and float(buf[-1]) == 0.0
+    Z = Yd.clone()
+    mp.trilevel_proj_l1infinf(Z, eta, X=Z, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Z, first)
+
+
 # ------------------------------------------------------------------ the five full-size workloads
 def test_workload_small_256x128(mp):
     w, Y = workloads.make("small_256x128")
