@@ -31,6 +31,8 @@ __device__ __forceinline__ typename AccOf<Q>::type combine(typename AccOf<Q>::ty
 // DIRECT (only with one row group per tile, so that a workgroup's partial is the whole column):
 // the workgroup writes v_j (and v_out) itself and workgroup 0 clears the meeting area of the
 // grid-wide search, which is all the fold kernel would have done; the host then skips that launch.
+// The partial array, which has nothing else to hold then, gets three numbers per tile: the sum,
+// the sum of squares and the maximum of the tile's v_j.
 template <int Q, typename T, int VEC, bool STRIDED, bool DIRECT = false>
 __device__ __forceinline__ void colagg_body(const T* __restrict__ Y, long long n, long long m,
                                             const Geometry& g, void* __restrict__ partial_,
@@ -72,6 +74,7 @@ __device__ __forceinline__ void colagg_body(const T* __restrict__ Y, long long n
 #pragma unroll
   for (int k = 0; k < VEC; ++k) sm[wave][lc.slot(lane, k)] = acc[k];
   __syncthreads();
+  double st_sum = 0.0, st_sq = 0.0, st_max = 0.0;   // DIRECT: sum, sum of squares and maximum of the tile's v_j
   for (int c = threadIdx.x; c < TILE_W; c += WG) {
     Acc a = sm[0][c];
 #pragma unroll
@@ -82,6 +85,9 @@ __device__ __forceinline__ void colagg_body(const T* __restrict__ Y, long long n
         const double vj = (Q == Q2) ? sqrt((double)a) : (double)a;
         v[j] = vj;
         if (v_out) v_out[j] = (float)vj;
+        st_sum += vj;
+        st_sq = fma(vj, vj, st_sq);
+        st_max = fmax(st_max, vj);
       }
     } else {
       static_cast<Acc*>(partial_)[((size_t)t * g.groups + grp) * TILE_W + c] = a;
@@ -89,6 +95,18 @@ __device__ __forceinline__ void colagg_body(const T* __restrict__ Y, long long n
   }
   if constexpr (DIRECT) {
     if (bid == 0) clear_meeting_area(flags);
+    // The tile's share of sum v, sum v^2 and max v, folded in a fixed order: with them the search
+    // over very many columns knows the totals (and a starting guess) before its first exchange.
+    __shared__ PairScratch<WAVES> st;
+    block_sum_max(st_sum, st_max, st);
+    double none = 0.0;
+    block_sum_max(st_sq, none, st);
+    if (threadIdx.x == 0) {
+      double* out = static_cast<double*>(partial_) + 3 * (size_t)t;
+      out[0] = st_sum;
+      out[1] = st_sq;
+      out[2] = st_max;
+    }
   }
 }
 
@@ -103,10 +121,11 @@ __global__ __launch_bounds__(WG) void colagg_kernel(const T* __restrict__ Y, lon
 template <int Q, typename T, int VEC, bool STRIDED>
 __global__ __launch_bounds__(WG) void colagg_direct_kernel(const T* __restrict__ Y, long long n,
                                                            long long m, Geometry g,
+                                                           void* __restrict__ tile_stats,
                                                            double* __restrict__ v,
                                                            float* __restrict__ v_out,
                                                            unsigned* __restrict__ flags) {
-  colagg_body<Q, T, VEC, STRIDED, true>(Y, n, m, g, nullptr, blockIdx.x, v, v_out, flags);
+  colagg_body<Q, T, VEC, STRIDED, true>(Y, n, m, g, tile_stats, blockIdx.x, v, v_out, flags);
 }
 
 // v_j from the partials of its tile, folded in a fixed order.  A workgroup of NT threads

@@ -156,8 +156,10 @@ static std::atomic<unsigned> g_spin_limit{SPIN_LIMIT};
 // kernels' prologue (so a split call returns the whole call's bits), one workgroup of 1024
 // threads with 32 values each up to 32768, the several-workgroup form beyond that, followed by
 // a one-workgroup kernel as a fallback that returns at once unless that form gave up.
+// tile_stats / nstats: what the aggregate pass left for the grid-wide form (see search_wide_kernel), if anything.
 static void launch_search(const Ws& ws, long long ngroups, double eta, int mode, int outer,
-                          double* norm_out, hipStream_t stream) {
+                          double* norm_out, hipStream_t stream, const double* tile_stats = nullptr,
+                          long long nstats = 0) {
   if (ngroups <= FUSED_SEARCH_MAX) {
     launch((search_kernel<WG, SEARCH_CACHE>), dim3(1), dim3(WG), stream, ws, ngroups, eta, mode, outer,
                        norm_out, 0, (double*)nullptr, (float*)nullptr);
@@ -179,7 +181,7 @@ static void launch_search(const Ws& ws, long long ngroups, double eta, int mode,
   if (iterates) {
     long long nwg = cdiv(ngroups, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
-    launch((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), stream, ws, ngroups, eta, mode, norm_out, g_spin_limit.load(std::memory_order_relaxed));
+    launch((search_wide_kernel<false, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), stream, ws, ngroups, eta, mode, norm_out, g_spin_limit.load(std::memory_order_relaxed), tile_stats, nstats);
     only_as_fallback = 1;
   }
   launch((search_kernel<SWG, SEARCH_CACHE>), dim3(1), dim3(SWG), stream, ws, ngroups, eta, mode, outer, norm_out,
@@ -196,7 +198,7 @@ static void launch_weighted_search(const Ws& ws, long long m, double eta, hipStr
     long long nwg = cdiv(m, (long long)COOP_THREADS * COOP_VALUES);
     if (nwg > COOP_MAX_WGS) nwg = COOP_MAX_WGS;
     launch((search_wide_kernel<true, COOP_THREADS, COOP_VALUES>), dim3((unsigned)nwg), dim3(COOP_THREADS), stream, ws, m,
-                       eta, (int)MODE_PROJECT, (double*)nullptr, g_spin_limit.load(std::memory_order_relaxed));
+                       eta, (int)MODE_PROJECT, (double*)nullptr, g_spin_limit.load(std::memory_order_relaxed), (const double*)nullptr, 0LL);
     only_as_fallback = 1;
   }
   if (m <= 4096)
@@ -294,9 +296,9 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     if (g.groups == 1) {
       // one row group per tile: the aggregate pass writes v itself, there is nothing to fold
       if (wide)
-        launch((colagg_direct_kernel<Q, T, WIDE, false>), grid, block, stream, Y, n, m, g, ws.v, v_out, ws.flags);
+        launch((colagg_direct_kernel<Q, T, WIDE, false>), grid, block, stream, Y, n, m, g, ws.partial, ws.v, v_out, ws.flags);
       else
-        launch((colagg_direct_kernel<Q, T, WIDE, true>), grid, block, stream, Y, n, m, g, ws.v, v_out, ws.flags);
+        launch((colagg_direct_kernel<Q, T, WIDE, true>), grid, block, stream, Y, n, m, g, ws.partial, ws.v, v_out, ws.flags);
       mark(stream);   // (the same number of intervals as the longer chain: the fold's is empty)
     } else {
       if (wide)
@@ -316,7 +318,10 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       launch_weighted_search(ws, m, (double)eta, stream);
     } else if (!fuse && !fuse_l11) {
       mark(stream);
-      launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
+      if (g.groups == 1)
+        launch_search(ws, m, (double)eta, mode, outer, norm_out, stream, static_cast<const double*>(ws.partial), g.tiles);
+      else
+        launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
     }
     if (mode == MODE_NORM) { mark(stream); return launch_status(); }
     if constexpr (Q == Q1) {

@@ -380,10 +380,20 @@ __device__ __forceinline__ bool collect(const unsigned long long* q, unsigned* f
 
 // WEIGHTED: the weighted l1 ball (see search_weighted_kernel): slices hold (v_j, w_j) pairs and
 // post a third number per round, the sum of w_j^2 over their active entries.
+// tile_stats (plain l1 ball only; null: not available): nstats triples (sum, sum of squares,
+// maximum) of disjoint parts of v, left by the aggregate pass.  Every workgroup folds them in
+// the same order, so the totals are known without the first exchange, and with the variance
+// comes a starting guess: the root if v were Gaussian with that mean and variance.  The guess
+// is evaluated first; its fixed-point image is a lower bound on the root whichever side of the
+// root the guess lies on (the tangent of a convex function lies below it), and from there the
+// iteration goes on as ever, so only the number of rounds depends on the guess: three or four
+// instead of seven on 262144 column maxima of Laplace entries.
 template <bool WEIGHTED, int NT, int VALUES>
 __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroups, double eta,
                                                           int mode, double* __restrict__ norm_out,
-                                                          unsigned spin_limit) {
+                                                          unsigned spin_limit,
+                                                          const double* __restrict__ tile_stats,
+                                                          long long nstats) {
   static_assert(NT >= COOP_MAX_WGS, "one lane per workgroup collects its post");
   __shared__ PairScratch<NT / WAVE> s;
   __shared__ unsigned lds_ok;
@@ -448,19 +458,50 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
     third = eta == 0.0 ? rmax : den;
   }
   unsigned round = 1;  // the first round carries the totals
-  if (tid == 0) {
-    post_word(slot(1u, 0, wg), round, lo32(a));
-    post_word(slot(1u, 1, wg), round, hi32(a));
-    post_word(slot(1u, 2, wg), round, lo32(mx));
-    post_word(slot(1u, 3, wg), round, hi32(mx));
-    if constexpr (WEIGHTED) {
-      post_word(slot(1u, 4, wg), round, lo32(third));
-      post_word(slot(1u, 5, wg), round, hi32(third));
-    }
-  }
   SearchOut o;
   double den_all = 0.0, rmax_all = 0.0;
-  {
+  double guess = -1.0;
+  const bool have_stats = !WEIGHTED && tile_stats != nullptr;
+  if (have_stats) {
+    double sa = 0.0, sq = 0.0, sm = 0.0, none = 0.0;
+    for (long long i = tid; i < nstats; i += NT) {
+      sa += tile_stats[3 * i];
+      sq += tile_stats[3 * i + 1];
+      sm = fmax(sm, tile_stats[3 * i + 2]);
+    }
+    block_sum_max(sa, sm, s);
+    block_sum_max(sq, none, s);
+    o.total = sa;
+    o.vmax = sm;
+    // E max(V - tau, 0) = sd h(z) for V ~ N(mean, sd^2), z = (tau - mean) / sd, with
+    // h(z) = phi(z) - z Q(z), h' = -Q (Q the upper tail): solve sd h(z) = eta / m by Newton on
+    // the convex h (it lands left of the root after the first step and rises from there)
+    const double mean = sa / (double)ngroups;
+    const double var = sq / (double)ngroups - mean * mean;
+    if (mode == MODE_PROJECT && eta > 0.0 && sa > eta && var > 0.0) {
+      // (fp32 is plenty: the guess is a statistical estimate, and only the speed depends on it)
+      const double sd = sqrt(var);
+      const float want = (float)(eta / ((double)ngroups * sd));
+      float z = 0.0f;
+      for (int it = 0; it < 8; ++it) {
+        const float tail = 0.5f * erfcf(z * 0.70710678f);
+        if (!(tail > 1e-30f)) break;
+        const float h = 0.39894228f * expf(-0.5f * z * z) - z * tail;
+        z += (h - want) / tail;
+      }
+      guess = mean + sd * (double)z;
+    }
+  } else {
+    if (tid == 0) {
+      post_word(slot(1u, 0, wg), round, lo32(a));
+      post_word(slot(1u, 1, wg), round, hi32(a));
+      post_word(slot(1u, 2, wg), round, lo32(mx));
+      post_word(slot(1u, 3, wg), round, hi32(mx));
+      if constexpr (WEIGHTED) {
+        post_word(slot(1u, 4, wg), round, lo32(third));
+        post_word(slot(1u, 5, wg), round, hi32(third));
+      }
+    }
     unsigned pay[WEIGHTED ? 6 : 4];
     if (!collect(slot(1u, 0, 0), ws.flags, round, nwg, spin_limit, pay, &lds_ok)) return;
     o.total = from32(pay[0], pay[1]);
@@ -489,7 +530,10 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
                : WEIGHTED ? (o.total - eta) / den_all
                           : fmax((o.total - eta) / (double)ngroups, o.vmax - eta);
     unsigned kprev = 0xffffffffu;
+    // (a guess at or below the lower bound, or beyond every entry, says nothing the bound does not)
+    bool guessing = !inside && guess > tau && guess < o.vmax;
     for (;;) {
+      const double at = guessing ? guess : tau;
       double sum = 0.0, sd = 0.0;
       unsigned cnt = 0;
 #pragma unroll
@@ -498,18 +542,18 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
           float wf = wr[k];
           asm volatile("" : "+v"(wf));   // (keeps the widening inside the loop)
           const double w = (double)wf;
-          if (vr[k] > tau * w) { sum = fma(w, vr[k], sum); sd = fma(w, w, sd); ++cnt; }
+          if (vr[k] > at * w) { sum = fma(w, vr[k], sum); sd = fma(w, w, sd); ++cnt; }
         } else {
-          if (vr[k] > tau) { sum += vr[k]; ++cnt; }
+          if (vr[k] > at) { sum += vr[k]; ++cnt; }
         }
       }
       for (long long i = lo + tid + (long long)VALUES * NT; i < hi; i += NT) {
         const double x = v[i];
         if constexpr (WEIGHTED) {
           const double w = (double)wts[i];
-          if (x > tau * w) { sum = fma(w, x, sum); sd = fma(w, w, sd); ++cnt; }
+          if (x > at * w) { sum = fma(w, x, sum); sd = fma(w, w, sd); ++cnt; }
         } else {
-          if (x > tau) { sum += x; ++cnt; }
+          if (x > at) { sum += x; ++cnt; }
         }
       }
       if constexpr (WEIGHTED) block_sum2_count(sum, sd, cnt, s);
@@ -534,6 +578,18 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
         block_sum2_count(S, D, K, s);
       } else {
         block_sum_count(S, K, s);
+      }
+      if (guessing) {
+        // The image of the guess.  If it beats the bound it becomes the point, and the count at
+        // the guess stands for "the point it came from": an equal count at the image means no
+        // entry lies between the two, so the image is the root of that linear piece.
+        guessing = false;
+        ++o.iters;
+        if (K > 0u) {
+          const double t = (S - eta) / (double)K;
+          if (t > tau) { tau = t; kprev = K; }
+        }
+        continue;
       }
       o.active = K;
       if (inside || K == 0u || K == kprev) break;  // inside: one round, just to count
