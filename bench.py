@@ -68,6 +68,7 @@ DIST_TEXT = {"normal": "i.i.d. N(0,1)", "normal_colscale": "N(0,1) x per-column 
              "laplace": "i.i.d. Laplace(0,1)", "uniform": "i.i.d. U(0,1)"}
 
 KERNEL_LABELS = {
+    3: ["held_clear", "held_slab+search"],
     4: ["colagg", "reduce", "colmap+search"],
     5: ["colagg", "reduce", "search", "colmap"],
     6: ["colagg", "reduce", "search", "l11_sweeps", "colmap"],
@@ -169,6 +170,41 @@ def bench_bilevel(torch, mp, Y_host, variant, frac, steps, warmup, cold=True, et
         "search_iters": res["search_iters"],
         "inner_sweeps": res["inner_sweeps"], "inner_pending": res["inner_pending"],
     }
+    if keep_output:
+        out["_x_timed"] = x_timed
+    del pairs
+    torch.cuda.empty_cache()
+    return out
+
+
+def bench_trilevel_head(torch, mp, Y_host, frac, steps, warmup, keep_output=False):
+    """The tri-level l1,inf,inf projection as the headline workload (--workload tensor_...): the
+    fields bench_bilevel reports, cold timing over rotating buffers."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    d0 = Y_host.shape[0]
+    npairs = max(2, -(-3 * INFINITY_CACHE_BYTES // (2 * Y_host.nbytes)))
+    Y0 = torch.from_numpy(Y_host).to(dev)
+    pairs = [(Y0, torch.empty_like(Y0))] + [(Y0.clone(), torch.empty_like(Y0)) for _ in range(npairs - 1)]
+    ws = mp.Workspace.for_call("tri", *Y_host.shape, device=dev)
+    # eta from the library itself: with a radius beyond the norm the record holds the norm
+    mp.trilevel_proj_l1infinf(pairs[0][0], 3.0e38, X=pairs[0][1], workspace=ws)
+    torch.cuda.synchronize()
+    eta = float(np.float32(frac * ws.result()["norm"]))
+    fn = lambda Y, X: mp.trilevel_proj_l1infinf(Y, eta, X=X, workspace=ws)
+    ms = time_calls(torch, fn, pairs, steps, warmup)
+    res = ws.result()
+    x_timed = pairs[(steps - 1) % npairs][1].cpu().numpy() if keep_output else None
+    k_raw = time_kernels(torch, mp, fn, pairs, min(steps, 100), min(warmup, 10))
+    excess = max(0.0, (sum(k_raw.values()) - ms) / len(k_raw))
+    k_ms = {k: max(v - excess, 0.0) for k, v in k_raw.items()}
+    warm_ms = time_calls(torch, fn, pairs[:1], steps, warmup)
+    elems = Y_host.size
+    out = {"shape": list(Y_host.shape), "variant": "tri", "storage": "f32", "eta": eta, "buffer_pairs": npairs,
+           "ms": ms, "ms_warm": warm_ms, "bytes_per_element_rw": 8.0, "eff_GBps_rw": 8.0 * elems / ms / 1e6,
+           "frac_of_peak_rw": 8.0 * elems / ms / 1e6 / HBM_PEAK_GBS, "kernel_ms": k_ms,
+           "kernel_ms_event_intervals": k_raw, "tau": res["tau"], "n_active": res["n_active"],
+           "search_iters": res["search_iters"]}
     if keep_output:
         out["_x_timed"] = x_timed
     del pairs
@@ -454,22 +490,24 @@ def cpu_baseline(Y_host, eta, x_timed, tau_gpu, budget_s=15.0):
     the GPU runs used; its result also checks the X the last timed GPU step produced."""
     import numpy as np
     from oracle import mlproj_oracle as orc
+    tensor = Y_host.ndim == 3
+    run = orc.trilevel_l1infinf if tensor else orc.bilevel_l1inf
     times = []
     t_all = time.perf_counter()
     while len(times) < 5 and (time.perf_counter() - t_all) < budget_s:
         t0 = time.perf_counter()
-        ref = orc.bilevel_l1inf(Y_host, eta)
+        ref = run(Y_host, eta)
         times.append(time.perf_counter() - t0)
     t = statistics.median(times)
-    n, m = Y_host.shape
     err = np.abs(x_timed.astype(np.float64) - ref["X"])
     bar = 1e-5 * np.abs(ref["X"]) + 1e-6
+    group_max = np.abs(x_timed).reshape(x_timed.shape[0], -1).max(axis=1) if tensor else np.abs(x_timed).max(axis=0)
     parity = {"max_abs_err": float(err.max()), "within_rtol1e-5_atol1e-6": bool((err <= bar).all()),
-              "support_identical": bool(np.array_equal(np.abs(x_timed).max(axis=0) > 0, np.asarray(ref["u"]) > 0)),
+              "support_identical": bool(np.array_equal(group_max > 0, np.asarray(ref["u"]) > 0)),
               "tau_rel_err": abs(tau_gpu - ref["tau"]) / ref["tau"] if ref["tau"] > 0 else 0.0}
     usable, logical, model = host_description()
-    return {"value": 8.0 * n * m / t / 1e9, "unit": "GB/s", "ms": t * 1e3, "cores": 1, "kind": "oracle",
-            "sample": "full %dx%d workload, median of %d runs of oracle.bilevel_l1inf" % (n, m, len(times)),
+    return {"value": 8.0 * Y_host.size / t / 1e9, "unit": "GB/s", "ms": t * 1e3, "cores": 1, "kind": "oracle",
+            "sample": "full %s workload, median of %d runs of oracle.%s" % ("x".join(map(str, Y_host.shape)), len(times), run.__name__),
             "nproc": usable, "logical_cpus": logical, "cpu_model": model,
             "gpu_x_vs_oracle": parity}, ref["X"]
 
@@ -503,8 +541,9 @@ def main():
 
     w, Y = workloads.make(args.workload)
     want_cpu = not (args.quick or args.no_cpu)
+    tensor = len(w.shape) == 3
     all_cores = x_all = None
-    if want_cpu:
+    if want_cpu and not tensor:
         # first, while this process has not touched the GPU: the leg that forks worker processes
         from oracle import mlproj_oracle as orc
         eta_cpu = float(np.float32(w.eta_frac * orc.norm_l1q(Y, "inf")))
@@ -515,17 +554,20 @@ def main():
     from paper_2405_02086_amd import binding as mp
     mp.lib()   # fail loudly if the HIP library is missing
 
-    head = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
+    if tensor:
+        head = bench_trilevel_head(torch, mp, Y, w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
+    else:
+        head = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
     x_timed = head.pop("_x_timed", None)
-    n, m = Y.shape
-    elems = n * m
+    elems = Y.size
+    what = "tri-level l1,inf,inf" if tensor else "bi-level l1,inf"
     # the dominant kernel: the one that reads Y and writes X (8 B/element)
     kms = head["kernel_ms"]
     dom = max(kms, key=kms.get)
     dom_ms = kms[dom]
     traffic_ok = args.workload in TRAFFIC_KIB and mp.lib().mlproj_version() in TRAFFIC_VERSIONS
     roofline = {
-        "bound": "hbm", "kernel": "%s (l1,inf; 8 B/element: reads Y, writes X)" % dom,
+        "bound": "hbm", "kernel": "%s (%s; 8 B/element: reads Y, writes X)" % (dom, what),
         "achieved": 8.0 * elems / dom_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": 8.0 * elems / dom_ms / 1e6 / HBM_PEAK_GBS,
         "traffic": TRAFFIC_KIB[args.workload] * 1024.0 if traffic_ok else None,
@@ -535,19 +577,20 @@ def main():
         "all_kernels_ms": {k: round(v, 5) for k, v in kms.items()},
     }
     line = {
-        "metric": "effective HBM GB/s of one bi-level l1,inf projection (8 B/element), cold caches",
+        "metric": "effective HBM GB/s of one %s projection (8 B/element), cold caches" % what,
         "value": head["eff_GBps_rw"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %dx%d fp32 row-major, entries %s, eta=%.2f*||Y||_1,inf; cold (%d rotating buffer pairs)"
-                               % (args.workload, n, m, DIST_TEXT[w.dist], w.eta_frac, head["buffer_pairs"]),
+        "config": {"workload": "%s: %s fp32 %s, entries %s, eta=%.2f*norm; cold (%d rotating buffer pairs)"
+                               % (args.workload, "x".join(map(str, Y.shape)), "C-order" if tensor else "row-major",
+                                  DIST_TEXT[w.dist], w.eta_frac, head["buffer_pairs"]),
                    "input_crc32": "%08x" % zlib.crc32(Y.tobytes())},
         "frac_of_hbm_peak": head["frac_of_peak_rw"], "ms_per_step_warm": head["ms_warm"],
         "roofline": roofline,
     }
     detail = {"headline": head,
               "generator": "numpy Generator(PCG64(%d)), see paper_2405_02086_amd/workloads.py" % w.seed}
-    if not args.quick:
+    if not args.quick and not tensor:
         also = {}
         wb, Yb = workloads.make("square_16384")
         for variant, steps in (("l1inf", 20), ("l12", 20), ("l11", 5)):
@@ -604,9 +647,10 @@ def main():
         }
     if want_cpu:
         base, x_ref = cpu_baseline(Y, head["eta"], x_timed, head["tau"])
-        base.update(all_cores)
-        if all_cores["eta_all_cores"] == head["eta"]:
-            base["all_cores_output_equals_one_thread_output"] = bool(np.array_equal(x_all, x_ref))
+        if all_cores is not None:
+            base.update(all_cores)
+            if all_cores["eta_all_cores"] == head["eta"]:
+                base["all_cores_output_equals_one_thread_output"] = bool(np.array_equal(x_all, x_ref))
         line["cpu_baseline"] = base
     # Everything bulky first (its own stdout line, and a file where a results folder exists); the
     # LAST line is the compact record.

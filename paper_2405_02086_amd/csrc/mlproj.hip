@@ -124,11 +124,16 @@ static int launch_status() {
   return refused ? MLPROJ_ERR_LAUNCH : MLPROJ_OK;
 }
 
-// Compute units of the current device (0 when there is none to ask).
+// Compute units of the current device (0 when there is none to ask).  A device's count never
+// changes, so it is asked for once per device and remembered.
 static int compute_units() {
+  constexpr int MAX_DEVICES = 64;
+  static std::atomic<int> known[MAX_DEVICES];   // 0: not asked yet
   int dev = -1, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) return 0;
+  if (dev < MAX_DEVICES && (cus = known[dev].load(std::memory_order_relaxed)) > 0) return cus;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 0;
+  if (dev < MAX_DEVICES) known[dev].store(cus, std::memory_order_relaxed);
   return cus;
 }
 
@@ -874,7 +879,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 360; }
+int mlproj_version(void) { return 362; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
