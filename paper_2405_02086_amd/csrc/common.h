@@ -76,7 +76,6 @@ struct Ws {
   unsigned* kprev;         // [m] l1,1: active count at the point whose Newton step is tlo, or NO_COUNT
   unsigned* done;          // [m] l1,1: 1 once tauj is final
   unsigned* gcnt;          // [m] l1,1: entries in the window, all workgroups
-  unsigned* gflag;         // [m] l1,1: some workgroup could not stage all of its window entries
   float* cand;             // [list_cap][m] l1,1: the window entries, slot-major
   int list_cap;            // slots per column in cand
   void* partial;           // [tiles][groups][tile_w] float (q = inf) or double
@@ -84,11 +83,13 @@ struct Ws {
   unsigned* partial_cnt2;  // [tiles][groups][tile_w] l1,1: entries above t*(1 + L11_WINDOW)
   const float* wts;        // [groups] weights of a weighted l1 ball as outer norm; null: the plain norms
   unsigned* posts;         // [HELD_POST_WORDS] one-pass tri-level kernel: what its workgroups post to one another
+  float* scale;            // [m] l1,1: the columns' scale estimates that anchor the grid (l11grid.h)
+  float* gpart;            // [tiles][groups][8][tile_w] l1,1: grid partials of the aggregate pass
 };
 
 struct Layout {
   size_t off_pending, off_flags, off_coop_q, off_v, off_tauj, off_kprev, off_partial, off_partial_cnt, off_partial_cnt2, bytes;
-  size_t off_tlo, off_lb, off_ub, off_done, off_gcnt, off_gflag, off_cand, off_posts;
+  size_t off_tlo, off_lb, off_ub, off_done, off_gcnt, off_cand, off_posts, off_scale, off_gpart;
   int list_cap;
 };
 
@@ -180,9 +181,10 @@ __host__ __device__ static inline Layout layout_for(const Geometry& g, long long
   L.off_ub = o;            o = align_up(o + per_col8, 256);
   L.off_done = o;          o = align_up(o + per_col4, 256);
   L.off_gcnt = o;          o = align_up(o + per_col4, 256);
-  L.off_gflag = o;         o = align_up(o + per_col4, 256);
   L.off_cand = o;          o = align_up(o + per_col4 * (size_t)L.list_cap, 256);
   L.off_posts = o;         o = align_up(o + (variant == MLPROJ_L1INFINF ? (size_t)HELD_POST_WORDS * 4 : 0), 256);
+  L.off_scale = o;         o = align_up(o + per_col4, 256);
+  L.off_gpart = o;         o = align_up(o + (variant == Q1 ? cells * 32 : 0), 256);
   L.bytes = o;
   return L;
 }
@@ -206,10 +208,11 @@ __host__ __device__ static inline Ws bind(void* workspace, const Layout& L) {
   w.ub = reinterpret_cast<double*>(b + L.off_ub);
   w.done = reinterpret_cast<unsigned*>(b + L.off_done);
   w.gcnt = reinterpret_cast<unsigned*>(b + L.off_gcnt);
-  w.gflag = reinterpret_cast<unsigned*>(b + L.off_gflag);
   w.cand = reinterpret_cast<float*>(b + L.off_cand);
   w.list_cap = L.list_cap;
   w.posts = reinterpret_cast<unsigned*>(b + L.off_posts);
+  w.scale = reinterpret_cast<float*>(b + L.off_scale);
+  w.gpart = reinterpret_cast<float*>(b + L.off_gpart);
   return w;
 }
 

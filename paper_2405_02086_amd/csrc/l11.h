@@ -145,9 +145,9 @@ __global__ __launch_bounds__(WG) void l11_sweep_kernel(const T* __restrict__ Y, 
 // Sweeps 1, 2, ...: sum and count of the entries above hi = tauj, and the entries in
 // (tlo, hi] themselves.  A workgroup stages the window entries of its tile's columns in LDS
 // (FILTER_LDS_SLOTS / TILE_W slots per column), then reserves room in each column's list with
-// one atomic add per column and copies them out.  gcnt ends as the true number of window
-// entries of the column whether or not they all fitted; gflag marks a column some workgroup
-// could not stage completely.
+// one atomic add per column and copies them out; an entry that finds the staging area full goes
+// to the column's list directly.  gcnt ends as the true number of window entries of the column
+// whether or not they all fitted the list.
 template <int TILE_W>
 struct FilterLds {
   double sum[WAVES][TILE_W];
@@ -212,7 +212,14 @@ __device__ __forceinline__ void l11_filter_body(const T* __restrict__ Y, long lo
           if (a >= clo[k] && !(a >= chi[k])) {
             const int c = lc.slot(lane, k);
             const unsigned slot = atomicAdd(&staged_cnt[c], 1u);
-            if (slot < (unsigned)CAPW) staged[slot][c] = a;
+            if (slot < (unsigned)CAPW) {
+              staged[slot][c] = a;
+            } else {
+              // no room left in the workgroup's staging area: straight into the column's list
+              // (rare; one global atomic per entry instead of one per column)
+              const unsigned off = atomicAdd(&ws.gcnt[lc.col(k)], 1u);
+              if (off < (unsigned)ws.list_cap) ws.cand[(size_t)off * (size_t)m + (size_t)lc.col(k)] = a;
+            }
           }
         }
       }
@@ -258,16 +265,12 @@ __device__ __forceinline__ void l11_filter_body(const T* __restrict__ Y, long lo
     static_cast<double*>(ws.partial)[cell] = a;
     ws.partial_cnt[cell] = k;
     const long long col = t * TILE_W + c;
-    const unsigned r = staged_cnt[c];
+    const unsigned seen = staged_cnt[c];
+    const unsigned r = seen < (unsigned)CAPW ? seen : (unsigned)CAPW;   // (the rest went to the list directly)
     if (col < m && r > 0u) {
-      if (r > (unsigned)CAPW) {
-        ws.gflag[col] = 1u;
-        atomicAdd(&ws.gcnt[col], r);
-      } else {
-        const unsigned off = atomicAdd(&ws.gcnt[col], r);
-        for (unsigned s = 0; s < r && off + s < (unsigned)ws.list_cap; ++s)
-          ws.cand[(size_t)(off + s) * (size_t)m + (size_t)col] = staged[s][c];
-      }
+      const unsigned off = atomicAdd(&ws.gcnt[col], r);
+      for (unsigned s = 0; s < r && off + s < (unsigned)ws.list_cap; ++s)
+        ws.cand[(size_t)(off + s) * (size_t)m + (size_t)col] = staged[s][c];
     }
   }
 }
@@ -338,7 +341,6 @@ __device__ __forceinline__ void l11_init_body(long long n, long long m, const Ws
   ws.kprev[j] = NO_COUNT;
   ws.done[j] = uj > 0.0 ? 0u : 1u;
   ws.gcnt[j] = 0u;
-  ws.gflag[j] = 0u;
 }
 
 template <int SC>
@@ -439,7 +441,7 @@ __device__ __forceinline__ void l11_update_body(long long n, long long m, const 
   double sc = 0.0;
   if (sweep > 0 && mine) {
     r = ws.gcnt[j];
-    complete = ws.gflag[j] == 0u && r <= (unsigned)ws.list_cap;
+    complete = r <= (unsigned)ws.list_cap;
     if (complete && r > 0u) {
       // every load is unconditional (a slot past the end re-reads the last entry and is then
       // blanked), so they are all in flight together
@@ -549,7 +551,6 @@ __device__ __forceinline__ void l11_update_body(long long n, long long m, const 
       open = closed ? 0u : 1u;
     }
     ws.gcnt[j] = 0u;
-    ws.gflag[j] = 0u;
   }
   const unsigned wg_open = block_sum_u(open, bs);
   if (threadIdx.x == 0) {

@@ -34,6 +34,7 @@
 #include "search.h"
 #include "map.h"
 #include "l11.h"
+#include "l11grid.h"
 #include "slab.h"
 #include "fibre.h"
 #include "tiny.h"
@@ -270,7 +271,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   Ws ws = bind(workspace, L);
   ws.wts = weights;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  const dim3 grid((unsigned)(g.tiles * g.groups)), block(WG);
+  const dim3 grid_dim((unsigned)(g.tiles * g.groups)), block(WG);
   const dim3 mgrid((unsigned)(g.tiles * g.map_groups));
   const int rthreads = fold_threads(g.groups);
   const int parts = reduce_parts(g.groups, rthreads);
@@ -296,20 +297,47 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       return launch_status();
     }
   }
+  // l1,1 with lock-step sweeps planned: the aggregate pass also evaluates the columns on a grid
+  // of thresholds, which stands in for the probing sweep (l11grid.h)
+  bool grid = false;
+  if constexpr (Q == Q1) {
+    int sweeps;
+    unsigned handoff;
+    plan_l11(n, m, (int)sizeof(T), &sweeps, &handoff);
+    // (worth it from 128 MiB on, where the probing pass costs more than the scale kernel, the grid
+    // arithmetic and the longer seeding; not on 16-bit storage, where the aggregate pass has twice
+    // the elements per byte and the grid arithmetic would double its time)
+    grid = mode == MODE_PROJECT && sweeps >= 1 && sizeof(T) == 4 && n * m >= (32LL << 20);
+  }
   if (stages & STAGE_AGGREGATE) {
     mark(stream);
-    if (g.groups == 1) {
+    if constexpr (Q == Q1) {
+      if (grid) {
+        launch((l11_scale_kernel<T>), dim3((unsigned)cdiv(m, WG)), block, stream, Y, n, m, ws.scale);
+        if (wide)
+          launch((colagg_grid_kernel<T, WIDE, false>), grid_dim, block, stream, Y, n, m, g, ws, (const float*)ws.scale, ws.gpart);
+        else
+          launch((colagg_grid_kernel<T, WIDE, true>), grid_dim, block, stream, Y, n, m, g, ws, (const float*)ws.scale, ws.gpart);
+      }
+    }
+    if (grid) {
+      mark(stream);
+      if (rthreads == 256)
+        launch((reduce_kernel<Q, 256>), rgrid, rblock, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+      else
+        launch((reduce_kernel<Q>), rgrid, rblock, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+    } else if (g.groups == 1) {
       // one row group per tile: the aggregate pass writes v itself, there is nothing to fold
       if (wide)
-        launch((colagg_direct_kernel<Q, T, WIDE, false>), grid, block, stream, Y, n, m, g, ws.partial, ws.v, v_out, ws.flags);
+        launch((colagg_direct_kernel<Q, T, WIDE, false>), grid_dim, block, stream, Y, n, m, g, ws.partial, ws.v, v_out, ws.flags);
       else
-        launch((colagg_direct_kernel<Q, T, WIDE, true>), grid, block, stream, Y, n, m, g, ws.partial, ws.v, v_out, ws.flags);
+        launch((colagg_direct_kernel<Q, T, WIDE, true>), grid_dim, block, stream, Y, n, m, g, ws.partial, ws.v, v_out, ws.flags);
       mark(stream);   // (the same number of intervals as the longer chain: the fold's is empty)
     } else {
       if (wide)
-        launch((colagg_kernel<Q, T, WIDE, false>), grid, block, stream, Y, n, m, g, ws.partial);
+        launch((colagg_kernel<Q, T, WIDE, false>), grid_dim, block, stream, Y, n, m, g, ws.partial);
       else
-        launch((colagg_kernel<Q, T, WIDE, true>), grid, block, stream, Y, n, m, g, ws.partial);
+        launch((colagg_kernel<Q, T, WIDE, true>), grid_dim, block, stream, Y, n, m, g, ws.partial);
       mark(stream);
       if (rthreads == 256)
         launch((reduce_kernel<Q, 256>), rgrid, rblock, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
@@ -323,7 +351,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       launch_weighted_search(ws, m, (double)eta, stream);
     } else if (!fuse && !fuse_l11) {
       mark(stream);
-      if (g.groups == 1)
+      if (g.groups == 1 && !grid)   // (the direct aggregate pass ran and left its per-tile triples)
         launch_search(ws, m, (double)eta, mode, outer, norm_out, stream, static_cast<const double*>(ws.partial), g.tiles);
       else
         launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
@@ -343,20 +371,30 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
         mark(stream);   // (the same number of intervals as the longer chain: this one is empty)
       } else {
         const dim3 igrid((unsigned)cdiv(m, WG));
-        if (!fuse_l11)
+        if (grid) {
+          const float* sc = ws.scale;
+          const float* gp = ws.gpart;
+          if (!fuse_l11)
+            launch((l11_init_grid_kernel<SEARCH_CACHE>), igrid, block, stream, n, m, g, ws, -1.0, outer, sc, gp);
+          else if (m > FUSED_SEARCH_MAX)
+            launch((l11_init_grid_kernel<SEARCH_CACHE_BIG>), igrid, block, stream, n, m, g, ws, (double)eta, outer, sc, gp);
+          else
+            launch((l11_init_grid_kernel<SEARCH_CACHE>), igrid, block, stream, n, m, g, ws, (double)eta, outer, sc, gp);
+        } else if (!fuse_l11)
           launch((l11_init_kernel<SEARCH_CACHE>), igrid, block, stream, n, m, ws, -1.0, outer);
         else if (m > FUSED_SEARCH_MAX)
           launch((l11_init_kernel<SEARCH_CACHE_BIG>), igrid, block, stream, n, m, ws, (double)eta, outer);
         else
           launch((l11_init_kernel<SEARCH_CACHE>), igrid, block, stream, n, m, ws, (double)eta, outer);
         if (fuse_l11) mark(stream);   // (keeps one interval for search + seeding, one for the sweeps)
-        for (int s = 0; s < sweeps; ++s) {
+        // (with the grid the seeding kernel has already done what sweep 0 and its update do)
+        for (int s = grid ? 1 : 0; s < sweeps; ++s) {
           if (s == 0) {
-            if (wide) launch((l11_sweep_kernel<T, WIDE, false>), grid, block, stream, Y, n, m, g, ws);
-            else launch((l11_sweep_kernel<T, WIDE, true>), grid, block, stream, Y, n, m, g, ws);
+            if (wide) launch((l11_sweep_kernel<T, WIDE, false>), grid_dim, block, stream, Y, n, m, g, ws);
+            else launch((l11_sweep_kernel<T, WIDE, true>), grid_dim, block, stream, Y, n, m, g, ws);
           } else {
-            if (wide) launch((l11_filter_kernel<T, WIDE, false>), grid, block, stream, Y, n, m, g, ws, s, handoff);
-            else launch((l11_filter_kernel<T, WIDE, true>), grid, block, stream, Y, n, m, g, ws, s, handoff);
+            if (wide) launch((l11_filter_kernel<T, WIDE, false>), grid_dim, block, stream, Y, n, m, g, ws, s, handoff);
+            else launch((l11_filter_kernel<T, WIDE, true>), grid_dim, block, stream, Y, n, m, g, ws, s, handoff);
           }
           launch(l11_update_kernel, dim3((unsigned)cdiv(m, UPD_COLS)), block, stream, n, m, g, ws, s, handoff);
         }
@@ -879,7 +917,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 362; }
+int mlproj_version(void) { return 370; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

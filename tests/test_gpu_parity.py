@@ -1110,6 +1110,34 @@ def test_l11_inner_searches_converge_on_hard_distributions(mp, family):
         assert got["res"]["inner_sweeps"] <= 10, (family, frac, got["res"]["inner_sweeps"])
 
 
+@pytest.mark.parametrize("shape", [(32770, 1028), (16400, 2054)])
+@pytest.mark.parametrize("family", ["gaussian", "laplace", "cauchy", "lognormal3", "sparse", "clusters", "constant",
+                                    "integers", "geometric", "uniform", "misleading_head", "empty_head"])
+def test_l11_grid_start_on_hard_distributions(mp, family, shape):
+    """From 32M fp32 elements on the aggregate pass also evaluates every column on a grid of
+    thresholds anchored at the mean magnitude of its first 128 rows, and the inner searches start
+    from that instead of a probing pass.  Whatever the grid says (heavy tails, ties, a head that
+    is a thousand times the rest or all zero), every threshold is still closed exactly.  The
+    second shape has rows that are not 16-byte aligned (the element-wise access form)."""
+    rng = np.random.default_rng([len(family), shape[1], 80])
+    n, m = shape
+    if family == "gaussian":
+        Y = rng.standard_normal((n, m))
+    elif family == "laplace":
+        Y = rng.laplace(size=(n, m))
+    elif family in ("misleading_head", "empty_head"):
+        Y = rng.standard_normal((n, m))
+        Y[:128] *= 1000.0 if family == "misleading_head" else 0.0
+    else:
+        Y = _hard_family(family, rng, n, m)
+    Y = Y.astype(np.float32)
+    for frac in (0.001, 0.1, 0.5, 0.95):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert got["res"]["inner_sweeps"] <= 10, (family, frac, got["res"]["inner_sweeps"])
+
+
 # ------------------------------------------------------------------ batches
 BATCH_SHAPES = [(256, 128), (1, 1), (33, 20), (300, 257), (131, 1028), (64, 4100), (9, 5000), (512, 8192),
                 (7, 16388), (40, 17000), (256, 128), (100, 260), (2065, 264), (5, 3), (77, 1024), (16, 16),
