@@ -917,7 +917,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 370; }
+int mlproj_version(void) { return 371; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -71,8 +71,13 @@ __device__ __forceinline__ void tiny_body(const T* Y, T* X, long long n,
                                           bool whole) {
   using Acc = typename AccOf<Q>::type;
   __shared__ Acc sm_part[TINY_WG * VEC];   // [row lane][column]
-  __shared__ double sm_v[TINY_WG * VEC];   // v, zero beyond column m
   __shared__ PairScratch<TINY_WAVES> bs;
+  // v (zero beyond column m) takes the place of row lane 0 of the partials, in their type (fp32
+  // maxima are exact, sums stay fp64): column c of that row is read by the one thread that then
+  // writes v_c, and the other rows lie behind it.  So the body's LDS is at most 32 KiB.
+  Acc* const sm_v = sm_part;
+  static_assert(sizeof(Acc) * TINY_WG * VEC + sizeof(PairScratch<TINY_WAVES>) <= 49152,
+                "tiny_body: the partial aggregates of this (q, storage type) need more LDS than planned");
   const int rl = TINY_WG / cw;
   const int tc = threadIdx.x % cw;
   const int tr = threadIdx.x / cw;
@@ -105,18 +110,18 @@ __device__ __forceinline__ void tiny_body(const T* Y, T* X, long long n,
     Acc a = sm_part[c];
     for (int r = 1; r < rl; ++r) a = combine<Q>(a, sm_part[r * width + c]);
     const double vj = (Q == Q2) ? sqrt((double)a) : (double)a;
-    sm_v[c] = c < m ? vj : 0.0;
+    sm_v[c] = c < m ? (Acc)vj : (Acc)0;
   }
   __syncthreads();
 
   // (the search of the map kernel's 256-thread workgroups, so that tau has the same bits here
   // as in the three-kernel chain and in a batch)
-  const SearchOut o = search_block<WG, SEARCH_CACHE, TINY_WG>(sm_v, m, eta, MODE_PROJECT, outer, bs);
+  const SearchOut o = search_block<WG, SEARCH_CACHE, TINY_WG, Acc>(sm_v, m, eta, MODE_PROJECT, outer, bs);
   const Top top = top_of(o);
   if (bid == 0) {
     if (threadIdx.x == 0) write_result(ws, o, nullptr);
     for (long long c = threadIdx.x; c < m; c += TINY_WG) {
-      const double uj = radius(sm_v[c], top);
+      const double uj = radius((double)sm_v[c], top);
       if (v_out) v_out[c] = (float)sm_v[c];
       if (u_out) u_out[c] = (float)uj;
       if (mask_out) mask_out[c] = uj > 0.0 ? 1 : 0;
@@ -126,7 +131,7 @@ __device__ __forceinline__ void tiny_body(const T* Y, T* X, long long n,
   double par[VEC];   // q = 2: scale u_j / v_j
 #pragma unroll
   for (int e = 0; e < VEC; ++e) {
-    const double vj = sm_v[tc * VEC + e];
+    const double vj = (double)sm_v[tc * VEC + e];
     const double uj = radius(vj, top);
     uf[e] = (float)uj;
     par[e] = (Q == Q2 && vj > 0.0) ? uj / vj : 0.0;
