@@ -572,7 +572,7 @@ def main():
         "achieved": 8.0 * elems / dom_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": 8.0 * elems / dom_ms / 1e6 / HBM_PEAK_GBS,
         "traffic": TRAFFIC_KIB[args.workload] * 1024.0 if traffic_ok else None,
-        "traffic_source": "profiles/ (rocprofv3 --pmc, library version %d)" % mp.lib().mlproj_version() if traffic_ok else None,
+        "traffic_source": "profiles/ (rocprofv3 --pmc, taken with library version %d)" % TRAFFIC_VERSIONS[0] if traffic_ok else None,
         "algorithmic_bytes": 8.0 * elems,
         "kernel_ms": dom_ms,
         "all_kernels_ms": {k: round(v, 5) for k, v in kms.items()},
