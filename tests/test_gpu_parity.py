@@ -1388,7 +1388,9 @@ def test_l11_root_exactly_on_repeated_entries(mp):
 
 # ------------------------------------------------------------------ tri-level on 16-bit storage
 @pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
-@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 4, 5), (17, 16, 16), (6, 50, 41), (300, 3, 2), (4, 64, 1024), (40, 33, 264)])
+# (the last three shapes are large enough, 1 MiB and more in every storage type, for the one-pass kernel)
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 4, 5), (17, 16, 16), (6, 50, 41), (300, 3, 2), (4, 64, 1024), (40, 33, 264),
+                                   (16, 128, 1024), (200, 40, 1000), (3, 1, 1000008)])
 def test_trilevel_stored_matches_oracle(mp, storage, shape):
     dev = torch.device("cuda:0")
     dt = getattr(torch, STORE_DTYPES[storage])
