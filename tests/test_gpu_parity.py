@@ -822,6 +822,74 @@ def test_graph_replay_of_the_other_launch_chains(mp):
     check(lambda X: mp.multilevel_proj(T, [1, 1], eta, X=X, workspace=ws), torch.zeros_like(T), lambda: T.mul_(0.5))
 
 
+def test_graph_replay_of_the_one_pass_and_grid_chains(mp):
+    """The one-pass tri-level kernel (its posted words are cleared by the small kernel recorded in
+    front of it, so every replay starts clean), the l1,1 chain whose aggregate pass carries the
+    grid, and the entry point that allocates nothing: recorded once, replayed four times with the
+    program's own eager calls in between, new data from the third replay on."""
+    rng = np.random.default_rng(53)
+    dev = torch.device("cuda:0")
+
+    def check(make_call, out, refresh, reps=4):
+        eager = make_call(None).clone()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            make_call(out)
+        for rep in range(reps):
+            out.zero_()
+            if rep == 2:
+                refresh()
+            eager = make_call(None).clone()       # (an eager call between the replays, on the same workspace)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), rep
+
+    T = torch.from_numpy(rng.standard_normal((96, 64, 128)).astype(np.float32)).to(dev)        # 3 MiB: one pass
+    ws = mp.Workspace.for_call("tri", *T.shape, device=dev)
+    w = T.abs().reshape(96, -1).max(dim=1).values.double().sum().item()
+    eta = float(np.float32(0.3 * w))
+    check(lambda X: mp.trilevel_proj_l1infinf(T, eta, X=X, workspace=ws), torch.zeros_like(T), lambda: T.mul_(0.5))
+    Y = torch.from_numpy(rng.standard_normal((8200, 4096)).astype(np.float32)).to(dev)        # 128 MiB: the grid
+    ws1 = mp.Workspace.for_call("l11", *Y.shape, device=dev)
+    eta1 = float(np.float32(0.2 * Y.abs().double().sum().item()))
+    check(lambda X: mp.bilevel_proj_l11(Y, eta1, X=X, workspace=ws1), torch.zeros_like(Y), lambda: Y.mul_(0.5))
+    Z = torch.from_numpy(rng.standard_normal((700, 900)).astype(np.float32)).to(dev)
+    eta2 = float(np.float32(0.2 * Z.abs().max(dim=0).values.double().sum().item()))
+    scratch_out = torch.zeros_like(Z)
+    check(lambda X: mp.bilevel_proj_l1inf_no_alloc(Z, eta2, scratch_out if X is None else X), torch.zeros_like(Z),
+          lambda: Z.mul_(0.5))
+
+
+def test_trilevel_one_pass_on_a_busy_gpu(mp):
+    """The one-pass kernel with its default patience while another stream keeps the GPU full of
+    the library's own long kernels: whether all of its workgroups run at once or some start late
+    and the others compute their maxima for them, the result is the oracle's and every kernel ends."""
+    rng = np.random.default_rng(54)
+    dev = torch.device("cuda:0")
+    big = torch.from_numpy(rng.standard_normal((8192, 8192)).astype(np.float32)).to(dev)
+    big_out = torch.empty_like(big)
+    big_ws = mp.Workspace.for_call("l11", 8192, 8192, device=dev)
+    shape = (256, 64, 256)
+    Y = rng.standard_normal(shape).astype(np.float32)
+    w = np.abs(Y).reshape(shape[0], -1).max(axis=1).astype(np.float64)
+    eta = float(np.float32(0.25 * w.sum()))
+    ref = orc.trilevel_l1infinf(Y, eta)
+    Yd = torch.from_numpy(Y).to(dev)
+    ws = mp.Workspace.for_call("tri", *shape, device=dev)
+    busy, mine = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for _ in range(6):
+            mp.bilevel_proj_l11(big, 1000.0, X=big_out, workspace=big_ws, stream=busy)
+        X = torch.empty_like(Yd)
+        mp.trilevel_proj_l1infinf(Yd, eta, X=X, workspace=ws, stream=mine)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(X.cpu().numpy(), ref["X"], rtol=RTOL, atol=ATOL)
+        assert ws.result()["tau"] == pytest.approx(ref["tau"], rel=1e-9)
+
+
 # ------------------------------------------------------------------ 16-bit storage
 STORE_DTYPES = {"bf16": "bfloat16", "f16": "float16", "f32": "float32"}
 
