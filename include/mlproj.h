@@ -146,14 +146,16 @@ int mlproj_set_l11_sweeps(int sweeps);
  * What a caller on a shared GPU sees is a call that takes a fraction of a millisecond longer
  * (the default, 256 polls of 1-2 us each, plus the one-workgroup search), never a stall.
  * 0 makes the several-workgroup search give up at once (which is how the tests exercise the
- * kernel behind it).  Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value
- * outside 0..4194304.                                                                        */
+ * kernel behind it).  The same number, capped at 64, is the patience of the one-pass tri-level
+ * kernel (see trilevel_proj_l1infinf): with 0 its workgroups never wait for one another.
+ * Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION for a value outside 0..4194304.    */
 int mlproj_set_search_spin_limit(int polls);
 
 /* Bytes of workspace a call of `variant` on dims (d0, d1, d2) needs; bi-level
  * variants take d0 = n, d1 = m, d2 = 1.  Host-only, touches no GPU.  The size is a few
  * MiB plus 8-16 bytes per column; MLPROJ_L11 adds up to about 1 KiB per column for the
- * lists of its per-column threshold searches.                                   */
+ * lists of its per-column threshold searches and a few MiB for the partial results of its
+ * aggregate pass.                                                                */
 int mlproj_workspace_bytes(int variant, long long d0, long long d1, long long d2,
                            size_t* bytes_out /* host */);
 
@@ -317,7 +319,14 @@ int bilevel_apply(int variant, const float* Y /* device, n*m */, float* X /* dev
  * each fibre Y_ab. is clipped to min(V_ab, u_a) -- which equals clipping it to u_a.
  * (The paper indexes its tensor (c, n, m) and keeps groups on the last axis; that is this
  * function applied to the transposed tensor, or bilevel_proj_l1inf on the (c*n) x m
- * reshape.)  v_out / u_out have d0 entries (w and u).                               */
+ * reshape.)  v_out / u_out have d0 entries (w and u).
+ * A tensor of at most 256 slabs (d0) and 64 MiB whose slabs are 16-byte aligned is projected in
+ * one pass over memory: every workgroup keeps its share of Y in registers between the aggregate
+ * and the clip, and the workgroups exchange their maxima inside the kernel.  That is fastest when
+ * all of them run at once, as they do on an otherwise idle GPU; on a GPU that other streams keep
+ * full a workgroup that has waited (at most 64 polls, about 0.1 ms) computes the missing maxima
+ * itself, so the call gets slower but never stalls, and the result is the same.  Other tensors
+ * take a chain of three kernels.                                                      */
 int trilevel_proj_l1infinf(const float* Y /* device, d0*d1*d2 */, float* X /* device, same */,
                            long long d0, long long d1, long long d2, float eta,
                            void* workspace, size_t workspace_bytes,

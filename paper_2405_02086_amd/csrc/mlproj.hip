@@ -300,18 +300,18 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   // l1,1 with lock-step sweeps planned: the aggregate pass also evaluates the columns on a grid
   // of thresholds, which stands in for the probing sweep (l11grid.h)
   bool grid = false;
-  if constexpr (Q == Q1) {
+  if constexpr (Q == Q1 && sizeof(T) == 4) {
     int sweeps;
     unsigned handoff;
     plan_l11(n, m, (int)sizeof(T), &sweeps, &handoff);
     // (worth it from 128 MiB on, where the probing pass costs more than the scale kernel, the grid
     // arithmetic and the longer seeding; not on 16-bit storage, where the aggregate pass has twice
     // the elements per byte and the grid arithmetic would double its time)
-    grid = mode == MODE_PROJECT && sweeps >= 1 && sizeof(T) == 4 && n * m >= (32LL << 20);
+    grid = mode == MODE_PROJECT && sweeps >= 1 && n * m >= (32LL << 20);
   }
   if (stages & STAGE_AGGREGATE) {
     mark(stream);
-    if constexpr (Q == Q1) {
+    if constexpr (Q == Q1 && sizeof(T) == 4) {
       if (grid) {
         launch((l11_scale_kernel<T>), dim3((unsigned)cdiv(m, WG)), block, stream, Y, n, m, ws.scale);
         if (wide)
