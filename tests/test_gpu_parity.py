@@ -259,7 +259,7 @@ def test_trilevel_matches_oracle(mp, shape):
         check_tri(run_tri(mp, Y, eta), orc.trilevel_l1infinf(Y, eta))
 
 
-# Tensors of at least 1 MiB that the register files hold take the one-pass kernel: one piece of a
+# Tensors that the register files hold (16-byte aligned slabs, at most 256 of them) take the one-pass kernel: one piece of a
 # slab per workgroup, up to 256 of them.  The shapes cover one piece per slab and several, a ragged
 # last piece, pieces shorter than a workgroup's 512 chunks, 256 slabs, one slab, and a slab length
 # that is not a multiple of 16 bytes (which takes the three-kernel chain).
@@ -1456,7 +1456,7 @@ def test_l11_root_exactly_on_repeated_entries(mp):
 
 # ------------------------------------------------------------------ tri-level on 16-bit storage
 @pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
-# (the last three shapes are large enough, 1 MiB and more in every storage type, for the one-pass kernel)
+# (the last three shapes are 1 MiB and more in every storage type: several pieces per slab in the one-pass kernel)
 @pytest.mark.parametrize("shape", [(1, 1, 1), (3, 4, 5), (17, 16, 16), (6, 50, 41), (300, 3, 2), (4, 64, 1024), (40, 33, 264),
                                    (16, 128, 1024), (200, 40, 1000), (3, 1, 1000008)])
 def test_trilevel_stored_matches_oracle(mp, storage, shape):
