@@ -918,7 +918,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 372; }
+int mlproj_version(void) { return 373; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

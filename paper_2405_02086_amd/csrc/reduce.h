@@ -139,6 +139,43 @@ __device__ __forceinline__ void block_sum_count(double& sum, unsigned& cnt, Pair
   cnt = c;
 }
 
+// ... and (sum, count, minimum) with a float minimum (+inf = no candidate).
+template <int NW>
+struct RoundScratch {
+  double a[NW];
+  unsigned u[NW];
+  float lo[NW];
+};
+__device__ __forceinline__ float wave_min_f(float x) {
+  x = fminf(x, __uint_as_float(dpp_u32<DPP_SWAP1>(__float_as_uint(x))));
+  x = fminf(x, __uint_as_float(dpp_u32<DPP_SWAP2>(__float_as_uint(x))));
+  x = fminf(x, __uint_as_float(dpp_u32<DPP_SHR4>(__float_as_uint(x))));
+  x = fminf(x, __uint_as_float(dpp_u32<DPP_SHR8>(__float_as_uint(x))));
+  x = fminf(x, __uint_as_float(dpp_u32<DPP_BCAST15>(__float_as_uint(x))));
+  x = fminf(x, __uint_as_float(dpp_u32<DPP_BCAST31>(__float_as_uint(x))));
+  return __uint_as_float(bcast63_u32(__float_as_uint(x)));
+}
+template <int NW>
+__device__ __forceinline__ void block_sum_count_min(double& sum, unsigned& cnt, float& mn, RoundScratch<NW>& s) {
+  sum = wave_sum(sum);
+  cnt = wave_sum_u(cnt);
+  mn = wave_min_f(mn);
+  if ((threadIdx.x & (WAVE - 1)) == 0) {
+    const int w = threadIdx.x / WAVE;
+    s.a[w] = sum; s.u[w] = cnt; s.lo[w] = mn;
+  }
+  __syncthreads();
+  double r = 0.0;
+  unsigned c = 0;
+  float l = INFINITY;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { r += s.a[w]; c += s.u[w]; l = fminf(l, s.lo[w]); }
+  __syncthreads();
+  sum = r;
+  cnt = c;
+  mn = l;
+}
+
 // ... and (sum, sum, count), for the weighted threshold search.
 template <int NW>
 __device__ __forceinline__ void block_sum2_count(double& sum, double& sum2, unsigned& cnt, PairScratch<NW>& s) {

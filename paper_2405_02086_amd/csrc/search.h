@@ -337,6 +337,13 @@ __device__ __forceinline__ double from32(unsigned lo, unsigned hi) {
   return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
+// A non-negative double as a float, rounded towards zero.
+__device__ __forceinline__ float float_at_or_below(double x) {
+  float f = (float)x;
+  if ((double)f > x) f = __uint_as_float(__float_as_uint(f) - 1u);   // (f > x >= 0: f is positive, also when it is inf)
+  return f;
+}
+
 // Collect W words of every workgroup's post of this round into pay[] of lane g (zeros in the
 // other lanes).  False, for every thread of the workgroup alike, when the search gives up.
 // spin_limit: polls a lane may spend waiting (checked every 64th); 0 = give up without polling,
@@ -386,8 +393,10 @@ __device__ __forceinline__ bool collect(const unsigned long long* q, unsigned* f
 // comes a starting guess: the root if v were Gaussian with that mean and variance.  The guess
 // is evaluated first; its fixed-point image is a lower bound on the root whichever side of the
 // root the guess lies on (the tangent of a convex function lies below it), and from there the
-// iteration goes on as ever, so only the number of rounds depends on the guess: three or four
-// instead of seven on 262144 column maxima of Laplace entries.
+// iteration goes on as ever, so only the number of rounds depends on the guess.  A round also
+// posts the smallest entry above its point (plain ball), which tells whether the point's image is
+// already the root: the round that only confirmed an unchanged count is not needed.  Three
+// exchanges instead of seven on 262144 column maxima of Laplace entries.
 template <bool WEIGHTED, int NT, int VALUES>
 __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroups, double eta,
                                                           int mode, double* __restrict__ norm_out,
@@ -396,6 +405,7 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
                                                           long long nstats) {
   static_assert(NT >= COOP_MAX_WGS, "one lane per workgroup collects its post");
   __shared__ PairScratch<NT / WAVE> s;
+  __shared__ RoundScratch<NT / WAVE> rs;
   __shared__ unsigned lds_ok;
   const int tid = threadIdx.x;
   const int nwg = (int)gridDim.x, wg = (int)blockIdx.x;
@@ -419,6 +429,18 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
     const long long ii = i < hi ? i : last;
     vr[k] = v[ii];
     if constexpr (WEIGHTED) wr[k] = wts[ii];
+  }
+  // (the first STAT_SLOTS triples per thread of the aggregate pass's statistics travel with them)
+  constexpr int STAT_SLOTS = 4;
+  const bool have_stats = !WEIGHTED && tile_stats != nullptr;
+  double st[STAT_SLOTS][3];
+#pragma unroll
+  for (int k = 0; k < STAT_SLOTS; ++k) {
+    const long long i = tid + (long long)k * NT;
+    const long long ii = have_stats ? (i < nstats ? i : nstats - 1) : 0;
+    const double* p = have_stats ? tile_stats + 3 * ii : v;
+#pragma unroll
+    for (int c = 0; c < 3; ++c) st[k][c] = p[have_stats ? c : 0];
   }
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -446,7 +468,7 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
     }
     mx = fmax(mx, x);
   }
-  block_sum_max(a, mx, s);
+  if (!have_stats) block_sum_max(a, mx, s);   // (with the statistics the totals come from them)
   double third = 0.0;   // weighted: the slice's sum of w^2, or with eta = 0 its maximum of v/w
   if constexpr (WEIGHTED) {
     double rmax = 0.0;
@@ -461,10 +483,17 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
   SearchOut o;
   double den_all = 0.0, rmax_all = 0.0;
   double guess = -1.0;
-  const bool have_stats = !WEIGHTED && tile_stats != nullptr;
   if (have_stats) {
     double sa = 0.0, sq = 0.0, sm = 0.0, none = 0.0;
-    for (long long i = tid; i < nstats; i += NT) {
+#pragma unroll
+    for (int k = 0; k < STAT_SLOTS; ++k) {
+      if (tid + (long long)k * NT < nstats) {
+        sa += st[k][0];
+        sq += st[k][1];
+        sm = fmax(sm, st[k][2]);
+      }
+    }
+    for (long long i = tid + (long long)STAT_SLOTS * NT; i < nstats; i += NT) {
       sa += tile_stats[3 * i];
       sq += tile_stats[3 * i + 1];
       sm = fmax(sm, tile_stats[3 * i + 2]);
@@ -536,6 +565,7 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
       const double at = guessing ? guess : tau;
       double sum = 0.0, sd = 0.0;
       unsigned cnt = 0;
+      double nxt = HUGE_VAL;   // (plain ball) the smallest entry above the point, +inf when there is none
 #pragma unroll
       for (int k = 0; k < VALUES; ++k) {
         if constexpr (WEIGHTED) {
@@ -544,7 +574,7 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
           const double w = (double)wf;
           if (vr[k] > at * w) { sum = fma(w, vr[k], sum); sd = fma(w, w, sd); ++cnt; }
         } else {
-          if (vr[k] > at) { sum += vr[k]; ++cnt; }
+          if (vr[k] > at) { sum += vr[k]; ++cnt; nxt = fmin(nxt, vr[k]); }
         }
       }
       for (long long i = lo + tid + (long long)VALUES * NT; i < hi; i += NT) {
@@ -553,11 +583,13 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
           const double w = (double)wts[i];
           if (x > at * w) { sum = fma(w, x, sum); sd = fma(w, w, sd); ++cnt; }
         } else {
-          if (x > at) { sum += x; ++cnt; }
+          if (x > at) { sum += x; ++cnt; nxt = fmin(nxt, x); }
         }
       }
+      // as a float, rounded down: a test against it can only err on the side of one more round
+      float nxt_f = float_at_or_below(nxt);
       if constexpr (WEIGHTED) block_sum2_count(sum, sd, cnt, s);
-      else block_sum_count(sum, cnt, s);
+      else block_sum_count_min(sum, cnt, nxt_f, rs);
       ++round;
       const unsigned par = round & 1u;
       if (tid == 0) {
@@ -567,17 +599,21 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
         if constexpr (WEIGHTED) {
           post_word(slot(par, 3, wg), round, lo32(sd));
           post_word(slot(par, 4, wg), round, hi32(sd));
+        } else {
+          post_word(slot(par, 3, wg), round, __float_as_uint(nxt_f));
         }
       }
-      unsigned pay[WEIGHTED ? 5 : 3];
+      unsigned pay[WEIGHTED ? 5 : 4];
       if (!collect(slot(par, 0, 0), ws.flags, round, nwg, spin_limit, pay, &lds_ok)) return;
       double S = from32(pay[0], pay[1]), D = 0.0;
       unsigned K = pay[2];
+      float above_pt = INFINITY;
       if constexpr (WEIGHTED) {
         D = from32(pay[3], pay[4]);
         block_sum2_count(S, D, K, s);
       } else {
-        block_sum_count(S, K, s);
+        if (tid < nwg) above_pt = __uint_as_float(pay[3]);
+        block_sum_count_min(S, K, above_pt, rs);
       }
       if (guessing) {
         // The image of the guess.  If it beats the bound it becomes the point, and the count at
@@ -597,6 +633,10 @@ __global__ __launch_bounds__(NT) void search_wide_kernel(Ws ws, long long ngroup
       const double t = WEIGHTED ? (S - eta) / D : (S - eta) / (double)K;
       if (t > tau) tau = t;
       ++o.iters;
+      // From below the image t of the point p lies at or right of p, and f is linear up to the
+      // smallest entry above p: if t stays left of that entry it is the root, and the K entries
+      // above p are the ones above t.  The posted neighbour decides it without another round.
+      if (!WEIGHTED && t < (double)above_pt) break;
     }
     o.tau = tau;
     o.inside = inside ? 1u : 0u;
