@@ -35,6 +35,7 @@
 #include "map.h"
 #include "l11.h"
 #include "l11grid.h"
+#include "l11held.h"
 #include "slab.h"
 #include "fibre.h"
 #include "tiny.h"
@@ -299,6 +300,18 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   }
   // l1,1 with lock-step sweeps planned: the aggregate pass also evaluates the columns on a grid
   // of thresholds, which stands in for the probing sweep (l11grid.h)
+  // l1,1 on at most 4096 rows (16-byte aligned rows, the whole call at once): after the aggregate
+  // pass one kernel holds 16 whole columns per workgroup in registers, runs the inner searches
+  // there, and maps and stores from the same registers (l11held.h)
+  int held_values = 0;
+  if constexpr (Q == Q1) {
+    // (measured: ahead of the lock-step sweeps up to 32M elements, 59 against 97 us at 4096 x 4096,
+    // 108 against 146 at 4096 x 8192; level or behind from 64M on, where the stripes no longer run
+    // all at once.  A forced sweep count, the test hook, keeps the sweeps.)
+    if (mode == MODE_PROJECT && stages == STAGE_ALL && !weights && wide && x_vec &&
+        n * m <= LH_MAX_ELEMS && g_l11_sweeps.load(std::memory_order_relaxed) == 0)
+      held_values = lh_values_for<T>(n);
+  }
   bool grid = false;
   if constexpr (Q == Q1 && sizeof(T) == 4) {
     int sweeps;
@@ -307,7 +320,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     // (worth it from 128 MiB on, where the probing pass costs more than the scale kernel, the grid
     // arithmetic and the longer seeding; not on 16-bit storage, where the aggregate pass has twice
     // the elements per byte and the grid arithmetic would double its time)
-    grid = mode == MODE_PROJECT && sweeps >= 1 && n * m >= (32LL << 20);
+    grid = mode == MODE_PROJECT && sweeps >= 1 && n * m >= (32LL << 20) && held_values == 0;
   }
   if (stages & STAGE_AGGREGATE) {
     mark(stream);
@@ -343,6 +356,28 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
         launch((reduce_kernel<Q, 256>), rgrid, rblock, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
       else
         launch((reduce_kernel<Q>), rgrid, rblock, stream, ws.partial, m, g, parts, ws.v, v_out, ws.flags);
+    }
+    if constexpr (Q == Q1) {
+      if (held_values > 0) {
+        const dim3 hgrid((unsigned)cdiv(m, LH_COLS)), hblock(LH_WG);
+        const bool seeded = m <= (long long)LH_WG * LH_SEARCH_CACHE;
+        mark(stream);
+        if (!seeded) launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
+        mark(stream);   // (the same number of intervals as the longer chain: the sweeps' is empty)
+        mark(stream);
+        const double seed_eta = seeded ? (double)eta : -1.0;
+        if (seeded) {
+          if (held_values == 32) launch((l11_held_kernel<T, 32, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+          else if (held_values == 64) launch((l11_held_kernel<T, 64, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+          else launch((l11_held_kernel<T, 128, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+        } else {
+          if (held_values == 32) launch((l11_held_kernel<T, 32, 0>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+          else if (held_values == 64) launch((l11_held_kernel<T, 64, 0>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+          else launch((l11_held_kernel<T, 128, 0>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+        }
+        mark(stream);
+        return launch_status();
+      }
     }
     // (l1,1: the kernel that seeds the inner searches runs the outer search the same way)
     const bool fuse_l11 = Q == Q1 && mode == MODE_PROJECT && m <= FUSED_SEARCH_MAX_BIG && !weights;
@@ -918,7 +953,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 373; }
+int mlproj_version(void) { return 374; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

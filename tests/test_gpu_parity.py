@@ -1454,6 +1454,93 @@ def test_l11_root_exactly_on_repeated_entries(mp):
     check_against_oracle(got, ref, 1)
 
 
+# ------------------------------------------------------------------ l1,1 with the columns in registers
+# Up to 4096 rows and 32M elements, with 16-byte aligned rows, one kernel holds 16 whole columns per
+# workgroup, runs the inner searches there and maps from the same registers.  The result record
+# shows it: no lock-step sweep, every kept column closed by the column-wise pass.
+# (rows: 1..4096 around the 1024 / 2048 register-count steps; columns: ragged stripes, more than
+# 32 stripes so that the stripe-to-workgroup permutation has full runs and a rest, and more than
+# 4096 columns, where a search kernel runs ahead)
+LH_SHAPES = [(1, 4), (5, 16), (37, 48), (1024, 64), (1025, 36), (2048, 20), (2049, 532), (4096, 16), (4096, 532),
+             (300, 1100), (333, 4100), (130, 8200), (1000, 10000), (2100, 1024)]
+
+
+def assert_columns_in_registers(res):
+    assert res["inner_sweeps"] == 0 and res["inner_pending"] == 0
+    assert res["inner_finished"] == (0 if res["inside_ball"] else res["n_active"])
+
+
+@pytest.mark.parametrize("shape", LH_SHAPES)
+def test_l11_columns_in_registers_matches_oracle(mp, shape):
+    Y = workloads.generate(shape, seed=61)
+    for frac in (0.001, 0.1, 0.5, 0.95, 1.5):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert_columns_in_registers(got["res"])
+    got = run_gpu(mp, Y, 0.0, 1)
+    assert not got["X"].any() and not got["u"].any() and got["res"]["n_active"] == 0
+
+
+@pytest.mark.parametrize("n", [700, 1500, 2500])
+@pytest.mark.parametrize("family", ["cauchy", "lognormal3", "sparse", "clusters", "constant", "integers",
+                                    "geometric", "uniform"])
+def test_l11_columns_in_registers_on_hard_distributions(mp, family, n):
+    """32, 64 and 128 values per thread; heavy tails, ties, constant and sparse columns."""
+    rng = np.random.default_rng([len(family), 81, n])
+    Y = _hard_family(family, rng, n, 528).astype(np.float32)
+    for frac in (0.001, 0.1, 0.5, 0.95):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert_columns_in_registers(got["res"])
+
+
+@pytest.mark.parametrize("name", ["binary", "outlier", "pow2", "two_levels", "two_rows", "denormal", "huge", "ramp",
+                                  "mixed_columns"])
+def test_l11_columns_in_registers_on_adversarial_columns(mp, name):
+    Y = _adversarial_l11_cases()[name]
+    Y = np.ascontiguousarray(Y[:, : Y.shape[1] // 4 * 4])
+    for frac in (1e-4, 0.01, 0.3, 0.9, 0.999):
+        eta = eta_for(Y, 1, frac)
+        got = run_gpu(mp, Y, eta, 1)
+        check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+        assert_columns_in_registers(got["res"])
+
+
+@pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape", [(1, 8), (70, 4104), (2065, 264), (4096, 40), (1000, 72), (3000, 1032)])
+def test_l11_columns_in_registers_on_stored_types(mp, storage, shape):
+    Y = stored_input(shape, storage, 36)
+    for frac in (0.05, 0.6, 1.2):
+        eta = eta_for(Y, 1, frac)
+        got = run_stored(mp, Y, eta, 1, storage)
+        check_stored(got, orc.bilevel_stored(Y, eta, 1, storage), 1, storage)
+        assert_columns_in_registers(got["res"])
+    eta = eta_for(Y, 1, 0.3)
+    got = run_stored(mp, Y, eta, 1, storage, inplace=True)
+    check_stored(got, orc.bilevel_stored(Y, eta, 1, storage), 1, storage)
+    assert_columns_in_registers(got["res"])
+
+
+def test_l11_columns_in_registers_in_place_and_against_the_sweeps(mp, l11_sweeps):
+    """In place, twice on the same workspace, and the same thresholds as the lock-step sweeps give
+    (both are exact, so X agrees to the last few bits)."""
+    Y = workloads.generate((3000, 2052), seed=62)
+    eta = eta_for(Y, 1, 0.2)
+    dev = torch.device("cuda:0")
+    ws = mp.Workspace.for_call("l11", 3000, 2052, device=dev)
+    a = run_gpu(mp, Y, eta, 1, workspace=ws)
+    b = run_gpu(mp, Y, eta, 1, workspace=ws, inplace=True)
+    assert np.array_equal(a["X"], b["X"]) and np.array_equal(a["u"], b["u"])
+    assert_columns_in_registers(b["res"])
+    l11_sweeps(3)
+    c = run_gpu(mp, Y, eta, 1, workspace=ws)
+    assert c["res"]["inner_sweeps"] >= 1
+    np.testing.assert_allclose(c["X"], a["X"], rtol=0, atol=1e-6)
+    assert np.array_equal(c["X"] != 0, a["X"] != 0)
+
+
 # ------------------------------------------------------------------ tri-level on 16-bit storage
 @pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
 # (the last three shapes are 1 MiB and more in every storage type: several pieces per slab in the one-pass kernel)
