@@ -104,7 +104,8 @@ typedef struct mlproj_result {
   uint32_t inner_sweeps; /* l1,1 only: lock-step passes over Y the per-column threshold searches took */
   uint32_t inner_pending;/* l1,1 only: columns whose inner search had not converged; always 0, since  */
                          /* the finishing pass closes every column exactly                           */
-  uint32_t inner_finished;/* l1,1 only: columns the lock-step passes left to the finishing pass       */
+  uint32_t inner_finished;/* l1,1 only: columns the lock-step passes left to the column-wise pass (all */
+                         /* kept columns when a call runs no lock-step pass at all)                   */
   uint32_t reserved[2];
 } mlproj_result;
 
@@ -132,7 +133,10 @@ int mlproj_trace_end(void);
  * for the per-column threshold searches before the column-wise finishing pass closes whatever is
  * still open.  1..16, or 0 for the default, which grows with the number of rows (none up to 1024
  * rows, or up to 4096 rows when the matrix has at most 4M elements; else 3 at 4096, 6 at 16384,
- * 12 beyond 131072): the finishing pass costs more per column the taller the matrix.  The
+ * 12 beyond 131072): the finishing pass costs more per column the taller the matrix.  With the
+ * default, a matrix of at most 4096 rows and 32M elements whose rows are 16-byte aligned is not
+ * swept at all: one kernel keeps 16 whole columns per workgroup in registers, finds their
+ * thresholds there and maps from the same registers; any forced value keeps the sweeps.  The
  * thresholds are exact for any value.  Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION
  * for a value outside 0..16.                                                                */
 int mlproj_set_l11_sweeps(int sweeps);
