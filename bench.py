@@ -30,9 +30,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (370, 371, 372, 373, 374)   # the library versions the counters in profiles/ hold for (371 and 372 changed the one-kernel path
+TRAFFIC_VERSIONS = (370, 371, 372, 373, 374, 375)   # the library versions the counters in profiles/ hold for (371 and 372 changed the one-kernel path
                                     # of tiny matrices and the size from which a tensor takes the one-pass kernel, 373 the grid-wide
-                                    # search of matrices with more than 32768 columns, 374 the l1,1 path of matrices of at most
+                                    # search of matrices with more than 32768 columns, 374 and 375 the l1,1 path of matrices of at most
                                     # 4096 rows; the kernels counted here are the same)
 TRAFFIC_KIB = {"square_4096": 32979.1 * 1.999 + 65564.1, "square_16384": 524922.7 * 1.999 + 1048620.6,
                "tensor_256x256x256": 32905.7 * 1.999 + 65612.4}
@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="square_4096")
+    ap.add_argument("--variant", default="l1inf", choices=["l1inf", "l12", "l11"],
+                    help="bi-level variant timed on the workload (other than l1inf: as --quick, for profiling runs)")
     ap.add_argument("--quick", action="store_true", help="headline workload only, no CPU baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     return ap.parse_args()
@@ -544,6 +546,8 @@ def main():
     from paper_2405_02086_amd import workloads
 
     w, Y = workloads.make(args.workload)
+    if args.variant != "l1inf":
+        args.quick = True
     want_cpu = not (args.quick or args.no_cpu)
     tensor = len(w.shape) == 3
     all_cores = x_all = None
@@ -561,15 +565,20 @@ def main():
     if tensor:
         head = bench_trilevel_head(torch, mp, Y, w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
     else:
-        head = bench_bilevel(torch, mp, Y, "l1inf", w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
+        head = bench_bilevel(torch, mp, Y, args.variant, w.eta_frac, args.steps, args.warmup, keep_output=want_cpu)
     x_timed = head.pop("_x_timed", None)
     elems = Y.size
-    what = "tri-level l1,inf,inf" if tensor else "bi-level l1,inf"
+    what = "tri-level l1,inf,inf" if tensor else "bi-level " + {"l1inf": "l1,inf", "l12": "l1,2", "l11": "l1,1"}[args.variant]
     # the dominant kernel: the one that reads Y and writes X (8 B/element)
     kms = head["kernel_ms"]
     dom = max(kms, key=kms.get)
     dom_ms = kms[dom]
-    traffic_ok = args.workload in TRAFFIC_KIB and mp.lib().mlproj_version() in TRAFFIC_VERSIONS
+    if args.variant == "l11" and head.get("inner_sweeps") == 0 and dom == "colmap":
+        # no lock-step sweep ran: the last kernel is the one that holds the columns in registers
+        # (inner searches and soft-threshold), not the plain map pass
+        dom = "l11_held (inner searches + map from registers)"
+    traffic_ok = (args.workload in TRAFFIC_KIB and args.variant == "l1inf"
+                  and mp.lib().mlproj_version() in TRAFFIC_VERSIONS)
     roofline = {
         "bound": "hbm", "kernel": "%s (%s; 8 B/element: reads Y, writes X)" % (dom, what),
         "achieved": 8.0 * elems / dom_ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -644,6 +653,7 @@ def main():
             "square_16384_l1inf": summary_of(also["square_16384/l1inf"]),
             "square_16384_l12": summary_of(also["square_16384/l12"]),
             "square_16384_l11": summary_of(also["square_16384/l11"]),
+            "square_4096_l11": summary_of(also["square_4096/l11"]),
             "tall_262144x256": summary_of(also["tall_262144x256/l1inf"]),
             "wide_256x262144": summary_of(also["wide_256x262144/l1inf"]),
             "tensor_256x256x256": summary_of(also["tensor_256x256x256/trilevel_proj_l1infinf"]),

@@ -109,17 +109,20 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
 
   // the stripe, as stored, every load in flight at once (a row past the end re-reads the last one)
   Pack<T, VEC> raw[ROWS];
+  auto request_stripe = [&]() {
 #pragma unroll
-  for (int u = 0; u < ROWS; ++u) {
-    const unsigned off = rl + u * RL < n ? off0 + (unsigned)u * step : off_last;
-    raw[u] = *reinterpret_cast<const Pack<T, VEC>*>(ybytes + off);
-  }
-  __builtin_amdgcn_sched_barrier(0);
+    for (int u = 0; u < ROWS; ++u) {
+      const unsigned off = rl + u * RL < n ? off0 + (unsigned)u * step : off_last;
+      raw[u] = *reinterpret_cast<const Pack<T, VEC>*>(ybytes + off);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
 
   Top top;
   bool inside, nothing;
   if constexpr (SC > 0) {
-    const SearchOut o = search_block<LH_WG, SC>(ws.v, m, seed_eta, MODE_PROJECT, outer, bs);
+    // (the stripe is requested right behind the search's own loads: the search runs under it)
+    const SearchOut o = search_block<LH_WG, SC, LH_WG, double>(ws.v, m, seed_eta, MODE_PROJECT, outer, bs, request_stripe);
     top = top_of(o);
     inside = o.inside != 0u;
     nothing = inside || o.active == 0u;
@@ -128,6 +131,7 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
       ws.res->inner_finished = nothing ? 0u : o.active;
     }
   } else {
+    request_stripe();
     mlproj_result* res = ws.res;
     top = top_of(res);
     inside = res->inside_ball != 0u;

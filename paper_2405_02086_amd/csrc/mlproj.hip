@@ -953,7 +953,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 374; }
+int mlproj_version(void) { return 375; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -47,10 +47,16 @@ __device__ __forceinline__ Top top_of(const mlproj_result* r) { return Top{r->ta
 // NT hold nothing and add zeros, so the result has the bits the NT-thread workgroup gets.
 // VT: the type v is stored in where the search reads it (fp64 in the workspace; fp32 for exact
 // l_inf aggregates staged in LDS); every value is widened exactly before it is used.
-template <int NT, int CACHE = SEARCH_CACHE, int NTHREADS = NT, typename VT = double>
+// after_loads: called once the loads of v are issued and before anything waits for them; a
+// caller that has loads of its own to issue (data the search does not depend on) issues them
+// there, so that the search runs while they are in flight (loads return in order: issued ahead
+// of v's, they would hold up the search's first wait).
+struct NothingAfterLoads { __device__ __forceinline__ void operator()() const {} };
+template <int NT, int CACHE = SEARCH_CACHE, int NTHREADS = NT, typename VT = double, typename AfterLoads = NothingAfterLoads>
 __device__ __forceinline__ SearchOut search_block(const VT* __restrict__ v, long long ngroups,
                                                   double eta, int mode, int outer,
-                                                  PairScratch<NTHREADS / WAVE>& s) {
+                                                  PairScratch<NTHREADS / WAVE>& s,
+                                                  AfterLoads after_loads = AfterLoads()) {
   static_assert(NTHREADS >= NT && NTHREADS % WAVE == 0, "whole wavefronts, at least NT threads");
   // (a thread beyond NT starts past the end of v: every bound check below leaves it idle)
   const long long tid = (NTHREADS == NT || threadIdx.x < NT) ? (long long)threadIdx.x : ngroups;
@@ -60,6 +66,10 @@ __device__ __forceinline__ SearchOut search_block(const VT* __restrict__ v, long
   for (int k = 0; k < CACHE; ++k) {
     const long long i = tid + (long long)k * NT;
     vr[k] = i < ngroups ? (double)v[i] : 0.0;  // 0 is never active: tau >= 0 and the test is strict
+  }
+  after_loads();
+#pragma unroll
+  for (int k = 0; k < CACHE; ++k) {
     a += vr[k];
     mx = fmax(mx, vr[k]);
   }
