@@ -5,6 +5,7 @@
 #include "aggregate.h"
 #include "common.h"
 #include "l11.h"
+#include "l11held.h"
 #include "map.h"
 #include "tiny.h"
 
@@ -182,6 +183,23 @@ __global__ __launch_bounds__(FIN_WG) void l11_finish_batch_kernel(BatchItems it,
     l11_finish_body<T, true>(static_cast<const T*>(b.Y), b.n, b.m, ws, plan.sweeps[p], plan.handoff[p], bid);
   else
     l11_finish_body<T, false>(static_cast<const T*>(b.Y), b.n, b.m, ws, plan.sweeps[p], plan.handoff[p], bid);
+}
+
+// l1,1 problems of at most 4096 rows after their aggregate pass: the columns-in-registers kernel
+// of l11held.h, every workgroup running the outer search of its own problem.  NV: the values per
+// thread the tallest problem of the launch needs.
+template <typename T, int NV>
+__global__ __launch_bounds__(LH_WG, NV <= 32 ? 4 : 2) void l11_held_batch_kernel(BatchItems it, BatchGrid gr,
+                                                                                int outer) {
+  constexpr int WIDE = 16 / (int)sizeof(T);
+  long long bid;
+  const int p = batch_find(gr, it.count, bid);
+  const BatchItem& b = it.item[p];
+  const Geometry g = plan_columns(b.n, b.m, WIDE, Q1);
+  const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
+  const long long stripes = (long long)(gr.first[p + 1] - gr.first[p]);
+  l11_held_body<T, NV, LH_SEARCH_CACHE>(static_cast<const T*>(b.Y), static_cast<T*>(b.X), b.n, b.m, ws, b.u_out,
+                                        b.mask_out, b.eta, outer, lh_stripe_of(bid, stripes));
 }
 
 }  // namespace mlproj

@@ -574,7 +574,20 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
     TinyPlan tp;
     return pick_vec(p.Y, p.m, (int)sizeof(T)) == WIDE && aligned(p.X, 16) && tiny_plan(p.n, p.m, WIDE, &tp);
   };
-  auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG && !tinyable(i); };
+  // l1,1 problems that a single call sends through the columns-in-registers kernel (see
+  // run_bilevel) take the same kernel here, so that a batch gives the bits of its single calls:
+  // the values per thread such a problem needs, 0 for the others.  Those of them with more than
+  // 4096 columns need a search kernel of their own ahead and are enqueued one by one.
+  auto held_values = [&](int i) {
+    if constexpr (Q != Q1) return 0;
+    const mlproj_problem& p = pr[i];
+    if (pick_vec(p.Y, p.m, (int)sizeof(T)) != WIDE || !aligned(p.X, 16) || p.n * p.m > LH_MAX_ELEMS ||
+        g_l11_sweeps.load(std::memory_order_relaxed) != 0)
+      return 0;
+    return lh_values_for<T>(p.n);
+  };
+  auto held_batchable = [&](int i) { return held_values(i) > 0 && pr[i].m <= (long long)LH_WG * LH_SEARCH_CACHE; };
+  auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG && !tinyable(i) && held_values(i) == 0; };
   if constexpr (tiny_built<Q, T>()) {
     int k = 0;
     while (k < count) {
@@ -600,6 +613,44 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
       tg.first[it.count] = wgs;
       mark(stream);
       launch((tiny_batch_kernel<Q, T>), dim3(wgs), dim3(TINY_WG), stream, it, tg, outer);
+      mark(stream);
+    }
+  }
+  if constexpr (Q == Q1) {
+    int k = 0;
+    while (k < count) {
+      BatchItems it;
+      BatchGrid agg, red, hel;
+      it.count = 0;
+      unsigned a = 0, r = 0, h = 0;
+      int values = 0;
+      for (; k < count && it.count < BATCH_MAX; ++k) {
+        if (!held_batchable(k)) continue;
+        const mlproj_problem& p = pr[k];
+        BatchItem& b = it.item[it.count];
+        b.Y = p.Y; b.X = p.X; b.ws = p.workspace;
+        b.v_out = p.v_out; b.u_out = p.u_out; b.mask_out = p.mask_out;
+        b.n = p.n; b.m = p.m; b.eta = (double)p.eta;
+        b.wide = 1; b.x_vec = 1; b.whole = 0;
+        const Geometry g = plan_columns(p.n, p.m, WIDE, Q);
+        agg.first[it.count] = a; a += (unsigned)(g.tiles * g.groups);
+        red.first[it.count] = r; r += (unsigned)cdiv(p.m, SWG / reduce_parts(g.groups, fold_threads(g.groups)));
+        hel.first[it.count] = h; h += (unsigned)cdiv(p.m, LH_COLS);
+        if (held_values(k) > values) values = held_values(k);
+        ++it.count;
+      }
+      if (it.count == 0) break;
+      agg.first[it.count] = a; red.first[it.count] = r; hel.first[it.count] = h;
+      mark(stream);
+      launch((colagg_batch_kernel<Q, T>), dim3(a), dim3(WG), stream, it, agg);
+      mark(stream);
+      launch((reduce_batch_kernel<Q, T>), dim3(r), dim3(SWG), stream, it, red);
+      mark(stream);
+      // (a problem's threads hold the rows they would hold in its single call, whatever the
+      // largest problem of the launch needs: slots past its last row stay empty)
+      if (values == 32) launch((l11_held_batch_kernel<T, 32>), dim3(h), dim3(LH_WG), stream, it, hel, outer);
+      else if (values == 64) launch((l11_held_batch_kernel<T, 64>), dim3(h), dim3(LH_WG), stream, it, hel, outer);
+      else launch((l11_held_batch_kernel<T, 128>), dim3(h), dim3(LH_WG), stream, it, hel, outer);
       mark(stream);
     }
   }
@@ -660,7 +711,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
   }
   int st = launch_status();
   for (int k = 0; k < count && st == MLPROJ_OK; ++k) {
-    if (batchable(k) || tinyable(k)) continue;
+    if (batchable(k) || tinyable(k) || held_batchable(k)) continue;
     st = run_bilevel<Q, T>(static_cast<const T*>(pr[k].Y), static_cast<T*>(pr[k].X), pr[k].n, pr[k].m, pr[k].eta,
                            pr[k].workspace, pr[k].workspace_bytes, pr[k].v_out, pr[k].u_out, stream_,
                            MODE_PROJECT, nullptr, STAGE_ALL, outer, pr[k].mask_out);
@@ -953,7 +1004,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 375; }
+int mlproj_version(void) { return 376; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -1263,6 +1263,34 @@ def test_batch_l11_problems_keep_their_own_sweep_plans(mp, l11_sweeps):
             assert torch.equal(mp.bilevel_proj_l11(Yd[i], etas[i]), Xs[i])
 
 
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_batch_l11_columns_in_registers(mp, storage):
+    """Problems a single call keeps in registers take the same kernel inside a batch (32, 64 and
+    128 values per thread in one launch), next to one with too many columns for the batch form
+    and one with unaligned rows; the bits of the single calls either way."""
+    dev = torch.device("cuda:0")
+    dt = getattr(torch, STORE_DTYPES[storage])
+    shapes = [(256, 128), (1024, 1024), (2048, 64), (4096, 32), (700, 2000), (37, 48), (3000, 400), (100, 4096),
+              (130, 8200), (600, 33), (1, 8), (4096, 528)]
+    Ys = [stored_input(sh, storage, 90 + i) for i, sh in enumerate(shapes)]
+    etas = [eta_for(Y, 1, [0.01, 0.3, 0.9, 1.5][i % 4]) for i, Y in enumerate(Ys)]
+    Yd = [torch.from_numpy(Y).to(dev).to(dt) for Y in Ys]
+    wss = [mp.Workspace.for_call("l11", *Y.shape, device=dev) for Y in Ys]
+    vs = [torch.full((Y.shape[1],), -1.0, device=dev) for Y in Ys]
+    us = [torch.full((Y.shape[1],), -1.0, device=dev) for Y in Ys]
+    masks = [torch.full((Y.shape[1],), 7, dtype=torch.uint8, device=dev) for Y in Ys]
+    Xs = mp.bilevel_proj_batch(Yd, etas, 1, workspaces=wss, v_outs=vs, u_outs=us, mask_outs=masks)
+    torch.cuda.synchronize()
+    refs = orc.bilevel_batch(Ys, etas, 1, storage)
+    for i, (Y, ref) in enumerate(zip(Ys, refs)):
+        got = {"X": Xs[i].float().cpu().numpy(), "v": vs[i].cpu().numpy(), "u": us[i].cpu().numpy(),
+               "mask": masks[i].cpu().numpy(), "res": wss[i].result()}
+        check_stored(got, ref, 1, storage)
+        if shapes[i] != (600, 33):
+            assert_columns_in_registers(got["res"])
+        assert torch.equal(mp.bilevel_proj_stored(Yd[i], etas[i], 1), Xs[i]), "problem %d differs from its single call" % i
+
+
 def test_prepared_batch_can_be_called_again_on_new_contents(mp):
     """The argument block is marshalled once; the buffers it points to may change between calls."""
     dev = torch.device("cuda:0")
