@@ -308,7 +308,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     // (measured: ahead of the lock-step sweeps up to 32M elements, 59 against 97 us at 4096 x 4096,
     // 108 against 146 at 4096 x 8192; level or behind from 64M on, where the stripes no longer run
     // all at once.  A forced sweep count, the test hook, keeps the sweeps.)
-    if (mode == MODE_PROJECT && stages == STAGE_ALL && !weights && wide && x_vec &&
+    if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec &&
         n * m <= LH_MAX_ELEMS && g_l11_sweeps.load(std::memory_order_relaxed) == 0)
       held_values = lh_values_for<T>(n);
   }
@@ -360,9 +360,11 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     if constexpr (Q == Q1) {
       if (held_values > 0) {
         const dim3 hgrid((unsigned)cdiv(m, LH_COLS)), hblock(LH_WG);
-        const bool seeded = m <= (long long)LH_WG * LH_SEARCH_CACHE;
+        // (a weighted outer ball has a search kernel of its own; the kernel reads its record)
+        const bool seeded = !weights && m <= (long long)LH_WG * LH_SEARCH_CACHE;
         mark(stream);
-        if (!seeded) launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
+        if (weights) launch_weighted_search(ws, m, (double)eta, stream);
+        else if (!seeded) launch_search(ws, m, (double)eta, mode, outer, norm_out, stream);
         mark(stream);   // (the same number of intervals as the longer chain: the sweeps' is empty)
         mark(stream);
         const double seed_eta = seeded ? (double)eta : -1.0;
@@ -1004,7 +1006,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 376; }
+int mlproj_version(void) { return 377; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -1016,6 +1016,8 @@ def test_weighted_outer_norm_matches_oracle(mp, storage, q, shape):
         got = run_weighted(mp, Y, eta, q, storage, w)
         check_stored(got, ref, q, storage)
         assert got["res"]["norm"] == pytest.approx(np.dot(w.astype(np.float64), ref["v"].astype(np.float64)), rel=1e-6)
+        if q == 1 and shape[0] <= 4096 and shape[1] % (4 if storage == "f32" else 8) == 0:
+            assert_columns_in_registers(got["res"])     # (the weighted search kernel ahead of the one-pass l1,1 kernel)
 
 
 @pytest.mark.parametrize("q", ["inf", 1, 2])
