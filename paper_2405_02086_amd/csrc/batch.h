@@ -188,9 +188,9 @@ __global__ __launch_bounds__(FIN_WG) void l11_finish_batch_kernel(BatchItems it,
 // l1,1 problems of at most 4096 rows after their aggregate pass: the columns-in-registers kernel
 // of l11held.h, every workgroup running the outer search of its own problem.  NV: the values per
 // thread the tallest problem of the launch needs.
-template <typename T, int NV>
-__global__ __launch_bounds__(LH_WG, NV <= 32 ? 4 : 2) void l11_held_batch_kernel(BatchItems it, BatchGrid gr,
-                                                                                int outer) {
+template <typename T, int NV, bool PACKED = false>
+__global__ __launch_bounds__(LH_WG, lh_min_waves(NV, PACKED)) void l11_held_batch_kernel(BatchItems it, BatchGrid gr,
+                                                                                        int outer) {
   constexpr int WIDE = 16 / (int)sizeof(T);
   long long bid;
   const int p = batch_find(gr, it.count, bid);

@@ -304,8 +304,15 @@ __device__ __forceinline__ long long lh_stripe_of(long long b, long long nstripe
   return ((k / LH_XCD_RUN) * XCDS + xcd) * LH_XCD_RUN + k % LH_XCD_RUN;
 }
 
-template <typename T, int NV, int SC>
-__global__ __launch_bounds__(LH_WG, NV <= 32 ? 4 : 2) void l11_held_kernel(
+// Registers: 32 values per thread leave room for two workgroups per CU, 128 for one.  64 fit two
+// only with some twenty registers spilled, which pays when there are more stripes than CUs (the
+// second workgroup's loads and stores run under the first one's arithmetic: 42 against 52 us at
+// 2048 x 8192) and costs when every stripe has a CU to itself (27 against 23 us at 2048 x 2048):
+// PACKED picks the two-per-CU build.
+constexpr int lh_min_waves(int nv, bool packed) { return nv <= 32 ? 4 : nv <= 64 ? (packed ? 4 : 2) : 2; }
+
+template <typename T, int NV, int SC, bool PACKED = false>
+__global__ __launch_bounds__(LH_WG, lh_min_waves(NV, PACKED)) void l11_held_kernel(
     const T* Y, T* X, long long n, long long m, Ws ws, float* __restrict__ u_out,
     unsigned char* __restrict__ mask_out, double seed_eta, int outer) {
   l11_held_body<T, NV, SC>(Y, X, n, m, ws, u_out, mask_out, seed_eta, outer,

@@ -368,12 +368,16 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
         mark(stream);   // (the same number of intervals as the longer chain: the sweeps' is empty)
         mark(stream);
         const double seed_eta = seeded ? (double)eta : -1.0;
+        // (64 values per thread: two workgroups per CU when there are more stripes than CUs)
+        const bool packed = held_values == 64 && cdiv(m, LH_COLS) > compute_units();
         if (seeded) {
           if (held_values == 32) launch((l11_held_kernel<T, 32, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+          else if (packed) launch((l11_held_kernel<T, 64, LH_SEARCH_CACHE, true>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
           else if (held_values == 64) launch((l11_held_kernel<T, 64, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
           else launch((l11_held_kernel<T, 128, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
         } else {
           if (held_values == 32) launch((l11_held_kernel<T, 32, 0>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+          else if (packed) launch((l11_held_kernel<T, 64, 0, true>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
           else if (held_values == 64) launch((l11_held_kernel<T, 64, 0>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
           else launch((l11_held_kernel<T, 128, 0>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
         }
@@ -651,6 +655,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
       // (a problem's threads hold the rows they would hold in its single call, whatever the
       // largest problem of the launch needs: slots past its last row stay empty)
       if (values == 32) launch((l11_held_batch_kernel<T, 32>), dim3(h), dim3(LH_WG), stream, it, hel, outer);
+      else if (values == 64 && (long long)h > compute_units()) launch((l11_held_batch_kernel<T, 64, true>), dim3(h), dim3(LH_WG), stream, it, hel, outer);
       else if (values == 64) launch((l11_held_batch_kernel<T, 64>), dim3(h), dim3(LH_WG), stream, it, hel, outer);
       else launch((l11_held_batch_kernel<T, 128>), dim3(h), dim3(LH_WG), stream, it, hel, outer);
       mark(stream);
@@ -1006,7 +1011,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 377; }
+int mlproj_version(void) { return 378; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
