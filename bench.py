@@ -30,12 +30,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (370, 371, 372, 373, 374, 375, 376, 377, 378)   # the library versions the counters in profiles/ hold for (371 and 372 changed the one-kernel path
-                                    # of tiny matrices and the size from which a tensor takes the one-pass kernel, 373 the grid-wide
-                                    # search of matrices with more than 32768 columns, 374 to 378 the l1,1 path of matrices of at most
-                                    # 4096 rows, single and in batches; the kernels counted here are the same)
-TRAFFIC_KIB = {"square_4096": 32979.1 * 1.999 + 65564.1, "square_16384": 524922.7 * 1.999 + 1048620.6,
-               "tensor_256x256x256": 32905.7 * 1.999 + 65612.4}
+TRAFFIC_VERSIONS = (378,)   # the library version the counters in profiles/ were taken with
+TRAFFIC_KIB = {"square_4096": 32981.1 * 1.999 + 65556.2, "square_16384": 524926.1 * 1.999 + 1048622.1,
+               "tensor_256x256x256": 32908.9 * 1.999 + 65626.7}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 
