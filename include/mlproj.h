@@ -136,7 +136,9 @@ int mlproj_trace_end(void);
  * 12 beyond 131072): the finishing pass costs more per column the taller the matrix.  With the
  * default, a matrix of at most 4096 rows and 32M elements whose rows are 16-byte aligned is not
  * swept at all: one kernel keeps 16 whole columns per workgroup in registers, finds their
- * thresholds there and maps from the same registers; any forced value keeps the sweeps.  The
+ * thresholds there and maps from the same registers (fp32: also up to 8192 rows, 8 columns per
+ * workgroup, while there are no more such stripes than compute units); any forced value keeps
+ * the sweeps.  The
  * thresholds are exact for any value.  Returns the previous value, or MLPROJ_ERR_BAD_DIMENSION
  * for a value outside 0..16.                                                                */
 int mlproj_set_l11_sweeps(int sweeps);

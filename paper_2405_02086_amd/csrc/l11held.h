@@ -27,18 +27,20 @@ namespace mlproj {
 // repeats bit for bit.  The owner thread steps the column's threshold and publishes it.
 constexpr int LH_WG = 512;
 constexpr int LH_COLS = 16;
+constexpr int LH_COLS_NARROW = 8;   // fp32, 4097 to 8192 rows: stripes of 8 columns (32-byte runs), 128 values per thread
 constexpr int LH_WAVES = LH_WG / WAVE;
 constexpr int LH_FOLD_ROWS = LH_WAVES * (WAVE / 16);   // partial rows per column in LDS
 constexpr long long LH_MAX_ELEMS = 32LL << 20;   // the host sends larger matrices through the sweeps
 constexpr int DPP_ROR2 = 0x122;
 constexpr int LH_SEARCH_CACHE = 8;   // values of v per thread when the kernel runs the outer search itself: up to 4096 columns
 
-template <typename T>
+template <typename T, int COLS = LH_COLS>
 struct LhShape {
   static constexpr int VEC = 16 / (int)sizeof(T);
-  static constexpr int CW = LH_COLS / VEC;
+  static constexpr int CW = COLS / VEC;
   static constexpr int RL = LH_WG / CW;
   static_assert(CW == 2 || CW == 4, "the crossbar fold is written for 2 or 4 lanes per run");
+  static_assert(COLS <= LH_COLS, "the LDS arrays hold LH_COLS columns");
 };
 
 // values per thread a matrix of n rows needs (32, 64 or 128), 0 when it has too many rows
@@ -46,6 +48,10 @@ template <typename T>
 static inline int lh_values_for(long long n) {
   const long long rows = (n + LhShape<T>::RL - 1) / LhShape<T>::RL * LhShape<T>::VEC;
   return rows <= 32 ? 32 : rows <= 64 ? 64 : rows <= 128 ? 128 : 0;
+}
+// ... and whether the narrow stripes (fp32 only) reach a matrix too tall for the wide ones
+static inline bool lh_narrow_fits(long long n) {
+  return (n + LhShape<float, LH_COLS_NARROW>::RL - 1) / LhShape<float, LH_COLS_NARROW>::RL * 4 <= 128;
 }
 
 struct LhLds {
@@ -83,11 +89,11 @@ __device__ __forceinline__ float lh_row_max(float x) {
 // itself (SC values of v per thread), workgroup 0 files the result record; SC = 0: a search
 // kernel ran before and the record is read.  X may alias Y (a thread reads and writes the same
 // elements only).
-template <typename T, int NV, int SC>
+template <typename T, int NV, int SC, int COLS = LH_COLS>
 __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, long long m, const Ws& ws,
                                               float* __restrict__ u_out, unsigned char* __restrict__ mask_out,
                                               double seed_eta, int outer, long long bid) {
-  using Sh = LhShape<T>;
+  using Sh = LhShape<T, COLS>;
   constexpr int VEC = Sh::VEC, CW = Sh::CW, RL = Sh::RL;
   constexpr int ROWS = NV / VEC;
   __shared__ LhLds lds;
@@ -97,7 +103,7 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
   const int wave = tid / WAVE;
   const int cw = tid % CW;            // which 16-byte piece of the stripe's run
   const int rl = tid / CW;            // row lane
-  const long long col0 = bid * LH_COLS + (long long)cw * VEC;
+  const long long col0 = bid * COLS + (long long)cw * VEC;
   const bool lane_ok = col0 < m;      // (m is a multiple of VEC: a lane's columns exist together)
   const long long col0c = lane_ok ? col0 : m - VEC;   // a lane past the end shadows the last columns
   // Byte offsets of the thread's elements from the start of the matrix, in 32 bits (the host
@@ -148,8 +154,8 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
   }
 
   // The owner of column c of the stripe: thread c.  Its column's radius, bounds and state.
-  const bool owner = tid < LH_COLS;
-  const long long j = bid * LH_COLS + tid;
+  const bool owner = tid < COLS;
+  const long long j = bid * COLS + tid;
   const long long jj = (owner && j < m) ? j : 0;
   double uj = 0.0, lb = 0.0, t = 0.0;
   bool mine = false, open = false, first = true;
@@ -311,12 +317,12 @@ __device__ __forceinline__ long long lh_stripe_of(long long b, long long nstripe
 // PACKED picks the two-per-CU build.
 constexpr int lh_min_waves(int nv, bool packed) { return nv <= 32 ? 4 : nv <= 64 ? (packed ? 4 : 2) : 2; }
 
-template <typename T, int NV, int SC, bool PACKED = false>
+template <typename T, int NV, int SC, bool PACKED = false, int COLS = LH_COLS>
 __global__ __launch_bounds__(LH_WG, lh_min_waves(NV, PACKED)) void l11_held_kernel(
     const T* Y, T* X, long long n, long long m, Ws ws, float* __restrict__ u_out,
     unsigned char* __restrict__ mask_out, double seed_eta, int outer) {
-  l11_held_body<T, NV, SC>(Y, X, n, m, ws, u_out, mask_out, seed_eta, outer,
-                           lh_stripe_of(blockIdx.x, gridDim.x));
+  l11_held_body<T, NV, SC, COLS>(Y, X, n, m, ws, u_out, mask_out, seed_eta, outer,
+                                 lh_stripe_of(blockIdx.x, gridDim.x));
 }
 
 }  // namespace mlproj

@@ -239,6 +239,14 @@ static void plan_l11(long long n, long long m, int elem_bytes, int* sweeps, unsi
           : n <= 131072 ? 8 : 12;
 }
 
+// l1,1 in fp32 on 4097 to 8192 rows: the columns-in-registers kernel on stripes of 8 columns, as
+// long as every stripe has a CU to itself.  (Measured against the lock-step sweeps, Gaussian /
+// Cauchy entries: 8192 x 512 53 / 53 against 73 / 129 us, 8192 x 2048 116 / 119 against 101 / 201;
+// with more stripes than CUs the 32-byte runs lose: 8192 x 4096 300 against 144.)
+static bool l11_narrow_stripes_fit(long long n, long long m) {
+  return lh_narrow_fits(n) && cdiv(m, LH_COLS_NARROW) <= compute_units();
+}
+
 // STAGE_AGGREGATE = aggregate + threshold search (+ inner searches for l1,1);
 // STAGE_APPLY = the per-column map.
 template <int Q, typename T = float>
@@ -298,12 +306,11 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
       return launch_status();
     }
   }
-  // l1,1 with lock-step sweeps planned: the aggregate pass also evaluates the columns on a grid
-  // of thresholds, which stands in for the probing sweep (l11grid.h)
   // l1,1 on at most 4096 rows (16-byte aligned rows, the whole call at once): after the aggregate
   // pass one kernel holds 16 whole columns per workgroup in registers, runs the inner searches
   // there, and maps and stores from the same registers (l11held.h)
   int held_values = 0;
+  int held_cols = LH_COLS;
   if constexpr (Q == Q1) {
     // (measured: ahead of the lock-step sweeps up to 32M elements, 59 against 97 us at 4096 x 4096,
     // 108 against 146 at 4096 x 8192; level or behind from 64M on, where the stripes no longer run
@@ -311,7 +318,17 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec &&
         n * m <= LH_MAX_ELEMS && g_l11_sweeps.load(std::memory_order_relaxed) == 0)
       held_values = lh_values_for<T>(n);
+    // (fp32 up to 8192 rows: stripes of 8 columns)
+    if constexpr (sizeof(T) == 4) {
+      if (held_values == 0 && mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && n * m <= LH_MAX_ELEMS &&
+          g_l11_sweeps.load(std::memory_order_relaxed) == 0 && l11_narrow_stripes_fit(n, m)) {
+        held_values = 128;
+        held_cols = LH_COLS_NARROW;
+      }
+    }
   }
+  // l1,1 with lock-step sweeps planned: the aggregate pass also evaluates the columns on a grid
+  // of thresholds, which stands in for the probing sweep (l11grid.h)
   bool grid = false;
   if constexpr (Q == Q1 && sizeof(T) == 4) {
     int sweeps;
@@ -359,7 +376,7 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
     }
     if constexpr (Q == Q1) {
       if (held_values > 0) {
-        const dim3 hgrid((unsigned)cdiv(m, LH_COLS)), hblock(LH_WG);
+        const dim3 hgrid((unsigned)cdiv(m, held_cols)), hblock(LH_WG);
         // (a weighted outer ball has a search kernel of its own; the kernel reads its record)
         const bool seeded = !weights && m <= (long long)LH_WG * LH_SEARCH_CACHE;
         mark(stream);
@@ -370,7 +387,16 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
         const double seed_eta = seeded ? (double)eta : -1.0;
         // (64 values per thread: two workgroups per CU when there are more stripes than CUs)
         const bool packed = held_values == 64 && cdiv(m, LH_COLS) > compute_units();
-        if (seeded) {
+        bool narrow_done = false;
+        if constexpr (sizeof(T) == 4) {
+          if (held_cols == LH_COLS_NARROW) {
+            if (seeded) launch((l11_held_kernel<T, 128, LH_SEARCH_CACHE, false, LH_COLS_NARROW>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+            else launch((l11_held_kernel<T, 128, 0, false, LH_COLS_NARROW>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
+            narrow_done = true;
+          }
+        }
+        if (narrow_done) {
+        } else if (seeded) {
           if (held_values == 32) launch((l11_held_kernel<T, 32, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
           else if (packed) launch((l11_held_kernel<T, 64, LH_SEARCH_CACHE, true>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
           else if (held_values == 64) launch((l11_held_kernel<T, 64, LH_SEARCH_CACHE>), hgrid, hblock, stream, Y, X, n, m, ws, u_out, mask_out, seed_eta, outer);
@@ -590,7 +616,9 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
     if (pick_vec(p.Y, p.m, (int)sizeof(T)) != WIDE || !aligned(p.X, 16) || p.n * p.m > LH_MAX_ELEMS ||
         g_l11_sweeps.load(std::memory_order_relaxed) != 0)
       return 0;
-    return lh_values_for<T>(p.n);
+    const int wide_stripes = lh_values_for<T>(p.n);
+    if (wide_stripes == 0 && sizeof(T) == 4 && l11_narrow_stripes_fit(p.n, p.m)) return -1;   // the narrow stripes: single calls only
+    return wide_stripes;
   };
   auto held_batchable = [&](int i) { return held_values(i) > 0 && pr[i].m <= (long long)LH_WG * LH_SEARCH_CACHE; };
   auto batchable = [&](int i) { return pr[i].m <= FUSED_SEARCH_MAX_BIG && !tinyable(i) && held_values(i) == 0; };
@@ -1011,7 +1039,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 378; }
+int mlproj_version(void) { return 379; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -1538,6 +1538,23 @@ def test_l11_columns_in_registers_on_adversarial_columns(mp, name):
         assert_columns_in_registers(got["res"])
 
 
+@pytest.mark.parametrize("shape", [(4097, 8), (4100, 36), (5000, 264), (8192, 20), (8192, 516), (6000, 2048), (7000, 1000)])
+def test_l11_columns_in_registers_narrow_stripes(mp, shape):
+    """fp32 matrices of 4097 to 8192 rows and at most 2048 columns: stripes of 8 columns, 128
+    values per thread (ragged stripes, more than 32 of them, the most the form takes)."""
+    rng = np.random.default_rng([shape[0], shape[1], 83])
+    for family in ("gaussian", "cauchy", "integers"):
+        Y = (rng.standard_normal(shape) if family == "gaussian" else _hard_family(family, rng, *shape)).astype(np.float32)
+        for frac in (0.001, 0.3, 0.95, 1.5):
+            eta = eta_for(Y, 1, frac)
+            got = run_gpu(mp, Y, eta, 1)
+            check_against_oracle(got, orc.bilevel(Y, eta, 1), 1)
+            assert_columns_in_registers(got["res"])
+    got = run_gpu(mp, Y, eta_for(Y, 1, 0.2), 1, inplace=True)
+    check_against_oracle(got, orc.bilevel(Y, eta_for(Y, 1, 0.2), 1), 1)
+    assert_columns_in_registers(got["res"])
+
+
 @pytest.mark.parametrize("storage", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("shape", [(1, 8), (70, 4104), (2065, 264), (4096, 40), (1000, 72), (3000, 1032)])
 def test_l11_columns_in_registers_on_stored_types(mp, storage, shape):
