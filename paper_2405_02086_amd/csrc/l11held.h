@@ -23,8 +23,9 @@ namespace mlproj {
 // lanes span the stripe, and the thread of row lane r holds rows r, r + RL, r + 2 RL, ...  The
 // partial sums and counts of a column are folded over the row lanes of a 16-lane row on the
 // DPP crossbar (rotations by CW, 2 CW, ... 8), then over the 4 rows of each of the 8
-// wavefronts through LDS by the column's owner thread, always in the same order: the result
-// repeats bit for bit.  The owner thread steps the column's threshold and publishes it.
+// wavefronts through LDS by the first wavefront (four lanes per column), always in the same
+// order: the result repeats bit for bit.  The column's owner thread steps its threshold and
+// publishes it.
 constexpr int LH_WG = 512;
 constexpr int LH_COLS = 16;
 constexpr int LH_COLS_NARROW = 8;   // fp32, 4097 to 8192 rows: stripes of 8 columns (32-byte runs), 128 values per thread
@@ -191,10 +192,16 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
         for (int k = 0; k < VEC; ++k) lds.s[wave * 4 + lane / 16][cw * VEC + k] = (double)hm[k];
       }
       __syncthreads();
+      // (the fold over the partial rows: the 64 lanes of the first wavefront take a quarter of the
+      // rows of one column each, lane = column + 16 * quarter, and meet on the crossbar)
+      double amax = 0.0;
+      if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < LH_FOLD_ROWS / 4; ++w) amax = fmax(amax, lds.s[(lane >> 4) * (LH_FOLD_ROWS / 4) + w][lane & 15]);
+        amax = fmax(amax, __shfl_xor(amax, 16));
+        amax = fmax(amax, __shfl_xor(amax, 32));
+      }
       if (owner) {
-        double amax = lds.s[0][tid];
-#pragma unroll 8
-        for (int w = 1; w < LH_FOLD_ROWS; ++w) amax = fmax(amax, lds.s[w][tid]);
         if (mine) {
           if (amax - uj > lb) lb = amax - uj;
           if (t <= lb || t >= amax) {   // the guess is no better than the bound, or beyond every entry
@@ -238,14 +245,20 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
         }
       }
       __syncthreads();
-      if (owner && open) {
-        double S = lds.s[0][tid];
-        unsigned K = lds.k[0][tid];
-#pragma unroll 8
-        for (int w = 1; w < LH_FOLD_ROWS; ++w) {
-          S += lds.s[w][tid];
-          K += lds.k[w][tid];
+      double S = 0.0;
+      unsigned K = 0u;
+      if (wave == 0) {   // (as for the maxima above; always in this order, so the sums repeat bit for bit)
+#pragma unroll
+        for (int w = 0; w < LH_FOLD_ROWS / 4; ++w) {
+          S += lds.s[(lane >> 4) * (LH_FOLD_ROWS / 4) + w][lane & 15];
+          K += lds.k[(lane >> 4) * (LH_FOLD_ROWS / 4) + w][lane & 15];
         }
+        S += __shfl_xor(S, 16);
+        K += __shfl_xor(K, 16);
+        S += __shfl_xor(S, 32);
+        K += __shfl_xor(K, 32);
+      }
+      if (owner && open) {
         if (first) {
           // from the guess: step to its fixed-point image (a lower bound from any point), or
           // back to the bound if it overshot every entry
