@@ -199,7 +199,7 @@ __global__ __launch_bounds__(LH_WG, lh_min_waves(NV, PACKED)) void l11_held_batc
   const Ws ws = bind(b.ws, layout_for(g, b.m, Q1));
   const long long stripes = (long long)(gr.first[p + 1] - gr.first[p]);
   l11_held_body<T, NV, LH_SEARCH_CACHE>(static_cast<const T*>(b.Y), static_cast<T*>(b.X), b.n, b.m, ws, b.u_out,
-                                        b.mask_out, b.eta, outer, lh_stripe_of(bid, stripes));
+                                        b.mask_out, b.eta, outer, stripe_of_workgroup(bid, stripes));
 }
 
 }  // namespace mlproj

@@ -762,13 +762,28 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
   }
 }
 
+// Which stripe a workgroup takes.  Workgroups go to the chip's 8 XCDs in turn (workgroup b to XCD
+// b % 8) and every XCD has an L2 of its own with 128-byte lines, so a line of Y that two
+// neighbouring stripes share would cross the fabric twice if the two landed on different XCDs.
+// Runs of STRIPE_XCD_RUN neighbouring stripes therefore go to workgroups 8 apart: the same XCD, one
+// after the other in dispatch order.  (A permutation of the full runs; the ragged rest keeps
+// its numbers.)
+constexpr int STRIPE_XCD_RUN = 4;
+constexpr int XCDS = 8;
+__device__ __forceinline__ long long stripe_of_workgroup(long long b, long long nstripes) {
+  const long long full = nstripes / (XCDS * STRIPE_XCD_RUN) * (XCDS * STRIPE_XCD_RUN);
+  if (b >= full) return b;
+  const long long xcd = b % XCDS, k = b / XCDS;
+  return ((k / STRIPE_XCD_RUN) * XCDS + xcd) * STRIPE_XCD_RUN + k % STRIPE_XCD_RUN;
+}
+
 static inline bool finish_held(long long n) { return n <= (long long)FIN_ROWS * FIN_HELD; }
 
 template <typename T, bool HELD>
 __global__ __launch_bounds__(FIN_WG, HELD ? 4 : 8) void l11_finish_kernel(const T* __restrict__ Y, long long n,
                                                             long long m, Ws ws, int sweeps,
                                                             unsigned handoff) {
-  l11_finish_body<T, HELD>(Y, n, m, ws, sweeps, handoff, blockIdx.x);
+  l11_finish_body<T, HELD>(Y, n, m, ws, sweeps, handoff, stripe_of_workgroup(blockIdx.x, gridDim.x));
 }
 
 // The seeded form (no sweep, no seeding kernel before it): short matrices of at most 4096
@@ -779,7 +794,7 @@ template <typename T, int SC>
 __global__ __launch_bounds__(FIN_WG, 4) void l11_finish_seeded_kernel(const T* __restrict__ Y, long long n,
                                                                       long long m, Ws ws, double eta,
                                                                       int outer) {
-  l11_finish_body<T, true, SC>(Y, n, m, ws, 0, 0u, blockIdx.x, eta, outer);
+  l11_finish_body<T, true, SC>(Y, n, m, ws, 0, 0u, stripe_of_workgroup(blockIdx.x, gridDim.x), eta, outer);
 }
 
 }  // namespace mlproj

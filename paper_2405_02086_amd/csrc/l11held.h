@@ -308,21 +308,6 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
   }
 }
 
-// Which stripe a workgroup takes.  Workgroups go to the chip's 8 XCDs in turn (workgroup b to XCD
-// b % 8) and every XCD has an L2 of its own with 128-byte lines, so a line of Y that two
-// neighbouring stripes share would cross the fabric twice if the two landed on different XCDs.
-// Runs of LH_XCD_RUN neighbouring stripes therefore go to workgroups 8 apart: the same XCD, one
-// after the other in dispatch order.  (A permutation of the full runs; the ragged rest keeps
-// its numbers.)
-constexpr int LH_XCD_RUN = 4;
-constexpr int XCDS = 8;
-__device__ __forceinline__ long long lh_stripe_of(long long b, long long nstripes) {
-  const long long full = nstripes / (XCDS * LH_XCD_RUN) * (XCDS * LH_XCD_RUN);
-  if (b >= full) return b;
-  const long long xcd = b % XCDS, k = b / XCDS;
-  return ((k / LH_XCD_RUN) * XCDS + xcd) * LH_XCD_RUN + k % LH_XCD_RUN;
-}
-
 // Registers: 32 values per thread leave room for two workgroups per CU, 128 for one.  64 fit two
 // only with some twenty registers spilled, which pays when there are more stripes than CUs (the
 // second workgroup's loads and stores run under the first one's arithmetic: 42 against 52 us at
@@ -335,7 +320,7 @@ __global__ __launch_bounds__(LH_WG, lh_min_waves(NV, PACKED)) void l11_held_kern
     const T* Y, T* X, long long n, long long m, Ws ws, float* __restrict__ u_out,
     unsigned char* __restrict__ mask_out, double seed_eta, int outer) {
   l11_held_body<T, NV, SC, COLS>(Y, X, n, m, ws, u_out, mask_out, seed_eta, outer,
-                                 lh_stripe_of(blockIdx.x, gridDim.x));
+                                 stripe_of_workgroup(blockIdx.x, gridDim.x));
 }
 
 }  // namespace mlproj

@@ -1039,7 +1039,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 380; }
+int mlproj_version(void) { return 381; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
