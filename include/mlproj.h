@@ -134,8 +134,9 @@ int mlproj_trace_end(void);
  * still open.  1..16, or 0 for the default, which grows with the number of rows (none up to 1024
  * rows, or up to 4096 rows when the matrix has at most 4M elements; else 3 at 4096, 6 at 16384,
  * 12 beyond 131072): the finishing pass costs more per column the taller the matrix.  With the
- * default, a matrix of at most 4096 rows and 32M elements whose rows are 16-byte aligned is not
- * swept at all: one kernel keeps 16 whole columns per workgroup in registers, finds their
+ * default, a matrix of at most 4096 rows and 64M elements (32M in 16-bit storage) whose rows are
+ * 16-byte aligned is not swept at all: one kernel keeps 16 whole columns per workgroup in
+ * registers (a stripe whose columns are all dropped is zeroed without being read), finds their
  * thresholds there and maps from the same registers (fp32: also up to 8192 rows, 8 columns per
  * workgroup, while there are no more such stripes than compute units); any forced value keeps
  * the sweeps.  The

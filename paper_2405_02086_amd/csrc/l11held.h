@@ -31,7 +31,10 @@ constexpr int LH_COLS = 16;
 constexpr int LH_COLS_NARROW = 8;   // fp32, 4097 to 8192 rows: stripes of 8 columns (32-byte runs), 128 values per thread
 constexpr int LH_WAVES = LH_WG / WAVE;
 constexpr int LH_FOLD_ROWS = LH_WAVES * (WAVE / 16);   // partial rows per column in LDS
-constexpr long long LH_MAX_ELEMS = 32LL << 20;   // the host sends larger matrices through the sweeps
+// The host sends larger matrices through the sweeps: 64M elements of fp32, 32M of a 16-bit type
+// (whose 16-column stripes are 32-byte runs: 1024 x 65536 bf16 takes 0.34 ms here against 0.21).
+template <typename T>
+constexpr long long lh_max_elems() { return sizeof(T) == 4 ? (64LL << 20) : (32LL << 20); }
 constexpr int DPP_ROR2 = 0x122;
 constexpr int LH_SEARCH_CACHE = 8;   // values of v per thread when the kernel runs the outer search itself: up to 4096 columns
 
@@ -108,7 +111,7 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
   const bool lane_ok = col0 < m;      // (m is a multiple of VEC: a lane's columns exist together)
   const long long col0c = lane_ok ? col0 : m - VEC;   // a lane past the end shadows the last columns
   // Byte offsets of the thread's elements from the start of the matrix, in 32 bits (the host
-  // sends at most LH_MAX_ELEMS elements here): one address register per access instead of two.
+  // sends at most lh_max_elems<T>() elements here): one address register per access instead of two.
   const unsigned off0 = (unsigned)(((long long)rl * m + col0c) * (long long)sizeof(T));
   const unsigned step = (unsigned)((long long)RL * m * (long long)sizeof(T));
   const unsigned off_last = (unsigned)(((n - 1) * m + col0c) * (long long)sizeof(T));
@@ -138,20 +141,11 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
       ws.res->inner_finished = nothing ? 0u : o.active;
     }
   } else {
-    request_stripe();
     mlproj_result* res = ws.res;
     top = top_of(res);
     inside = res->inside_ball != 0u;
     nothing = inside || res->n_active == 0u;
     if (bid == 0 && tid == 0) res->inner_finished = nothing ? 0u : res->n_active;
-  }
-
-  float held[ROWS][VEC];
-#pragma unroll
-  for (int u = 0; u < ROWS; ++u) {
-    const bool row_ok = rl + (long long)u * RL < n;
-#pragma unroll
-    for (int k = 0; k < VEC; ++k) held[u][k] = row_ok ? (float)raw[u].e[k] : 0.0f;   // |0| is never above a threshold
   }
 
   // The owner of column c of the stripe: thread c.  Its column's radius, bounds and state.
@@ -172,6 +166,32 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
       if (u_out) u_out[j] = (float)uj;
       if (mask_out) mask_out[j] = uj > 0.0 ? 1 : 0;
     }
+  }
+  if constexpr (SC == 0) {
+    // The search ran ahead, so the radii are known before anything of Y is: a stripe whose
+    // columns are all dropped (the sparse results the projection is used for) is zeroed without
+    // being read.
+    const bool need = inside || __syncthreads_or((owner && j < m && uj > 0.0) ? 1 : 0) != 0;
+    if (!need) {
+      if (lane_ok) {
+        float zero[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) zero[k] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < ROWS; ++u)
+          if (rl + u * RL < n) store_row_nt<VEC, true>(reinterpret_cast<T*>(reinterpret_cast<char*>(X) + (off0 + (unsigned)u * step)), zero);
+      }
+      return;
+    }
+    request_stripe();
+  }
+
+  float held[ROWS][VEC];
+#pragma unroll
+  for (int u = 0; u < ROWS; ++u) {
+    const bool row_ok = rl + (long long)u * RL < n;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) held[u][k] = row_ok ? (float)raw[u].e[k] : 0.0f;   // |0| is never above a threshold
   }
 
   if (!nothing) {

@@ -312,15 +312,16 @@ static int run_bilevel(const T* Y, T* X, long long n, long long m, float eta,
   int held_values = 0;
   int held_cols = LH_COLS;
   if constexpr (Q == Q1) {
-    // (measured: ahead of the lock-step sweeps up to 32M elements, 59 against 97 us at 4096 x 4096,
-    // 108 against 146 at 4096 x 8192; level or behind from 64M on, where the stripes no longer run
-    // all at once.  A forced sweep count, the test hook, keeps the sweeps.)
+    // (measured: ahead of the lock-step sweeps up to 64M elements, 57 against 97 us at 4096 x 4096,
+    // 108 against 146 at 4096 x 8192, 219 against 227 at 4096 x 16384, and far ahead where most
+    // columns are dropped, whose stripes are not even read; behind at 128M.  A forced sweep count,
+    // the test hook, keeps the sweeps.)
     if (mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec &&
-        n * m <= LH_MAX_ELEMS && g_l11_sweeps.load(std::memory_order_relaxed) == 0)
+        n * m <= lh_max_elems<T>() && g_l11_sweeps.load(std::memory_order_relaxed) == 0)
       held_values = lh_values_for<T>(n);
     // (fp32 up to 8192 rows: stripes of 8 columns)
     if constexpr (sizeof(T) == 4) {
-      if (held_values == 0 && mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && n * m <= LH_MAX_ELEMS &&
+      if (held_values == 0 && mode == MODE_PROJECT && stages == STAGE_ALL && wide && x_vec && n * m <= lh_max_elems<T>() &&
           g_l11_sweeps.load(std::memory_order_relaxed) == 0 && l11_narrow_stripes_fit(n, m)) {
         held_values = 128;
         held_cols = LH_COLS_NARROW;
@@ -613,7 +614,7 @@ static int run_batch(int outer, int count, const mlproj_problem* pr, void* strea
   auto held_values = [&](int i) {
     if constexpr (Q != Q1) return 0;
     const mlproj_problem& p = pr[i];
-    if (pick_vec(p.Y, p.m, (int)sizeof(T)) != WIDE || !aligned(p.X, 16) || p.n * p.m > LH_MAX_ELEMS ||
+    if (pick_vec(p.Y, p.m, (int)sizeof(T)) != WIDE || !aligned(p.X, 16) || p.n * p.m > lh_max_elems<T>() ||
         g_l11_sweeps.load(std::memory_order_relaxed) != 0)
       return 0;
     const int wide_stripes = lh_values_for<T>(p.n);
@@ -1039,7 +1040,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 381; }
+int mlproj_version(void) { return 382; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {

@@ -1485,7 +1485,7 @@ def test_l11_root_exactly_on_repeated_entries(mp):
 
 
 # ------------------------------------------------------------------ l1,1 with the columns in registers
-# Up to 4096 rows and 32M elements, with 16-byte aligned rows, one kernel holds 16 whole columns per
+# Up to 4096 rows and 64M elements, with 16-byte aligned rows, one kernel holds 16 whole columns per
 # workgroup, runs the inner searches there and maps from the same registers.  The result record
 # shows it: no lock-step sweep, every kept column closed by the column-wise pass.
 # (rows: 1..4096 around the 1024 / 2048 register-count steps; columns: ragged stripes, more than
@@ -1568,6 +1568,27 @@ def test_l11_columns_in_registers_on_stored_types(mp, storage, shape):
     got = run_stored(mp, Y, eta, 1, storage, inplace=True)
     check_stored(got, orc.bilevel_stored(Y, eta, 1, storage), 1, storage)
     assert_columns_in_registers(got["res"])
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_l11_columns_in_registers_skips_dropped_stripes(mp, storage):
+    """More than 4096 columns (the search runs ahead): a few columns carry all the weight, so whole
+    stripes are dropped and zeroed without being read; neighbours of kept columns inside a kept
+    stripe, stripes at the ragged end, in place, and X pre-filled with other values."""
+    rng = np.random.default_rng(85)
+    n, m = 600, 4648
+    Y = rng.standard_normal((n, m)).astype(np.float32)
+    heavy = np.r_[3, 4, 1000, 2047, 2048, 4632, 4647]
+    Y[:, heavy] *= 50.0
+    Y = orc.round_to_storage(Y, storage)
+    for frac in (0.01, 0.03):
+        eta = eta_for(Y, 1, frac)
+        ref = orc.bilevel_stored(Y, eta, 1, storage)
+        assert 0 < int(ref["mask"].sum()) <= len(heavy), "only heavy columns survive this radius"
+        for inplace in (False, True):
+            got = run_stored(mp, Y, eta, 1, storage, inplace=inplace)
+            check_stored(got, ref, 1, storage)
+            assert_columns_in_registers(got["res"])
 
 
 def test_l11_columns_in_registers_in_place_and_against_the_sweeps(mp, l11_sweeps):
