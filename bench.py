@@ -30,9 +30,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (378, 379, 380, 381, 382)   # the library versions the counters in profiles/ hold for (379 to 382 changed the l1,1 path of short matrices; the kernels counted here are the same)
-TRAFFIC_KIB = {"square_4096": 32981.1 * 1.999 + 65556.2, "square_16384": 524926.1 * 1.999 + 1048622.1,
-               "tensor_256x256x256": 32908.9 * 1.999 + 65626.7}
+TRAFFIC_VERSIONS = (382,)   # the library version the counters in profiles/ were taken with
+TRAFFIC_KIB = {"square_4096": 32979.1 * 1.999 + 65557.7, "square_16384": 524922.6 * 1.999 + 1048622.9,
+               "tensor_256x256x256": 32906.8 * 1.999 + 65625.0}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 
