@@ -119,14 +119,27 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
 
   // the stripe, as stored, every load in flight at once (a row past the end re-reads the last one)
   Pack<T, VEC> raw[ROWS];
-  auto request_stripe = [&]() {
+  auto request_rows = [&](auto first, auto last) {   // (compile-time bounds: raw[] must stay in registers)
 #pragma unroll
-    for (int u = 0; u < ROWS; ++u) {
+    for (int u = decltype(first)::value; u < decltype(last)::value; ++u) {
       const unsigned off = rl + u * RL < n ? off0 + (unsigned)u * step : off_last;
       raw[u] = *reinterpret_cast<const Pack<T, VEC>*>(ybytes + off);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
+  // (with the search ahead: the first quarter of the rows is requested at once, the rest when
+  // the stripe is known to be needed)
+  constexpr int EARLY = ROWS >= 4 ? ROWS / 4 : 1;
+  using R0 = std::integral_constant<int, 0>;
+  using RE = std::integral_constant<int, EARLY>;
+  using RN = std::integral_constant<int, ROWS>;
+  auto request_stripe = [&]() { request_rows(R0(), RN()); };
+
+  // The owner of column c of the stripe: thread c.
+  const bool owner = tid < COLS;
+  const long long j = bid * COLS + tid;
+  const long long jj = (owner && j < m) ? j : 0;
+  double vj = 0.0;
 
   Top top;
   bool inside, nothing;
@@ -141,22 +154,24 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
       ws.res->inner_finished = nothing ? 0u : o.active;
     }
   } else {
+    // (the record and the column sums are requested ahead of the rows: loads return in order)
     mlproj_result* res = ws.res;
     top = top_of(res);
     inside = res->inside_ball != 0u;
-    nothing = inside || res->n_active == 0u;
-    if (bid == 0 && tid == 0) res->inner_finished = nothing ? 0u : res->n_active;
+    const unsigned n_active = res->n_active;
+    if (owner) vj = ws.v[jj];
+    __builtin_amdgcn_sched_barrier(0);
+    request_rows(R0(), RE());
+    nothing = inside || n_active == 0u;
+    if (bid == 0 && tid == 0) res->inner_finished = nothing ? 0u : n_active;
   }
 
-  // The owner of column c of the stripe: thread c.  Its column's radius, bounds and state.
-  const bool owner = tid < COLS;
-  const long long j = bid * COLS + tid;
-  const long long jj = (owner && j < m) ? j : 0;
+  // The owner's column: its radius, bounds and state.
   double uj = 0.0, lb = 0.0, t = 0.0;
   bool mine = false, open = false, first = true;
   unsigned kprev = NO_COUNT;
   if (owner) {
-    const double vj = ws.v[jj];
+    if constexpr (SC > 0) vj = ws.v[jj];
     uj = j < m ? radius_of(ws, jj, vj, top) : 0.0;
     mine = j < m && !inside && uj > 0.0;
     // (a dropped column maps to zero: threshold +inf; inside the ball nothing moves: threshold 0)
@@ -168,9 +183,10 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
     }
   }
   if constexpr (SC == 0) {
-    // The search ran ahead, so the radii are known before anything of Y is: a stripe whose
-    // columns are all dropped (the sparse results the projection is used for) is zeroed without
-    // being read.
+    // The search ran ahead, so the radii are known early: a stripe whose columns are all dropped
+    // (the sparse results the projection is used for) is zeroed, and three quarters of it are
+    // never read (the first quarter was requested with the radii, so that a stripe that is
+    // needed does not wait twice).
     const bool need = inside || __syncthreads_or((owner && j < m && uj > 0.0) ? 1 : 0) != 0;
     if (!need) {
       if (lane_ok) {
@@ -183,7 +199,7 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
       }
       return;
     }
-    request_stripe();
+    request_rows(RE(), RN());
   }
 
   float held[ROWS][VEC];
