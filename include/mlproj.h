@@ -136,7 +136,7 @@ int mlproj_trace_end(void);
  * 12 beyond 131072): the finishing pass costs more per column the taller the matrix.  With the
  * default, a matrix of at most 4096 rows and 64M elements (32M in 16-bit storage) whose rows are
  * 16-byte aligned is not swept at all: one kernel keeps 16 whole columns per workgroup in
- * registers (a stripe whose columns are all dropped is zeroed without being read), finds their
+ * registers (a stripe whose columns are all dropped is zeroed with most of it unread), finds their
  * thresholds there and maps from the same registers (fp32: also up to 8192 rows, 8 columns per
  * workgroup, while there are no more such stripes than compute units); any forced value keeps
  * the sweeps.  The
