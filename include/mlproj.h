@@ -144,6 +144,14 @@ int mlproj_trace_end(void);
  * for a value outside 0..16.                                                                */
 int mlproj_set_l11_sweeps(int sweeps);
 
+/* mlproj_stripe_of_workgroup -- the column-stripe kernels of MLPROJ_L11 (16 or 8 whole columns per
+ * workgroup: the one-pass kernel for short matrices and the finishing pass) deal their stripes so
+ * that runs of 4 neighbouring stripes, which share cache lines of Y, run on one of the chip's 8
+ * XCDs (workgroup b goes to XCD b mod 8): returns the stripe that workgroup `workgroup` of
+ * `stripes` takes, a permutation of 0 .. stripes-1; -1 for arguments out of range.  Host only,
+ * touches no GPU: here so that the permutation can be checked without one.                    */
+int mlproj_stripe_of_workgroup(long long workgroup, long long stripes);
+
 /* mlproj_set_search_spin_limit -- vectors of more than 32768 groups are searched (Eq. 6-7) by up
  * to 64 workgroups that exchange their sums every round, which needs all of them running at
  * once.  On an idle GPU they are; on a GPU that other streams keep full some may have to wait

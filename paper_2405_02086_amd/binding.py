@@ -74,6 +74,8 @@ def lib():
     L.mlproj_set_l11_sweeps.argtypes = [c_i]
     L.mlproj_set_search_spin_limit.restype = c_i
     L.mlproj_set_search_spin_limit.argtypes = [c_i]
+    L.mlproj_stripe_of_workgroup.restype = c_i
+    L.mlproj_stripe_of_workgroup.argtypes = [c_ll, c_ll]
     L.mlproj_norm_l1q.restype = c_i
     L.mlproj_norm_l1q.argtypes = [c_vp, c_ll, c_ll, c_i, c_vp, c_sz, c_vp, c_vp, c_vp]
     for name in ("bilevel_proj_l1inf", "bilevel_proj_l11", "bilevel_proj_l12"):
@@ -130,7 +132,7 @@ EXPORTS = (
     "mlproj_multilevel_workspace_bytes", "multilevel_proj", "multilevel_proj_p", "bilevel_proj_pq",
     "bilevel_proj_stored", "bilevel_proj_batch", "trilevel_proj_stored", "mlproj_set_l11_sweeps",
     "multilevel_proj_stored", "bilevel_proj_weighted", "multilevel_proj_weighted", "mlproj_set_search_spin_limit",
-    "bilevel_proj_l1inf_no_alloc",
+    "bilevel_proj_l1inf_no_alloc", "mlproj_stripe_of_workgroup",
 )
 
 

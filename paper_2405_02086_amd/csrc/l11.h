@@ -770,7 +770,7 @@ __device__ __forceinline__ void l11_finish_body(const T* __restrict__ Y, long lo
 // its numbers.)
 constexpr int STRIPE_XCD_RUN = 4;
 constexpr int XCDS = 8;
-__device__ __forceinline__ long long stripe_of_workgroup(long long b, long long nstripes) {
+__host__ __device__ __forceinline__ long long stripe_of_workgroup(long long b, long long nstripes) {
   const long long full = nstripes / (XCDS * STRIPE_XCD_RUN) * (XCDS * STRIPE_XCD_RUN);
   if (b >= full) return b;
   const long long xcd = b % XCDS, k = b / XCDS;

@@ -1040,7 +1040,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 383; }
+int mlproj_version(void) { return 384; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
@@ -1076,6 +1076,11 @@ int mlproj_trace_end(void) {
 int mlproj_set_l11_sweeps(int sweeps) {
   if (sweeps < 0 || sweeps > MAX_INNER_SWEEPS) return MLPROJ_ERR_BAD_DIMENSION;
   return g_l11_sweeps.exchange(sweeps, std::memory_order_relaxed);
+}
+
+int mlproj_stripe_of_workgroup(long long workgroup, long long stripes) {
+  if (stripes <= 0 || stripes > 0x7fffffffLL || workgroup < 0 || workgroup >= stripes) return -1;
+  return (int)stripe_of_workgroup(workgroup, stripes);
 }
 
 int mlproj_set_search_spin_limit(int polls) {

@@ -203,6 +203,23 @@ def test_search_spin_limit_knob(lib):
     assert lib.mlproj_set_search_spin_limit(default) == default
 
 
+def test_stripes_are_dealt_to_workgroups_by_a_permutation_that_keeps_neighbours_on_one_xcd(lib):
+    """The column-stripe kernels of l1,1 take stripe f(b) in workgroup b.  f must be a permutation
+    of 0..n-1 for every n (a hole would leave columns unprojected), and runs of 4 neighbouring
+    stripes must sit in workgroups 8 apart, i.e. on the same XCD and consecutive in its queue."""
+    f = lib.mlproj_stripe_of_workgroup
+    for n in list(range(1, 300)) + [511, 512, 513, 625, 1000, 4096, 16384, 16385]:
+        image = [f(b, n) for b in range(n)]
+        assert sorted(image) == list(range(n)), n
+        where = {s: b for b, s in enumerate(image)}
+        full = n // 32 * 32
+        for s0 in range(0, full, 4):
+            bs = [where[s0 + i] for i in range(4)]
+            assert len({b % 8 for b in bs}) == 1 and [b // 8 for b in bs] == list(range(bs[0] // 8, bs[0] // 8 + 4)), (n, s0)
+        assert image[full:] == list(range(full, n))      # the ragged rest keeps its numbers
+    assert f(0, 0) == -1 and f(-1, 5) == -1 and f(5, 5) == -1
+
+
 def test_weighted_multilevel_argument_checks(lib):
     big = 1 << 30
     LL, I = ctypes.c_longlong, ctypes.c_int
