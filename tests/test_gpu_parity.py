@@ -855,6 +855,16 @@ def test_graph_replay_of_the_one_pass_and_grid_chains(mp):
     ws1 = mp.Workspace.for_call("l11", *Y.shape, device=dev)
     eta1 = float(np.float32(0.2 * Y.abs().double().sum().item()))
     check(lambda X: mp.bilevel_proj_l11(Y, eta1, X=X, workspace=ws1), torch.zeros_like(Y), lambda: Y.mul_(0.5))
+    # l1,1 with the columns in registers: the kernel that searches itself, the one behind a search
+    # kernel (whose first heavy columns leave whole stripes dropped), and the narrow stripes
+    for shape in ((1000, 512), (300, 5000), (5000, 64)):
+        A = rng.standard_normal(shape).astype(np.float32)
+        A[:, :3] *= 40.0
+        Yh = torch.from_numpy(A).to(dev)
+        wsh = mp.Workspace.for_call("l11", *shape, device=dev)
+        etah = float(np.float32(0.05 * Yh.abs().double().sum().item()))
+        check(lambda X: mp.bilevel_proj_l11(Yh, etah, X=X, workspace=wsh), torch.zeros_like(Yh), lambda: Yh.mul_(0.5))
+        assert wsh.result()["inner_sweeps"] == 0 and wsh.result()["inner_finished"] == wsh.result()["n_active"]
     Z = torch.from_numpy(rng.standard_normal((700, 900)).astype(np.float32)).to(dev)
     eta2 = float(np.float32(0.2 * Z.abs().max(dim=0).values.double().sum().item()))
     scratch_out = torch.zeros_like(Z)
