@@ -44,6 +44,19 @@ __device__ __forceinline__ float above(double t) {
   return f;
 }
 
+// True for every thread of the workgroup when at least one column of its tile is still open.  A
+// tile whose columns are all closed (dropped columns are closed from the start: with sparse
+// results most tiles are) needs nothing from a sweep: the update kernel reads the partial sums
+// of open columns only.
+template <typename LC, int VEC>
+__device__ __forceinline__ bool tile_has_open_column(const LC& lc, const Ws& ws) {
+  bool any = false;
+#pragma unroll
+  for (int k = 0; k < VEC; ++k)
+    if (lc.ok[k]) any = any || ws.done[lc.col(k)] == 0u;
+  return __syncthreads_or(any ? 1 : 0) != 0;
+}
+
 // Sweep 0: sum and count of the entries above t = tauj, count above t*(1 + L11_WINDOW).
 // (`bid` is the workgroup's number within its own problem: blockIdx.x for a single matrix.
 // The LDS arrays belong to the kernel, so that a kernel which holds both access forms of a
@@ -72,6 +85,7 @@ __device__ __forceinline__ void l11_sweep_body(const T* __restrict__ Y, long lon
   const long long t = bid % g.tiles;
   const long long grp = bid / g.tiles;
   const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
+  if (!tile_has_open_column<LaneCols<T, VEC, STRIDED>, VEC>(lc, ws)) return;
 
   double sum[VEC];
   unsigned cnt[VEC], cnt2[VEC];
@@ -177,6 +191,7 @@ __device__ __forceinline__ void l11_filter_body(const T* __restrict__ Y, long lo
   const long long t = bid % g.tiles;
   const long long grp = bid / g.tiles;
   const LaneCols<T, VEC, STRIDED> lc(t * TILE_W, lane, m);
+  if (!tile_has_open_column<LaneCols<T, VEC, STRIDED>, VEC>(lc, ws)) return;
 
   for (int c = threadIdx.x; c < TILE_W; c += WG) staged_cnt[c] = 0u;
   __syncthreads();

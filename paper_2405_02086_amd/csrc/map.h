@@ -61,6 +61,38 @@ __device__ __forceinline__ void colmap_body(const T* Y, T* X, long long n, long 
     top = top_of(ws.res);
     inside = ws.res->inside_ball != 0u;
   }
+  if constexpr (Q == Q1) {
+    // A tile whose columns are all dropped (with sparse results most tiles are) is zeroed
+    // without reading the rest of it.
+    if (!inside) {
+      bool kept = false;
+#pragma unroll
+      for (int k = 0; k < VEC; ++k)
+        if (lc.ok[k]) kept = kept || radius_of(ws, lc.col(k), ws.v[lc.col(k)], top) > 0.0;
+      if (!__syncthreads_or(kept ? 1 : 0)) {
+        if (grp == 0 && wave == 0) {
+#pragma unroll
+          for (int k = 0; k < VEC; ++k) {
+            if (lc.ok[k] && u_out) u_out[lc.col(k)] = 0.0f;
+            if (lc.ok[k] && mask_out) mask_out[lc.col(k)] = 0;
+          }
+        }
+        if (col_ok) {
+          float zero[VEC];
+#pragma unroll
+          for (int k = 0; k < VEC; ++k) zero[k] = 0.0f;
+          for (; b >= 0; b -= g.map_groups) {
+#pragma unroll
+            for (int r = 0; r < U; ++r) {
+              const long long row = b * MAP_RBLK + wave + (long long)r * WAVES;
+              if (row < n) lc.template store_nt<XVEC>(X + row * m, zero);
+            }
+          }
+        }
+        return;
+      }
+    }
+  }
   if (!col_ok) return;
 
   float uf[VEC];
