@@ -1601,6 +1601,27 @@ def test_l11_columns_in_registers_skips_dropped_stripes(mp, storage):
             assert_columns_in_registers(got["res"])
 
 
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_l11_sweeps_skip_tiles_without_open_columns(mp, storage):
+    """Too tall for the columns-in-registers kernel: a few heavy columns in two of the five
+    256-column tiles carry all the weight, so the sweeps and the map pass skip the other tiles
+    (and zero them); next to a radius that keeps every column."""
+    rng = np.random.default_rng(86)
+    n, m = 8300, 1100
+    Y = rng.standard_normal((n, m)).astype(np.float32)
+    heavy = np.r_[5, 6, 255, 1030, 1099]
+    Y[:, heavy] *= 50.0
+    Y = orc.round_to_storage(Y, storage)
+    for frac, sparse in ((0.01, True), (0.04, True), (0.6, False)):
+        eta = eta_for(Y, 1, frac)
+        ref = orc.bilevel_stored(Y, eta, 1, storage)
+        assert (int(ref["mask"].sum()) <= len(heavy)) == sparse
+        for inplace in (False, True):
+            got = run_stored(mp, Y, eta, 1, storage, inplace=inplace)
+            check_stored(got, ref, 1, storage)
+            assert got["res"]["inner_sweeps"] >= 1
+
+
 def test_l11_columns_in_registers_in_place_and_against_the_sweeps(mp, l11_sweeps):
     """In place, twice on the same workspace, and the same thresholds as the lock-step sweeps give
     (both are exact, so X agrees to the last few bits)."""
