@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the map kernel from the rocprofv3 --pmc runs summarised in
 # profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB), valid for these library versions only.
-TRAFFIC_VERSIONS = (382, 383, 384, 385)   # the library versions the counters in profiles/ hold for (383 and 385 changed l1,1 kernels only, 384 no kernel)
+TRAFFIC_VERSIONS = (382, 383, 384, 385, 386)   # the library versions the counters in profiles/ hold for (383, 385 and 386 changed l1,1 kernels only, 384 no kernel)
 TRAFFIC_KIB = {"square_4096": 32979.1 * 1.999 + 65557.7, "square_16384": 524922.6 * 1.999 + 1048622.9,
                "tensor_256x256x256": 32906.8 * 1.999 + 65625.0}
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024

@@ -174,8 +174,6 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
     if constexpr (SC > 0) vj = ws.v[jj];
     uj = j < m ? radius_of(ws, jj, vj, top) : 0.0;
     mine = j < m && !inside && uj > 0.0;
-    // (a dropped column maps to zero: threshold +inf; inside the ball nothing moves: threshold 0)
-    t = mine ? l11_guess(vj, uj, n, lb) : (inside ? 0.0 : HUGE_VAL);
     open = mine;
     if (j < m) {
       if (u_out) u_out[j] = (float)uj;
@@ -201,6 +199,9 @@ __device__ __forceinline__ void l11_held_body(const T* Y, T* X, long long n, lon
     }
     request_rows(RE(), RN());
   }
+  // (the starting guess only now: with the search ahead, the rest of the stripe is on its way)
+  // a dropped column maps to zero: threshold +inf; inside the ball nothing moves: threshold 0
+  if (owner) t = mine ? l11_guess(vj, uj, n, lb) : (inside ? 0.0 : HUGE_VAL);
 
   float held[ROWS][VEC];
 #pragma unroll

@@ -1040,7 +1040,7 @@ using namespace mlproj;
 
 extern "C" {
 
-int mlproj_version(void) { return 385; }
+int mlproj_version(void) { return 386; }
 
 const char* mlproj_status_string(int status) {
   switch (status) {
